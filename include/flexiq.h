@@ -1,0 +1,140 @@
+/*
+ * flexiq.h -- C ABI of the gfx950 (MI355X) FlexiQ hot path: channel-level mixed 4-bit / 8-bit
+ * quantized GEMM and implicit-GEMM convolution (arXiv 2510.02822).
+ *
+ * Conventions
+ *   - Every function returns FLEXIQ_OK (0) or a negative flexiq_status; nothing throws or aborts.
+ *     flexiq_strerror() names a code; after FLEXIQ_EHIP, flexiq_last_hip_error() gives the HIP text.
+ *   - "host" / "dev" in a comment says where a pointer must live.  Device pointers are the caller's
+ *     (e.g. torch tensors); the library never frees or reallocates them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device work of the
+ *     run-time entry points is asynchronous on it; they never synchronise and never allocate.
+ *   - Input channels are handled in "stored order": the permutation chosen offline (small-range
+ *     channels first).  Activations are expected already in stored order, as the paper arranges by
+ *     reordering the previous layer's output channels (Section 5, steps 1-2);
+ *     flexiq_permute_channels() is the run-time reorder operator of Section 5, step 3.
+ *   - A layer handle may be used from one stream at a time; flexiq_set_ratio() must not run
+ *     concurrently with a launch on the same handle.
+ */
+#ifndef FLEXIQ_H
+#define FLEXIQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FLEXIQ_OK = 0,
+    FLEXIQ_EINVAL = -1, /* null pointer, bad shape, ratio outside [0,1], C not a multiple of group_size ... */
+    FLEXIQ_EALIGN = -2, /* a device pointer is not 16-byte aligned */
+    FLEXIQ_ENOMEM = -3, /* host or device allocation failed (offline entry points only) */
+    FLEXIQ_EHIP = -4    /* a HIP runtime call failed; see flexiq_last_hip_error() */
+} flexiq_status;
+
+const char *flexiq_strerror(int status);
+const char *flexiq_last_hip_error(void);
+
+/* Opaque packed layer.  Owns (device) the permuted int8 weights, the cached packed 4-bit copy of
+ * every channel group, the extraction positions and the scales, and (host) copies of the small
+ * tables.  One handle serves every low-bit ratio: nothing is repacked when the ratio changes
+ * (Section 7, "Low-bitwidth Ratio Adjustment"). */
+typedef struct flexiq_layer flexiq_layer;
+
+/* Description of one linear (R = S = 1) or convolution layer to quantise and pack.
+ * Problem statement of Section 2.3: C feature channels, a low-bit subset chosen per target ratio. */
+typedef struct {
+    int32_t N;               /* output channels */
+    int32_t C;               /* input (feature) channels; reduction length K = R*S*C */
+    int32_t R, S;            /* filter height, width (1,1 for a linear layer) */
+    int32_t group_size;      /* channels per same-bitwidth group: 32 or 64 (Sections 4.2, 7); C % group_size == 0 */
+    const float *W;          /* host fp32 [N][R][S][C], channels in ORIGINAL order */
+    const float *act_absmax; /* host fp32 [C]: calibration max|x| of each input channel, ORIGINAL order (Section 4.2) */
+    float x_scale;           /* per-tensor activation scale S of Eq. 1 */
+    const int32_t *perm;     /* optional host int32 [C]: stored position -> original channel.  NULL: ascending
+                                error-estimation score (Section 4.2), ties by original index */
+    const float *bias;       /* optional host fp32 [N] */
+} flexiq_pack_desc;
+
+/* Offline steps (Eq. 1; Sections 4.1, 4.2, 5): per-output-channel symmetric int8 quantisation of W,
+ * channel scores and order, channel groups, extraction positions a_shift[g] (from the calibration
+ * ranges) and w_shift[n][g] (from the quantised weights, over all filter taps), permuted int8 weight
+ * tiles and the packed 4-bit bit-lowered copy.  Runs HIP kernels on the current device and
+ * synchronises; allocates device memory owned by the handle.  *out is set only on success. */
+int flexiq_quantize_pack(const flexiq_pack_desc *desc, flexiq_layer **out);
+
+/* Releases the handle and its device memory.  NULL is accepted. */
+int flexiq_layer_free(flexiq_layer *layer);
+
+/* Read-only views of the handle's host tables (valid until flexiq_layer_free); any out pointer may be NULL.
+ *   perm      int32 [C]        stored position -> original channel
+ *   a_shift   uint8 [G]        activation extraction position per group, G = C / group_size
+ *   w_shift   uint8 [N][G]     weight extraction position per (output channel, group)
+ *   w_scale   fp32  [N]        per-output-channel weight scale
+ *   G         number of channel groups;  max_4bit_ch: current count of 4-bit channels (Section 7) */
+int flexiq_layer_info(const flexiq_layer *layer, const int32_t **perm, const uint8_t **a_shift,
+                      const uint8_t **w_shift, const float **w_scale, int32_t *G, int32_t *max_4bit_ch);
+
+/* Copies the handle's device buffers back for inspection (tests: "no repacking between calls").
+ *   w8 : host int8  [N][R*S][C]    permuted 8-bit weights, decoded from the tiled device layout
+ *   w4 : host uint8 [N][R*S][C/2]  4-bit codes of ALL groups, channel c in byte c/2 (low half for even c)
+ * Either may be NULL.  Synchronises the device. */
+int flexiq_layer_dump(const flexiq_layer *layer, int8_t *w8, uint8_t *w4);
+
+/* Run-time ratio switch (Section 7): sets max_4bit_ch = group_size * ceil(r * G), the number of
+ * leading stored channels computed at 4 bits.  Host-only, O(1): one integer in the handle, passed to
+ * the next launch as a kernel argument.  r must lie in [0,1].  *max_4bit_ch (optional) gets the value. */
+int flexiq_set_ratio(flexiq_layer *layer, float r, int32_t *max_4bit_ch);
+
+/* Eq. 1 on the producer side: q[i] = clip(round_half_even(x[i] / scale), -127, 127).
+ * x: dev fp32 [n], q: dev int8 [n]. */
+int flexiq_quantize_act(const float *x, int8_t *q, int64_t n, float scale, void *stream);
+
+/* Effective-bit extraction (Section 4.1) as a stand-alone kernel:
+ * src dev int8 [rows][C]  ->  dst dev uint8 [rows][C/2]; channel c goes to byte c/2, low half for even c,
+ * as a two's-complement 4-bit code clamp((v >> s), -8, 7), s = shifts[row][c/group_size] if per_row
+ * else shifts[c/group_size].  shifts: dev uint8, values 0..4.  mode bit 0: 0 = truncate (the method),
+ * 1 = round half up before the shift (variant). */
+int flexiq_bitlower(const int8_t *src, uint8_t *dst, int64_t rows, int32_t C, int32_t group_size,
+                    const uint8_t *shifts, int per_row, int mode, void *stream);
+
+/* Section 5 step 3, the residual reorder operator: dst[row][j] = src[row][perm[j]] for every row.
+ * src, dst: dev int8 [rows][C]; uses the handle's permutation. */
+int flexiq_permute_channels(const flexiq_layer *layer, const int8_t *src, int8_t *dst, int64_t rows, void *stream);
+
+/* Outputs of a GEMM / conv call; any subset may be NULL (at least one must be set).
+ *   acc : dev int32 [M][N]  raw accumulators (parity / debugging)
+ *   y   : dev fp32  [M][N]  y = float(acc) * (x_scale * w_scale[n]) + bias[n]
+ *   q   : dev int8  [M][N]  next layer's input: clip(round_half_even(fma(float(acc), m[n], b[n])), -128, 127)
+ *                           with m[n] = (x_scale*w_scale[n]) * (1/out_scale), b[n] = bias[n] * (1/out_scale),
+ *                           every operation a correctly rounded fp32 one
+ *   out_scale : scale of q (used only when q != NULL; must be > 0) */
+typedef struct {
+    int32_t *acc;
+    float *y;
+    int8_t *q;
+    float out_scale;
+} flexiq_out;
+
+/* Mixed-precision GEMM (Sections 2.3, 7):
+ *   acc[m][n] = sum_{g < G4} 2^(a_shift[g]+w_shift[n][g]) * sum_{k in g} L(X[m][k], a_shift[g]) * L(W[n][k], w_shift[n][g])
+ *             + sum_{k >= max_4bit_ch} X[m][k] * W[n][k],          L(v, s) = clamp(v >> s, -8, 7)
+ * with G4 = max_4bit_ch / group_size as last set by flexiq_set_ratio (0 after packing).
+ * X: dev int8 [M][C] row-major, channels in stored order, 16-byte aligned; M >= 0 (M == 0 is a no-op).
+ * The activations are bit-lowered on the fly inside the kernel; the weights of 4-bit groups are read
+ * from the packed 4-bit copy and expanded in registers.  Layer must be linear (R = S = 1). */
+int flexiq_mixed_gemm(const flexiq_layer *layer, const int8_t *X, int64_t M, const flexiq_out *out, void *stream);
+
+/* The same sum as an implicit GEMM over (filter tap, channel) for a convolution layer:
+ * X: dev int8 NHWC [B][H][W][C], stored channel order, zero padding `pad`, stride `stride`;
+ * outputs are [B][Ho][Wo][N] with Ho = (H + 2*pad - R)/stride + 1 (likewise Wo).
+ * The channel groups, a_shift and the 4-bit prefix are the same for every tap. */
+int flexiq_mixed_conv_implicit(const flexiq_layer *layer, const int8_t *X, int32_t B, int32_t H, int32_t W,
+                               int32_t stride, int32_t pad, const flexiq_out *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXIQ_H */

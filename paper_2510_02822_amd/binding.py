@@ -1,0 +1,219 @@
+"""ctypes binding of libflexiq.so.  Same names as the C entry points; tensors in, tensors out."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflexiq.so")
+_lib = None
+
+
+class FlexiqError(RuntimeError):
+    pass
+
+
+class _PackDesc(C.Structure):
+    _fields_ = [("N", C.c_int32), ("C", C.c_int32), ("R", C.c_int32), ("S", C.c_int32),
+                ("group_size", C.c_int32), ("W", C.c_void_p), ("act_absmax", C.c_void_p),
+                ("x_scale", C.c_float), ("perm", C.c_void_p), ("bias", C.c_void_p)]
+
+
+class _Out(C.Structure):
+    _fields_ = [("acc", C.c_void_p), ("y", C.c_void_p), ("q", C.c_void_p), ("out_scale", C.c_float)]
+
+
+def exported_symbols():
+    """Names include/flexiq.h declares."""
+    return ["flexiq_strerror", "flexiq_last_hip_error", "flexiq_quantize_pack", "flexiq_layer_free",
+            "flexiq_layer_info", "flexiq_layer_dump", "flexiq_set_ratio", "flexiq_quantize_act",
+            "flexiq_bitlower", "flexiq_permute_channels", "flexiq_mixed_gemm", "flexiq_mixed_conv_implicit"]
+
+
+def load():
+    """Load libflexiq.so; raise if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FlexiqError("libflexiq.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(hipcc --offload-arch=gfx950).  There is no CPU fallback.")
+    L = C.CDLL(LIB_PATH)
+    L.flexiq_strerror.restype = C.c_char_p
+    L.flexiq_strerror.argtypes = [C.c_int]
+    L.flexiq_last_hip_error.restype = C.c_char_p
+    L.flexiq_quantize_pack.argtypes = [C.POINTER(_PackDesc), C.POINTER(C.c_void_p)]
+    L.flexiq_layer_free.argtypes = [C.c_void_p]
+    L.flexiq_layer_info.argtypes = [C.c_void_p] + [C.POINTER(C.c_void_p)] * 4 + [C.POINTER(C.c_int32)] * 2
+    L.flexiq_layer_dump.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    L.flexiq_set_ratio.argtypes = [C.c_void_p, C.c_float, C.POINTER(C.c_int32)]
+    L.flexiq_quantize_act.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p]
+    L.flexiq_bitlower.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_int,
+                                  C.c_int, C.c_void_p]
+    L.flexiq_permute_channels.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+    L.flexiq_mixed_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(_Out), C.c_void_p]
+    L.flexiq_mixed_conv_implicit.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_int32, C.POINTER(_Out), C.c_void_p]
+    L.flexiq_debug_force_tile.argtypes = [C.c_int]
+    for name in exported_symbols():
+        getattr(L, name)
+    _lib = L
+    return L
+
+
+def _check(rc: int):
+    if rc != 0:
+        L = load()
+        msg = L.flexiq_strerror(rc).decode()
+        if rc == -4:
+            msg += " (" + L.flexiq_last_hip_error().decode() + ")"
+        raise FlexiqError("flexiq status %d: %s" % (rc, msg))
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+class Layer:
+    """Owns a flexiq_layer handle; frees it on garbage collection."""
+
+    def __init__(self, handle: int, N: int, Cc: int, R: int, S: int, group_size: int):
+        self._h = C.c_void_p(handle)
+        self.N, self.C, self.R, self.S, self.group_size = N, Cc, R, S, group_size
+
+    def __del__(self):
+        try:
+            if self._h and _lib is not None:
+                _lib.flexiq_layer_free(self._h)
+                self._h = None
+        except Exception:
+            pass
+
+    def info(self):
+        """Host tables of the handle as numpy copies."""
+        L = load()
+        ps = [C.c_void_p() for _ in range(4)]
+        G = C.c_int32()
+        k4 = C.c_int32()
+        _check(L.flexiq_layer_info(self._h, *[C.byref(p) for p in ps], C.byref(G), C.byref(k4)))
+        g = G.value
+
+        def arr(p, ct, n):
+            return np.ctypeslib.as_array(C.cast(p, C.POINTER(ct)), shape=(n,)).copy()
+        return {"perm": arr(ps[0], C.c_int32, self.C), "a_shift": arr(ps[1], C.c_uint8, g),
+                "w_shift": arr(ps[2], C.c_uint8, self.N * g).reshape(self.N, g),
+                "w_scale": arr(ps[3], C.c_float, self.N), "G": g, "max_4bit_ch": k4.value}
+
+
+def flexiq_quantize_pack(W, act_absmax, x_scale: float, group_size: int, perm=None, bias=None) -> Layer:
+    """W: fp32 [N][C] or [N][R][S][C] (numpy, original channel order)."""
+    L = load()
+    W = _f32(W)
+    if W.ndim == 2:
+        W = W[:, None, None, :]
+    N, R, S, Cc = W.shape
+    W = np.ascontiguousarray(W)
+    am = _f32(act_absmax)
+    assert am.shape == (Cc,)
+    pm = None if perm is None else np.ascontiguousarray(perm, dtype=np.int32)
+    bs = None if bias is None else _f32(bias)
+    d = _PackDesc(N, Cc, R, S, group_size, W.ctypes.data, am.ctypes.data, float(x_scale),
+                  None if pm is None else pm.ctypes.data, None if bs is None else bs.ctypes.data)
+    h = C.c_void_p()
+    _check(L.flexiq_quantize_pack(C.byref(d), C.byref(h)))
+    return Layer(h.value, N, Cc, R, S, group_size)
+
+
+def flexiq_layer_dump(layer: Layer):
+    L = load()
+    T = layer.R * layer.S
+    w8 = np.empty((layer.N, T, layer.C), np.int8)
+    w4 = np.empty((layer.N, T, layer.C // 2), np.uint8)
+    _check(L.flexiq_layer_dump(layer._h, w8.ctypes.data, w4.ctypes.data))
+    return w8, w4
+
+
+def flexiq_set_ratio(layer: Layer, r: float) -> int:
+    k4 = C.c_int32()
+    _check(load().flexiq_set_ratio(layer._h, float(r), C.byref(k4)))
+    return k4.value
+
+
+def flexiq_quantize_act(x, scale: float, out=None):
+    import torch
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+    q = out if out is not None else torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    _check(load().flexiq_quantize_act(x.data_ptr(), q.data_ptr(), x.numel(), float(scale), _stream()))
+    return q
+
+
+def flexiq_bitlower(src, group_size: int, shifts, per_row: bool, mode: int = 0):
+    import torch
+    assert src.is_cuda and src.dtype == torch.int8 and src.is_contiguous() and src.dim() == 2
+    rows, Cc = src.shape
+    dst = torch.empty((rows, Cc // 2), dtype=torch.uint8, device=src.device)
+    _check(load().flexiq_bitlower(src.data_ptr(), dst.data_ptr(), rows, Cc, group_size, shifts.data_ptr(),
+                                  1 if per_row else 0, mode, _stream()))
+    return dst
+
+
+def flexiq_permute_channels(layer: Layer, src):
+    import torch
+    assert src.is_cuda and src.dtype == torch.int8 and src.is_contiguous()
+    dst = torch.empty_like(src)
+    _check(load().flexiq_permute_channels(layer._h, src.data_ptr(), dst.data_ptr(), src.numel() // layer.C, _stream()))
+    return dst
+
+
+def _outs(shape, device, want_acc, want_y, want_q, out_scale, bufs):
+    import torch
+    acc = y = q = None
+    if want_acc:
+        acc = bufs.get("acc") if bufs and "acc" in bufs else torch.empty(shape, dtype=torch.int32, device=device)
+    if want_y:
+        y = bufs.get("y") if bufs and "y" in bufs else torch.empty(shape, dtype=torch.float32, device=device)
+    if want_q:
+        q = bufs.get("q") if bufs and "q" in bufs else torch.empty(shape, dtype=torch.int8, device=device)
+    o = _Out(acc.data_ptr() if acc is not None else None, y.data_ptr() if y is not None else None,
+             q.data_ptr() if q is not None else None, float(out_scale))
+    return o, {"acc": acc, "y": y, "q": q}
+
+
+def flexiq_mixed_gemm(layer: Layer, X, acc: bool = False, y: bool = False, q: bool = False,
+                      out_scale: float = 1.0, bufs: Optional[dict] = None):
+    """X: int8 cuda [M][C] in stored channel order.  Returns a dict of the requested outputs."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.int8 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == layer.C
+    M = X.shape[0]
+    o, res = _outs((M, layer.N), X.device, acc, y, q, out_scale, bufs)
+    _check(load().flexiq_mixed_gemm(layer._h, X.data_ptr(), M, C.byref(o), _stream()))
+    return res
+
+
+def flexiq_mixed_conv_implicit(layer: Layer, X, stride: int, pad: int, acc: bool = False, y: bool = False,
+                               q: bool = False, out_scale: float = 1.0, bufs: Optional[dict] = None):
+    """X: int8 cuda NHWC [B][H][W][C] in stored channel order."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.int8 and X.is_contiguous() and X.dim() == 4 and X.shape[3] == layer.C
+    B, H, Wd, _ = X.shape
+    Ho = (H + 2 * pad - layer.R) // stride + 1
+    Wo = (Wd + 2 * pad - layer.S) // stride + 1
+    o, res = _outs((B, Ho, Wo, layer.N), X.device, acc, y, q, out_scale, bufs)
+    _check(load().flexiq_mixed_conv_implicit(layer._h, X.data_ptr(), B, H, Wd, stride, pad, C.byref(o), _stream()))
+    return res
+
+
+def debug_force_tile(index: int) -> int:
+    """Force a tile shape of the GEMM kernel table (-1: automatic).  Returns the table size."""
+    rc = load().flexiq_debug_force_tile(index)
+    if rc < 0:
+        _check(rc)
+    return rc

@@ -1,0 +1,59 @@
+// Internal definitions shared by the translation units of libflexiq (HIP side only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "flexiq.h"
+
+namespace flexiq {
+
+// Channels are processed in "units" of 32 (the smallest group size of Section 7); a K-step of the
+// matrix pipeline is two units = 64 reduction elements = one v_mfma_i32_16x16x64_i8.
+constexpr int kUnit = 32;
+constexpr int kNPadTo = 256;  // weight tiles are padded in N to the largest block tile
+
+// Record a failed HIP call for flexiq_last_hip_error().
+void set_hip_error(hipError_t e, const char *what);
+
+#define FLEXIQ_HIP(call)                         \
+    do {                                         \
+        hipError_t e__ = (call);                 \
+        if (e__ != hipSuccess) {                 \
+            ::flexiq::set_hip_error(e__, #call); \
+            return FLEXIQ_EHIP;                  \
+        }                                        \
+    } while (0)
+
+}  // namespace flexiq
+
+// Device layouts (all offsets in bytes unless noted), U = T * C/32 units with T = R*S filter taps,
+// unit u = tap * (C/32) + c32 (tap-major), Npad = N rounded up to 256, rows >= N are zero:
+//   w8     int8  [U][2][Npad][16]   8-bit weights; plane q2 of unit u holds stored channels
+//                                   c32*32 + q2*16 .. +15 of every output channel
+//   w4     uint8 [U][Npad][16]      4-bit codes of the same 32 channels: dword e (0..3) of a row
+//                                   carries channels 8e..8e+3 in the low halves of its bytes 0..3
+//                                   and channels 8e+4..8e+7 in the high halves
+//   wshift uint8 [G][Npad]          weight extraction position per (group, output channel)
+//   ashift uint8 [G]                activation extraction position per group
+//   cs     fp32  [Npad]             x_scale * w_scale[n]
+//   bias   fp32  [Npad]             zeros when the layer has no bias
+struct flexiq_layer {
+    int32_t N, C, R, S, group_size;
+    int32_t G, T, U, Npad;
+    int32_t max_4bit_ch;
+    float x_scale;
+    bool has_bias;
+    std::vector<int32_t> perm;
+    std::vector<uint8_t> a_shift, w_shift;
+    std::vector<float> w_scale, bias;
+    int device;
+    int8_t *d_w8;
+    uint8_t *d_w4;
+    uint8_t *d_wshift;
+    uint8_t *d_ashift;
+    float *d_cs;
+    float *d_bias;
+    int32_t *d_perm;
+};

@@ -1,0 +1,523 @@
+// Mixed 4-bit / 8-bit GEMM and implicit-GEMM convolution for gfx950 (Section 7 of the paper,
+// re-designed for CDNA4).
+//
+// gfx950 has no 4-bit integer matrix instruction, so a 4-bit channel group cannot run on a faster
+// matrix path than an 8-bit one.  The group's contribution
+//     2^(sa+sw) * sum_k L(x,sa) * L(w,sw)   =   sum_k (L(x,sa) << sa) * (L(w,sw) << sw)
+// is instead formed by putting each bit-lowered operand back at its extraction position as an int8
+// value (both factors fit: |L << s| <= 128) and feeding the same v_mfma_i32_16x16x64_i8 and the same
+// int32 accumulator as the 8-bit groups: bit-exact by distributivity, and the separate
+// shift-and-accumulate stage of the paper's CUDA kernel disappears.  What the 4-bit groups save
+// here is weight bytes (they are streamed from the packed 4-bit copy), not matrix cycles.
+//
+// Work decomposition: a block owns a BM x BN output tile; the reduction runs in K-steps of 64
+// elements (two 32-channel units, each independently 4-bit or 8-bit).  Per K-step the block
+// stages the activation tile (bit-lowered on the way: clamp + mask, packed 16-bit VALU ops) and the
+// weight tile (8-bit planes copied, 4-bit codes expanded with the per-row position) into LDS as
+// four 16-byte "k-planes", so that an MFMA fragment read is 16 lanes x 16 contiguous bytes.
+// The MFMA "A" operand is the weight fragment and "B" the activation fragment, so a lane ends up
+// with four consecutive output channels of one output row: 16-byte fp32 / 4-byte int8 stores.
+#include <mutex>
+
+#include "flexiq_internal.h"
+
+namespace flexiq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef short v2s __attribute__((ext_vector_type(2)));
+
+struct GemmParams {
+    const int8_t *X;
+    const int8_t *W8;
+    const uint8_t *W4;
+    const uint8_t *wshift;
+    const uint8_t *ashift;
+    const float *cs;
+    const float *bias;
+    int32_t *acc;
+    float *y;
+    int8_t *q;
+    float r_out;     // 1 / out_scale
+    int64_t M;       // output rows (tokens, or B*Ho*Wo output pixels)
+    int32_t N, Npad, C;
+    int32_t K4;      // max_4bit_ch: leading stored channels computed at 4 bits
+    int32_t gs_shift;  // log2(group_size / 32): unit c32 belongs to group c32 >> gs_shift
+    int32_t U;       // units in the reduction (even), CU = C/32 per tap
+    int32_t CU;
+    int32_t T;       // filter taps
+    int32_t tiles_m, tiles_n;
+    // convolution geometry (unused for the linear form)
+    int32_t H, Wd, Ho, Wo, S, stride, pad;
+};
+
+// clamp(v, -(8<<s), (8<<s)-1) & (0xFF << s) on the four int8 lanes of a dword: the bit-lowered value
+// put back at its position.  lo2/hi2 hold the bounds in the high byte of each 16-bit half.
+__device__ __forceinline__ uint32_t lower4(uint32_t d, v2s lo2, v2s hi2, uint32_t mask)
+{
+    v2s o = __builtin_bit_cast(v2s, d);           // odd bytes are the high bytes of the halves
+    v2s e = o << (short)8;                        // even bytes moved up
+    o = __builtin_elementwise_min(__builtin_elementwise_max(o, lo2), hi2);
+    e = __builtin_elementwise_min(__builtin_elementwise_max(e, lo2), hi2);
+    uint32_t r = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, o), __builtin_bit_cast(uint32_t, e), 0x07030501u);
+    return r & mask;
+}
+
+__device__ __forceinline__ v4i lower16(v4i x, int s)
+{
+    short lo = (short)((-(8 << s)) << 8);
+    short hi = (short)(((((8 << s) - 1) << 8) | 0xFF));
+    v2s lo2 = {lo, lo}, hi2 = {hi, hi};
+    uint32_t mask = 0x01010101u * ((0xFFu << s) & 0xFFu);
+    v4i r;
+    r.x = (int)lower4((uint32_t)x.x, lo2, hi2, mask);
+    r.y = (int)lower4((uint32_t)x.y, lo2, hi2, mask);
+    r.z = (int)lower4((uint32_t)x.z, lo2, hi2, mask);
+    r.w = (int)lower4((uint32_t)x.w, lo2, hi2, mask);
+    return r;
+}
+
+// Four 4-bit codes sitting in the HIGH halves of the bytes of p -> four int8 values code << sw.
+// Each 16-bit half is shifted right arithmetically by t = 4 - sw with the wanted byte on top, which
+// sign-extends the code and leaves junk only in the low sw bits (cleared by mask) and the low byte.
+__device__ __forceinline__ uint32_t expand_hi(uint32_t p, short t, uint32_t mask)
+{
+    v2s o = __builtin_bit_cast(v2s, p);
+    v2s e = o << (short)8;
+    o = o >> t;
+    e = e >> t;
+    uint32_t r = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, o), __builtin_bit_cast(uint32_t, e), 0x07030501u);
+    return r & mask;
+}
+
+// 16 bytes of 4-bit codes (32 channels of one output channel) -> 32 int8 values at position sw.
+__device__ __forceinline__ void expand32(v4i p, int sw, v4i &first16, v4i &second16)
+{
+    short t = (short)(4 - sw);
+    uint32_t mask = 0x01010101u * ((0xFFu << sw) & 0xFFu);
+    uint32_t w[4] = {(uint32_t)p.x, (uint32_t)p.y, (uint32_t)p.z, (uint32_t)p.w};
+    uint32_t o[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        o[2 * e] = expand_hi(w[e] << 4, t, mask);  // low halves: channels 8e .. 8e+3
+        o[2 * e + 1] = expand_hi(w[e], t, mask);   // high halves: channels 8e+4 .. 8e+7
+    }
+    first16 = (v4i){(int)o[0], (int)o[1], (int)o[2], (int)o[3]};
+    second16 = (v4i){(int)o[4], (int)o[5], (int)o[6], (int)o[7]};
+}
+
+template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV>
+struct Cfg {
+    static constexpr int NT = 64 * WAVES_M * WAVES_N;
+    static constexpr int BM = WAVES_M * TM * 16;
+    static constexpr int BN = WAVES_N * TN * 16;
+    static constexpr int XPS = (BM + 4) * 16;  // bytes per activation k-plane (+4 chunks: staggers the planes over the banks)
+    static constexpr int WPS = (BN + 4) * 16;
+    static constexpr int STAGE = 4 * XPS + 4 * WPS;
+    static constexpr int XL = (BM * 4 + NT - 1) / NT;   // 16-byte activation chunks per thread per K-step
+    static constexpr int WL8 = (BN * 2 + NT - 1) / NT;  // 16-byte chunks per thread per 8-bit unit
+    static constexpr int WL4 = (BN + NT - 1) / NT;      // 16-byte chunks per thread per 4-bit unit
+    static constexpr int LDS_BYTES = 2 * STAGE;
+};
+
+template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void k_mixed(const GemmParams p)
+{
+    using C_ = Cfg<WAVES_M, WAVES_N, TM, TN, CONV>;
+    constexpr int NT = C_::NT, BM = C_::BM, BN = C_::BN, XPS = C_::XPS, WPS = C_::WPS, STAGE = C_::STAGE;
+    constexpr int XL = C_::XL, WL8 = C_::WL8, WL4 = C_::WL4;
+    extern __shared__ __align__(16) unsigned char lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+    // ---- block -> tile.  Consecutive block ids land on different XCDs (8 of them, each with its own
+    // L2); renumber so that the blocks sharing an XCD walk neighbouring tiles, then sweep bands of 8
+    // tile rows with the tile column varying slowest inside a band (weights stay L2-resident).
+    int tile_m, tile_n;
+    {
+        const int nb = gridDim.x;
+        int b = blockIdx.x;
+        if (nb % 8 == 0) b = (b % 8) * (nb / 8) + b / 8;
+        constexpr int GMB = 8;
+        const int band = b / (GMB * p.tiles_n);
+        const int rows_in_band = min(GMB, p.tiles_m - band * GMB);
+        const int r = b - band * GMB * p.tiles_n;
+        tile_m = band * GMB + r % rows_in_band;
+        tile_n = r / rows_in_band;
+    }
+    const int64_t m0 = (int64_t)tile_m * BM;
+    const int n0 = tile_n * BN;
+
+    // ---- per-thread activation chunk slots: slot i -> (row i/4, k-plane i%4)
+    int64_t xbase[XL];  // linear: byte offset of the row; conv: pixel index of image b's origin
+    int xh0[XL], xw0[XL];
+    bool xrow_ok[XL];
+#pragma unroll
+    for (int j = 0; j < XL; ++j) {
+        const int slot = tid + j * NT;
+        const int row = slot >> 2;
+        const int64_t m = m0 + row;
+        xrow_ok[j] = (slot < BM * 4) && (m < p.M);
+        if (CONV) {
+            const int64_t mm = xrow_ok[j] ? m : 0;
+            const int wo = (int)(mm % p.Wo);
+            const int ho = (int)((mm / p.Wo) % p.Ho);
+            const int64_t b = mm / ((int64_t)p.Wo * p.Ho);
+            xbase[j] = b * p.H * p.Wd;
+            xh0[j] = ho * p.stride - p.pad;
+            xw0[j] = wo * p.stride - p.pad;
+        } else {
+            xbase[j] = (xrow_ok[j] ? m : 0) * p.C;
+            xh0[j] = xw0[j] = 0;
+        }
+    }
+
+    v4i xr[XL];
+    v4i wr[2][WL8];
+    int wsh[2][WL4];
+
+    const int steps = p.U >> 1;
+
+    auto unit_is4 = [&](int u) -> bool { return (u % p.CU) * kUnit < p.K4; };
+
+    // ---- global -> registers for K-step s
+    auto load_step = [&](int s) {
+#pragma unroll
+        for (int j = 0; j < XL; ++j) {
+            const int slot = tid + j * NT;
+            const int q = slot & 3;
+            const int u = 2 * s + (q >> 1);
+            const int tap = u / p.CU;
+            const int c32 = u - tap * p.CU;
+            bool ok = xrow_ok[j] && tap < p.T;
+            int64_t off;
+            if (CONV) {
+                const int dy = tap / p.S, dx = tap - dy * p.S;
+                const int hi = xh0[j] + dy, wi = xw0[j] + dx;
+                ok = ok && hi >= 0 && hi < p.H && wi >= 0 && wi < p.Wd;
+                off = (xbase[j] + (int64_t)hi * p.Wd + wi) * p.C + c32 * kUnit + (q & 1) * 16;
+            } else {
+                off = xbase[j] + c32 * kUnit + (q & 1) * 16;
+            }
+            v4i v = {0, 0, 0, 0};
+            if (ok) v = *reinterpret_cast<const v4i *>(p.X + off);
+            xr[j] = v;
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int u = 2 * s + h;
+            if (unit_is4(u)) {
+                const int g = (u % p.CU) >> p.gs_shift;
+#pragma unroll
+                for (int j = 0; j < WL4; ++j) {
+                    const int row = tid + j * NT;
+                    if (row < BN) {
+                        wr[h][j] = *reinterpret_cast<const v4i *>(p.W4 + ((int64_t)u * p.Npad + n0 + row) * 16);
+                        wsh[h][j] = p.wshift[(int64_t)g * p.Npad + n0 + row];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < WL8; ++j) {
+                    const int slot = tid + j * NT;  // (plane q2, row): q2 = slot / BN
+                    if (slot < 2 * BN) {
+                        const int q2 = slot / BN, row = slot - q2 * BN;
+                        wr[h][j] = *reinterpret_cast<const v4i *>(p.W8 + (((int64_t)u * 2 + q2) * p.Npad + n0 + row) * 16);
+                    }
+                }
+            }
+        }
+    };
+
+    // ---- registers -> LDS stage, lowering / expanding the 4-bit units on the way
+    auto store_step = [&](int s, unsigned char *stage) {
+        unsigned char *xs = stage, *ws = stage + 4 * XPS;
+#pragma unroll
+        for (int j = 0; j < XL; ++j) {
+            const int slot = tid + j * NT;
+            if (slot < BM * 4) {
+                const int q = slot & 3, row = slot >> 2;
+                const int u = 2 * s + (q >> 1);
+                v4i v = xr[j];
+                if (unit_is4(u)) {
+                    const int sa = p.ashift[(u % p.CU) >> p.gs_shift];
+                    v = lower16(v, sa);
+                }
+                *reinterpret_cast<v4i *>(xs + q * XPS + row * 16) = v;
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int u = 2 * s + h;
+            if (unit_is4(u)) {
+#pragma unroll
+                for (int j = 0; j < WL4; ++j) {
+                    const int row = tid + j * NT;
+                    if (row < BN) {
+                        v4i a, b;
+                        expand32(wr[h][j], wsh[h][j], a, b);
+                        *reinterpret_cast<v4i *>(ws + (2 * h) * WPS + row * 16) = a;
+                        *reinterpret_cast<v4i *>(ws + (2 * h + 1) * WPS + row * 16) = b;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < WL8; ++j) {
+                    const int slot = tid + j * NT;
+                    if (slot < 2 * BN) {
+                        const int q2 = slot / BN, row = slot - q2 * BN;
+                        *reinterpret_cast<v4i *>(ws + (2 * h + q2) * WPS + row * 16) = wr[h][j];
+                    }
+                }
+            }
+        }
+    };
+
+    v4i acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b) acc[a][b] = (v4i){0, 0, 0, 0};
+
+    const int frag_plane = lane >> 4, frag_row = lane & 15;
+    auto compute = [&](const unsigned char *stage) {
+        const unsigned char *xs = stage + frag_plane * XPS + (wm * TM * 16 + frag_row) * 16;
+        const unsigned char *ws = stage + 4 * XPS + frag_plane * WPS + (wn * TN * 16 + frag_row) * 16;
+        v4i wf[TN];
+#pragma unroll
+        for (int a = 0; a < TN; ++a) wf[a] = *reinterpret_cast<const v4i *>(ws + a * 256);
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+            v4i xf = *reinterpret_cast<const v4i *>(xs + b * 256);
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+                acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[a], xf, acc[a][b], 0, 0, 0);
+        }
+    };
+
+    // ---- main loop: two LDS stages, one barrier per K-step
+    load_step(0);
+    store_step(0, lds);
+    __syncthreads();
+    for (int s = 0; s < steps; ++s) {
+        unsigned char *cur = lds + (s & 1) * STAGE;
+        unsigned char *nxt = lds + ((s + 1) & 1) * STAGE;
+        if (s + 1 < steps) load_step(s + 1);
+        compute(cur);
+        if (s + 1 < steps) store_step(s + 1, nxt);
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane holds output row m (lane & 15) and four consecutive output channels
+    const bool want_q = p.q != nullptr, want_y = p.y != nullptr, want_acc = p.acc != nullptr;
+    const bool n_vec = (p.N & 3) == 0;
+#pragma unroll
+    for (int a = 0; a < TN; ++a) {
+        const int n = n0 + (wn * TN + a) * 16 + 4 * frag_plane;
+        if (n >= p.N) continue;
+        const float4 cs = *reinterpret_cast<const float4 *>(p.cs + n);  // cs/bias are padded to Npad
+        const float4 bi = *reinterpret_cast<const float4 *>(p.bias + n);
+        const float csv[4] = {cs.x, cs.y, cs.z, cs.w}, biv[4] = {bi.x, bi.y, bi.z, bi.w};
+        float mul[4], add[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            mul[i] = csv[i] * p.r_out;
+            add[i] = biv[i] * p.r_out;
+        }
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+            const int64_t m = m0 + (wm * TM + b) * 16 + frag_row;
+            if (m >= p.M) continue;
+            const v4i v = acc[a][b];
+            const int iv[4] = {v.x, v.y, v.z, v.w};
+            const int64_t o = m * p.N + n;
+            if (n_vec) {
+                if (want_acc) *reinterpret_cast<v4i *>(p.acc + o) = v;
+                if (want_y) {
+                    float4 y;
+                    y.x = __builtin_fmaf((float)iv[0], csv[0], biv[0]);
+                    y.y = __builtin_fmaf((float)iv[1], csv[1], biv[1]);
+                    y.z = __builtin_fmaf((float)iv[2], csv[2], biv[2]);
+                    y.w = __builtin_fmaf((float)iv[3], csv[3], biv[3]);
+                    *reinterpret_cast<float4 *>(p.y + o) = y;
+                }
+                if (want_q) {
+                    uint32_t u[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float t = __builtin_fmaf((float)iv[i], mul[i], add[i]);
+                        t = __builtin_amdgcn_fmed3f(t, -128.0f, 127.0f);
+                        u[i] = __builtin_bit_cast(uint32_t, t + 12582912.0f);  // 1.5 * 2^23: integer lands in the low bits
+                    }
+                    uint32_t w01 = __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u);
+                    uint32_t w23 = __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu);
+                    *reinterpret_cast<uint32_t *>(p.q + o) = w01 | w23;
+                }
+            } else {
+                for (int i = 0; i < 4 && n + i < p.N; ++i) {
+                    if (want_acc) p.acc[o + i] = iv[i];
+                    if (want_y) p.y[o + i] = __builtin_fmaf((float)iv[i], csv[i], biv[i]);
+                    if (want_q) {
+                        float t = __builtin_fmaf((float)iv[i], mul[i], add[i]);
+                        t = __builtin_amdgcn_fmed3f(t, -128.0f, 127.0f);
+                        p.q[o + i] = (int8_t)(__builtin_bit_cast(uint32_t, t + 12582912.0f) & 0xFF);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host side: tile-shape choice and launch
+// ---------------------------------------------------------------------------------------------
+
+typedef void (*kernel_fn)(const GemmParams);
+struct TileShape {
+    int BM, BN, lds;
+    kernel_fn lin, conv;
+};
+
+template <int WAVES_M, int WAVES_N, int TM, int TN>
+static TileShape make_shape()
+{
+    using C_ = Cfg<WAVES_M, WAVES_N, TM, TN, false>;
+    return TileShape{C_::BM, C_::BN, C_::LDS_BYTES, k_mixed<WAVES_M, WAVES_N, TM, TN, false>,
+                     k_mixed<WAVES_M, WAVES_N, TM, TN, true>};
+}
+
+static const TileShape *shapes(int *count)
+{
+    static const TileShape tab[] = {
+        make_shape<2, 2, 8, 8>(),   // 256 x 256
+        make_shape<1, 4, 13, 4>(),  // 208 x 256
+        make_shape<1, 4, 10, 4>(),  // 160 x 256
+        make_shape<2, 2, 4, 8>(),   // 128 x 256
+        make_shape<2, 2, 8, 4>(),   // 256 x 128
+        make_shape<2, 2, 4, 4>(),   // 128 x 128
+        make_shape<2, 2, 2, 4>(),   //  64 x 128
+        make_shape<2, 2, 2, 2>(),   //  64 x  64
+    };
+    *count = (int)(sizeof(tab) / sizeof(tab[0]));
+    return tab;
+}
+
+static int g_num_cu = 0;
+static int g_force_shape = -1;
+
+// Pick the tile shape with the smallest modelled time: waves of blocks over the CUs times the cost
+// of one tile (matrix work plus a per-K-step overhead that penalises small tiles).
+static const TileShape &choose_shape(int64_t M, int N)
+{
+    int cnt;
+    const TileShape *tab = shapes(&cnt);
+    if (g_force_shape >= 0 && g_force_shape < cnt) return tab[g_force_shape];
+    if (g_num_cu <= 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            g_num_cu = prop.multiProcessorCount;
+        if (g_num_cu <= 0) g_num_cu = 256;
+    }
+    double best = 1e300;
+    int bi = 0;
+    for (int i = 0; i < cnt; ++i) {
+        const double tm = (double)((M + tab[i].BM - 1) / tab[i].BM), tn = (double)((N + tab[i].BN - 1) / tab[i].BN);
+        const double rounds = __builtin_ceil(tm * tn / g_num_cu);
+        // per K-step: BM*BN/256 MFMA issue slots of 16 cycles per SIMD + staging cost ~ (BM + BN) * 0.6
+        const double tile = (double)tab[i].BM * tab[i].BN / 256.0 * 4.0 + 0.6 * (tab[i].BM + tab[i].BN) + 40.0;
+        const double cost = rounds * tile;
+        if (cost < best) {
+            best = cost;
+            bi = i;
+        }
+    }
+    return tab[bi];
+}
+
+static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, bool conv,
+                  int H, int Wd, int Ho, int Wo, int stride, int pad)
+{
+    GemmParams p;
+    p.X = X; p.W8 = L->d_w8; p.W4 = L->d_w4; p.wshift = L->d_wshift; p.ashift = L->d_ashift;
+    p.cs = L->d_cs; p.bias = L->d_bias;
+    p.acc = out->acc; p.y = out->y; p.q = out->q;
+    p.r_out = out->q ? 1.0f / out->out_scale : 1.0f;
+    p.M = M; p.N = L->N; p.Npad = L->Npad; p.C = L->C;
+    p.K4 = L->max_4bit_ch;
+    p.gs_shift = L->group_size == 64 ? 1 : 0;
+    p.U = L->U; p.CU = L->C / kUnit; p.T = L->T;
+    p.H = H; p.Wd = Wd; p.Ho = Ho; p.Wo = Wo; p.S = L->S; p.stride = stride; p.pad = pad;
+    const TileShape &ts = choose_shape(M, L->N);
+    p.tiles_m = (int)((M + ts.BM - 1) / ts.BM);
+    p.tiles_n = (L->N + ts.BN - 1) / ts.BN;
+    const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
+    if (blocks > 0x7fffffff) return FLEXIQ_EINVAL;
+    kernel_fn fn = conv ? ts.conv : ts.lin;
+    {  // raise the dynamic-LDS limit once per kernel
+        static std::mutex mu;
+        static std::vector<const void *> attr_done;
+        std::lock_guard<std::mutex> lk(mu);
+        bool seen = false;
+        for (const void *f : attr_done) seen = seen || f == (const void *)fn;
+        if (!seen) {
+            FLEXIQ_HIP(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, ts.lds));
+            attr_done.push_back((const void *)fn);
+        }
+    }
+    const int nt = 256;
+    hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3(nt), ts.lds, (hipStream_t)stream, p);
+    FLEXIQ_HIP(hipGetLastError());
+    return FLEXIQ_OK;
+}
+
+static int check_out(const flexiq_out *out)
+{
+    if (!out || (!out->acc && !out->y && !out->q)) return FLEXIQ_EINVAL;
+    if (out->q && !(out->out_scale > 0.0f)) return FLEXIQ_EINVAL;
+    const void *ps[] = {out->acc, out->y, out->q};
+    for (const void *q : ps)
+        if (q && (reinterpret_cast<uintptr_t>(q) & 15u)) return FLEXIQ_EALIGN;
+    return FLEXIQ_OK;
+}
+
+}  // namespace flexiq
+
+using namespace flexiq;
+
+// Test / tuning hook: force tile shape `index` of the internal table (-1 = automatic choice).
+extern "C" int flexiq_debug_force_tile(int index)
+{
+    int cnt;
+    (void)shapes(&cnt);
+    if (index < -1 || index >= cnt) return FLEXIQ_EINVAL;
+    g_force_shape = index;
+    return cnt;
+}
+
+extern "C" int flexiq_mixed_gemm(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream)
+{
+    if (!L || M < 0 || L->R != 1 || L->S != 1) return FLEXIQ_EINVAL;
+    int rc = check_out(out);
+    if (rc) return rc;
+    if (M == 0) return FLEXIQ_OK;
+    if (!X) return FLEXIQ_EINVAL;
+    if (reinterpret_cast<uintptr_t>(X) & 15u) return FLEXIQ_EALIGN;
+    return launch(L, X, M, out, stream, false, 1, 1, 1, 1, 1, 0);
+}
+
+extern "C" int flexiq_mixed_conv_implicit(const flexiq_layer *L, const int8_t *X, int32_t B, int32_t H, int32_t W,
+                                          int32_t stride, int32_t pad, const flexiq_out *out, void *stream)
+{
+    if (!L || B < 0 || H <= 0 || W <= 0 || stride <= 0 || pad < 0) return FLEXIQ_EINVAL;
+    if (H + 2 * pad < L->R || W + 2 * pad < L->S) return FLEXIQ_EINVAL;
+    int rc = check_out(out);
+    if (rc) return rc;
+    const int Ho = (H + 2 * pad - L->R) / stride + 1, Wo = (W + 2 * pad - L->S) / stride + 1;
+    const int64_t M = (int64_t)B * Ho * Wo;
+    if (M == 0) return FLEXIQ_OK;
+    if (!X) return FLEXIQ_EINVAL;
+    if (reinterpret_cast<uintptr_t>(X) & 15u) return FLEXIQ_EALIGN;
+    return launch(L, X, M, out, stream, true, H, W, Ho, Wo, stride, pad);
+}

@@ -1,0 +1,462 @@
+// Offline steps of the method as HIP kernels: per-output-channel weight quantisation (Eq. 1),
+// channel scores and order (Section 4.2), extraction positions (Section 4.1), layout in stored
+// order with same-bitwidth channels contiguous (Section 5), and the packed 8-bit / 4-bit weight
+// tiles the GEMM kernels stream.  Also the layer handle, the ratio switch (Section 7) and the
+// small element-wise run-time kernels (activation quantiser, stand-alone bit-lowering, channel
+// reorder operator).
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <numeric>
+#include <string>
+
+#include "flexiq_internal.h"
+
+namespace flexiq {
+
+static std::mutex g_err_mu;
+static std::string g_err = "";
+
+void set_hip_error(hipError_t e, const char *what)
+{
+    std::lock_guard<std::mutex> lk(g_err_mu);
+    g_err = std::string(hipGetErrorName(e)) + ": " + hipGetErrorString(e) + " in " + what;
+    (void)hipGetLastError();  // clear the sticky "last error"
+}
+
+// ---------------------------------------------------------------------------------------------
+// Weight quantisation, Eq. 1 with one scale per output channel
+// ---------------------------------------------------------------------------------------------
+
+// One block per output channel n: scale[n] = max|W[n][:]| / 127 (1 if the row is all zero).
+__global__ void k_row_scale(const float *__restrict__ W, int64_t Kt, float *__restrict__ scale)
+{
+    __shared__ float red[256];
+    const float *row = W + (int64_t)blockIdx.x * Kt;
+    float m = 0.0f;
+    for (int64_t i = threadIdx.x; i < Kt; i += blockDim.x) m = fmaxf(m, fabsf(row[i]));
+    red[threadIdx.x] = m;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) scale[blockIdx.x] = red[0] == 0.0f ? 1.0f : __fdiv_rn(red[0], 127.0f);
+}
+
+__device__ __forceinline__ int quant_code(float x, float S, float lo, float hi)
+{
+    float t = rintf(__fdiv_rn(x, S));  // round to nearest, ties to even
+    t = fminf(fmaxf(t, lo), hi);
+    return (int)t;
+}
+
+// q[n][i] = clip(round(W[n][i] / scale[n]), -127, 127), natural channel order.
+__global__ void k_quantize_rows(const float *__restrict__ W, const float *__restrict__ scale, int64_t Kt,
+                                int64_t total, int8_t *__restrict__ q)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    q[i] = (int8_t)quant_code(W[i], scale[i / Kt], -127.0f, 127.0f);
+}
+
+// wmax[c] = max over output channels and taps of |Wq[n][t][c]|  (the weight range of Section 4.2).
+__global__ void k_chan_wmax(const int8_t *__restrict__ q, int N, int T, int C, int *__restrict__ wmax)
+{
+    int n = blockIdx.x;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) {
+        int m = 0;
+        for (int t = 0; t < T; ++t) {
+            int w = q[((int64_t)n * T + t) * C + c];
+            m = max(m, w < 0 ? -w : w);
+        }
+        atomicMax(&wmax[c], m);
+    }
+}
+
+// Extraction position of the weights of (output channel n, group g): OR the magnitude bits of the
+// group's values over all taps (ones' complement for negatives), take the highest set bit p, keep
+// the three bits below it: s = max(0, p - 2)  (Section 4.1).
+__global__ void k_weight_shift(const int8_t *__restrict__ q, const int32_t *__restrict__ perm, int N, int T, int C,
+                               int gs, int Npad, uint8_t *__restrict__ ws_ng, uint8_t *__restrict__ ws_gn)
+{
+    int G = C / gs;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)N * G) return;
+    int n = (int)(i / G), g = (int)(i % G);
+    unsigned m = 0;
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < gs; ++j) {
+            int w = q[((int64_t)n * T + t) * C + perm[g * gs + j]];
+            m |= (unsigned)(w >= 0 ? w : ~w) & 0x7Fu;
+        }
+    int p = m ? 31 - __clz(m) : -1;
+    int s = max(0, p - 2);
+    ws_ng[(int64_t)n * G + g] = (uint8_t)s;
+    ws_gn[(int64_t)g * Npad + n] = (uint8_t)s;
+}
+
+// One thread per (unit u, padded output channel n): gathers the 32 stored channels of the unit and
+// writes the two 16-byte planes of the 8-bit tile and the 16 bytes of 4-bit codes.
+__global__ void k_pack_tiles(const int8_t *__restrict__ q, const int32_t *__restrict__ perm,
+                             const uint8_t *__restrict__ ws_ng, int N, int T, int C, int gs, int Npad, int U,
+                             int8_t *__restrict__ w8, uint8_t *__restrict__ w4)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)U * Npad) return;
+    int u = (int)(i / Npad), n = (int)(i % Npad);
+    int CU = C / kUnit;
+    int tap = u / CU, c32 = u % CU;
+    int v[32];
+    int s = 0;
+    if (n < N && tap < T) {
+        for (int j = 0; j < 32; ++j) v[j] = q[((int64_t)n * T + tap) * C + perm[c32 * 32 + j]];
+        s = ws_ng[(int64_t)n * (C / gs) + (c32 * 32) / gs];
+    } else {
+        for (int j = 0; j < 32; ++j) v[j] = 0;
+    }
+    uint32_t d8[8], d4[4];
+    for (int d = 0; d < 8; ++d)
+        d8[d] = (uint32_t)(v[4 * d] & 0xFF) | ((uint32_t)(v[4 * d + 1] & 0xFF) << 8) |
+                ((uint32_t)(v[4 * d + 2] & 0xFF) << 16) | ((uint32_t)(v[4 * d + 3] & 0xFF) << 24);
+    for (int e = 0; e < 4; ++e) {
+        uint32_t w = 0;
+        for (int b = 0; b < 4; ++b) {
+            int lo = min(7, max(-8, v[8 * e + b] >> s)) & 0xF;
+            int hi = min(7, max(-8, v[8 * e + 4 + b] >> s)) & 0xF;
+            w |= (uint32_t)(lo | (hi << 4)) << (8 * b);
+        }
+        d4[e] = w;
+    }
+    uint4 *p8 = reinterpret_cast<uint4 *>(w8);
+    p8[((int64_t)u * 2 + 0) * Npad + n] = make_uint4(d8[0], d8[1], d8[2], d8[3]);
+    p8[((int64_t)u * 2 + 1) * Npad + n] = make_uint4(d8[4], d8[5], d8[6], d8[7]);
+    reinterpret_cast<uint4 *>(w4)[(int64_t)u * Npad + n] = make_uint4(d4[0], d4[1], d4[2], d4[3]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Run-time element-wise kernels
+// ---------------------------------------------------------------------------------------------
+
+// Eq. 1 for activations: four values per thread, one packed dword out.
+__global__ void k_quantize_act(const float *__restrict__ x, int8_t *__restrict__ q, int64_t n, float S)
+{
+    int64_t i4 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i4 >= n) return;
+    if (i4 + 4 <= n) {
+        float4 v = *reinterpret_cast<const float4 *>(x + i4);
+        uint32_t w = (uint32_t)(quant_code(v.x, S, -127.f, 127.f) & 0xFF) |
+                     ((uint32_t)(quant_code(v.y, S, -127.f, 127.f) & 0xFF) << 8) |
+                     ((uint32_t)(quant_code(v.z, S, -127.f, 127.f) & 0xFF) << 16) |
+                     ((uint32_t)(quant_code(v.w, S, -127.f, 127.f) & 0xFF) << 24);
+        *reinterpret_cast<uint32_t *>(q + i4) = w;
+    } else {
+        for (int64_t i = i4; i < n; ++i) q[i] = (int8_t)quant_code(x[i], S, -127.f, 127.f);
+    }
+}
+
+// Stand-alone effective-bit extraction (Section 4.1): eight channels per thread.
+__global__ void k_bitlower(const int8_t *__restrict__ src, uint8_t *__restrict__ dst, int64_t rows, int C, int gs,
+                           const uint8_t *__restrict__ shifts, int per_row, int mode)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int C8 = C / 8;
+    if (i >= rows * C8) return;
+    int64_t row = i / C8;
+    int c0 = (int)(i % C8) * 8;
+    int G = C / gs;
+    int s = per_row ? shifts[row * G + c0 / gs] : shifts[c0 / gs];  // 8 | group size: one position for all eight
+    uint2 in = *reinterpret_cast<const uint2 *>(src + row * C + c0);
+    uint32_t w[2] = {in.x, in.y};
+    int half = (mode & 1) && s > 0 ? 1 << (s - 1) : 0;
+    uint32_t out = 0;
+    for (int j = 0; j < 8; ++j) {
+        int v = (int)(int8_t)((w[j >> 2] >> (8 * (j & 3))) & 0xFF);
+        int l = min(7, max(-8, (v + half) >> s)) & 0xF;
+        out |= (uint32_t)l << (4 * j);
+    }
+    *reinterpret_cast<uint32_t *>(dst + row * (C / 2) + c0 / 2) = out;
+}
+
+// Residual reorder operator (Section 5, step 3): dst[row][j] = src[row][perm[j]], four bytes per thread.
+__global__ void k_permute_channels(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
+                                   const int32_t *__restrict__ perm, int64_t rows, int C)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int C4 = C / 4;
+    if (i >= rows * C4) return;
+    int64_t row = i / C4;
+    int j0 = (int)(i % C4) * 4;
+    const int8_t *s = src + row * C;
+    uint32_t w = (uint32_t)(uint8_t)s[perm[j0]] | ((uint32_t)(uint8_t)s[perm[j0 + 1]] << 8) |
+                 ((uint32_t)(uint8_t)s[perm[j0 + 2]] << 16) | ((uint32_t)(uint8_t)s[perm[j0 + 3]] << 24);
+    *reinterpret_cast<uint32_t *>(dst + row * C + j0) = w;
+}
+
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace flexiq
+
+using namespace flexiq;
+
+extern "C" const char *flexiq_strerror(int status)
+{
+    switch (status) {
+        case FLEXIQ_OK: return "ok";
+        case FLEXIQ_EINVAL: return "invalid argument";
+        case FLEXIQ_EALIGN: return "device pointer not 16-byte aligned";
+        case FLEXIQ_ENOMEM: return "out of memory";
+        case FLEXIQ_EHIP: return "HIP runtime error";
+        default: return "unknown flexiq status";
+    }
+}
+
+extern "C" const char *flexiq_last_hip_error(void)
+{
+    static thread_local std::string copy;
+    std::lock_guard<std::mutex> lk(g_err_mu);
+    copy = g_err;
+    return copy.c_str();
+}
+
+namespace {
+struct DevBuf {  // frees on scope exit unless released
+    void *p = nullptr;
+    ~DevBuf()
+    {
+        if (p) (void)hipFree(p);
+    }
+    void *release()
+    {
+        void *r = p;
+        p = nullptr;
+        return r;
+    }
+};
+}  // namespace
+
+extern "C" int flexiq_layer_free(flexiq_layer *L)
+{
+    if (!L) return FLEXIQ_OK;
+    void *bufs[] = {L->d_w8, L->d_w4, L->d_wshift, L->d_ashift, L->d_cs, L->d_bias, L->d_perm};
+    int rc = FLEXIQ_OK;
+    for (void *b : bufs)
+        if (b && hipFree(b) != hipSuccess) rc = FLEXIQ_EHIP;
+    delete L;
+    return rc;
+}
+
+extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **out)
+{
+    if (!d || !out || !d->W || !d->act_absmax) return FLEXIQ_EINVAL;
+    if (d->N <= 0 || d->C <= 0 || d->R <= 0 || d->S <= 0) return FLEXIQ_EINVAL;
+    if (d->group_size != 32 && d->group_size != 64) return FLEXIQ_EINVAL;
+    if (d->C % d->group_size != 0) return FLEXIQ_EINVAL;
+    if (!(d->x_scale > 0.0f) || !std::isfinite(d->x_scale)) return FLEXIQ_EINVAL;
+    const int N = d->N, C = d->C, T = d->R * d->S, gs = d->group_size, G = C / gs;
+    if (d->perm) {  // must be a permutation of 0..C-1
+        std::vector<char> seen(C, 0);
+        for (int j = 0; j < C; ++j) {
+            int v = d->perm[j];
+            if (v < 0 || v >= C || seen[v]) return FLEXIQ_EINVAL;
+            seen[v] = 1;
+        }
+    }
+    flexiq_layer *L = new (std::nothrow) flexiq_layer();
+    if (!L) return FLEXIQ_ENOMEM;
+    struct Guard {
+        flexiq_layer *l;
+        ~Guard()
+        {
+            if (l) flexiq_layer_free(l);
+        }
+    } guard{L};
+    L->N = N; L->C = C; L->R = d->R; L->S = d->S; L->group_size = gs; L->G = G; L->T = T;
+    const int CU = C / kUnit;
+    const int U = (T * CU + 1) & ~1;  // an even number of units: a K-step is two of them
+    L->U = U;
+    L->Npad = (int)(cdiv(N, kNPadTo) * kNPadTo);
+    L->max_4bit_ch = 0;
+    L->x_scale = d->x_scale;
+    L->has_bias = d->bias != nullptr;
+    L->d_w8 = nullptr; L->d_w4 = nullptr; L->d_wshift = nullptr; L->d_ashift = nullptr;
+    L->d_cs = nullptr; L->d_bias = nullptr; L->d_perm = nullptr;
+    FLEXIQ_HIP(hipGetDevice(&L->device));
+    const int Npad = L->Npad;
+    const int64_t Kt = (int64_t)T * C, total = (int64_t)N * Kt;
+
+    DevBuf dW, dScale, dQ, dWmax, dWsNG;
+    FLEXIQ_HIP(hipMalloc(&dW.p, total * sizeof(float)));
+    FLEXIQ_HIP(hipMalloc(&dScale.p, N * sizeof(float)));
+    FLEXIQ_HIP(hipMalloc(&dQ.p, total));
+    FLEXIQ_HIP(hipMalloc(&dWmax.p, C * sizeof(int)));
+    FLEXIQ_HIP(hipMalloc(&dWsNG.p, (size_t)N * G));
+    FLEXIQ_HIP(hipMemcpy(dW.p, d->W, total * sizeof(float), hipMemcpyHostToDevice));
+    FLEXIQ_HIP(hipMemset(dWmax.p, 0, C * sizeof(int)));
+
+    k_row_scale<<<N, 256>>>((const float *)dW.p, Kt, (float *)dScale.p);
+    k_quantize_rows<<<(unsigned)cdiv(total, 256), 256>>>((const float *)dW.p, (const float *)dScale.p, Kt, total,
+                                                         (int8_t *)dQ.p);
+    k_chan_wmax<<<N, 256>>>((const int8_t *)dQ.p, N, T, C, (int *)dWmax.p);
+    FLEXIQ_HIP(hipGetLastError());
+
+    L->w_scale.resize(N);
+    std::vector<int> wmax(C);
+    FLEXIQ_HIP(hipMemcpy(L->w_scale.data(), dScale.p, N * sizeof(float), hipMemcpyDeviceToHost));
+    FLEXIQ_HIP(hipMemcpy(wmax.data(), dWmax.p, C * sizeof(int), hipMemcpyDeviceToHost));
+
+    // Calibration range of each channel as an 8-bit code, error-estimation score, stored order.
+    std::vector<int> rq(C);
+    for (int c = 0; c < C; ++c) {
+        float t = nearbyintf(d->act_absmax[c] / d->x_scale);
+        rq[c] = (int)std::min(127.0f, std::max(0.0f, t));
+    }
+    L->perm.resize(C);
+    if (d->perm) {
+        std::memcpy(L->perm.data(), d->perm, C * sizeof(int32_t));
+    } else {
+        std::vector<int64_t> score(C);
+        for (int c = 0; c < C; ++c) score[c] = (int64_t)wmax[c] * rq[c];
+        std::iota(L->perm.begin(), L->perm.end(), 0);
+        std::stable_sort(L->perm.begin(), L->perm.end(), [&](int a, int b) { return score[a] < score[b]; });
+    }
+    // Activation position of a group: the smallest that fits [-a, a], a = widest calibrated range in the group.
+    L->a_shift.resize(G);
+    for (int g = 0; g < G; ++g) {
+        int a = 0;
+        for (int j = 0; j < gs; ++j) a = std::max(a, rq[L->perm[g * gs + j]]);
+        int s = 0;
+        while (s < 4 && a > (8 << s) - 1) ++s;
+        L->a_shift[g] = (uint8_t)s;
+    }
+
+    FLEXIQ_HIP(hipMalloc((void **)&L->d_perm, C * sizeof(int32_t)));
+    FLEXIQ_HIP(hipMemcpy(L->d_perm, L->perm.data(), C * sizeof(int32_t), hipMemcpyHostToDevice));
+    FLEXIQ_HIP(hipMalloc((void **)&L->d_ashift, G));
+    FLEXIQ_HIP(hipMemcpy(L->d_ashift, L->a_shift.data(), G, hipMemcpyHostToDevice));
+    FLEXIQ_HIP(hipMalloc((void **)&L->d_wshift, (size_t)G * Npad));
+    FLEXIQ_HIP(hipMemset(L->d_wshift, 0, (size_t)G * Npad));
+    FLEXIQ_HIP(hipMalloc((void **)&L->d_w8, (size_t)U * 2 * Npad * 16));
+    FLEXIQ_HIP(hipMalloc((void **)&L->d_w4, (size_t)U * Npad * 16));
+
+    k_weight_shift<<<(unsigned)cdiv((int64_t)N * G, 256), 256>>>((const int8_t *)dQ.p, L->d_perm, N, T, C, gs, Npad,
+                                                                 (uint8_t *)dWsNG.p, L->d_wshift);
+    k_pack_tiles<<<(unsigned)cdiv((int64_t)U * Npad, 256), 256>>>((const int8_t *)dQ.p, L->d_perm,
+                                                                  (const uint8_t *)dWsNG.p, N, T, C, gs, Npad, U,
+                                                                  L->d_w8, L->d_w4);
+    FLEXIQ_HIP(hipGetLastError());
+    L->w_shift.resize((size_t)N * G);
+    FLEXIQ_HIP(hipMemcpy(L->w_shift.data(), dWsNG.p, (size_t)N * G, hipMemcpyDeviceToHost));
+
+    std::vector<float> cs(Npad, 0.0f), bias(Npad, 0.0f);
+    for (int n = 0; n < N; ++n) cs[n] = d->x_scale * L->w_scale[n];
+    if (d->bias) {
+        L->bias.assign(d->bias, d->bias + N);
+        std::copy(d->bias, d->bias + N, bias.begin());
+    }
+    FLEXIQ_HIP(hipMalloc((void **)&L->d_cs, Npad * sizeof(float)));
+    FLEXIQ_HIP(hipMalloc((void **)&L->d_bias, Npad * sizeof(float)));
+    FLEXIQ_HIP(hipMemcpy(L->d_cs, cs.data(), Npad * sizeof(float), hipMemcpyHostToDevice));
+    FLEXIQ_HIP(hipMemcpy(L->d_bias, bias.data(), Npad * sizeof(float), hipMemcpyHostToDevice));
+    FLEXIQ_HIP(hipDeviceSynchronize());
+    guard.l = nullptr;
+    *out = L;
+    return FLEXIQ_OK;
+}
+
+extern "C" int flexiq_layer_info(const flexiq_layer *L, const int32_t **perm, const uint8_t **a_shift,
+                                 const uint8_t **w_shift, const float **w_scale, int32_t *G, int32_t *max_4bit_ch)
+{
+    if (!L) return FLEXIQ_EINVAL;
+    if (perm) *perm = L->perm.data();
+    if (a_shift) *a_shift = L->a_shift.data();
+    if (w_shift) *w_shift = L->w_shift.data();
+    if (w_scale) *w_scale = L->w_scale.data();
+    if (G) *G = L->G;
+    if (max_4bit_ch) *max_4bit_ch = L->max_4bit_ch;
+    return FLEXIQ_OK;
+}
+
+extern "C" int flexiq_layer_dump(const flexiq_layer *L, int8_t *w8, uint8_t *w4)
+{
+    if (!L) return FLEXIQ_EINVAL;
+    const int N = L->N, C = L->C, T = L->T, Npad = L->Npad, U = L->U, CU = C / kUnit;
+    FLEXIQ_HIP(hipDeviceSynchronize());
+    if (w8) {
+        std::vector<int8_t> raw((size_t)U * 2 * Npad * 16);
+        FLEXIQ_HIP(hipMemcpy(raw.data(), L->d_w8, raw.size(), hipMemcpyDeviceToHost));
+        for (int n = 0; n < N; ++n)
+            for (int t = 0; t < T; ++t)
+                for (int c = 0; c < C; ++c) {
+                    int u = t * CU + c / 32, q2 = (c % 32) / 16, j = c % 16;
+                    w8[((size_t)n * T + t) * C + c] = raw[(((size_t)u * 2 + q2) * Npad + n) * 16 + j];
+                }
+    }
+    if (w4) {
+        std::vector<uint8_t> raw((size_t)U * Npad * 16);
+        FLEXIQ_HIP(hipMemcpy(raw.data(), L->d_w4, raw.size(), hipMemcpyDeviceToHost));
+        std::memset(w4, 0, (size_t)N * T * (C / 2));
+        for (int n = 0; n < N; ++n)
+            for (int t = 0; t < T; ++t)
+                for (int c = 0; c < C; ++c) {
+                    int u = t * CU + c / 32, j = c % 32;
+                    int e = j / 8, r = j % 8, b = r % 4, hi = r / 4;
+                    int code = (raw[((size_t)u * Npad + n) * 16 + e * 4 + b] >> (4 * hi)) & 0xF;
+                    w4[((size_t)n * T + t) * (C / 2) + c / 2] |= (uint8_t)(code << (4 * (c & 1)));
+                }
+    }
+    return FLEXIQ_OK;
+}
+
+extern "C" int flexiq_set_ratio(flexiq_layer *L, float r, int32_t *max_4bit_ch)
+{
+    if (!L || !(r >= 0.0f) || !(r <= 1.0f)) return FLEXIQ_EINVAL;
+    int g4 = (int)std::ceil((double)r * L->G - 1e-6);
+    g4 = std::min(std::max(g4, 0), (int)L->G);
+    L->max_4bit_ch = g4 * L->group_size;
+    if (max_4bit_ch) *max_4bit_ch = L->max_4bit_ch;
+    return FLEXIQ_OK;
+}
+
+extern "C" int flexiq_quantize_act(const float *x, int8_t *q, int64_t n, float scale, void *stream)
+{
+    if (n < 0 || !(scale > 0.0f)) return FLEXIQ_EINVAL;
+    if (n == 0) return FLEXIQ_OK;
+    if (!x || !q) return FLEXIQ_EINVAL;
+    if (!aligned16(x) || !aligned16(q)) return FLEXIQ_EALIGN;
+    int64_t threads = cdiv(n, 4);
+    k_quantize_act<<<(unsigned)cdiv(threads, 256), 256, 0, (hipStream_t)stream>>>(x, q, n, scale);
+    FLEXIQ_HIP(hipGetLastError());
+    return FLEXIQ_OK;
+}
+
+extern "C" int flexiq_bitlower(const int8_t *src, uint8_t *dst, int64_t rows, int32_t C, int32_t group_size,
+                               const uint8_t *shifts, int per_row, int mode, void *stream)
+{
+    if (rows < 0 || C <= 0 || group_size <= 0 || C % group_size != 0 || group_size % 8 != 0) return FLEXIQ_EINVAL;
+    if (mode != 0 && mode != 1) return FLEXIQ_EINVAL;
+    if (rows == 0) return FLEXIQ_OK;
+    if (!src || !dst || !shifts) return FLEXIQ_EINVAL;
+    if (!aligned16(src) || !aligned16(dst)) return FLEXIQ_EALIGN;
+    int64_t threads = rows * (C / 8);
+    k_bitlower<<<(unsigned)cdiv(threads, 256), 256, 0, (hipStream_t)stream>>>(src, dst, rows, C, group_size, shifts,
+                                                                             per_row ? 1 : 0, mode);
+    FLEXIQ_HIP(hipGetLastError());
+    return FLEXIQ_OK;
+}
+
+extern "C" int flexiq_permute_channels(const flexiq_layer *L, const int8_t *src, int8_t *dst, int64_t rows,
+                                       void *stream)
+{
+    if (!L || rows < 0) return FLEXIQ_EINVAL;
+    if (rows == 0) return FLEXIQ_OK;
+    if (!src || !dst || src == dst) return FLEXIQ_EINVAL;
+    if (!aligned16(src) || !aligned16(dst)) return FLEXIQ_EALIGN;
+    int64_t threads = rows * (L->C / 4);
+    k_permute_channels<<<(unsigned)cdiv(threads, 256), 256, 0, (hipStream_t)stream>>>(src, dst, L->d_perm, rows, L->C);
+    FLEXIQ_HIP(hipGetLastError());
+    return FLEXIQ_OK;
+}

@@ -1,0 +1,257 @@
+"""GPU parity: the HIP library through its C ABI against the CPU oracle, element by element.
+int32 accumulators, int8 codes, indices and packed bytes must match bit for bit; fp32 outputs
+within 1e-5 relative."""
+import numpy as np
+import pytest
+
+import workloads
+from helpers import both_layers, check_y
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import oracle
+    import paper_2510_02822_amd as fq
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    fq.load()
+    oracle.build()
+    return torch, oracle, fq, torch.device("cuda:0")
+
+
+def _dev(torch, a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def test_pack_matches_oracle(env):
+    torch, oracle, fq, dev = env
+    for case in (workloads.config0(), workloads.make_linear("odd", 9, 1, 8, 192, 72, 64, outlier_frac=0.02),
+                 workloads.make_conv("c", 9, 2, 1, 5, 5, 96, 40, 3, 3, 1, 1, 32)):
+        ol, hl, _ = both_layers(case)
+        info = hl.info()
+        assert (info["perm"] == ol.perm).all()
+        assert (info["w_scale"] == ol.w_scale).all()
+        assert (info["a_shift"] == ol.a_shift).all()
+        assert (info["w_shift"] == ol.w_shift).all()
+        assert info["G"] == ol.G and info["max_4bit_ch"] == 0
+        w8, w4 = fq.flexiq_layer_dump(hl)
+        T = ol.R * ol.S
+        Wq = ol.Wq.reshape(ol.N, T, ol.C)
+        assert (w8 == Wq).all()
+        # the cached 4-bit copy of ALL groups is the oracle's bit-lowering of the stored 8-bit weights
+        for t in range(T):
+            ref4 = oracle.bitlower_pack(Wq[:, t, :], ol.group_size, ol.w_shift, per_row=True)
+            assert (w4[:, t, :] == ref4).all()
+
+
+def test_pack_with_given_perm(env):
+    torch, oracle, fq, dev = env
+    case = workloads.config0()
+    perm = np.random.default_rng(5).permutation(case.K).astype(np.int32)
+    ol, hl, _ = both_layers(case, perm=perm)
+    assert (hl.info()["perm"] == perm).all()
+    w8, _ = fq.flexiq_layer_dump(hl)
+    assert (w8[:, 0, :] == ol.Wq.reshape(ol.N, ol.C)).all()
+
+
+def test_quantize_act(env):
+    torch, oracle, fq, dev = env
+    rng = np.random.default_rng(1)
+    for n in (0, 1, 3, 4, 5, 1023, 4096, 100003):
+        x = (rng.standard_normal(n) * 3).astype(np.float32)
+        if n > 8:
+            x[:8] = np.array([0.5, 1.5, 2.5, -0.5, -1.5, 1e9, -1e9, 0.0], np.float32) * np.float32(0.05)
+        S = 0.05
+        xd = torch.empty(max(n, 4), dtype=torch.float32, device=dev)[:n]
+        xd.copy_(torch.from_numpy(x))
+        q = fq.flexiq_quantize_act(xd, S)
+        torch.cuda.synchronize()
+        assert (q.cpu().numpy() == oracle.quantize(x, S)).all()
+
+
+def test_bitlower_exhaustive(env):
+    torch, oracle, fq, dev = env
+    # all 256 values x 5 positions x both modes
+    vals = np.arange(-128, 128, dtype=np.int16).astype(np.int8)
+    src = np.tile(vals, (5, 1))                                 # rows: one per position, C = 256
+    for mode in (0, 1):
+        for gs in (32, 64):
+            G = 256 // gs
+            shifts = np.repeat(np.arange(5, dtype=np.uint8)[:, None], G, axis=1)   # per row
+            got = fq.flexiq_bitlower(_dev(torch, src, dev), gs, _dev(torch, shifts, dev), per_row=True, mode=mode)
+            torch.cuda.synchronize()
+            assert (got.cpu().numpy() == oracle.bitlower_pack(src, gs, shifts, per_row=True, mode=mode)).all()
+    rng = np.random.default_rng(2)
+    src = rng.integers(-128, 128, size=(37, 192)).astype(np.int8)
+    sh = rng.integers(0, 5, size=6).astype(np.uint8)
+    got = fq.flexiq_bitlower(_dev(torch, src, dev), 32, _dev(torch, sh, dev), per_row=False)
+    assert (got.cpu().numpy() == oracle.bitlower_pack(src, 32, sh, per_row=False)).all()
+
+
+def test_permute_channels(env):
+    torch, oracle, fq, dev = env
+    case = workloads.config0()
+    ol, hl, x_scale = both_layers(case)
+    Xq = oracle.quantize(case.X, x_scale)
+    got = fq.flexiq_permute_channels(hl, _dev(torch, Xq, dev))
+    assert (got.cpu().numpy() == Xq[:, ol.perm]).all()
+
+
+def _run_gemm_case(env, case, ratios, rows=None, check_q=True):
+    torch, oracle, fq, dev = env
+    ol, hl, x_scale = both_layers(case)
+    Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
+    if rows is not None:
+        Xq = np.ascontiguousarray(Xq[:rows])
+    Xd = _dev(torch, Xq, dev)
+    for r in ratios:
+        k4 = fq.flexiq_set_ratio(hl, r)
+        assert k4 == oracle.groups_for_ratio(r, ol.G) * ol.group_size
+        ref = oracle.forward_gemm(ol, Xq, r)
+        so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
+        out = fq.flexiq_mixed_gemm(hl, Xd, acc=True, y=True, q=check_q, out_scale=so)
+        torch.cuda.synchronize()
+        assert (out["acc"].cpu().numpy() == ref).all(), (case.name, r)
+        check_y(out["y"].cpu().numpy(), ref, ol)
+        if check_q:
+            assert (out["q"].cpu().numpy() == oracle.requant_i8(ref, x_scale, ol.w_scale, so, ol.bias)).all()
+
+
+def test_gemm_config0_all_ratios_all_tiles(env):
+    torch, oracle, fq, dev = env
+    n = fq.debug_force_tile(-1)
+    try:
+        for t in range(n):
+            fq.debug_force_tile(t)
+            _run_gemm_case(env, workloads.config0(), (0.0, 0.25, 0.5, 0.75, 1.0))
+    finally:
+        fq.debug_force_tile(-1)
+
+
+@pytest.mark.parametrize("M,K,N,gs", [(1, 64, 16, 32), (17, 64, 4, 64), (333, 192, 72, 32), (300, 320, 520, 64),
+                                      (700, 96, 260, 32), (5, 128, 7, 32)])
+def test_gemm_ragged_shapes(env, M, K, N, gs):
+    # several tiles plus a ragged tail in M and N; N = 7 exercises the scalar store path
+    case = workloads.make_linear("ragged", 8, M + N, M, K, N, gs, outlier_frac=0.02)
+    G = K // gs
+    ratios = sorted({0.0, 1.0, 0.5, 1.0 / G})
+    _run_gemm_case(env, case, ratios)
+
+
+def test_gemm_ragged_all_tiles(env):
+    torch, oracle, fq, dev = env
+    n = fq.debug_force_tile(-1)
+    case = workloads.make_linear("ragged_tiles", 8, 77, 531, 160, 328, 32, outlier_frac=0.02)
+    try:
+        for t in range(n):
+            fq.debug_force_tile(t)
+            _run_gemm_case(env, case, (0.0, 0.6, 1.0))
+    finally:
+        fq.debug_force_tile(-1)
+
+
+def test_gemm_saturating_inputs(env):
+    # activations far beyond the calibrated range: the clamp of the lowering is active everywhere
+    torch, oracle, fq, dev = env
+    case = workloads.make_linear("sat", 8, 3, 96, 128, 64, 32)
+    case.X *= 6.0
+    _run_gemm_case(env, case, (0.0, 0.5, 1.0))
+    case.X[:] = 1e9
+    _run_gemm_case(env, case, (1.0,))
+    case.X[:] = -1e9
+    _run_gemm_case(env, case, (1.0,))
+
+
+def test_gemm_empty_and_errors(env):
+    torch, oracle, fq, dev = env
+    case = workloads.config0()
+    ol, hl, x_scale = both_layers(case)
+    X0 = torch.empty((0, case.K), dtype=torch.int8, device=dev)
+    out = fq.flexiq_mixed_gemm(hl, X0, acc=True)
+    assert out["acc"].shape == (0, case.N)
+    with pytest.raises(fq.FlexiqError):
+        fq.flexiq_set_ratio(hl, 1.5)
+    with pytest.raises(fq.FlexiqError):
+        fq.flexiq_set_ratio(hl, -0.1)
+    X = torch.zeros((8, case.K), dtype=torch.int8, device=dev)
+    with pytest.raises(fq.FlexiqError):
+        fq.flexiq_mixed_gemm(hl, X)                      # no output requested
+    with pytest.raises(fq.FlexiqError):
+        fq.flexiq_mixed_gemm(hl, X, q=True, out_scale=0.0)
+    Xmis = torch.zeros(8 * case.K + 16, dtype=torch.int8, device=dev)[1:1 + 8 * case.K].view(8, case.K)
+    with pytest.raises(fq.FlexiqError):
+        fq.flexiq_mixed_gemm(hl, Xmis.contiguous() if False else Xmis, acc=True)   # misaligned pointer
+
+
+def test_ratio_switch_needs_no_repack(env):
+    # one handle, packed once, serves every ratio: device buffers identical before and after
+    torch, oracle, fq, dev = env
+    case = workloads.config0()
+    ol, hl, x_scale = both_layers(case)
+    w8a, w4a = fq.flexiq_layer_dump(hl)
+    Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
+    Xd = _dev(torch, Xq, dev)
+    sched = workloads.config4_ratio_schedule(12)
+    for r in sched:
+        fq.flexiq_set_ratio(hl, float(r))
+        got = fq.flexiq_mixed_gemm(hl, Xd, acc=True)["acc"].cpu().numpy()
+        fresh = both_layers(case)[1]
+        fq.flexiq_set_ratio(fresh, float(r))
+        assert (got == fq.flexiq_mixed_gemm(fresh, Xd, acc=True)["acc"].cpu().numpy()).all()
+        assert (got == oracle.forward_gemm(ol, Xq, float(r))).all()
+    w8b, w4b = fq.flexiq_layer_dump(hl)
+    assert (w8a == w8b).all() and (w4a == w4b).all()
+
+
+@pytest.mark.parametrize("B,H,C,N,R,stride,pad,gs", [(2, 7, 64, 24, 3, 1, 1, 32), (3, 9, 128, 72, 3, 2, 1, 64),
+                                                     (2, 6, 96, 130, 1, 1, 0, 32), (2, 8, 64, 64, 1, 2, 0, 32),
+                                                     (1, 5, 32, 16, 3, 1, 1, 32), (5, 14, 64, 96, 3, 1, 1, 32)])
+def test_conv_small(env, B, H, C, N, R, stride, pad, gs):
+    torch, oracle, fq, dev = env
+    case = workloads.make_conv("conv", 7, B * H + C + N + R, B, H, H, C, N, R, R, stride, pad, gs)
+    ol, hl, x_scale = both_layers(case)
+    Xq = np.ascontiguousarray(oracle.quantize(case.X, x_scale)[..., ol.perm])
+    Xd = _dev(torch, Xq, dev)
+    G = C // gs
+    for r in sorted({0.0, 1.0 / G, 1.0}):
+        fq.flexiq_set_ratio(hl, r)
+        ref = oracle.forward_conv(ol, Xq, stride, pad, r)
+        so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
+        out = fq.flexiq_mixed_conv_implicit(hl, Xd, stride, pad, acc=True, y=True, q=True, out_scale=so)
+        torch.cuda.synchronize()
+        assert (out["acc"].cpu().numpy() == ref).all(), r
+        check_y(out["y"].cpu().numpy(), ref, ol)
+        assert (out["q"].cpu().numpy() == oracle.requant_i8(ref, x_scale, ol.w_scale, so, ol.bias)).all()
+
+
+def test_conv_all_tiles(env):
+    torch, oracle, fq, dev = env
+    case = workloads.make_conv("conv_tiles", 7, 99, 3, 10, 10, 64, 80, 3, 3, 1, 1, 32)
+    ol, hl, x_scale = both_layers(case)
+    Xq = np.ascontiguousarray(oracle.quantize(case.X, x_scale)[..., ol.perm])
+    Xd = _dev(torch, Xq, dev)
+    n = fq.debug_force_tile(-1)
+    try:
+        for t in range(n):
+            fq.debug_force_tile(t)
+            for r in (0.0, 0.5, 1.0):
+                fq.flexiq_set_ratio(hl, r)
+                got = fq.flexiq_mixed_conv_implicit(hl, Xd, 1, 1, acc=True)["acc"].cpu().numpy()
+                assert (got == oracle.forward_conv(ol, Xq, 1, 1, r)).all(), (t, r)
+    finally:
+        fq.debug_force_tile(-1)
+
+
+def test_determinism(env):
+    # integer accumulation is order independent: two runs must be identical (a mismatch = race / stray read)
+    torch, oracle, fq, dev = env
+    case = workloads.make_linear("det", 8, 5, 1000, 256, 512, 32, outlier_frac=0.02)
+    ol, hl, x_scale = both_layers(case)
+    Xd = _dev(torch, oracle.quantize(case.X, x_scale)[:, ol.perm], dev)
+    fq.flexiq_set_ratio(hl, 0.5)
+    a = fq.flexiq_mixed_gemm(hl, Xd, acc=True)["acc"].clone()
+    for _ in range(3):
+        b = fq.flexiq_mixed_gemm(hl, Xd, acc=True)["acc"]
+        assert torch.equal(a, b)
