@@ -499,9 +499,9 @@ extern "C" int flexiq_debug_force_tile(int index)
 extern "C" int flexiq_mixed_gemm(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream)
 {
     if (!L || M < 0 || L->R != 1 || L->S != 1) return FLEXIQ_EINVAL;
+    if (M == 0) return FLEXIQ_OK;  // empty input: nothing to write, output pointers are not looked at
     int rc = check_out(out);
     if (rc) return rc;
-    if (M == 0) return FLEXIQ_OK;
     if (!X) return FLEXIQ_EINVAL;
     if (reinterpret_cast<uintptr_t>(X) & 15u) return FLEXIQ_EALIGN;
     return launch(L, X, M, out, stream, false, 1, 1, 1, 1, 1, 0);
@@ -512,11 +512,11 @@ extern "C" int flexiq_mixed_conv_implicit(const flexiq_layer *L, const int8_t *X
 {
     if (!L || B < 0 || H <= 0 || W <= 0 || stride <= 0 || pad < 0) return FLEXIQ_EINVAL;
     if (H + 2 * pad < L->R || W + 2 * pad < L->S) return FLEXIQ_EINVAL;
-    int rc = check_out(out);
-    if (rc) return rc;
     const int Ho = (H + 2 * pad - L->R) / stride + 1, Wo = (W + 2 * pad - L->S) / stride + 1;
     const int64_t M = (int64_t)B * Ho * Wo;
-    if (M == 0) return FLEXIQ_OK;
+    if (M == 0) return FLEXIQ_OK;  // empty batch
+    int rc = check_out(out);
+    if (rc) return rc;
     if (!X) return FLEXIQ_EINVAL;
     if (reinterpret_cast<uintptr_t>(X) & 15u) return FLEXIQ_EALIGN;
     return launch(L, X, M, out, stream, true, H, W, Ho, Wo, stride, pad);
