@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the FlexiQ hot path on one MI355X.
+
+Workload (BASELINE.json `metric`: "... vs low-bit ratio r (ViT-B fc1)", configs[1]): the ViT-B/16
+MLP fc1 linear at batch 32, M = 32*197 = 6304 tokens, K = 768, N = 3072, channel group size 32.
+One step = one pass of the run-time hot path over the ratio sweep r in {0, .25, .5, .75, 1}: per
+ratio the O(1) ratio switch, then the mixed 4/8-bit MFMA GEMM with on-the-fly bit-lowering of
+the activations, in-register expansion of the packed 4-bit weights and the fused per-channel
+dequant + int8 requant epilogue.  Inputs (int8 activations in stored channel order, packed layer)
+are resident in HBM before the timed region; the offline steps (weight quantisation, channel
+order, positions, packing) run once before it, as in the paper.
+
+Prints ONE JSON line.  `value` = total int8 ops of the K timed steps / wall time (TOPS).
+`roofline` covers the GEMM kernel (the only kernel in the timed region): algorithmic ops per launch
+= 2*M*N*K, average launch duration from HIP events recorded around every launch of the timed
+region.  `cpu_baseline` times the CPU oracle on a bounded row sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "mixed int4/int8 GEMM TOPS & % int8 MFMA peak vs low-bit ratio r (ViT-B fc1)"
+INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix peak, 5.0 POP/s
+HBM_PEAK_GBS = 8000.0
+RATIOS = (0.0, 0.25, 0.5, 0.75, 1.0)
+
+# HBM bytes per launch of the GEMM kernel on this workload from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (see profiles/); None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(M, N, K, r, out_bytes_per_elem=1):
+    """Bytes one call must move: int8 activations, weights (1 B per 8-bit channel, 1/2 B per 4-bit
+    channel), position table and scales, output."""
+    return M * K + N * K * (1.0 - r / 2.0) + N * (K // 32) + 8 * N + M * N * out_bytes_per_elem
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--layer", default="fc1", choices=["fc1", "fc2"])
+    ap.add_argument("--out", default="q", choices=["q", "y", "acc"], help="epilogue output written in the timed region")
+    ap.add_argument("--cpu-rows", type=int, default=768, help="rows of the workload the CPU oracle is timed on (0: skip)")
+    ap.add_argument("--no-events", action="store_true", help="do not record per-launch events in the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (the method is single-device; rows of M would shard "
+            "data-parallel with replicated weights).  --gpus %d is not supported." % args.gpus)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2510_02822_amd as fq
+    import workloads
+
+    fq.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.time()
+    case = workloads.config1(args.layer)
+    M, K, N, gs = case.M, case.K, case.N, case.group_size
+    absmax_c = np.abs(case.Xcal).max(0)
+    x_scale = float(np.float32(absmax_c.max()) / np.float32(127.0))
+    layer = fq.flexiq_quantize_pack(case.W, absmax_c, x_scale, gs, bias=case.bias)
+    Xq_nat = fq.flexiq_quantize_act(torch.from_numpy(case.X).to(dev), x_scale)
+    Xq = fq.flexiq_permute_channels(layer, Xq_nat)
+    torch.cuda.synchronize()
+    log("setup %.1fs: %s M=%d K=%d N=%d gs=%d" % (time.time() - t0, case.name, M, K, N, gs))
+
+    # output scale for the requant epilogue: from one fp32 pass at r = 0
+    fq.flexiq_set_ratio(layer, 0.0)
+    y0 = fq.flexiq_mixed_gemm(layer, Xq, y=True)["y"]
+    out_scale = float(y0.abs().max().item() / 127.0)
+    del y0
+    want = {"acc": args.out == "acc", "y": args.out == "y", "q": args.out == "q"}
+    dt = {"acc": torch.int32, "y": torch.float32, "q": torch.int8}[args.out]
+    bufs = {args.out: torch.empty((M, N), dtype=dt, device=dev)}
+    out_bytes = 1 if args.out == "q" else 4
+
+    def one_step(events=None):
+        for i, r in enumerate(RATIOS):
+            fq.flexiq_set_ratio(layer, r)
+            if events is not None:
+                events[i][0].record()
+            fq.flexiq_mixed_gemm(layer, Xq, out_scale=out_scale, bufs=bufs, **want)
+            if events is not None:
+                events[i][1].record()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+
+    use_ev = not args.no_events
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in RATIOS]
+           for _ in range(args.steps)] if use_ev else None
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for s in range(args.steps):
+        one_step(evs[s] if use_ev else None)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t1
+
+    ops_call = 2.0 * M * N * K
+    ops_step = ops_call * len(RATIOS)
+    value = ops_step * args.steps / wall / 1e12
+    per_r = []
+    avg_us = None
+    if use_ev:
+        tot = 0.0
+        for i, r in enumerate(RATIOS):
+            ts = np.array([evs[s][i][0].elapsed_time(evs[s][i][1]) for s in range(args.steps)]) * 1e3  # us
+            tot += ts.sum()
+            med = float(np.median(ts))
+            per_r.append({"r": r, "us_median": round(med, 2), "us_mean": round(float(ts.mean()), 2),
+                          "tops": round(ops_call / med / 1e6, 1),
+                          "frac_int8_mfma_peak": round(ops_call / med / 1e6 / INT8_MFMA_PEAK_TOPS, 4),
+                          "algorithmic_GBs": round(algorithmic_bytes(M, N, K, r, out_bytes) / med / 1e3, 1)})
+        avg_us = tot / (args.steps * len(RATIOS))
+    achieved = ops_call / avg_us / 1e6 if avg_us else value
+    roofline = {"bound": "mfma", "kernel": "flexiq::k_mixed (int8 MFMA mixed GEMM)", "achieved": round(achieved, 1),
+                "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
+                "avg_launch_us": round(avg_us, 2) if avg_us else None,
+                "ops_per_launch": ops_call, "traffic": MEASURED_TRAFFIC_BYTES}
+
+    # ---- CPU oracle on a bounded row sample (rank 0, N = 1 only), with a parity check on those rows
+    cpu = None
+    parity = None
+    if args.cpu_rows > 0:
+        import oracle
+        oracle.build()
+        rows = min(args.cpu_rows, M)
+        ol = oracle.prepare_layer(case.W, absmax_c, x_scale, gs, bias=case.bias)
+        Xs = oracle.quantize(case.X[:rows], x_scale)[:, ol.perm]
+        cores = len(os.sched_getaffinity(0))
+        try:
+            cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+        except ValueError:
+            pass
+        tc = time.perf_counter()
+        refs = [oracle.forward_gemm(ol, Xs, r) for r in RATIOS]
+        cpu_s = time.perf_counter() - tc
+        cpu_tops = 2.0 * rows * N * K * len(RATIOS) / cpu_s / 1e12
+        cpu = {"value": round(cpu_tops, 6), "unit": "TOPS", "cores": cores, "kind": "oracle",
+               "sample": "first %d of %d rows of the same layer, all N and K, ratio sweep %s, %.1f s"
+                         % (rows, M, list(RATIOS), cpu_s)}
+        ok = True
+        Xd = Xq[:rows].contiguous()
+        for r, ref in zip(RATIOS, refs):
+            fq.flexiq_set_ratio(layer, r)
+            got = fq.flexiq_mixed_gemm(layer, Xd, acc=True)["acc"].cpu().numpy()
+            ok = ok and bool((got == ref).all())
+        parity = "int32 accumulators bit-exact with the oracle on %d rows x %d ratios" % (rows, len(RATIOS)) if ok \
+            else "MISMATCH against the oracle"
+
+    line = {
+        "metric": METRIC, "value": round(value, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall / args.steps * 1e3, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "i8", "data": "synthetic",
+        "config": {"workload": "ViT-B/16 MLP %s, batch 32 @224px: M=%d K=%d N=%d, group size %d, ratio sweep %s "
+                               "per step, epilogue=%s" % (args.layer, M, K, N, gs, list(RATIOS),
+                                                          {"q": "int8 requant", "y": "fp32 dequant", "acc": "int32 dump"}[args.out]),
+                   "M": M, "K": K, "N": N, "group_size": gs, "ratios": list(RATIOS)},
+        "roofline": roofline, "cpu_baseline": cpu, "per_r": per_r, "parity": parity,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
