@@ -28,15 +28,16 @@ void set_hip_error(hipError_t e, const char *what);
 
 }  // namespace flexiq
 
-// Device layouts (all offsets in bytes unless noted), U = T * C/32 units with T = R*S filter taps,
-// unit u = tap * (C/32) + c32 (tap-major), Npad = N rounded up to 256, rows >= N are zero:
+// Device layouts (all offsets in bytes unless noted), T = R*S filter taps, CUp = C/32 rounded up to
+// even, U = T * CUp units, unit u = tap * CUp + c32 (tap-major; a pad unit c32 == C/32 is all zero),
+// Npad = N rounded up to 256, rows >= N are zero:
 //   w8     int8  [U][2][Npad][16]   8-bit weights; plane q2 of unit u holds stored channels
 //                                   c32*32 + q2*16 .. +15 of every output channel
 //   w4     uint8 [U][Npad][16]      4-bit codes of the same 32 channels: dword e (0..3) of a row
 //                                   carries channels 8e..8e+3 in the low halves of its bytes 0..3
 //                                   and channels 8e+4..8e+7 in the high halves
 //   wshift uint8 [G][Npad]          weight extraction position per (group, output channel)
-//   ashift uint8 [G]                activation extraction position per group
+//   ashift int32 [G+1]              activation extraction position per group (+1 entry for the pad unit)
 //   cs     fp32  [Npad]             x_scale * w_scale[n]
 //   bias   fp32  [Npad]             zeros when the layer has no bias
 struct flexiq_layer {
@@ -52,7 +53,7 @@ struct flexiq_layer {
     int8_t *d_w8;
     uint8_t *d_w4;
     uint8_t *d_wshift;
-    uint8_t *d_ashift;
+    int32_t *d_ashift;
     float *d_cs;
     float *d_bias;
     int32_t *d_perm;

@@ -31,7 +31,7 @@ struct GemmParams {
     const int8_t *W8;
     const uint8_t *W4;
     const uint8_t *wshift;
-    const uint8_t *ashift;
+    const int32_t *ashift;
     const float *cs;
     const float *bias;
     int32_t *acc;
@@ -105,29 +105,173 @@ __device__ __forceinline__ void expand32(v4i p, int sw, v4i &first16, v4i &secon
     second16 = (v4i){(int)o[4], (int)o[5], (int)o[6], (int)o[7]};
 }
 
-template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV>
+template <int WAVES_M, int WAVES_N, int TM, int TN>
 struct Cfg {
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
     static constexpr int BM = WAVES_M * TM * 16;
     static constexpr int BN = WAVES_N * TN * 16;
-    static constexpr int XPS = (BM + 4) * 16;  // bytes per activation k-plane (+4 chunks: staggers the planes over the banks)
-    static constexpr int WPS = (BN + 4) * 16;
-    static constexpr int STAGE = 4 * XPS + 4 * WPS;
     static constexpr int XL = (BM * 4 + NT - 1) / NT;   // 16-byte activation chunks per thread per K-step
     static constexpr int WL8 = (BN * 2 + NT - 1) / NT;  // 16-byte chunks per thread per 8-bit unit
     static constexpr int WL4 = (BN + NT - 1) / NT;      // 16-byte chunks per thread per 4-bit unit
+    static constexpr int XROWS = XL * (NT / 4);         // rows staged per K-step (>= BM; the excess reads as zero)
+    static constexpr int XPS = (XROWS + 4) * 16;        // bytes per activation k-plane (+4 chunks staggers the planes over the banks)
+    static constexpr int WPS = (BN + 4) * 16;
+    static constexpr int STAGE = 4 * XPS + 4 * WPS;
     static constexpr int LDS_BYTES = 2 * STAGE;
 };
 
-template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void k_mixed(const GemmParams p)
+// How the two 32-channel units of the NEXT K-step are staged.
+enum StepMode { kMode88 = 0, kMode44 = 1, kMode48 = 2, kModeNone = 3 };
+
+template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV, int OCC>
+struct Kern {
+    using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
+    static constexpr int NT = C_::NT, BM = C_::BM, BN = C_::BN, XPS = C_::XPS, WPS = C_::WPS, STAGE = C_::STAGE;
+    static constexpr int XL = C_::XL, WL8 = C_::WL8, WL4 = C_::WL4;
+
+    const GemmParams &p;
+    unsigned char *lds;
+    int tid;
+    __amdgpu_buffer_rsrc_t rx, rw8, rw4, rws;
+    // per-thread staging addresses
+    int xvoff[XL];            // byte offset of each activation chunk inside the block's buffer window
+    int xh0[XL], xw0[XL], xpix[XL];  // conv: top-left input coordinate and pixel index of the image origin
+    int x_lds;                // LDS byte offset of chunk 0 inside a stage (chunk j adds j * (NT/4) * 16)
+    int w8voff[WL8], w8lds[WL8];
+    int w4voff[WL4], w4lds[WL4];
+    // staging registers
+    v4i xr[XL];
+    v4i wr[2][WL8];
+    int wsh[2][WL4];
+    // scalar K-step iteration state (phase-major: all 4-bit steps, then mixed, then 8-bit)
+    int n4, mixed, SP;  // per tap: full 4-bit steps, 0/1 mixed step, steps in total
+    int it_phase, it_tap, it_c64;
+
+    __device__ __forceinline__ Kern(const GemmParams &pp, unsigned char *l) : p(pp), lds(l) {}
+
+    __device__ __forceinline__ int phase_begin(int ph) const { return ph == 0 ? 0 : (ph == 1 ? n4 : n4 + mixed); }
+    __device__ __forceinline__ int phase_end(int ph) const { return ph == 0 ? n4 : (ph == 1 ? n4 + mixed : SP); }
+
+    // first non-empty phase at or after ph (3 = done)
+    __device__ __forceinline__ void seek_phase(int ph)
+    {
+        while (ph < 3 && phase_begin(ph) == phase_end(ph)) ++ph;
+        it_phase = ph;
+        it_tap = 0;
+        it_c64 = ph < 3 ? phase_begin(ph) : 0;
+    }
+    __device__ __forceinline__ void advance()
+    {
+        if (++it_c64 == phase_end(it_phase)) {
+            it_c64 = phase_begin(it_phase);
+            if (++it_tap == p.T) seek_phase(it_phase + 1);
+        }
+    }
+    __device__ __forceinline__ int cur_mode() const
+    {
+        return it_phase == 0 ? kMode44 : (it_phase == 1 ? kMode48 : (it_phase == 2 ? kMode88 : kModeNone));
+    }
+
+    // ---- global -> registers for the K-step the iterator points at
+    template <int MODE>
+    __device__ __forceinline__ void load_step()
+    {
+        const int tap = it_tap, c64 = it_c64;
+        if (CONV) {
+            const int dy = tap / p.S, dx = tap - dy * p.S;
+#pragma unroll
+            for (int j = 0; j < XL; ++j) {
+                const int hi = xh0[j] + dy, wi = xw0[j] + dx;
+                const bool ok = hi >= 0 && hi < p.H && wi >= 0 && wi < p.Wd && xpix[j] >= 0;
+                const int off = ok ? (xpix[j] + hi * p.Wd + wi) * p.C + xvoff[j] : (int)0x80000000;
+                xr[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, c64 * 64, 0);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < XL; ++j) xr[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, xvoff[j], c64 * 64, 0);
+        }
+        const int u0 = tap * (2 * SP) + 2 * c64;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int u = u0 + h;
+            const bool four = MODE == kMode44 || (MODE == kMode48 && h == 0);
+            if (four) {
+                const int g = (2 * c64 + h) >> p.gs_shift;
+#pragma unroll
+                for (int j = 0; j < WL4; ++j) {
+                    wr[h][j] = __builtin_amdgcn_raw_buffer_load_b128(rw4, w4voff[j], u * 16 * p.Npad, 0);
+                    wsh[h][j] = __builtin_amdgcn_raw_buffer_load_b8(rws, w4voff[j] >> 4, g * p.Npad, 0);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < WL8; ++j)
+                    wr[h][j] = __builtin_amdgcn_raw_buffer_load_b128(rw8, w8voff[j], u * 32 * p.Npad, 0);
+            }
+        }
+    }
+
+    // ---- registers -> LDS stage, bit-lowering the activations / expanding the 4-bit weights of 4-bit units.
+    // (tap, c64) are those the registers were loaded for.
+    template <int MODE>
+    __device__ __forceinline__ void store_step(unsigned char *stage, int c64)
+    {
+        unsigned char *xs = stage, *ws = stage + 4 * XPS;
+        const int q = tid & 3;
+        // this thread's chunks all lie in unit q>>1 of the step
+        const bool x_four = MODE == kMode44 || (MODE == kMode48 && (q >> 1) == 0);
+        if (MODE == kMode88) {
+#pragma unroll
+            for (int j = 0; j < XL; ++j) *reinterpret_cast<v4i *>(xs + x_lds + j * (NT / 4) * 16) = xr[j];
+        } else {
+            // positions of the two units (uniform); a thread uses the one of its own unit
+            const int sa0 = p.ashift[(2 * c64) >> p.gs_shift], sa1 = p.ashift[(2 * c64 + 1) >> p.gs_shift];
+            const int sa = (q >> 1) ? sa1 : sa0;
+#pragma unroll
+            for (int j = 0; j < XL; ++j) {
+                v4i v = xr[j];
+                if (MODE == kMode44) {
+                    v = lower16(v, sa);
+                } else {
+                    const v4i l = lower16(v, sa);
+                    v = x_four ? l : v;
+                }
+                *reinterpret_cast<v4i *>(xs + x_lds + j * (NT / 4) * 16) = v;
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const bool four = MODE == kMode44 || (MODE == kMode48 && h == 0);
+            if (four) {
+#pragma unroll
+                for (int j = 0; j < WL4; ++j) {
+                    if (BN % NT == 0 || tid + j * NT < BN) {
+                        v4i a, b;
+                        expand32(wr[h][j], wsh[h][j], a, b);
+                        *reinterpret_cast<v4i *>(ws + (2 * h) * WPS + w4lds[j]) = a;
+                        *reinterpret_cast<v4i *>(ws + (2 * h + 1) * WPS + w4lds[j]) = b;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < WL8; ++j)
+                    if ((2 * BN) % NT == 0 || tid + j * NT < 2 * BN)
+                        *reinterpret_cast<v4i *>(ws + (2 * h) * WPS + w8lds[j]) = wr[h][j];
+            }
+        }
+    }
+};
+
+template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV, int OCC>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void k_mixed(const GemmParams p)
 {
-    using C_ = Cfg<WAVES_M, WAVES_N, TM, TN, CONV>;
-    constexpr int NT = C_::NT, BM = C_::BM, BN = C_::BN, XPS = C_::XPS, WPS = C_::WPS, STAGE = C_::STAGE;
-    constexpr int XL = C_::XL, WL8 = C_::WL8, WL4 = C_::WL4;
+    using K_ = Kern<WAVES_M, WAVES_N, TM, TN, CONV, OCC>;
+    constexpr int NT = K_::NT, BM = K_::BM, BN = K_::BN, XPS = K_::XPS, WPS = K_::WPS, STAGE = K_::STAGE;
+    constexpr int XL = K_::XL, WL8 = K_::WL8, WL4 = K_::WL4;
     extern __shared__ __align__(16) unsigned char lds[];
 
+    K_ k(p, lds);
     const int tid = threadIdx.x;
+    k.tid = tid;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
@@ -148,131 +292,66 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void k_mixed(const GemmPara
     }
     const int64_t m0 = (int64_t)tile_m * BM;
     const int n0 = tile_n * BN;
+    const int rows_valid = (int)min((int64_t)BM, p.M - m0);
 
-    // ---- per-thread activation chunk slots: slot i -> (row i/4, k-plane i%4)
-    int64_t xbase[XL];  // linear: byte offset of the row; conv: pixel index of image b's origin
-    int xh0[XL], xw0[XL];
-    bool xrow_ok[XL];
+    // ---- buffer windows: reads past a window return zero, which is what rows beyond M, padded
+    // pixels and dummy staging rows need
+    constexpr int kRsrcFlags = 0x00020000;
+    k.rw8 = __builtin_amdgcn_make_buffer_rsrc((void *)(p.W8 + (int64_t)n0 * 16), 0, p.U * 32 * p.Npad - n0 * 16, kRsrcFlags);
+    k.rw4 = __builtin_amdgcn_make_buffer_rsrc((void *)(p.W4 + (int64_t)n0 * 16), 0, p.U * 16 * p.Npad - n0 * 16, kRsrcFlags);
+    k.rws = __builtin_amdgcn_make_buffer_rsrc((void *)(p.wshift + n0), 0, (p.C >> (5 + p.gs_shift)) * p.Npad - n0, kRsrcFlags);
+    const int xq = tid & 3;
+    if (CONV) {
+        const int64_t hw_out = (int64_t)p.Ho * p.Wo;
+        const int64_t img0 = m0 / hw_out;
+        const int64_t img_bytes = (int64_t)p.H * p.Wd * p.C;
+        const int64_t imgs_left = (p.M / hw_out) - img0;  // images from img0 to the end of the batch
+        const int64_t win = min(imgs_left * img_bytes, (int64_t)0x7fffffff);
+        k.rx = __builtin_amdgcn_make_buffer_rsrc((void *)(p.X + img0 * img_bytes), 0, (int)win, kRsrcFlags);
 #pragma unroll
-    for (int j = 0; j < XL; ++j) {
-        const int slot = tid + j * NT;
-        const int row = slot >> 2;
-        const int64_t m = m0 + row;
-        xrow_ok[j] = (slot < BM * 4) && (m < p.M);
-        if (CONV) {
-            const int64_t mm = xrow_ok[j] ? m : 0;
+        for (int j = 0; j < XL; ++j) {
+            const int row = (tid >> 2) + j * (NT / 4);
+            const int64_t m = m0 + row;
+            const bool ok = row < rows_valid;
+            const int64_t mm = ok ? m : m0;
             const int wo = (int)(mm % p.Wo);
             const int ho = (int)((mm / p.Wo) % p.Ho);
-            const int64_t b = mm / ((int64_t)p.Wo * p.Ho);
-            xbase[j] = b * p.H * p.Wd;
-            xh0[j] = ho * p.stride - p.pad;
-            xw0[j] = wo * p.stride - p.pad;
-        } else {
-            xbase[j] = (xrow_ok[j] ? m : 0) * p.C;
-            xh0[j] = xw0[j] = 0;
+            const int b = (int)(mm / hw_out - img0);
+            k.xpix[j] = ok ? b * p.H * p.Wd : -1;
+            k.xh0[j] = ho * p.stride - p.pad;
+            k.xw0[j] = wo * p.stride - p.pad;
+            k.xvoff[j] = xq * 16;
+        }
+    } else {
+        k.rx = __builtin_amdgcn_make_buffer_rsrc((void *)(p.X + m0 * p.C), 0, rows_valid * p.C, kRsrcFlags);
+#pragma unroll
+        for (int j = 0; j < XL; ++j) {
+            const int row = (tid >> 2) + j * (NT / 4);
+            k.xvoff[j] = row * p.C + xq * 16;  // rows >= rows_valid fall outside the window: zeros
+            k.xh0[j] = k.xw0[j] = k.xpix[j] = 0;
         }
     }
+    k.x_lds = xq * XPS + (tid >> 2) * 16;
+#pragma unroll
+    for (int j = 0; j < WL8; ++j) {
+        const int i = tid + j * NT;
+        const int q2 = i / BN, row = i - q2 * BN;
+        k.w8voff[j] = (q2 * p.Npad + row) * 16;
+        k.w8lds[j] = q2 * WPS + row * 16;
+    }
+#pragma unroll
+    for (int j = 0; j < WL4; ++j) {
+        const int row = tid + j * NT;
+        k.w4voff[j] = row * 16;
+        k.w4lds[j] = row * 16;
+    }
 
-    v4i xr[XL];
-    v4i wr[2][WL8];
-    int wsh[2][WL4];
-
-    const int steps = p.U >> 1;
-
-    auto unit_is4 = [&](int u) -> bool { return (u % p.CU) * kUnit < p.K4; };
-
-    // ---- global -> registers for K-step s
-    auto load_step = [&](int s) {
-#pragma unroll
-        for (int j = 0; j < XL; ++j) {
-            const int slot = tid + j * NT;
-            const int q = slot & 3;
-            const int u = 2 * s + (q >> 1);
-            const int tap = u / p.CU;
-            const int c32 = u - tap * p.CU;
-            bool ok = xrow_ok[j] && tap < p.T;
-            int64_t off;
-            if (CONV) {
-                const int dy = tap / p.S, dx = tap - dy * p.S;
-                const int hi = xh0[j] + dy, wi = xw0[j] + dx;
-                ok = ok && hi >= 0 && hi < p.H && wi >= 0 && wi < p.Wd;
-                off = (xbase[j] + (int64_t)hi * p.Wd + wi) * p.C + c32 * kUnit + (q & 1) * 16;
-            } else {
-                off = xbase[j] + c32 * kUnit + (q & 1) * 16;
-            }
-            v4i v = {0, 0, 0, 0};
-            if (ok) v = *reinterpret_cast<const v4i *>(p.X + off);
-            xr[j] = v;
-        }
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int u = 2 * s + h;
-            if (unit_is4(u)) {
-                const int g = (u % p.CU) >> p.gs_shift;
-#pragma unroll
-                for (int j = 0; j < WL4; ++j) {
-                    const int row = tid + j * NT;
-                    if (row < BN) {
-                        wr[h][j] = *reinterpret_cast<const v4i *>(p.W4 + ((int64_t)u * p.Npad + n0 + row) * 16);
-                        wsh[h][j] = p.wshift[(int64_t)g * p.Npad + n0 + row];
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < WL8; ++j) {
-                    const int slot = tid + j * NT;  // (plane q2, row): q2 = slot / BN
-                    if (slot < 2 * BN) {
-                        const int q2 = slot / BN, row = slot - q2 * BN;
-                        wr[h][j] = *reinterpret_cast<const v4i *>(p.W8 + (((int64_t)u * 2 + q2) * p.Npad + n0 + row) * 16);
-                    }
-                }
-            }
-        }
-    };
-
-    // ---- registers -> LDS stage, lowering / expanding the 4-bit units on the way
-    auto store_step = [&](int s, unsigned char *stage) {
-        unsigned char *xs = stage, *ws = stage + 4 * XPS;
-#pragma unroll
-        for (int j = 0; j < XL; ++j) {
-            const int slot = tid + j * NT;
-            if (slot < BM * 4) {
-                const int q = slot & 3, row = slot >> 2;
-                const int u = 2 * s + (q >> 1);
-                v4i v = xr[j];
-                if (unit_is4(u)) {
-                    const int sa = p.ashift[(u % p.CU) >> p.gs_shift];
-                    v = lower16(v, sa);
-                }
-                *reinterpret_cast<v4i *>(xs + q * XPS + row * 16) = v;
-            }
-        }
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int u = 2 * s + h;
-            if (unit_is4(u)) {
-#pragma unroll
-                for (int j = 0; j < WL4; ++j) {
-                    const int row = tid + j * NT;
-                    if (row < BN) {
-                        v4i a, b;
-                        expand32(wr[h][j], wsh[h][j], a, b);
-                        *reinterpret_cast<v4i *>(ws + (2 * h) * WPS + row * 16) = a;
-                        *reinterpret_cast<v4i *>(ws + (2 * h + 1) * WPS + row * 16) = b;
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < WL8; ++j) {
-                    const int slot = tid + j * NT;
-                    if (slot < 2 * BN) {
-                        const int q2 = slot / BN, row = slot - q2 * BN;
-                        *reinterpret_cast<v4i *>(ws + (2 * h + q2) * WPS + row * 16) = wr[h][j];
-                    }
-                }
-            }
-        }
-    };
+    // ---- K-step enumeration
+    k.SP = (p.CU + 1) >> 1;
+    k.n4 = p.K4 >> 6;
+    k.mixed = (p.K4 & 63) ? 1 : 0;
+    const int steps = p.T * k.SP;
+    k.seek_phase(0);
 
     v4i acc[TN][TM];
 #pragma unroll
@@ -281,33 +360,74 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void k_mixed(const GemmPara
         for (int b = 0; b < TM; ++b) acc[a][b] = (v4i){0, 0, 0, 0};
 
     const int frag_plane = lane >> 4, frag_row = lane & 15;
+    const int xs_frag = frag_plane * XPS + (wm * TM * 16 + frag_row) * 16;
+    const int ws_frag = 4 * XPS + frag_plane * WPS + (wn * TN * 16 + frag_row) * 16;
     auto compute = [&](const unsigned char *stage) {
-        const unsigned char *xs = stage + frag_plane * XPS + (wm * TM * 16 + frag_row) * 16;
-        const unsigned char *ws = stage + 4 * XPS + frag_plane * WPS + (wn * TN * 16 + frag_row) * 16;
         v4i wf[TN];
 #pragma unroll
-        for (int a = 0; a < TN; ++a) wf[a] = *reinterpret_cast<const v4i *>(ws + a * 256);
+        for (int a = 0; a < TN; ++a) wf[a] = *reinterpret_cast<const v4i *>(stage + ws_frag + a * 256);
 #pragma unroll
         for (int b = 0; b < TM; ++b) {
-            v4i xf = *reinterpret_cast<const v4i *>(xs + b * 256);
+            v4i xf = *reinterpret_cast<const v4i *>(stage + xs_frag + b * 256);
 #pragma unroll
             for (int a = 0; a < TN; ++a)
                 acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[a], xf, acc[a][b], 0, 0, 0);
         }
     };
 
-    // ---- main loop: two LDS stages, one barrier per K-step
-    load_step(0);
-    store_step(0, lds);
+    // ---- prologue: stage K-step 0
+    {
+        const int mode = k.cur_mode(), c64 = k.it_c64;
+        if (mode == kMode44) { k.template load_step<kMode44>(); k.template store_step<kMode44>(lds, c64); }
+        else if (mode == kMode48) { k.template load_step<kMode48>(); k.template store_step<kMode48>(lds, c64); }
+        else { k.template load_step<kMode88>(); k.template store_step<kMode88>(lds, c64); }
+        k.advance();
+    }
     __syncthreads();
-    for (int s = 0; s < steps; ++s) {
+
+    // ---- main loop: two LDS stages, one barrier per K-step.  The iterator `k` always points at the
+    // NEXT step to stage.  Steps are enumerated phase by phase (all-4-bit, mixed, all-8-bit); while the
+    // next step stays in the current phase the body is straight-line code specialised on that phase
+    // (hot loops below); the one step per phase whose successor lies in another phase (or nowhere) runs
+    // the generic body.  The accumulators are only ever touched in `compute`, in straight-line code.
+    int s = 0;  // K-step being computed
+    auto generic_step = [&]() {
         unsigned char *cur = lds + (s & 1) * STAGE;
         unsigned char *nxt = lds + ((s + 1) & 1) * STAGE;
-        if (s + 1 < steps) load_step(s + 1);
+        const int mode = k.cur_mode();
+        const int c64 = k.it_c64;
+        if (mode == kMode44) k.template load_step<kMode44>();
+        else if (mode == kMode48) k.template load_step<kMode48>();
+        else if (mode == kMode88) k.template load_step<kMode88>();
+        __builtin_amdgcn_sched_barrier(0x38F);
         compute(cur);
-        if (s + 1 < steps) store_step(s + 1, nxt);
+        if (mode == kMode44) k.template store_step<kMode44>(nxt, c64);
+        else if (mode == kMode48) k.template store_step<kMode48>(nxt, c64);
+        else if (mode == kMode88) k.template store_step<kMode88>(nxt, c64);
+        if (mode != kModeNone) k.advance();
+        ++s;
         __syncthreads();
+    };
+#define FLEXIQ_HOT_LOOP(MODE, PHASE)                                                         \
+    while (s + 1 < steps && k.it_phase == (PHASE)) {                                         \
+        unsigned char *cur = lds + (s & 1) * STAGE;                                          \
+        unsigned char *nxt = lds + ((s + 1) & 1) * STAGE;                                    \
+        const int c64 = k.it_c64;                                                            \
+        k.template load_step<MODE>();                                                        \
+        __builtin_amdgcn_sched_barrier(0x38F); /* global loads stay ahead of the matrix work */ \
+        compute(cur);                                                                        \
+        k.template store_step<MODE>(nxt, c64);                                               \
+        k.advance();                                                                         \
+        ++s;                                                                                 \
+        __syncthreads();                                                                     \
     }
+    FLEXIQ_HOT_LOOP(kMode44, 0)
+    if (s < steps && k.it_phase != 2) generic_step();
+    FLEXIQ_HOT_LOOP(kMode48, 1)
+    if (s < steps && k.it_phase != 2) generic_step();
+    FLEXIQ_HOT_LOOP(kMode88, 2)
+    while (s < steps) generic_step();
+#undef FLEXIQ_HOT_LOOP
 
     // ---- epilogue: lane holds output row m (lane & 15) and four consecutive output channels
     const bool want_q = p.q != nullptr, want_y = p.y != nullptr, want_acc = p.acc != nullptr;
@@ -379,25 +499,26 @@ struct TileShape {
     kernel_fn lin, conv;
 };
 
-template <int WAVES_M, int WAVES_N, int TM, int TN>
+template <int WAVES_M, int WAVES_N, int TM, int TN, int OCC>
 static TileShape make_shape()
 {
-    using C_ = Cfg<WAVES_M, WAVES_N, TM, TN, false>;
-    return TileShape{C_::BM, C_::BN, C_::LDS_BYTES, k_mixed<WAVES_M, WAVES_N, TM, TN, false>,
-                     k_mixed<WAVES_M, WAVES_N, TM, TN, true>};
+    using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
+    static_assert(C_::NT == 256, "the launcher uses 256 threads");
+    return TileShape{C_::BM, C_::BN, C_::LDS_BYTES, k_mixed<WAVES_M, WAVES_N, TM, TN, false, OCC>,
+                     k_mixed<WAVES_M, WAVES_N, TM, TN, true, OCC>};
 }
 
 static const TileShape *shapes(int *count)
 {
     static const TileShape tab[] = {
-        make_shape<2, 2, 8, 8>(),   // 256 x 256
-        make_shape<1, 4, 13, 4>(),  // 208 x 256
-        make_shape<1, 4, 10, 4>(),  // 160 x 256
-        make_shape<2, 2, 4, 8>(),   // 128 x 256
-        make_shape<2, 2, 8, 4>(),   // 256 x 128
-        make_shape<2, 2, 4, 4>(),   // 128 x 128
-        make_shape<2, 2, 2, 4>(),   //  64 x 128
-        make_shape<2, 2, 2, 2>(),   //  64 x  64
+        make_shape<2, 2, 8, 8, 1>(),   // 256 x 256
+        make_shape<1, 4, 13, 4, 1>(),  // 208 x 256
+        make_shape<1, 4, 10, 4, 1>(),  // 160 x 256
+        make_shape<2, 2, 4, 8, 2>(),   // 128 x 256, two blocks per CU
+        make_shape<2, 2, 8, 4, 2>(),   // 256 x 128, two blocks per CU
+        make_shape<2, 2, 4, 4, 2>(),   // 128 x 128
+        make_shape<2, 2, 2, 4, 2>(),   //  64 x 128
+        make_shape<2, 2, 2, 2, 2>(),   //  64 x  64
     };
     *count = (int)(sizeof(tab) / sizeof(tab[0]));
     return tab;
@@ -448,6 +569,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     p.K4 = L->max_4bit_ch;
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.U = L->U; p.CU = L->C / kUnit; p.T = L->T;
+    if ((int64_t)L->U * 32 * L->Npad > 0x7fffffff) return FLEXIQ_EINVAL;  // weight window must fit a buffer descriptor
     p.H = H; p.Wd = Wd; p.Ho = Ho; p.Wo = Wo; p.S = L->S; p.stride = stride; p.pad = pad;
     const TileShape &ts = choose_shape(M, L->N);
     p.tiles_m = (int)((M + ts.BM - 1) / ts.BM);

@@ -107,11 +107,11 @@ __global__ void k_pack_tiles(const int8_t *__restrict__ q, const int32_t *__rest
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)U * Npad) return;
     int u = (int)(i / Npad), n = (int)(i % Npad);
-    int CU = C / kUnit;
-    int tap = u / CU, c32 = u % CU;
+    int CU = C / kUnit, CUp = (CU + 1) & ~1;  // every tap is padded to an even number of units
+    int tap = u / CUp, c32 = u % CUp;
     int v[32];
     int s = 0;
-    if (n < N && tap < T) {
+    if (n < N && c32 < CU) {
         for (int j = 0; j < 32; ++j) v[j] = q[((int64_t)n * T + tap) * C + perm[c32 * 32 + j]];
         s = ws_ng[(int64_t)n * (C / gs) + (c32 * 32) / gs];
     } else {
@@ -276,7 +276,8 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
     } guard{L};
     L->N = N; L->C = C; L->R = d->R; L->S = d->S; L->group_size = gs; L->G = G; L->T = T;
     const int CU = C / kUnit;
-    const int U = (T * CU + 1) & ~1;  // an even number of units: a K-step is two of them
+    const int CUp = (CU + 1) & ~1;
+    const int U = T * CUp;  // every tap holds an even number of units (a K-step is two of them); the pad unit is zero
     L->U = U;
     L->Npad = (int)(cdiv(N, kNPadTo) * kNPadTo);
     L->max_4bit_ch = 0;
@@ -335,8 +336,12 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
 
     FLEXIQ_HIP(hipMalloc((void **)&L->d_perm, C * sizeof(int32_t)));
     FLEXIQ_HIP(hipMemcpy(L->d_perm, L->perm.data(), C * sizeof(int32_t), hipMemcpyHostToDevice));
-    FLEXIQ_HIP(hipMalloc((void **)&L->d_ashift, G));
-    FLEXIQ_HIP(hipMemcpy(L->d_ashift, L->a_shift.data(), G, hipMemcpyHostToDevice));
+    {
+        std::vector<int32_t> a32(L->a_shift.begin(), L->a_shift.end());
+        a32.push_back(0);  // the pad unit of an odd unit count reads one past the last group
+        FLEXIQ_HIP(hipMalloc((void **)&L->d_ashift, a32.size() * sizeof(int32_t)));
+        FLEXIQ_HIP(hipMemcpy(L->d_ashift, a32.data(), a32.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    }
     FLEXIQ_HIP(hipMalloc((void **)&L->d_wshift, (size_t)G * Npad));
     FLEXIQ_HIP(hipMemset(L->d_wshift, 0, (size_t)G * Npad));
     FLEXIQ_HIP(hipMalloc((void **)&L->d_w8, (size_t)U * 2 * Npad * 16));
@@ -383,7 +388,7 @@ extern "C" int flexiq_layer_info(const flexiq_layer *L, const int32_t **perm, co
 extern "C" int flexiq_layer_dump(const flexiq_layer *L, int8_t *w8, uint8_t *w4)
 {
     if (!L) return FLEXIQ_EINVAL;
-    const int N = L->N, C = L->C, T = L->T, Npad = L->Npad, U = L->U, CU = C / kUnit;
+    const int N = L->N, C = L->C, T = L->T, Npad = L->Npad, U = L->U, CU = ((C / kUnit) + 1) & ~1;
     FLEXIQ_HIP(hipDeviceSynchronize());
     if (w8) {
         std::vector<int8_t> raw((size_t)U * 2 * Npad * 16);
