@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--out", default="q", choices=["q", "y", "acc"], help="epilogue output written in the timed region")
     ap.add_argument("--cpu-rows", type=int, default=768, help="rows of the workload the CPU oracle is timed on (0: skip)")
     ap.add_argument("--no-events", action="store_true", help="do not record per-launch events in the timed region")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="after the timed region run one plain device copy of this many MiB (reference for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (the method is single-device; rows of M would shard "
@@ -115,6 +118,15 @@ def main():
         one_step(evs[s] if use_ev else None)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t1
+
+    if args.calib_copy_mib > 0:
+        src = torch.empty(args.calib_copy_mib << 20, dtype=torch.int8, device=dev)
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ops_call = 2.0 * M * N * K
     ops_step = ops_call * len(RATIOS)
