@@ -5,25 +5,32 @@
 // matrix path than an 8-bit one.  The group's contribution
 //     2^(sa+sw) * sum_k L(x,sa) * L(w,sw)   =   sum_k (L(x,sa) << sa) * (L(w,sw) << sw)
 // is instead formed by putting each bit-lowered operand back at its extraction position as an int8
-// value (both factors fit: |L << s| <= 128) and feeding the same v_mfma_i32_16x16x64_i8 and the same
-// int32 accumulator as the 8-bit groups: bit-exact by distributivity, and the separate
-// shift-and-accumulate stage of the paper's CUDA kernel disappears.  What the 4-bit groups save
-// here is weight bytes (they are streamed from the packed 4-bit copy), not matrix cycles.
+// value (both factors fit: |L << s| <= 128) and feeding the same int8 MFMA and the same int32
+// accumulator as the 8-bit groups: bit-exact by distributivity, and the separate shift-and-accumulate
+// stage of the paper's CUDA kernel disappears.  What the 4-bit groups save here is weight bytes (they
+// are streamed from the packed 4-bit copy), not matrix cycles.
 //
-// Work decomposition: a block owns a BM x BN output tile; the reduction runs in K-steps of 64
-// elements (two 32-channel units, each independently 4-bit or 8-bit).  Per K-step the block
-// stages the activation tile (bit-lowered on the way: clamp + mask, packed 16-bit VALU ops) and the
-// weight tile (8-bit planes copied, 4-bit codes expanded with the per-row position) into LDS as
-// four 16-byte "k-planes", so that an MFMA fragment read is 16 lanes x 16 contiguous bytes.
-// The MFMA "A" operand is the weight fragment and "B" the activation fragment, so a lane ends up
-// with four consecutive output channels of one output row: 16-byte fp32 / 4-byte int8 stores.
+// Work decomposition: a block of four waves (one per SIMD) owns a BM x BN output tile; the reduction
+// runs in K-steps of 64 elements (two 32-channel units, each independently 4-bit or 8-bit), each
+// K-step being two k-halves of v_mfma_i32_32x32x32_i8 (a single wave per SIMD keeps the matrix pipe
+// full with this instruction shape; the 16x16x64 shape needs two).  Tiles travel
+//     global --buffer_load--> registers --(bit-lower / expand)--> LDS ring of three stages --> MFMA fragments,
+// as four 16-byte "k-planes" per stage so that a fragment read is 32 lanes x 16 contiguous bytes.
+// The loop is software-pipelined by hand: every MFMA is followed by at most a few memory or VALU
+// instructions (fragment reads for the next k-half into a second register set, LDS stores of the tile
+// two steps ahead, global loads of the tile three steps ahead), pinned in place with scheduling
+// fences, so that loads are spread evenly over the texture-address unit and no wave waits on LDS.
+// The MFMA "A" operand is the weight fragment and "B" the activation fragment, so a lane ends up with
+// four consecutive output channels of one output row.
 #include <mutex>
+#include <type_traits>
 
 #include "flexiq_internal.h"
 
 namespace flexiq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
 typedef short v2s __attribute__((ext_vector_type(2)));
 
 struct GemmParams {
@@ -42,7 +49,8 @@ struct GemmParams {
     int32_t N, Npad, C;
     int32_t K4;      // max_4bit_ch: leading stored channels computed at 4 bits
     int32_t gs_shift;  // log2(group_size / 32): unit c32 belongs to group c32 >> gs_shift
-    int32_t U;       // units in the reduction (even), CU = C/32 per tap
+    int32_t G;       // channel groups
+    int32_t U;       // units in the reduction (even per tap), CU = C/32 per tap
     int32_t CU;
     int32_t T;       // filter taps
     int32_t tiles_m, tiles_n;
@@ -105,173 +113,56 @@ __device__ __forceinline__ void expand32(v4i p, int sw, v4i &first16, v4i &secon
     second16 = (v4i){(int)o[4], (int)o[5], (int)o[6], (int)o[7]};
 }
 
+
+// clamp + mask with a per-lane position (the two units of a K-step may have different positions)
+__device__ __forceinline__ v4i lower16v(v4i x, v2s lo2, v2s hi2, uint32_t mask)
+{
+    v4i r;
+    r.x = (int)lower4((uint32_t)x.x, lo2, hi2, mask);
+    r.y = (int)lower4((uint32_t)x.y, lo2, hi2, mask);
+    r.z = (int)lower4((uint32_t)x.z, lo2, hi2, mask);
+    r.w = (int)lower4((uint32_t)x.w, lo2, hi2, mask);
+    return r;
+}
+
 template <int WAVES_M, int WAVES_N, int TM, int TN>
 struct Cfg {
-    static constexpr int NT = 64 * WAVES_M * WAVES_N;
-    static constexpr int BM = WAVES_M * TM * 16;
-    static constexpr int BN = WAVES_N * TN * 16;
+    static_assert(WAVES_M * WAVES_N == 4, "four waves per block");
+    static constexpr int NT = 256;
+    static constexpr int BM = WAVES_M * TM * 32;
+    static constexpr int BN = WAVES_N * TN * 32;
     static constexpr int XL = (BM * 4 + NT - 1) / NT;   // 16-byte activation chunks per thread per K-step
     static constexpr int WL8 = (BN * 2 + NT - 1) / NT;  // 16-byte chunks per thread per 8-bit unit
     static constexpr int WL4 = (BN + NT - 1) / NT;      // 16-byte chunks per thread per 4-bit unit
+    static constexpr int NS = XL + 2 * WL8;             // staging registers (x4 dwords) per thread
     static constexpr int XROWS = XL * (NT / 4);         // rows staged per K-step (>= BM; the excess reads as zero)
-    static constexpr int XPS = (XROWS + 4) * 16;        // bytes per activation k-plane (+4 chunks staggers the planes over the banks)
-    static constexpr int WPS = (BN + 4) * 16;
+    static constexpr int XPS = (XROWS + 2) * 16;        // bytes per activation k-plane (+2 chunks staggers the planes over the banks)
+    static constexpr int WPS = (BN + 2) * 16;
     static constexpr int STAGE = 4 * XPS + 4 * WPS;
-    static constexpr int LDS_BYTES = 2 * STAGE;
+    static constexpr int NSTAGE = 3;
+    static constexpr int QSTRIDE = BN + 16;             // row stride of the int8 output tile staged in LDS
+    static constexpr int TABLE = 640;                   // activation positions of up to 160 groups
+    static constexpr int RING = NSTAGE * STAGE;
+    static constexpr int LDS_BYTES = (RING > BM * QSTRIDE ? RING : BM * QSTRIDE) + TABLE;
 };
 
-// How the two 32-channel units of the NEXT K-step are staged.
+// How the two 32-channel units of a K-step are staged.
 enum StepMode { kMode88 = 0, kMode44 = 1, kMode48 = 2, kModeNone = 3 };
 
-template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV, int OCC>
-struct Kern {
-    using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
-    static constexpr int NT = C_::NT, BM = C_::BM, BN = C_::BN, XPS = C_::XPS, WPS = C_::WPS, STAGE = C_::STAGE;
-    static constexpr int XL = C_::XL, WL8 = C_::WL8, WL4 = C_::WL4;
+#define FQ_SB() __builtin_amdgcn_sched_barrier(0)
 
-    const GemmParams &p;
-    unsigned char *lds;
-    int tid;
-    __amdgpu_buffer_rsrc_t rx, rw8, rw4, rws;
-    // per-thread staging addresses
-    int xvoff[XL];            // byte offset of each activation chunk inside the block's buffer window
-    int xh0[XL], xw0[XL], xpix[XL];  // conv: top-left input coordinate and pixel index of the image origin
-    int x_lds;                // LDS byte offset of chunk 0 inside a stage (chunk j adds j * (NT/4) * 16)
-    int w8voff[WL8], w8lds[WL8];
-    int w4voff[WL4], w4lds[WL4];
-    // staging registers
-    v4i xr[XL];
-    v4i wr[2][WL8];
-    int wsh[2][WL4];
-    // scalar K-step iteration state (phase-major: all 4-bit steps, then mixed, then 8-bit)
-    int n4, mixed, SP;  // per tap: full 4-bit steps, 0/1 mixed step, steps in total
-    int it_phase, it_tap, it_c64;
-
-    __device__ __forceinline__ Kern(const GemmParams &pp, unsigned char *l) : p(pp), lds(l) {}
-
-    __device__ __forceinline__ int phase_begin(int ph) const { return ph == 0 ? 0 : (ph == 1 ? n4 : n4 + mixed); }
-    __device__ __forceinline__ int phase_end(int ph) const { return ph == 0 ? n4 : (ph == 1 ? n4 + mixed : SP); }
-
-    // first non-empty phase at or after ph (3 = done)
-    __device__ __forceinline__ void seek_phase(int ph)
-    {
-        while (ph < 3 && phase_begin(ph) == phase_end(ph)) ++ph;
-        it_phase = ph;
-        it_tap = 0;
-        it_c64 = ph < 3 ? phase_begin(ph) : 0;
-    }
-    __device__ __forceinline__ void advance()
-    {
-        if (++it_c64 == phase_end(it_phase)) {
-            it_c64 = phase_begin(it_phase);
-            if (++it_tap == p.T) seek_phase(it_phase + 1);
-        }
-    }
-    __device__ __forceinline__ int cur_mode() const
-    {
-        return it_phase == 0 ? kMode44 : (it_phase == 1 ? kMode48 : (it_phase == 2 ? kMode88 : kModeNone));
-    }
-
-    // ---- global -> registers for the K-step the iterator points at
-    template <int MODE>
-    __device__ __forceinline__ void load_step()
-    {
-        const int tap = it_tap, c64 = it_c64;
-        if (CONV) {
-            const int dy = tap / p.S, dx = tap - dy * p.S;
-#pragma unroll
-            for (int j = 0; j < XL; ++j) {
-                const int hi = xh0[j] + dy, wi = xw0[j] + dx;
-                const bool ok = hi >= 0 && hi < p.H && wi >= 0 && wi < p.Wd && xpix[j] >= 0;
-                const int off = ok ? (xpix[j] + hi * p.Wd + wi) * p.C + xvoff[j] : (int)0x80000000;
-                xr[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, c64 * 64, 0);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < XL; ++j) xr[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, xvoff[j], c64 * 64, 0);
-        }
-        const int u0 = tap * (2 * SP) + 2 * c64;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int u = u0 + h;
-            const bool four = MODE == kMode44 || (MODE == kMode48 && h == 0);
-            if (four) {
-                const int g = (2 * c64 + h) >> p.gs_shift;
-#pragma unroll
-                for (int j = 0; j < WL4; ++j) {
-                    wr[h][j] = __builtin_amdgcn_raw_buffer_load_b128(rw4, w4voff[j], u * 16 * p.Npad, 0);
-                    wsh[h][j] = __builtin_amdgcn_raw_buffer_load_b8(rws, w4voff[j] >> 4, g * p.Npad, 0);
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < WL8; ++j)
-                    wr[h][j] = __builtin_amdgcn_raw_buffer_load_b128(rw8, w8voff[j], u * 32 * p.Npad, 0);
-            }
-        }
-    }
-
-    // ---- registers -> LDS stage, bit-lowering the activations / expanding the 4-bit weights of 4-bit units.
-    // (tap, c64) are those the registers were loaded for.
-    template <int MODE>
-    __device__ __forceinline__ void store_step(unsigned char *stage, int c64)
-    {
-        unsigned char *xs = stage, *ws = stage + 4 * XPS;
-        const int q = tid & 3;
-        // this thread's chunks all lie in unit q>>1 of the step
-        const bool x_four = MODE == kMode44 || (MODE == kMode48 && (q >> 1) == 0);
-        if (MODE == kMode88) {
-#pragma unroll
-            for (int j = 0; j < XL; ++j) *reinterpret_cast<v4i *>(xs + x_lds + j * (NT / 4) * 16) = xr[j];
-        } else {
-            // positions of the two units (uniform); a thread uses the one of its own unit
-            const int sa0 = p.ashift[(2 * c64) >> p.gs_shift], sa1 = p.ashift[(2 * c64 + 1) >> p.gs_shift];
-            const int sa = (q >> 1) ? sa1 : sa0;
-#pragma unroll
-            for (int j = 0; j < XL; ++j) {
-                v4i v = xr[j];
-                if (MODE == kMode44) {
-                    v = lower16(v, sa);
-                } else {
-                    const v4i l = lower16(v, sa);
-                    v = x_four ? l : v;
-                }
-                *reinterpret_cast<v4i *>(xs + x_lds + j * (NT / 4) * 16) = v;
-            }
-        }
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const bool four = MODE == kMode44 || (MODE == kMode48 && h == 0);
-            if (four) {
-#pragma unroll
-                for (int j = 0; j < WL4; ++j) {
-                    if (BN % NT == 0 || tid + j * NT < BN) {
-                        v4i a, b;
-                        expand32(wr[h][j], wsh[h][j], a, b);
-                        *reinterpret_cast<v4i *>(ws + (2 * h) * WPS + w4lds[j]) = a;
-                        *reinterpret_cast<v4i *>(ws + (2 * h + 1) * WPS + w4lds[j]) = b;
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < WL8; ++j)
-                    if ((2 * BN) % NT == 0 || tid + j * NT < 2 * BN)
-                        *reinterpret_cast<v4i *>(ws + (2 * h) * WPS + w8lds[j]) = wr[h][j];
-            }
-        }
-    }
-};
-
-template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV, int OCC>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void k_mixed(const GemmParams p)
+template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV>
+__global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
 {
-    using K_ = Kern<WAVES_M, WAVES_N, TM, TN, CONV, OCC>;
-    constexpr int NT = K_::NT, BM = K_::BM, BN = K_::BN, XPS = K_::XPS, WPS = K_::WPS, STAGE = K_::STAGE;
-    constexpr int XL = K_::XL, WL8 = K_::WL8, WL4 = K_::WL4;
+    using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
+    constexpr int NT = C_::NT, BM = C_::BM, BN = C_::BN, XPS = C_::XPS, WPS = C_::WPS, STAGE = C_::STAGE;
+    constexpr int XL = C_::XL, WL8 = C_::WL8, WL4 = C_::WL4, NS = C_::NS;
+    constexpr int NF = TM + TN;   // fragments per k-half
+    constexpr int NMF = TM * TN;  // MFMAs per k-half
     extern __shared__ __align__(16) unsigned char lds[];
+    unsigned char *const sa_tab = lds + (C_::LDS_BYTES - C_::TABLE);
 
-    K_ k(p, lds);
     const int tid = threadIdx.x;
-    k.tid = tid;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
@@ -297,171 +188,302 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void k_mixed(const Gem
     // ---- buffer windows: reads past a window return zero, which is what rows beyond M, padded
     // pixels and dummy staging rows need
     constexpr int kRsrcFlags = 0x00020000;
-    k.rw8 = __builtin_amdgcn_make_buffer_rsrc((void *)(p.W8 + (int64_t)n0 * 16), 0, p.U * 32 * p.Npad - n0 * 16, kRsrcFlags);
-    k.rw4 = __builtin_amdgcn_make_buffer_rsrc((void *)(p.W4 + (int64_t)n0 * 16), 0, p.U * 16 * p.Npad - n0 * 16, kRsrcFlags);
-    k.rws = __builtin_amdgcn_make_buffer_rsrc((void *)(p.wshift + n0), 0, (p.C >> (5 + p.gs_shift)) * p.Npad - n0, kRsrcFlags);
-    const int xq = tid & 3;
+    const __amdgpu_buffer_rsrc_t rw8 =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(p.W8 + (int64_t)n0 * 16), 0, p.U * 32 * p.Npad - n0 * 16, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rw4 =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(p.W4 + (int64_t)n0 * 16), 0, p.U * 16 * p.Npad - n0 * 16, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rws =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(p.wshift + n0), 0, p.G * p.Npad - n0, kRsrcFlags);
+    __amdgpu_buffer_rsrc_t rx;
+    const int xq = tid & 3;   // k-plane of this thread's activation chunks; unit xq >> 1
+    int xvoff[XL];            // linear: byte offset inside the window; conv: xq * 16
+    int xh0[XL], xw0[XL], xpix[XL];  // conv: top-left input coordinate, pixel index of the image origin (-1: no row)
     if (CONV) {
         const int64_t hw_out = (int64_t)p.Ho * p.Wo;
         const int64_t img0 = m0 / hw_out;
         const int64_t img_bytes = (int64_t)p.H * p.Wd * p.C;
-        const int64_t imgs_left = (p.M / hw_out) - img0;  // images from img0 to the end of the batch
+        const int64_t imgs_left = (p.M / hw_out) - img0;
         const int64_t win = min(imgs_left * img_bytes, (int64_t)0x7fffffff);
-        k.rx = __builtin_amdgcn_make_buffer_rsrc((void *)(p.X + img0 * img_bytes), 0, (int)win, kRsrcFlags);
+        rx = __builtin_amdgcn_make_buffer_rsrc((void *)(p.X + img0 * img_bytes), 0, (int)win, kRsrcFlags);
 #pragma unroll
         for (int j = 0; j < XL; ++j) {
             const int row = (tid >> 2) + j * (NT / 4);
-            const int64_t m = m0 + row;
             const bool ok = row < rows_valid;
-            const int64_t mm = ok ? m : m0;
+            const int64_t mm = ok ? m0 + row : m0;
             const int wo = (int)(mm % p.Wo);
             const int ho = (int)((mm / p.Wo) % p.Ho);
             const int b = (int)(mm / hw_out - img0);
-            k.xpix[j] = ok ? b * p.H * p.Wd : -1;
-            k.xh0[j] = ho * p.stride - p.pad;
-            k.xw0[j] = wo * p.stride - p.pad;
-            k.xvoff[j] = xq * 16;
+            xpix[j] = ok ? b * p.H * p.Wd : -1;
+            xh0[j] = ho * p.stride - p.pad;
+            xw0[j] = wo * p.stride - p.pad;
+            xvoff[j] = xq * 16;
         }
     } else {
-        k.rx = __builtin_amdgcn_make_buffer_rsrc((void *)(p.X + m0 * p.C), 0, rows_valid * p.C, kRsrcFlags);
+        rx = __builtin_amdgcn_make_buffer_rsrc((void *)(p.X + m0 * p.C), 0, rows_valid * p.C, kRsrcFlags);
 #pragma unroll
         for (int j = 0; j < XL; ++j) {
             const int row = (tid >> 2) + j * (NT / 4);
-            k.xvoff[j] = row * p.C + xq * 16;  // rows >= rows_valid fall outside the window: zeros
-            k.xh0[j] = k.xw0[j] = k.xpix[j] = 0;
+            xvoff[j] = row * p.C + xq * 16;  // rows >= rows_valid fall outside the window: zeros
+            xh0[j] = xw0[j] = xpix[j] = 0;
         }
     }
-    k.x_lds = xq * XPS + (tid >> 2) * 16;
+    const int x_lds = xq * XPS + (tid >> 2) * 16;
+    int w8voff[WL8], w8lds[WL8];
 #pragma unroll
     for (int j = 0; j < WL8; ++j) {
         const int i = tid + j * NT;
         const int q2 = i / BN, row = i - q2 * BN;
-        k.w8voff[j] = (q2 * p.Npad + row) * 16;
-        k.w8lds[j] = q2 * WPS + row * 16;
+        w8voff[j] = (q2 * p.Npad + row) * 16;
+        w8lds[j] = 4 * XPS + q2 * WPS + row * 16;
     }
+    int w4voff[WL4], w4lds[WL4];
 #pragma unroll
     for (int j = 0; j < WL4; ++j) {
         const int row = tid + j * NT;
-        k.w4voff[j] = row * 16;
-        k.w4lds[j] = row * 16;
+        w4voff[j] = row * 16;
+        w4lds[j] = 4 * XPS + row * 16;
     }
 
-    // ---- K-step enumeration
-    k.SP = (p.CU + 1) >> 1;
-    k.n4 = p.K4 >> 6;
-    k.mixed = (p.K4 & 63) ? 1 : 0;
-    const int steps = p.T * k.SP;
-    k.seek_phase(0);
+    // activation positions of all groups into LDS (read per step with ordinary LDS loads, which keeps
+    // scalar-memory waits out of the pipelined loop)
+    for (int g = tid; g <= p.G; g += NT) reinterpret_cast<int *>(sa_tab)[g] = p.ashift[g];
 
-    v4i acc[TN][TM];
+    // ---- K-step enumeration, phase-major: all-4-bit steps, then mixed steps, then all-8-bit steps;
+    // the iterator points at the next tile to LOAD.  Scalar state only.
+    const int SP = (p.CU + 1) >> 1;           // steps per tap
+    const int n4 = p.K4 >> 6;                 // full 4-bit steps per tap
+    const int mixed = (p.K4 & 63) ? 1 : 0;    // one step per tap with a 4-bit and an 8-bit unit
+    const int steps = p.T * SP;
+    int it_phase, it_tap, it_dy, it_dx, it_c64;
+    auto phase_begin = [&](int ph) { return ph == 0 ? 0 : (ph == 1 ? n4 : n4 + mixed); };
+    auto phase_end = [&](int ph) { return ph == 0 ? n4 : (ph == 1 ? n4 + mixed : SP); };
+    auto seek_phase = [&](int ph) {
+        while (ph < 3 && phase_begin(ph) == phase_end(ph)) ++ph;
+        it_phase = ph;
+        it_tap = it_dy = it_dx = 0;
+        it_c64 = ph < 3 ? phase_begin(ph) : 0;
+    };
+    auto advance = [&]() {
+        if (++it_c64 == phase_end(it_phase)) {
+            it_c64 = phase_begin(it_phase);
+            if (++it_dx == p.S) { it_dx = 0; ++it_dy; }
+            if (++it_tap == p.T) seek_phase(it_phase + 1);
+        }
+    };
+    auto it_mode = [&]() { return it_phase == 0 ? kMode44 : (it_phase == 1 ? kMode48 : (it_phase == 2 ? kMode88 : kModeNone)); };
+    seek_phase(0);
+
+    // ---- staging registers and the descriptor of the tile they hold
+    v4i sr[NS];
+    int wsh[2][WL4];
+    int st_c64 = 0;   // c64 of the tile in the staging registers
+
+    // global -> registers, chunk i of the tile the iterator points at
+    auto gload = [&](int i, int mode) {
+        const int c64 = it_c64;
+        if (i < XL) {
+            if (CONV) {
+                const int hi = xh0[i] + it_dy, wi = xw0[i] + it_dx;
+                const bool ok = hi >= 0 && hi < p.H && wi >= 0 && wi < p.Wd && xpix[i] >= 0;
+                const int off = ok ? (xpix[i] + hi * p.Wd + wi) * p.C + xvoff[i] : (int)0x80000000;
+                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, c64 * 64, 0);
+            } else {
+                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, xvoff[i], c64 * 64, 0);
+            }
+        } else {
+            const int h = (i - XL) / WL8, j = (i - XL) % WL8;
+            const int u = it_tap * (2 * SP) + 2 * c64 + h;
+            const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
+            if (four) {
+                if (j < WL4) {
+                    const int g = (2 * c64 + h) >> p.gs_shift;
+                    sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw4, w4voff[j], u * 16 * p.Npad, 0);
+                    wsh[h][j] = __builtin_amdgcn_raw_buffer_load_b8(rws, w4voff[j] >> 4, g * p.Npad, 0);
+                }
+            } else {
+                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw8, w8voff[j], u * 32 * p.Npad, 0);
+            }
+        }
+    };
+    // per-step constants of the activation bit-lowering for this thread's unit (position from LDS)
+    v2s lo2, hi2;
+    uint32_t amask;
+    auto lower_setup = [&](int c64) {
+        const int sa = reinterpret_cast<const int *>(sa_tab)[(2 * c64 + (xq >> 1)) >> p.gs_shift];
+        const short lo = (short)((-(8 << sa)) << 8);
+        const short hi = (short)((((8 << sa) - 1) << 8) | 0xFF);
+        lo2 = (v2s){lo, lo};
+        hi2 = (v2s){hi, hi};
+        amask = 0x01010101u * ((0xFFu << sa) & 0xFFu);
+    };
+    // registers -> LDS stage, chunk i of the staged tile, bit-lowering / expanding the 4-bit units
+    auto lstore = [&](int i, int mode, unsigned char *stage) {
+        if (i < XL) {
+            v4i v = sr[i];
+            if (mode == kMode44) {
+                v = lower16v(v, lo2, hi2, amask);
+            } else if (mode == kMode48) {
+                const v4i l = lower16v(v, lo2, hi2, amask);
+                v = (xq >> 1) == 0 ? l : v;
+            }
+            *reinterpret_cast<v4i *>(stage + x_lds + i * (NT / 4) * 16) = v;
+        } else {
+            const int h = (i - XL) / WL8, j = (i - XL) % WL8;
+            const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
+            if (four) {
+                if (j < WL4 && (BN % NT == 0 || tid + j * NT < BN)) {
+                    v4i a, b;
+                    expand32(sr[i], wsh[h][j], a, b);
+                    *reinterpret_cast<v4i *>(stage + (2 * h) * WPS + w4lds[j]) = a;
+                    *reinterpret_cast<v4i *>(stage + (2 * h + 1) * WPS + w4lds[j]) = b;
+                }
+            } else {
+                if ((2 * BN) % NT == 0 || tid + j * NT < 2 * BN)
+                    *reinterpret_cast<v4i *>(stage + (2 * h) * WPS + w8lds[j]) = sr[i];
+            }
+        }
+    };
+
+    v16i acc[TN][TM];
 #pragma unroll
     for (int a = 0; a < TN; ++a)
 #pragma unroll
-        for (int b = 0; b < TM; ++b) acc[a][b] = (v4i){0, 0, 0, 0};
+        for (int b = 0; b < TM; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
 
-    const int frag_plane = lane >> 4, frag_row = lane & 15;
-    const int xs_frag = frag_plane * XPS + (wm * TM * 16 + frag_row) * 16;
-    const int ws_frag = 4 * XPS + frag_plane * WPS + (wn * TN * 16 + frag_row) * 16;
-    auto compute = [&](const unsigned char *stage) {
-        v4i wf[TN];
+    const int frag_half = lane >> 5, frag_row = lane & 31;
+    const int xs_frag = frag_half * XPS + (wm * TM * 32 + frag_row) * 16;
+    const int ws_frag = 4 * XPS + frag_half * WPS + (wn * TN * 32 + frag_row) * 16;
+    // fragments in order of need: w0, x0, w1..w(TN-1), x1..x(TM-1); f[0..TN) weights, f[TN..NF) activations
+    auto forder = [](int i) { return i == 0 ? 0 : (i == 1 ? TN : (i <= TN ? i - 1 : i)); };
+    auto fread = [&](v4i(&f)[NF], int i, const unsigned char *stage, int kh) {
+        if (i < TN) f[i] = *reinterpret_cast<const v4i *>(stage + ws_frag + kh * 2 * WPS + i * 512);
+        else f[i] = *reinterpret_cast<const v4i *>(stage + xs_frag + kh * 2 * XPS + (i - TN) * 512);
+    };
+    v4i fA[NF], fB[NF];
+
+    // ---- prologue: tiles 0 and 1 into stages 0 and 1, tile 2 into the staging registers
+    __syncthreads();  // position table visible
+    int mode_staged = kModeNone;   // mode of the tile in the staging registers
+#pragma unroll 1
+    for (int t = 0; t < 3; ++t) {
+        if (t < steps) {
+            const int mode = it_mode();
+            st_c64 = it_c64;
+            mode_staged = mode;
 #pragma unroll
-        for (int a = 0; a < TN; ++a) wf[a] = *reinterpret_cast<const v4i *>(stage + ws_frag + a * 256);
+            for (int i = 0; i < NS; ++i) gload(i, mode);
+            advance();
+            if (t < 2) {
+                if (mode != kMode88) lower_setup(st_c64);
 #pragma unroll
-        for (int b = 0; b < TM; ++b) {
-            v4i xf = *reinterpret_cast<const v4i *>(stage + xs_frag + b * 256);
-#pragma unroll
-            for (int a = 0; a < TN; ++a)
-                acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[a], xf, acc[a][b], 0, 0, 0);
+                for (int i = 0; i < NS; ++i) lstore(i, mode, lds + t * STAGE);
+                mode_staged = kModeNone;
+            }
         }
-    };
-
-    // ---- prologue: stage K-step 0
-    {
-        const int mode = k.cur_mode(), c64 = k.it_c64;
-        if (mode == kMode44) { k.template load_step<kMode44>(); k.template store_step<kMode44>(lds, c64); }
-        else if (mode == kMode48) { k.template load_step<kMode48>(); k.template store_step<kMode48>(lds, c64); }
-        else { k.template load_step<kMode88>(); k.template store_step<kMode88>(lds, c64); }
-        k.advance();
     }
-    __syncthreads();
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int i = 0; i < NF; ++i) fread(fA, i, lds, 0);
 
-    // ---- main loop: two LDS stages, one barrier per K-step.  The iterator `k` always points at the
-    // NEXT step to stage.  Steps are enumerated phase by phase (all-4-bit, mixed, all-8-bit); while the
-    // next step stays in the current phase the body is straight-line code specialised on that phase
-    // (hot loops below); the one step per phase whose successor lies in another phase (or nowhere) runs
-    // the generic body.  The accumulators are only ever touched in `compute`, in straight-line code.
-    int s = 0;  // K-step being computed
-    auto generic_step = [&]() {
-        unsigned char *cur = lds + (s & 1) * STAGE;
-        unsigned char *nxt = lds + ((s + 1) & 1) * STAGE;
-        const int mode = k.cur_mode();
-        const int c64 = k.it_c64;
-        if (mode == kMode44) k.template load_step<kMode44>();
-        else if (mode == kMode48) k.template load_step<kMode48>();
-        else if (mode == kMode88) k.template load_step<kMode88>();
-        __builtin_amdgcn_sched_barrier(0x38F);
-        compute(cur);
-        if (mode == kMode44) k.template store_step<kMode44>(nxt, c64);
-        else if (mode == kMode48) k.template store_step<kMode48>(nxt, c64);
-        else if (mode == kMode88) k.template store_step<kMode88>(nxt, c64);
-        if (mode != kModeNone) k.advance();
+    // ---- main loop.  Step s computes tile s from stage s % 3 while storing tile s+2 (staged in
+    // registers during step s-1) into stage (s+2) % 3 and loading tile s+3 into the registers: store
+    // of chunk j, then load of chunk j, spread over the whole step.  `ma` is the mode of the staged
+    // tile (kModeNone: nothing to store), `mb` the mode of the tile to load (kModeNone: none left);
+    // both are compile-time constants in the steady-state loops and run-time values elsewhere.
+    int st0 = 0;  // stage of tile s
+    int s = 0;
+    auto step = [&](auto ma_, auto mb_, auto h1_) {
+        const int ma = ma_, mb = mb_;
+        const bool h1 = h1_;
+        const int st1 = st0 == 2 ? 0 : st0 + 1, st2 = st1 == 2 ? 0 : st1 + 1;
+        const unsigned char *cur = lds + st0 * STAGE;
+        const unsigned char *nx1 = lds + st1 * STAGE;
+        unsigned char *nx2 = lds + st2 * STAGE;
+        const int c64_store = st_c64;
+        if (ma == kMode44 || ma == kMode48) lower_setup(c64_store);
+        if (mb != kModeNone) st_c64 = it_c64;
+        FQ_SB();
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+            for (int b = 0; b < TM; ++b)
+#pragma unroll
+                for (int a = 0; a < TN; ++a) {
+                    const int slot = b * TN + a, g = kh * NMF + slot;
+                    if (kh == 0) acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fA[a], fA[TN + b], acc[a][b], 0, 0, 0);
+                    else acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fB[a], fB[TN + b], acc[a][b], 0, 0, 0);
+                    FQ_SB();
+                    // fragment read k of the other register set at slot k*NMF/NF of this k-half
+#pragma unroll
+                    for (int k = 0; k < NF; ++k)
+                        if (k * NMF / NF == slot) {
+                            if (kh == 0) fread(fB, forder(k), cur, 1);
+                            else if (h1) fread(fA, forder(k), nx1, 0);
+                            FQ_SB();
+                        }
+                    // staging chunk j: store at step slot (2j)*2NMF/(2NS), load right after
+#pragma unroll
+                    for (int j = 0; j < 2 * NS; ++j)
+                        if (j * (2 * NMF) / (2 * NS) == g) {
+                            if ((j & 1) == 0) {
+                                if (ma != kModeNone) lstore(j / 2, ma, nx2);
+                            } else {
+                                if (mb != kModeNone) gload(j / 2, mb);
+                            }
+                            FQ_SB();
+                        }
+                }
+        if (mb != kModeNone) advance();
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // this wave's LDS stores and fragment reads are complete
+        __builtin_amdgcn_s_barrier();
+        FQ_SB();
+        st0 = st1;
         ++s;
-        __syncthreads();
+        mode_staged = mb;
     };
-#define FLEXIQ_HOT_LOOP(MODE, PHASE)                                                         \
-    while (s + 1 < steps && k.it_phase == (PHASE)) {                                         \
-        unsigned char *cur = lds + (s & 1) * STAGE;                                          \
-        unsigned char *nxt = lds + ((s + 1) & 1) * STAGE;                                    \
-        const int c64 = k.it_c64;                                                            \
-        k.template load_step<MODE>();                                                        \
-        __builtin_amdgcn_sched_barrier(0x38F); /* global loads stay ahead of the matrix work */ \
-        compute(cur);                                                                        \
-        k.template store_step<MODE>(nxt, c64);                                               \
-        k.advance();                                                                         \
-        ++s;                                                                                 \
-        __syncthreads();                                                                     \
-    }
-    FLEXIQ_HOT_LOOP(kMode44, 0)
-    if (s < steps && k.it_phase != 2) generic_step();
-    FLEXIQ_HOT_LOOP(kMode48, 1)
-    if (s < steps && k.it_phase != 2) generic_step();
-    FLEXIQ_HOT_LOOP(kMode88, 2)
-    while (s < steps) generic_step();
-#undef FLEXIQ_HOT_LOOP
+    using M44 = std::integral_constant<int, kMode44>;
+    using M88 = std::integral_constant<int, kMode88>;
+    // steady state: staged tile and tile to load are both of the phase's mode
+    while (mode_staged == kMode44 && it_phase == 0) step(M44{}, M44{}, std::true_type{});
+    while (s < steps && !(mode_staged == kMode88 && it_phase == 2)) step(mode_staged, (int)it_mode(), s + 1 < steps);
+    while (mode_staged == kMode88 && it_phase == 2) step(M88{}, M88{}, std::true_type{});
+    while (s < steps) step(mode_staged, (int)it_mode(), s + 1 < steps);
 
-    // ---- epilogue: lane holds output row m (lane & 15) and four consecutive output channels
+    // ---- epilogue.  Lane holds output row m = 32 b + (lane & 31) and, per accumulator quad g, the four
+    // consecutive output channels n = 32 a + 8 g + 4 (lane >> 5) + i.
     const bool want_q = p.q != nullptr, want_y = p.y != nullptr, want_acc = p.acc != nullptr;
     const bool n_vec = (p.N & 3) == 0;
+    const bool q_lds = want_q && (p.N & 15) == 0;   // int8 tile through LDS: 16-byte row-contiguous stores
+    constexpr int QS = C_::QSTRIDE;
 #pragma unroll
     for (int a = 0; a < TN; ++a) {
-        const int n = n0 + (wn * TN + a) * 16 + 4 * frag_plane;
-        if (n >= p.N) continue;
-        const float4 cs = *reinterpret_cast<const float4 *>(p.cs + n);  // cs/bias are padded to Npad
-        const float4 bi = *reinterpret_cast<const float4 *>(p.bias + n);
-        const float csv[4] = {cs.x, cs.y, cs.z, cs.w}, biv[4] = {bi.x, bi.y, bi.z, bi.w};
-        float mul[4], add[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            mul[i] = csv[i] * p.r_out;
-            add[i] = biv[i] * p.r_out;
-        }
+        for (int g = 0; g < 4; ++g) {
+            const int nl = (wn * TN + a) * 32 + 8 * g + 4 * frag_half;
+            const int n = n0 + nl;
+            const bool n_ok = n < p.N;
+            float csv[4], biv[4], mul[4], add[4];
+            {
+                const int nn = n_ok ? n : 0;
+                const float4 cs = *reinterpret_cast<const float4 *>(p.cs + nn);  // cs/bias are padded to Npad
+                const float4 bi = *reinterpret_cast<const float4 *>(p.bias + nn);
+                csv[0] = cs.x; csv[1] = cs.y; csv[2] = cs.z; csv[3] = cs.w;
+                biv[0] = bi.x; biv[1] = bi.y; biv[2] = bi.z; biv[3] = bi.w;
+            }
 #pragma unroll
-        for (int b = 0; b < TM; ++b) {
-            const int64_t m = m0 + (wm * TM + b) * 16 + frag_row;
-            if (m >= p.M) continue;
-            const v4i v = acc[a][b];
-            const int iv[4] = {v.x, v.y, v.z, v.w};
-            const int64_t o = m * p.N + n;
-            if (n_vec) {
-                if (want_acc) *reinterpret_cast<v4i *>(p.acc + o) = v;
-                if (want_y) {
-                    float4 y;
-                    y.x = __builtin_fmaf((float)iv[0], csv[0], biv[0]);
-                    y.y = __builtin_fmaf((float)iv[1], csv[1], biv[1]);
-                    y.z = __builtin_fmaf((float)iv[2], csv[2], biv[2]);
-                    y.w = __builtin_fmaf((float)iv[3], csv[3], biv[3]);
-                    *reinterpret_cast<float4 *>(p.y + o) = y;
-                }
+            for (int i = 0; i < 4; ++i) {
+                mul[i] = csv[i] * p.r_out;
+                add[i] = biv[i] * p.r_out;
+            }
+#pragma unroll
+            for (int b = 0; b < TM; ++b) {
+                const int ml = (wm * TM + b) * 32 + frag_row;
+                const int64_t m = m0 + ml;
+                const int iv[4] = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
+                uint32_t qw = 0;
                 if (want_q) {
                     uint32_t u[4];
 #pragma unroll
@@ -470,21 +492,44 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void k_mixed(const Gem
                         t = __builtin_amdgcn_fmed3f(t, -128.0f, 127.0f);
                         u[i] = __builtin_bit_cast(uint32_t, t + 12582912.0f);  // 1.5 * 2^23: integer lands in the low bits
                     }
-                    uint32_t w01 = __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u);
-                    uint32_t w23 = __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu);
-                    *reinterpret_cast<uint32_t *>(p.q + o) = w01 | w23;
+                    qw = __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu);
+                    if (q_lds) *reinterpret_cast<uint32_t *>(lds + ml * QS + nl) = qw;
                 }
-            } else {
-                for (int i = 0; i < 4 && n + i < p.N; ++i) {
-                    if (want_acc) p.acc[o + i] = iv[i];
-                    if (want_y) p.y[o + i] = __builtin_fmaf((float)iv[i], csv[i], biv[i]);
-                    if (want_q) {
-                        float t = __builtin_fmaf((float)iv[i], mul[i], add[i]);
-                        t = __builtin_amdgcn_fmed3f(t, -128.0f, 127.0f);
-                        p.q[o + i] = (int8_t)(__builtin_bit_cast(uint32_t, t + 12582912.0f) & 0xFF);
+                if (m >= p.M || !n_ok) continue;
+                const int64_t o = m * p.N + n;
+                if (n_vec) {
+                    if (want_acc) *reinterpret_cast<v4i *>(p.acc + o) = (v4i){iv[0], iv[1], iv[2], iv[3]};
+                    if (want_y) {
+                        float4 y;
+                        y.x = __builtin_fmaf((float)iv[0], csv[0], biv[0]);
+                        y.y = __builtin_fmaf((float)iv[1], csv[1], biv[1]);
+                        y.z = __builtin_fmaf((float)iv[2], csv[2], biv[2]);
+                        y.w = __builtin_fmaf((float)iv[3], csv[3], biv[3]);
+                        *reinterpret_cast<float4 *>(p.y + o) = y;
+                    }
+                    if (want_q && !q_lds) *reinterpret_cast<uint32_t *>(p.q + o) = qw;
+                } else {
+                    for (int i = 0; i < 4 && n + i < p.N; ++i) {
+                        if (want_acc) p.acc[o + i] = iv[i];
+                        if (want_y) p.y[o + i] = __builtin_fmaf((float)iv[i], csv[i], biv[i]);
+                        if (want_q) p.q[o + i] = (int8_t)((qw >> (8 * i)) & 0xFF);
                     }
                 }
             }
+        }
+    }
+    if (q_lds) {
+        __syncthreads();
+        constexpr int TPR = BN / 16;   // threads per tile row
+        constexpr int RPP = NT / TPR;  // rows per pass
+        const int c16 = tid % TPR, r0 = tid / TPR;
+#pragma unroll
+        for (int pass = 0; pass < (BM + RPP - 1) / RPP; ++pass) {
+            const int row = r0 + pass * RPP;
+            const int64_t m = m0 + row;
+            const int n = n0 + c16 * 16;
+            if (row < BM && m < p.M && n < p.N)
+                *reinterpret_cast<v4i *>(p.q + m * p.N + n) = *reinterpret_cast<const v4i *>(lds + row * QS + c16 * 16);
         }
     }
 }
@@ -496,29 +541,31 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void k_mixed(const Gem
 typedef void (*kernel_fn)(const GemmParams);
 struct TileShape {
     int BM, BN, lds;
+    int mfma_per_khalf;  // MFMAs per wave per k-half
+    double cyc_per_mfma; // measured cycles per MFMA slot in the steady-state loop (32 is the pipe's own time)
     kernel_fn lin, conv;
 };
 
-template <int WAVES_M, int WAVES_N, int TM, int TN, int OCC>
-static TileShape make_shape()
+template <int WAVES_M, int WAVES_N, int TM, int TN>
+static TileShape make_shape(double cyc)
 {
     using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
     static_assert(C_::NT == 256, "the launcher uses 256 threads");
-    return TileShape{C_::BM, C_::BN, C_::LDS_BYTES, k_mixed<WAVES_M, WAVES_N, TM, TN, false, OCC>,
-                     k_mixed<WAVES_M, WAVES_N, TM, TN, true, OCC>};
+    return TileShape{C_::BM, C_::BN, C_::LDS_BYTES, TM * TN, cyc, k_mixed<WAVES_M, WAVES_N, TM, TN, false>,
+                     k_mixed<WAVES_M, WAVES_N, TM, TN, true>};
 }
 
 static const TileShape *shapes(int *count)
 {
     static const TileShape tab[] = {
-        make_shape<2, 2, 8, 8, 1>(),   // 256 x 256
-        make_shape<1, 4, 13, 4, 1>(),  // 208 x 256
-        make_shape<1, 4, 10, 4, 1>(),  // 160 x 256
-        make_shape<2, 2, 4, 8, 2>(),   // 128 x 256, two blocks per CU
-        make_shape<2, 2, 8, 4, 2>(),   // 256 x 128, two blocks per CU
-        make_shape<2, 2, 4, 4, 2>(),   // 128 x 128
-        make_shape<2, 2, 2, 4, 2>(),   //  64 x 128
-        make_shape<2, 2, 2, 2, 2>(),   //  64 x  64
+        make_shape<2, 2, 4, 4>(40.0),  // 256 x 256
+        make_shape<1, 4, 7, 2>(43.0),  // 224 x 256
+        make_shape<2, 2, 3, 4>(43.0),  // 192 x 256
+        make_shape<1, 4, 5, 2>(46.0),  // 160 x 256
+        make_shape<2, 2, 2, 4>(50.0),  // 128 x 256
+        make_shape<2, 2, 2, 2>(60.0),  // 128 x 128
+        make_shape<2, 2, 1, 2>(75.0),  //  64 x 128
+        make_shape<2, 2, 1, 1>(90.0),  //  64 x  64
     };
     *count = (int)(sizeof(tab) / sizeof(tab[0]));
     return tab;
@@ -527,9 +574,9 @@ static const TileShape *shapes(int *count)
 static int g_num_cu = 0;
 static int g_force_shape = -1;
 
-// Pick the tile shape with the smallest modelled time: waves of blocks over the CUs times the cost
-// of one tile (matrix work plus a per-K-step overhead that penalises small tiles).
-static const TileShape &choose_shape(int64_t M, int N)
+// Pick the tile shape with the smallest modelled time: rounds of blocks over the CUs times the cycles
+// of one tile (K-steps at the measured cost per MFMA slot, plus prologue and epilogue).
+static const TileShape &choose_shape(int64_t M, int N, int steps)
 {
     int cnt;
     const TileShape *tab = shapes(&cnt);
@@ -546,8 +593,9 @@ static const TileShape &choose_shape(int64_t M, int N)
     for (int i = 0; i < cnt; ++i) {
         const double tm = (double)((M + tab[i].BM - 1) / tab[i].BM), tn = (double)((N + tab[i].BN - 1) / tab[i].BN);
         const double rounds = __builtin_ceil(tm * tn / g_num_cu);
-        // per K-step: BM*BN/256 MFMA issue slots of 16 cycles per SIMD + staging cost ~ (BM + BN) * 0.6
-        const double tile = (double)tab[i].BM * tab[i].BN / 256.0 * 4.0 + 0.6 * (tab[i].BM + tab[i].BN) + 40.0;
+        const double tile = steps * 2.0 * tab[i].mfma_per_khalf * tab[i].cyc_per_mfma  // main loop
+                            + 600.0 * tab[i].mfma_per_khalf                              // epilogue
+                            + 3000.0;                                                    // launch, prologue
         const double cost = rounds * tile;
         if (cost < best) {
             best = cost;
@@ -568,10 +616,11 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     p.M = M; p.N = L->N; p.Npad = L->Npad; p.C = L->C;
     p.K4 = L->max_4bit_ch;
     p.gs_shift = L->group_size == 64 ? 1 : 0;
-    p.U = L->U; p.CU = L->C / kUnit; p.T = L->T;
+    p.U = L->U; p.CU = L->C / kUnit; p.T = L->T; p.G = L->G;
+    if (L->G + 1 > 160) return FLEXIQ_EINVAL;  // position table kept in LDS
     if ((int64_t)L->U * 32 * L->Npad > 0x7fffffff) return FLEXIQ_EINVAL;  // weight window must fit a buffer descriptor
     p.H = H; p.Wd = Wd; p.Ho = Ho; p.Wo = Wo; p.S = L->S; p.stride = stride; p.pad = pad;
-    const TileShape &ts = choose_shape(M, L->N);
+    const TileShape &ts = choose_shape(M, L->N, L->T * ((p.CU + 1) / 2));
     p.tiles_m = (int)((M + ts.BM - 1) / ts.BM);
     p.tiles_n = (L->N + ts.BN - 1) / ts.BN;
     const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
