@@ -141,7 +141,7 @@ struct Cfg {
     static constexpr int STAGE = 4 * XPS + 4 * WPS;
     static constexpr int NSTAGE = 3;
     static constexpr int QSTRIDE = BN + 16;             // row stride of the int8 output tile staged in LDS
-    static constexpr int TABLE = 640;                   // activation positions of up to 160 groups
+    static constexpr int TABLE = 640 + 2 * BN * 4;      // activation positions of up to 160 groups; scale and bias of the tile's columns
     static constexpr int RING = NSTAGE * STAGE;
     static constexpr int LDS_BYTES = (RING > BM * QSTRIDE ? RING : BM * QSTRIDE) + TABLE;
 };
@@ -161,10 +161,14 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
     constexpr int NMF = TM * TN;  // MFMAs per k-half
     extern __shared__ __align__(16) unsigned char lds[];
     unsigned char *const sa_tab = lds + (C_::LDS_BYTES - C_::TABLE);
+    float *const cs_tab = reinterpret_cast<float *>(sa_tab + 640);  // [BN] scales, then [BN] biases
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+#ifdef FLEXIQ_TIMING
+    long long tq0 = __builtin_readcyclecounter();
+#endif
 
     // ---- block -> tile.  Consecutive block ids land on different XCDs (8 of them, each with its own
     // L2); renumber so that the blocks sharing an XCD walk neighbouring tiles, then sweep bands of 8
@@ -178,8 +182,9 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
         const int band = b / (GMB * p.tiles_n);
         const int rows_in_band = min(GMB, p.tiles_m - band * GMB);
         const int r = b - band * GMB * p.tiles_n;
-        tile_m = band * GMB + r % rows_in_band;
-        tile_n = r / rows_in_band;
+        // the division runs on the vector ALU; tell the compiler the result is wave-uniform
+        tile_m = __builtin_amdgcn_readfirstlane(band * GMB + r % rows_in_band);
+        tile_n = __builtin_amdgcn_readfirstlane(r / rows_in_band);
     }
     const int64_t m0 = (int64_t)tile_m * BM;
     const int n0 = tile_n * BN;
@@ -194,7 +199,8 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
         __builtin_amdgcn_make_buffer_rsrc((void *)(p.W4 + (int64_t)n0 * 16), 0, p.U * 16 * p.Npad - n0 * 16, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t rws =
         __builtin_amdgcn_make_buffer_rsrc((void *)(p.wshift + n0), 0, p.G * p.Npad - n0, kRsrcFlags);
-    __amdgpu_buffer_rsrc_t rx;
+    const int8_t *xbase;  // origin and size of the activation window of this block
+    int xwin;
     const int xq = tid & 3;   // k-plane of this thread's activation chunks; unit xq >> 1
     int xvoff[XL];            // linear: byte offset inside the window; conv: xq * 16
     int xh0[XL], xw0[XL], xpix[XL];  // conv: top-left input coordinate, pixel index of the image origin (-1: no row)
@@ -204,7 +210,8 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
         const int64_t img_bytes = (int64_t)p.H * p.Wd * p.C;
         const int64_t imgs_left = (p.M / hw_out) - img0;
         const int64_t win = min(imgs_left * img_bytes, (int64_t)0x7fffffff);
-        rx = __builtin_amdgcn_make_buffer_rsrc((void *)(p.X + img0 * img_bytes), 0, (int)win, kRsrcFlags);
+        xbase = p.X + img0 * img_bytes;
+        xwin = (int)win;
 #pragma unroll
         for (int j = 0; j < XL; ++j) {
             const int row = (tid >> 2) + j * (NT / 4);
@@ -219,7 +226,8 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
             xvoff[j] = xq * 16;
         }
     } else {
-        rx = __builtin_amdgcn_make_buffer_rsrc((void *)(p.X + m0 * p.C), 0, rows_valid * p.C, kRsrcFlags);
+        xbase = p.X + m0 * p.C;
+        xwin = rows_valid * p.C;
 #pragma unroll
         for (int j = 0; j < XL; ++j) {
             const int row = (tid >> 2) + j * (NT / 4);
@@ -227,6 +235,7 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
             xh0[j] = xw0[j] = xpix[j] = 0;
         }
     }
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)xbase, 0, xwin, kRsrcFlags);
     const int x_lds = xq * XPS + (tid >> 2) * 16;
     int w8voff[WL8], w8lds[WL8];
 #pragma unroll
@@ -247,6 +256,10 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
     // activation positions of all groups into LDS (read per step with ordinary LDS loads, which keeps
     // scalar-memory waits out of the pipelined loop)
     for (int g = tid; g <= p.G; g += NT) reinterpret_cast<int *>(sa_tab)[g] = p.ashift[g];
+    for (int c = tid; c < BN; c += NT) {  // cs/bias are padded to Npad >= n0 + BN
+        cs_tab[c] = p.cs[n0 + c];
+        cs_tab[BN + c] = p.bias[n0 + c];
+    }
 
     // ---- K-step enumeration, phase-major: all-4-bit steps, then mixed steps, then all-8-bit steps;
     // the iterator points at the next tile to LOAD.  Scalar state only.
@@ -254,24 +267,37 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
     const int n4 = p.K4 >> 6;                 // full 4-bit steps per tap
     const int mixed = (p.K4 & 63) ? 1 : 0;    // one step per tap with a 4-bit and an 8-bit unit
     const int steps = p.T * SP;
-    int it_phase, it_tap, it_dy, it_dx, it_c64;
-    auto phase_begin = [&](int ph) { return ph == 0 ? 0 : (ph == 1 ? n4 : n4 + mixed); };
-    auto phase_end = [&](int ph) { return ph == 0 ? n4 : (ph == 1 ? n4 + mixed : SP); };
-    auto seek_phase = [&](int ph) {
-        while (ph < 3 && phase_begin(ph) == phase_end(ph)) ++ph;
-        it_phase = ph;
-        it_tap = it_dy = it_dx = 0;
-        it_c64 = ph < 3 ? phase_begin(ph) : 0;
-    };
+    // Phase p covers c64 in [pb(p), pe(p)) of every tap; pn(p) is the next non-empty phase (3 = done).
+    // The update is written with selects only: the steady-state loops must stay single basic blocks
+    // so that the compiler can count outstanding loads exactly across the back edge.
+    auto pb = [&](int ph) { return ph == 0 ? 0 : (ph == 1 ? n4 : n4 + mixed); };
+    auto pe = [&](int ph) { return ph == 0 ? n4 : (ph == 1 ? n4 + mixed : SP); };
+    const int ne0 = n4 > 0, ne1 = mixed > 0, ne2 = n4 + mixed < SP;
+    const int first_phase = ne0 ? 0 : (ne1 ? 1 : (ne2 ? 2 : 3));
+    const int next1 = ne1 ? 1 : (ne2 ? 2 : 3), next2 = ne2 ? 2 : 3;
+    auto pn = [&](int ph) { return ph == 0 ? next1 : (ph == 1 ? next2 : 3); };
+    int it_phase = first_phase, it_tap = 0, it_dy = 0, it_dx = 0;
+    int it_c64 = first_phase < 3 ? pb(first_phase) : 0;
+    int it_b = it_c64, it_e = first_phase < 3 ? pe(first_phase) : 0;  // bounds of the current phase
     auto advance = [&]() {
-        if (++it_c64 == phase_end(it_phase)) {
-            it_c64 = phase_begin(it_phase);
-            if (++it_dx == p.S) { it_dx = 0; ++it_dy; }
-            if (++it_tap == p.T) seek_phase(it_phase + 1);
-        }
+        const int c = it_c64 + 1;
+        const bool wrap_c = c == it_e;                  // this tap's part of the phase is finished
+        const int dx1 = it_dx + 1;
+        const bool wrap_x = dx1 == p.S;
+        const int tap1 = it_tap + 1;
+        const bool wrap_t = wrap_c && tap1 == p.T;      // the phase is finished
+        const int ph = wrap_t ? pn(it_phase) : it_phase;
+        const int nb = wrap_t ? (ph < 3 ? pb(ph) : 0) : it_b;
+        const int ne = wrap_t ? (ph < 3 ? pe(ph) : 0) : it_e;
+        it_dy = wrap_t ? 0 : (wrap_c && wrap_x ? it_dy + 1 : it_dy);
+        it_dx = wrap_t ? 0 : (wrap_c ? (wrap_x ? 0 : dx1) : it_dx);
+        it_tap = wrap_t ? 0 : (wrap_c ? tap1 : it_tap);
+        it_c64 = wrap_c ? nb : c;
+        it_phase = ph;
+        it_b = nb;
+        it_e = ne;
     };
     auto it_mode = [&]() { return it_phase == 0 ? kMode44 : (it_phase == 1 ? kMode48 : (it_phase == 2 ? kMode88 : kModeNone)); };
-    seek_phase(0);
 
     // ---- staging registers and the descriptor of the tile they hold
     v4i sr[NS];
@@ -388,6 +414,9 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
 #pragma unroll
     for (int i = 0; i < NF; ++i) fread(fA, i, lds, 0);
 
+#ifdef FLEXIQ_TIMING
+    long long tq1 = __builtin_readcyclecounter();
+#endif
     // ---- main loop.  Step s computes tile s from stage s % 3 while storing tile s+2 (staged in
     // registers during step s-1) into stage (s+2) % 3 and loading tile s+3 into the registers: store
     // of chunk j, then load of chunk j, spread over the whole step.  `ma` is the mode of the staged
@@ -446,78 +475,111 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
     };
     using M44 = std::integral_constant<int, kMode44>;
     using M88 = std::integral_constant<int, kMode88>;
-    // steady state: staged tile and tile to load are both of the phase's mode
-    while (mode_staged == kMode44 && it_phase == 0) step(M44{}, M44{}, std::true_type{});
-    while (s < steps && !(mode_staged == kMode88 && it_phase == 2)) step(mode_staged, (int)it_mode(), s + 1 < steps);
-    while (mode_staged == kMode88 && it_phase == 2) step(M88{}, M88{}, std::true_type{});
-    while (s < steps) step(mode_staged, (int)it_mode(), s + 1 < steps);
+    using MNone = std::integral_constant<int, kModeNone>;
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    // A sequence of loops in the order the cases occur (each may run zero times), so that every
+    // variant of the step body is straight-line code and the accumulators never pass through a
+    // run-time selection between code paths:
+    //   steady 4-bit | transitions (generic, run-time modes) | steady 8-bit | drain: store the last staged
+    //   tile without loading | last steps with nothing left to stage
+    // (Entering a steady-state loop with no load in flight lets the compiler count the loads of the loop
+    // itself exactly, instead of waiting for all of them before the first store of every step.)
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    while (mode_staged == kMode44 && it_phase == 0) step(M44{}, M44{}, T_{});
+    while (s < steps && it_phase != 3 && !(mode_staged == kMode88 && it_phase == 2)) step(mode_staged, (int)it_mode(), s + 1 < steps);
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    while (mode_staged == kMode88 && it_phase == 2) step(M88{}, M88{}, T_{});
+    while (s < steps && mode_staged == kMode88) step(M88{}, MNone{}, T_{});
+    while (s < steps && mode_staged == kMode44) step(M44{}, MNone{}, T_{});
+    while (s < steps && mode_staged != kModeNone) step(mode_staged, (int)kModeNone, s + 1 < steps);
+    while (s + 1 < steps) step(MNone{}, MNone{}, T_{});
+    while (s < steps) step(MNone{}, MNone{}, F_{});
 
+#ifdef FLEXIQ_TIMING
+    long long tq2 = __builtin_readcyclecounter();
+#endif
     // ---- epilogue.  Lane holds output row m = 32 b + (lane & 31) and, per accumulator quad g, the four
-    // consecutive output channels n = 32 a + 8 g + 4 (lane >> 5) + i.
+    // consecutive output channels n = 32 a + 8 g + 4 (lane >> 5) + i.  The body is instantiated with
+    // compile-time output flags for the common cases (int8 only; fp32 and/or int32 only) and once
+    // with run-time flags for everything else (ragged N, several outputs at once).
+#ifdef FLEXIQ_TIMING
+    const bool want_q = p.q != nullptr, want_y = p.y != nullptr, want_acc = false;
+#else
     const bool want_q = p.q != nullptr, want_y = p.y != nullptr, want_acc = p.acc != nullptr;
+#endif
     const bool n_vec = (p.N & 3) == 0;
     const bool q_lds = want_q && (p.N & 15) == 0;   // int8 tile through LDS: 16-byte row-contiguous stores
     constexpr int QS = C_::QSTRIDE;
+    auto epilogue = [&](auto wq_, auto wy_, auto wa_, auto nv_, auto ql_) {
+        const bool wq = wq_, wy = wy_, wa = wa_, nv = nv_, ql = ql_;
 #pragma unroll
-    for (int a = 0; a < TN; ++a) {
+        for (int a = 0; a < TN; ++a) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int nl = (wn * TN + a) * 32 + 8 * g + 4 * frag_half;
-            const int n = n0 + nl;
-            const bool n_ok = n < p.N;
-            float csv[4], biv[4], mul[4], add[4];
-            {
-                const int nn = n_ok ? n : 0;
-                const float4 cs = *reinterpret_cast<const float4 *>(p.cs + nn);  // cs/bias are padded to Npad
-                const float4 bi = *reinterpret_cast<const float4 *>(p.bias + nn);
-                csv[0] = cs.x; csv[1] = cs.y; csv[2] = cs.z; csv[3] = cs.w;
-                biv[0] = bi.x; biv[1] = bi.y; biv[2] = bi.z; biv[3] = bi.w;
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                mul[i] = csv[i] * p.r_out;
-                add[i] = biv[i] * p.r_out;
-            }
-#pragma unroll
-            for (int b = 0; b < TM; ++b) {
-                const int ml = (wm * TM + b) * 32 + frag_row;
-                const int64_t m = m0 + ml;
-                const int iv[4] = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
-                uint32_t qw = 0;
-                if (want_q) {
-                    uint32_t u[4];
+            for (int g = 0; g < 4; ++g) {
+                const int nl = (wn * TN + a) * 32 + 8 * g + 4 * frag_half;
+                const int n = n0 + nl;
+                const bool n_ok = n < p.N;
+                float csv[4], biv[4], mul[4], add[4];
+                {
+                    const float4 cs = *reinterpret_cast<const float4 *>(cs_tab + nl);
+                    const float4 bi = *reinterpret_cast<const float4 *>(cs_tab + BN + nl);
+                    csv[0] = cs.x; csv[1] = cs.y; csv[2] = cs.z; csv[3] = cs.w;
+                    biv[0] = bi.x; biv[1] = bi.y; biv[2] = bi.z; biv[3] = bi.w;
+                }
+                if (wq) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        float t = __builtin_fmaf((float)iv[i], mul[i], add[i]);
-                        t = __builtin_amdgcn_fmed3f(t, -128.0f, 127.0f);
-                        u[i] = __builtin_bit_cast(uint32_t, t + 12582912.0f);  // 1.5 * 2^23: integer lands in the low bits
+                        mul[i] = csv[i] * p.r_out;
+                        add[i] = biv[i] * p.r_out;
                     }
-                    qw = __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu);
-                    if (q_lds) *reinterpret_cast<uint32_t *>(lds + ml * QS + nl) = qw;
                 }
-                if (m >= p.M || !n_ok) continue;
-                const int64_t o = m * p.N + n;
-                if (n_vec) {
-                    if (want_acc) *reinterpret_cast<v4i *>(p.acc + o) = (v4i){iv[0], iv[1], iv[2], iv[3]};
-                    if (want_y) {
-                        float4 y;
-                        y.x = __builtin_fmaf((float)iv[0], csv[0], biv[0]);
-                        y.y = __builtin_fmaf((float)iv[1], csv[1], biv[1]);
-                        y.z = __builtin_fmaf((float)iv[2], csv[2], biv[2]);
-                        y.w = __builtin_fmaf((float)iv[3], csv[3], biv[3]);
-                        *reinterpret_cast<float4 *>(p.y + o) = y;
+#pragma unroll
+                for (int b = 0; b < TM; ++b) {
+                    const int ml = (wm * TM + b) * 32 + frag_row;
+                    const int64_t m = m0 + ml;
+                    const int iv[4] = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
+                    uint32_t qw = 0;
+                    if (wq) {
+                        uint32_t u[4];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            float t = __builtin_fmaf((float)iv[i], mul[i], add[i]);
+                            t = __builtin_amdgcn_fmed3f(t, -128.0f, 127.0f);
+                            u[i] = __builtin_bit_cast(uint32_t, t + 12582912.0f);  // 1.5 * 2^23: integer lands in the low bits
+                        }
+                        qw = __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu);
+                        if (ql) *reinterpret_cast<uint32_t *>(lds + ml * QS + nl) = qw;
                     }
-                    if (want_q && !q_lds) *reinterpret_cast<uint32_t *>(p.q + o) = qw;
-                } else {
-                    for (int i = 0; i < 4 && n + i < p.N; ++i) {
-                        if (want_acc) p.acc[o + i] = iv[i];
-                        if (want_y) p.y[o + i] = __builtin_fmaf((float)iv[i], csv[i], biv[i]);
-                        if (want_q) p.q[o + i] = (int8_t)((qw >> (8 * i)) & 0xFF);
+                    if (!(wy || wa || (wq && !ql))) continue;   // nothing goes straight to global memory
+                    if (m >= p.M || !n_ok) continue;
+                    const int64_t o = m * p.N + n;
+                    if (nv) {
+                        if (wa) *reinterpret_cast<v4i *>(p.acc + o) = (v4i){iv[0], iv[1], iv[2], iv[3]};
+                        if (wy) {
+                            float4 y;
+                            y.x = __builtin_fmaf((float)iv[0], csv[0], biv[0]);
+                            y.y = __builtin_fmaf((float)iv[1], csv[1], biv[1]);
+                            y.z = __builtin_fmaf((float)iv[2], csv[2], biv[2]);
+                            y.w = __builtin_fmaf((float)iv[3], csv[3], biv[3]);
+                            *reinterpret_cast<float4 *>(p.y + o) = y;
+                        }
+                        if (wq && !ql) *reinterpret_cast<uint32_t *>(p.q + o) = qw;
+                    } else {
+                        for (int i = 0; i < 4 && n + i < p.N; ++i) {
+                            if (wa) p.acc[o + i] = iv[i];
+                            if (wy) p.y[o + i] = __builtin_fmaf((float)iv[i], csv[i], biv[i]);
+                            if (wq) p.q[o + i] = (int8_t)((qw >> (8 * i)) & 0xFF);
+                        }
                     }
                 }
             }
         }
-    }
+    };
+    if (q_lds && !want_y && !want_acc) epilogue(T_{}, F_{}, F_{}, T_{}, T_{});
+    else if (n_vec && !want_q && want_y && !want_acc) epilogue(F_{}, T_{}, F_{}, T_{}, F_{});
+    else if (n_vec && !want_q && !want_y && want_acc) epilogue(F_{}, F_{}, T_{}, T_{}, F_{});
+    else epilogue(want_q, want_y, want_acc, n_vec, q_lds);
     if (q_lds) {
         __syncthreads();
         constexpr int TPR = BN / 16;   // threads per tile row
@@ -532,6 +594,15 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
                 *reinterpret_cast<v4i *>(p.q + m * p.N + n) = *reinterpret_cast<const v4i *>(lds + row * QS + c16 * 16);
         }
     }
+#ifdef FLEXIQ_TIMING
+    {
+        long long tq3 = __builtin_readcyclecounter();
+        if (lane == 0 && p.acc) {
+            int *d = p.acc + ((int64_t)blockIdx.x * 4 + wave) * 4;
+            d[0] = (int)(tq1 - tq0); d[1] = (int)(tq2 - tq1); d[2] = (int)(tq3 - tq2); d[3] = steps;
+        }
+    }
+#endif
 }
 
 // ---------------------------------------------------------------------------------------------
