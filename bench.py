@@ -12,8 +12,7 @@ order, positions, packing) run once before it, as in the paper.
 
 Prints ONE JSON line.  `value` = total int8 ops of the K timed steps / wall time (TOPS).
 `roofline` covers the GEMM kernel (the only kernel in the timed region): algorithmic ops per launch
-= 2*M*N*K, average launch duration from HIP events recorded around every launch of the timed
-region.  `cpu_baseline` times the CPU oracle on a bounded row sample of the same workload.
+= 2*M*N*K, average launch duration = HIP-event time of the timed region / launches in it.  `cpu_baseline` times the CPU oracle on a bounded row sample of the same workload.
 """
 from __future__ import annotations
 
@@ -55,8 +54,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--layer", default="fc1", choices=["fc1", "fc2"])
     ap.add_argument("--out", default="q", choices=["q", "y", "acc"], help="epilogue output written in the timed region")
-    ap.add_argument("--cpu-rows", type=int, default=768, help="rows of the workload the CPU oracle is timed on (0: skip)")
-    ap.add_argument("--no-events", action="store_true", help="do not record per-launch events in the timed region")
+    ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the workload the CPU oracle is timed on (0: skip)")
+    ap.add_argument("--eager", action="store_true", help="launch from Python instead of replaying a captured HIP graph")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed region run one plain device copy of this many MiB (reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -96,28 +95,60 @@ def main():
     bufs = {args.out: torch.empty((M, N), dtype=dt, device=dev)}
     out_bytes = 1 if args.out == "q" else 4
 
-    def one_step(events=None):
-        for i, r in enumerate(RATIOS):
-            fq.flexiq_set_ratio(layer, r)
-            if events is not None:
-                events[i][0].record()
+    def one_step():
+        for r in RATIOS:
+            fq.flexiq_set_ratio(layer, r)      # O(1) host-side switch; the value travels as a kernel argument
             fq.flexiq_mixed_gemm(layer, Xq, out_scale=out_scale, bufs=bufs, **want)
-            if events is not None:
-                events[i][1].record()
 
-    for _ in range(args.warmup):
+    for _ in range(2):
         one_step()
     torch.cuda.synchronize()
+    # One step (the ratio sweep) is captured once into a HIP graph and replayed: launch-bound Python
+    # overhead stays out of the device timeline.  --eager launches from Python instead.
+    step_graph = None
+    if not args.eager:
+        step_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(step_graph):
+            one_step()
+    run_step = step_graph.replay if step_graph is not None else one_step
 
-    use_ev = not args.no_events
-    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in RATIOS]
-           for _ in range(args.steps)] if use_ev else None
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for s in range(args.steps):
-        one_step(evs[s] if use_ev else None)
+    e0.record()
+    for _ in range(args.steps):
+        run_step()
+    e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t1
+    dev_us = e0.elapsed_time(e1) * 1e3          # HIP events on the launch stream around the timed region
+
+    # per-ratio launch times (outside the timed region): 10 launches per graph, median of 7 replays
+    per_r_us = {}
+    for r in RATIOS:
+        fq.flexiq_set_ratio(layer, r)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(10):
+                fq.flexiq_mixed_gemm(layer, Xq, out_scale=out_scale, bufs=bufs, **want)
+        g.replay()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(7):
+            a0 = torch.cuda.Event(enable_timing=True)
+            a1 = torch.cuda.Event(enable_timing=True)
+            a0.record()
+            g.replay()
+            a1.record()
+            torch.cuda.synchronize()
+            ts.append(a0.elapsed_time(a1) * 1e3 / 10)
+        per_r_us[r] = float(np.median(ts))
+        del g
 
     if args.calib_copy_mib > 0:
         src = torch.empty(args.calib_copy_mib << 20, dtype=torch.int8, device=dev)
@@ -132,18 +163,12 @@ def main():
     ops_step = ops_call * len(RATIOS)
     value = ops_step * args.steps / wall / 1e12
     per_r = []
-    avg_us = None
-    if use_ev:
-        tot = 0.0
-        for i, r in enumerate(RATIOS):
-            ts = np.array([evs[s][i][0].elapsed_time(evs[s][i][1]) for s in range(args.steps)]) * 1e3  # us
-            tot += ts.sum()
-            med = float(np.median(ts))
-            per_r.append({"r": r, "us_median": round(med, 2), "us_mean": round(float(ts.mean()), 2),
-                          "tops": round(ops_call / med / 1e6, 1),
-                          "frac_int8_mfma_peak": round(ops_call / med / 1e6 / INT8_MFMA_PEAK_TOPS, 4),
-                          "algorithmic_GBs": round(algorithmic_bytes(M, N, K, r, out_bytes) / med / 1e3, 1)})
-        avg_us = tot / (args.steps * len(RATIOS))
+    for r in RATIOS:
+        us = per_r_us[r]
+        per_r.append({"r": r, "us": round(us, 2), "tops": round(ops_call / us / 1e6, 1),
+                      "frac_int8_mfma_peak": round(ops_call / us / 1e6 / INT8_MFMA_PEAK_TOPS, 4),
+                      "algorithmic_GBs": round(algorithmic_bytes(M, N, K, r, out_bytes) / us / 1e3, 1)})
+    avg_us = dev_us / (args.steps * len(RATIOS))
     achieved = ops_call / avg_us / 1e6 if avg_us else value
     roofline = {"bound": "mfma", "kernel": "flexiq::k_mixed (int8 MFMA mixed GEMM)", "achieved": round(achieved, 1),
                 "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
