@@ -32,9 +32,10 @@ INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix peak, 5.0 POP/s
 HBM_PEAK_GBS = 8000.0
 RATIOS = (0.0, 0.25, 0.5, 0.75, 1.0)
 
-# HBM bytes per launch of the GEMM kernel on this workload from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (see profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# Bytes per launch of the GEMM kernel on the default workload (fc1, int8 output) measured with
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the readings of a 256 MiB device copy (fetch x2.0,
+# write x1.0): median fetch 22.2 MB + write 19.4 MB.  See profiles/k_mixed_vitb_fc1_hbm_traffic.txt.
+MEASURED_TRAFFIC_BYTES = {("fc1", "q"): 41.6e6}
 
 
 def log(*a):
@@ -173,7 +174,7 @@ def main():
     roofline = {"bound": "mfma", "kernel": "flexiq::k_mixed (int8 MFMA mixed GEMM)", "achieved": round(achieved, 1),
                 "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
                 "avg_launch_us": round(avg_us, 2) if avg_us else None,
-                "ops_per_launch": ops_call, "traffic": MEASURED_TRAFFIC_BYTES}
+                "ops_per_launch": ops_call, "traffic": MEASURED_TRAFFIC_BYTES.get((args.layer, args.out))}
 
     # ---- CPU oracle on a bounded row sample (rank 0, N = 1 only), with a parity check on those rows
     cpu = None
