@@ -151,8 +151,10 @@ enum StepMode { kMode88 = 0, kMode44 = 1, kMode48 = 2, kModeNone = 3 };
 
 #define FQ_SB() __builtin_amdgcn_sched_barrier(0)
 
+// Tiles with at most 128 accumulator registers per lane are compiled for two blocks per CU (two waves per
+// SIMD): one block's prologue, epilogue and 4-bit VALU work then overlap the other's matrix work.
 template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV>
-__global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
+__global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const GemmParams p)
 {
     using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
     constexpr int NT = C_::NT, BM = C_::BM, BN = C_::BN, XPS = C_::XPS, WPS = C_::WPS, STAGE = C_::STAGE;
@@ -343,25 +345,43 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
         amask = 0x01010101u * ((0xFFu << sa) & 0xFFu);
     };
     // registers -> LDS stage, chunk i of the staged tile, bit-lowering / expanding the 4-bit units
+    // registers -> LDS stage for chunk i of the staged tile.  The VALU work of the 4-bit units (bit-lowering
+    // of activations, expansion of 4-bit weight codes) is cut into four pieces per chunk, lmicro(i, 0..3),
+    // so that it can be spread over the MFMA stream and co-issue with it; lstore(i) then writes the chunk.
+    uint32_t wexp[8];   // expanded weights of the 4-bit chunk in progress
+    auto lmicro = [&](int i, int k, int mode) {
+        if (i < XL) {
+            if (mode == kMode44) {
+                sr[i][k] = (int)lower4((uint32_t)sr[i][k], lo2, hi2, amask);
+            } else if (mode == kMode48) {
+                const int l = (int)lower4((uint32_t)sr[i][k], lo2, hi2, amask);
+                sr[i][k] = (xq >> 1) == 0 ? l : sr[i][k];
+            }
+        } else {
+            const int h = (i - XL) / WL8, j = (i - XL) % WL8;
+            const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
+            if (four && j < WL4) {
+                const int sw = wsh[h][j];
+                const short t = (short)(4 - sw);
+                const uint32_t mask = 0x01010101u * ((0xFFu << sw) & 0xFFu);
+                const uint32_t w = (uint32_t)sr[i][k];
+                wexp[2 * k] = expand_hi(w << 4, t, mask);  // low halves: channels 8k .. 8k+3
+                wexp[2 * k + 1] = expand_hi(w, t, mask);   // high halves: channels 8k+4 .. 8k+7
+            }
+        }
+    };
     auto lstore = [&](int i, int mode, unsigned char *stage) {
         if (i < XL) {
-            v4i v = sr[i];
-            if (mode == kMode44) {
-                v = lower16v(v, lo2, hi2, amask);
-            } else if (mode == kMode48) {
-                const v4i l = lower16v(v, lo2, hi2, amask);
-                v = (xq >> 1) == 0 ? l : v;
-            }
-            *reinterpret_cast<v4i *>(stage + x_lds + i * (NT / 4) * 16) = v;
+            *reinterpret_cast<v4i *>(stage + x_lds + i * (NT / 4) * 16) = sr[i];
         } else {
             const int h = (i - XL) / WL8, j = (i - XL) % WL8;
             const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
             if (four) {
                 if (j < WL4 && (BN % NT == 0 || tid + j * NT < BN)) {
-                    v4i a, b;
-                    expand32(sr[i], wsh[h][j], a, b);
-                    *reinterpret_cast<v4i *>(stage + (2 * h) * WPS + w4lds[j]) = a;
-                    *reinterpret_cast<v4i *>(stage + (2 * h + 1) * WPS + w4lds[j]) = b;
+                    *reinterpret_cast<v4i *>(stage + (2 * h) * WPS + w4lds[j]) =
+                        (v4i){(int)wexp[0], (int)wexp[1], (int)wexp[2], (int)wexp[3]};
+                    *reinterpret_cast<v4i *>(stage + (2 * h + 1) * WPS + w4lds[j]) =
+                        (v4i){(int)wexp[4], (int)wexp[5], (int)wexp[6], (int)wexp[7]};
                 }
             } else {
                 if ((2 * BN) % NT == 0 || tid + j * NT < 2 * BN)
@@ -404,7 +424,11 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
             if (t < 2) {
                 if (mode != kMode88) lower_setup(st_c64);
 #pragma unroll
-                for (int i = 0; i < NS; ++i) lstore(i, mode, lds + t * STAGE);
+                for (int i = 0; i < NS; ++i) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) lmicro(i, k, mode);
+                    lstore(i, mode, lds + t * STAGE);
+                }
                 mode_staged = kModeNone;
             }
         }
@@ -453,14 +477,18 @@ __global__ __launch_bounds__(256) void k_mixed(const GemmParams p)
                             else if (h1) fread(fA, forder(k), nx1, 0);
                             FQ_SB();
                         }
-                    // staging chunk j: store at step slot (2j)*2NMF/(2NS), load right after
+                    // staging chunk i: four pieces of VALU work, the LDS store, then the global load of the
+                    // next tile's chunk i into the same registers; position t = 6 i + k at step slot t*2NMF/(6 NS)
 #pragma unroll
-                    for (int j = 0; j < 2 * NS; ++j)
-                        if (j * (2 * NMF) / (2 * NS) == g) {
-                            if ((j & 1) == 0) {
-                                if (ma != kModeNone) lstore(j / 2, ma, nx2);
+                    for (int t = 0; t < 6 * NS; ++t)
+                        if (t * (2 * NMF) / (6 * NS) == g) {
+                            const int i = t / 6, k = t % 6;
+                            if (k < 4) {
+                                if (ma == kMode44 || ma == kMode48) lmicro(i, k, ma);
+                            } else if (k == 4) {
+                                if (ma != kModeNone) lstore(i, ma, nx2);
                             } else {
-                                if (mb != kModeNone) gload(j / 2, mb);
+                                if (mb != kModeNone) gload(i, mb);
                             }
                             FQ_SB();
                         }
