@@ -80,8 +80,10 @@ int flexiq_layer_info(const flexiq_layer *layer, const int32_t **perm, const uin
 /* Copies the handle's device buffers back for inspection (tests: "no repacking between calls").
  *   w8 : host int8  [N][R*S][C]    permuted 8-bit weights, decoded from the tiled device layout
  *   w4 : host uint8 [N][R*S][C/2]  4-bit codes of ALL groups, channel c in byte c/2 (low half for even c)
- * Either may be NULL.  Synchronises the device. */
-int flexiq_layer_dump(const flexiq_layer *layer, int8_t *w8, uint8_t *w4);
+ *   w4x: host int8  [N][R*S][C]    the copy of those codes that the matrix kernel streams for compute-bound
+ *                                  shapes: every code put back at its extraction position, code << w_shift
+ * Any may be NULL.  Synchronises the device. */
+int flexiq_layer_dump(const flexiq_layer *layer, int8_t *w8, uint8_t *w4, int8_t *w4x);
 
 /* Run-time ratio switch (Section 7): sets max_4bit_ch = group_size * ceil(r * G), the number of
  * leading stored channels computed at 4 bits.  Host-only, O(1): one integer in the handle, passed to

@@ -8,7 +8,8 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libflexiq.so")
+# FLEXIQ_LIB names another build of the same library (e.g. an instrumented one); there is no non-HIP path
+LIB_PATH = os.environ.get("FLEXIQ_LIB") or os.path.join(_HERE, "libflexiq.so")
 _lib = None
 
 
@@ -48,7 +49,7 @@ def load():
     L.flexiq_quantize_pack.argtypes = [C.POINTER(_PackDesc), C.POINTER(C.c_void_p)]
     L.flexiq_layer_free.argtypes = [C.c_void_p]
     L.flexiq_layer_info.argtypes = [C.c_void_p] + [C.POINTER(C.c_void_p)] * 4 + [C.POINTER(C.c_int32)] * 2
-    L.flexiq_layer_dump.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    L.flexiq_layer_dump.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.flexiq_set_ratio.argtypes = [C.c_void_p, C.c_float, C.POINTER(C.c_int32)]
     L.flexiq_quantize_act.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p]
     L.flexiq_bitlower.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_int,
@@ -58,6 +59,7 @@ def load():
     L.flexiq_mixed_conv_implicit.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                              C.c_int32, C.POINTER(_Out), C.c_void_p]
     L.flexiq_debug_force_tile.argtypes = [C.c_int]
+    L.flexiq_debug_force_packed4.argtypes = [C.c_int]
     for name in exported_symbols():
         getattr(L, name)
     _lib = L
@@ -137,8 +139,9 @@ def flexiq_layer_dump(layer: Layer):
     T = layer.R * layer.S
     w8 = np.empty((layer.N, T, layer.C), np.int8)
     w4 = np.empty((layer.N, T, layer.C // 2), np.uint8)
-    _check(L.flexiq_layer_dump(layer._h, w8.ctypes.data, w4.ctypes.data))
-    return w8, w4
+    w4x = np.empty((layer.N, T, layer.C), np.int8)
+    _check(L.flexiq_layer_dump(layer._h, w8.ctypes.data, w4.ctypes.data, w4x.ctypes.data))
+    return w8, w4, w4x
 
 
 def flexiq_set_ratio(layer: Layer, r: float) -> int:
@@ -217,3 +220,8 @@ def debug_force_tile(index: int) -> int:
     if rc < 0:
         _check(rc)
     return rc
+
+
+def debug_force_packed4(mode: int) -> None:
+    """Where the GEMM kernel takes the weights of 4-bit units from: 1 = packed codes, 0 = expanded copy, -1 = automatic."""
+    _check(load().flexiq_debug_force_packed4(mode))

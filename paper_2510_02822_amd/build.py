@@ -9,7 +9,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflexiq.so")
-SOURCES = ["pack.hip", "gemm.hip"]
+NUM_TILE_SHAPES = 8
+# (source, object, extra flags): the kernel of every tile shape is a translation unit of its own
+UNITS = [("pack.hip", "pack.o", []), ("gemm.hip", "gemm.o", [])] + \
+        [("mixed_tile.hip", "mixed_tile_%d.o" % i, ["-DFQ_TILE=%d" % i]) for i in range(NUM_TILE_SHAPES)]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -18,9 +21,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
 def build(verbose: bool = False, extra=()) -> str:
     objs = []
     procs = []
-    for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    for src, o, defs in UNITS:
+        obj = os.path.join(CSRC, o)
+        cmd = ["hipcc", *FLAGS, *defs, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     for cmd, pr in procs:

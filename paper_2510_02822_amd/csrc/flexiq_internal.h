@@ -36,6 +36,10 @@ void set_hip_error(hipError_t e, const char *what);
 //   w4     uint8 [U][Npad][16]      4-bit codes of the same 32 channels: dword e (0..3) of a row
 //                                   carries channels 8e..8e+3 in the low halves of its bytes 0..3
 //                                   and channels 8e+4..8e+7 in the high halves
+//   w4x    int8  [U][2][Npad][16]   the same 4-bit codes, each put back at its extraction position as an
+//                                   int8 value (code << wshift), in the layout of w8: the copy the matrix
+//                                   kernel streams when the problem is compute-bound, so that no expansion
+//                                   work shares the vector ALU with the matrix pipe
 //   wshift uint8 [G][Npad]          weight extraction position per (group, output channel)
 //   ashift int32 [G+1]              activation extraction position per group (+1 entry for the pad unit)
 //   cs     fp32  [Npad]             x_scale * w_scale[n]
@@ -52,6 +56,7 @@ struct flexiq_layer {
     int device;
     int8_t *d_w8;
     uint8_t *d_w4;
+    int8_t *d_w4x;
     uint8_t *d_wshift;
     int32_t *d_ashift;
     float *d_cs;

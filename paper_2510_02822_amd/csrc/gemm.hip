@@ -1,677 +1,30 @@
-// Mixed 4-bit / 8-bit GEMM and implicit-GEMM convolution for gfx950 (Section 7 of the paper,
-// re-designed for CDNA4).
-//
-// gfx950 has no 4-bit integer matrix instruction, so a 4-bit channel group cannot run on a faster
-// matrix path than an 8-bit one.  The group's contribution
-//     2^(sa+sw) * sum_k L(x,sa) * L(w,sw)   =   sum_k (L(x,sa) << sa) * (L(w,sw) << sw)
-// is instead formed by putting each bit-lowered operand back at its extraction position as an int8
-// value (both factors fit: |L << s| <= 128) and feeding the same int8 MFMA and the same int32
-// accumulator as the 8-bit groups: bit-exact by distributivity, and the separate shift-and-accumulate
-// stage of the paper's CUDA kernel disappears.  What the 4-bit groups save here is weight bytes (they
-// are streamed from the packed 4-bit copy), not matrix cycles.
-//
-// Work decomposition: a block of four waves (one per SIMD) owns a BM x BN output tile; the reduction
-// runs in K-steps of 64 elements (two 32-channel units, each independently 4-bit or 8-bit), each
-// K-step being two k-halves of v_mfma_i32_32x32x32_i8 (a single wave per SIMD keeps the matrix pipe
-// full with this instruction shape; the 16x16x64 shape needs two).  Tiles travel
-//     global --buffer_load--> registers --(bit-lower / expand)--> LDS ring of three stages --> MFMA fragments,
-// as four 16-byte "k-planes" per stage so that a fragment read is 32 lanes x 16 contiguous bytes.
-// The loop is software-pipelined by hand: every MFMA is followed by at most a few memory or VALU
-// instructions (fragment reads for the next k-half into a second register set, LDS stores of the tile
-// two steps ahead, global loads of the tile three steps ahead), pinned in place with scheduling
-// fences, so that loads are spread evenly over the texture-address unit and no wave waits on LDS.
-// The MFMA "A" operand is the weight fragment and "B" the activation fragment, so a lane ends up with
-// four consecutive output channels of one output row.
+// Host side of the mixed GEMM / implicit-GEMM convolution (Section 7 of the paper): tile-shape choice,
+// launch, and the C entry points.  The kernel itself is in mixed_kernel.h.
 #include <mutex>
-#include <type_traits>
 
-#include "flexiq_internal.h"
+#include "mixed_kernel.h"
 
 namespace flexiq {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef short v2s __attribute__((ext_vector_type(2)));
-
-struct GemmParams {
-    const int8_t *X;
-    const int8_t *W8;
-    const uint8_t *W4;
-    const uint8_t *wshift;
-    const int32_t *ashift;
-    const float *cs;
-    const float *bias;
-    int32_t *acc;
-    float *y;
-    int8_t *q;
-    float r_out;     // 1 / out_scale
-    int64_t M;       // output rows (tokens, or B*Ho*Wo output pixels)
-    int32_t N, Npad, C;
-    int32_t K4;      // max_4bit_ch: leading stored channels computed at 4 bits
-    int32_t gs_shift;  // log2(group_size / 32): unit c32 belongs to group c32 >> gs_shift
-    int32_t G;       // channel groups
-    int32_t U;       // units in the reduction (even per tap), CU = C/32 per tap
-    int32_t CU;
-    int32_t T;       // filter taps
-    int32_t tiles_m, tiles_n;
-    // convolution geometry (unused for the linear form)
-    int32_t H, Wd, Ho, Wo, S, stride, pad;
-};
-
-// clamp(v, -(8<<s), (8<<s)-1) & (0xFF << s) on the four int8 lanes of a dword: the bit-lowered value
-// put back at its position.  lo2/hi2 hold the bounds in the high byte of each 16-bit half.
-__device__ __forceinline__ uint32_t lower4(uint32_t d, v2s lo2, v2s hi2, uint32_t mask)
-{
-    v2s o = __builtin_bit_cast(v2s, d);           // odd bytes are the high bytes of the halves
-    v2s e = o << (short)8;                        // even bytes moved up
-    o = __builtin_elementwise_min(__builtin_elementwise_max(o, lo2), hi2);
-    e = __builtin_elementwise_min(__builtin_elementwise_max(e, lo2), hi2);
-    uint32_t r = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, o), __builtin_bit_cast(uint32_t, e), 0x07030501u);
-    return r & mask;
-}
-
-__device__ __forceinline__ v4i lower16(v4i x, int s)
-{
-    short lo = (short)((-(8 << s)) << 8);
-    short hi = (short)(((((8 << s) - 1) << 8) | 0xFF));
-    v2s lo2 = {lo, lo}, hi2 = {hi, hi};
-    uint32_t mask = 0x01010101u * ((0xFFu << s) & 0xFFu);
-    v4i r;
-    r.x = (int)lower4((uint32_t)x.x, lo2, hi2, mask);
-    r.y = (int)lower4((uint32_t)x.y, lo2, hi2, mask);
-    r.z = (int)lower4((uint32_t)x.z, lo2, hi2, mask);
-    r.w = (int)lower4((uint32_t)x.w, lo2, hi2, mask);
-    return r;
-}
-
-// Four 4-bit codes sitting in the HIGH halves of the bytes of p -> four int8 values code << sw.
-// Each 16-bit half is shifted right arithmetically by t = 4 - sw with the wanted byte on top, which
-// sign-extends the code and leaves junk only in the low sw bits (cleared by mask) and the low byte.
-__device__ __forceinline__ uint32_t expand_hi(uint32_t p, short t, uint32_t mask)
-{
-    v2s o = __builtin_bit_cast(v2s, p);
-    v2s e = o << (short)8;
-    o = o >> t;
-    e = e >> t;
-    uint32_t r = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, o), __builtin_bit_cast(uint32_t, e), 0x07030501u);
-    return r & mask;
-}
-
-// 16 bytes of 4-bit codes (32 channels of one output channel) -> 32 int8 values at position sw.
-__device__ __forceinline__ void expand32(v4i p, int sw, v4i &first16, v4i &second16)
-{
-    short t = (short)(4 - sw);
-    uint32_t mask = 0x01010101u * ((0xFFu << sw) & 0xFFu);
-    uint32_t w[4] = {(uint32_t)p.x, (uint32_t)p.y, (uint32_t)p.z, (uint32_t)p.w};
-    uint32_t o[8];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        o[2 * e] = expand_hi(w[e] << 4, t, mask);  // low halves: channels 8e .. 8e+3
-        o[2 * e + 1] = expand_hi(w[e], t, mask);   // high halves: channels 8e+4 .. 8e+7
-    }
-    first16 = (v4i){(int)o[0], (int)o[1], (int)o[2], (int)o[3]};
-    second16 = (v4i){(int)o[4], (int)o[5], (int)o[6], (int)o[7]};
-}
-
-
-// clamp + mask with a per-lane position (the two units of a K-step may have different positions)
-__device__ __forceinline__ v4i lower16v(v4i x, v2s lo2, v2s hi2, uint32_t mask)
-{
-    v4i r;
-    r.x = (int)lower4((uint32_t)x.x, lo2, hi2, mask);
-    r.y = (int)lower4((uint32_t)x.y, lo2, hi2, mask);
-    r.z = (int)lower4((uint32_t)x.z, lo2, hi2, mask);
-    r.w = (int)lower4((uint32_t)x.w, lo2, hi2, mask);
-    return r;
-}
-
-template <int WAVES_M, int WAVES_N, int TM, int TN>
-struct Cfg {
-    static_assert(WAVES_M * WAVES_N == 4, "four waves per block");
-    static constexpr int NT = 256;
-    static constexpr int BM = WAVES_M * TM * 32;
-    static constexpr int BN = WAVES_N * TN * 32;
-    static constexpr int XL = (BM * 4 + NT - 1) / NT;   // 16-byte activation chunks per thread per K-step
-    static constexpr int WL8 = (BN * 2 + NT - 1) / NT;  // 16-byte chunks per thread per 8-bit unit
-    static constexpr int WL4 = (BN + NT - 1) / NT;      // 16-byte chunks per thread per 4-bit unit
-    static constexpr int NS = XL + 2 * WL8;             // staging registers (x4 dwords) per thread
-    static constexpr int XROWS = XL * (NT / 4);         // rows staged per K-step (>= BM; the excess reads as zero)
-    static constexpr int XPS = (XROWS + 2) * 16;        // bytes per activation k-plane (+2 chunks staggers the planes over the banks)
-    static constexpr int WPS = (BN + 2) * 16;
-    static constexpr int STAGE = 4 * XPS + 4 * WPS;
-    static constexpr int NSTAGE = 3;
-    static constexpr int QSTRIDE = BN + 16;             // row stride of the int8 output tile staged in LDS
-    static constexpr int TABLE = 640 + 2 * BN * 4;      // activation positions of up to 160 groups; scale and bias of the tile's columns
-    static constexpr int RING = NSTAGE * STAGE;
-    static constexpr int LDS_BYTES = (RING > BM * QSTRIDE ? RING : BM * QSTRIDE) + TABLE;
-};
-
-// How the two 32-channel units of a K-step are staged.
-enum StepMode { kMode88 = 0, kMode44 = 1, kMode48 = 2, kModeNone = 3 };
-
-#define FQ_SB() __builtin_amdgcn_sched_barrier(0)
-
-// Tiles with at most 128 accumulator registers per lane are compiled for two blocks per CU (two waves per
-// SIMD): one block's prologue, epilogue and 4-bit VALU work then overlap the other's matrix work.
-template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV>
-__global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const GemmParams p)
-{
-    using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
-    constexpr int NT = C_::NT, BM = C_::BM, BN = C_::BN, XPS = C_::XPS, WPS = C_::WPS, STAGE = C_::STAGE;
-    constexpr int XL = C_::XL, WL8 = C_::WL8, WL4 = C_::WL4, NS = C_::NS;
-    constexpr int NF = TM + TN;   // fragments per k-half
-    constexpr int NMF = TM * TN;  // MFMAs per k-half
-    extern __shared__ __align__(16) unsigned char lds[];
-    unsigned char *const sa_tab = lds + (C_::LDS_BYTES - C_::TABLE);
-    float *const cs_tab = reinterpret_cast<float *>(sa_tab + 640);  // [BN] scales, then [BN] biases
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-#ifdef FLEXIQ_TIMING
-    long long tq0 = __builtin_readcyclecounter();
-#endif
-
-    // ---- block -> tile.  Consecutive block ids land on different XCDs (8 of them, each with its own
-    // L2); renumber so that the blocks sharing an XCD walk neighbouring tiles, then sweep bands of 8
-    // tile rows with the tile column varying slowest inside a band (weights stay L2-resident).
-    int tile_m, tile_n;
-    {
-        const int nb = gridDim.x;
-        int b = blockIdx.x;
-        if (nb % 8 == 0) b = (b % 8) * (nb / 8) + b / 8;
-        constexpr int GMB = 8;
-        const int band = b / (GMB * p.tiles_n);
-        const int rows_in_band = min(GMB, p.tiles_m - band * GMB);
-        const int r = b - band * GMB * p.tiles_n;
-        // the division runs on the vector ALU; tell the compiler the result is wave-uniform
-        tile_m = __builtin_amdgcn_readfirstlane(band * GMB + r % rows_in_band);
-        tile_n = __builtin_amdgcn_readfirstlane(r / rows_in_band);
-    }
-    const int64_t m0 = (int64_t)tile_m * BM;
-    const int n0 = tile_n * BN;
-    const int rows_valid = (int)min((int64_t)BM, p.M - m0);
-
-    // ---- buffer windows: reads past a window return zero, which is what rows beyond M, padded
-    // pixels and dummy staging rows need
-    constexpr int kRsrcFlags = 0x00020000;
-    const __amdgpu_buffer_rsrc_t rw8 =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(p.W8 + (int64_t)n0 * 16), 0, p.U * 32 * p.Npad - n0 * 16, kRsrcFlags);
-    const __amdgpu_buffer_rsrc_t rw4 =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(p.W4 + (int64_t)n0 * 16), 0, p.U * 16 * p.Npad - n0 * 16, kRsrcFlags);
-    const __amdgpu_buffer_rsrc_t rws =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(p.wshift + n0), 0, p.G * p.Npad - n0, kRsrcFlags);
-    const int8_t *xbase;  // origin and size of the activation window of this block
-    int xwin;
-    const int xq = tid & 3;   // k-plane of this thread's activation chunks; unit xq >> 1
-    int xvoff[XL];            // linear: byte offset inside the window; conv: xq * 16
-    int xh0[XL], xw0[XL], xpix[XL];  // conv: top-left input coordinate, pixel index of the image origin (-1: no row)
-    if (CONV) {
-        const int64_t hw_out = (int64_t)p.Ho * p.Wo;
-        const int64_t img0 = m0 / hw_out;
-        const int64_t img_bytes = (int64_t)p.H * p.Wd * p.C;
-        const int64_t imgs_left = (p.M / hw_out) - img0;
-        const int64_t win = min(imgs_left * img_bytes, (int64_t)0x7fffffff);
-        xbase = p.X + img0 * img_bytes;
-        xwin = (int)win;
-#pragma unroll
-        for (int j = 0; j < XL; ++j) {
-            const int row = (tid >> 2) + j * (NT / 4);
-            const bool ok = row < rows_valid;
-            const int64_t mm = ok ? m0 + row : m0;
-            const int wo = (int)(mm % p.Wo);
-            const int ho = (int)((mm / p.Wo) % p.Ho);
-            const int b = (int)(mm / hw_out - img0);
-            xpix[j] = ok ? b * p.H * p.Wd : -1;
-            xh0[j] = ho * p.stride - p.pad;
-            xw0[j] = wo * p.stride - p.pad;
-            xvoff[j] = xq * 16;
-        }
-    } else {
-        xbase = p.X + m0 * p.C;
-        xwin = rows_valid * p.C;
-#pragma unroll
-        for (int j = 0; j < XL; ++j) {
-            const int row = (tid >> 2) + j * (NT / 4);
-            xvoff[j] = row * p.C + xq * 16;  // rows >= rows_valid fall outside the window: zeros
-            xh0[j] = xw0[j] = xpix[j] = 0;
-        }
-    }
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)xbase, 0, xwin, kRsrcFlags);
-    const int x_lds = xq * XPS + (tid >> 2) * 16;
-    int w8voff[WL8], w8lds[WL8];
-#pragma unroll
-    for (int j = 0; j < WL8; ++j) {
-        const int i = tid + j * NT;
-        const int q2 = i / BN, row = i - q2 * BN;
-        w8voff[j] = (q2 * p.Npad + row) * 16;
-        w8lds[j] = 4 * XPS + q2 * WPS + row * 16;
-    }
-    int w4voff[WL4], w4lds[WL4];
-#pragma unroll
-    for (int j = 0; j < WL4; ++j) {
-        const int row = tid + j * NT;
-        w4voff[j] = row * 16;
-        w4lds[j] = 4 * XPS + row * 16;
-    }
-
-    // activation positions of all groups into LDS (read per step with ordinary LDS loads, which keeps
-    // scalar-memory waits out of the pipelined loop)
-    for (int g = tid; g <= p.G; g += NT) reinterpret_cast<int *>(sa_tab)[g] = p.ashift[g];
-    for (int c = tid; c < BN; c += NT) {  // cs/bias are padded to Npad >= n0 + BN
-        cs_tab[c] = p.cs[n0 + c];
-        cs_tab[BN + c] = p.bias[n0 + c];
-    }
-
-    // ---- K-step enumeration, phase-major: all-4-bit steps, then mixed steps, then all-8-bit steps;
-    // the iterator points at the next tile to LOAD.  Scalar state only.
-    const int SP = (p.CU + 1) >> 1;           // steps per tap
-    const int n4 = p.K4 >> 6;                 // full 4-bit steps per tap
-    const int mixed = (p.K4 & 63) ? 1 : 0;    // one step per tap with a 4-bit and an 8-bit unit
-    const int steps = p.T * SP;
-    // Phase p covers c64 in [pb(p), pe(p)) of every tap; pn(p) is the next non-empty phase (3 = done).
-    // The update is written with selects only: the steady-state loops must stay single basic blocks
-    // so that the compiler can count outstanding loads exactly across the back edge.
-    auto pb = [&](int ph) { return ph == 0 ? 0 : (ph == 1 ? n4 : n4 + mixed); };
-    auto pe = [&](int ph) { return ph == 0 ? n4 : (ph == 1 ? n4 + mixed : SP); };
-    const int ne0 = n4 > 0, ne1 = mixed > 0, ne2 = n4 + mixed < SP;
-    const int first_phase = ne0 ? 0 : (ne1 ? 1 : (ne2 ? 2 : 3));
-    const int next1 = ne1 ? 1 : (ne2 ? 2 : 3), next2 = ne2 ? 2 : 3;
-    auto pn = [&](int ph) { return ph == 0 ? next1 : (ph == 1 ? next2 : 3); };
-    int it_phase = first_phase, it_tap = 0, it_dy = 0, it_dx = 0;
-    int it_c64 = first_phase < 3 ? pb(first_phase) : 0;
-    int it_b = it_c64, it_e = first_phase < 3 ? pe(first_phase) : 0;  // bounds of the current phase
-    auto advance = [&]() {
-        const int c = it_c64 + 1;
-        const bool wrap_c = c == it_e;                  // this tap's part of the phase is finished
-        const int dx1 = it_dx + 1;
-        const bool wrap_x = dx1 == p.S;
-        const int tap1 = it_tap + 1;
-        const bool wrap_t = wrap_c && tap1 == p.T;      // the phase is finished
-        const int ph = wrap_t ? pn(it_phase) : it_phase;
-        const int nb = wrap_t ? (ph < 3 ? pb(ph) : 0) : it_b;
-        const int ne = wrap_t ? (ph < 3 ? pe(ph) : 0) : it_e;
-        it_dy = wrap_t ? 0 : (wrap_c && wrap_x ? it_dy + 1 : it_dy);
-        it_dx = wrap_t ? 0 : (wrap_c ? (wrap_x ? 0 : dx1) : it_dx);
-        it_tap = wrap_t ? 0 : (wrap_c ? tap1 : it_tap);
-        it_c64 = wrap_c ? nb : c;
-        it_phase = ph;
-        it_b = nb;
-        it_e = ne;
-    };
-    auto it_mode = [&]() { return it_phase == 0 ? kMode44 : (it_phase == 1 ? kMode48 : (it_phase == 2 ? kMode88 : kModeNone)); };
-
-    // ---- staging registers and the descriptor of the tile they hold
-    v4i sr[NS];
-    int wsh[2][WL4];
-    int st_c64 = 0;   // c64 of the tile in the staging registers
-
-    // global -> registers, chunk i of the tile the iterator points at
-    auto gload = [&](int i, int mode) {
-        const int c64 = it_c64;
-        if (i < XL) {
-            if (CONV) {
-                const int hi = xh0[i] + it_dy, wi = xw0[i] + it_dx;
-                const bool ok = hi >= 0 && hi < p.H && wi >= 0 && wi < p.Wd && xpix[i] >= 0;
-                const int off = ok ? (xpix[i] + hi * p.Wd + wi) * p.C + xvoff[i] : (int)0x80000000;
-                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, c64 * 64, 0);
-            } else {
-                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, xvoff[i], c64 * 64, 0);
-            }
-        } else {
-            const int h = (i - XL) / WL8, j = (i - XL) % WL8;
-            const int u = it_tap * (2 * SP) + 2 * c64 + h;
-            const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
-            if (four) {
-                if (j < WL4) {
-                    const int g = (2 * c64 + h) >> p.gs_shift;
-                    sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw4, w4voff[j], u * 16 * p.Npad, 0);
-                    wsh[h][j] = __builtin_amdgcn_raw_buffer_load_b8(rws, w4voff[j] >> 4, g * p.Npad, 0);
-                }
-            } else {
-                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw8, w8voff[j], u * 32 * p.Npad, 0);
-            }
-        }
-    };
-    // per-step constants of the activation bit-lowering for this thread's unit (position from LDS)
-    v2s lo2, hi2;
-    uint32_t amask;
-    auto lower_setup = [&](int c64) {
-        const int sa = reinterpret_cast<const int *>(sa_tab)[(2 * c64 + (xq >> 1)) >> p.gs_shift];
-        const short lo = (short)((-(8 << sa)) << 8);
-        const short hi = (short)((((8 << sa) - 1) << 8) | 0xFF);
-        lo2 = (v2s){lo, lo};
-        hi2 = (v2s){hi, hi};
-        amask = 0x01010101u * ((0xFFu << sa) & 0xFFu);
-    };
-    // registers -> LDS stage, chunk i of the staged tile, bit-lowering / expanding the 4-bit units
-    // registers -> LDS stage for chunk i of the staged tile.  The VALU work of the 4-bit units (bit-lowering
-    // of activations, expansion of 4-bit weight codes) is cut into four pieces per chunk, lmicro(i, 0..3),
-    // so that it can be spread over the MFMA stream and co-issue with it; lstore(i) then writes the chunk.
-    uint32_t wexp[8];   // expanded weights of the 4-bit chunk in progress
-    auto lmicro = [&](int i, int k, int mode) {
-        if (i < XL) {
-            if (mode == kMode44) {
-                sr[i][k] = (int)lower4((uint32_t)sr[i][k], lo2, hi2, amask);
-            } else if (mode == kMode48) {
-                const int l = (int)lower4((uint32_t)sr[i][k], lo2, hi2, amask);
-                sr[i][k] = (xq >> 1) == 0 ? l : sr[i][k];
-            }
-        } else {
-            const int h = (i - XL) / WL8, j = (i - XL) % WL8;
-            const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
-            if (four && j < WL4) {
-                const int sw = wsh[h][j];
-                const short t = (short)(4 - sw);
-                const uint32_t mask = 0x01010101u * ((0xFFu << sw) & 0xFFu);
-                const uint32_t w = (uint32_t)sr[i][k];
-                wexp[2 * k] = expand_hi(w << 4, t, mask);  // low halves: channels 8k .. 8k+3
-                wexp[2 * k + 1] = expand_hi(w, t, mask);   // high halves: channels 8k+4 .. 8k+7
-            }
-        }
-    };
-    auto lstore = [&](int i, int mode, unsigned char *stage) {
-        if (i < XL) {
-            *reinterpret_cast<v4i *>(stage + x_lds + i * (NT / 4) * 16) = sr[i];
-        } else {
-            const int h = (i - XL) / WL8, j = (i - XL) % WL8;
-            const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
-            if (four) {
-                if (j < WL4 && (BN % NT == 0 || tid + j * NT < BN)) {
-                    *reinterpret_cast<v4i *>(stage + (2 * h) * WPS + w4lds[j]) =
-                        (v4i){(int)wexp[0], (int)wexp[1], (int)wexp[2], (int)wexp[3]};
-                    *reinterpret_cast<v4i *>(stage + (2 * h + 1) * WPS + w4lds[j]) =
-                        (v4i){(int)wexp[4], (int)wexp[5], (int)wexp[6], (int)wexp[7]};
-                }
-            } else {
-                if ((2 * BN) % NT == 0 || tid + j * NT < 2 * BN)
-                    *reinterpret_cast<v4i *>(stage + (2 * h) * WPS + w8lds[j]) = sr[i];
-            }
-        }
-    };
-
-    v16i acc[TN][TM];
-#pragma unroll
-    for (int a = 0; a < TN; ++a)
-#pragma unroll
-        for (int b = 0; b < TM; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
-
-    const int frag_half = lane >> 5, frag_row = lane & 31;
-    const int xs_frag = frag_half * XPS + (wm * TM * 32 + frag_row) * 16;
-    const int ws_frag = 4 * XPS + frag_half * WPS + (wn * TN * 32 + frag_row) * 16;
-    // fragments in order of need: w0, x0, w1..w(TN-1), x1..x(TM-1); f[0..TN) weights, f[TN..NF) activations
-    auto forder = [](int i) { return i == 0 ? 0 : (i == 1 ? TN : (i <= TN ? i - 1 : i)); };
-    auto fread = [&](v4i(&f)[NF], int i, const unsigned char *stage, int kh) {
-        if (i < TN) f[i] = *reinterpret_cast<const v4i *>(stage + ws_frag + kh * 2 * WPS + i * 512);
-        else f[i] = *reinterpret_cast<const v4i *>(stage + xs_frag + kh * 2 * XPS + (i - TN) * 512);
-    };
-    v4i fA[NF], fB[NF];
-
-    // ---- prologue: tiles 0 and 1 into stages 0 and 1, tile 2 into the staging registers
-    __syncthreads();  // position table visible
-    int mode_staged = kModeNone;   // mode of the tile in the staging registers
-#pragma unroll 1
-    for (int t = 0; t < 3; ++t) {
-        if (t < steps) {
-            const int mode = it_mode();
-            st_c64 = it_c64;
-            mode_staged = mode;
-#pragma unroll
-            for (int i = 0; i < NS; ++i) gload(i, mode);
-            advance();
-            if (t < 2) {
-                if (mode != kMode88) lower_setup(st_c64);
-#pragma unroll
-                for (int i = 0; i < NS; ++i) {
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) lmicro(i, k, mode);
-                    lstore(i, mode, lds + t * STAGE);
-                }
-                mode_staged = kModeNone;
-            }
-        }
-    }
-    __builtin_amdgcn_s_waitcnt(0xc07f);
-    __builtin_amdgcn_s_barrier();
-#pragma unroll
-    for (int i = 0; i < NF; ++i) fread(fA, i, lds, 0);
-
-#ifdef FLEXIQ_TIMING
-    long long tq1 = __builtin_readcyclecounter();
-#endif
-    // ---- main loop.  Step s computes tile s from stage s % 3 while storing tile s+2 (staged in
-    // registers during step s-1) into stage (s+2) % 3 and loading tile s+3 into the registers: store
-    // of chunk j, then load of chunk j, spread over the whole step.  `ma` is the mode of the staged
-    // tile (kModeNone: nothing to store), `mb` the mode of the tile to load (kModeNone: none left);
-    // both are compile-time constants in the steady-state loops and run-time values elsewhere.
-    int st0 = 0;  // stage of tile s
-    int s = 0;
-    auto step = [&](auto ma_, auto mb_, auto h1_) {
-        const int ma = ma_, mb = mb_;
-        const bool h1 = h1_;
-        const int st1 = st0 == 2 ? 0 : st0 + 1, st2 = st1 == 2 ? 0 : st1 + 1;
-        const unsigned char *cur = lds + st0 * STAGE;
-        const unsigned char *nx1 = lds + st1 * STAGE;
-        unsigned char *nx2 = lds + st2 * STAGE;
-        const int c64_store = st_c64;
-        if (ma == kMode44 || ma == kMode48) lower_setup(c64_store);
-        if (mb != kModeNone) st_c64 = it_c64;
-        FQ_SB();
-#pragma unroll
-        for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-            for (int b = 0; b < TM; ++b)
-#pragma unroll
-                for (int a = 0; a < TN; ++a) {
-                    const int slot = b * TN + a, g = kh * NMF + slot;
-                    if (kh == 0) acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fA[a], fA[TN + b], acc[a][b], 0, 0, 0);
-                    else acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fB[a], fB[TN + b], acc[a][b], 0, 0, 0);
-                    FQ_SB();
-                    // fragment read k of the other register set at slot k*NMF/NF of this k-half
-#pragma unroll
-                    for (int k = 0; k < NF; ++k)
-                        if (k * NMF / NF == slot) {
-                            if (kh == 0) fread(fB, forder(k), cur, 1);
-                            else if (h1) fread(fA, forder(k), nx1, 0);
-                            FQ_SB();
-                        }
-                    // staging chunk i: four pieces of VALU work, the LDS store, then the global load of the
-                    // next tile's chunk i into the same registers; position t = 6 i + k at step slot t*2NMF/(6 NS)
-#pragma unroll
-                    for (int t = 0; t < 6 * NS; ++t)
-                        if (t * (2 * NMF) / (6 * NS) == g) {
-                            const int i = t / 6, k = t % 6;
-                            if (k < 4) {
-                                if (ma == kMode44 || ma == kMode48) lmicro(i, k, ma);
-                            } else if (k == 4) {
-                                if (ma != kModeNone) lstore(i, ma, nx2);
-                            } else {
-                                if (mb != kModeNone) gload(i, mb);
-                            }
-                            FQ_SB();
-                        }
-                }
-        if (mb != kModeNone) advance();
-        __builtin_amdgcn_s_waitcnt(0xc07f);  // this wave's LDS stores and fragment reads are complete
-        __builtin_amdgcn_s_barrier();
-        FQ_SB();
-        st0 = st1;
-        ++s;
-        mode_staged = mb;
-    };
-    using M44 = std::integral_constant<int, kMode44>;
-    using M88 = std::integral_constant<int, kMode88>;
-    using MNone = std::integral_constant<int, kModeNone>;
-    using T_ = std::true_type;
-    using F_ = std::false_type;
-    // A sequence of loops in the order the cases occur (each may run zero times), so that every
-    // variant of the step body is straight-line code and the accumulators never pass through a
-    // run-time selection between code paths:
-    //   steady 4-bit | transitions (generic, run-time modes) | steady 8-bit | drain: store the last staged
-    //   tile without loading | last steps with nothing left to stage
-    // (Entering a steady-state loop with no load in flight lets the compiler count the loads of the loop
-    // itself exactly, instead of waiting for all of them before the first store of every step.)
-    __builtin_amdgcn_s_waitcnt(0x0070);
-    while (mode_staged == kMode44 && it_phase == 0) step(M44{}, M44{}, T_{});
-    while (s < steps && it_phase != 3 && !(mode_staged == kMode88 && it_phase == 2)) step(mode_staged, (int)it_mode(), s + 1 < steps);
-    __builtin_amdgcn_s_waitcnt(0x0070);
-    while (mode_staged == kMode88 && it_phase == 2) step(M88{}, M88{}, T_{});
-    while (s < steps && mode_staged == kMode88) step(M88{}, MNone{}, T_{});
-    while (s < steps && mode_staged == kMode44) step(M44{}, MNone{}, T_{});
-    while (s < steps && mode_staged != kModeNone) step(mode_staged, (int)kModeNone, s + 1 < steps);
-    while (s + 1 < steps) step(MNone{}, MNone{}, T_{});
-    while (s < steps) step(MNone{}, MNone{}, F_{});
-
-#ifdef FLEXIQ_TIMING
-    long long tq2 = __builtin_readcyclecounter();
-#endif
-    // ---- epilogue.  Lane holds output row m = 32 b + (lane & 31) and, per accumulator quad g, the four
-    // consecutive output channels n = 32 a + 8 g + 4 (lane >> 5) + i.  The body is instantiated with
-    // compile-time output flags for the common cases (int8 only; fp32 and/or int32 only) and once
-    // with run-time flags for everything else (ragged N, several outputs at once).
-#ifdef FLEXIQ_TIMING
-    const bool want_q = p.q != nullptr, want_y = p.y != nullptr, want_acc = false;
-#else
-    const bool want_q = p.q != nullptr, want_y = p.y != nullptr, want_acc = p.acc != nullptr;
-#endif
-    const bool n_vec = (p.N & 3) == 0;
-    const bool q_lds = want_q && (p.N & 15) == 0;   // int8 tile through LDS: 16-byte row-contiguous stores
-    constexpr int QS = C_::QSTRIDE;
-    auto epilogue = [&](auto wq_, auto wy_, auto wa_, auto nv_, auto ql_) {
-        const bool wq = wq_, wy = wy_, wa = wa_, nv = nv_, ql = ql_;
-#pragma unroll
-        for (int a = 0; a < TN; ++a) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int nl = (wn * TN + a) * 32 + 8 * g + 4 * frag_half;
-                const int n = n0 + nl;
-                const bool n_ok = n < p.N;
-                float csv[4], biv[4], mul[4], add[4];
-                {
-                    const float4 cs = *reinterpret_cast<const float4 *>(cs_tab + nl);
-                    const float4 bi = *reinterpret_cast<const float4 *>(cs_tab + BN + nl);
-                    csv[0] = cs.x; csv[1] = cs.y; csv[2] = cs.z; csv[3] = cs.w;
-                    biv[0] = bi.x; biv[1] = bi.y; biv[2] = bi.z; biv[3] = bi.w;
-                }
-                if (wq) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        mul[i] = csv[i] * p.r_out;
-                        add[i] = biv[i] * p.r_out;
-                    }
-                }
-#pragma unroll
-                for (int b = 0; b < TM; ++b) {
-                    const int ml = (wm * TM + b) * 32 + frag_row;
-                    const int64_t m = m0 + ml;
-                    const int iv[4] = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
-                    uint32_t qw = 0;
-                    if (wq) {
-                        uint32_t u[4];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            float t = __builtin_fmaf((float)iv[i], mul[i], add[i]);
-                            t = __builtin_amdgcn_fmed3f(t, -128.0f, 127.0f);
-                            u[i] = __builtin_bit_cast(uint32_t, t + 12582912.0f);  // 1.5 * 2^23: integer lands in the low bits
-                        }
-                        qw = __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu);
-                        if (ql) *reinterpret_cast<uint32_t *>(lds + ml * QS + nl) = qw;
-                    }
-                    if (!(wy || wa || (wq && !ql))) continue;   // nothing goes straight to global memory
-                    if (m >= p.M || !n_ok) continue;
-                    const int64_t o = m * p.N + n;
-                    if (nv) {
-                        if (wa) *reinterpret_cast<v4i *>(p.acc + o) = (v4i){iv[0], iv[1], iv[2], iv[3]};
-                        if (wy) {
-                            float4 y;
-                            y.x = __builtin_fmaf((float)iv[0], csv[0], biv[0]);
-                            y.y = __builtin_fmaf((float)iv[1], csv[1], biv[1]);
-                            y.z = __builtin_fmaf((float)iv[2], csv[2], biv[2]);
-                            y.w = __builtin_fmaf((float)iv[3], csv[3], biv[3]);
-                            *reinterpret_cast<float4 *>(p.y + o) = y;
-                        }
-                        if (wq && !ql) *reinterpret_cast<uint32_t *>(p.q + o) = qw;
-                    } else {
-                        for (int i = 0; i < 4 && n + i < p.N; ++i) {
-                            if (wa) p.acc[o + i] = iv[i];
-                            if (wy) p.y[o + i] = __builtin_fmaf((float)iv[i], csv[i], biv[i]);
-                            if (wq) p.q[o + i] = (int8_t)((qw >> (8 * i)) & 0xFF);
-                        }
-                    }
-                }
-            }
-        }
-    };
-    if (q_lds && !want_y && !want_acc) epilogue(T_{}, F_{}, F_{}, T_{}, T_{});
-    else if (n_vec && !want_q && want_y && !want_acc) epilogue(F_{}, T_{}, F_{}, T_{}, F_{});
-    else if (n_vec && !want_q && !want_y && want_acc) epilogue(F_{}, F_{}, T_{}, T_{}, F_{});
-    else epilogue(want_q, want_y, want_acc, n_vec, q_lds);
-    if (q_lds) {
-        __syncthreads();
-        constexpr int TPR = BN / 16;   // threads per tile row
-        constexpr int RPP = NT / TPR;  // rows per pass
-        const int c16 = tid % TPR, r0 = tid / TPR;
-#pragma unroll
-        for (int pass = 0; pass < (BM + RPP - 1) / RPP; ++pass) {
-            const int row = r0 + pass * RPP;
-            const int64_t m = m0 + row;
-            const int n = n0 + c16 * 16;
-            if (row < BM && m < p.M && n < p.N)
-                *reinterpret_cast<v4i *>(p.q + m * p.N + n) = *reinterpret_cast<const v4i *>(lds + row * QS + c16 * 16);
-        }
-    }
-#ifdef FLEXIQ_TIMING
-    {
-        long long tq3 = __builtin_readcyclecounter();
-        if (lane == 0 && p.acc) {
-            int *d = p.acc + ((int64_t)blockIdx.x * 4 + wave) * 4;
-            d[0] = (int)(tq1 - tq0); d[1] = (int)(tq2 - tq1); d[2] = (int)(tq3 - tq2); d[3] = steps;
-        }
-    }
-#endif
-}
 
 // ---------------------------------------------------------------------------------------------
 // Host side: tile-shape choice and launch
 // ---------------------------------------------------------------------------------------------
 
-typedef void (*kernel_fn)(const GemmParams);
-struct TileShape {
-    int BM, BN, lds;
-    int mfma_per_khalf;  // MFMAs per wave per k-half
-    double cyc_per_mfma; // measured cycles per MFMA slot in the steady-state loop (32 is the pipe's own time)
-    kernel_fn lin, conv;
-};
-
-template <int WAVES_M, int WAVES_N, int TM, int TN>
-static TileShape make_shape(double cyc)
-{
-    using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
-    static_assert(C_::NT == 256, "the launcher uses 256 threads");
-    return TileShape{C_::BM, C_::BN, C_::LDS_BYTES, TM * TN, cyc, k_mixed<WAVES_M, WAVES_N, TM, TN, false>,
-                     k_mixed<WAVES_M, WAVES_N, TM, TN, true>};
-}
-
 static const TileShape *shapes(int *count)
 {
-    static const TileShape tab[] = {
-        make_shape<2, 2, 4, 4>(40.0),  // 256 x 256
-        make_shape<1, 4, 7, 2>(43.0),  // 224 x 256
-        make_shape<2, 2, 3, 4>(43.0),  // 192 x 256
-        make_shape<1, 4, 5, 2>(46.0),  // 160 x 256
-        make_shape<2, 2, 2, 4>(50.0),  // 128 x 256
-        make_shape<2, 2, 2, 2>(60.0),  // 128 x 128
-        make_shape<2, 2, 1, 2>(75.0),  //  64 x 128
-        make_shape<2, 2, 1, 1>(90.0),  //  64 x  64
-    };
-    *count = (int)(sizeof(tab) / sizeof(tab[0]));
+    static const TileShape tab[kNumTileShapes] = {tile_shape_0(), tile_shape_1(), tile_shape_2(), tile_shape_3(),
+                                                  tile_shape_4(), tile_shape_5(), tile_shape_6(), tile_shape_7()};
+    *count = kNumTileShapes;
     return tab;
 }
 
 static int g_num_cu = 0;
 static int g_force_shape = -1;
+static int g_force_packed = -1;
+
+// Up to this many output rows the weights dominate the traffic and the call is bound by memory: the 4-bit
+// units are then streamed as packed codes (half the bytes); above it from the expanded copy.
+constexpr int64_t kPackedMaxRows = 256;
 
 // Pick the tile shape with the smallest modelled time: rounds of blocks over the CUs times the cycles
 // of one tile (K-steps at the measured cost per MFMA slot, plus prologue and epilogue).
@@ -708,7 +61,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
                   int H, int Wd, int Ho, int Wo, int stride, int pad)
 {
     GemmParams p;
-    p.X = X; p.W8 = L->d_w8; p.W4 = L->d_w4; p.wshift = L->d_wshift; p.ashift = L->d_ashift;
+    p.X = X; p.W8 = L->d_w8; p.W4 = L->d_w4; p.W4X = L->d_w4x; p.wshift = L->d_wshift; p.ashift = L->d_ashift;
     p.cs = L->d_cs; p.bias = L->d_bias;
     p.acc = out->acc; p.y = out->y; p.q = out->q;
     p.r_out = out->q ? 1.0f / out->out_scale : 1.0f;
@@ -724,7 +77,8 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     p.tiles_n = (L->N + ts.BN - 1) / ts.BN;
     const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
     if (blocks > 0x7fffffff) return FLEXIQ_EINVAL;
-    kernel_fn fn = conv ? ts.conv : ts.lin;
+    const bool packed = g_force_packed >= 0 ? g_force_packed != 0 : M <= kPackedMaxRows;
+    kernel_fn fn = ts.fn[conv ? 1 : 0][packed ? 1 : 0];
     {  // raise the dynamic-LDS limit once per kernel
         static std::mutex mu;
         static std::vector<const void *> attr_done;
@@ -764,6 +118,15 @@ extern "C" int flexiq_debug_force_tile(int index)
     if (index < -1 || index >= cnt) return FLEXIQ_EINVAL;
     g_force_shape = index;
     return cnt;
+}
+
+// Test / tuning hook: 1 = 4-bit units always from the packed codes, 0 = always from the expanded copy,
+// -1 = automatic (by the number of output rows).
+extern "C" int flexiq_debug_force_packed4(int mode)
+{
+    if (mode < -1 || mode > 1) return FLEXIQ_EINVAL;
+    g_force_packed = mode;
+    return FLEXIQ_OK;
 }
 
 extern "C" int flexiq_mixed_gemm(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream)

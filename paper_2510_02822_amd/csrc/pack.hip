@@ -102,7 +102,7 @@ __global__ void k_weight_shift(const int8_t *__restrict__ q, const int32_t *__re
 // writes the two 16-byte planes of the 8-bit tile and the 16 bytes of 4-bit codes.
 __global__ void k_pack_tiles(const int8_t *__restrict__ q, const int32_t *__restrict__ perm,
                              const uint8_t *__restrict__ ws_ng, int N, int T, int C, int gs, int Npad, int U,
-                             int8_t *__restrict__ w8, uint8_t *__restrict__ w4)
+                             int8_t *__restrict__ w8, uint8_t *__restrict__ w4, int8_t *__restrict__ w4x)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)U * Npad) return;
@@ -117,10 +117,14 @@ __global__ void k_pack_tiles(const int8_t *__restrict__ q, const int32_t *__rest
     } else {
         for (int j = 0; j < 32; ++j) v[j] = 0;
     }
-    uint32_t d8[8], d4[4];
-    for (int d = 0; d < 8; ++d)
+    uint32_t d8[8], dx[8], d4[4];
+    for (int d = 0; d < 8; ++d) {
         d8[d] = (uint32_t)(v[4 * d] & 0xFF) | ((uint32_t)(v[4 * d + 1] & 0xFF) << 8) |
                 ((uint32_t)(v[4 * d + 2] & 0xFF) << 16) | ((uint32_t)(v[4 * d + 3] & 0xFF) << 24);
+        uint32_t w = 0;
+        for (int b = 0; b < 4; ++b) w |= (uint32_t)((min(7, max(-8, v[4 * d + b] >> s)) * (1 << s)) & 0xFF) << (8 * b);
+        dx[d] = w;
+    }
     for (int e = 0; e < 4; ++e) {
         uint32_t w = 0;
         for (int b = 0; b < 4; ++b) {
@@ -134,6 +138,9 @@ __global__ void k_pack_tiles(const int8_t *__restrict__ q, const int32_t *__rest
     p8[((int64_t)u * 2 + 0) * Npad + n] = make_uint4(d8[0], d8[1], d8[2], d8[3]);
     p8[((int64_t)u * 2 + 1) * Npad + n] = make_uint4(d8[4], d8[5], d8[6], d8[7]);
     reinterpret_cast<uint4 *>(w4)[(int64_t)u * Npad + n] = make_uint4(d4[0], d4[1], d4[2], d4[3]);
+    uint4 *px = reinterpret_cast<uint4 *>(w4x);
+    px[((int64_t)u * 2 + 0) * Npad + n] = make_uint4(dx[0], dx[1], dx[2], dx[3]);
+    px[((int64_t)u * 2 + 1) * Npad + n] = make_uint4(dx[4], dx[5], dx[6], dx[7]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -241,7 +248,7 @@ struct DevBuf {  // frees on scope exit unless released
 extern "C" int flexiq_layer_free(flexiq_layer *L)
 {
     if (!L) return FLEXIQ_OK;
-    void *bufs[] = {L->d_w8, L->d_w4, L->d_wshift, L->d_ashift, L->d_cs, L->d_bias, L->d_perm};
+    void *bufs[] = {L->d_w8, L->d_w4, L->d_w4x, L->d_wshift, L->d_ashift, L->d_cs, L->d_bias, L->d_perm};
     int rc = FLEXIQ_OK;
     for (void *b : bufs)
         if (b && hipFree(b) != hipSuccess) rc = FLEXIQ_EHIP;
@@ -283,7 +290,7 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
     L->max_4bit_ch = 0;
     L->x_scale = d->x_scale;
     L->has_bias = d->bias != nullptr;
-    L->d_w8 = nullptr; L->d_w4 = nullptr; L->d_wshift = nullptr; L->d_ashift = nullptr;
+    L->d_w8 = nullptr; L->d_w4 = nullptr; L->d_w4x = nullptr; L->d_wshift = nullptr; L->d_ashift = nullptr;
     L->d_cs = nullptr; L->d_bias = nullptr; L->d_perm = nullptr;
     FLEXIQ_HIP(hipGetDevice(&L->device));
     const int Npad = L->Npad;
@@ -346,12 +353,13 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
     FLEXIQ_HIP(hipMemset(L->d_wshift, 0, (size_t)G * Npad));
     FLEXIQ_HIP(hipMalloc((void **)&L->d_w8, (size_t)U * 2 * Npad * 16));
     FLEXIQ_HIP(hipMalloc((void **)&L->d_w4, (size_t)U * Npad * 16));
+    FLEXIQ_HIP(hipMalloc((void **)&L->d_w4x, (size_t)U * Npad * 32));
 
     k_weight_shift<<<(unsigned)cdiv((int64_t)N * G, 256), 256>>>((const int8_t *)dQ.p, L->d_perm, N, T, C, gs, Npad,
                                                                  (uint8_t *)dWsNG.p, L->d_wshift);
     k_pack_tiles<<<(unsigned)cdiv((int64_t)U * Npad, 256), 256>>>((const int8_t *)dQ.p, L->d_perm,
                                                                   (const uint8_t *)dWsNG.p, N, T, C, gs, Npad, U,
-                                                                  L->d_w8, L->d_w4);
+                                                                  L->d_w8, L->d_w4, L->d_w4x);
     FLEXIQ_HIP(hipGetLastError());
     L->w_shift.resize((size_t)N * G);
     FLEXIQ_HIP(hipMemcpy(L->w_shift.data(), dWsNG.p, (size_t)N * G, hipMemcpyDeviceToHost));
@@ -385,19 +393,22 @@ extern "C" int flexiq_layer_info(const flexiq_layer *L, const int32_t **perm, co
     return FLEXIQ_OK;
 }
 
-extern "C" int flexiq_layer_dump(const flexiq_layer *L, int8_t *w8, uint8_t *w4)
+extern "C" int flexiq_layer_dump(const flexiq_layer *L, int8_t *w8, uint8_t *w4, int8_t *w4x)
 {
     if (!L) return FLEXIQ_EINVAL;
     const int N = L->N, C = L->C, T = L->T, Npad = L->Npad, U = L->U, CU = ((C / kUnit) + 1) & ~1;
     FLEXIQ_HIP(hipDeviceSynchronize());
-    if (w8) {
+    int8_t *const dst8[2] = {w8, w4x};
+    const int8_t *const src8[2] = {L->d_w8, L->d_w4x};
+    for (int k = 0; k < 2; ++k) {
+        if (!dst8[k]) continue;
         std::vector<int8_t> raw((size_t)U * 2 * Npad * 16);
-        FLEXIQ_HIP(hipMemcpy(raw.data(), L->d_w8, raw.size(), hipMemcpyDeviceToHost));
+        FLEXIQ_HIP(hipMemcpy(raw.data(), src8[k], raw.size(), hipMemcpyDeviceToHost));
         for (int n = 0; n < N; ++n)
             for (int t = 0; t < T; ++t)
                 for (int c = 0; c < C; ++c) {
                     int u = t * CU + c / 32, q2 = (c % 32) / 16, j = c % 16;
-                    w8[((size_t)n * T + t) * C + c] = raw[(((size_t)u * 2 + q2) * Npad + n) * 16 + j];
+                    dst8[k][((size_t)n * T + t) * C + c] = raw[(((size_t)u * 2 + q2) * Npad + n) * 16 + j];
                 }
     }
     if (w4) {

@@ -36,7 +36,7 @@ def test_pack_matches_oracle(env):
         assert (info["a_shift"] == ol.a_shift).all()
         assert (info["w_shift"] == ol.w_shift).all()
         assert info["G"] == ol.G and info["max_4bit_ch"] == 0
-        w8, w4 = fq.flexiq_layer_dump(hl)
+        w8, w4, w4x = fq.flexiq_layer_dump(hl)
         T = ol.R * ol.S
         Wq = ol.Wq.reshape(ol.N, T, ol.C)
         assert (w8 == Wq).all()
@@ -44,6 +44,11 @@ def test_pack_matches_oracle(env):
         for t in range(T):
             ref4 = oracle.bitlower_pack(Wq[:, t, :], ol.group_size, ol.w_shift, per_row=True)
             assert (w4[:, t, :] == ref4).all()
+            # ... and the expanded copy holds every code at its position: L(w, s) << s
+            sh = np.repeat(ol.w_shift.astype(np.int32), ol.group_size, axis=1)
+            lowered = np.clip(Wq[:, t, :].astype(np.int32) >> sh, -8, 7)
+            assert (np.vectorize(oracle.bitlower)(Wq[:5, t, :17].astype(int), sh[:5, :17]) == lowered[:5, :17]).all()
+            assert (w4x[:, t, :].astype(np.int32) == lowered << sh).all()
 
 
 def test_pack_with_given_perm(env):
@@ -52,7 +57,7 @@ def test_pack_with_given_perm(env):
     perm = np.random.default_rng(5).permutation(case.K).astype(np.int32)
     ol, hl, _ = both_layers(case, perm=perm)
     assert (hl.info()["perm"] == perm).all()
-    w8, _ = fq.flexiq_layer_dump(hl)
+    w8, _, _ = fq.flexiq_layer_dump(hl)
     assert (w8[:, 0, :] == ol.Wq.reshape(ol.N, ol.C)).all()
 
 
@@ -111,12 +116,17 @@ def _run_gemm_case(env, case, ratios, rows=None, check_q=True):
         assert k4 == oracle.groups_for_ratio(r, ol.G) * ol.group_size
         ref = oracle.forward_gemm(ol, Xq, r)
         so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
-        out = fq.flexiq_mixed_gemm(hl, Xd, acc=True, y=True, q=check_q, out_scale=so)
-        torch.cuda.synchronize()
-        assert (out["acc"].cpu().numpy() == ref).all(), (case.name, r)
-        check_y(out["y"].cpu().numpy(), ref, ol)
-        if check_q:
-            assert (out["q"].cpu().numpy() == oracle.requant_i8(ref, x_scale, ol.w_scale, so, ol.bias)).all()
+        try:
+            for packed in (0, 1):   # 4-bit weights from the expanded copy, then from the packed codes
+                fq.debug_force_packed4(packed)
+                out = fq.flexiq_mixed_gemm(hl, Xd, acc=True, y=True, q=check_q, out_scale=so)
+                torch.cuda.synchronize()
+                assert (out["acc"].cpu().numpy() == ref).all(), (case.name, r, packed)
+                check_y(out["y"].cpu().numpy(), ref, ol)
+                if check_q:
+                    assert (out["q"].cpu().numpy() == oracle.requant_i8(ref, x_scale, ol.w_scale, so, ol.bias)).all()
+        finally:
+            fq.debug_force_packed4(-1)
 
 
 def test_gemm_config0_all_ratios_all_tiles(env):
@@ -190,7 +200,7 @@ def test_ratio_switch_needs_no_repack(env):
     torch, oracle, fq, dev = env
     case = workloads.config0()
     ol, hl, x_scale = both_layers(case)
-    w8a, w4a = fq.flexiq_layer_dump(hl)
+    w8a, w4a, w4xa = fq.flexiq_layer_dump(hl)
     Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
     Xd = _dev(torch, Xq, dev)
     sched = workloads.config4_ratio_schedule(12)
@@ -201,8 +211,8 @@ def test_ratio_switch_needs_no_repack(env):
         fq.flexiq_set_ratio(fresh, float(r))
         assert (got == fq.flexiq_mixed_gemm(fresh, Xd, acc=True)["acc"].cpu().numpy()).all()
         assert (got == oracle.forward_gemm(ol, Xq, float(r))).all()
-    w8b, w4b = fq.flexiq_layer_dump(hl)
-    assert (w8a == w8b).all() and (w4a == w4b).all()
+    w8b, w4b, w4xb = fq.flexiq_layer_dump(hl)
+    assert (w8a == w8b).all() and (w4a == w4b).all() and (w4xa == w4xb).all()
 
 
 @pytest.mark.parametrize("B,H,C,N,R,stride,pad,gs", [(2, 7, 64, 24, 3, 1, 1, 32), (3, 9, 128, 72, 3, 2, 1, 64),
@@ -238,10 +248,14 @@ def test_conv_all_tiles(env):
             fq.debug_force_tile(t)
             for r in (0.0, 0.5, 1.0):
                 fq.flexiq_set_ratio(hl, r)
-                got = fq.flexiq_mixed_conv_implicit(hl, Xd, 1, 1, acc=True)["acc"].cpu().numpy()
-                assert (got == oracle.forward_conv(ol, Xq, 1, 1, r)).all(), (t, r)
+                ref = oracle.forward_conv(ol, Xq, 1, 1, r)
+                for packed in (0, 1):
+                    fq.debug_force_packed4(packed)
+                    got = fq.flexiq_mixed_conv_implicit(hl, Xd, 1, 1, acc=True)["acc"].cpu().numpy()
+                    assert (got == ref).all(), (t, r, packed)
     finally:
         fq.debug_force_tile(-1)
+        fq.debug_force_packed4(-1)
 
 
 def test_determinism(env):
