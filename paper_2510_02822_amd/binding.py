@@ -60,6 +60,8 @@ def load():
                                              C.c_int32, C.POINTER(_Out), C.c_void_p]
     L.flexiq_debug_force_tile.argtypes = [C.c_int]
     L.flexiq_debug_force_packed4.argtypes = [C.c_int]
+    L.flexiq_debug_max_blocks.argtypes = [C.c_int]
+    L.flexiq_debug_last_launch.argtypes = [C.c_int]
     for name in exported_symbols():
         getattr(L, name)
     _lib = L
@@ -225,3 +227,16 @@ def debug_force_tile(index: int) -> int:
 def debug_force_packed4(mode: int) -> None:
     """Where the GEMM kernel takes the weights of 4-bit units from: 1 = packed codes, 0 = expanded copy, -1 = automatic."""
     _check(load().flexiq_debug_force_packed4(mode))
+
+
+def debug_max_blocks(n: int) -> None:
+    """Blocks of a linear GEMM call: 0 = automatic (a resident wave of blocks, each walking several output tiles),
+    n > 0 = at most n blocks, n < 0 = one block per output tile."""
+    _check(load().flexiq_debug_max_blocks(int(n)))
+
+
+def debug_last_launch() -> dict:
+    """Tile shape index, block count and resident blocks per CU of the last GEMM / convolution launch."""
+    L = load()
+    return {"tile": L.flexiq_debug_last_launch(0), "blocks": L.flexiq_debug_last_launch(1),
+            "resident": L.flexiq_debug_last_launch(2)}

@@ -40,7 +40,8 @@ void set_hip_error(hipError_t e, const char *what);
 //                                   int8 value (code << wshift), in the layout of w8: the copy the matrix
 //                                   kernel streams when the problem is compute-bound, so that no expansion
 //                                   work shares the vector ALU with the matrix pipe
-//   wshift uint8 [G][Npad]          weight extraction position per (group, output channel)
+//   wshift uint8 [G+1][Npad]        weight extraction position per (group, output channel); row G is zero
+//                                   (looked up by the pad unit)
 //   ashift int32 [G+1]              activation extraction position per group (+1 entry for the pad unit)
 //   cs     fp32  [Npad]             x_scale * w_scale[n]
 //   bias   fp32  [Npad]             zeros when the layer has no bias

@@ -1,6 +1,9 @@
 // Host side of the mixed GEMM / implicit-GEMM convolution (Section 7 of the paper): tile-shape choice,
 // launch, and the C entry points.  The kernel itself is in mixed_kernel.h.
+#include <algorithm>
 #include <mutex>
+#include <utility>
+#include <vector>
 
 #include "mixed_kernel.h"
 
@@ -21,18 +24,15 @@ static const TileShape *shapes(int *count)
 static int g_num_cu = 0;
 static int g_force_shape = -1;
 static int g_force_packed = -1;
+static int g_max_blocks = 0;
+static int g_last_shape = -1, g_last_blocks = 0, g_last_resident = 0;
 
 // Up to this many output rows the weights dominate the traffic and the call is bound by memory: the 4-bit
 // units are then streamed as packed codes (half the bytes); above it from the expanded copy.
 constexpr int64_t kPackedMaxRows = 256;
 
-// Pick the tile shape with the smallest modelled time: rounds of blocks over the CUs times the cycles
-// of one tile (K-steps at the measured cost per MFMA slot, plus prologue and epilogue).
-static const TileShape &choose_shape(int64_t M, int N, int steps)
+static int num_cu()
 {
-    int cnt;
-    const TileShape *tab = shapes(&cnt);
-    if (g_force_shape >= 0 && g_force_shape < cnt) return tab[g_force_shape];
     if (g_num_cu <= 0) {
         int dev = 0;
         hipDeviceProp_t prop;
@@ -40,21 +40,53 @@ static const TileShape &choose_shape(int64_t M, int N, int steps)
             g_num_cu = prop.multiProcessorCount;
         if (g_num_cu <= 0) g_num_cu = 256;
     }
+    return g_num_cu;
+}
+
+// Blocks of kernel `fn` that fit on one CU (registers and LDS); raises the dynamic-LDS limit on first use.
+static int resident_blocks(kernel_fn fn, int lds)
+{
+    static std::mutex mu;
+    static std::vector<std::pair<const void *, int>> done;
+    std::lock_guard<std::mutex> lk(mu);
+    for (const auto &f : done)
+        if (f.first == (const void *)fn) return f.second;
+    int resident = 0;
+    if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return -1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, (const void *)fn, 256, lds) != hipSuccess) return -1;
+    if (resident < 1) resident = 1;
+    done.emplace_back((const void *)fn, resident);
+    return resident;
+}
+
+// Pick the tile shape with the smallest modelled time on the busiest CU: the tiles that CU has to compute, how
+// many of them run side by side, and per tile the K-steps (slower when the CU is shared) plus the epilogue.
+static int choose_shape(int64_t M, int N, int steps, bool conv, bool packed)
+{
+    int cnt;
+    const TileShape *tab = shapes(&cnt);
+    if (g_force_shape >= 0 && g_force_shape < cnt) return g_force_shape;
+    const int ncu = num_cu();
     double best = 1e300;
     int bi = 0;
     for (int i = 0; i < cnt; ++i) {
-        const double tm = (double)((M + tab[i].BM - 1) / tab[i].BM), tn = (double)((N + tab[i].BN - 1) / tab[i].BN);
-        const double rounds = __builtin_ceil(tm * tn / g_num_cu);
-        const double tile = steps * 2.0 * tab[i].mfma_per_khalf * tab[i].cyc_per_mfma  // main loop
-                            + 600.0 * tab[i].mfma_per_khalf                              // epilogue
-                            + 3000.0;                                                    // launch, prologue
-        const double cost = rounds * tile;
+        const int occ = resident_blocks(tab[i].fn[conv ? 1 : 0][packed ? 1 : 0], tab[i].lds);
+        if (occ < 1) continue;
+        const double tiles = (double)((M + tab[i].BM - 1) / tab[i].BM) * (double)((N + tab[i].BN - 1) / tab[i].BN);
+        const double tiles_cu = __builtin_ceil(tiles / ncu);
+        const double conc = tiles_cu < occ ? tiles_cu : occ;
+        const double seq = __builtin_ceil(tiles_cu / conc);
+        const double step = tab[i].step_alone * (1.0 + tab[i].share * (conc - 1.0));
+        const double prologue = 8000.0;
+        const bool walks = tab[i].multi && !conv && steps >= 4;   // prologue paid once per block
+        const double cost = walks ? prologue + seq * (steps * step + tab[i].epilogue)
+                                  : seq * (prologue + steps * step + tab[i].epilogue);
         if (cost < best) {
             best = cost;
             bi = i;
         }
     }
-    return tab[bi];
+    return bi;
 }
 
 static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, bool conv,
@@ -70,26 +102,31 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.U = L->U; p.CU = L->C / kUnit; p.T = L->T; p.G = L->G;
     if (L->G + 1 > 160) return FLEXIQ_EINVAL;  // position table kept in LDS
+    if (L->C / kUnit >= 2 * 65535) return FLEXIQ_EINVAL;  // K-step indices are kept in 16-bit fields
     if ((int64_t)L->U * 32 * L->Npad > 0x7fffffff) return FLEXIQ_EINVAL;  // weight window must fit a buffer descriptor
     p.H = H; p.Wd = Wd; p.Ho = Ho; p.Wo = Wo; p.S = L->S; p.stride = stride; p.pad = pad;
-    const TileShape &ts = choose_shape(M, L->N, L->T * ((p.CU + 1) / 2));
+    const int steps = L->T * ((p.CU + 1) / 2);
+    const bool packed = g_force_packed >= 0 ? g_force_packed != 0 : M <= kPackedMaxRows;
+    int cnt;
+    g_last_shape = choose_shape(M, L->N, steps, conv, packed);
+    const TileShape &ts = shapes(&cnt)[g_last_shape];
     p.tiles_m = (int)((M + ts.BM - 1) / ts.BM);
     p.tiles_n = (L->N + ts.BN - 1) / ts.BN;
-    const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
-    if (blocks > 0x7fffffff) return FLEXIQ_EINVAL;
-    const bool packed = g_force_packed >= 0 ? g_force_packed != 0 : M <= kPackedMaxRows;
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    if (tiles > 0x7fffffff) return FLEXIQ_EINVAL;
     kernel_fn fn = ts.fn[conv ? 1 : 0][packed ? 1 : 0];
-    {  // raise the dynamic-LDS limit once per kernel
-        static std::mutex mu;
-        static std::vector<const void *> attr_done;
-        std::lock_guard<std::mutex> lk(mu);
-        bool seen = false;
-        for (const void *f : attr_done) seen = seen || f == (const void *)fn;
-        if (!seen) {
-            FLEXIQ_HIP(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, ts.lds));
-            attr_done.push_back((const void *)fn);
-        }
+    const int resident = resident_blocks(fn, ts.lds);   // blocks of this kernel that fit on one CU
+    if (resident < 1) {
+        set_hip_error(hipGetLastError(), "hipFuncSetAttribute / hipOccupancyMaxActiveBlocksPerMultiprocessor");
+        return FLEXIQ_EHIP;
     }
+    // A linear layer with at least four K-steps runs as one resident wave of blocks, each walking several
+    // output tiles (the kernel's load pipeline then runs on across tile boundaries); otherwise one block per tile.
+    int64_t blocks = tiles;
+    if (ts.multi && !conv && steps >= 4 && g_max_blocks >= 0)
+        blocks = std::min<int64_t>(tiles, g_max_blocks > 0 ? (int64_t)g_max_blocks : (int64_t)num_cu() * resident);
+    g_last_blocks = (int)blocks;
+    g_last_resident = resident;
     const int nt = 256;
     hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3(nt), ts.lds, (hipStream_t)stream, p);
     FLEXIQ_HIP(hipGetLastError());
@@ -118,6 +155,21 @@ extern "C" int flexiq_debug_force_tile(int index)
     if (index < -1 || index >= cnt) return FLEXIQ_EINVAL;
     g_force_shape = index;
     return cnt;
+}
+
+// Test / tuning hook: what the last launch used.  which = 0: tile shape index, 1: blocks launched,
+// 2: blocks of that kernel resident per CU.
+extern "C" int flexiq_debug_last_launch(int which)
+{
+    return which == 0 ? g_last_shape : (which == 1 ? g_last_blocks : g_last_resident);
+}
+
+// Test / tuning hook for the number of blocks of a linear call: 0 = automatic (one resident wave of blocks,
+// each walking several output tiles), n > 0 = at most n blocks, n < 0 = one block per output tile.
+extern "C" int flexiq_debug_max_blocks(int n)
+{
+    g_max_blocks = n;
+    return FLEXIQ_OK;
 }
 
 // Test / tuning hook: 1 = 4-bit units always from the packed codes, 0 = always from the expanded copy,

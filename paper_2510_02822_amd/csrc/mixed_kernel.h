@@ -144,10 +144,14 @@ struct Cfg {
     static constexpr int WPS = (BN + 2) * 16;
     static constexpr int STAGE = 4 * XPS + 4 * WPS;
     static constexpr int NSTAGE = 3;
-    static constexpr int QSTRIDE = BN + 16;             // row stride of the int8 output tile staged in LDS
-    static constexpr int TABLE = 640 + 2 * BN * 4;      // activation positions of up to 160 groups; scale and bias of the tile's columns
+    // activation positions of up to 160 groups; scale and bias of the columns of two consecutive tiles
+    static constexpr int TABLE = 640 + 2 * (2 * BN * 4);
     static constexpr int RING = NSTAGE * STAGE;
-    static constexpr int LDS_BYTES = (RING > BM * QSTRIDE ? RING : BM * QSTRIDE) + TABLE;
+    // A block may walk several output tiles.  Not for the largest tiles: their accumulators fill the register
+    // file, and the values that would have to stay live across an epilogue (staged K-step, first fragments of
+    // the next tile) do not fit beside them.
+    static constexpr bool MULTI = TM * TN <= 10;
+    static constexpr int LDS_BYTES = RING + TABLE;
 };
 
 // How the two 32-channel units of a K-step are staged.
@@ -175,8 +179,8 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     constexpr int NF = TM + TN;   // fragments per k-half
     constexpr int NMF = TM * TN;  // MFMAs per k-half
     extern __shared__ __align__(16) unsigned char lds[];
-    unsigned char *const sa_tab = lds + (C_::LDS_BYTES - C_::TABLE);
-    float *const cs_tab = reinterpret_cast<float *>(sa_tab + 640);  // [BN] scales, then [BN] biases
+    unsigned char *const sa_tab = lds + C_::RING;
+    float *const cs_tab = reinterpret_cast<float *>(sa_tab + 640);  // two copies (tile parity) of [BN] scales + [BN] biases
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -185,14 +189,15 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     long long tq0 = __builtin_readcyclecounter(), tqa = 0, tqb = 0, tqc = 0, tqd = 0;
 #endif
 
-    // ---- block -> tile.  Consecutive block ids land on different XCDs (8 of them, each with its own
-    // L2); renumber so that the blocks sharing an XCD walk neighbouring tiles, then sweep bands of 8
-    // tile rows with the tile column varying slowest inside a band (weights stay L2-resident).
-    int tile_m, tile_n;
-    {
-        const int nb = gridDim.x;
-        int b = blockIdx.x;
-        if (nb % 8 == 0) b = (b % 8) * (nb / 8) + b / 8;
+    // ---- tile index -> tile.  A block computes the tiles blockIdx.x, blockIdx.x + gridDim.x, ... one after
+    // the other with the load pipeline running on across the tile boundary.  Consecutive block ids land on
+    // different XCDs (8 of them, each with its own L2); tile indices are renumbered so that the blocks sharing
+    // an XCD walk neighbouring tiles, then sweep bands of 8 tile rows with the tile column varying slowest
+    // inside a band (weights stay L2-resident).
+    const int total_tiles = p.tiles_m * p.tiles_n;
+    auto map_tile = [&](int t, int &tile_m, int &tile_n) {
+        int b = t;
+        if (total_tiles % 8 == 0) b = (b % 8) * (total_tiles / 8) + b / 8;
         constexpr int GMB = 8;
         const int band = b / (GMB * p.tiles_n);
         const int rows_in_band = min(GMB, p.tiles_m - band * GMB);
@@ -200,24 +205,30 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
         // the division runs on the vector ALU; tell the compiler the result is wave-uniform
         tile_m = __builtin_amdgcn_readfirstlane(band * GMB + r % rows_in_band);
         tile_n = __builtin_amdgcn_readfirstlane(r / rows_in_band);
+    };
+    int ctile = blockIdx.x;   // tile being computed
+    int64_t m0;               // its origin
+    int n0;
+    {
+        int tile_m, tile_n;
+        map_tile(ctile, tile_m, tile_n);
+        m0 = (int64_t)tile_m * BM;
+        n0 = tile_n * BN;
     }
-    const int64_t m0 = (int64_t)tile_m * BM;
-    const int n0 = tile_n * BN;
-    const int rows_valid = (int)min((int64_t)BM, p.M - m0);
+    const int rows_valid = (int)min((int64_t)BM, p.M - m0);   // of the block's first tile
 
-    // ---- buffer windows: reads past a window return zero, which is what rows beyond M, padded
-    // pixels and dummy staging rows need
+    // ---- buffer windows.  Weights: the whole arrays (every access is in range by construction: tiles are
+    // padded to Npad columns and to whole units), the tile's column offset travels in the scalar offset.
+    // Activations: a window per tile; reads past it return zero, which is what rows beyond M, padded pixels
+    // and dummy staging rows need.
     constexpr int kRsrcFlags = 0x00020000;
-    const __amdgpu_buffer_rsrc_t rw8 =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(p.W8 + (int64_t)n0 * 16), 0, p.U * 32 * p.Npad - n0 * 16, kRsrcFlags);
-    const __amdgpu_buffer_rsrc_t rw4 =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(p.W4 + (int64_t)n0 * 16), 0, p.U * 16 * p.Npad - n0 * 16, kRsrcFlags);
-    const __amdgpu_buffer_rsrc_t rw4x =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(p.W4X + (int64_t)n0 * 16), 0, p.U * 32 * p.Npad - n0 * 16, kRsrcFlags);
-    const __amdgpu_buffer_rsrc_t rws =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(p.wshift + n0), 0, p.G * p.Npad - n0, kRsrcFlags);
-    const int8_t *xbase;  // origin and size of the activation window of this block
+    const __amdgpu_buffer_rsrc_t rw8 = __builtin_amdgcn_make_buffer_rsrc((void *)p.W8, 0, p.U * 32 * p.Npad, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rw4 = __builtin_amdgcn_make_buffer_rsrc((void *)p.W4, 0, p.U * 16 * p.Npad, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rw4x = __builtin_amdgcn_make_buffer_rsrc((void *)p.W4X, 0, p.U * 32 * p.Npad, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rws = __builtin_amdgcn_make_buffer_rsrc((void *)p.wshift, 0, (p.G + 1) * p.Npad, kRsrcFlags);
+    const int8_t *xbase;  // origin and size of the activation window of the tile being LOADED
     int xwin;
+    int ld_n0 = n0;       // and its first column
     const int xq = tid & 3;   // k-plane of this thread's activation chunks; unit xq >> 1
     int xvoff[XL];            // linear: byte offset inside the window; conv: xq * 16
     int xh0[XL], xw0[XL], xpix[XL];  // conv: top-left input coordinate, pixel index of the image origin (-1: no row)
@@ -252,7 +263,24 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
             xh0[j] = xw0[j] = xpix[j] = 0;
         }
     }
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)xbase, 0, xwin, kRsrcFlags);
+    // The tile the loads move on to when the current one is finished (linear form only; a convolution
+    // block is launched for a single tile).
+    const int8_t *pd_xbase = xbase;
+    int pd_xwin = 0, pd_n0 = 0;
+    bool pd_valid = false;
+    auto set_pending = [&](int t) {
+        pd_valid = C_::MULTI && !CONV && t < total_tiles;
+        if (pd_valid) {
+            int tile_m, tile_n;
+            map_tile(t, tile_m, tile_n);
+            const int64_t pm0 = (int64_t)tile_m * BM;
+            pd_xbase = p.X + pm0 * p.C;
+            pd_xwin = (int)min((int64_t)BM, p.M - pm0) * p.C;
+            pd_n0 = tile_n * BN;
+        }
+    };
+    set_pending(ctile + (int)gridDim.x);
+    const int xpad = (p.CU & 1) && xq >= 2 ? 32 : 0;
     const int x_lds = xq * XPS + (tid >> 2) * 16;
     int w8voff[WL8], w8lds[WL8];
 #pragma unroll
@@ -275,8 +303,9 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     // here, written to LDS after the prologue's tile loads have been issued (one memory latency for all)
     static_assert(BN <= NT && 160 <= NT, "one table element per thread");
     const int sa_v = tid <= p.G ? p.ashift[tid] : 0;
-    const float cs_v = tid < BN ? p.cs[n0 + tid] : 0.0f;      // cs/bias are padded to Npad >= n0 + BN
-    const float bias_v = tid < BN ? p.bias[n0 + tid] : 0.0f;
+    float cs_v = tid < BN ? p.cs[n0 + tid] : 0.0f;      // cs/bias are padded to Npad >= n0 + BN
+    float bias_v = tid < BN ? p.bias[n0 + tid] : 0.0f;
+    int parity = 0;   // which copy of the scale / bias table belongs to the tile being computed
 
     // ---- K-step enumeration, phase-major: all-4-bit steps, then mixed steps, then all-8-bit steps;
     // the iterator points at the next tile to LOAD.  Scalar state only.
@@ -284,35 +313,41 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     const int n4 = p.K4 >> 6;                 // full 4-bit steps per tap
     const int mixed = (p.K4 & 63) ? 1 : 0;    // one step per tap with a 4-bit and an 8-bit unit
     const int steps = p.T * SP;
-    // Phase p covers c64 in [pb(p), pe(p)) of every tap; pn(p) is the next non-empty phase (3 = done).
-    // The update is written with selects only: the steady-state loops must stay single basic blocks
-    // so that the compiler can count outstanding loads exactly across the back edge.
-    auto pb = [&](int ph) { return ph == 0 ? 0 : (ph == 1 ? n4 : n4 + mixed); };
-    auto pe = [&](int ph) { return ph == 0 ? n4 : (ph == 1 ? n4 + mixed : SP); };
+    // Phase ph covers c64 in [pb(ph), pe(ph)) of every tap; pn(ph) is the next non-empty phase (3 = done).
+    // The three small tables are packed into scalars and indexed with shifts, and the update is written with
+    // selects only: the steady-state loops stay free of branches and of scalar-memory waits.
     const int ne0 = n4 > 0, ne1 = mixed > 0, ne2 = n4 + mixed < SP;
     const int first_phase = ne0 ? 0 : (ne1 ? 1 : (ne2 ? 2 : 3));
     const int next1 = ne1 ? 1 : (ne2 ? 2 : 3), next2 = ne2 ? 2 : 3;
-    auto pn = [&](int ph) { return ph == 0 ? next1 : (ph == 1 ? next2 : 3); };
+    const uint64_t pb_tab = ((uint64_t)n4 << 16) | ((uint64_t)(n4 + mixed) << 32);                       // 16 bits per phase
+    const uint64_t pe_tab = (uint64_t)n4 | ((uint64_t)(n4 + mixed) << 16) | ((uint64_t)SP << 32);
+    const uint32_t pn_tab = (uint32_t)next1 | ((uint32_t)next2 << 4) | (3u << 8) | (3u << 12);             // 4 bits per phase
+    auto pb = [&](int ph) { return (int)((pb_tab >> (16 * ph)) & 0xFFFFu); };
+    auto pe = [&](int ph) { return (int)((pe_tab >> (16 * ph)) & 0xFFFFu); };
+    auto pn = [&](int ph) { return (int)((pn_tab >> (4 * ph)) & 15u); };
     int it_phase = first_phase, it_tap = 0, it_dy = 0, it_dx = 0;
-    int it_c64 = first_phase < 3 ? pb(first_phase) : 0;
-    int it_b = it_c64, it_e = first_phase < 3 ? pe(first_phase) : 0;  // bounds of the current phase
+    int it_c64 = pb(first_phase);
     auto advance = [&]() {
         const int c = it_c64 + 1;
-        const bool wrap_c = c == it_e;                  // this tap's part of the phase is finished
-        const int dx1 = it_dx + 1;
-        const bool wrap_x = dx1 == p.S;
+        const bool wrap_c = c == pe(it_phase);          // this tap's part of the phase is finished
         const int tap1 = it_tap + 1;
         const bool wrap_t = wrap_c && tap1 == p.T;      // the phase is finished
-        const int ph = wrap_t ? pn(it_phase) : it_phase;
-        const int nb = wrap_t ? (ph < 3 ? pb(ph) : 0) : it_b;
-        const int ne = wrap_t ? (ph < 3 ? pe(ph) : 0) : it_e;
-        it_dy = wrap_t ? 0 : (wrap_c && wrap_x ? it_dy + 1 : it_dy);
-        it_dx = wrap_t ? 0 : (wrap_c ? (wrap_x ? 0 : dx1) : it_dx);
+        const int ph_in = pn(it_phase);
+        const bool go_next = wrap_t && ph_in == 3 && pd_valid;   // the tile is finished and another one follows
+        const int ph = wrap_t ? (go_next ? first_phase : ph_in) : it_phase;
+        xbase = go_next ? pd_xbase : xbase;
+        xwin = go_next ? pd_xwin : xwin;
+        ld_n0 = go_next ? pd_n0 : ld_n0;
+        pd_valid = go_next ? false : pd_valid;
+        if (CONV) {
+            const int dx1 = it_dx + 1;
+            const bool wrap_x = dx1 == p.S;
+            it_dy = wrap_t ? 0 : (wrap_c && wrap_x ? it_dy + 1 : it_dy);
+            it_dx = wrap_t ? 0 : (wrap_c ? (wrap_x ? 0 : dx1) : it_dx);
+        }
         it_tap = wrap_t ? 0 : (wrap_c ? tap1 : it_tap);
-        it_c64 = wrap_c ? nb : c;
+        it_c64 = wrap_c ? pb(ph) : c;
         it_phase = ph;
-        it_b = nb;
-        it_e = ne;
     };
     auto it_mode = [&]() { return it_phase == 0 ? kMode44 : (it_phase == 1 ? kMode48 : (it_phase == 2 ? kMode88 : kModeNone)); };
 
@@ -325,13 +360,17 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     auto gload = [&](v4i(&sr)[NS], int(&wsh)[2][WL4], int i, int mode) {
         const int c64 = it_c64;
         if (i < XL) {
+            const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)xbase, 0, xwin, kRsrcFlags);
+            // pad unit of an odd unit count: its weights are zero; read the unit before it again instead of
+            // the 32 bytes after the row, which for the last row may lie outside the tensor
+            const int back = c64 == SP - 1 ? xpad : 0;
             if (CONV) {
                 const int hi = xh0[i] + it_dy, wi = xw0[i] + it_dx;
                 const bool ok = hi >= 0 && hi < p.H && wi >= 0 && wi < p.Wd && xpix[i] >= 0;
-                const int off = ok ? (xpix[i] + hi * p.Wd + wi) * p.C + xvoff[i] : (int)0x80000000;
+                const int off = ok ? (xpix[i] + hi * p.Wd + wi) * p.C + xvoff[i] - back : (int)0x80000000;
                 sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, c64 * 64, 0);
             } else {
-                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, xvoff[i], c64 * 64, 0);
+                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, xvoff[i] - back, c64 * 64, 0);
             }
         } else {
             const int h = (i - XL) / WL8, j = (i - XL) % WL8;
@@ -340,13 +379,13 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
             if (four && PACKED4) {
                 if (j < WL4) {
                     const int g = (2 * c64 + h) >> p.gs_shift;
-                    sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw4, w4voff[j], u * 16 * p.Npad, 0);
-                    wsh[h][j] = __builtin_amdgcn_raw_buffer_load_b8(rws, w4voff[j] >> 4, g * p.Npad, 0);
+                    sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw4, w4voff[j], u * 16 * p.Npad + ld_n0 * 16, 0);
+                    wsh[h][j] = __builtin_amdgcn_raw_buffer_load_b8(rws, w4voff[j] >> 4, g * p.Npad + ld_n0, 0);
                 }
             } else if (four) {
-                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw4x, w8voff[j], u * 32 * p.Npad, 0);
+                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw4x, w8voff[j], u * 32 * p.Npad + ld_n0 * 16, 0);
             } else {
-                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw8, w8voff[j], u * 32 * p.Npad, 0);
+                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw8, w8voff[j], u * 32 * p.Npad + ld_n0 * 16, 0);
             }
         }
     };
@@ -467,12 +506,15 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     }
     FQ_TS(tqd);
     v16i acc[TN][TM];
+    auto zero_acc = [&]() {
 #pragma unroll
-    for (int a = 0; a < TN; ++a)
+        for (int a = 0; a < TN; ++a)
 #pragma unroll
-        for (int b = 0; b < TM; ++b)
+            for (int b = 0; b < TM; ++b)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
+                for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
+    };
+    zero_acc();
 
     __builtin_amdgcn_s_waitcnt(0xc07f);
     __builtin_amdgcn_s_barrier();
@@ -480,15 +522,20 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     for (int i = 0; i < NF; ++i) fread(fA, i, lds, 0);
 
 #ifdef FLEXIQ_TIMING
-    long long tq1 = __builtin_readcyclecounter();
+    long long tq1 = __builtin_readcyclecounter(), t_epi = 0;
+    int n_tiles = 0;
 #endif
     // ---- main loop.  Step s computes tile s from stage s % 3 while storing tile s+2 (staged in
     // registers during step s-1) into stage (s+2) % 3 and loading tile s+3 into the registers: store
     // of chunk j, then load of chunk j, spread over the whole step.  `ma` is the mode of the staged
     // tile (kModeNone: nothing to store), `mb` the mode of the tile to load (kModeNone: none left);
     // both are compile-time constants in the steady-state loops and run-time values elsewhere.
+    // The K-steps of the block's successive output tiles form one sequence: while the last steps of an
+    // output tile are computed, the first K-steps of the next one are already being loaded and staged.
     int st0 = 0;  // stage of tile s
-    int s = 0;
+    int s = 0;    // K-step within the output tile being computed
+    constexpr int kStageSlots = 2 * NMF > 2 ? 2 * NMF - 2 : 1;    // slots that carry staging work
+    constexpr int kAdvanceSlot = 2 * NMF > 2 ? 2 * NMF - 2 : 0;   // slot after which the load iterator moves on
     auto step = [&](auto ma_, auto mb_, auto h1_) {
         const int ma = ma_, mb = mb_;
         const bool h1 = h1_;
@@ -519,80 +566,70 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                             FQ_SB();
                         }
                     // staging chunk i: four pieces of VALU work, the LDS store, then the global load of the
-                    // next tile's chunk i into the same registers; position t = 6 i + k at step slot t*2NMF/(6 NS)
+                    // next tile's chunk i into the same registers; position t = 6 i + k, spread over the step's
+                    // slots but the last two, where the scalar iterator update runs in the shadow of the MFMAs
 #pragma unroll
                     for (int t = 0; t < 6 * NS; ++t)
-                        if (t * (2 * NMF) / (6 * NS) == g) {
+                        if (t * kStageSlots / (6 * NS) == g) {
                             const int i = t / 6, k = t % 6;
                             if (k < 4) {
                                 if (ma == kMode44 || ma == kMode48) lmicro(sr, wsh, i, k, ma);
                             } else if (k == 4) {
+#ifndef FQ_EXP_NOLSTORE
                                 if (ma != kModeNone) lstore(sr, i, ma, nx2);
+#endif
                             } else {
+#ifndef FQ_EXP_NOGLOAD
                                 if (mb != kModeNone) gload(sr, wsh, i, mb);
+#endif
                             }
                             FQ_SB();
                         }
+                    if (g == kAdvanceSlot && mb != kModeNone) {
+                        advance();
+                        FQ_SB();
+                    }
                 }
-        if (mb != kModeNone) advance();
         __builtin_amdgcn_s_waitcnt(0xc07f);  // this wave's LDS stores and fragment reads are complete
+#ifndef FQ_EXP_NOBARRIER
         __builtin_amdgcn_s_barrier();
+#endif
         FQ_SB();
         st0 = st1;
         ++s;
         mode_staged = mb;
     };
-    using M44 = std::integral_constant<int, kMode44>;
-    using M88 = std::integral_constant<int, kMode88>;
-    using MNone = std::integral_constant<int, kModeNone>;
-    using T_ = std::true_type;
-    using F_ = std::false_type;
-    // A sequence of loops in the order the cases occur (each may run zero times), so that every
-    // variant of the step body is straight-line code and the accumulators never pass through a
-    // run-time selection between code paths:
-    //   steady 4-bit | transitions (generic, run-time modes) | steady 8-bit | drain: store the last staged
-    //   tile without loading | last steps with nothing left to stage
-    // (Entering a steady-state loop with no load in flight lets the compiler count the loads of the loop
-    // itself exactly, instead of waiting for all of them before the first store of every step.)
-    __builtin_amdgcn_s_waitcnt(0x0070);
-    while (mode_staged == kMode44 && it_phase == 0) step(M44{}, M44{}, T_{});
-    while (s < steps && it_phase != 3 && !(mode_staged == kMode88 && it_phase == 2)) step(mode_staged, (int)it_mode(), s + 1 < steps);
-    __builtin_amdgcn_s_waitcnt(0x0070);
-    while (mode_staged == kMode88 && it_phase == 2) step(M88{}, M88{}, T_{});
-    while (s < steps && mode_staged == kMode88) step(M88{}, MNone{}, T_{});
-    while (s < steps && mode_staged == kMode44) step(M44{}, MNone{}, T_{});
-    while (s < steps && mode_staged != kModeNone) step(mode_staged, (int)kModeNone, s + 1 < steps);
-    while (s + 1 < steps) step(MNone{}, MNone{}, T_{});
-    while (s < steps) step(MNone{}, MNone{}, F_{});
 
-#ifdef FLEXIQ_TIMING
-    long long tq2 = __builtin_readcyclecounter();
-#endif
-    // ---- epilogue.  Lane holds output row m = 32 b + (lane & 31) and, per accumulator quad g, the four
-    // consecutive output channels n = 32 a + 8 g + 4 (lane >> 5) + i.  The body is instantiated with
-    // compile-time output flags for the common cases (int8 only; fp32 and/or int32 only) and once
-    // with run-time flags for everything else (ragged N, several outputs at once).
+    // ---- epilogue of one output tile.  Lane holds output row m = 32 b + (lane & 31) and, per accumulator
+    // quad g, the four consecutive output channels n = 32 a + 8 g + 4 (lane >> 5) + i.  The body is
+    // instantiated with compile-time output flags for the common cases (int8 only; fp32 or int32 only) and
+    // once with run-time flags for everything else (ragged N, several outputs at once).
 #ifdef FLEXIQ_TIMING
     const bool want_q = p.q != nullptr, want_y = p.y != nullptr, want_acc = false;
 #else
     const bool want_q = p.q != nullptr, want_y = p.y != nullptr, want_acc = p.acc != nullptr;
 #endif
     const bool n_vec = (p.N & 3) == 0;
-    const bool q_lds = want_q && (p.N & 15) == 0;   // int8 tile through LDS: 16-byte row-contiguous stores
-    constexpr int QS = C_::QSTRIDE;
-    auto epilogue = [&](auto wq_, auto wy_, auto wa_, auto nv_, auto ql_) {
-        const bool wq = wq_, wy = wy_, wa = wa_, nv = nv_, ql = ql_;
-#pragma unroll
-        for (int a = 0; a < TN; ++a) {
+    const bool q_rows = want_q && (p.N & 15) == 0;   // int8 output as 16-byte row-contiguous pieces
+    const int frag_half_e = lane >> 5, frag_row_e = lane & 31;
+    // (one call handles fragment column a; the variant is chosen per column, which keeps the live ranges of the
+    // accumulators short where the variants branch apart)
+    auto epilogue = [&](auto a_, auto wq_, auto wy_, auto wa_, auto nv_, auto qr_) {
+        const bool wq = wq_, wy = wy_, wa = wa_, nv = nv_, qr = qr_;
+        constexpr int a = decltype(a_)::value;
+        const float *tab = cs_tab + parity * (2 * BN);
+        {
+            uint32_t qrow[TM][4];   // int8 codes of the four quads of fragment (a, b)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int nl = (wn * TN + a) * 32 + 8 * g + 4 * frag_half;
+                FQ_SB();   // keep the accumulator reads of later quads from being hoisted (register pressure)
+                const int nl = (wn * TN + a) * 32 + 8 * g + 4 * frag_half_e;
                 const int n = n0 + nl;
                 const bool n_ok = n < p.N;
                 float csv[4], biv[4], mul[4], add[4];
                 {
-                    const float4 cs = *reinterpret_cast<const float4 *>(cs_tab + nl);
-                    const float4 bi = *reinterpret_cast<const float4 *>(cs_tab + BN + nl);
+                    const float4 cs = *reinterpret_cast<const float4 *>(tab + nl);
+                    const float4 bi = *reinterpret_cast<const float4 *>(tab + BN + nl);
                     csv[0] = cs.x; csv[1] = cs.y; csv[2] = cs.z; csv[3] = cs.w;
                     biv[0] = bi.x; biv[1] = bi.y; biv[2] = bi.z; biv[3] = bi.w;
                 }
@@ -605,7 +642,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                 }
 #pragma unroll
                 for (int b = 0; b < TM; ++b) {
-                    const int ml = (wm * TM + b) * 32 + frag_row;
+                    const int ml = (wm * TM + b) * 32 + frag_row_e;
                     const int64_t m = m0 + ml;
                     const int iv[4] = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
                     uint32_t qw = 0;
@@ -618,9 +655,9 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                             u[i] = __builtin_bit_cast(uint32_t, t + 12582912.0f);  // 1.5 * 2^23: integer lands in the low bits
                         }
                         qw = __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu);
-                        if (ql) *reinterpret_cast<uint32_t *>(lds + ml * QS + nl) = qw;
+                        qrow[b][g] = qw;
                     }
-                    if (!(wy || wa || (wq && !ql))) continue;   // nothing goes straight to global memory
+                    if (!(wy || wa || (wq && !qr))) continue;   // nothing is stored quad by quad
                     if (m >= p.M || !n_ok) continue;
                     const int64_t o = m * p.N + n;
                     if (nv) {
@@ -633,7 +670,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                             y.w = __builtin_fmaf((float)iv[3], csv[3], biv[3]);
                             *reinterpret_cast<float4 *>(p.y + o) = y;
                         }
-                        if (wq && !ql) *reinterpret_cast<uint32_t *>(p.q + o) = qw;
+                        if (wq && !qr) *reinterpret_cast<uint32_t *>(p.q + o) = qw;
                     } else {
                         for (int i = 0; i < 4 && n + i < p.N; ++i) {
                             if (wa) p.acc[o + i] = iv[i];
@@ -643,33 +680,98 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                     }
                 }
             }
+            FQ_SB();
+            if (wq && qr) {
+                // The two halves of the wave hold alternating 4-byte pieces of a row.  Exchanging quads 0 <-> 2
+                // and 1 <-> 3 between the halves leaves lanes 0..31 with channels 0..15 of the fragment's 32 and
+                // lanes 32..63 with channels 16..31: one 16-byte store per lane.
+#pragma unroll
+                for (int b = 0; b < TM; ++b) {
+                    const auto s02 = __builtin_amdgcn_permlane32_swap(qrow[b][0], qrow[b][2], false, false);
+                    const auto s13 = __builtin_amdgcn_permlane32_swap(qrow[b][1], qrow[b][3], false, false);
+                    const int64_t m = m0 + (wm * TM + b) * 32 + frag_row_e;
+                    const int n = n0 + (wn * TN + a) * 32 + 16 * frag_half_e;
+                    if (m < p.M && n < p.N)
+                        *reinterpret_cast<v4i *>(p.q + m * p.N + n) = (v4i){(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+                }
+            }
         }
     };
-    if (q_lds && !want_y && !want_acc) epilogue(T_{}, F_{}, F_{}, T_{}, T_{});
-    else if (n_vec && !want_q && want_y && !want_acc) epilogue(F_{}, T_{}, F_{}, T_{}, F_{});
-    else if (n_vec && !want_q && !want_y && want_acc) epilogue(F_{}, F_{}, T_{}, T_{}, F_{});
-    else epilogue(want_q, want_y, want_acc, n_vec, q_lds);
-    if (q_lds) {
-        __syncthreads();
-        constexpr int TPR = BN / 16;   // threads per tile row
-        constexpr int RPP = NT / TPR;  // rows per pass
-        const int c16 = tid % TPR, r0 = tid / TPR;
-#pragma unroll
-        for (int pass = 0; pass < (BM + RPP - 1) / RPP; ++pass) {
-            const int row = r0 + pass * RPP;
-            const int64_t m = m0 + row;
-            const int n = n0 + c16 * 16;
-            if (row < BM && m < p.M && n < p.N)
-                *reinterpret_cast<v4i *>(p.q + m * p.N + n) = *reinterpret_cast<const v4i *>(lds + row * QS + c16 * 16);
+    using M44 = std::integral_constant<int, kMode44>;
+    using M88 = std::integral_constant<int, kMode88>;
+    using MNone = std::integral_constant<int, kModeNone>;
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    // Every variant of the step body is straight-line code inside a loop of its own, and the loops follow each
+    // other in the order the cases occur (each may run zero times), so that the accumulators never pass
+    // through a run-time selection between code paths:
+    //   steady 4-bit | transitions (generic, run-time modes) | steady 8-bit | drain: store the last staged
+    //   tile without loading | last steps with nothing left to stage
+    // The sequence is repeated until the output tile is complete (s == steps); then its epilogue runs and the
+    // next output tile of the block, whose first K-steps are already staged, takes over.
+    // (Entering a steady-state loop with no load or store in flight lets the compiler count the loads of the
+    // loop itself exactly, instead of waiting for all of them before the first LDS store of every step.)
+    for (;;) {
+        const bool more_tiles = C_::MULTI && !CONV && ctile + (int)gridDim.x < total_tiles;
+        __builtin_amdgcn_s_waitcnt(0x0070);
+        while (s < steps && mode_staged == kMode44 && it_phase == 0) step(M44{}, M44{}, T_{});
+        while (s < steps && mode_staged != kModeNone && it_phase != 3 &&
+               !(mode_staged == kMode44 && it_phase == 0) && !(mode_staged == kMode88 && it_phase == 2))
+            step(mode_staged, (int)it_mode(), true);
+        __builtin_amdgcn_s_waitcnt(0x0070);
+        while (s < steps && mode_staged == kMode88 && it_phase == 2) step(M88{}, M88{}, T_{});
+        while (s < steps && mode_staged == kMode88 && it_phase == 3) step(M88{}, MNone{}, T_{});
+        while (s < steps && mode_staged == kMode44 && it_phase == 3) step(M44{}, MNone{}, T_{});
+        while (s < steps && mode_staged == kMode48 && it_phase == 3) step(mode_staged, (int)kModeNone, true);
+        while (s + 1 < steps && mode_staged == kModeNone) step(MNone{}, MNone{}, T_{});
+        while (s < steps && mode_staged == kModeNone) step(MNone{}, MNone{}, F_{});
+        if (s < steps) continue;
+
+#ifdef FLEXIQ_TIMING
+        const long long te0 = __builtin_readcyclecounter();
+#endif
+        auto epilogue_col = [&](auto a_) {
+            if (q_rows && !want_y && !want_acc) epilogue(a_, T_{}, F_{}, F_{}, T_{}, T_{});
+            else if (n_vec && !want_q && want_y && !want_acc) epilogue(a_, F_{}, T_{}, F_{}, T_{}, F_{});
+            else if (n_vec && !want_q && !want_y && want_acc) epilogue(a_, F_{}, F_{}, T_{}, T_{}, F_{});
+            else epilogue(a_, want_q, want_y, want_acc, n_vec, q_rows);
+            FQ_SB();
+        };
+        epilogue_col(std::integral_constant<int, 0>{});
+        if constexpr (TN > 1) epilogue_col(std::integral_constant<int, 1>{});
+        if constexpr (TN > 2) epilogue_col(std::integral_constant<int, 2>{});
+        if constexpr (TN > 3) epilogue_col(std::integral_constant<int, 3>{});
+        static_assert(TN <= 4, "epilogue handles up to four fragment columns");
+#ifdef FLEXIQ_TIMING
+        t_epi += __builtin_readcyclecounter() - te0;
+        ++n_tiles;
+#endif
+        if (!more_tiles) break;
+
+        // ---- next output tile of this block
+        ctile += (int)gridDim.x;
+        {
+            int tile_m, tile_n;
+            map_tile(ctile, tile_m, tile_n);
+            m0 = (int64_t)tile_m * BM;
+            n0 = tile_n * BN;
         }
+        set_pending(ctile + (int)gridDim.x);   // the loads are inside this tile by now
+        parity ^= 1;                           // the other table copy was last read two epilogues ago
+        if (tid < BN) {
+            cs_tab[parity * (2 * BN) + tid] = p.cs[n0 + tid];
+            cs_tab[parity * (2 * BN) + BN + tid] = p.bias[n0 + tid];
+        }
+        zero_acc();
+        s = 0;
     }
 #ifdef FLEXIQ_TIMING
     {
         long long tq3 = __builtin_readcyclecounter();
         if (lane == 0 && p.acc) {
             int *d = p.acc + ((int64_t)blockIdx.x * 4 + wave) * 8;
-            d[0] = (int)(tq1 - tq0); d[1] = (int)(tq2 - tq1); d[2] = (int)(tq3 - tq2); d[3] = steps;
-            d[4] = (int)(tqa - tq0); d[5] = (int)(tqb - tqa); d[6] = (int)(tqc - tqb); d[7] = (int)(tqd - tqc);
+            d[0] = (int)(tq1 - tq0); d[1] = (int)(tq3 - tq1 - t_epi); d[2] = (int)t_epi; d[3] = steps * n_tiles;
+            d[4] = (int)(tqa - tq0); d[5] = (int)(tqb - tqa); d[6] = (int)(tqc - tqb); d[7] = n_tiles;
         }
     }
 #endif
@@ -678,21 +780,23 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
 typedef void (*kernel_fn)(const GemmParams);
 struct TileShape {
     int BM, BN, lds;
-    int mfma_per_khalf;  // MFMAs per wave per k-half
-    double cyc_per_mfma; // measured cycles per MFMA slot in the steady-state loop (32 is the pipe's own time)
+    bool multi;          // a block of this shape may walk several output tiles (linear form)
+    // Measured on MI355X (ViT-B / ViT-L MLP shapes, 8-bit steps), in shader cycles; used by the shape choice:
+    double step_alone;   // one K-step of a block that has its CU to itself
+    double share;        // relative growth of that time per further block resident on the same CU
+    double epilogue;     // epilogue of one output tile
     kernel_fn fn[2][2];  // [convolution][4-bit weights from the packed codes]
 };
 
 template <int WAVES_M, int WAVES_N, int TM, int TN>
-inline TileShape make_shape(double cyc)
+inline TileShape make_shape(double step_alone, double share, double epilogue)
 {
     using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
     static_assert(C_::NT == 256, "the launcher uses 256 threads");
-    return TileShape{C_::BM, C_::BN, C_::LDS_BYTES, TM * TN, cyc,
+    return TileShape{C_::BM, C_::BN, C_::LDS_BYTES, C_::MULTI, step_alone, share, epilogue,
                      {{k_mixed<WAVES_M, WAVES_N, TM, TN, false, false>, k_mixed<WAVES_M, WAVES_N, TM, TN, false, true>},
                       {k_mixed<WAVES_M, WAVES_N, TM, TN, true, false>, k_mixed<WAVES_M, WAVES_N, TM, TN, true, true>}}};
 }
-
 
 // Shape i of the table, defined in mixed_tile.hip built with -DFQ_TILE=i.
 constexpr int kNumTileShapes = 8;

@@ -349,8 +349,9 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
         FLEXIQ_HIP(hipMalloc((void **)&L->d_ashift, a32.size() * sizeof(int32_t)));
         FLEXIQ_HIP(hipMemcpy(L->d_ashift, a32.data(), a32.size() * sizeof(int32_t), hipMemcpyHostToDevice));
     }
-    FLEXIQ_HIP(hipMalloc((void **)&L->d_wshift, (size_t)G * Npad));
-    FLEXIQ_HIP(hipMemset(L->d_wshift, 0, (size_t)G * Npad));
+    // one more (zero) row than groups: the pad unit of an odd unit count looks up group G
+    FLEXIQ_HIP(hipMalloc((void **)&L->d_wshift, (size_t)(G + 1) * Npad));
+    FLEXIQ_HIP(hipMemset(L->d_wshift, 0, (size_t)(G + 1) * Npad));
     FLEXIQ_HIP(hipMalloc((void **)&L->d_w8, (size_t)U * 2 * Npad * 16));
     FLEXIQ_HIP(hipMalloc((void **)&L->d_w4, (size_t)U * Npad * 16));
     FLEXIQ_HIP(hipMalloc((void **)&L->d_w4x, (size_t)U * Npad * 32));

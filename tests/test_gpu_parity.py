@@ -162,6 +162,23 @@ def test_gemm_ragged_all_tiles(env):
         fq.debug_force_tile(-1)
 
 
+def test_gemm_blocks_walk_several_tiles(env):
+    # few blocks, many output tiles: every block computes a sequence of tiles with its load pipeline running
+    # across the tile boundaries (ragged last tile row and column included); compared with one block per tile
+    torch, oracle, fq, dev = env
+    n = fq.debug_force_tile(-1)
+    case = workloads.make_linear("walk", 8, 78, 531, 320, 592, 32, outlier_frac=0.02)
+    try:
+        for t in range(n):
+            fq.debug_force_tile(t)
+            for nb in (1, 3, 7, -1):
+                fq.debug_max_blocks(nb)
+                _run_gemm_case(env, case, (0.0, 0.3, 0.5, 1.0))
+    finally:
+        fq.debug_force_tile(-1)
+        fq.debug_max_blocks(0)
+
+
 def test_gemm_saturating_inputs(env):
     # activations far beyond the calibrated range: the clamp of the lowering is active everywhere
     torch, oracle, fq, dev = env
