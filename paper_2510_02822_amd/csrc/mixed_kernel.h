@@ -13,13 +13,20 @@
 // Work decomposition: a block of four waves (one per SIMD) owns a BM x BN output tile; the reduction
 // runs in K-steps of 64 elements (two 32-channel units, each independently 4-bit or 8-bit), each
 // K-step being two k-halves of v_mfma_i32_32x32x32_i8 (a single wave per SIMD keeps the matrix pipe
-// full with this instruction shape; the 16x16x64 shape needs two).  Tiles travel
-//     global --buffer_load--> registers --(bit-lower / expand)--> LDS ring of three stages --> MFMA fragments,
-// as four 16-byte "k-planes" per stage so that a fragment read is 32 lanes x 16 contiguous bytes.
+// full with this instruction shape; the 16x16x64 shape needs two).  Operand tiles live in an LDS ring of
+// four stages and arrive there, three K-steps ahead of their use, by one of two routes:
+//   * straight from global memory (buffer loads that write LDS, no register hop): every weight tile that
+//     needs no arithmetic (8-bit units; 4-bit units from the position-expanded copy) and the activation tile
+//     of an all-8-bit K-step;
+//   * through registers, where the vector ALU bit-lowers the activations of 4-bit units (and, for few-row
+//     calls, expands packed 4-bit weight codes) before an ordinary LDS store.
+// A weight tile is stored as four 16-byte "k-planes" of BN rows (the global layout is the same, so a wave
+// copies 64 rows of a plane with one instruction); an activation tile is stored row-major, 64 bytes per row,
+// with the four 16-byte pieces of a row permuted by (row / 4) % 4, which makes both the 64-byte-coalesced
+// global reads and the 16-byte-per-lane MFMA fragment reads free of bank conflicts.
 // The loop is software-pipelined by hand: every MFMA is followed by at most a few memory or VALU
-// instructions (fragment reads for the next k-half into a second register set, LDS stores of the tile
-// two steps ahead, global loads of the tile three steps ahead), pinned in place with scheduling
-// fences, so that loads are spread evenly over the texture-address unit and no wave waits on LDS.
+// instructions (fragment reads for the next k-half into a second register set, loads of the tile three steps
+// ahead, lowering and LDS stores of the register-routed pieces), pinned in place with scheduling fences.
 // The MFMA "A" operand is the weight fragment and "B" the activation fragment, so a lane ends up with
 // four consecutive output channels of one output row.
 //
@@ -129,27 +136,33 @@ __device__ __forceinline__ v4i lower16v(v4i x, v2s lo2, v2s hi2, uint32_t mask)
     return r;
 }
 
+// 16 bytes per lane from a buffer straight into LDS: lane l of the wave writes dst + 16 l (dst wave-uniform).
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+__device__ __forceinline__ void lds_load16(__amdgpu_buffer_rsrc_t r, unsigned char *dst, int voff, int soff)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)dst, 16, voff, soff, 0, 0);
+}
+
 template <int WAVES_M, int WAVES_N, int TM, int TN>
 struct Cfg {
     static_assert(WAVES_M * WAVES_N == 4, "four waves per block");
     static constexpr int NT = 256;
     static constexpr int BM = WAVES_M * TM * 32;
     static constexpr int BN = WAVES_N * TN * 32;
-    static constexpr int XL = (BM * 4 + NT - 1) / NT;   // 16-byte activation chunks per thread per K-step
-    static constexpr int WL8 = (BN * 2 + NT - 1) / NT;  // 16-byte chunks per thread per 8-bit unit
-    static constexpr int WL4 = (BN + NT - 1) / NT;      // 16-byte chunks per thread per 4-bit unit
-    static constexpr int NS = XL + 2 * WL8;             // staging registers (x4 dwords) per thread
-    static constexpr int XROWS = XL * (NT / 4);         // rows staged per K-step (>= BM; the excess reads as zero)
-    static constexpr int XPS = (XROWS + 2) * 16;        // bytes per activation k-plane (+2 chunks staggers the planes over the banks)
-    static constexpr int WPS = (BN + 2) * 16;
-    static constexpr int STAGE = 4 * XPS + 4 * WPS;
-    static constexpr int NSTAGE = 3;
+    static_assert(BN % 64 == 0, "a wave copies 64 weight rows per instruction");
+    static constexpr int XI = (BM + 63) / 64;           // activation pieces per thread per K-step (a wave instruction covers 16 rows)
+    static constexpr int XROWS = XI * 64;               // rows staged per K-step (>= BM; the excess reads as zero)
+    static constexpr int WI = BN / 64;                  // direct weight loads per wave per K-step (4 planes x BN rows / 64 / 4 waves)
+    static constexpr int WL4 = (BN + NT - 1) / NT;      // packed-code pieces per thread per 4-bit unit
+    static constexpr int XBYTES = XROWS * 64;           // activation tile, row-major
+    static constexpr int WPS = (BN + 2) * 16;           // bytes per weight k-plane (+2 pieces staggers the planes over the banks)
+    static constexpr int STAGE = XBYTES + 4 * WPS;
+    static constexpr int NSTAGE = 4;
     // activation positions of up to 160 groups; scale and bias of the columns of two consecutive tiles
     static constexpr int TABLE = 640 + 2 * (2 * BN * 4);
     static constexpr int RING = NSTAGE * STAGE;
     // A block may walk several output tiles.  Not for the largest tiles: their accumulators fill the register
-    // file, and the values that would have to stay live across an epilogue (staged K-step, first fragments of
-    // the next tile) do not fit beside them.
+    // file, and the values that would have to stay live across an epilogue do not fit beside them.
     static constexpr bool MULTI = TM * TN <= 10;
     static constexpr int LDS_BYTES = RING + TABLE;
 };
@@ -164,18 +177,21 @@ enum StepMode { kMode88 = 0, kMode44 = 1, kMode48 = 2, kModeNone = 3 };
 #define FQ_TS(v)
 #endif
 
-// Tiles with at most 128 accumulator registers per lane are compiled for two blocks per CU (two waves per
-// SIMD): one block's prologue, epilogue and 4-bit VALU work then overlap the other's matrix work.
+// Tiles with at most 128 accumulator registers per lane are compiled for two blocks per CU where LDS allows:
+// one block's prologue and epilogue then overlap the other's matrix work.
 //
 // PACKED4 selects where the weights of a 4-bit unit come from: the packed codes (half the bytes, expanded in
-// registers with vector-ALU work: for memory-bound shapes) or the copy that is already expanded (staged
+// registers with vector-ALU work: for memory-bound shapes) or the copy that is already expanded (copied
 // exactly like an 8-bit unit: for compute-bound shapes).
 template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV, bool PACKED4>
 __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const GemmParams p)
 {
     using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
-    constexpr int NT = C_::NT, BM = C_::BM, BN = C_::BN, XPS = C_::XPS, WPS = C_::WPS, STAGE = C_::STAGE;
-    constexpr int XL = C_::XL, WL8 = C_::WL8, WL4 = C_::WL4, NS = C_::NS;
+    constexpr int NT = C_::NT, BM = C_::BM, BN = C_::BN, XBYTES = C_::XBYTES, WPS = C_::WPS, STAGE = C_::STAGE;
+    constexpr int XI = C_::XI, WI = C_::WI, WL4 = C_::WL4;
+    constexpr int NP = PACKED4 ? 2 * WL4 : 0;   // packed-code pieces per thread per K-step
+    constexpr int NSR = XI + NP;                // staging registers (x4 dwords) per thread
+    constexpr int NI = XI + WI + NP;            // staging items per K-step: activation pieces, direct weight loads, packed pieces
     constexpr int NF = TM + TN;   // fragments per k-half
     constexpr int NMF = TM * TN;  // MFMAs per k-half
     extern __shared__ __align__(16) unsigned char lds[];
@@ -183,7 +199,8 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     float *const cs_tab = reinterpret_cast<float *>(sa_tab + 640);  // two copies (tile parity) of [BN] scales + [BN] biases
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: lives in a scalar register
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 #ifdef FLEXIQ_TIMING
     long long tq0 = __builtin_readcyclecounter(), tqa = 0, tqb = 0, tqc = 0, tqd = 0;
@@ -229,9 +246,12 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     const int8_t *xbase;  // origin and size of the activation window of the tile being LOADED
     int xwin;
     int ld_n0 = n0;       // and its first column
-    const int xq = tid & 3;   // k-plane of this thread's activation chunks; unit xq >> 1
-    int xvoff[XL];            // linear: byte offset inside the window; conv: xq * 16
-    int xh0[XL], xw0[XL], xpix[XL];  // conv: top-left input coordinate, pixel index of the image origin (-1: no row)
+    // Activation piece j of a thread: row 16 (wave + 4 j) + lane / 4 of the tile, LDS slot lane % 4 of that row,
+    // which holds k-plane xq = slot ^ ((row / 4) % 4); (row / 4) % 4 = (lane / 16) % 4 for every j.
+    const int xrow = lane >> 2;
+    const int xq = (lane & 3) ^ ((lane >> 4) & 3);   // k-plane of this thread's activation pieces; unit xq >> 1
+    int xvoff[XI];                    // linear: byte offset inside the window; conv: xq * 16
+    int xh0[XI], xw0[XI], xpix[XI];   // conv: top-left input coordinate, pixel index of the image origin (-1: no row)
     if (CONV) {
         const int64_t hw_out = (int64_t)p.Ho * p.Wo;
         const int64_t img0 = m0 / hw_out;
@@ -241,8 +261,8 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
         xbase = p.X + img0 * img_bytes;
         xwin = (int)win;
 #pragma unroll
-        for (int j = 0; j < XL; ++j) {
-            const int row = (tid >> 2) + j * (NT / 4);
+        for (int j = 0; j < XI; ++j) {
+            const int row = 16 * (wave + 4 * j) + xrow;
             const bool ok = row < rows_valid;
             const int64_t mm = ok ? m0 + row : m0;
             const int wo = (int)(mm % p.Wo);
@@ -257,8 +277,8 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
         xbase = p.X + m0 * p.C;
         xwin = rows_valid * p.C;
 #pragma unroll
-        for (int j = 0; j < XL; ++j) {
-            const int row = (tid >> 2) + j * (NT / 4);
+        for (int j = 0; j < XI; ++j) {
+            const int row = 16 * (wave + 4 * j) + xrow;
             xvoff[j] = row * p.C + xq * 16;  // rows >= rows_valid fall outside the window: zeros
             xh0[j] = xw0[j] = xpix[j] = 0;
         }
@@ -280,22 +300,22 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
         }
     };
     set_pending(ctile + (int)gridDim.x);
-    const int xpad = (p.CU & 1) && xq >= 2 ? 32 : 0;
-    const int x_lds = xq * XPS + (tid >> 2) * 16;
-    int w8voff[WL8], w8lds[WL8];
+    const int x_lds = (16 * wave) * 64 + lane * 16;   // piece j adds 64 rows: j * 4096
+    int wvoff[WI];   // per-lane offset of direct weight load j: k-plane parity, 64-row block, row = lane
 #pragma unroll
-    for (int j = 0; j < WL8; ++j) {
-        const int i = tid + j * NT;
-        const int q2 = i / BN, row = i - q2 * BN;
-        w8voff[j] = (q2 * p.Npad + row) * 16;
-        w8lds[j] = 4 * XPS + q2 * WPS + row * 16;
+    for (int j = 0; j < WI; ++j) {
+        const int idx = wave + 4 * j;
+        const int pl = idx / (BN / 64), blk = idx % (BN / 64);
+        wvoff[j] = ((pl & 1) * p.Npad + blk * 64 + lane) * 16;
     }
+    // Direct weight load j of this wave: index wave + 4 j over (k-plane, block of 64 rows); scalar values.
+    // Packed pieces: row tid + j * NT of the tile (one thread per row).
     int w4voff[WL4], w4lds[WL4];
 #pragma unroll
     for (int j = 0; j < WL4; ++j) {
         const int row = tid + j * NT;
         w4voff[j] = row * 16;
-        w4lds[j] = 4 * XPS + row * 16;
+        w4lds[j] = XBYTES + row * 16;
     }
 
     FQ_TS(tqa);
@@ -351,118 +371,128 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     };
     auto it_mode = [&]() { return it_phase == 0 ? kMode44 : (it_phase == 1 ? kMode48 : (it_phase == 2 ? kMode88 : kModeNone)); };
 
-    // ---- staging registers and the descriptor of the tile they hold
-    v4i sr[NS];
+    // ---- staging registers (register-routed pieces only) and the descriptor of the tile they hold
+    v4i sr[NSR > 0 ? NSR : 1];
     int wsh[2][WL4];
     int st_c64 = 0;   // c64 of the tile in the staging registers
 
-    // global -> registers, chunk i of the tile the iterator points at
-    auto gload = [&](v4i(&sr)[NS], int(&wsh)[2][WL4], int i, int mode) {
+    // Item i of the K-step the iterator points at: load it, either straight into `stage` or into registers.
+    // (The K offset of an activation piece goes into the per-lane offset, which the buffer range check covers:
+    // what the pad unit of an odd unit count would read past the end of the window's last row comes back as zero.)
+    const int ustride = 32 * p.Npad;   // bytes between the units of the 8-bit weight layout
+    auto gload = [&](v4i(&sr)[NSR > 0 ? NSR : 1], int(&wsh)[2][WL4], int i, int mode, unsigned char *stage) {
         const int c64 = it_c64;
-        if (i < XL) {
+        if (i < XI) {
             const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)xbase, 0, xwin, kRsrcFlags);
-            // pad unit of an odd unit count: its weights are zero; read the unit before it again instead of
-            // the 32 bytes after the row, which for the last row may lie outside the tensor
-            const int back = c64 == SP - 1 ? xpad : 0;
+            int off;
             if (CONV) {
                 const int hi = xh0[i] + it_dy, wi = xw0[i] + it_dx;
                 const bool ok = hi >= 0 && hi < p.H && wi >= 0 && wi < p.Wd && xpix[i] >= 0;
-                const int off = ok ? (xpix[i] + hi * p.Wd + wi) * p.C + xvoff[i] - back : (int)0x80000000;
-                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, c64 * 64, 0);
+                off = ok ? (xpix[i] + hi * p.Wd + wi) * p.C + xvoff[i] + c64 * 64 : (int)0x80000000;
             } else {
-                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, xvoff[i] - back, c64 * 64, 0);
+                off = xvoff[i] + c64 * 64;
             }
-        } else {
-            const int h = (i - XL) / WL8, j = (i - XL) % WL8;
-            const int u = it_tap * (2 * SP) + 2 * c64 + h;
+            if (mode == kMode88)
+                lds_load16(rx, stage + (16 * (wave + 4 * i)) * 64, off, 0);
+            else
+                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
+        } else if (i < XI + WI) {
+            const int j = i - XI;
+            const int idx = wave + 4 * j;                       // (k-plane, 64-row block) of this copy
+            const int pl = idx / (BN / 64), blk = idx % (BN / 64);
+            const int h = pl >> 1;                              // unit of the K-step
             const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
-            if (four && PACKED4) {
-                if (j < WL4) {
-                    const int g = (2 * c64 + h) >> p.gs_shift;
-                    sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw4, w4voff[j], u * 16 * p.Npad + ld_n0 * 16, 0);
-                    wsh[h][j] = __builtin_amdgcn_raw_buffer_load_b8(rws, w4voff[j] >> 4, g * p.Npad + ld_n0, 0);
-                }
-            } else if (four) {
-                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw4x, w8voff[j], u * 32 * p.Npad + ld_n0 * 16, 0);
+            const int wbase = (it_tap * (2 * SP) + 2 * c64) * ustride + ld_n0 * 16;   // same for every item of the step
+            const int soff = wbase + (h ? ustride : 0);
+            unsigned char *dst = stage + XBYTES + pl * WPS + blk * 1024;
+            if (four) {
+                if (!PACKED4) lds_load16(rw4x, dst, wvoff[j], soff);
             } else {
-                sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rw8, w8voff[j], u * 32 * p.Npad + ld_n0 * 16, 0);
+                lds_load16(rw8, dst, wvoff[j], soff);
+            }
+        } else if (PACKED4) {
+            const int h = (i - XI - WI) / WL4, j = (i - XI - WI) % WL4;
+            const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
+            if (four && (BN % NT == 0 || tid + j * NT < BN)) {
+                const int u = it_tap * (2 * SP) + 2 * c64 + h;
+                const int g = (2 * c64 + h) >> p.gs_shift;
+                sr[XI + h * WL4 + j] = __builtin_amdgcn_raw_buffer_load_b128(rw4, w4voff[j], u * 16 * p.Npad + ld_n0 * 16, 0);
+                wsh[h][j] = __builtin_amdgcn_raw_buffer_load_b8(rws, w4voff[j] >> 4, g * p.Npad + ld_n0, 0);
             }
         }
     };
-    // per-step constants of the activation bit-lowering for this thread's unit (position from LDS)
+    // per-step constants of the activation bit-lowering for this thread's unit.  The position comes from the
+    // LDS table; sa_fetch() is called a step ahead of lower_setup() so that no step starts by waiting for LDS.
     v2s lo2, hi2;
     uint32_t amask;
-    auto lower_setup = [&](int c64) {
-        const int sa = reinterpret_cast<const int *>(sa_tab)[(2 * c64 + (xq >> 1)) >> p.gs_shift];
+    int sa_next = 0;
+    auto sa_fetch = [&](int c64) { sa_next = reinterpret_cast<const int *>(sa_tab)[(2 * c64 + (xq >> 1)) >> p.gs_shift]; };
+    auto lower_setup = [&]() {
+        const int sa = sa_next;
         const short lo = (short)((-(8 << sa)) << 8);
         const short hi = (short)((((8 << sa) - 1) << 8) | 0xFF);
         lo2 = (v2s){lo, lo};
         hi2 = (v2s){hi, hi};
         amask = 0x01010101u * ((0xFFu << sa) & 0xFFu);
     };
-    // registers -> LDS stage, chunk i of the staged tile, bit-lowering / expanding the 4-bit units
-    // registers -> LDS stage for chunk i of the staged tile.  The VALU work of the 4-bit units (bit-lowering
-    // of activations, expansion of 4-bit weight codes) is cut into four pieces per chunk, lmicro(i, 0..3),
-    // so that it can be spread over the MFMA stream and co-issue with it; lstore(i) then writes the chunk.
-    uint32_t wexp[8];   // expanded weights of the 4-bit chunk in progress
-    auto lmicro = [&](v4i(&sr)[NS], int(&wsh)[2][WL4], int i, int k, int mode) {
-        if (i < XL) {
+    // Register-routed pieces of the staged K-step -> LDS.  The VALU work of the 4-bit units (bit-lowering
+    // of activations, expansion of packed weight codes) is cut into four pieces per item, lmicro(i, 0..3),
+    // so that it can be spread over the MFMA stream and co-issue with it; lstore(i) then writes the item.
+    uint32_t wexp[8];   // expanded weights of the packed piece in progress
+    auto lmicro = [&](v4i(&sr)[NSR > 0 ? NSR : 1], int(&wsh)[2][WL4], int i, int k, int mode) {
+        if (i < XI) {
             if (mode == kMode44) {
                 sr[i][k] = (int)lower4((uint32_t)sr[i][k], lo2, hi2, amask);
             } else if (mode == kMode48) {
                 const int l = (int)lower4((uint32_t)sr[i][k], lo2, hi2, amask);
                 sr[i][k] = (xq >> 1) == 0 ? l : sr[i][k];
             }
-        } else {
-            const int h = (i - XL) / WL8, j = (i - XL) % WL8;
+        } else if (PACKED4 && i >= XI + WI) {
+            const int h = (i - XI - WI) / WL4, j = (i - XI - WI) % WL4;
             const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
-            if (PACKED4 && four && j < WL4) {
+            if (four) {
                 const int sw = wsh[h][j];
                 const short t = (short)(4 - sw);
                 const uint32_t mask = 0x01010101u * ((0xFFu << sw) & 0xFFu);
-                const uint32_t w = (uint32_t)sr[i][k];
+                const uint32_t w = (uint32_t)sr[XI + h * WL4 + j][k];
                 wexp[2 * k] = expand_hi(w << 4, t, mask);  // low halves: channels 8k .. 8k+3
                 wexp[2 * k + 1] = expand_hi(w, t, mask);   // high halves: channels 8k+4 .. 8k+7
             }
         }
     };
-    auto lstore = [&](v4i(&sr)[NS], int i, int mode, unsigned char *stage) {
-        if (i < XL) {
-            *reinterpret_cast<v4i *>(stage + x_lds + i * (NT / 4) * 16) = sr[i];
-        } else {
-            const int h = (i - XL) / WL8, j = (i - XL) % WL8;
+    auto lstore = [&](v4i(&sr)[NSR > 0 ? NSR : 1], int i, int mode, unsigned char *stage) {
+        if (i < XI) {
+            if (mode == kMode44 || mode == kMode48) *reinterpret_cast<v4i *>(stage + x_lds + i * 4096) = sr[i];
+        } else if (PACKED4 && i >= XI + WI) {
+            const int h = (i - XI - WI) / WL4, j = (i - XI - WI) % WL4;
             const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
-            if (PACKED4 && four) {
-                if (j < WL4 && (BN % NT == 0 || tid + j * NT < BN)) {
-                    *reinterpret_cast<v4i *>(stage + (2 * h) * WPS + w4lds[j]) =
-                        (v4i){(int)wexp[0], (int)wexp[1], (int)wexp[2], (int)wexp[3]};
-                    *reinterpret_cast<v4i *>(stage + (2 * h + 1) * WPS + w4lds[j]) =
-                        (v4i){(int)wexp[4], (int)wexp[5], (int)wexp[6], (int)wexp[7]};
-                }
-            } else {
-                if ((2 * BN) % NT == 0 || tid + j * NT < 2 * BN)
-                    *reinterpret_cast<v4i *>(stage + (2 * h) * WPS + w8lds[j]) = sr[i];
+            if (four && (BN % NT == 0 || tid + j * NT < BN)) {
+                *reinterpret_cast<v4i *>(stage + (2 * h) * WPS + w4lds[j]) = (v4i){(int)wexp[0], (int)wexp[1], (int)wexp[2], (int)wexp[3]};
+                *reinterpret_cast<v4i *>(stage + (2 * h + 1) * WPS + w4lds[j]) = (v4i){(int)wexp[4], (int)wexp[5], (int)wexp[6], (int)wexp[7]};
             }
         }
     };
 
     const int frag_half = lane >> 5, frag_row = lane & 31;
-    const int xs_frag = frag_half * XPS + (wm * TM * 32 + frag_row) * 16;
-    const int ws_frag = 4 * XPS + frag_half * WPS + (wn * TN * 32 + frag_row) * 16;
+    const int fsw = (frag_row >> 2) & 3;
+    const int xs_frag0 = (wm * TM * 32 + frag_row) * 64 + ((frag_half ^ fsw) * 16);          // k-half 0
+    const int xs_frag1 = (wm * TM * 32 + frag_row) * 64 + (((2 + frag_half) ^ fsw) * 16);    // k-half 1
+    const int ws_frag = XBYTES + frag_half * WPS + (wn * TN * 32 + frag_row) * 16;
     // fragments in order of need: w0, x0, w1..w(TN-1), x1..x(TM-1); f[0..TN) weights, f[TN..NF) activations
     auto forder = [](int i) { return i == 0 ? 0 : (i == 1 ? TN : (i <= TN ? i - 1 : i)); };
     auto fread = [&](v4i(&f)[NF], int i, const unsigned char *stage, int kh) {
         if (i < TN) f[i] = *reinterpret_cast<const v4i *>(stage + ws_frag + kh * 2 * WPS + i * 512);
-        else f[i] = *reinterpret_cast<const v4i *>(stage + xs_frag + kh * 2 * XPS + (i - TN) * 512);
+        else f[i] = *reinterpret_cast<const v4i *>(stage + (kh ? xs_frag1 : xs_frag0) + (i - TN) * 2048);
     };
     v4i fA[NF], fB[NF];
 
-    // ---- prologue: the loads of tiles 0, 1 and 2 are all issued before anything waits (tiles 0 and 1 into
-    // registers of their own, tile 2 into the staging registers of the main loop); then the tables and
-    // tiles 0 and 1 go to LDS (stages 0 and 1).
-    int mode_staged = kModeNone;   // mode of the tile in the staging registers
+    // ---- prologue: the loads of K-steps 0, 1 and 2 are all issued before anything waits (straight into
+    // stages 0, 1, 2; the register-routed pieces of steps 0 and 1 into registers of their own, those of
+    // step 2 into the staging registers of the main loop); then the tables and the register-routed pieces of
+    // steps 0 and 1 go to LDS.
+    int mode_staged = kModeNone;   // mode of K-step s+2, whose register-routed pieces sit in the staging registers
     {
-        v4i sp[2][NS];
+        v4i sp[2][NSR > 0 ? NSR : 1];
         int wp[2][2][WL4];
         int pmode[2] = {kModeNone, kModeNone}, pc64[2] = {0, 0};
 #pragma unroll
@@ -471,7 +501,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                 pmode[t] = it_mode();
                 pc64[t] = it_c64;
 #pragma unroll
-                for (int i = 0; i < NS; ++i) gload(sp[t], wp[t], i, pmode[t]);
+                for (int i = 0; i < NI; ++i) gload(sp[t], wp[t], i, pmode[t], lds + t * STAGE);
                 advance();
             }
         }
@@ -479,7 +509,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
             mode_staged = it_mode();
             st_c64 = it_c64;
 #pragma unroll
-            for (int i = 0; i < NS; ++i) gload(sr, wsh, i, mode_staged);
+            for (int i = 0; i < NI; ++i) gload(sr, wsh, i, mode_staged, lds + 2 * STAGE);
             advance();
         }
         FQ_TS(tqb);
@@ -494,9 +524,12 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             if (t < steps) {
-                if (pmode[t] != kMode88) lower_setup(pc64[t]);
+                if (pmode[t] != kMode88) {
+                    sa_fetch(pc64[t]);
+                    lower_setup();
+                }
 #pragma unroll
-                for (int i = 0; i < NS; ++i) {
+                for (int i = 0; i < NI; ++i) {
 #pragma unroll
                     for (int k = 0; k < 4; ++k) lmicro(sp[t], wp[t], i, k, pmode[t]);
                     lstore(sp[t], i, pmode[t], lds + t * STAGE);
@@ -504,6 +537,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
             }
         }
     }
+    if (mode_staged == kMode44 || mode_staged == kMode48) sa_fetch(st_c64);
     FQ_TS(tqd);
     v16i acc[TN][TM];
     auto zero_acc = [&]() {
@@ -516,6 +550,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     };
     zero_acc();
 
+    __builtin_amdgcn_s_waitcnt(0x0070);   // every direct load of the prologue has landed
     __builtin_amdgcn_s_waitcnt(0xc07f);
     __builtin_amdgcn_s_barrier();
 #pragma unroll
@@ -525,26 +560,25 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     long long tq1 = __builtin_readcyclecounter(), t_epi = 0;
     int n_tiles = 0;
 #endif
-    // ---- main loop.  Step s computes tile s from stage s % 3 while storing tile s+2 (staged in
-    // registers during step s-1) into stage (s+2) % 3 and loading tile s+3 into the registers: store
-    // of chunk j, then load of chunk j, spread over the whole step.  `ma` is the mode of the staged
-    // tile (kModeNone: nothing to store), `mb` the mode of the tile to load (kModeNone: none left);
-    // both are compile-time constants in the steady-state loops and run-time values elsewhere.
+    // ---- main loop.  Step s computes K-step s from stage s % 4 while K-step s+3 is loaded (straight into stage
+    // (s+3) % 4, or into the staging registers) and the register-routed pieces of K-step s+2 (loaded during step
+    // s-1) are lowered / expanded and stored into stage (s+2) % 4.  `ma` is the mode of K-step s+2 (kModeNone:
+    // there is none), `mb` the mode of K-step s+3 (kModeNone: nothing left to load); both are compile-time
+    // constants in the steady-state loops and run-time values elsewhere.
     // The K-steps of the block's successive output tiles form one sequence: while the last steps of an
     // output tile are computed, the first K-steps of the next one are already being loaded and staged.
-    int st0 = 0;  // stage of tile s
+    int o_cur = 0, o_nx1 = STAGE, o_nx2 = 2 * STAGE, o_nx3 = 3 * STAGE;   // byte offsets of the stages of K-steps s .. s+3
     int s = 0;    // K-step within the output tile being computed
     constexpr int kStageSlots = 2 * NMF > 2 ? 2 * NMF - 2 : 1;    // slots that carry staging work
     constexpr int kAdvanceSlot = 2 * NMF > 2 ? 2 * NMF - 2 : 0;   // slot after which the load iterator moves on
     auto step = [&](auto ma_, auto mb_, auto h1_) {
         const int ma = ma_, mb = mb_;
         const bool h1 = h1_;
-        const int st1 = st0 == 2 ? 0 : st0 + 1, st2 = st1 == 2 ? 0 : st1 + 1;
-        const unsigned char *cur = lds + st0 * STAGE;
-        const unsigned char *nx1 = lds + st1 * STAGE;
-        unsigned char *nx2 = lds + st2 * STAGE;
-        const int c64_store = st_c64;
-        if (ma == kMode44 || ma == kMode48) lower_setup(c64_store);
+        const unsigned char *cur = lds + o_cur;
+        const unsigned char *nx1 = lds + o_nx1;
+        unsigned char *nx2 = lds + o_nx2;
+        unsigned char *nx3 = lds + o_nx3;
+        if (ma == kMode44 || ma == kMode48) lower_setup();   // from the position fetched during the previous step
         if (mb != kModeNone) st_c64 = it_c64;
         FQ_SB();
 #pragma unroll
@@ -565,37 +599,74 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                             else if (h1) fread(fA, forder(k), nx1, 0);
                             FQ_SB();
                         }
-                    // staging chunk i: four pieces of VALU work, the LDS store, then the global load of the
-                    // next tile's chunk i into the same registers; position t = 6 i + k, spread over the step's
-                    // slots but the last two, where the scalar iterator update runs in the shadow of the MFMAs
+                    // Staging work, spread over the step's slots but the last two (where the scalar iterator update
+                    // runs in the shadow of the MFMAs).  An activation piece or packed-code piece i has six events:
+                    // four pieces of VALU work and the LDS store of K-step s+2's copy, then the load of K-step s+3's
+                    // into the same registers (or straight into LDS).  Each of the three item groups is spread evenly
+                    // over the slots on its own, so VALU-heavy and load-only events alternate.
 #pragma unroll
-                    for (int t = 0; t < 6 * NS; ++t)
-                        if (t * kStageSlots / (6 * NS) == g) {
+                    for (int t = 0; t < 6 * XI; ++t)
+                        if (t * kStageSlots / (6 * XI) == g) {
                             const int i = t / 6, k = t % 6;
                             if (k < 4) {
                                 if (ma == kMode44 || ma == kMode48) lmicro(sr, wsh, i, k, ma);
                             } else if (k == 4) {
 #ifndef FQ_EXP_NOLSTORE
-                                if (ma != kModeNone) lstore(sr, i, ma, nx2);
+                                if (ma == kMode44 || ma == kMode48) lstore(sr, i, ma, nx2);
 #endif
                             } else {
 #ifndef FQ_EXP_NOGLOAD
-                                if (mb != kModeNone) gload(sr, wsh, i, mb);
+                                if (mb != kModeNone) gload(sr, wsh, i, mb, nx3);
 #endif
                             }
                             FQ_SB();
                         }
+#pragma unroll
+                    for (int j = 0; j < WI; ++j)
+                        if ((2 * j + 1) * kStageSlots / (2 * WI) == g) {
+#ifndef FQ_EXP_NOGLOAD
+                            if (mb != kModeNone) gload(sr, wsh, XI + j, mb, nx3);
+#endif
+                            FQ_SB();
+                        }
+#pragma unroll
+                    for (int t = 0; t < 6 * NP; ++t)
+                        if (t * kStageSlots / (6 * (NP > 0 ? NP : 1)) == g) {
+                            const int i = XI + WI + t / 6, k = t % 6;
+                            if (k < 4) {
+                                if (ma == kMode44 || ma == kMode48) lmicro(sr, wsh, i, k, ma);
+                            } else if (k == 4) {
+                                if (ma == kMode44 || ma == kMode48) lstore(sr, i, ma, nx2);
+                            } else {
+                                if (mb != kModeNone) gload(sr, wsh, i, mb, nx3);
+                            }
+                            FQ_SB();
+                        }
                     if (g == kAdvanceSlot && mb != kModeNone) {
+                        if (mb == kMode44 || mb == kMode48) sa_fetch(st_c64);   // position for the next step's lowering
                         advance();
                         FQ_SB();
                     }
                 }
+        // The direct loads of the previous step (K-step s+2) must have landed before the barrier publishes them;
+        // this step's own loads may stay in flight.  Their number is known at compile time where every wave
+        // issues the same loads; otherwise wait for everything.
+        if (!PACKED4 && (mb == kMode88 || mb == kMode44 || mb == kMode48))
+            __builtin_amdgcn_s_waitcnt(0x0070 | ((XI + WI) & 15) | (((XI + WI) >> 4) << 14));
+        else
+            __builtin_amdgcn_s_waitcnt(0x0070);
         __builtin_amdgcn_s_waitcnt(0xc07f);  // this wave's LDS stores and fragment reads are complete
 #ifndef FQ_EXP_NOBARRIER
         __builtin_amdgcn_s_barrier();
 #endif
         FQ_SB();
-        st0 = st1;
+        {
+            const int t = o_cur;
+            o_cur = o_nx1;
+            o_nx1 = o_nx2;
+            o_nx2 = o_nx3;
+            o_nx3 = t;
+        }
         ++s;
         mode_staged = mb;
     };
@@ -713,19 +784,22 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     // loop itself exactly, instead of waiting for all of them before the first LDS store of every step.)
     for (;;) {
         const bool more_tiles = C_::MULTI && !CONV && ctile + (int)gridDim.x < total_tiles;
-        __builtin_amdgcn_s_waitcnt(0x0070);
-        while (s < steps && mode_staged == kMode44 && it_phase == 0) step(M44{}, M44{}, T_{});
-        while (s < steps && mode_staged != kModeNone && it_phase != 3 &&
-               !(mode_staged == kMode44 && it_phase == 0) && !(mode_staged == kMode88 && it_phase == 2))
-            step(mode_staged, (int)it_mode(), true);
-        __builtin_amdgcn_s_waitcnt(0x0070);
-        while (s < steps && mode_staged == kMode88 && it_phase == 2) step(M88{}, M88{}, T_{});
-        while (s < steps && mode_staged == kMode88 && it_phase == 3) step(M88{}, MNone{}, T_{});
-        while (s < steps && mode_staged == kMode44 && it_phase == 3) step(M44{}, MNone{}, T_{});
-        while (s < steps && mode_staged == kMode48 && it_phase == 3) step(mode_staged, (int)kModeNone, true);
-        while (s + 1 < steps && mode_staged == kModeNone) step(MNone{}, MNone{}, T_{});
-        while (s < steps && mode_staged == kModeNone) step(MNone{}, MNone{}, F_{});
-        if (s < steps) continue;
+        // Nothing in flight (in particular none of the previous epilogue's stores) when the K loop starts: the
+        // compiler can then count the register-routed loads of the 4-bit loops exactly.
+        if (n4 + mixed > 0 || PACKED4) __builtin_amdgcn_s_waitcnt(0x0070);
+        while (s < steps) {
+            while (s < steps && mode_staged == kMode44 && it_phase == 0) step(M44{}, M44{}, T_{});
+            while (s < steps && mode_staged == kMode44 && it_phase == 2) step(M44{}, M88{}, T_{});   // at most once
+            while (s < steps && mode_staged == kMode88 && it_phase == 2) step(M88{}, M88{}, T_{});
+            while (s < steps && mode_staged == kMode88 && it_phase == 0) step(M88{}, M44{}, T_{});   // next tile begins
+            while (s < steps && mode_staged != kModeNone && it_phase != 3 && (mode_staged == kMode48 || it_phase == 1))
+                step(mode_staged, (int)it_mode(), true);                                             // mixed steps
+            while (s < steps && mode_staged == kMode88 && it_phase == 3) step(M88{}, MNone{}, T_{});
+            while (s < steps && mode_staged == kMode44 && it_phase == 3) step(M44{}, MNone{}, T_{});
+            while (s < steps && mode_staged == kMode48 && it_phase == 3) step(mode_staged, (int)kModeNone, true);
+            while (s + 1 < steps && mode_staged == kModeNone) step(MNone{}, MNone{}, T_{});
+            while (s < steps && mode_staged == kModeNone) step(MNone{}, MNone{}, F_{});
+        }
 
 #ifdef FLEXIQ_TIMING
         const long long te0 = __builtin_readcyclecounter();
