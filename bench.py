@@ -34,8 +34,8 @@ RATIOS = (0.0, 0.25, 0.5, 0.75, 1.0)
 
 # Bytes per launch of the GEMM kernel on the default workload (fc1, int8 output) measured with
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the readings of a 256 MiB device copy (fetch x2.0,
-# write x1.0): median fetch 22.2 MB + write 19.4 MB.  See profiles/k_mixed_vitb_fc1_hbm_traffic.txt.
-MEASURED_TRAFFIC_BYTES = {("fc1", "q"): 41.6e6}
+# write x1.0): median fetch 25.3 MB + write 19.8 MB.  See profiles/k_mixed_vitb_fc1_hbm_traffic.txt.
+MEASURED_TRAFFIC_BYTES = {("fc1", "q"): 45.1e6}
 
 
 def log(*a):
@@ -44,7 +44,7 @@ def log(*a):
 
 def algorithmic_bytes(M, N, K, r, out_bytes_per_elem=1):
     """Bytes one call must move: int8 activations, weights (1 B per 8-bit channel, 1/2 B per 4-bit
-    channel), position table and scales, output."""
+    channel when the packed codes are streamed), position table and scales, output."""
     return M * K + N * K * (1.0 - r / 2.0) + N * (K // 32) + 8 * N + M * N * out_bytes_per_elem
 
 

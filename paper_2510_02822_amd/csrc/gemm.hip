@@ -27,9 +27,12 @@ static int g_force_packed = -1;
 static int g_max_blocks = 0;
 static int g_last_shape = -1, g_last_blocks = 0, g_last_resident = 0;
 
-// Up to this many output rows the weights dominate the traffic and the call is bound by memory: the 4-bit
-// units are then streamed as packed codes (half the bytes); above it from the expanded copy.
-constexpr int64_t kPackedMaxRows = 256;
+// Calls with at most this many output rows stream the 4-bit units as packed codes (half the weight bytes, expanded
+// in registers); larger ones use the expanded copy.  Measured on MI355X the packed route never wins with this
+// kernel: a call with few rows has too few blocks to be limited by memory bandwidth, and pays for the expansion
+// in its (latency-bound) K loop.  It therefore stays off by default (-1) and is kept, parity-tested, for a
+// split-K small-batch kernel; flexiq_debug_force_packed4(1) selects it.
+constexpr int64_t kPackedMaxRows = -1;
 
 static int num_cu()
 {
