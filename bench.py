@@ -151,6 +151,33 @@ def main():
         per_r_us[r] = float(np.median(ts))
         del g
 
+    # run-time extraction positions (Section 4.1, dynamic option): cost of the OR scan next to the GEMM it serves
+    # (outside the timed region; the paper reports 2-5 % of the layer)
+    dyn = []
+    for r in RATIOS[1:]:
+        fq.flexiq_set_ratio(layer, r)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(10):
+                fq.flexiq_dynamic_positions(layer, Xq)
+                fq.flexiq_mixed_gemm(layer, Xq, out_scale=out_scale, bufs=bufs, **want)
+        g.replay()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(7):
+            a0 = torch.cuda.Event(enable_timing=True)
+            a1 = torch.cuda.Event(enable_timing=True)
+            a0.record()
+            g.replay()
+            a1.record()
+            torch.cuda.synchronize()
+            ts.append(a0.elapsed_time(a1) * 1e3 / 10)
+        both = float(np.median(ts))
+        dyn.append({"r": r, "scan_plus_gemm_us": round(both, 2),
+                    "overhead_frac": round(both / per_r_us[r] - 1.0, 4)})
+        del g
+    fq.flexiq_static_positions(layer)
+
     if args.calib_copy_mib > 0:
         src = torch.empty(args.calib_copy_mib << 20, dtype=torch.int8, device=dev)
         dst = torch.empty_like(src)
@@ -214,7 +241,7 @@ def main():
                                "per step, epilogue=%s" % (args.layer, M, K, N, gs, list(RATIOS),
                                                           {"q": "int8 requant", "y": "fp32 dequant", "acc": "int32 dump"}[args.out]),
                    "M": M, "K": K, "N": N, "group_size": gs, "ratios": list(RATIOS)},
-        "roofline": roofline, "cpu_baseline": cpu, "per_r": per_r, "parity": parity,
+        "roofline": roofline, "cpu_baseline": cpu, "per_r": per_r, "dynamic_positions": dyn, "parity": parity,
     }
     print(json.dumps(line), flush=True)
 

@@ -102,6 +102,25 @@ int flexiq_quantize_act(const float *x, int8_t *q, int64_t n, float scale, void 
 int flexiq_bitlower(const int8_t *src, uint8_t *dst, int64_t rows, int32_t C, int32_t group_size,
                     const uint8_t *shifts, int per_row, int mode, void *stream);
 
+/* Extraction positions of the activations found at run time (Section 4.1, the dynamic option; Section 9
+ * "Finding extraction positions at runtime"): for every channel group that is computed at 4 bits under the
+ * handle's current ratio, the magnitude bits of all its values in X (ones' complement for negative values) are
+ * OR-ed together; with p the highest set bit the position is max(0, p - 2).  Groups beyond the 4-bit range keep
+ * their calibrated position.  The result stays on the device, in the handle, and every later
+ * flexiq_mixed_gemm / flexiq_mixed_conv_implicit call on the handle uses it until flexiq_static_positions() or
+ * the next scan; the scan is ordered on `stream` like any kernel (call it on the stream of the GEMM, with the
+ * activations the GEMM will read).  After flexiq_set_ratio() raises the ratio, scan again.
+ *   X    : dev int8 [rows][C], channels in stored order (rows = tokens, or B*H*W pixels of an NHWC tensor), 16-byte aligned
+ * One kernel, no allocation, no host synchronisation.  rows == 0: every scanned group gets position 0. */
+int flexiq_dynamic_positions(flexiq_layer *layer, const int8_t *X, int64_t rows, void *stream);
+
+/* Back to the calibrated positions of flexiq_quantize_pack (host-side switch, O(1)). */
+int flexiq_static_positions(flexiq_layer *layer);
+
+/* Copies the activation positions that the next GEMM / conv call would use to the host (tests).
+ *   a_shift : host uint8 [G].  Synchronises the device. */
+int flexiq_layer_positions(const flexiq_layer *layer, uint8_t *a_shift);
+
 /* Section 5 step 3, the residual reorder operator: dst[row][j] = src[row][perm[j]] for every row.
  * src, dst: dev int8 [rows][C]; uses the handle's permutation. */
 int flexiq_permute_channels(const flexiq_layer *layer, const int8_t *src, int8_t *dst, int64_t rows, void *stream);

@@ -167,6 +167,17 @@ def act_shifts(range_q_perm, group_size: int) -> np.ndarray:
     return out
 
 
+def dynamic_act_shifts(Xq_perm, group_size: int, G4: int, a_shift_static) -> np.ndarray:
+    """Activation positions found at run time (Section 4.1, dynamic option): for each of the first G4 groups the
+    OR scan of shift_from_values over every value of the group in Xq_perm ([..., C], stored order); the other
+    groups keep the calibrated position."""
+    X = _c(Xq_perm, np.int8).reshape(-1, np.shape(Xq_perm)[-1])
+    out = np.array(a_shift_static, np.uint8).copy()
+    for g in range(G4):
+        out[g] = shift_from_values(X[:, g * group_size:(g + 1) * group_size]) if X.shape[0] else 0
+    return out
+
+
 def weight_shifts(Wq_ntc, group_size: int) -> np.ndarray:
     Wq = _c(Wq_ntc, np.int8)
     N, T, Cc = Wq.shape

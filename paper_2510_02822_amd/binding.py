@@ -31,7 +31,8 @@ def exported_symbols():
     """Names include/flexiq.h declares."""
     return ["flexiq_strerror", "flexiq_last_hip_error", "flexiq_quantize_pack", "flexiq_layer_free",
             "flexiq_layer_info", "flexiq_layer_dump", "flexiq_set_ratio", "flexiq_quantize_act",
-            "flexiq_bitlower", "flexiq_permute_channels", "flexiq_mixed_gemm", "flexiq_mixed_conv_implicit"]
+            "flexiq_bitlower", "flexiq_dynamic_positions", "flexiq_static_positions", "flexiq_layer_positions",
+            "flexiq_permute_channels", "flexiq_mixed_gemm", "flexiq_mixed_conv_implicit"]
 
 
 def load():
@@ -54,6 +55,9 @@ def load():
     L.flexiq_quantize_act.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p]
     L.flexiq_bitlower.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_int,
                                   C.c_int, C.c_void_p]
+    L.flexiq_dynamic_positions.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+    L.flexiq_static_positions.argtypes = [C.c_void_p]
+    L.flexiq_layer_positions.argtypes = [C.c_void_p, C.c_void_p]
     L.flexiq_permute_channels.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     L.flexiq_mixed_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(_Out), C.c_void_p]
     L.flexiq_mixed_conv_implicit.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
@@ -168,6 +172,25 @@ def flexiq_bitlower(src, group_size: int, shifts, per_row: bool, mode: int = 0):
     _check(load().flexiq_bitlower(src.data_ptr(), dst.data_ptr(), rows, Cc, group_size, shifts.data_ptr(),
                                   1 if per_row else 0, mode, _stream()))
     return dst
+
+
+def flexiq_dynamic_positions(layer: Layer, X) -> None:
+    """Scan X (int8, [..., C] contiguous, stored channel order) for the run-time extraction positions of the
+    groups that are 4-bit under the current ratio; later GEMM / conv calls on the handle use them."""
+    import torch
+    assert X.dtype == torch.int8 and X.is_cuda and X.is_contiguous() and X.shape[-1] == layer.C
+    rows = X.numel() // layer.C
+    _check(load().flexiq_dynamic_positions(layer._h, X.data_ptr(), rows, _stream()))
+
+
+def flexiq_static_positions(layer: Layer) -> None:
+    _check(load().flexiq_static_positions(layer._h))
+
+
+def flexiq_layer_positions(layer: Layer) -> np.ndarray:
+    out = np.empty(layer.C // layer.group_size, np.uint8)
+    _check(load().flexiq_layer_positions(layer._h, out.ctypes.data))
+    return out
 
 
 def flexiq_permute_channels(layer: Layer, src):

@@ -42,7 +42,10 @@ void set_hip_error(hipError_t e, const char *what);
 //                                   work shares the vector ALU with the matrix pipe
 //   wshift uint8 [G+1][Npad]        weight extraction position per (group, output channel); row G is zero
 //                                   (looked up by the pad unit)
-//   ashift int32 [G+1]              activation extraction position per group (+1 entry for the pad unit)
+//   ashift int32 [G+1]              activation extraction position per group (+1 entry for the pad unit);
+//                                   a second table of the same shape holds the positions found at run time
+//   scan   uint32 [G+1]             OR masks of the run-time scan per group, then a block counter; all zero
+//                                   between calls (the scan kernel cleans up after itself)
 //   cs     fp32  [Npad]             x_scale * w_scale[n]
 //   bias   fp32  [Npad]             zeros when the layer has no bias
 struct flexiq_layer {
@@ -60,6 +63,9 @@ struct flexiq_layer {
     int8_t *d_w4x;
     uint8_t *d_wshift;
     int32_t *d_ashift;
+    int32_t *d_ashift_dyn;
+    uint32_t *d_scan;
+    bool dynamic;   // GEMM / conv calls read d_ashift_dyn instead of d_ashift
     float *d_cs;
     float *d_bias;
     int32_t *d_perm;

@@ -96,7 +96,8 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
                   int H, int Wd, int Ho, int Wo, int stride, int pad)
 {
     GemmParams p;
-    p.X = X; p.W8 = L->d_w8; p.W4 = L->d_w4; p.W4X = L->d_w4x; p.wshift = L->d_wshift; p.ashift = L->d_ashift;
+    p.X = X; p.W8 = L->d_w8; p.W4 = L->d_w4; p.W4X = L->d_w4x; p.wshift = L->d_wshift;
+    p.ashift = L->dynamic ? L->d_ashift_dyn : L->d_ashift;
     p.cs = L->d_cs; p.bias = L->d_bias;
     p.acc = out->acc; p.y = out->y; p.q = out->q;
     p.r_out = out->q ? 1.0f / out->out_scale : 1.0f;

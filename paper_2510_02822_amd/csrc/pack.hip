@@ -147,6 +147,80 @@ __global__ void k_pack_tiles(const int8_t *__restrict__ q, const int32_t *__rest
 // Run-time element-wise kernels
 // ---------------------------------------------------------------------------------------------
 
+// Extraction positions found at run time (Section 4.1, dynamic option; Section 9 "Finding extraction positions
+// at runtime"): per channel group the magnitude bits of all values (ones' complement for negative ones) are
+// OR-ed together; with p the highest set bit, three more bits below the sign can be kept: s = max(0, p - 2).
+// Thread (tx, ty) of a block of 1024 ORs the 16 channels at column piece blockIdx.y*TX + tx over the rows
+// blockIdx.x*TY + ty, + gridDim.x*TY, ...; the block combines its rows in LDS and adds what is new to the group's
+// mask (an atomic only if a coherent read shows bits missing: the masks have seven bits and fill up after the
+// first few blocks, so the atomics on one address do not queue up).  The block that finishes last turns the
+// masks of the scanned groups (the first g4) into positions, copies the calibrated positions of the other
+// groups, and leaves the masks and the counter zero for the next call.  No block waits for another.
+constexpr int kScanThreads = 1024;
+__global__ __launch_bounds__(kScanThreads) void k_dyn_positions(const int8_t *__restrict__ X, int64_t rows, int C,
+                                                                int pieces, int tx_log2, int gs, int G, int g4,
+                                                                uint32_t *scan, const int32_t *__restrict__ ashift_static,
+                                                                int32_t *__restrict__ ashift_dyn)
+{
+    __shared__ uint32_t sh[kScanThreads];
+    __shared__ int last;
+    const int tid = threadIdx.x;
+    const int TX = 1 << tx_log2, TY = kScanThreads >> tx_log2;
+    const int tx = tid & (TX - 1), ty = tid >> tx_log2;
+    const int piece = blockIdx.y * TX + tx;
+    const bool active = piece < pieces;
+    uint32_t m = 0;
+    if (active) {
+        uint32_t acc = 0;
+        const int64_t step = (int64_t)gridDim.x * TY;
+        const int8_t *src = X + (int64_t)piece * 16;
+        auto fold = [](const uint4 v) {   // per byte: v >= 0 ? v : ~v, then the four dwords together
+            const uint32_t f0 = ((v.x >> 7) & 0x01010101u) * 0xFFu, f1 = ((v.y >> 7) & 0x01010101u) * 0xFFu;
+            const uint32_t f2 = ((v.z >> 7) & 0x01010101u) * 0xFFu, f3 = ((v.w >> 7) & 0x01010101u) * 0xFFu;
+            return (v.x ^ f0) | (v.y ^ f1) | (v.z ^ f2) | (v.w ^ f3);
+        };
+        int64_t r = (int64_t)blockIdx.x * TY + ty;
+        for (; r + 3 * step < rows; r += 4 * step) {   // four independent loads in flight
+            const uint4 v0 = *reinterpret_cast<const uint4 *>(src + r * C);
+            const uint4 v1 = *reinterpret_cast<const uint4 *>(src + (r + step) * C);
+            const uint4 v2 = *reinterpret_cast<const uint4 *>(src + (r + 2 * step) * C);
+            const uint4 v3 = *reinterpret_cast<const uint4 *>(src + (r + 3 * step) * C);
+            acc |= fold(v0) | fold(v1) | fold(v2) | fold(v3);
+        }
+        for (; r < rows; r += step) acc |= fold(*reinterpret_cast<const uint4 *>(src + r * C));
+        acc |= acc >> 16;
+        acc |= acc >> 8;
+        m = acc & 0x7Fu;
+    }
+    sh[tid] = m;
+    __syncthreads();
+    if (ty == 0 && active) {
+        for (int y = 1; y < TY; ++y) m |= sh[y * TX + tx];
+        uint32_t *dst = &scan[(piece * 16) / gs];
+        const uint32_t seen = __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (m & ~seen) atomicOr(dst, m);
+    }
+    // The only results other blocks need are those of the atomics above, which are performed at the device's
+    // coherence point: it is enough that they have completed before this block's ticket is drawn (a full
+    // release fence would also write back the L2, i.e. the whole output of the kernel before this one).
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __syncthreads();
+    if (tid == 0) last = atomicAdd(&scan[G], 1u) == gridDim.x * gridDim.y - 1;
+    __syncthreads();
+    if (!last) return;
+    for (int g = tid; g <= G; g += kScanThreads) {
+        if (g < g4) {
+            const uint32_t mask = atomicOr(&scan[g], 0u);   // device-scope read of what all blocks added
+            const int p = mask ? 31 - __clz((int)mask) : -1;
+            ashift_dyn[g] = p - 2 > 0 ? p - 2 : 0;
+            scan[g] = 0;
+        } else {
+            ashift_dyn[g] = ashift_static[g];
+        }
+    }
+    if (tid == 0) scan[G] = 0;
+}
+
 // Eq. 1 for activations: four values per thread, one packed dword out.
 __global__ void k_quantize_act(const float *__restrict__ x, int8_t *__restrict__ q, int64_t n, float S)
 {
@@ -248,7 +322,7 @@ struct DevBuf {  // frees on scope exit unless released
 extern "C" int flexiq_layer_free(flexiq_layer *L)
 {
     if (!L) return FLEXIQ_OK;
-    void *bufs[] = {L->d_w8, L->d_w4, L->d_w4x, L->d_wshift, L->d_ashift, L->d_cs, L->d_bias, L->d_perm};
+    void *bufs[] = {L->d_w8, L->d_w4, L->d_w4x, L->d_wshift, L->d_ashift, L->d_ashift_dyn, L->d_scan, L->d_cs, L->d_bias, L->d_perm};
     int rc = FLEXIQ_OK;
     for (void *b : bufs)
         if (b && hipFree(b) != hipSuccess) rc = FLEXIQ_EHIP;
@@ -290,7 +364,7 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
     L->max_4bit_ch = 0;
     L->x_scale = d->x_scale;
     L->has_bias = d->bias != nullptr;
-    L->d_w8 = nullptr; L->d_w4 = nullptr; L->d_w4x = nullptr; L->d_wshift = nullptr; L->d_ashift = nullptr;
+    L->d_w8 = nullptr; L->d_w4 = nullptr; L->d_w4x = nullptr; L->d_wshift = nullptr; L->d_ashift = nullptr; L->d_ashift_dyn = nullptr; L->d_scan = nullptr; L->dynamic = false;
     L->d_cs = nullptr; L->d_bias = nullptr; L->d_perm = nullptr;
     FLEXIQ_HIP(hipGetDevice(&L->device));
     const int Npad = L->Npad;
@@ -348,6 +422,10 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
         a32.push_back(0);  // the pad unit of an odd unit count reads one past the last group
         FLEXIQ_HIP(hipMalloc((void **)&L->d_ashift, a32.size() * sizeof(int32_t)));
         FLEXIQ_HIP(hipMemcpy(L->d_ashift, a32.data(), a32.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+        FLEXIQ_HIP(hipMalloc((void **)&L->d_ashift_dyn, a32.size() * sizeof(int32_t)));
+        FLEXIQ_HIP(hipMemcpy(L->d_ashift_dyn, a32.data(), a32.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+        FLEXIQ_HIP(hipMalloc((void **)&L->d_scan, (size_t)(G + 1) * sizeof(uint32_t)));
+        FLEXIQ_HIP(hipMemset(L->d_scan, 0, (size_t)(G + 1) * sizeof(uint32_t)));
     }
     // one more (zero) row than groups: the pad unit of an odd unit count looks up group G
     FLEXIQ_HIP(hipMalloc((void **)&L->d_wshift, (size_t)(G + 1) * Npad));
@@ -462,6 +540,49 @@ extern "C" int flexiq_bitlower(const int8_t *src, uint8_t *dst, int64_t rows, in
     k_bitlower<<<(unsigned)cdiv(threads, 256), 256, 0, (hipStream_t)stream>>>(src, dst, rows, C, group_size, shifts,
                                                                              per_row ? 1 : 0, mode);
     FLEXIQ_HIP(hipGetLastError());
+    return FLEXIQ_OK;
+}
+
+extern "C" int flexiq_dynamic_positions(flexiq_layer *L, const int8_t *X, int64_t rows, void *stream)
+{
+    if (!L || rows < 0) return FLEXIQ_EINVAL;
+    if (rows > 0 && !X) return FLEXIQ_EINVAL;
+    if (rows > 0 && !aligned16(X)) return FLEXIQ_EALIGN;
+    const int g4 = L->max_4bit_ch / L->group_size;
+    const int pieces = L->max_4bit_ch / 16;             // 16-channel pieces per row to scan
+    int tx_log2 = 0;
+    while ((1 << tx_log2) < pieces && tx_log2 < 8) ++tx_log2;
+    const int TX = 1 << tx_log2, TY = kScanThreads >> tx_log2;
+    unsigned gx = 1, gy = 1;
+    if (pieces > 0 && rows > 0) {
+        gy = (unsigned)cdiv(pieces, TX);
+        // about four rows per thread, and few blocks: every block ends with one atomic on a shared counter
+        gx = (unsigned)std::min<int64_t>(cdiv(rows, (int64_t)TY * 4), std::max<int64_t>(1, 128 / gy));
+        if (gx < 1) gx = 1;
+    }
+    k_dyn_positions<<<dim3(gx, gy), kScanThreads, 0, (hipStream_t)stream>>>(X, pieces > 0 ? rows : 0, L->C, pieces,
+                                                                            tx_log2, L->group_size, L->G, g4, L->d_scan,
+                                                                            L->d_ashift, L->d_ashift_dyn);
+    FLEXIQ_HIP(hipGetLastError());
+    L->dynamic = true;
+    return FLEXIQ_OK;
+}
+
+extern "C" int flexiq_static_positions(flexiq_layer *L)
+{
+    if (!L) return FLEXIQ_EINVAL;
+    L->dynamic = false;
+    return FLEXIQ_OK;
+}
+
+extern "C" int flexiq_layer_positions(const flexiq_layer *L, uint8_t *a_shift)
+{
+    if (!L || !a_shift) return FLEXIQ_EINVAL;
+    std::vector<int32_t> a32(L->G);
+    FLEXIQ_HIP(hipDeviceSynchronize());
+    FLEXIQ_HIP(hipMemcpy(a32.data(), L->dynamic ? L->d_ashift_dyn : L->d_ashift, a32.size() * sizeof(int32_t),
+                         hipMemcpyDeviceToHost));
+    for (int g = 0; g < L->G; ++g) a_shift[g] = (uint8_t)a32[g];
     return FLEXIQ_OK;
 }
 

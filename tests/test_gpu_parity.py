@@ -179,6 +179,59 @@ def test_gemm_blocks_walk_several_tiles(env):
         fq.debug_max_blocks(0)
 
 
+@pytest.mark.parametrize("M,K,N,gs,scale", [(300, 256, 96, 32, 1.0), (1000, 192, 72, 32, 4.0), (77, 512, 64, 64, 0.25),
+                                            (2500, 96, 40, 32, 2.0), (1, 64, 16, 32, 1.0)])
+def test_dynamic_positions(env, M, K, N, gs, scale):
+    # positions found by the run-time OR scan == the oracle's scan, and the GEMM that uses them == the oracle's
+    # GEMM with those positions; `scale` moves the run-time range above / below the calibrated one
+    torch, oracle, fq, dev = env
+    case = workloads.make_linear("dyn", 8, M + K + N, M, K, N, gs, outlier_frac=0.02)
+    case.X *= scale
+    ol, hl, x_scale = both_layers(case)
+    Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
+    Xd = _dev(torch, Xq, dev)
+    G = K // gs
+    for r in (1.0, 0.5, 1.0 / G, 0.0):
+        k4 = fq.flexiq_set_ratio(hl, r)
+        G4 = k4 // gs
+        fq.flexiq_dynamic_positions(hl, Xd)
+        want = oracle.dynamic_act_shifts(Xq, gs, G4, ol.a_shift)
+        assert (fq.flexiq_layer_positions(hl) == want).all(), (r, fq.flexiq_layer_positions(hl), want)
+        ref = oracle.mixed_gemm(Xq, ol.Wq.reshape(N, K), gs, G4, want, ol.w_shift)
+        got = fq.flexiq_mixed_gemm(hl, Xd, acc=True)["acc"].cpu().numpy()
+        assert (got == ref).all(), r
+        # twice in a row: the scan leaves its scratch clean
+        fq.flexiq_dynamic_positions(hl, Xd)
+        assert (fq.flexiq_layer_positions(hl) == want).all()
+        # and back to the calibrated positions
+        fq.flexiq_static_positions(hl)
+        assert (fq.flexiq_layer_positions(hl) == ol.a_shift).all()
+        assert (fq.flexiq_mixed_gemm(hl, Xd, acc=True)["acc"].cpu().numpy() == oracle.forward_gemm(ol, Xq, r)).all()
+    # empty input: scanned groups get position 0
+    fq.flexiq_set_ratio(hl, 1.0)
+    fq.flexiq_dynamic_positions(hl, Xd[:0])
+    assert (fq.flexiq_layer_positions(hl) == 0).all()
+    fq.flexiq_static_positions(hl)
+
+
+def test_dynamic_positions_conv(env):
+    torch, oracle, fq, dev = env
+    case = workloads.make_conv("dynconv", 7, 41, 3, 9, 9, 64, 48, 3, 3, 1, 1, 32)
+    case.X *= 3.0
+    ol, hl, x_scale = both_layers(case)
+    Xq = np.ascontiguousarray(oracle.quantize(case.X, x_scale)[..., ol.perm])
+    Xd = _dev(torch, Xq, dev)
+    fq.flexiq_set_ratio(hl, 0.5)
+    G4 = oracle.groups_for_ratio(0.5, ol.G)
+    fq.flexiq_dynamic_positions(hl, Xd)
+    want = oracle.dynamic_act_shifts(Xq, 32, G4, ol.a_shift)
+    assert (fq.flexiq_layer_positions(hl) == want).all()
+    ref = oracle.mixed_conv(Xq, ol.Wq, 1, 1, 32, G4, want, ol.w_shift)
+    got = fq.flexiq_mixed_conv_implicit(hl, Xd, 1, 1, acc=True)["acc"].cpu().numpy()
+    assert (got == ref).all()
+    fq.flexiq_static_positions(hl)
+
+
 def test_gemm_saturating_inputs(env):
     # activations far beyond the calibrated range: the clamp of the lowering is active everywhere
     torch, oracle, fq, dev = env

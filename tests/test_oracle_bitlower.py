@@ -129,3 +129,22 @@ def test_round_variant_self_consistency(oracle):
         assert oracle.bitlower(q, 0, 1) == oracle.bitlower(q, 0, 0)
         for s in range(1, 5):
             assert oracle.bitlower(q, s, 1) == max(-8, min(7, (q + 2 ** (s - 1)) >> s))
+
+
+def test_dynamic_act_shifts_match_range_definition(oracle):
+    # the OR scan over a group == the position of the group's (min, max) range (Section 4.1), group by group,
+    # and only the first G4 groups are rescanned
+    rng = np.random.default_rng(11)
+    gs, G = 32, 6
+    X = np.zeros((50, gs * G), np.int8)
+    for g, amp in enumerate((3, 9, 20, 40, 100, 127)):
+        X[:, g * gs:(g + 1) * gs] = rng.integers(-amp, amp + 1, size=(50, gs))
+        X[0, g * gs] = -amp          # make sure the extreme is present
+    static = np.full(G, 4, np.uint8)
+    for G4 in (0, 1, 3, 6):
+        got = oracle.dynamic_act_shifts(X, gs, G4, static)
+        for g in range(G):
+            blk = X[:, g * gs:(g + 1) * gs]
+            want = oracle.shift_for_range(int(blk.min()), int(blk.max())) if g < G4 else 4
+            assert got[g] == want
+    assert list(oracle.dynamic_act_shifts(X, gs, 6, static)) == [0, 1, 2, 3, 4, 4]
