@@ -151,6 +151,18 @@ def main():
         per_r_us[r] = float(np.median(ts))
         del g
 
+    # ratio switch (Section 7 "Low-bitwidth Ratio Adjustment"): host cost of one flexiq_set_ratio call through the
+    # Python binding (an upper bound of the C call, which writes one integer), and the per-launch time of the
+    # sweep, where every launch follows a switch, against launches at a fixed ratio
+    n_sw = 20000
+    t_sw = time.perf_counter()
+    for i in range(n_sw):
+        fq.flexiq_set_ratio(layer, RATIOS[i % len(RATIOS)])
+    switch_ns = (time.perf_counter() - t_sw) / n_sw * 1e9
+    ratio_switch = {"set_ratio_host_ns": round(switch_ns, 1),
+                    "sweep_us_per_launch": round(dev_us / (args.steps * len(RATIOS)), 2),
+                    "fixed_ratio_mean_us_per_launch": round(float(np.mean([per_r_us[r] for r in RATIOS])), 2)}
+
     # run-time extraction positions (Section 4.1, dynamic option): cost of the OR scan next to the GEMM it serves
     # (outside the timed region; the paper reports 2-5 % of the layer)
     dyn = []
@@ -241,7 +253,7 @@ def main():
                                "per step, epilogue=%s" % (args.layer, M, K, N, gs, list(RATIOS),
                                                           {"q": "int8 requant", "y": "fp32 dequant", "acc": "int32 dump"}[args.out]),
                    "M": M, "K": K, "N": N, "group_size": gs, "ratios": list(RATIOS)},
-        "roofline": roofline, "cpu_baseline": cpu, "per_r": per_r, "dynamic_positions": dyn, "parity": parity,
+        "roofline": roofline, "cpu_baseline": cpu, "per_r": per_r, "dynamic_positions": dyn, "ratio_switch": ratio_switch, "parity": parity,
     }
     print(json.dumps(line), flush=True)
 

@@ -46,8 +46,8 @@ void set_hip_error(hipError_t e, const char *what);
 //                                   a second table of the same shape holds the positions found at run time
 //   scan   uint32 [G+1]             OR masks of the run-time scan per group, then a block counter; all zero
 //                                   between calls (the scan kernel cleans up after itself)
-//   cs     fp32  [Npad]             x_scale * w_scale[n]
-//   bias   fp32  [Npad]             zeros when the layer has no bias
+//   cs     fp32  [2][Npad]          x_scale * w_scale[n], then the biases (zeros when the layer has none):
+//                                   one allocation, d_bias = d_cs + Npad
 struct flexiq_layer {
     int32_t N, C, R, S, group_size;
     int32_t G, T, U, Npad;

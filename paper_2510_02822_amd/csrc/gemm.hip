@@ -81,7 +81,7 @@ static int choose_shape(int64_t M, int N, int steps, bool conv, bool packed)
         const double seq = __builtin_ceil(tiles_cu / conc);
         const double step = tab[i].step_alone * (1.0 + tab[i].share * (conc - 1.0));
         const double prologue = 8000.0;
-        const bool walks = tab[i].multi && !conv && steps >= 4;   // prologue paid once per block
+        const bool walks = tab[i].multi;   // prologue paid once per block
         const double cost = walks ? prologue + seq * (steps * step + tab[i].epilogue)
                                   : seq * (prologue + steps * step + tab[i].epilogue);
         if (cost < best) {
@@ -106,6 +106,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.U = L->U; p.CU = L->C / kUnit; p.T = L->T; p.G = L->G;
     if (L->G + 1 > 160) return FLEXIQ_EINVAL;  // position table kept in LDS
+    if (M > 0x7fffffff - 256) return FLEXIQ_EINVAL;  // row indices are 32-bit in the kernel
     if (L->C / kUnit >= 2 * 65535) return FLEXIQ_EINVAL;  // K-step indices are kept in 16-bit fields
     if ((int64_t)L->U * 32 * L->Npad > 0x7fffffff) return FLEXIQ_EINVAL;  // weight window must fit a buffer descriptor
     p.H = H; p.Wd = Wd; p.Ho = Ho; p.Wo = Wo; p.S = L->S; p.stride = stride; p.pad = pad;
@@ -124,10 +125,10 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
         set_hip_error(hipGetLastError(), "hipFuncSetAttribute / hipOccupancyMaxActiveBlocksPerMultiprocessor");
         return FLEXIQ_EHIP;
     }
-    // A linear layer with at least four K-steps runs as one resident wave of blocks, each walking several
-    // output tiles (the kernel's load pipeline then runs on across tile boundaries); otherwise one block per tile.
+    // Shapes whose blocks can walk several output tiles are launched as one resident wave of blocks (the kernel's
+    // load pipeline then runs on across tile boundaries); the others with one block per tile.
     int64_t blocks = tiles;
-    if (ts.multi && !conv && steps >= 4 && g_max_blocks >= 0)
+    if (ts.multi && g_max_blocks >= 0)
         blocks = std::min<int64_t>(tiles, g_max_blocks > 0 ? (int64_t)g_max_blocks : (int64_t)num_cu() * resident);
     g_last_blocks = (int)blocks;
     g_last_resident = resident;

@@ -143,6 +143,12 @@ __device__ __forceinline__ void lds_load16(__amdgpu_buffer_rsrc_t r, unsigned ch
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)dst, 16, voff, soff, 0, 0);
 }
 
+// 4 bytes per lane: lane l writes dst + 4 l.
+__device__ __forceinline__ void lds_load4(__amdgpu_buffer_rsrc_t r, void *dst, int voff, int soff)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)dst, 4, voff, soff, 0, 0);
+}
+
 template <int WAVES_M, int WAVES_N, int TM, int TN>
 struct Cfg {
     static_assert(WAVES_M * WAVES_N == 4, "four waves per block");
@@ -232,7 +238,6 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
         m0 = (int64_t)tile_m * BM;
         n0 = tile_n * BN;
     }
-    const int rows_valid = (int)min((int64_t)BM, p.M - m0);   // of the block's first tile
 
     // ---- buffer windows.  Weights: the whole arrays (every access is in range by construction: tiles are
     // padded to Npad columns and to whole units), the tile's column offset travels in the scalar offset.
@@ -243,63 +248,56 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     const __amdgpu_buffer_rsrc_t rw4 = __builtin_amdgcn_make_buffer_rsrc((void *)p.W4, 0, p.U * 16 * p.Npad, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t rw4x = __builtin_amdgcn_make_buffer_rsrc((void *)p.W4X, 0, p.U * 32 * p.Npad, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t rws = __builtin_amdgcn_make_buffer_rsrc((void *)p.wshift, 0, (p.G + 1) * p.Npad, kRsrcFlags);
-    const int8_t *xbase;  // origin and size of the activation window of the tile being LOADED
+    const __amdgpu_buffer_rsrc_t rcs = __builtin_amdgcn_make_buffer_rsrc((void *)p.cs, 0, 2 * p.Npad * 4, kRsrcFlags);   // scales, then biases
+    // ---- the tile being LOADED (it runs ahead of the tile being computed by three K-steps, which may be
+    // several tiles when K is short): its index, activation window and first column
+    int ltile = ctile;
+    const int8_t *xbase;
     int xwin;
-    int ld_n0 = n0;       // and its first column
+    int ld_n0;
     // Activation piece j of a thread: row 16 (wave + 4 j) + lane / 4 of the tile, LDS slot lane % 4 of that row,
     // which holds k-plane xq = slot ^ ((row / 4) % 4); (row / 4) % 4 = (lane / 16) % 4 for every j.
     const int xrow = lane >> 2;
     const int xq = (lane & 3) ^ ((lane >> 4) & 3);   // k-plane of this thread's activation pieces; unit xq >> 1
     int xvoff[XI];                    // linear: byte offset inside the window; conv: xq * 16
     int xh0[XI], xw0[XI], xpix[XI];   // conv: top-left input coordinate, pixel index of the image origin (-1: no row)
-    if (CONV) {
-        const int64_t hw_out = (int64_t)p.Ho * p.Wo;
-        const int64_t img0 = m0 / hw_out;
-        const int64_t img_bytes = (int64_t)p.H * p.Wd * p.C;
-        const int64_t imgs_left = (p.M / hw_out) - img0;
-        const int64_t win = min(imgs_left * img_bytes, (int64_t)0x7fffffff);
-        xbase = p.X + img0 * img_bytes;
-        xwin = (int)win;
 #pragma unroll
-        for (int j = 0; j < XI; ++j) {
-            const int row = 16 * (wave + 4 * j) + xrow;
-            const bool ok = row < rows_valid;
-            const int64_t mm = ok ? m0 + row : m0;
-            const int wo = (int)(mm % p.Wo);
-            const int ho = (int)((mm / p.Wo) % p.Ho);
-            const int b = (int)(mm / hw_out - img0);
-            xpix[j] = ok ? b * p.H * p.Wd : -1;
-            xh0[j] = ho * p.stride - p.pad;
-            xw0[j] = wo * p.stride - p.pad;
-            xvoff[j] = xq * 16;
-        }
-    } else {
-        xbase = p.X + m0 * p.C;
-        xwin = rows_valid * p.C;
-#pragma unroll
-        for (int j = 0; j < XI; ++j) {
-            const int row = 16 * (wave + 4 * j) + xrow;
-            xvoff[j] = row * p.C + xq * 16;  // rows >= rows_valid fall outside the window: zeros
-            xh0[j] = xw0[j] = xpix[j] = 0;
-        }
+    for (int j = 0; j < XI; ++j) {
+        xvoff[j] = CONV ? xq * 16 : (16 * (wave + 4 * j) + xrow) * p.C + xq * 16;  // linear: rows past the window read zeros
+        xh0[j] = xw0[j] = xpix[j] = 0;
     }
-    // The tile the loads move on to when the current one is finished (linear form only; a convolution
-    // block is launched for a single tile).
-    const int8_t *pd_xbase = xbase;
-    int pd_xwin = 0, pd_n0 = 0;
-    bool pd_valid = false;
-    auto set_pending = [&](int t) {
-        pd_valid = C_::MULTI && !CONV && t < total_tiles;
-        if (pd_valid) {
-            int tile_m, tile_n;
-            map_tile(t, tile_m, tile_n);
-            const int64_t pm0 = (int64_t)tile_m * BM;
-            pd_xbase = p.X + pm0 * p.C;
-            pd_xwin = (int)min((int64_t)BM, p.M - pm0) * p.C;
-            pd_n0 = tile_n * BN;
+    auto load_tile_context = [&](int64_t lm0, int ln0) {
+        const int rows_valid = (int)min((int64_t)BM, p.M - lm0);
+        ld_n0 = ln0;
+        if (CONV) {
+            // 32-bit row arithmetic (the launcher refuses M >= 2^31): 64-bit divisions would cost thousands of
+            // cycles per tile
+            const uint32_t hw_out = (uint32_t)(p.Ho * p.Wo), m32 = (uint32_t)lm0;
+            const uint32_t img0 = m32 / hw_out;
+            const int64_t img_bytes = (int64_t)p.H * p.Wd * p.C;
+            const int64_t imgs_left = (int64_t)((uint32_t)p.M / hw_out) - img0;
+            const int64_t win = min(imgs_left * img_bytes, (int64_t)0x7fffffff);
+            xbase = p.X + (int64_t)img0 * img_bytes;
+            xwin = (int)win;
+#pragma unroll
+            for (int j = 0; j < XI; ++j) {
+                const int row = 16 * (wave + 4 * j) + xrow;
+                const bool ok = row < rows_valid;
+                const uint32_t mm = ok ? m32 + (uint32_t)row : m32;
+                const uint32_t t = mm / (uint32_t)p.Wo;
+                const int wo = (int)(mm - t * (uint32_t)p.Wo);
+                const uint32_t b = t / (uint32_t)p.Ho;
+                const int ho = (int)(t - b * (uint32_t)p.Ho);
+                xpix[j] = ok ? (int)(b - img0) * p.H * p.Wd : -1;
+                xh0[j] = ho * p.stride - p.pad;
+                xw0[j] = wo * p.stride - p.pad;
+            }
+        } else {
+            xbase = p.X + lm0 * p.C;
+            xwin = rows_valid * p.C;
         }
     };
-    set_pending(ctile + (int)gridDim.x);
+    load_tile_context(m0, n0);
     const int x_lds = (16 * wave) * 64 + lane * 16;   // piece j adds 64 rows: j * 4096
     int wvoff[WI];   // per-lane offset of direct weight load j: k-plane parity, 64-row block, row = lane
 #pragma unroll
@@ -319,13 +317,22 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     }
 
     FQ_TS(tqa);
-    // activation positions of all groups and the scale / bias of the tile's columns: loaded into registers
-    // here, written to LDS after the prologue's tile loads have been issued (one memory latency for all)
+    // activation positions of all groups: loaded into a register here, written to LDS after the prologue's tile
+    // loads have been issued (one memory latency for all)
     static_assert(BN <= NT && 160 <= NT, "one table element per thread");
     const int sa_v = tid <= p.G ? p.ashift[tid] : 0;
-    float cs_v = tid < BN ? p.cs[n0 + tid] : 0.0f;      // cs/bias are padded to Npad >= n0 + BN
-    float bias_v = tid < BN ? p.bias[n0 + tid] : 0.0f;
     int parity = 0;   // which copy of the scale / bias table belongs to the tile being computed
+    // Scales and biases of the BN columns from column c0 on, straight into table copy `par` (no register hop, so
+    // nothing has to wait for them here; the end-of-step waits of the K loop cover them before the epilogue).
+    // cs/bias are padded to Npad >= c0 + BN.
+    auto fetch_scales = [&](int c0, int par) {
+        if (wave * 64 < BN) {
+            float *dst = cs_tab + par * (2 * BN) + wave * 64;
+            lds_load4(rcs, dst, (wave * 64 + lane) * 4, c0 * 4);
+            lds_load4(rcs, dst + BN, (wave * 64 + lane) * 4, (p.Npad + c0) * 4);
+        }
+    };
+    fetch_scales(n0, 0);
 
     // ---- K-step enumeration, phase-major: all-4-bit steps, then mixed steps, then all-8-bit steps;
     // the iterator points at the next tile to LOAD.  Scalar state only.
@@ -353,12 +360,20 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
         const int tap1 = it_tap + 1;
         const bool wrap_t = wrap_c && tap1 == p.T;      // the phase is finished
         const int ph_in = pn(it_phase);
-        const bool go_next = wrap_t && ph_in == 3 && pd_valid;   // the tile is finished and another one follows
+        // The tile is finished: move on to the block's next tile if there is one (a branch, taken once per tile;
+        // the tile mapping and, for a convolution, the per-row gather state are vector-ALU work).
+        bool go_next = false;
+        if (C_::MULTI && wrap_t && ph_in == 3) {
+            const int nt = ltile + (int)gridDim.x;
+            if (nt < total_tiles) {
+                go_next = true;
+                ltile = nt;
+                int tile_m, tile_n;
+                map_tile(nt, tile_m, tile_n);
+                load_tile_context((int64_t)tile_m * BM, tile_n * BN);
+            }
+        }
         const int ph = wrap_t ? (go_next ? first_phase : ph_in) : it_phase;
-        xbase = go_next ? pd_xbase : xbase;
-        xwin = go_next ? pd_xwin : xwin;
-        ld_n0 = go_next ? pd_n0 : ld_n0;
-        pd_valid = go_next ? false : pd_valid;
         if (CONV) {
             const int dx1 = it_dx + 1;
             const bool wrap_x = dx1 == p.S;
@@ -497,7 +512,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
         int pmode[2] = {kModeNone, kModeNone}, pc64[2] = {0, 0};
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            if (t < steps) {
+            if (it_phase != 3) {   // the block has a K-step t (of its first tile, or of a following one when K is short)
                 pmode[t] = it_mode();
                 pc64[t] = it_c64;
 #pragma unroll
@@ -505,7 +520,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                 advance();
             }
         }
-        if (2 < steps) {
+        if (it_phase != 3) {
             mode_staged = it_mode();
             st_c64 = it_c64;
 #pragma unroll
@@ -514,16 +529,12 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
         }
         FQ_TS(tqb);
         if (tid <= p.G) reinterpret_cast<int *>(sa_tab)[tid] = sa_v;
-        if (tid < BN) {
-            cs_tab[tid] = cs_v;
-            cs_tab[BN + tid] = bias_v;
-        }
         __builtin_amdgcn_s_waitcnt(0xc07f);
         __builtin_amdgcn_s_barrier();   // position table visible
         FQ_TS(tqc);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            if (t < steps) {
+            if (pmode[t] != kModeNone) {
                 if (pmode[t] != kMode88) {
                     sa_fetch(pc64[t]);
                     lower_setup();
@@ -569,6 +580,8 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     // output tile are computed, the first K-steps of the next one are already being loaded and staged.
     int o_cur = 0, o_nx1 = STAGE, o_nx2 = 2 * STAGE, o_nx3 = 3 * STAGE;   // byte offsets of the stages of K-steps s .. s+3
     int s = 0;    // K-step within the output tile being computed
+    // K-steps this block still has to compute, over all its tiles (the last one reads no fragments ahead)
+    int flat_left = steps * (C_::MULTI ? (total_tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 1);
     constexpr int kStageSlots = 2 * NMF > 2 ? 2 * NMF - 2 : 1;    // slots that carry staging work
     constexpr int kAdvanceSlot = 2 * NMF > 2 ? 2 * NMF - 2 : 0;   // slot after which the load iterator moves on
     auto step = [&](auto ma_, auto mb_, auto h1_) {
@@ -668,6 +681,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
             o_nx3 = t;
         }
         ++s;
+        --flat_left;
         mode_staged = mb;
     };
 
@@ -762,7 +776,11 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                     const auto s13 = __builtin_amdgcn_permlane32_swap(qrow[b][1], qrow[b][3], false, false);
                     const int64_t m = m0 + (wm * TM + b) * 32 + frag_row_e;
                     const int n = n0 + (wn * TN + a) * 32 + 16 * frag_half_e;
+#ifdef FQ_EXP_NOQSTORE
+                    if (m < p.M && n < p.N && s02[0] == 0x12345678)   // experiment: (almost) never stores
+#else
                     if (m < p.M && n < p.N)
+#endif
                         *reinterpret_cast<v4i *>(p.q + m * p.N + n) = (v4i){(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
                 }
             }
@@ -783,7 +801,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     // (Entering a steady-state loop with no load or store in flight lets the compiler count the loads of the
     // loop itself exactly, instead of waiting for all of them before the first LDS store of every step.)
     for (;;) {
-        const bool more_tiles = C_::MULTI && !CONV && ctile + (int)gridDim.x < total_tiles;
+        const bool more_tiles = C_::MULTI && ctile + (int)gridDim.x < total_tiles;
         // Nothing in flight (in particular none of the previous epilogue's stores) when the K loop starts: the
         // compiler can then count the register-routed loads of the 4-bit loops exactly.
         if (n4 + mixed > 0 || PACKED4) __builtin_amdgcn_s_waitcnt(0x0070);
@@ -797,8 +815,8 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
             while (s < steps && mode_staged == kMode88 && it_phase == 3) step(M88{}, MNone{}, T_{});
             while (s < steps && mode_staged == kMode44 && it_phase == 3) step(M44{}, MNone{}, T_{});
             while (s < steps && mode_staged == kMode48 && it_phase == 3) step(mode_staged, (int)kModeNone, true);
-            while (s + 1 < steps && mode_staged == kModeNone) step(MNone{}, MNone{}, T_{});
-            while (s < steps && mode_staged == kModeNone) step(MNone{}, MNone{}, F_{});
+            while (s < steps && mode_staged == kModeNone && flat_left > 1) step(MNone{}, MNone{}, T_{});
+            while (s < steps && mode_staged == kModeNone && flat_left <= 1) step(MNone{}, MNone{}, F_{});
         }
 
 #ifdef FLEXIQ_TIMING
@@ -830,12 +848,8 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
             m0 = (int64_t)tile_m * BM;
             n0 = tile_n * BN;
         }
-        set_pending(ctile + (int)gridDim.x);   // the loads are inside this tile by now
         parity ^= 1;                           // the other table copy was last read two epilogues ago
-        if (tid < BN) {
-            cs_tab[parity * (2 * BN) + tid] = p.cs[n0 + tid];
-            cs_tab[parity * (2 * BN) + BN + tid] = p.bias[n0 + tid];
-        }
+        fetch_scales(n0, parity);
         zero_acc();
         s = 0;
     }

@@ -322,7 +322,7 @@ struct DevBuf {  // frees on scope exit unless released
 extern "C" int flexiq_layer_free(flexiq_layer *L)
 {
     if (!L) return FLEXIQ_OK;
-    void *bufs[] = {L->d_w8, L->d_w4, L->d_w4x, L->d_wshift, L->d_ashift, L->d_ashift_dyn, L->d_scan, L->d_cs, L->d_bias, L->d_perm};
+    void *bufs[] = {L->d_w8, L->d_w4, L->d_w4x, L->d_wshift, L->d_ashift, L->d_ashift_dyn, L->d_scan, L->d_cs, L->d_perm};   // d_bias is the second half of d_cs
     int rc = FLEXIQ_OK;
     for (void *b : bufs)
         if (b && hipFree(b) != hipSuccess) rc = FLEXIQ_EHIP;
@@ -449,8 +449,8 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
         L->bias.assign(d->bias, d->bias + N);
         std::copy(d->bias, d->bias + N, bias.begin());
     }
-    FLEXIQ_HIP(hipMalloc((void **)&L->d_cs, Npad * sizeof(float)));
-    FLEXIQ_HIP(hipMalloc((void **)&L->d_bias, Npad * sizeof(float)));
+    FLEXIQ_HIP(hipMalloc((void **)&L->d_cs, 2 * (size_t)Npad * sizeof(float)));   // scales, then biases
+    L->d_bias = L->d_cs + Npad;
     FLEXIQ_HIP(hipMemcpy(L->d_cs, cs.data(), Npad * sizeof(float), hipMemcpyHostToDevice));
     FLEXIQ_HIP(hipMemcpy(L->d_bias, bias.data(), Npad * sizeof(float), hipMemcpyHostToDevice));
     FLEXIQ_HIP(hipDeviceSynchronize());
