@@ -624,22 +624,16 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                             if (k < 4) {
                                 if (ma == kMode44 || ma == kMode48) lmicro(sr, wsh, i, k, ma);
                             } else if (k == 4) {
-#ifndef FQ_EXP_NOLSTORE
                                 if (ma == kMode44 || ma == kMode48) lstore(sr, i, ma, nx2);
-#endif
                             } else {
-#ifndef FQ_EXP_NOGLOAD
                                 if (mb != kModeNone) gload(sr, wsh, i, mb, nx3);
-#endif
                             }
                             FQ_SB();
                         }
 #pragma unroll
                     for (int j = 0; j < WI; ++j)
                         if ((2 * j + 1) * kStageSlots / (2 * WI) == g) {
-#ifndef FQ_EXP_NOGLOAD
                             if (mb != kModeNone) gload(sr, wsh, XI + j, mb, nx3);
-#endif
                             FQ_SB();
                         }
 #pragma unroll
@@ -669,9 +663,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
         else
             __builtin_amdgcn_s_waitcnt(0x0070);
         __builtin_amdgcn_s_waitcnt(0xc07f);  // this wave's LDS stores and fragment reads are complete
-#ifndef FQ_EXP_NOBARRIER
         __builtin_amdgcn_s_barrier();
-#endif
         FQ_SB();
         {
             const int t = o_cur;
@@ -776,11 +768,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                     const auto s13 = __builtin_amdgcn_permlane32_swap(qrow[b][1], qrow[b][3], false, false);
                     const int64_t m = m0 + (wm * TM + b) * 32 + frag_row_e;
                     const int n = n0 + (wn * TN + a) * 32 + 16 * frag_half_e;
-#ifdef FQ_EXP_NOQSTORE
-                    if (m < p.M && n < p.N && s02[0] == 0x12345678)   // experiment: (almost) never stores
-#else
                     if (m < p.M && n < p.N)
-#endif
                         *reinterpret_cast<v4i *>(p.q + m * p.N + n) = (v4i){(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
                 }
             }
