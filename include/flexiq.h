@@ -56,6 +56,12 @@ typedef struct {
     const int32_t *perm;     /* optional host int32 [C]: stored position -> original channel.  NULL: ascending
                                 error-estimation score (Section 4.2), ties by original index */
     const float *bias;       /* optional host fp32 [N] */
+    const int32_t *out_perm; /* optional host int32 [N]: output column j of this layer = original output channel
+                                out_perm[j].  Set it to the NEXT layer's stored channel order (its `perm`) and this
+                                layer writes its outputs directly in the order the next layer reads them: the static
+                                reordering of Section 5, steps 1-2 (only residual paths need the run-time
+                                flexiq_permute_channels).  Every per-output-channel table of the handle (w_scale,
+                                w_shift, dumps) is then indexed by output column.  NULL: original order */
 } flexiq_pack_desc;
 
 /* Offline steps (Eq. 1; Sections 4.1, 4.2, 5): per-output-channel symmetric int8 quantisation of W,
@@ -144,14 +150,18 @@ typedef struct {
  *             + sum_{k >= max_4bit_ch} X[m][k] * W[n][k],          L(v, s) = clamp(v >> s, -8, 7)
  * with G4 = max_4bit_ch / group_size as last set by flexiq_set_ratio (0 after packing).
  * X: dev int8 [M][C] row-major, channels in stored order, 16-byte aligned; M >= 0 (M == 0 is a no-op).
- * The activations are bit-lowered on the fly inside the kernel; the weights of 4-bit groups are read
- * from the packed 4-bit copy and expanded in registers.  Layer must be linear (R = S = 1). */
+ * The activations are bit-lowered on the fly inside the kernel, at the handle's current positions (calibrated, or
+ * those of the last flexiq_dynamic_positions scan); the weights of 4-bit groups are read from the handle's cached
+ * lowered copies.  Layer must be linear (R = S = 1).  Launches on `stream`; allocates nothing; returns before the
+ * kernel has run.  Errors: FLEXIQ_EINVAL (null / inconsistent arguments, M >= 2^31 - 256, more than 159 channel
+ * groups, current device is not the handle's), FLEXIQ_EALIGN, FLEXIQ_EHIP. */
 int flexiq_mixed_gemm(const flexiq_layer *layer, const int8_t *X, int64_t M, const flexiq_out *out, void *stream);
 
 /* The same sum as an implicit GEMM over (filter tap, channel) for a convolution layer:
  * X: dev int8 NHWC [B][H][W][C], stored channel order, zero padding `pad`, stride `stride`;
  * outputs are [B][Ho][Wo][N] with Ho = (H + 2*pad - R)/stride + 1 (likewise Wo).
- * The channel groups, a_shift and the 4-bit prefix are the same for every tap. */
+ * The channel groups, a_shift and the 4-bit prefix are the same for every tap.
+ * Further limit: H*W*C * (256 / (Ho*Wo) + 2) must be below 2^31 bytes (a block reads its images through a 2 GiB window). */
 int flexiq_mixed_conv_implicit(const flexiq_layer *layer, const int8_t *X, int32_t B, int32_t H, int32_t W,
                                int32_t stride, int32_t pad, const flexiq_out *out, void *stream);
 

@@ -20,7 +20,7 @@ class FlexiqError(RuntimeError):
 class _PackDesc(C.Structure):
     _fields_ = [("N", C.c_int32), ("C", C.c_int32), ("R", C.c_int32), ("S", C.c_int32),
                 ("group_size", C.c_int32), ("W", C.c_void_p), ("act_absmax", C.c_void_p),
-                ("x_scale", C.c_float), ("perm", C.c_void_p), ("bias", C.c_void_p)]
+                ("x_scale", C.c_float), ("perm", C.c_void_p), ("bias", C.c_void_p), ("out_perm", C.c_void_p)]
 
 
 class _Out(C.Structure):
@@ -121,8 +121,9 @@ class Layer:
                 "w_scale": arr(ps[3], C.c_float, self.N), "G": g, "max_4bit_ch": k4.value}
 
 
-def flexiq_quantize_pack(W, act_absmax, x_scale: float, group_size: int, perm=None, bias=None) -> Layer:
-    """W: fp32 [N][C] or [N][R][S][C] (numpy, original channel order)."""
+def flexiq_quantize_pack(W, act_absmax, x_scale: float, group_size: int, perm=None, bias=None, out_perm=None) -> Layer:
+    """W: fp32 [N][C] or [N][R][S][C] (numpy, original channel order).  out_perm: output column j = original
+    output channel out_perm[j] (e.g. the next layer's stored channel order)."""
     L = load()
     W = _f32(W)
     if W.ndim == 2:
@@ -133,8 +134,11 @@ def flexiq_quantize_pack(W, act_absmax, x_scale: float, group_size: int, perm=No
     assert am.shape == (Cc,)
     pm = None if perm is None else np.ascontiguousarray(perm, dtype=np.int32)
     bs = None if bias is None else _f32(bias)
+    op = None if out_perm is None else np.ascontiguousarray(out_perm, dtype=np.int32)
+    assert op is None or op.shape == (N,)
     d = _PackDesc(N, Cc, R, S, group_size, W.ctypes.data, am.ctypes.data, float(x_scale),
-                  None if pm is None else pm.ctypes.data, None if bs is None else bs.ctypes.data)
+                  None if pm is None else pm.ctypes.data, None if bs is None else bs.ctypes.data,
+                  None if op is None else op.ctypes.data)
     h = C.c_void_p()
     _check(L.flexiq_quantize_pack(C.byref(d), C.byref(h)))
     return Layer(h.value, N, Cc, R, S, group_size)

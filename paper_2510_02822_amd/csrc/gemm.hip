@@ -21,6 +21,7 @@ static const TileShape *shapes(int *count)
     return tab;
 }
 
+// Process-wide tuning / test switches (not synchronised: set them while no call is in flight).
 static int g_num_cu = 0;
 static int g_force_shape = -1;
 static int g_force_packed = -1;
@@ -105,6 +106,11 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     p.K4 = L->max_4bit_ch;
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.U = L->U; p.CU = L->C / kUnit; p.T = L->T; p.G = L->G;
+    {   // the handle's buffers live on the device it was packed on
+        int dev = -1;
+        FLEXIQ_HIP(hipGetDevice(&dev));
+        if (dev != L->device) return FLEXIQ_EINVAL;
+    }
     if (L->G + 1 > 160) return FLEXIQ_EINVAL;  // position table kept in LDS
     if (M > 0x7fffffff - 256) return FLEXIQ_EINVAL;  // row indices are 32-bit in the kernel
     if (L->C / kUnit >= 2 * 65535) return FLEXIQ_EINVAL;  // K-step indices are kept in 16-bit fields
@@ -205,6 +211,9 @@ extern "C" int flexiq_mixed_conv_implicit(const flexiq_layer *L, const int8_t *X
     const int Ho = (H + 2 * pad - L->R) / stride + 1, Wo = (W + 2 * pad - L->S) / stride + 1;
     const int64_t M = (int64_t)B * Ho * Wo;
     if (M == 0) return FLEXIQ_OK;  // empty batch
+    // A block addresses its input through a 2 GiB window that starts at the first image it touches; the images
+    // of the tallest tile (256 output rows) must fit in it.
+    if ((int64_t)H * W * L->C * (256 / ((int64_t)Ho * Wo) + 2) > 0x7fffffff) return FLEXIQ_EINVAL;
     int rc = check_out(out);
     if (rc) return rc;
     if (!X) return FLEXIQ_EINVAL;

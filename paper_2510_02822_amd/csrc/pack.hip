@@ -346,6 +346,27 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
             seen[v] = 1;
         }
     }
+    // Output order: the rows of W (and the biases) are taken in the order out_perm names; everything after
+    // this point sees an ordinary layer whose channel n is the caller's channel out_perm[n].
+    std::vector<float> Wrows, bias_rows;
+    const float *Wsrc = d->W, *bias_src = d->bias;
+    if (d->out_perm) {
+        std::vector<char> seen(N, 0);
+        for (int n = 0; n < N; ++n) {
+            int v = d->out_perm[n];
+            if (v < 0 || v >= N || seen[v]) return FLEXIQ_EINVAL;
+            seen[v] = 1;
+        }
+        const size_t row = (size_t)T * C;
+        Wrows.resize((size_t)N * row);
+        for (int n = 0; n < N; ++n) std::memcpy(&Wrows[(size_t)n * row], d->W + (size_t)d->out_perm[n] * row, row * sizeof(float));
+        Wsrc = Wrows.data();
+        if (d->bias) {
+            bias_rows.resize(N);
+            for (int n = 0; n < N; ++n) bias_rows[n] = d->bias[d->out_perm[n]];
+            bias_src = bias_rows.data();
+        }
+    }
     flexiq_layer *L = new (std::nothrow) flexiq_layer();
     if (!L) return FLEXIQ_ENOMEM;
     struct Guard {
@@ -376,7 +397,7 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
     FLEXIQ_HIP(hipMalloc(&dQ.p, total));
     FLEXIQ_HIP(hipMalloc(&dWmax.p, C * sizeof(int)));
     FLEXIQ_HIP(hipMalloc(&dWsNG.p, (size_t)N * G));
-    FLEXIQ_HIP(hipMemcpy(dW.p, d->W, total * sizeof(float), hipMemcpyHostToDevice));
+    FLEXIQ_HIP(hipMemcpy(dW.p, Wsrc, total * sizeof(float), hipMemcpyHostToDevice));
     FLEXIQ_HIP(hipMemset(dWmax.p, 0, C * sizeof(int)));
 
     k_row_scale<<<N, 256>>>((const float *)dW.p, Kt, (float *)dScale.p);
@@ -445,9 +466,9 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
 
     std::vector<float> cs(Npad, 0.0f), bias(Npad, 0.0f);
     for (int n = 0; n < N; ++n) cs[n] = d->x_scale * L->w_scale[n];
-    if (d->bias) {
-        L->bias.assign(d->bias, d->bias + N);
-        std::copy(d->bias, d->bias + N, bias.begin());
+    if (bias_src) {
+        L->bias.assign(bias_src, bias_src + N);
+        std::copy(bias_src, bias_src + N, bias.begin());
     }
     FLEXIQ_HIP(hipMalloc((void **)&L->d_cs, 2 * (size_t)Npad * sizeof(float)));   // scales, then biases
     L->d_bias = L->d_cs + Npad;

@@ -232,6 +232,44 @@ def test_dynamic_positions_conv(env):
     fq.flexiq_static_positions(hl)
 
 
+def test_two_layer_chain_static_reorder(env):
+    # Section 5, steps 1-2: fc1 is packed so that it writes its int8 outputs in the stored channel order of fc2;
+    # the chain fc1 -> int8 requant -> fc2 then needs no run-time reorder and equals the oracle's chain, in which
+    # the oracle permutes explicitly.  Run once with calibrated and once with run-time positions for fc2.
+    torch, oracle, fq, dev = env
+    M, K1, N1, N2, gs = 300, 192, 256, 96, 32
+    c1 = workloads.make_linear("chain1", 8, 201, M, K1, N1, gs, outlier_frac=0.02)
+    c2 = workloads.make_linear("chain2", 8, 202, M, N1, N2, gs, outlier_frac=0.02)
+    xs1, am1 = __import__("helpers").calib(c1)
+    o1 = oracle.prepare_layer(c1.W, am1, xs1, gs, bias=c1.bias)
+    Xq = oracle.quantize(c1.X, xs1)[:, o1.perm]
+    r1, r2 = 0.5, 0.75
+    acc1 = oracle.forward_gemm(o1, Xq, r1)
+    y1 = oracle.dequant_f64(acc1, xs1, o1.w_scale, o1.bias)
+    s_mid = float(np.abs(y1).max() / 127.0)                       # scale of the intermediate int8 tensor
+    q1 = oracle.requant_i8(acc1, xs1, o1.w_scale, s_mid, o1.bias)   # original output-channel order
+    o2 = oracle.prepare_layer(c2.W, np.abs(q1).max(0).astype(np.float32) * np.float32(s_mid), s_mid, gs, bias=c2.bias)
+    X2 = np.ascontiguousarray(q1[:, o2.perm])                     # what fc2 reads: its stored order
+    # HIP side: fc2 first (its order is what fc1 must produce), then fc1 with that output order
+    h2 = fq.flexiq_quantize_pack(c2.W, np.abs(q1).max(0).astype(np.float32) * np.float32(s_mid), s_mid, gs, bias=c2.bias)
+    assert (h2.info()["perm"] == o2.perm).all()
+    h1 = fq.flexiq_quantize_pack(c1.W, am1, xs1, gs, bias=c1.bias, out_perm=o2.perm)
+    assert (h1.info()["w_scale"] == o1.w_scale[o2.perm]).all()
+    fq.flexiq_set_ratio(h1, r1)
+    fq.flexiq_set_ratio(h2, r2)
+    mid = fq.flexiq_mixed_gemm(h1, _dev(torch, Xq, dev), q=True, out_scale=s_mid)["q"]
+    assert (mid.cpu().numpy() == X2).all()
+    got = fq.flexiq_mixed_gemm(h2, mid, acc=True)["acc"].cpu().numpy()
+    assert (got == oracle.forward_gemm(o2, X2, r2)).all()
+    G4 = oracle.groups_for_ratio(r2, o2.G)
+    fq.flexiq_dynamic_positions(h2, mid)
+    dyn = oracle.dynamic_act_shifts(X2, gs, G4, o2.a_shift)
+    got = fq.flexiq_mixed_gemm(h2, mid, acc=True)["acc"].cpu().numpy()
+    assert (got == oracle.mixed_gemm(X2, o2.Wq.reshape(N2, N1), gs, G4, dyn, o2.w_shift)).all()
+    with pytest.raises(fq.FlexiqError):
+        fq.flexiq_quantize_pack(c1.W, am1, xs1, gs, out_perm=np.zeros(N1, np.int32))   # not a permutation
+
+
 def test_gemm_saturating_inputs(env):
     # activations far beyond the calibrated range: the clamp of the lowering is active everywhere
     torch, oracle, fq, dev = env
