@@ -151,6 +151,32 @@ def main():
         per_r_us[r] = float(np.median(ts))
         del g
 
+    # the same GEMM when the producing layer has lowered the activations already (flexiq_out.lower_for on the
+    # producer, flexiq_input_prelowered on this layer): what the fused producer epilogue buys the consumer.
+    # Side measurement; the timed region above lowers on the fly.
+    pre = []
+    fq.flexiq_input_prelowered(layer, True)
+    for r in RATIOS[1:]:
+        fq.flexiq_set_ratio(layer, r)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(10):
+                fq.flexiq_mixed_gemm(layer, Xq, out_scale=out_scale, bufs=bufs, **want)
+        g.replay()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(7):
+            a0 = torch.cuda.Event(enable_timing=True)
+            a1 = torch.cuda.Event(enable_timing=True)
+            a0.record()
+            g.replay()
+            a1.record()
+            torch.cuda.synchronize()
+            ts.append(a0.elapsed_time(a1) * 1e3 / 10)
+        pre.append({"r": r, "us": round(float(np.median(ts)), 2)})
+        del g
+    fq.flexiq_input_prelowered(layer, False)
+
     # ratio switch (Section 7 "Low-bitwidth Ratio Adjustment"): host cost of one flexiq_set_ratio call through the
     # Python binding (an upper bound of the C call, which writes one integer), and the per-launch time of the
     # sweep, where every launch follows a switch, against launches at a fixed ratio
@@ -253,7 +279,7 @@ def main():
                                "per step, epilogue=%s" % (args.layer, M, K, N, gs, list(RATIOS),
                                                           {"q": "int8 requant", "y": "fp32 dequant", "acc": "int32 dump"}[args.out]),
                    "M": M, "K": K, "N": N, "group_size": gs, "ratios": list(RATIOS)},
-        "roofline": roofline, "cpu_baseline": cpu, "per_r": per_r, "dynamic_positions": dyn, "ratio_switch": ratio_switch, "parity": parity,
+        "roofline": roofline, "cpu_baseline": cpu, "per_r": per_r, "prelowered_input": pre, "dynamic_positions": dyn, "ratio_switch": ratio_switch, "parity": parity,
     }
     print(json.dumps(line), flush=True)
 

@@ -120,6 +120,12 @@ int flexiq_bitlower(const int8_t *src, uint8_t *dst, int64_t rows, int32_t C, in
  * One kernel, no allocation, no host synchronisation.  rows == 0: every scanned group gets position 0. */
 int flexiq_dynamic_positions(flexiq_layer *layer, const int8_t *X, int64_t rows, void *stream);
 
+/* Tells the handle that the activations handed to flexiq_mixed_gemm / flexiq_mixed_conv_implicit are bit-lowered
+ * already for its current ratio and positions (written by the producing layer with flexiq_out.lower_for): the
+ * kernel then copies them like 8-bit activations and only the weights of the 4-bit groups differ.  Host-side
+ * switch, O(1); on != 0 enables.  The caller keeps producer and consumer settings consistent. */
+int flexiq_input_prelowered(flexiq_layer *layer, int on);
+
 /* Back to the calibrated positions of flexiq_quantize_pack (host-side switch, O(1)). */
 int flexiq_static_positions(flexiq_layer *layer);
 
@@ -137,12 +143,19 @@ int flexiq_permute_channels(const flexiq_layer *layer, const int8_t *src, int8_t
  *   q   : dev int8  [M][N]  next layer's input: clip(round_half_even(fma(float(acc), m[n], b[n])), -128, 127)
  *                           with m[n] = (x_scale*w_scale[n]) * (1/out_scale), b[n] = bias[n] * (1/out_scale),
  *                           every operation a correctly rounded fp32 one
- *   out_scale : scale of q (used only when q != NULL; must be > 0) */
+ *   out_scale : scale of q (used only when q != NULL; must be > 0)
+ *   lower_for : optional.  The layer that will consume q (its C == this layer's N, and this layer was packed
+ *               with out_perm = that layer's stored channel order).  The codes of the columns that are 4-bit
+ *               channels of the consumer under ITS current ratio are then written bit-lowered at ITS current
+ *               positions, L(v, s) << s (Section 4.1), in the same pass: the consumer, switched with
+ *               flexiq_input_prelowered(consumer, 1), no longer lowers them itself.  Both settings of the consumer
+ *               are read when this call is made.  NULL: plain int8 codes */
 typedef struct {
     int32_t *acc;
     float *y;
     int8_t *q;
     float out_scale;
+    const flexiq_layer *lower_for;
 } flexiq_out;
 
 /* Mixed-precision GEMM (Sections 2.3, 7):
@@ -154,7 +167,7 @@ typedef struct {
  * those of the last flexiq_dynamic_positions scan); the weights of 4-bit groups are read from the handle's cached
  * lowered copies.  Layer must be linear (R = S = 1).  Launches on `stream`; allocates nothing; returns before the
  * kernel has run.  Errors: FLEXIQ_EINVAL (null / inconsistent arguments, M >= 2^31 - 256, more than 159 channel
- * groups, current device is not the handle's), FLEXIQ_EALIGN, FLEXIQ_EHIP. */
+ * groups, a padded weight matrix of 1 GiB or more, current device is not the handle's), FLEXIQ_EALIGN, FLEXIQ_EHIP. */
 int flexiq_mixed_gemm(const flexiq_layer *layer, const int8_t *X, int64_t M, const flexiq_out *out, void *stream);
 
 /* The same sum as an implicit GEMM over (filter tap, channel) for a convolution layer:

@@ -24,7 +24,8 @@ class _PackDesc(C.Structure):
 
 
 class _Out(C.Structure):
-    _fields_ = [("acc", C.c_void_p), ("y", C.c_void_p), ("q", C.c_void_p), ("out_scale", C.c_float)]
+    _fields_ = [("acc", C.c_void_p), ("y", C.c_void_p), ("q", C.c_void_p), ("out_scale", C.c_float),
+                ("lower_for", C.c_void_p)]
 
 
 def exported_symbols():
@@ -32,7 +33,7 @@ def exported_symbols():
     return ["flexiq_strerror", "flexiq_last_hip_error", "flexiq_quantize_pack", "flexiq_layer_free",
             "flexiq_layer_info", "flexiq_layer_dump", "flexiq_set_ratio", "flexiq_quantize_act",
             "flexiq_bitlower", "flexiq_dynamic_positions", "flexiq_static_positions", "flexiq_layer_positions",
-            "flexiq_permute_channels", "flexiq_mixed_gemm", "flexiq_mixed_conv_implicit"]
+            "flexiq_input_prelowered", "flexiq_permute_channels", "flexiq_mixed_gemm", "flexiq_mixed_conv_implicit"]
 
 
 def load():
@@ -57,6 +58,7 @@ def load():
                                   C.c_int, C.c_void_p]
     L.flexiq_dynamic_positions.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     L.flexiq_static_positions.argtypes = [C.c_void_p]
+    L.flexiq_input_prelowered.argtypes = [C.c_void_p, C.c_int]
     L.flexiq_layer_positions.argtypes = [C.c_void_p, C.c_void_p]
     L.flexiq_permute_channels.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     L.flexiq_mixed_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(_Out), C.c_void_p]
@@ -187,6 +189,11 @@ def flexiq_dynamic_positions(layer: Layer, X) -> None:
     _check(load().flexiq_dynamic_positions(layer._h, X.data_ptr(), rows, _stream()))
 
 
+def flexiq_input_prelowered(layer: Layer, on: bool) -> None:
+    """The activations given to this layer's GEMM / conv calls are lowered already (flexiq_out.lower_for)."""
+    _check(load().flexiq_input_prelowered(layer._h, 1 if on else 0))
+
+
 def flexiq_static_positions(layer: Layer) -> None:
     _check(load().flexiq_static_positions(layer._h))
 
@@ -205,7 +212,7 @@ def flexiq_permute_channels(layer: Layer, src):
     return dst
 
 
-def _outs(shape, device, want_acc, want_y, want_q, out_scale, bufs):
+def _outs(shape, device, want_acc, want_y, want_q, out_scale, bufs, lower_for=None):
     import torch
     acc = y = q = None
     if want_acc:
@@ -215,30 +222,33 @@ def _outs(shape, device, want_acc, want_y, want_q, out_scale, bufs):
     if want_q:
         q = bufs.get("q") if bufs and "q" in bufs else torch.empty(shape, dtype=torch.int8, device=device)
     o = _Out(acc.data_ptr() if acc is not None else None, y.data_ptr() if y is not None else None,
-             q.data_ptr() if q is not None else None, float(out_scale))
+             q.data_ptr() if q is not None else None, float(out_scale),
+             lower_for._h if lower_for is not None else None)
     return o, {"acc": acc, "y": y, "q": q}
 
 
 def flexiq_mixed_gemm(layer: Layer, X, acc: bool = False, y: bool = False, q: bool = False,
-                      out_scale: float = 1.0, bufs: Optional[dict] = None):
-    """X: int8 cuda [M][C] in stored channel order.  Returns a dict of the requested outputs."""
+                      out_scale: float = 1.0, bufs: Optional[dict] = None, lower_for: Optional[Layer] = None):
+    """X: int8 cuda [M][C] in stored channel order.  Returns a dict of the requested outputs.
+    lower_for: the layer that consumes q (flexiq_out.lower_for)."""
     import torch
     assert X.is_cuda and X.dtype == torch.int8 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == layer.C
     M = X.shape[0]
-    o, res = _outs((M, layer.N), X.device, acc, y, q, out_scale, bufs)
+    o, res = _outs((M, layer.N), X.device, acc, y, q, out_scale, bufs, lower_for)
     _check(load().flexiq_mixed_gemm(layer._h, X.data_ptr(), M, C.byref(o), _stream()))
     return res
 
 
 def flexiq_mixed_conv_implicit(layer: Layer, X, stride: int, pad: int, acc: bool = False, y: bool = False,
-                               q: bool = False, out_scale: float = 1.0, bufs: Optional[dict] = None):
+                               q: bool = False, out_scale: float = 1.0, bufs: Optional[dict] = None,
+                               lower_for: Optional[Layer] = None):
     """X: int8 cuda NHWC [B][H][W][C] in stored channel order."""
     import torch
     assert X.is_cuda and X.dtype == torch.int8 and X.is_contiguous() and X.dim() == 4 and X.shape[3] == layer.C
     B, H, Wd, _ = X.shape
     Ho = (H + 2 * pad - layer.R) // stride + 1
     Wo = (Wd + 2 * pad - layer.S) // stride + 1
-    o, res = _outs((B, Ho, Wo, layer.N), X.device, acc, y, q, out_scale, bufs)
+    o, res = _outs((B, Ho, Wo, layer.N), X.device, acc, y, q, out_scale, bufs, lower_for)
     _check(load().flexiq_mixed_conv_implicit(layer._h, X.data_ptr(), B, H, Wd, stride, pad, C.byref(o), _stream()))
     return res
 

@@ -39,7 +39,9 @@ void set_hip_error(hipError_t e, const char *what);
 //   w4x    int8  [U][2][Npad][16]   the same 4-bit codes, each put back at its extraction position as an
 //                                   int8 value (code << wshift), in the layout of w8: the copy the matrix
 //                                   kernel streams when the problem is compute-bound, so that no expansion
-//                                   work shares the vector ALU with the matrix pipe
+//                                   work shares the vector ALU with the matrix pipe.  w8 and w4x are the two
+//                                   halves of one allocation (d_w4x = d_w8 + U*Npad*32): one buffer
+//                                   descriptor reaches both
 //   wshift uint8 [G+1][Npad]        weight extraction position per (group, output channel); row G is zero
 //                                   (looked up by the pad unit)
 //   ashift int32 [G+1]              activation extraction position per group (+1 entry for the pad unit);
@@ -66,6 +68,7 @@ struct flexiq_layer {
     int32_t *d_ashift_dyn;
     uint32_t *d_scan;
     bool dynamic;   // GEMM / conv calls read d_ashift_dyn instead of d_ashift
+    bool x_prelowered;   // the caller's activations are bit-lowered already (by the producing layer's epilogue)
     float *d_cs;
     float *d_bias;
     int32_t *d_perm;

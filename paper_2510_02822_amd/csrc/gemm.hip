@@ -97,13 +97,23 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
                   int H, int Wd, int Ho, int Wo, int stride, int pad)
 {
     GemmParams p;
-    p.X = X; p.W8 = L->d_w8; p.W4 = L->d_w4; p.W4X = L->d_w4x; p.wshift = L->d_wshift;
+    p.X = X; p.W8 = L->d_w8; p.W4 = L->d_w4; p.wshift = L->d_wshift;
     p.ashift = L->dynamic ? L->d_ashift_dyn : L->d_ashift;
     p.cs = L->d_cs; p.bias = L->d_bias;
     p.acc = out->acc; p.y = out->y; p.q = out->q;
     p.r_out = out->q ? 1.0f / out->out_scale : 1.0f;
     p.M = M; p.N = L->N; p.Npad = L->Npad; p.C = L->C;
-    p.K4 = L->max_4bit_ch;
+    p.K4 = L->x_prelowered ? 0 : L->max_4bit_ch;
+    p.K4pre = L->x_prelowered ? L->max_4bit_ch : 0;
+    p.next_ashift = nullptr; p.next_K4 = 0; p.next_G = 0; p.next_gs_log2 = 5;
+    if (out->lower_for) {
+        const flexiq_layer *nx = out->lower_for;
+        if (!out->q || nx->C != L->N || nx->device != L->device) return FLEXIQ_EINVAL;
+        p.next_ashift = nx->dynamic ? nx->d_ashift_dyn : nx->d_ashift;
+        p.next_K4 = nx->max_4bit_ch;
+        p.next_G = nx->G;
+        p.next_gs_log2 = nx->group_size == 64 ? 6 : 5;
+    }
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.U = L->U; p.CU = L->C / kUnit; p.T = L->T; p.G = L->G;
     {   // the handle's buffers live on the device it was packed on
@@ -114,10 +124,11 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     if (L->G + 1 > 160) return FLEXIQ_EINVAL;  // position table kept in LDS
     if (M > 0x7fffffff - 256) return FLEXIQ_EINVAL;  // row indices are 32-bit in the kernel
     if (L->C / kUnit >= 2 * 65535) return FLEXIQ_EINVAL;  // K-step indices are kept in 16-bit fields
-    if ((int64_t)L->U * 32 * L->Npad > 0x7fffffff) return FLEXIQ_EINVAL;  // weight window must fit a buffer descriptor
+    if ((int64_t)L->U * 32 * L->Npad * 2 > 0x7fffffff) return FLEXIQ_EINVAL;  // both int8 weight copies must fit one buffer descriptor
     p.H = H; p.Wd = Wd; p.Ho = Ho; p.Wo = Wo; p.S = L->S; p.stride = stride; p.pad = pad;
     const int steps = L->T * ((p.CU + 1) / 2);
-    const bool packed = g_force_packed >= 0 ? g_force_packed != 0 : M <= kPackedMaxRows;
+    // (activations that arrive lowered always pair with the expanded weight copy)
+    const bool packed = !L->x_prelowered && (g_force_packed >= 0 ? g_force_packed != 0 : M <= kPackedMaxRows);
     int cnt;
     g_last_shape = choose_shape(M, L->N, steps, conv, packed);
     const TileShape &ts = shapes(&cnt)[g_last_shape];

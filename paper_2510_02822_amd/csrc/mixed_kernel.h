@@ -45,9 +45,9 @@ typedef short v2s __attribute__((ext_vector_type(2)));
 
 struct GemmParams {
     const int8_t *X;
-    const int8_t *W8;
+    const int8_t *W8;    // 8-bit weights, and right behind them (U * 32 * Npad bytes further) the 4-bit codes expanded
+                         // to int8 at their position, in the same layout
     const uint8_t *W4;
-    const int8_t *W4X;   // 4-bit codes expanded to int8 at their position, layout of W8
     const uint8_t *wshift;
     const int32_t *ashift;
     const float *cs;
@@ -58,7 +58,13 @@ struct GemmParams {
     float r_out;     // 1 / out_scale
     int64_t M;       // output rows (tokens, or B*Ho*Wo output pixels)
     int32_t N, Npad, C;
-    int32_t K4;      // max_4bit_ch: leading stored channels computed at 4 bits
+    int32_t K4;      // leading stored channels whose ACTIVATIONS are bit-lowered in the kernel (max_4bit_ch, or 0
+                     // when the caller hands in activations that are lowered already)
+    int32_t K4pre;   // leading stored channels whose activations arrive lowered already (their weights are the 4-bit
+                     // copies although the kernel treats the activations as 8-bit); 0 in the ordinary case
+    // optional: lower the int8 output for the layer that consumes it (its positions, its 4-bit channel count)
+    const int32_t *next_ashift;
+    int32_t next_K4, next_G, next_gs_log2;
     int32_t gs_shift;  // log2(group_size / 32): unit c32 belongs to group c32 >> gs_shift
     int32_t G;       // channel groups
     int32_t U;       // units in the reduction (even per tap), CU = C/32 per tap
@@ -164,8 +170,9 @@ struct Cfg {
     static constexpr int WPS = (BN + 2) * 16;           // bytes per weight k-plane (+2 pieces staggers the planes over the banks)
     static constexpr int STAGE = XBYTES + 4 * WPS;
     static constexpr int NSTAGE = 4;
-    // activation positions of up to 160 groups; scale and bias of the columns of two consecutive tiles
-    static constexpr int TABLE = 640 + 2 * (2 * BN * 4);
+    // activation positions of up to 160 groups; scale, bias and the consumer's extraction position of the columns
+    // of two consecutive tiles
+    static constexpr int TABLE = 640 + 2 * (3 * BN * 4);
     static constexpr int RING = NSTAGE * STAGE;
     // A block may walk several output tiles.  Not for the largest tiles: their accumulators fill the register
     // file, and the values that would have to stay live across an epilogue do not fit beside them.
@@ -202,7 +209,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     constexpr int NMF = TM * TN;  // MFMAs per k-half
     extern __shared__ __align__(16) unsigned char lds[];
     unsigned char *const sa_tab = lds + C_::RING;
-    float *const cs_tab = reinterpret_cast<float *>(sa_tab + 640);  // two copies (tile parity) of [BN] scales + [BN] biases
+    float *const cs_tab = reinterpret_cast<float *>(sa_tab + 640);  // two copies (tile parity) of [BN] scales, [BN] biases, [BN] positions
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -244,11 +251,12 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     // Activations: a window per tile; reads past it return zero, which is what rows beyond M, padded pixels
     // and dummy staging rows need.
     constexpr int kRsrcFlags = 0x00020000;
-    const __amdgpu_buffer_rsrc_t rw8 = __builtin_amdgcn_make_buffer_rsrc((void *)p.W8, 0, p.U * 32 * p.Npad, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rw8 = __builtin_amdgcn_make_buffer_rsrc((void *)p.W8, 0, 2 * p.U * 32 * p.Npad, kRsrcFlags);   // both int8 copies
     const __amdgpu_buffer_rsrc_t rw4 = __builtin_amdgcn_make_buffer_rsrc((void *)p.W4, 0, p.U * 16 * p.Npad, kRsrcFlags);
-    const __amdgpu_buffer_rsrc_t rw4x = __builtin_amdgcn_make_buffer_rsrc((void *)p.W4X, 0, p.U * 32 * p.Npad, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t rws = __builtin_amdgcn_make_buffer_rsrc((void *)p.wshift, 0, (p.G + 1) * p.Npad, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t rcs = __builtin_amdgcn_make_buffer_rsrc((void *)p.cs, 0, 2 * p.Npad * 4, kRsrcFlags);   // scales, then biases
+    const __amdgpu_buffer_rsrc_t rnx =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(p.next_ashift ? p.next_ashift : p.ashift), 0, p.next_ashift ? (p.next_G + 1) * 4 : 0, kRsrcFlags);
     // ---- the tile being LOADED (it runs ahead of the tile being computed by three K-steps, which may be
     // several tiles when K is short): its index, activation window and first column
     int ltile = ctile;
@@ -327,9 +335,12 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     // cs/bias are padded to Npad >= c0 + BN.
     auto fetch_scales = [&](int c0, int par) {
         if (wave * 64 < BN) {
-            float *dst = cs_tab + par * (2 * BN) + wave * 64;
+            float *dst = cs_tab + par * (3 * BN) + wave * 64;
             lds_load4(rcs, dst, (wave * 64 + lane) * 4, c0 * 4);
             lds_load4(rcs, dst + BN, (wave * 64 + lane) * 4, (p.Npad + c0) * 4);
+            // position of the consumer's channel group that output column c0 + c falls into (an empty descriptor,
+            // hence zeros, when there is no consumer to lower for)
+            lds_load4(rnx, dst + 2 * BN, ((c0 + wave * 64 + lane) >> p.next_gs_log2) * 4, 0);
         }
     };
     fetch_scales(n0, 0);
@@ -395,6 +406,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     // (The K offset of an activation piece goes into the per-lane offset, which the buffer range check covers:
     // what the pad unit of an odd unit count would read past the end of the window's last row comes back as zero.)
     const int ustride = 32 * p.Npad;   // bytes between the units of the 8-bit weight layout
+    const int w4x_delta = p.U * ustride;   // from the 8-bit copy to the expanded 4-bit copy
     auto gload = [&](v4i(&sr)[NSR > 0 ? NSR : 1], int(&wsh)[2][WL4], int i, int mode, unsigned char *stage) {
         const int c64 = it_c64;
         if (i < XI) {
@@ -416,15 +428,15 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
             const int idx = wave + 4 * j;                       // (k-plane, 64-row block) of this copy
             const int pl = idx / (BN / 64), blk = idx % (BN / 64);
             const int h = pl >> 1;                              // unit of the K-step
-            const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
+            // 4-bit unit?  Known at compile time in the steady steps.  Activations that arrive lowered make every
+            // step an 8-bit step as far as they are concerned, while the weights of their leading channels still come
+            // from the 4-bit copy: that case costs the 8-bit steps one scalar compare.
+            const bool four_mode = mode == kMode44 || (mode == kMode48 && h == 0);
+            const bool four = four_mode || (!PACKED4 && (2 * c64 + h) * 32 < p.K4pre);
             const int wbase = (it_tap * (2 * SP) + 2 * c64) * ustride + ld_n0 * 16;   // same for every item of the step
             const int soff = wbase + (h ? ustride : 0);
             unsigned char *dst = stage + XBYTES + pl * WPS + blk * 1024;
-            if (four) {
-                if (!PACKED4) lds_load16(rw4x, dst, wvoff[j], soff);
-            } else {
-                lds_load16(rw8, dst, wvoff[j], soff);
-            }
+            if (!(PACKED4 && four)) lds_load16(rw8, dst, wvoff[j], soff + (four ? w4x_delta : 0));
         } else if (PACKED4) {
             const int h = (i - XI - WI) / WL4, j = (i - XI - WI) % WL4;
             const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
@@ -687,14 +699,15 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     const bool want_q = p.q != nullptr, want_y = p.y != nullptr, want_acc = p.acc != nullptr;
 #endif
     const bool n_vec = (p.N & 3) == 0;
+    const bool lower_out = p.next_ashift != nullptr;   // int8 output lowered for the consuming layer
     const bool q_rows = want_q && (p.N & 15) == 0;   // int8 output as 16-byte row-contiguous pieces
     const int frag_half_e = lane >> 5, frag_row_e = lane & 31;
     // (one call handles fragment column a; the variant is chosen per column, which keeps the live ranges of the
     // accumulators short where the variants branch apart)
-    auto epilogue = [&](auto a_, auto wq_, auto wy_, auto wa_, auto nv_, auto qr_) {
-        const bool wq = wq_, wy = wy_, wa = wa_, nv = nv_, qr = qr_;
+    auto epilogue = [&](auto a_, auto wq_, auto wy_, auto wa_, auto nv_, auto qr_, auto lw_) {
+        const bool wq = wq_, wy = wy_, wa = wa_, nv = nv_, qr = qr_, lw = lw_;
         constexpr int a = decltype(a_)::value;
-        const float *tab = cs_tab + parity * (2 * BN);
+        const float *tab = cs_tab + parity * (3 * BN);
         {
             uint32_t qrow[TM][4];   // int8 codes of the four quads of fragment (a, b)
 #pragma unroll
@@ -710,11 +723,22 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                     csv[0] = cs.x; csv[1] = cs.y; csv[2] = cs.z; csv[3] = cs.w;
                     biv[0] = bi.x; biv[1] = bi.y; biv[2] = bi.z; biv[3] = bi.w;
                 }
+                float qlo = -128.0f, qhi = 127.0f;   // clamp of the int8 code
+                uint32_t qmask = 0xFFFFFFFFu;
                 if (wq) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         mul[i] = csv[i] * p.r_out;
                         add[i] = biv[i] * p.r_out;
+                    }
+                    // Output lowered for the consumer (its 4-bit channels only): L(v, s) << s = clamp(v, -(8<<s),
+                    // (8<<s)-1) with the low s bits cleared; the four columns of a quad share a channel group.
+                    if (lw) {
+                        const bool lowered = n < p.next_K4;
+                        const int sp = reinterpret_cast<const int *>(tab + 2 * BN)[nl];
+                        qhi = (float)((8 << (lowered ? sp : 4)) - 1);
+                        qlo = -1.0f - qhi;
+                        qmask = lowered ? 0x01010101u * ((0xFFu << sp) & 0xFFu) : 0xFFFFFFFFu;
                     }
                 }
 #pragma unroll
@@ -728,10 +752,10 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             float t = __builtin_fmaf((float)iv[i], mul[i], add[i]);
-                            t = __builtin_amdgcn_fmed3f(t, -128.0f, 127.0f);
+                            t = __builtin_amdgcn_fmed3f(t, qlo, qhi);
                             u[i] = __builtin_bit_cast(uint32_t, t + 12582912.0f);  // 1.5 * 2^23: integer lands in the low bits
                         }
-                        qw = __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu);
+                        qw = (__builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu)) & qmask;
                         qrow[b][g] = qw;
                     }
                     if (!(wy || wa || (wq && !qr))) continue;   // nothing is stored quad by quad
@@ -811,10 +835,11 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
         const long long te0 = __builtin_readcyclecounter();
 #endif
         auto epilogue_col = [&](auto a_) {
-            if (q_rows && !want_y && !want_acc) epilogue(a_, T_{}, F_{}, F_{}, T_{}, T_{});
-            else if (n_vec && !want_q && want_y && !want_acc) epilogue(a_, F_{}, T_{}, F_{}, T_{}, F_{});
-            else if (n_vec && !want_q && !want_y && want_acc) epilogue(a_, F_{}, F_{}, T_{}, T_{}, F_{});
-            else epilogue(a_, want_q, want_y, want_acc, n_vec, q_rows);
+            if (q_rows && !want_y && !want_acc && !lower_out) epilogue(a_, T_{}, F_{}, F_{}, T_{}, T_{}, F_{});
+            else if (q_rows && !want_y && !want_acc) epilogue(a_, T_{}, F_{}, F_{}, T_{}, T_{}, T_{});
+            else if (n_vec && !want_q && want_y && !want_acc) epilogue(a_, F_{}, T_{}, F_{}, T_{}, F_{}, F_{});
+            else if (n_vec && !want_q && !want_y && want_acc) epilogue(a_, F_{}, F_{}, T_{}, T_{}, F_{}, F_{});
+            else epilogue(a_, want_q, want_y, want_acc, n_vec, q_rows, lower_out);
             FQ_SB();
         };
         epilogue_col(std::integral_constant<int, 0>{});

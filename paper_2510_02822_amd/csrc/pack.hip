@@ -322,7 +322,7 @@ struct DevBuf {  // frees on scope exit unless released
 extern "C" int flexiq_layer_free(flexiq_layer *L)
 {
     if (!L) return FLEXIQ_OK;
-    void *bufs[] = {L->d_w8, L->d_w4, L->d_w4x, L->d_wshift, L->d_ashift, L->d_ashift_dyn, L->d_scan, L->d_cs, L->d_perm};   // d_bias is the second half of d_cs
+    void *bufs[] = {L->d_w8, L->d_w4, L->d_wshift, L->d_ashift, L->d_ashift_dyn, L->d_scan, L->d_cs, L->d_perm};   // d_w4x is the second half of d_w8, d_bias of d_cs
     int rc = FLEXIQ_OK;
     for (void *b : bufs)
         if (b && hipFree(b) != hipSuccess) rc = FLEXIQ_EHIP;
@@ -385,7 +385,7 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
     L->max_4bit_ch = 0;
     L->x_scale = d->x_scale;
     L->has_bias = d->bias != nullptr;
-    L->d_w8 = nullptr; L->d_w4 = nullptr; L->d_w4x = nullptr; L->d_wshift = nullptr; L->d_ashift = nullptr; L->d_ashift_dyn = nullptr; L->d_scan = nullptr; L->dynamic = false;
+    L->d_w8 = nullptr; L->d_w4 = nullptr; L->d_w4x = nullptr; L->d_wshift = nullptr; L->d_ashift = nullptr; L->d_ashift_dyn = nullptr; L->d_scan = nullptr; L->dynamic = false; L->x_prelowered = false;
     L->d_cs = nullptr; L->d_bias = nullptr; L->d_perm = nullptr;
     FLEXIQ_HIP(hipGetDevice(&L->device));
     const int Npad = L->Npad;
@@ -451,9 +451,11 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
     // one more (zero) row than groups: the pad unit of an odd unit count looks up group G
     FLEXIQ_HIP(hipMalloc((void **)&L->d_wshift, (size_t)(G + 1) * Npad));
     FLEXIQ_HIP(hipMemset(L->d_wshift, 0, (size_t)(G + 1) * Npad));
-    FLEXIQ_HIP(hipMalloc((void **)&L->d_w8, (size_t)U * 2 * Npad * 16));
+    // the 8-bit copy and the expanded 4-bit copy share one allocation: the kernel reaches both through one
+    // buffer descriptor and picks the copy with a scalar offset
+    FLEXIQ_HIP(hipMalloc((void **)&L->d_w8, (size_t)U * Npad * 32 * 2));
+    L->d_w4x = L->d_w8 + (size_t)U * Npad * 32;
     FLEXIQ_HIP(hipMalloc((void **)&L->d_w4, (size_t)U * Npad * 16));
-    FLEXIQ_HIP(hipMalloc((void **)&L->d_w4x, (size_t)U * Npad * 32));
 
     k_weight_shift<<<(unsigned)cdiv((int64_t)N * G, 256), 256>>>((const int8_t *)dQ.p, L->d_perm, N, T, C, gs, Npad,
                                                                  (uint8_t *)dWsNG.p, L->d_wshift);
@@ -586,6 +588,13 @@ extern "C" int flexiq_dynamic_positions(flexiq_layer *L, const int8_t *X, int64_
                                                                             L->d_ashift, L->d_ashift_dyn);
     FLEXIQ_HIP(hipGetLastError());
     L->dynamic = true;
+    return FLEXIQ_OK;
+}
+
+extern "C" int flexiq_input_prelowered(flexiq_layer *L, int on)
+{
+    if (!L) return FLEXIQ_EINVAL;
+    L->x_prelowered = on != 0;
     return FLEXIQ_OK;
 }
 

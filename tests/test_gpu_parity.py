@@ -266,8 +266,26 @@ def test_two_layer_chain_static_reorder(env):
     dyn = oracle.dynamic_act_shifts(X2, gs, G4, o2.a_shift)
     got = fq.flexiq_mixed_gemm(h2, mid, acc=True)["acc"].cpu().numpy()
     assert (got == oracle.mixed_gemm(X2, o2.Wq.reshape(N2, N1), gs, G4, dyn, o2.w_shift)).all()
+    fq.flexiq_static_positions(h2)
+    # Fused producer: fc1's epilogue also bit-lowers the columns that are 4-bit channels of fc2 (fc2's ratio and
+    # positions); fc2, told so, copies its activations like 8-bit ones.  Same accumulators as lowering on the fly.
+    for r2b in (0.75, 1.0, 0.25, 0.0):
+        k4 = fq.flexiq_set_ratio(h2, r2b)
+        mid_l = fq.flexiq_mixed_gemm(h1, _dev(torch, Xq, dev), q=True, out_scale=s_mid, lower_for=h2)["q"]
+        sh = np.repeat(o2.a_shift.astype(np.int32), gs)[None, :]
+        want_mid = X2.astype(np.int32).copy()
+        want_mid[:, :k4] = (np.clip(want_mid[:, :k4] >> sh[:, :k4], -8, 7)) << sh[:, :k4]
+        assert all(oracle.bitlower(int(X2[i, j]), int(sh[0, j])) << int(sh[0, j]) == want_mid[i, j]
+                   for i in (0, 7, 299) for j in range(0, k4, 5))
+        assert (mid_l.cpu().numpy().astype(np.int32) == want_mid).all(), r2b
+        fq.flexiq_input_prelowered(h2, True)
+        got = fq.flexiq_mixed_gemm(h2, mid_l, acc=True)["acc"].cpu().numpy()
+        fq.flexiq_input_prelowered(h2, False)
+        assert (got == oracle.forward_gemm(o2, X2, r2b)).all(), r2b
     with pytest.raises(fq.FlexiqError):
         fq.flexiq_quantize_pack(c1.W, am1, xs1, gs, out_perm=np.zeros(N1, np.int32))   # not a permutation
+    with pytest.raises(fq.FlexiqError):
+        fq.flexiq_mixed_gemm(h2, mid, q=True, out_scale=1.0, lower_for=h2)             # consumer width mismatch
 
 
 def test_gemm_saturating_inputs(env):
