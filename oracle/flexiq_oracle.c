@@ -352,13 +352,16 @@ void fq_o_dequant_f64(const int32_t *acc, int64_t M, int64_t N, float x_scale, c
 }
 
 /* Requantised 8-bit output for the next layer (Eq. 1 applied to y with the
- * output scale).  The integer code is decided in fp32, by the same sequence
- * of correctly rounded single-precision operations the HIP library uses:
+ * output scale).  The paper fixes neither the precision nor the order of the
+ * operations of this step; the integer code is decided in fp32, by the same
+ * sequence of correctly rounded single-precision operations the HIP library
+ * uses.  The code is formed in offset form (code + 128, an unsigned byte):
  *   c[n]   = S_x * S_w[n]            r = 1 / S_out
- *   mul[n] = c[n] * r                add[n] = bias[n] * r
- *   t      = fma(float(acc), mul[n], add[n])          (one rounding)
- *   q      = clip(round_half_even(t), -128, 127)
- * Compile with -ffp-contract=off so that no other operation is fused.       */
+ *   mul[n] = c[n] * r                add[n] = bias[n] * r + 128   (two roundings)
+ *   t      = fma(float(acc), mul[n], add[n])                      (one rounding)
+ *   q      = clip(round_half_even(t), 0, 255) - 128
+ * which is clip(round(y / S_out), -128, 127) up to single-precision rounding
+ * of t.  Compile with -ffp-contract=off so that no other operation is fused. */
 void fq_o_requant_i8(const int32_t *acc, int64_t M, int64_t N, float x_scale, const float *w_scale,
                      const float *bias, float out_scale, int8_t *q)
 {
@@ -366,13 +369,14 @@ void fq_o_requant_i8(const int32_t *acc, int64_t M, int64_t N, float x_scale, co
     for (int64_t n = 0; n < N; ++n) {
         volatile float c = x_scale * w_scale[n];
         volatile float mul = c * r;
-        volatile float add = bias ? bias[n] * r : 0.0f;
+        volatile float add0 = bias ? bias[n] * r : 0.0f;
+        volatile float add = add0 + 128.0f;
         for (int64_t m = 0; m < M; ++m) {
             float t = fmaf((float)acc[m * N + n], mul, add);
             t = nearbyintf(t);
-            if (t < -128.0f) t = -128.0f;
-            if (t > 127.0f) t = 127.0f;
-            q[m * N + n] = (int8_t)t;
+            if (t < 0.0f) t = 0.0f;
+            if (t > 255.0f) t = 255.0f;
+            q[m * N + n] = (int8_t)((int)t - 128);
         }
     }
 }

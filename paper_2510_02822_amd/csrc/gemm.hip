@@ -103,8 +103,8 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     p.acc = out->acc; p.y = out->y; p.q = out->q;
     p.r_out = out->q ? 1.0f / out->out_scale : 1.0f;
     p.M = M; p.N = L->N; p.Npad = L->Npad; p.C = L->C;
-    p.K4 = L->x_prelowered ? 0 : L->max_4bit_ch;
-    p.K4pre = L->x_prelowered ? L->max_4bit_ch : 0;
+    p.K4 = L->max_4bit_ch;
+    p.x_pre = L->x_prelowered ? 1 : 0;
     p.next_ashift = nullptr; p.next_K4 = 0; p.next_G = 0; p.next_gs_log2 = 5;
     if (out->lower_for) {
         const flexiq_layer *nx = out->lower_for;

@@ -58,10 +58,9 @@ struct GemmParams {
     float r_out;     // 1 / out_scale
     int64_t M;       // output rows (tokens, or B*Ho*Wo output pixels)
     int32_t N, Npad, C;
-    int32_t K4;      // leading stored channels whose ACTIVATIONS are bit-lowered in the kernel (max_4bit_ch, or 0
-                     // when the caller hands in activations that are lowered already)
-    int32_t K4pre;   // leading stored channels whose activations arrive lowered already (their weights are the 4-bit
-                     // copies although the kernel treats the activations as 8-bit); 0 in the ordinary case
+    int32_t K4;      // max_4bit_ch: leading stored channels computed at 4 bits
+    int32_t x_pre;   // nonzero: the activations of those channels arrive lowered already (the kernel copies them like
+                     // 8-bit ones; the weights are the 4-bit copies all the same)
     // optional: lower the int8 output for the layer that consumes it (its positions, its 4-bit channel count)
     const int32_t *next_ashift;
     int32_t next_K4, next_G, next_gs_log2;
@@ -214,6 +213,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: lives in a scalar register
+    __builtin_assume(wave >= 0 && wave < 4);
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 #ifdef FLEXIQ_TIMING
     long long tq0 = __builtin_readcyclecounter(), tqa = 0, tqb = 0, tqc = 0, tqd = 0;
@@ -308,11 +308,13 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     load_tile_context(m0, n0);
     const int x_lds = (16 * wave) * 64 + lane * 16;   // piece j adds 64 rows: j * 4096
     int wvoff[WI];   // per-lane offset of direct weight load j: k-plane parity, 64-row block, row = lane
+    int wdst[WI];    // where it lands inside a stage (scalar)
 #pragma unroll
     for (int j = 0; j < WI; ++j) {
         const int idx = wave + 4 * j;
         const int pl = idx / (BN / 64), blk = idx % (BN / 64);
         wvoff[j] = ((pl & 1) * p.Npad + blk * 64 + lane) * 16;
+        wdst[j] = XBYTES + pl * WPS + blk * 1024;
     }
     // Direct weight load j of this wave: index wave + 4 j over (k-plane, block of 64 rows); scalar values.
     // Packed pieces: row tid + j * NT of the tile (one thread per row).
@@ -346,56 +348,82 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     fetch_scales(n0, 0);
 
     // ---- K-step enumeration, phase-major: all-4-bit steps, then mixed steps, then all-8-bit steps;
-    // the iterator points at the next tile to LOAD.  Scalar state only.
+    // the iterator points at the next K-step to LOAD.  Scalar state only.
     const int SP = (p.CU + 1) >> 1;           // steps per tap
     const int n4 = p.K4 >> 6;                 // full 4-bit steps per tap
     const int mixed = (p.K4 & 63) ? 1 : 0;    // one step per tap with a 4-bit and an 8-bit unit
     const int steps = p.T * SP;
+    const int ustride = 32 * p.Npad;          // bytes between the units of the 8-bit weight layout
+    const int w4x_delta = p.U * ustride;      // from the 8-bit copy to the expanded 4-bit copy
     // Phase ph covers c64 in [pb(ph), pe(ph)) of every tap; pn(ph) is the next non-empty phase (3 = done).
-    // The three small tables are packed into scalars and indexed with shifts, and the update is written with
-    // selects only: the steady-state loops stay free of branches and of scalar-memory waits.
+    // The three small tables are packed into scalars and indexed with shifts (no scalar-memory waits).
     const int ne0 = n4 > 0, ne1 = mixed > 0, ne2 = n4 + mixed < SP;
     const int first_phase = ne0 ? 0 : (ne1 ? 1 : (ne2 ? 2 : 3));
     const int next1 = ne1 ? 1 : (ne2 ? 2 : 3), next2 = ne2 ? 2 : 3;
     const uint64_t pb_tab = ((uint64_t)n4 << 16) | ((uint64_t)(n4 + mixed) << 32);                       // 16 bits per phase
     const uint64_t pe_tab = (uint64_t)n4 | ((uint64_t)(n4 + mixed) << 16) | ((uint64_t)SP << 32);
     const uint32_t pn_tab = (uint32_t)next1 | ((uint32_t)next2 << 4) | (3u << 8) | (3u << 12);             // 4 bits per phase
+    // how the activations of a phase's steps are staged: by the phase, unless they arrive lowered already (then
+    // every step copies them like an 8-bit step, while the weights still follow the phase)
+    const uint32_t pm_tab = p.x_pre ? ((uint32_t)kMode88 | (kMode88 << 4) | (kMode88 << 8) | (kModeNone << 12))
+                                    : ((uint32_t)kMode44 | (kMode48 << 4) | (kMode88 << 8) | (kModeNone << 12));
     auto pb = [&](int ph) { return (int)((pb_tab >> (16 * ph)) & 0xFFFFu); };
     auto pe = [&](int ph) { return (int)((pe_tab >> (16 * ph)) & 0xFFFFu); };
     auto pn = [&](int ph) { return (int)((pn_tab >> (4 * ph)) & 15u); };
     int it_phase = first_phase, it_tap = 0, it_dy = 0, it_dx = 0;
     int it_c64 = pb(first_phase);
+    // derived state, refreshed whenever phase, tap or tile change: end of the phase's range, staging mode of its
+    // steps, and the scalar offsets of the step's two weight units (tile column, tap, c64 and the choice between
+    // the 8-bit copy and the expanded 4-bit copy all folded in)
+    int it_pe, it_mode, it_w0, it_w1;
+    auto refresh_iterator = [&]() {
+        it_pe = pe(it_phase);
+        it_mode = (int)((pm_tab >> (4 * it_phase)) & 15u);
+        const int base = (it_tap * (2 * SP) + 2 * it_c64) * ustride + ld_n0 * 16;
+        it_w0 = base + (it_phase <= 1 ? w4x_delta : 0);
+        it_w1 = base + ustride + (it_phase == 0 ? w4x_delta : 0);
+    };
+    refresh_iterator();
+    // Within a phase and tap the update is three scalar additions; everything else (next tap, next phase, next
+    // output tile of the block: tile mapping and, for a convolution, the per-row gather state) sits behind one
+    // uniform branch.
     auto advance = [&]() {
         const int c = it_c64 + 1;
-        const bool wrap_c = c == pe(it_phase);          // this tap's part of the phase is finished
+        if (__builtin_expect(c != it_pe, 1)) {
+            it_c64 = c;
+            it_w0 += 2 * ustride;
+            it_w1 += 2 * ustride;
+            return;
+        }
         const int tap1 = it_tap + 1;
-        const bool wrap_t = wrap_c && tap1 == p.T;      // the phase is finished
-        const int ph_in = pn(it_phase);
-        // The tile is finished: move on to the block's next tile if there is one (a branch, taken once per tile;
-        // the tile mapping and, for a convolution, the per-row gather state are vector-ALU work).
-        bool go_next = false;
-        if (C_::MULTI && wrap_t && ph_in == 3) {
-            const int nt = ltile + (int)gridDim.x;
-            if (nt < total_tiles) {
-                go_next = true;
-                ltile = nt;
-                int tile_m, tile_n;
-                map_tile(nt, tile_m, tile_n);
-                load_tile_context((int64_t)tile_m * BM, tile_n * BN);
+        if (tap1 == p.T) {   // the phase is finished
+            int ph = pn(it_phase);
+            if (C_::MULTI && ph == 3) {   // and with it the tile: move on to the block's next tile if there is one
+                const int nt = ltile + (int)gridDim.x;
+                if (nt < total_tiles) {
+                    ltile = nt;
+                    int tile_m, tile_n;
+                    map_tile(nt, tile_m, tile_n);
+                    load_tile_context((int64_t)tile_m * BM, tile_n * BN);
+                    ph = first_phase;
+                }
+            }
+            it_phase = ph;
+            it_tap = 0;
+            it_dy = 0;
+            it_dx = 0;
+        } else {
+            it_tap = tap1;
+            if (CONV) {
+                const int dx1 = it_dx + 1;
+                const bool wrap_x = dx1 == p.S;
+                it_dy = wrap_x ? it_dy + 1 : it_dy;
+                it_dx = wrap_x ? 0 : dx1;
             }
         }
-        const int ph = wrap_t ? (go_next ? first_phase : ph_in) : it_phase;
-        if (CONV) {
-            const int dx1 = it_dx + 1;
-            const bool wrap_x = dx1 == p.S;
-            it_dy = wrap_t ? 0 : (wrap_c && wrap_x ? it_dy + 1 : it_dy);
-            it_dx = wrap_t ? 0 : (wrap_c ? (wrap_x ? 0 : dx1) : it_dx);
-        }
-        it_tap = wrap_t ? 0 : (wrap_c ? tap1 : it_tap);
-        it_c64 = wrap_c ? pb(ph) : c;
-        it_phase = ph;
+        it_c64 = pb(it_phase);
+        refresh_iterator();
     };
-    auto it_mode = [&]() { return it_phase == 0 ? kMode44 : (it_phase == 1 ? kMode48 : (it_phase == 2 ? kMode88 : kModeNone)); };
 
     // ---- staging registers (register-routed pieces only) and the descriptor of the tile they hold
     v4i sr[NSR > 0 ? NSR : 1];
@@ -405,8 +433,6 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     // Item i of the K-step the iterator points at: load it, either straight into `stage` or into registers.
     // (The K offset of an activation piece goes into the per-lane offset, which the buffer range check covers:
     // what the pad unit of an odd unit count would read past the end of the window's last row comes back as zero.)
-    const int ustride = 32 * p.Npad;   // bytes between the units of the 8-bit weight layout
-    const int w4x_delta = p.U * ustride;   // from the 8-bit copy to the expanded 4-bit copy
     auto gload = [&](v4i(&sr)[NSR > 0 ? NSR : 1], int(&wsh)[2][WL4], int i, int mode, unsigned char *stage) {
         const int c64 = it_c64;
         if (i < XI) {
@@ -428,15 +454,10 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
             const int idx = wave + 4 * j;                       // (k-plane, 64-row block) of this copy
             const int pl = idx / (BN / 64), blk = idx % (BN / 64);
             const int h = pl >> 1;                              // unit of the K-step
-            // 4-bit unit?  Known at compile time in the steady steps.  Activations that arrive lowered make every
-            // step an 8-bit step as far as they are concerned, while the weights of their leading channels still come
-            // from the 4-bit copy: that case costs the 8-bit steps one scalar compare.
+            // (which copy of the weights a unit reads is part of the iterator's offsets; only the packed-code
+            // variant needs to know here, to leave its 4-bit units to the register route)
             const bool four_mode = mode == kMode44 || (mode == kMode48 && h == 0);
-            const bool four = four_mode || (!PACKED4 && (2 * c64 + h) * 32 < p.K4pre);
-            const int wbase = (it_tap * (2 * SP) + 2 * c64) * ustride + ld_n0 * 16;   // same for every item of the step
-            const int soff = wbase + (h ? ustride : 0);
-            unsigned char *dst = stage + XBYTES + pl * WPS + blk * 1024;
-            if (!(PACKED4 && four)) lds_load16(rw8, dst, wvoff[j], soff + (four ? w4x_delta : 0));
+            if (!(PACKED4 && four_mode)) lds_load16(rw8, stage + wdst[j], wvoff[j], h ? it_w1 : it_w0);
         } else if (PACKED4) {
             const int h = (i - XI - WI) / WL4, j = (i - XI - WI) % WL4;
             const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
@@ -518,27 +539,29 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     // step 2 into the staging registers of the main loop); then the tables and the register-routed pieces of
     // steps 0 and 1 go to LDS.
     int mode_staged = kModeNone;   // mode of K-step s+2, whose register-routed pieces sit in the staging registers
+    bool plain_prologue;           // K-steps 0, 1 and 2 all exist and are plain copies into LDS
     {
         v4i sp[2][NSR > 0 ? NSR : 1];
         int wp[2][2][WL4];
         int pmode[2] = {kModeNone, kModeNone}, pc64[2] = {0, 0};
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            if (it_phase != 3) {   // the block has a K-step t (of its first tile, or of a following one when K is short)
-                pmode[t] = it_mode();
+            if (it_mode != kModeNone) {   // the block has a K-step t (of its first tile, or of a following one when K is short)
+                pmode[t] = it_mode;
                 pc64[t] = it_c64;
 #pragma unroll
                 for (int i = 0; i < NI; ++i) gload(sp[t], wp[t], i, pmode[t], lds + t * STAGE);
                 advance();
             }
         }
-        if (it_phase != 3) {
-            mode_staged = it_mode();
+        if (it_mode != kModeNone) {
+            mode_staged = it_mode;
             st_c64 = it_c64;
 #pragma unroll
             for (int i = 0; i < NI; ++i) gload(sr, wsh, i, mode_staged, lds + 2 * STAGE);
             advance();
         }
+        plain_prologue = !PACKED4 && pmode[0] == kMode88 && pmode[1] == kMode88 && mode_staged == kMode88;
         FQ_TS(tqb);
         if (tid <= p.G) reinterpret_cast<int *>(sa_tab)[tid] = sa_v;
         __builtin_amdgcn_s_waitcnt(0xc07f);
@@ -573,7 +596,12 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     };
     zero_acc();
 
-    __builtin_amdgcn_s_waitcnt(0x0070);   // every direct load of the prologue has landed
+    // K-step 0 has landed.  Steps 1 and 2 may stay in flight when all three are plain copies (every wave then has
+    // the same number of loads outstanding, and the wait at the end of step 0 covers steps 1 and 2).
+    if (plain_prologue)
+        __builtin_amdgcn_s_waitcnt(0x0070 | ((2 * (XI + WI)) & 15) | (((2 * (XI + WI)) >> 4) << 14));
+    else
+        __builtin_amdgcn_s_waitcnt(0x0070);
     __builtin_amdgcn_s_waitcnt(0xc07f);
     __builtin_amdgcn_s_barrier();
 #pragma unroll
@@ -592,8 +620,6 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     // output tile are computed, the first K-steps of the next one are already being loaded and staged.
     int o_cur = 0, o_nx1 = STAGE, o_nx2 = 2 * STAGE, o_nx3 = 3 * STAGE;   // byte offsets of the stages of K-steps s .. s+3
     int s = 0;    // K-step within the output tile being computed
-    // K-steps this block still has to compute, over all its tiles (the last one reads no fragments ahead)
-    int flat_left = steps * (C_::MULTI ? (total_tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 1);
     constexpr int kStageSlots = 2 * NMF > 2 ? 2 * NMF - 2 : 1;    // slots that carry staging work
     constexpr int kAdvanceSlot = 2 * NMF > 2 ? 2 * NMF - 2 : 0;   // slot after which the load iterator moves on
     auto step = [&](auto ma_, auto mb_, auto h1_) {
@@ -604,7 +630,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
         unsigned char *nx2 = lds + o_nx2;
         unsigned char *nx3 = lds + o_nx3;
         if (ma == kMode44 || ma == kMode48) lower_setup();   // from the position fetched during the previous step
-        if (mb != kModeNone) st_c64 = it_c64;
+        if (mb == kMode44 || mb == kMode48) st_c64 = it_c64;
         FQ_SB();
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh)
@@ -685,7 +711,6 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
             o_nx3 = t;
         }
         ++s;
-        --flat_left;
         mode_staged = mb;
     };
 
@@ -723,21 +748,24 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                     csv[0] = cs.x; csv[1] = cs.y; csv[2] = cs.z; csv[3] = cs.w;
                     biv[0] = bi.x; biv[1] = bi.y; biv[2] = bi.z; biv[3] = bi.w;
                 }
-                float qlo = -128.0f, qhi = 127.0f;   // clamp of the int8 code
+                // The int8 code is formed in offset form: t = acc * mul + (add + 128) in one fused operation, then
+                // one instruction rounds t to nearest-even, saturates it to 0..255 and puts it into its byte; flipping
+                // the top bit of every byte gives the two's-complement code clamp(round(.), -128, 127).
+                float qlo = 0.0f, qhi = 255.0f;   // clamp of the offset code when the output is lowered as well
                 uint32_t qmask = 0xFFFFFFFFu;
                 if (wq) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         mul[i] = csv[i] * p.r_out;
-                        add[i] = biv[i] * p.r_out;
+                        add[i] = biv[i] * p.r_out + 128.0f;
                     }
                     // Output lowered for the consumer (its 4-bit channels only): L(v, s) << s = clamp(v, -(8<<s),
                     // (8<<s)-1) with the low s bits cleared; the four columns of a quad share a channel group.
                     if (lw) {
                         const bool lowered = n < p.next_K4;
                         const int sp = reinterpret_cast<const int *>(tab + 2 * BN)[nl];
-                        qhi = (float)((8 << (lowered ? sp : 4)) - 1);
-                        qlo = -1.0f - qhi;
+                        qhi = (float)((8 << (lowered ? sp : 4)) + 127);
+                        qlo = 255.0f - qhi;
                         qmask = lowered ? 0x01010101u * ((0xFFu << sp) & 0xFFu) : 0xFFFFFFFFu;
                     }
                 }
@@ -748,14 +776,14 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
                     const int iv[4] = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
                     uint32_t qw = 0;
                     if (wq) {
-                        uint32_t u[4];
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             float t = __builtin_fmaf((float)iv[i], mul[i], add[i]);
-                            t = __builtin_amdgcn_fmed3f(t, qlo, qhi);
-                            u[i] = __builtin_bit_cast(uint32_t, t + 12582912.0f);  // 1.5 * 2^23: integer lands in the low bits
+                            if (lw) t = __builtin_amdgcn_fmed3f(t, qlo, qhi);
+                            qw = __builtin_amdgcn_cvt_pk_u8_f32(t, i, qw);
                         }
-                        qw = (__builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu)) & qmask;
+                        qw ^= 0x80808080u;
+                        if (lw) qw &= qmask;
                         qrow[b][g] = qw;
                     }
                     if (!(wy || wa || (wq && !qr))) continue;   // nothing is stored quad by quad
@@ -816,19 +844,22 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
         const bool more_tiles = C_::MULTI && ctile + (int)gridDim.x < total_tiles;
         // Nothing in flight (in particular none of the previous epilogue's stores) when the K loop starts: the
         // compiler can then count the register-routed loads of the 4-bit loops exactly.
-        if (n4 + mixed > 0 || PACKED4) __builtin_amdgcn_s_waitcnt(0x0070);
+        if ((n4 + mixed > 0 && !p.x_pre) || PACKED4) __builtin_amdgcn_s_waitcnt(0x0070);
         while (s < steps) {
-            while (s < steps && mode_staged == kMode44 && it_phase == 0) step(M44{}, M44{}, T_{});
-            while (s < steps && mode_staged == kMode44 && it_phase == 2) step(M44{}, M88{}, T_{});   // at most once
-            while (s < steps && mode_staged == kMode88 && it_phase == 2) step(M88{}, M88{}, T_{});
-            while (s < steps && mode_staged == kMode88 && it_phase == 0) step(M88{}, M44{}, T_{});   // next tile begins
-            while (s < steps && mode_staged != kModeNone && it_phase != 3 && (mode_staged == kMode48 || it_phase == 1))
-                step(mode_staged, (int)it_mode(), true);                                             // mixed steps
-            while (s < steps && mode_staged == kMode88 && it_phase == 3) step(M88{}, MNone{}, T_{});
-            while (s < steps && mode_staged == kMode44 && it_phase == 3) step(M44{}, MNone{}, T_{});
-            while (s < steps && mode_staged == kMode48 && it_phase == 3) step(mode_staged, (int)kModeNone, true);
-            while (s < steps && mode_staged == kModeNone && flat_left > 1) step(MNone{}, MNone{}, T_{});
-            while (s < steps && mode_staged == kModeNone && flat_left <= 1) step(MNone{}, MNone{}, F_{});
+            if (mode_staged == kMode44 && it_mode == kMode44)
+                do step(M44{}, M44{}, T_{}); while (s < steps && it_mode == kMode44);
+            if (s < steps && mode_staged == kMode44 && it_mode == kMode88) step(M44{}, M88{}, T_{});
+            if (s < steps && mode_staged == kMode88 && it_mode == kMode88)
+                do step(M88{}, M88{}, T_{}); while (s < steps && it_mode == kMode88);
+            if (s < steps && mode_staged == kMode88 && it_mode == kMode44) step(M88{}, M44{}, T_{});   // next tile begins
+            while (s < steps && mode_staged != kModeNone && it_mode != kModeNone && (mode_staged == kMode48 || it_mode == kMode48))
+                step(mode_staged, it_mode, true);                                                      // mixed steps
+            if (s < steps && mode_staged == kMode88 && it_mode == kModeNone) step(M88{}, MNone{}, T_{});
+            if (s < steps && mode_staged == kMode44 && it_mode == kModeNone) step(M44{}, MNone{}, T_{});
+            if (s < steps && mode_staged == kMode48 && it_mode == kModeNone) step(mode_staged, (int)kModeNone, true);
+            // nothing left to stage; the block's very last step reads no fragments ahead
+            while (s < steps && mode_staged == kModeNone && (more_tiles || s + 1 < steps)) step(MNone{}, MNone{}, T_{});
+            if (s < steps && mode_staged == kModeNone && !more_tiles && s + 1 >= steps) step(MNone{}, MNone{}, F_{});
         }
 
 #ifdef FLEXIQ_TIMING
