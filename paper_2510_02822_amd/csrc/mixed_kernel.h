@@ -196,7 +196,8 @@ enum StepMode { kMode88 = 0, kMode44 = 1, kMode48 = 2, kModeNone = 3 };
 // registers with vector-ALU work: for memory-bound shapes) or the copy that is already expanded (copied
 // exactly like an 8-bit unit: for compute-bound shapes).
 template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV, bool PACKED4>
-__global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const GemmParams p)
+// (two blocks per CU only where two copies of the block's LDS fit: otherwise the register budget of a lone block)
+__global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM, TN>::LDS_BYTES <= 160 * 1024 ? 2 : 1)) void k_mixed(const GemmParams p)
 {
     using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
     constexpr int NT = C_::NT, BM = C_::BM, BN = C_::BN, XBYTES = C_::XBYTES, WPS = C_::WPS, STAGE = C_::STAGE;
@@ -308,13 +309,11 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
     load_tile_context(m0, n0);
     const int x_lds = (16 * wave) * 64 + lane * 16;   // piece j adds 64 rows: j * 4096
     int wvoff[WI];   // per-lane offset of direct weight load j: k-plane parity, 64-row block, row = lane
-    int wdst[WI];    // where it lands inside a stage (scalar)
 #pragma unroll
     for (int j = 0; j < WI; ++j) {
         const int idx = wave + 4 * j;
         const int pl = idx / (BN / 64), blk = idx % (BN / 64);
         wvoff[j] = ((pl & 1) * p.Npad + blk * 64 + lane) * 16;
-        wdst[j] = XBYTES + pl * WPS + blk * 1024;
     }
     // Direct weight load j of this wave: index wave + 4 j over (k-plane, block of 64 rows); scalar values.
     // Packed pieces: row tid + j * NT of the tile (one thread per row).
@@ -393,36 +392,42 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
             it_c64 = c;
             it_w0 += 2 * ustride;
             it_w1 += 2 * ustride;
-            return;
-        }
-        const int tap1 = it_tap + 1;
-        if (tap1 == p.T) {   // the phase is finished
-            int ph = pn(it_phase);
-            if (C_::MULTI && ph == 3) {   // and with it the tile: move on to the block's next tile if there is one
-                const int nt = ltile + (int)gridDim.x;
-                if (nt < total_tiles) {
-                    ltile = nt;
-                    int tile_m, tile_n;
-                    map_tile(nt, tile_m, tile_n);
-                    load_tile_context((int64_t)tile_m * BM, tile_n * BN);
-                    ph = first_phase;
-                }
-            }
-            it_phase = ph;
-            it_tap = 0;
-            it_dy = 0;
-            it_dx = 0;
         } else {
-            it_tap = tap1;
-            if (CONV) {
-                const int dx1 = it_dx + 1;
-                const bool wrap_x = dx1 == p.S;
-                it_dy = wrap_x ? it_dy + 1 : it_dy;
-                it_dx = wrap_x ? 0 : dx1;
+            const int tap1 = it_tap + 1;
+            if (tap1 != p.T) {   // same phase, next filter tap
+                const int first = pb(it_phase);
+                const int dw = 2 * (SP + 1 + first - it_pe) * ustride;
+                it_tap = tap1;
+                it_c64 = first;
+                it_w0 += dw;
+                it_w1 += dw;
+                if (CONV) {
+                    const int dx1 = it_dx + 1;
+                    const bool wrap_x = dx1 == p.S;
+                    it_dy = wrap_x ? it_dy + 1 : it_dy;
+                    it_dx = wrap_x ? 0 : dx1;
+                }
+            } else {             // the phase is finished
+                int ph = pn(it_phase);
+                // ... and with it the tile: move on to the block's next tile if there is one
+                if (C_::MULTI && ph == 3) {
+                    const int nt = ltile + (int)gridDim.x;
+                    if (nt < total_tiles) {
+                        ltile = nt;
+                        int tile_m, tile_n;
+                        map_tile(nt, tile_m, tile_n);
+                        load_tile_context((int64_t)tile_m * BM, tile_n * BN);
+                        ph = first_phase;
+                    }
+                }
+                it_dy = 0;
+                it_dx = 0;
+                it_tap = 0;
+                it_phase = ph;
+                it_c64 = pb(ph);
+                refresh_iterator();
             }
         }
-        it_c64 = pb(it_phase);
-        refresh_iterator();
     };
 
     // ---- staging registers (register-routed pieces only) and the descriptor of the tile they hold
@@ -457,7 +462,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void k_mixed(const Gem
             // (which copy of the weights a unit reads is part of the iterator's offsets; only the packed-code
             // variant needs to know here, to leave its 4-bit units to the register route)
             const bool four_mode = mode == kMode44 || (mode == kMode48 && h == 0);
-            if (!(PACKED4 && four_mode)) lds_load16(rw8, stage + wdst[j], wvoff[j], h ? it_w1 : it_w0);
+            if (!(PACKED4 && four_mode)) lds_load16(rw8, stage + XBYTES + pl * WPS + blk * 1024, wvoff[j], h ? it_w1 : it_w0);
         } else if (PACKED4) {
             const int h = (i - XI - WI) / WL4, j = (i - XI - WI) % WL4;
             const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
