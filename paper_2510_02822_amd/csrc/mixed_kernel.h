@@ -740,16 +740,23 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
         const float *tab = cs_tab + parity * (3 * BN);
         {
             uint32_t qrow[TM][4];   // int8 codes of the four quads of fragment (a, b)
+            // scale and bias of a quad's four columns are read from the LDS table one quad ahead
+            const int nl0 = (wn * TN + a) * 32 + 4 * frag_half_e;
+            float4 cs_nx = *reinterpret_cast<const float4 *>(tab + nl0);
+            float4 bi_nx = *reinterpret_cast<const float4 *>(tab + BN + nl0);
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 FQ_SB();   // keep the accumulator reads of later quads from being hoisted (register pressure)
-                const int nl = (wn * TN + a) * 32 + 8 * g + 4 * frag_half_e;
+                const int nl = nl0 + 8 * g;
                 const int n = n0 + nl;
                 const bool n_ok = n < p.N;
                 float csv[4], biv[4], mul[4], add[4];
                 {
-                    const float4 cs = *reinterpret_cast<const float4 *>(tab + nl);
-                    const float4 bi = *reinterpret_cast<const float4 *>(tab + BN + nl);
+                    const float4 cs = cs_nx, bi = bi_nx;
+                    if (g < 3) {
+                        cs_nx = *reinterpret_cast<const float4 *>(tab + nl + 8);
+                        bi_nx = *reinterpret_cast<const float4 *>(tab + BN + nl + 8);
+                    }
                     csv[0] = cs.x; csv[1] = cs.y; csv[2] = cs.z; csv[3] = cs.w;
                     biv[0] = bi.x; biv[1] = bi.y; biv[2] = bi.z; biv[3] = bi.w;
                 }
