@@ -16,7 +16,8 @@ namespace flexiq {
 static const TileShape *shapes(int *count)
 {
     static const TileShape tab[kNumTileShapes] = {tile_shape_0(), tile_shape_1(), tile_shape_2(), tile_shape_3(),
-                                                  tile_shape_4(), tile_shape_5(), tile_shape_6(), tile_shape_7()};
+                                                  tile_shape_4(), tile_shape_5(), tile_shape_6(), tile_shape_7(),
+                                                  tile_shape_8(), tile_shape_9(), tile_shape_10(), tile_shape_11()};
     *count = kNumTileShapes;
     return tab;
 }
@@ -48,7 +49,7 @@ static int num_cu()
 }
 
 // Blocks of kernel `fn` that fit on one CU (registers and LDS); raises the dynamic-LDS limit on first use.
-static int resident_blocks(kernel_fn fn, int lds)
+static int resident_blocks(kernel_fn fn, int threads, int lds)
 {
     static std::mutex mu;
     static std::vector<std::pair<const void *, int>> done;
@@ -57,7 +58,7 @@ static int resident_blocks(kernel_fn fn, int lds)
         if (f.first == (const void *)fn) return f.second;
     int resident = 0;
     if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return -1;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, (const void *)fn, 256, lds) != hipSuccess) return -1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, (const void *)fn, threads, lds) != hipSuccess) return -1;
     if (resident < 1) resident = 1;
     done.emplace_back((const void *)fn, resident);
     return resident;
@@ -74,14 +75,14 @@ static int choose_shape(int64_t M, int N, int steps, bool conv, bool packed)
     double best = 1e300;
     int bi = 0;
     for (int i = 0; i < cnt; ++i) {
-        const int occ = resident_blocks(tab[i].fn[conv ? 1 : 0][packed ? 1 : 0], tab[i].lds);
+        const int occ = resident_blocks(tab[i].fn[conv ? 1 : 0][packed ? 1 : 0], tab[i].threads, tab[i].lds);
         if (occ < 1) continue;
         const double tiles = (double)((M + tab[i].BM - 1) / tab[i].BM) * (double)((N + tab[i].BN - 1) / tab[i].BN);
         const double tiles_cu = __builtin_ceil(tiles / ncu);
         const double conc = tiles_cu < occ ? tiles_cu : occ;
         const double seq = __builtin_ceil(tiles_cu / conc);
         const double step = tab[i].step_alone * (1.0 + tab[i].share * (conc - 1.0));
-        const double prologue = 8000.0;
+        const double prologue = 7000.0;
         const bool walks = tab[i].multi;   // prologue paid once per block
         const double cost = walks ? prologue + seq * (steps * step + tab[i].epilogue)
                                   : seq * (prologue + steps * step + tab[i].epilogue);
@@ -137,7 +138,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     if (tiles > 0x7fffffff) return FLEXIQ_EINVAL;
     kernel_fn fn = ts.fn[conv ? 1 : 0][packed ? 1 : 0];
-    const int resident = resident_blocks(fn, ts.lds);   // blocks of this kernel that fit on one CU
+    const int resident = resident_blocks(fn, ts.threads, ts.lds);   // blocks of this kernel that fit on one CU
     if (resident < 1) {
         set_hip_error(hipGetLastError(), "hipFuncSetAttribute / hipOccupancyMaxActiveBlocksPerMultiprocessor");
         return FLEXIQ_EHIP;
@@ -149,8 +150,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
         blocks = std::min<int64_t>(tiles, g_max_blocks > 0 ? (int64_t)g_max_blocks : (int64_t)num_cu() * resident);
     g_last_blocks = (int)blocks;
     g_last_resident = resident;
-    const int nt = 256;
-    hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3(nt), ts.lds, (hipStream_t)stream, p);
+    hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3(ts.threads), ts.lds, (hipStream_t)stream, p);
     FLEXIQ_HIP(hipGetLastError());
     return FLEXIQ_OK;
 }

@@ -156,14 +156,16 @@ __device__ __forceinline__ void lds_load4(__amdgpu_buffer_rsrc_t r, void *dst, i
 
 template <int WAVES_M, int WAVES_N, int TM, int TN>
 struct Cfg {
-    static_assert(WAVES_M * WAVES_N == 4, "four waves per block");
-    static constexpr int NT = 256;
+    static constexpr int NW = WAVES_M * WAVES_N;        // waves per block: 4 (one per SIMD) or 8 (two per SIMD)
+    static_assert(NW == 4 || NW == 8, "four or eight waves per block");
+    static constexpr int NT = 64 * NW;
     static constexpr int BM = WAVES_M * TM * 32;
     static constexpr int BN = WAVES_N * TN * 32;
     static_assert(BN % 64 == 0, "a wave copies 64 weight rows per instruction");
-    static constexpr int XI = (BM + 63) / 64;           // activation pieces per thread per K-step (a wave instruction covers 16 rows)
-    static constexpr int XROWS = XI * 64;               // rows staged per K-step (>= BM; the excess reads as zero)
-    static constexpr int WI = BN / 64;                  // direct weight loads per wave per K-step (4 planes x BN rows / 64 / 4 waves)
+    static constexpr int XI = (BM + 16 * NW - 1) / (16 * NW);   // activation pieces per thread per K-step (a wave instruction covers 16 rows)
+    static constexpr int XROWS = XI * 16 * NW;          // rows staged per K-step (>= BM; the excess reads as zero)
+    static_assert((4 * (BN / 64)) % NW == 0, "weight copies divide evenly over the waves");
+    static constexpr int WI = 4 * (BN / 64) / NW;       // direct weight loads per wave per K-step (4 planes x BN rows / 64 rows per copy)
     static constexpr int WL4 = (BN + NT - 1) / NT;      // packed-code pieces per thread per 4-bit unit
     static constexpr int XBYTES = XROWS * 64;           // activation tile, row-major
     static constexpr int WPS = (BN + 2) * 16;           // bytes per weight k-plane (+2 pieces staggers the planes over the banks)
@@ -197,10 +199,10 @@ enum StepMode { kMode88 = 0, kMode44 = 1, kMode48 = 2, kModeNone = 3 };
 // exactly like an 8-bit unit: for compute-bound shapes).
 template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV, bool PACKED4>
 // (two blocks per CU only where two copies of the block's LDS fit: otherwise the register budget of a lone block)
-__global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM, TN>::LDS_BYTES <= 160 * 1024 ? 2 : 1)) void k_mixed(const GemmParams p)
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM, TN>::LDS_BYTES <= 160 * 1024 ? 2 : 1)) void k_mixed(const GemmParams p)
 {
     using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
-    constexpr int NT = C_::NT, BM = C_::BM, BN = C_::BN, XBYTES = C_::XBYTES, WPS = C_::WPS, STAGE = C_::STAGE;
+    constexpr int NW = C_::NW, NT = C_::NT, BM = C_::BM, BN = C_::BN, XBYTES = C_::XBYTES, WPS = C_::WPS, STAGE = C_::STAGE;
     constexpr int XI = C_::XI, WI = C_::WI, WL4 = C_::WL4;
     constexpr int NP = PACKED4 ? 2 * WL4 : 0;   // packed-code pieces per thread per K-step
     constexpr int NSR = XI + NP;                // staging registers (x4 dwords) per thread
@@ -214,7 +216,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: lives in a scalar register
-    __builtin_assume(wave >= 0 && wave < 4);
+    __builtin_assume(wave >= 0 && wave < NW);
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 #ifdef FLEXIQ_TIMING
     long long tq0 = __builtin_readcyclecounter(), tqa = 0, tqb = 0, tqc = 0, tqd = 0;
@@ -264,7 +266,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
     const int8_t *xbase;
     int xwin;
     int ld_n0;
-    // Activation piece j of a thread: row 16 (wave + 4 j) + lane / 4 of the tile, LDS slot lane % 4 of that row,
+    // Activation piece j of a thread: row 16 (wave + NW j) + lane / 4 of the tile, LDS slot lane % 4 of that row,
     // which holds k-plane xq = slot ^ ((row / 4) % 4); (row / 4) % 4 = (lane / 16) % 4 for every j.
     const int xrow = lane >> 2;
     const int xq = (lane & 3) ^ ((lane >> 4) & 3);   // k-plane of this thread's activation pieces; unit xq >> 1
@@ -272,7 +274,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
     int xh0[XI], xw0[XI], xpix[XI];   // conv: top-left input coordinate, pixel index of the image origin (-1: no row)
 #pragma unroll
     for (int j = 0; j < XI; ++j) {
-        xvoff[j] = CONV ? xq * 16 : (16 * (wave + 4 * j) + xrow) * p.C + xq * 16;  // linear: rows past the window read zeros
+        xvoff[j] = CONV ? xq * 16 : (16 * (wave + NW * j) + xrow) * p.C + xq * 16;  // linear: rows past the window read zeros
         xh0[j] = xw0[j] = xpix[j] = 0;
     }
     auto load_tile_context = [&](int64_t lm0, int ln0) {
@@ -290,7 +292,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
             xwin = (int)win;
 #pragma unroll
             for (int j = 0; j < XI; ++j) {
-                const int row = 16 * (wave + 4 * j) + xrow;
+                const int row = 16 * (wave + NW * j) + xrow;
                 const bool ok = row < rows_valid;
                 const uint32_t mm = ok ? m32 + (uint32_t)row : m32;
                 const uint32_t t = mm / (uint32_t)p.Wo;
@@ -307,15 +309,15 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
         }
     };
     load_tile_context(m0, n0);
-    const int x_lds = (16 * wave) * 64 + lane * 16;   // piece j adds 64 rows: j * 4096
+    const int x_lds = (16 * wave) * 64 + lane * 16;   // piece j adds 16 NW rows: j * NW * 1024
     int wvoff[WI];   // per-lane offset of direct weight load j: k-plane parity, 64-row block, row = lane
 #pragma unroll
     for (int j = 0; j < WI; ++j) {
-        const int idx = wave + 4 * j;
+        const int idx = wave + NW * j;
         const int pl = idx / (BN / 64), blk = idx % (BN / 64);
         wvoff[j] = ((pl & 1) * p.Npad + blk * 64 + lane) * 16;
     }
-    // Direct weight load j of this wave: index wave + 4 j over (k-plane, block of 64 rows); scalar values.
+    // Direct weight load j of this wave: index wave + NW j over (k-plane, block of 64 rows); scalar values.
     // Packed pieces: row tid + j * NT of the tile (one thread per row).
     int w4voff[WL4], w4lds[WL4];
 #pragma unroll
@@ -451,12 +453,12 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
                 off = xvoff[i] + c64 * 64;
             }
             if (mode == kMode88)
-                lds_load16(rx, stage + (16 * (wave + 4 * i)) * 64, off, 0);
+                lds_load16(rx, stage + (16 * (wave + NW * i)) * 64, off, 0);
             else
                 sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
         } else if (i < XI + WI) {
             const int j = i - XI;
-            const int idx = wave + 4 * j;                       // (k-plane, 64-row block) of this copy
+            const int idx = wave + NW * j;                      // (k-plane, 64-row block) of this copy
             const int pl = idx / (BN / 64), blk = idx % (BN / 64);
             const int h = pl >> 1;                              // unit of the K-step
             // (which copy of the weights a unit reads is part of the iterator's offsets; only the packed-code
@@ -515,7 +517,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
     };
     auto lstore = [&](v4i(&sr)[NSR > 0 ? NSR : 1], int i, int mode, unsigned char *stage) {
         if (i < XI) {
-            if (mode == kMode44 || mode == kMode48) *reinterpret_cast<v4i *>(stage + x_lds + i * 4096) = sr[i];
+            if (mode == kMode44 || mode == kMode48) *reinterpret_cast<v4i *>(stage + x_lds + i * (NW * 1024)) = sr[i];
         } else if (PACKED4 && i >= XI + WI) {
             const int h = (i - XI - WI) / WL4, j = (i - XI - WI) % WL4;
             const bool four = mode == kMode44 || (mode == kMode48 && h == 0);
@@ -601,10 +603,11 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
     };
     zero_acc();
 
-    // K-step 0 has landed.  Steps 1 and 2 may stay in flight when all three are plain copies (every wave then has
-    // the same number of loads outstanding, and the wait at the end of step 0 covers steps 1 and 2).
+    // K-steps 0 and 1 have landed (step 0 reads the first fragments of step 1 ahead).  Step 2 may stay in flight
+    // when all three are plain copies: every wave then has the same number of loads outstanding, and the wait at
+    // the end of step 0 covers it.
     if (plain_prologue)
-        __builtin_amdgcn_s_waitcnt(0x0070 | ((2 * (XI + WI)) & 15) | (((2 * (XI + WI)) >> 4) << 14));
+        __builtin_amdgcn_s_waitcnt(0x0070 | ((XI + WI) & 15) | (((XI + WI) >> 4) << 14));
     else
         __builtin_amdgcn_s_waitcnt(0x0070);
     __builtin_amdgcn_s_waitcnt(0xc07f);
@@ -613,7 +616,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
     for (int i = 0; i < NF; ++i) fread(fA, i, lds, 0);
 
 #ifdef FLEXIQ_TIMING
-    long long tq1 = __builtin_readcyclecounter(), t_epi = 0;
+    long long tq1 = __builtin_readcyclecounter(), t_epi = 0, t_wait_vm = 0, t_wait_bar = 0;
     int n_tiles = 0;
 #endif
     // ---- main loop.  Step s computes K-step s from stage s % 4 while K-step s+3 is loaded (straight into stage
@@ -701,12 +704,22 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
         // The direct loads of the previous step (K-step s+2) must have landed before the barrier publishes them;
         // this step's own loads may stay in flight.  Their number is known at compile time where every wave
         // issues the same loads; otherwise wait for everything.
+#ifdef FLEXIQ_TIMING
+        const long long tw0 = __builtin_readcyclecounter();
+#endif
         if (!PACKED4 && (mb == kMode88 || mb == kMode44 || mb == kMode48))
             __builtin_amdgcn_s_waitcnt(0x0070 | ((XI + WI) & 15) | (((XI + WI) >> 4) << 14));
         else
             __builtin_amdgcn_s_waitcnt(0x0070);
+#ifdef FLEXIQ_TIMING
+        const long long tw1 = __builtin_readcyclecounter();
+#endif
         __builtin_amdgcn_s_waitcnt(0xc07f);  // this wave's LDS stores and fragment reads are complete
         __builtin_amdgcn_s_barrier();
+#ifdef FLEXIQ_TIMING
+        t_wait_vm += tw1 - tw0;
+        t_wait_bar += __builtin_readcyclecounter() - tw1;
+#endif
         FQ_SB();
         {
             const int t = o_cur;
@@ -913,9 +926,9 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
     {
         long long tq3 = __builtin_readcyclecounter();
         if (lane == 0 && p.acc) {
-            int *d = p.acc + ((int64_t)blockIdx.x * 4 + wave) * 8;
+            int *d = p.acc + ((int64_t)blockIdx.x * NW + wave) * 8;
             d[0] = (int)(tq1 - tq0); d[1] = (int)(tq3 - tq1 - t_epi); d[2] = (int)t_epi; d[3] = steps * n_tiles;
-            d[4] = (int)(tqa - tq0); d[5] = (int)(tqb - tqa); d[6] = (int)(tqc - tqb); d[7] = n_tiles;
+            d[4] = (int)(tqa - tq0); d[5] = (int)t_wait_vm; d[6] = (int)t_wait_bar; d[7] = n_tiles;
         }
     }
 #endif
@@ -923,7 +936,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM,
 
 typedef void (*kernel_fn)(const GemmParams);
 struct TileShape {
-    int BM, BN, lds;
+    int BM, BN, threads, lds;
     bool multi;          // a block of this shape may walk several output tiles (linear form)
     // Measured on MI355X (ViT-B / ViT-L MLP shapes, 8-bit steps), in shader cycles; used by the shape choice:
     double step_alone;   // one K-step of a block that has its CU to itself
@@ -936,14 +949,13 @@ template <int WAVES_M, int WAVES_N, int TM, int TN>
 inline TileShape make_shape(double step_alone, double share, double epilogue)
 {
     using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
-    static_assert(C_::NT == 256, "the launcher uses 256 threads");
-    return TileShape{C_::BM, C_::BN, C_::LDS_BYTES, C_::MULTI, step_alone, share, epilogue,
+    return TileShape{C_::BM, C_::BN, C_::NT, C_::LDS_BYTES, C_::MULTI, step_alone, share, epilogue,
                      {{k_mixed<WAVES_M, WAVES_N, TM, TN, false, false>, k_mixed<WAVES_M, WAVES_N, TM, TN, false, true>},
                       {k_mixed<WAVES_M, WAVES_N, TM, TN, true, false>, k_mixed<WAVES_M, WAVES_N, TM, TN, true, true>}}};
 }
 
 // Shape i of the table, defined in mixed_tile.hip built with -DFQ_TILE=i.
-constexpr int kNumTileShapes = 8;
+constexpr int kNumTileShapes = 12;
 TileShape tile_shape_0();
 TileShape tile_shape_1();
 TileShape tile_shape_2();
@@ -952,5 +964,9 @@ TileShape tile_shape_4();
 TileShape tile_shape_5();
 TileShape tile_shape_6();
 TileShape tile_shape_7();
+TileShape tile_shape_8();
+TileShape tile_shape_9();
+TileShape tile_shape_10();
+TileShape tile_shape_11();
 
 }  // namespace flexiq
