@@ -216,6 +216,38 @@ def main():
         del g
     fq.flexiq_static_positions(layer)
 
+    # the same scan done by the producing layer's own epilogue (flexiq_out.scan_for): this layer as the producer of
+    # a consumer with C = N input channels; its GEMM with and without the scan.  Side measurement.
+    fused_scan = None
+    if args.out == "q":
+        rng2 = np.random.default_rng(7)
+        W2 = (rng2.standard_normal((32, N)) * 0.02).astype(np.float32)
+        cons = fq.flexiq_quantize_pack(W2, np.full(N, 127.0 * out_scale, np.float32), float(out_scale), 32)
+        fq.flexiq_set_ratio(cons, 1.0)
+        fq.flexiq_set_ratio(layer, 0.5)
+        res = {}
+        for tag, kw in (("gemm_us", {}), ("gemm_with_scan_us", {"scan_for": cons})):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for _ in range(10):
+                    fq.flexiq_mixed_gemm(layer, Xq, out_scale=out_scale, bufs=bufs, q=True, **kw)
+            g.replay()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(7):
+                a0 = torch.cuda.Event(enable_timing=True)
+                a1 = torch.cuda.Event(enable_timing=True)
+                a0.record()
+                g.replay()
+                a1.record()
+                torch.cuda.synchronize()
+                ts.append(a0.elapsed_time(a1) * 1e3 / 10)
+            res[tag] = round(float(np.median(ts)), 2)
+            del g
+        res["overhead_frac"] = round(res["gemm_with_scan_us"] / res["gemm_us"] - 1.0, 4)
+        fused_scan = res
+        del cons
+
     if args.calib_copy_mib > 0:
         src = torch.empty(args.calib_copy_mib << 20, dtype=torch.int8, device=dev)
         dst = torch.empty_like(src)
@@ -279,7 +311,7 @@ def main():
                                "per step, epilogue=%s" % (args.layer, M, K, N, gs, list(RATIOS),
                                                           {"q": "int8 requant", "y": "fp32 dequant", "acc": "int32 dump"}[args.out]),
                    "M": M, "K": K, "N": N, "group_size": gs, "ratios": list(RATIOS)},
-        "roofline": roofline, "cpu_baseline": cpu, "per_r": per_r, "prelowered_input": pre, "dynamic_positions": dyn, "ratio_switch": ratio_switch, "parity": parity,
+        "roofline": roofline, "cpu_baseline": cpu, "per_r": per_r, "prelowered_input": pre, "dynamic_positions": dyn, "fused_scan": fused_scan, "ratio_switch": ratio_switch, "parity": parity,
     }
     print(json.dumps(line), flush=True)
 

@@ -140,8 +140,9 @@ int flexiq_permute_channels(const flexiq_layer *layer, const int8_t *src, int8_t
 /* Outputs of a GEMM / conv call; any subset may be NULL (at least one must be set).
  *   acc : dev int32 [M][N]  raw accumulators (parity / debugging)
  *   y   : dev fp32  [M][N]  y = float(acc) * (x_scale * w_scale[n]) + bias[n]
- *   q   : dev int8  [M][N]  next layer's input: clip(round_half_even(fma(float(acc), m[n], b[n])), -128, 127)
- *                           with m[n] = (x_scale*w_scale[n]) * (1/out_scale), b[n] = bias[n] * (1/out_scale),
+ *   q   : dev int8  [M][N]  next layer's input, clip(round(y / out_scale), -128, 127), decided in fp32 in offset
+ *                           form: clip(round_half_even(fma(float(acc), m[n], b[n])), 0, 255) - 128 with
+ *                           m[n] = (x_scale*w_scale[n]) * (1/out_scale), b[n] = bias[n] * (1/out_scale) + 128,
  *                           every operation a correctly rounded fp32 one
  *   out_scale : scale of q (used only when q != NULL; must be > 0)
  *   lower_for : optional.  The layer that will consume q (its C == this layer's N, and this layer was packed
@@ -149,13 +150,24 @@ int flexiq_permute_channels(const flexiq_layer *layer, const int8_t *src, int8_t
  *               channels of the consumer under ITS current ratio are then written bit-lowered at ITS current
  *               positions, L(v, s) << s (Section 4.1), in the same pass: the consumer, switched with
  *               flexiq_input_prelowered(consumer, 1), no longer lowers them itself.  Both settings of the consumer
- *               are read when this call is made.  NULL: plain int8 codes */
+ *               are read when this call is made.  NULL: plain int8 codes
+ *   scan_for  : optional, not together with lower_for.  The layer that will consume q (same conditions).  The
+ *               run-time scan of flexiq_dynamic_positions (Section 4.1; Section 9 "Finding extraction positions at
+ *               runtime") is done on q in the same pass: the epilogue ORs the magnitude bits of every channel
+ *               group of the consumer into mask words of the consumer's handle, and the consumer's following GEMM /
+ *               conv calls turn the masks of their 4-bit groups (the ratio in force at THAT call) into positions in
+ *               their prologue; no second kernel, no waiting.  The call switches the consumer to these positions, as
+ *               flexiq_dynamic_positions would; flexiq_static_positions switches back.  The handle keeps two mask
+ *               sets in turn: calls that scan for one consumer, and that consumer's own calls, must be issued in
+ *               stream order from one host thread.  A call with M == 0 launches nothing and changes nothing.
+ *               NULL: no scan */
 typedef struct {
     int32_t *acc;
     float *y;
     int8_t *q;
     float out_scale;
     const flexiq_layer *lower_for;
+    flexiq_layer *scan_for;
 } flexiq_out;
 
 /* Mixed-precision GEMM (Sections 2.3, 7):

@@ -25,7 +25,7 @@ class _PackDesc(C.Structure):
 
 class _Out(C.Structure):
     _fields_ = [("acc", C.c_void_p), ("y", C.c_void_p), ("q", C.c_void_p), ("out_scale", C.c_float),
-                ("lower_for", C.c_void_p)]
+                ("lower_for", C.c_void_p), ("scan_for", C.c_void_p)]
 
 
 def exported_symbols():
@@ -212,7 +212,7 @@ def flexiq_permute_channels(layer: Layer, src):
     return dst
 
 
-def _outs(shape, device, want_acc, want_y, want_q, out_scale, bufs, lower_for=None):
+def _outs(shape, device, want_acc, want_y, want_q, out_scale, bufs, lower_for=None, scan_for=None):
     import torch
     acc = y = q = None
     if want_acc:
@@ -223,32 +223,33 @@ def _outs(shape, device, want_acc, want_y, want_q, out_scale, bufs, lower_for=No
         q = bufs.get("q") if bufs and "q" in bufs else torch.empty(shape, dtype=torch.int8, device=device)
     o = _Out(acc.data_ptr() if acc is not None else None, y.data_ptr() if y is not None else None,
              q.data_ptr() if q is not None else None, float(out_scale),
-             lower_for._h if lower_for is not None else None)
+             lower_for._h if lower_for is not None else None, scan_for._h if scan_for is not None else None)
     return o, {"acc": acc, "y": y, "q": q}
 
 
 def flexiq_mixed_gemm(layer: Layer, X, acc: bool = False, y: bool = False, q: bool = False,
-                      out_scale: float = 1.0, bufs: Optional[dict] = None, lower_for: Optional[Layer] = None):
+                      out_scale: float = 1.0, bufs: Optional[dict] = None, lower_for: Optional[Layer] = None,
+                      scan_for: Optional[Layer] = None):
     """X: int8 cuda [M][C] in stored channel order.  Returns a dict of the requested outputs.
-    lower_for: the layer that consumes q (flexiq_out.lower_for)."""
+    lower_for / scan_for: the layer that consumes q (flexiq_out.lower_for, flexiq_out.scan_for)."""
     import torch
     assert X.is_cuda and X.dtype == torch.int8 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == layer.C
     M = X.shape[0]
-    o, res = _outs((M, layer.N), X.device, acc, y, q, out_scale, bufs, lower_for)
+    o, res = _outs((M, layer.N), X.device, acc, y, q, out_scale, bufs, lower_for, scan_for)
     _check(load().flexiq_mixed_gemm(layer._h, X.data_ptr(), M, C.byref(o), _stream()))
     return res
 
 
 def flexiq_mixed_conv_implicit(layer: Layer, X, stride: int, pad: int, acc: bool = False, y: bool = False,
                                q: bool = False, out_scale: float = 1.0, bufs: Optional[dict] = None,
-                               lower_for: Optional[Layer] = None):
+                               lower_for: Optional[Layer] = None, scan_for: Optional[Layer] = None):
     """X: int8 cuda NHWC [B][H][W][C] in stored channel order."""
     import torch
     assert X.is_cuda and X.dtype == torch.int8 and X.is_contiguous() and X.dim() == 4 and X.shape[3] == layer.C
     B, H, Wd, _ = X.shape
     Ho = (H + 2 * pad - layer.R) // stride + 1
     Wo = (Wd + 2 * pad - layer.S) // stride + 1
-    o, res = _outs((B, Ho, Wo, layer.N), X.device, acc, y, q, out_scale, bufs, lower_for)
+    o, res = _outs((B, Ho, Wo, layer.N), X.device, acc, y, q, out_scale, bufs, lower_for, scan_for)
     _check(load().flexiq_mixed_conv_implicit(layer._h, X.data_ptr(), B, H, Wd, stride, pad, C.byref(o), _stream()))
     return res
 

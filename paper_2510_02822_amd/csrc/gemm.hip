@@ -13,6 +13,12 @@ namespace flexiq {
 // Host side: tile-shape choice and launch
 // ---------------------------------------------------------------------------------------------
 
+// Clears a few words (the mask set a producer is about to fill, when no consumer call has cleared it).
+__global__ void k_zero_words(uint32_t *w, int n)
+{
+    for (int i = threadIdx.x; i < n; i += blockDim.x) w[i] = 0;
+}
+
 static const TileShape *shapes(int *count)
 {
     static const TileShape tab[kNumTileShapes] = {tile_shape_0(), tile_shape_1(), tile_shape_2(), tile_shape_3(),
@@ -99,7 +105,13 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
 {
     GemmParams p;
     p.X = X; p.W8 = L->d_w8; p.W4 = L->d_w4; p.wshift = L->d_wshift;
-    p.ashift = L->dynamic ? L->d_ashift_dyn : L->d_ashift;
+    p.ashift = L->dynamic == 1 ? L->d_ashift_dyn : L->d_ashift;
+    p.scan_masks = nullptr; p.scan_clear = nullptr; p.scan_g4 = 0;
+    if (L->dynamic == 2) {   // positions from the masks the producing layer left; the other set is cleared on the way
+        p.scan_masks = L->d_masks + (size_t)L->mask_cur * (L->G + 1);
+        p.scan_clear = L->d_masks + (size_t)(1 - L->mask_cur) * (L->G + 1);
+        p.scan_g4 = L->max_4bit_ch / L->group_size;
+    }
     p.cs = L->d_cs; p.bias = L->d_bias;
     p.acc = out->acc; p.y = out->y; p.q = out->q;
     p.r_out = out->q ? 1.0f / out->out_scale : 1.0f;
@@ -107,11 +119,26 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     p.K4 = L->max_4bit_ch;
     p.x_pre = L->x_prelowered ? 1 : 0;
     p.next_ashift = nullptr; p.next_K4 = 0; p.next_G = 0; p.next_gs_log2 = 5;
+    p.next_scan = nullptr;
+    if (out->lower_for && out->scan_for) return FLEXIQ_EINVAL;   // lowering needs positions the scan has yet to find
     if (out->lower_for) {
         const flexiq_layer *nx = out->lower_for;
         if (!out->q || nx->C != L->N || nx->device != L->device) return FLEXIQ_EINVAL;
-        p.next_ashift = nx->dynamic ? nx->d_ashift_dyn : nx->d_ashift;
+        if (nx->dynamic == 2) return FLEXIQ_EINVAL;   // its positions exist only as masks
+        p.next_ashift = nx->dynamic == 1 ? nx->d_ashift_dyn : nx->d_ashift;
         p.next_K4 = nx->max_4bit_ch;
+        p.next_G = nx->G;
+        p.next_gs_log2 = nx->group_size == 64 ? 6 : 5;
+    }
+    if (out->scan_for) {
+        flexiq_layer *nx = out->scan_for;
+        if (!out->q || nx->C != L->N || nx->device != L->device || nx == L) return FLEXIQ_EINVAL;
+        if (nx->mask_dirty[nx->mask_set]) {   // the set was never consumed (two producer calls in a row): clear it first
+            k_zero_words<<<1, 256, 0, (hipStream_t)stream>>>(nx->d_masks + (size_t)nx->mask_set * (nx->G + 1), nx->G + 1);
+            FLEXIQ_HIP(hipGetLastError());
+            nx->mask_dirty[nx->mask_set] = false;
+        }
+        p.next_scan = nx->d_masks + (size_t)nx->mask_set * (nx->G + 1);
         p.next_G = nx->G;
         p.next_gs_log2 = nx->group_size == 64 ? 6 : 5;
     }
@@ -152,6 +179,14 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     g_last_resident = resident;
     hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3(ts.threads), ts.lds, (hipStream_t)stream, p);
     FLEXIQ_HIP(hipGetLastError());
+    if (out->scan_for) {   // the consumer's next calls take their positions from the masks this launch leaves
+        flexiq_layer *nx = out->scan_for;
+        nx->mask_dirty[nx->mask_set] = true;
+        nx->mask_cur = nx->mask_set;
+        nx->mask_set = 1 - nx->mask_set;
+        nx->dynamic = 2;
+    }
+    if (L->dynamic == 2) L->mask_dirty[1 - L->mask_cur] = false;   // this launch cleared it
     return FLEXIQ_OK;
 }
 

@@ -64,6 +64,14 @@ struct GemmParams {
     // optional: lower the int8 output for the layer that consumes it (its positions, its 4-bit channel count)
     const int32_t *next_ashift;
     int32_t next_K4, next_G, next_gs_log2;
+    // optional: scan the int8 output for the consumer's run-time positions (OR of the magnitude bits per channel
+    // group of the consumer, merged into its mask words with fire-and-forget atomics)
+    uint32_t *next_scan;          // consumer's mask words [next_G] (zero before the call); null: no scan
+    // optional: this layer's own positions come from such masks (highest magnitude bit p of a 4-bit group ->
+    // max(0, p - 2); the table `ashift` for the other groups); block 0 clears the other mask set on the way
+    const uint32_t *scan_masks;
+    uint32_t *scan_clear;
+    int32_t scan_g4;
     int32_t gs_shift;  // log2(group_size / 32): unit c32 belongs to group c32 >> gs_shift
     int32_t G;       // channel groups
     int32_t U;       // units in the reduction (even per tap), CU = C/32 per tap
@@ -173,7 +181,8 @@ struct Cfg {
     static constexpr int NSTAGE = 4;
     // activation positions of up to 160 groups; scale, bias and the consumer's extraction position of the columns
     // of two consecutive tiles
-    static constexpr int TABLE = 640 + 2 * (3 * BN * 4);
+    // ... and the block's share of the masks it collects for a consuming layer (up to 160 groups)
+    static constexpr int TABLE = 640 + 2 * (3 * BN * 4) + 640;
     static constexpr int RING = NSTAGE * STAGE;
     // A block may walk several output tiles.  Not for the largest tiles: their accumulators fill the register
     // file, and the values that would have to stay live across an epilogue do not fit beside them.
@@ -212,6 +221,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     extern __shared__ __align__(16) unsigned char lds[];
     unsigned char *const sa_tab = lds + C_::RING;
     float *const cs_tab = reinterpret_cast<float *>(sa_tab + 640);  // two copies (tile parity) of [BN] scales, [BN] biases, [BN] positions
+    uint32_t *const mask_tab = reinterpret_cast<uint32_t *>(sa_tab + 640 + 2 * (3 * BN * 4));   // scan for a consumer: OR masks per group
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -331,7 +341,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // activation positions of all groups: loaded into a register here, written to LDS after the prologue's tile
     // loads have been issued (one memory latency for all)
     static_assert(BN <= NT && 160 <= NT, "one table element per thread");
-    const int sa_v = tid <= p.G ? p.ashift[tid] : 0;
+    int sa_v = tid <= p.G ? p.ashift[tid] : 0;
+    if (p.scan_masks) {
+        if (tid < p.scan_g4) {
+            const uint32_t mask = p.scan_masks[tid];
+            const int hb = mask ? 31 - __builtin_clz(mask) : -1;
+            sa_v = hb - 2 > 0 ? hb - 2 : 0;
+        }
+        if (blockIdx.x == 0 && tid <= p.G) p.scan_clear[tid] = 0;
+    }
     int parity = 0;   // which copy of the scale / bias table belongs to the tile being computed
     // Scales and biases of the BN columns from column c0 on, straight into table copy `par` (no register hop, so
     // nothing has to wait for them here; the end-of-step waits of the K loop cover them before the epilogue).
@@ -571,6 +589,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         plain_prologue = !PACKED4 && pmode[0] == kMode88 && pmode[1] == kMode88 && mode_staged == kMode88;
         FQ_TS(tqb);
         if (tid <= p.G) reinterpret_cast<int *>(sa_tab)[tid] = sa_v;
+        if (p.next_scan && tid < 160) mask_tab[tid] = 0;
         __builtin_amdgcn_s_waitcnt(0xc07f);
         __builtin_amdgcn_s_barrier();   // position table visible
         FQ_TS(tqc);
@@ -630,6 +649,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     int s = 0;    // K-step within the output tile being computed
     constexpr int kStageSlots = 2 * NMF > 2 ? 2 * NMF - 2 : 1;    // slots that carry staging work
     constexpr int kAdvanceSlot = 2 * NMF > 2 ? 2 * NMF - 2 : 0;   // slot after which the load iterator moves on
+    // fragment reads of the second k-half that are issued after the last slot with staging work
+    constexpr int kLateReads = [] {
+        int n = 0;
+        for (int k = 0; k < NF; ++k)
+            if (NMF + k * NMF / NF > kStageSlots - 1) ++n;
+        return n < 15 ? n : 15;
+    }();
     auto step = [&](auto ma_, auto mb_, auto h1_) {
         const int ma = ma_, mb = mb_;
         const bool h1 = h1_;
@@ -714,7 +740,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
 #ifdef FLEXIQ_TIMING
         const long long tw1 = __builtin_readcyclecounter();
 #endif
-        __builtin_amdgcn_s_waitcnt(0xc07f);  // this wave's LDS stores and fragment reads are complete
+        // This wave's LDS stores and its reads of the stage that is refilled next are complete.  The fragment reads
+        // issued after the last staging slot (they read the next step's stage, which nobody overwrites yet) may
+        // stay in flight across the barrier: LDS operations complete in order, so allowing that many outstanding
+        // ones still covers every store.
+        if (h1)
+            __builtin_amdgcn_s_waitcnt(0xc07f | (kLateReads << 8));
+        else
+            __builtin_amdgcn_s_waitcnt(0xc07f);
         __builtin_amdgcn_s_barrier();
 #ifdef FLEXIQ_TIMING
         t_wait_vm += tw1 - tw0;
@@ -743,16 +776,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
 #endif
     const bool n_vec = (p.N & 3) == 0;
     const bool lower_out = p.next_ashift != nullptr;   // int8 output lowered for the consuming layer
+    const bool scan_out = p.next_scan != nullptr;      // int8 output scanned for the consuming layer's positions
     const bool q_rows = want_q && (p.N & 15) == 0;   // int8 output as 16-byte row-contiguous pieces
     const int frag_half_e = lane >> 5, frag_row_e = lane & 31;
     // (one call handles fragment column a; the variant is chosen per column, which keeps the live ranges of the
     // accumulators short where the variants branch apart)
-    auto epilogue = [&](auto a_, auto wq_, auto wy_, auto wa_, auto nv_, auto qr_, auto lw_) {
-        const bool wq = wq_, wy = wy_, wa = wa_, nv = nv_, qr = qr_, lw = lw_;
+    auto epilogue = [&](auto a_, auto wq_, auto wy_, auto wa_, auto nv_, auto qr_, auto lw_, auto sc_) {
+        const bool wq = wq_, wy = wy_, wa = wa_, nv = nv_, qr = qr_, lw = lw_, sc = sc_;
         constexpr int a = decltype(a_)::value;
         const float *tab = cs_tab + parity * (3 * BN);
         {
             uint32_t qrow[TM][4];   // int8 codes of the four quads of fragment (a, b)
+            uint32_t seen = 0;      // scan: OR of the magnitude bits (v >= 0 ? v : ~v) of this lane's valid codes, per byte
             // scale and bias of a quad's four columns are read from the LDS table one quad ahead
             const int nl0 = (wn * TN + a) * 32 + 4 * frag_half_e;
             float4 cs_nx = *reinterpret_cast<const float4 *>(tab + nl0);
@@ -810,6 +845,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                         qw ^= 0x80808080u;
                         if (lw) qw &= qmask;
                         qrow[b][g] = qw;
+                        if (sc) {
+                            const uint32_t flip = ((qw >> 7) & 0x01010101u) * 0xFFu;
+                            seen |= (m < p.M && n_ok) ? (qw ^ flip) : 0u;
+                        }
                     }
                     if (!(wy || wa || (wq && !qr))) continue;   // nothing is stored quad by quad
                     if (m >= p.M || !n_ok) continue;
@@ -835,6 +874,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                 }
             }
             FQ_SB();
+            if (wq && sc) {
+                // The 32 columns of a fragment column lie in one channel group of the consumer (its groups are 32 or 64
+                // channels, tiles start at multiples of 32).  Fold the four bytes, OR over the wave one bit at a
+                // time (wave-uniform result), and merge.
+                seen |= seen >> 16;
+                seen |= seen >> 8;
+                uint32_t w = 0;
+#pragma unroll
+                for (int bit = 0; bit < 7; ++bit)
+                    if (__builtin_amdgcn_ballot_w64(((seen >> bit) & 1u) != 0u) != 0) w |= 1u << bit;
+                const int ncol = n0 + (wn * TN + a) * 32;
+                // (into the block's LDS copy; the device-wide merge happens once, when the block has finished its
+                // tiles: a global atomic per tile would hold up the loads queued behind it)
+                if (lane == 0 && w != 0 && ncol < p.N) __hip_atomic_fetch_or(mask_tab + (ncol >> p.next_gs_log2), w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
             if (wq && qr) {
                 // The two halves of the wave hold alternating 4-byte pieces of a row.  Exchanging quads 0 <-> 2
                 // and 1 <-> 3 between the halves leaves lanes 0..31 with channels 0..15 of the fragment's 32 and
@@ -891,11 +945,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         const long long te0 = __builtin_readcyclecounter();
 #endif
         auto epilogue_col = [&](auto a_) {
-            if (q_rows && !want_y && !want_acc && !lower_out) epilogue(a_, T_{}, F_{}, F_{}, T_{}, T_{}, F_{});
-            else if (q_rows && !want_y && !want_acc) epilogue(a_, T_{}, F_{}, F_{}, T_{}, T_{}, T_{});
-            else if (n_vec && !want_q && want_y && !want_acc) epilogue(a_, F_{}, T_{}, F_{}, T_{}, F_{}, F_{});
-            else if (n_vec && !want_q && !want_y && want_acc) epilogue(a_, F_{}, F_{}, T_{}, T_{}, F_{}, F_{});
-            else epilogue(a_, want_q, want_y, want_acc, n_vec, q_rows, lower_out);
+            if (q_rows && !want_y && !want_acc && !lower_out && !scan_out) epilogue(a_, T_{}, F_{}, F_{}, T_{}, T_{}, F_{}, F_{});
+            else if (q_rows && !want_y && !want_acc && !scan_out) epilogue(a_, T_{}, F_{}, F_{}, T_{}, T_{}, T_{}, F_{});
+            else if (q_rows && !want_y && !want_acc && !lower_out) epilogue(a_, T_{}, F_{}, F_{}, T_{}, T_{}, F_{}, T_{});
+            else if (n_vec && !want_q && want_y && !want_acc) epilogue(a_, F_{}, T_{}, F_{}, T_{}, F_{}, F_{}, F_{});
+            else if (n_vec && !want_q && !want_y && want_acc) epilogue(a_, F_{}, F_{}, T_{}, T_{}, F_{}, F_{}, F_{});
+            else epilogue(a_, want_q, want_y, want_acc, n_vec, q_rows, lower_out, scan_out);
             FQ_SB();
         };
         epilogue_col(std::integral_constant<int, 0>{});
@@ -921,6 +976,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         fetch_scales(n0, parity);
         zero_acc();
         s = 0;
+    }
+    // ---- scan for the consumer: merge the block's masks into the consumer's mask words (device-scope atomics,
+    // fire-and-forget; the consumer's kernel reads them after this kernel has ended)
+    if (scan_out) {
+        __syncthreads();
+        if (tid < p.next_G) {
+            const uint32_t m = mask_tab[tid];
+            if (m) atomicOr(p.next_scan + tid, m);
+        }
     }
 #ifdef FLEXIQ_TIMING
     {

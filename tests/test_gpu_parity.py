@@ -288,6 +288,72 @@ def test_two_layer_chain_static_reorder(env):
         fq.flexiq_mixed_gemm(h2, mid, q=True, out_scale=1.0, lower_for=h2)             # consumer width mismatch
 
 
+def test_producer_scans_for_consumer(env):
+    # Section 4.1 / Section 9 "Finding extraction positions at runtime", done where the tensor is produced: fc1's
+    # epilogue ORs the magnitude bits of its int8 output per channel group of fc2 and the last block leaves fc2's
+    # run-time positions.  Checked for every tile shape of the producer (all reduction paths over the wave), on a
+    # ragged row count (rows of the last tile beyond M carry the bias and must not count), for several ratios of the
+    # consumer in a row (the scan words must be clean again after every call) and two output scales.
+    torch, oracle, fq, dev = env
+    M, K1, N1, N2, gs = 300, 192, 256, 96, 32
+    c1 = workloads.make_linear("scan1", 8, 211, M, K1, N1, gs, outlier_frac=0.02)
+    c2 = workloads.make_linear("scan2", 8, 212, M, N1, N2, gs, outlier_frac=0.02)
+    xs1, am1 = __import__("helpers").calib(c1)
+    o1 = oracle.prepare_layer(c1.W, am1, xs1, gs, bias=c1.bias)
+    Xq = oracle.quantize(c1.X, xs1)[:, o1.perm]
+    acc1 = oracle.forward_gemm(o1, Xq, 0.5)
+    y1 = oracle.dequant_f64(acc1, xs1, o1.w_scale, o1.bias)
+    s0 = float(np.abs(y1).max() / 127.0)
+    n_tiles = fq.debug_force_tile(-1)
+    seen_dynamic = False   # the scan changed something against the calibrated positions
+    try:
+        for s_mid in (s0, 6.0 * s0):
+            q1 = oracle.requant_i8(acc1, xs1, o1.w_scale, s_mid, o1.bias)
+            am2 = np.abs(q1).max(0).astype(np.float32) * np.float32(s_mid) * np.float32(3.0)   # calibrated too wide
+            o2 = oracle.prepare_layer(c2.W, am2, s_mid, gs, bias=c2.bias)
+            X2 = np.ascontiguousarray(q1[:, o2.perm])
+            h2 = fq.flexiq_quantize_pack(c2.W, am2, s_mid, gs, bias=c2.bias)
+            h1 = fq.flexiq_quantize_pack(c1.W, am1, xs1, gs, bias=c1.bias, out_perm=o2.perm)
+            fq.flexiq_set_ratio(h1, 0.5)
+            for t in range(n_tiles):
+                for r2 in (0.75, 0.25, 1.0):
+                    fq.flexiq_set_ratio(h2, r2)
+                    G4 = oracle.groups_for_ratio(r2, o2.G)
+                    fq.debug_force_tile(t)
+                    mid = fq.flexiq_mixed_gemm(h1, _dev(torch, Xq, dev), q=True, out_scale=s_mid, scan_for=h2)["q"]
+                    fq.debug_force_tile(-1)
+                    assert (mid.cpu().numpy() == X2).all(), (t, r2)
+                    dyn = oracle.dynamic_act_shifts(X2, gs, G4, o2.a_shift)
+                    assert (fq.flexiq_layer_positions(h2) == dyn).all(), (t, r2, s_mid)
+                    seen_dynamic |= bool((dyn != o2.a_shift).any())
+                    got = fq.flexiq_mixed_gemm(h2, mid, acc=True)["acc"].cpu().numpy()
+                    assert (got == oracle.mixed_gemm(X2, o2.Wq.reshape(N2, N1), gs, G4, dyn, o2.w_shift)).all(), (t, r2)
+            # two producer calls in a row (the first on other data): only the last one counts
+            fq.flexiq_set_ratio(h2, 0.75)
+            fq.flexiq_mixed_gemm(h1, _dev(torch, (Xq // 2).astype(np.int8), dev), q=True, out_scale=s_mid / 4, scan_for=h2)
+            mid = fq.flexiq_mixed_gemm(h1, _dev(torch, Xq, dev), q=True, out_scale=s_mid, scan_for=h2)["q"]
+            G4 = oracle.groups_for_ratio(0.75, o2.G)
+            assert (fq.flexiq_layer_positions(h2) == oracle.dynamic_act_shifts(X2, gs, G4, o2.a_shift)).all()
+            # the ratio in force when the consumer runs decides which groups use the masks
+            fq.flexiq_set_ratio(h2, 1.0)
+            dyn = oracle.dynamic_act_shifts(X2, gs, o2.G, o2.a_shift)
+            got = fq.flexiq_mixed_gemm(h2, mid, acc=True)["acc"].cpu().numpy()
+            assert (got == oracle.mixed_gemm(X2, o2.Wq.reshape(N2, N1), gs, o2.G, dyn, o2.w_shift)).all()
+            with pytest.raises(fq.FlexiqError):
+                fq.flexiq_mixed_gemm(h1, _dev(torch, Xq, dev), q=True, out_scale=s_mid, lower_for=h2)   # positions exist only as masks
+            # same result as the stand-alone scan kernel
+            fq.flexiq_set_ratio(h2, 1.0)
+            fq.flexiq_dynamic_positions(h2, mid)
+            assert (fq.flexiq_layer_positions(h2) == oracle.dynamic_act_shifts(X2, gs, o2.G, o2.a_shift)).all()
+            with pytest.raises(fq.FlexiqError):
+                fq.flexiq_mixed_gemm(h1, _dev(torch, Xq, dev), q=True, out_scale=s_mid, lower_for=h2, scan_for=h2)
+            with pytest.raises(fq.FlexiqError):
+                fq.flexiq_mixed_gemm(h1, _dev(torch, Xq, dev), acc=True, scan_for=h2)   # needs the int8 output
+    finally:
+        fq.debug_force_tile(-1)
+    assert seen_dynamic
+
+
 def test_gemm_saturating_inputs(env):
     # activations far beyond the calibrated range: the clamp of the lowering is active everywhere
     torch, oracle, fq, dev = env
