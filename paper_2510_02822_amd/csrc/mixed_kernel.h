@@ -7,10 +7,13 @@
 // is instead formed by putting each bit-lowered operand back at its extraction position as an int8
 // value (both factors fit: |L << s| <= 128) and feeding the same int8 MFMA and the same int32
 // accumulator as the 8-bit groups: bit-exact by distributivity, and the separate shift-and-accumulate
-// stage of the paper's CUDA kernel disappears.  What the 4-bit groups save here is weight bytes (they
-// are streamed from the packed 4-bit copy), not matrix cycles.
+// stage of the paper's CUDA kernel disappears.  A 4-bit group therefore costs the same matrix cycles as
+// an 8-bit one; its weights can be streamed from the packed 4-bit copy (half the bytes) or, by default,
+// from a copy that is already expanded (no vector-ALU work beside the matrix pipe).
 //
-// Work decomposition: a block of four waves (one per SIMD) owns a BM x BN output tile; the reduction
+// Work decomposition: a block of four waves (one per SIMD) or eight waves (two per SIMD: the second
+// wave's MFMAs fill the issue slots the first one spends on copies, address updates and the epilogue)
+// owns a BM x BN output tile; the reduction
 // runs in K-steps of 64 elements (two 32-channel units, each independently 4-bit or 8-bit), each
 // K-step being two k-halves of v_mfma_i32_32x32x32_i8 (a single wave per SIMD keeps the matrix pipe
 // full with this instruction shape; the 16x16x64 shape needs two).  Operand tiles live in an LDS ring of
