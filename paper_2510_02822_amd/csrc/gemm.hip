@@ -162,6 +162,13 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     const TileShape &ts = shapes(&cnt)[g_last_shape];
     p.tiles_m = (int)((M + ts.BM - 1) / ts.BM);
     p.tiles_n = (L->N + ts.BN - 1) / ts.BN;
+    {   // constants of the kernel's tile-index divisions
+        const uint32_t d1 = 8u * (uint32_t)p.tiles_n, d2 = (uint32_t)(p.tiles_m % 8);
+        p.band_div = d1;
+        p.band_mag = (uint32_t)((1ull << 32) / d1);
+        p.tail_div = d2 ? d2 : 1u;
+        p.tail_mag = d2 > 1 ? (uint32_t)((1ull << 32) / d2) : 0xffffffffu;
+    }
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     if (tiles > 0x7fffffff) return FLEXIQ_EINVAL;
     kernel_fn fn = ts.fn[conv ? 1 : 0][packed ? 1 : 0];

@@ -81,6 +81,9 @@ struct GemmParams {
     int32_t CU;
     int32_t T;       // filter taps
     int32_t tiles_m, tiles_n;
+    // division of a tile index by 8 * tiles_n and by tiles_m % 8 (the two run-time divisors of the tile mapping) by
+    // multiplication: mag = floor(2^32 / d); d = 1 where the divisor would be 0
+    uint32_t band_div, band_mag, tail_div, tail_mag;
     // convolution geometry (unused for the linear form)
     int32_t H, Wd, Ho, Wo, S, stride, pad;
 };
@@ -241,16 +244,26 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // an XCD walk neighbouring tiles, then sweep bands of 8 tile rows with the tile column varying slowest
     // inside a band (weights stay L2-resident).
     const int total_tiles = p.tiles_m * p.tiles_n;
+    // n / d for n < 2^31 with mag = floor(2^32 / d): the product's high word is the quotient or one less
+    auto udiv = [](uint32_t n, uint32_t d, uint32_t mag, uint32_t &rem) {
+        uint32_t q = __umulhi(n, mag);
+        uint32_t r = n - q * d;
+        const bool more = r >= d;
+        q = more ? q + 1 : q;
+        rem = more ? r - d : r;
+        return q;
+    };
     auto map_tile = [&](int t, int &tile_m, int &tile_n) {
-        int b = t;
-        if (total_tiles % 8 == 0) b = (b % 8) * (total_tiles / 8) + b / 8;
+        uint32_t b = (uint32_t)t;
+        if (total_tiles % 8 == 0) b = (b % 8) * (uint32_t)(total_tiles / 8) + b / 8;
         constexpr int GMB = 8;
-        const int band = b / (GMB * p.tiles_n);
-        const int rows_in_band = min(GMB, p.tiles_m - band * GMB);
-        const int r = b - band * GMB * p.tiles_n;
-        // the division runs on the vector ALU; tell the compiler the result is wave-uniform
-        tile_m = __builtin_amdgcn_readfirstlane(band * GMB + r % rows_in_band);
-        tile_n = __builtin_amdgcn_readfirstlane(r / rows_in_band);
+        uint32_t r;
+        const int band = (int)udiv(b, p.band_div, p.band_mag, r);   // r: index inside the band
+        const bool full = p.tiles_m - band * GMB >= GMB;            // a band of 8 tile rows, or the shorter last one
+        uint32_t rt;
+        const uint32_t qt = udiv(r, p.tail_div, p.tail_mag, rt);
+        tile_m = band * GMB + (int)(full ? (r & 7u) : rt);
+        tile_n = (int)(full ? (r >> 3) : qt);
     };
     int ctile = blockIdx.x;   // tile being computed
     int64_t m0;               // its origin
@@ -640,6 +653,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
 #ifdef FLEXIQ_TIMING
     long long tq1 = __builtin_readcyclecounter(), t_epi = 0, t_wait_vm = 0, t_wait_bar = 0;
     int n_tiles = 0;
+    long long t_tile0 = tq1, t_sw = 0;
+    __shared__ long long t_at[8][2][16];   // [wave][first tile / later tiles][step]
+    if (lane < 32) t_at[wave][lane >> 4][lane & 15] = 0;
 #endif
     // ---- main loop.  Step s computes K-step s from stage s % 4 while K-step s+3 is loaded (straight into stage
     // (s+3) % 4, or into the staging registers) and the register-routed pieces of K-step s+2 (loaded during step
@@ -754,7 +770,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         __builtin_amdgcn_s_barrier();
 #ifdef FLEXIQ_TIMING
         t_wait_vm += tw1 - tw0;
-        t_wait_bar += __builtin_readcyclecounter() - tw1;
+        {
+            const long long now = __builtin_readcyclecounter();
+            t_wait_bar += now - tw1;
+            if (lane == 0) t_at[wave][n_tiles > 0 ? 1 : 0][s < 15 ? s : 15] += now - t_tile0;
+        }
 #endif
         FQ_SB();
         {
@@ -979,6 +999,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         fetch_scales(n0, parity);
         zero_acc();
         s = 0;
+#ifdef FLEXIQ_TIMING
+        FQ_SB();
+        t_tile0 = __builtin_readcyclecounter();
+        t_sw += t_tile0 - te0 - 0;
+        FQ_SB();
+#endif
     }
     // ---- scan for the consumer: merge the block's masks into the consumer's mask words (device-scope atomics,
     // fire-and-forget; the consumer's kernel reads them after this kernel has ended)
@@ -995,7 +1021,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         if (lane == 0 && p.acc) {
             int *d = p.acc + ((int64_t)blockIdx.x * NW + wave) * 8;
             d[0] = (int)(tq1 - tq0); d[1] = (int)(tq3 - tq1 - t_epi); d[2] = (int)t_epi; d[3] = steps * n_tiles;
-            d[4] = (int)(tqa - tq0); d[5] = (int)t_wait_vm; d[6] = (int)t_wait_bar; d[7] = n_tiles;
+            d[4] = (int)t_sw; d[5] = (int)t_wait_vm; d[6] = (int)t_wait_bar; d[7] = n_tiles;
+            int *e = p.acc + (int64_t)gridDim.x * NW * 8 + ((int64_t)blockIdx.x * NW + wave) * 32;
+            for (int i = 0; i < 32; ++i) e[i] = (int)t_at[wave][i >> 4][i & 15];
         }
     }
 #endif
