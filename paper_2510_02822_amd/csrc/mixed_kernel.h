@@ -651,7 +651,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     for (int i = 0; i < NF; ++i) fread(fA, i, lds, 0);
 
 #ifdef FLEXIQ_TIMING
-    long long tq1 = __builtin_readcyclecounter(), t_epi = 0, t_wait_vm = 0, t_wait_bar = 0;
+    long long tq1 = __builtin_readcyclecounter(), t_epi = 0, t_wait_vm = 0, t_wait_bar = 0, t_wait0 = 0;
     int n_tiles = 0;
     long long t_tile0 = tq1, t_sw = 0;
     __shared__ long long t_at[8][2][16];   // [wave][first tile / later tiles][step]
@@ -770,6 +770,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         __builtin_amdgcn_s_barrier();
 #ifdef FLEXIQ_TIMING
         t_wait_vm += tw1 - tw0;
+        if (s == 0) t_wait0 += tw1 - tw0;
         {
             const long long now = __builtin_readcyclecounter();
             t_wait_bar += now - tw1;
@@ -1021,7 +1022,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         if (lane == 0 && p.acc) {
             int *d = p.acc + ((int64_t)blockIdx.x * NW + wave) * 8;
             d[0] = (int)(tq1 - tq0); d[1] = (int)(tq3 - tq1 - t_epi); d[2] = (int)t_epi; d[3] = steps * n_tiles;
-            d[4] = (int)t_sw; d[5] = (int)t_wait_vm; d[6] = (int)t_wait_bar; d[7] = n_tiles;
+            d[4] = (int)t_wait0; d[5] = (int)t_wait_vm; d[6] = (int)t_wait_bar; d[7] = n_tiles;
             int *e = p.acc + (int64_t)gridDim.x * NW * 8 + ((int64_t)blockIdx.x * NW + wave) * 32;
             for (int i = 0; i < 32; ++i) e[i] = (int)t_at[wave][i >> 4][i & 15];
         }
