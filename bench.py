@@ -104,17 +104,21 @@ def main():
     for _ in range(2):
         one_step()
     torch.cuda.synchronize()
-    # One step (the ratio sweep) is captured once into a HIP graph and replayed: launch-bound Python
-    # overhead stays out of the device timeline.  --eager launches from Python instead.
-    step_graph = None
+    # Steps (ratio sweeps) are captured into a HIP graph, several to a graph, and replayed: launch-bound Python
+    # overhead and most graph-to-graph launch gaps stay out of the device timeline.  --eager launches from Python.
+    chunk = 1
     if not args.eager:
+        chunk = next(c for c in (20, 10, 5, 4, 2, 1) if args.steps % c == 0)
         step_graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(step_graph):
-            one_step()
-    run_step = step_graph.replay if step_graph is not None else one_step
+            for _ in range(chunk):
+                one_step()
+        run_chunk = step_graph.replay
+    else:
+        run_chunk = one_step
 
-    for _ in range(args.warmup):
-        run_step()
+    for _ in range(-(-args.warmup // chunk)):    # at least the requested warm-up steps
+        run_chunk()
     torch.cuda.synchronize()
 
     e0 = torch.cuda.Event(enable_timing=True)
@@ -122,8 +126,8 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     e0.record()
-    for _ in range(args.steps):
-        run_step()
+    for _ in range(args.steps // chunk):      # exactly args.steps steps
+        run_chunk()
     e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t1
@@ -314,7 +318,7 @@ def main():
         "config": {"workload": "ViT-B/16 MLP %s, batch 32 @224px: M=%d K=%d N=%d, group size %d, ratio sweep %s "
                                "per step, epilogue=%s" % (args.layer, M, K, N, gs, list(RATIOS),
                                                           {"q": "int8 requant", "y": "fp32 dequant", "acc": "int32 dump"}[args.out]),
-                   "M": M, "K": K, "N": N, "group_size": gs, "ratios": list(RATIOS)},
+                   "M": M, "K": K, "N": N, "group_size": gs, "ratios": list(RATIOS), "steps_per_graph": chunk},
         "roofline": roofline, "cpu_baseline": cpu, "per_r": per_r, "prelowered_input": pre, "dynamic_positions": dyn, "fused_scan": fused_scan, "ratio_switch": ratio_switch, "parity": parity,
     }
     print(json.dumps(line), flush=True)
