@@ -153,14 +153,13 @@ int flexiq_permute_channels(const flexiq_layer *layer, const int8_t *src, int8_t
  *               are read when this call is made.  NULL: plain int8 codes
  *   scan_for  : optional, not together with lower_for.  The layer that will consume q (same conditions).  The
  *               run-time scan of flexiq_dynamic_positions (Section 4.1; Section 9 "Finding extraction positions at
- *               runtime") is done on q in the same pass: the epilogue ORs the magnitude bits of every channel
- *               group of the consumer into mask words of the consumer's handle, and the consumer's following GEMM /
- *               conv calls turn the masks of their 4-bit groups (the ratio in force at THAT call) into positions in
- *               their prologue; no second kernel, no waiting.  The call switches the consumer to these positions, as
- *               flexiq_dynamic_positions would; flexiq_static_positions switches back.  The handle keeps two mask
- *               sets in turn: calls that scan for one consumer, and that consumer's own calls, must be issued in
- *               stream order from one host thread.  A call with M == 0 launches nothing and changes nothing.
- *               NULL: no scan */
+ *               runtime") is done on q in the same pass: every block ORs the magnitude bits of the codes it writes
+ *               per channel group of the consumer, and the block that finishes last leaves the consumer's run-time
+ *               positions for its 4-bit groups (its ratio when this call is made) and switches it to them, exactly
+ *               as flexiq_dynamic_positions(consumer, q, M) would, without a second kernel.  Uses the consumer's scan
+ *               scratch, which the kernel leaves clean (safe to replay from a captured graph): calls that scan for
+ *               the same consumer must not overlap, nor overlap its flexiq_dynamic_positions.  A call with M == 0
+ *               launches nothing and leaves the positions as they were.  NULL: no scan */
 typedef struct {
     int32_t *acc;
     float *y;

@@ -47,9 +47,8 @@ void set_hip_error(hipError_t e, const char *what);
 //   ashift int32 [G+1]              activation extraction position per group (+1 entry for the pad unit);
 //                                   a second table of the same shape holds the positions found at run time
 //   scan   uint32 [G+1]             OR masks of the run-time scan per group, then a block counter; all zero
-//                                   between calls (the scan kernel cleans up after itself)
-//   masks  uint32 [2][G+1]          OR masks left by a producing layer's epilogue (flexiq_out.scan_for), two sets
-//                                   used alternately
+//                                   between calls (the scanning kernel, stand-alone or a producing layer's GEMM,
+//                                   cleans up after itself)
 //   cs     fp32  [2][Npad]          x_scale * w_scale[n], then the biases (zeros when the layer has none):
 //                                   one allocation, d_bias = d_cs + Npad
 struct flexiq_layer {
@@ -69,16 +68,8 @@ struct flexiq_layer {
     int32_t *d_ashift;
     int32_t *d_ashift_dyn;
     uint32_t *d_scan;
-    // Where GEMM / conv calls take the activation positions from: 0 the calibrated table d_ashift, 1 the run-time
-    // table d_ashift_dyn (written by the stand-alone scan), 2 the OR masks a producing layer's epilogue left in
-    // d_masks (turned into positions in the kernel's prologue).
-    int dynamic;
-    // Two sets of G+1 mask words.  A producer ORs into set `mask_set` and flips it; the consumer reads the set written
-    // last (`mask_cur`) and clears the other one for the next producer call, so neither kernel waits for anything.
-    // Host-side bookkeeping of calls in stream order (mutable: consuming calls take the handle as const).
-    uint32_t *d_masks;
-    mutable int mask_set, mask_cur;
-    mutable bool mask_dirty[2];
+    bool dynamic;   // GEMM / conv calls read d_ashift_dyn (written by the stand-alone scan kernel or by the
+                    // epilogue of a producing layer's call) instead of d_ashift
     bool x_prelowered;   // the caller's activations are bit-lowered already (by the producing layer's epilogue)
     float *d_cs;
     float *d_bias;

@@ -13,12 +13,6 @@ namespace flexiq {
 // Host side: tile-shape choice and launch
 // ---------------------------------------------------------------------------------------------
 
-// Clears a few words (the mask set a producer is about to fill, when no consumer call has cleared it).
-__global__ void k_zero_words(uint32_t *w, int n)
-{
-    for (int i = threadIdx.x; i < n; i += blockDim.x) w[i] = 0;
-}
-
 static const TileShape *shapes(int *count)
 {
     static const TileShape tab[kNumTileShapes] = {tile_shape_0(), tile_shape_1(), tile_shape_2(), tile_shape_3(),
@@ -103,15 +97,9 @@ static int choose_shape(int64_t M, int N, int steps, bool conv, bool packed)
 static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, bool conv,
                   int H, int Wd, int Ho, int Wo, int stride, int pad)
 {
-    GemmParams p;
+    GemmParams p = {};   // every field starts as zero / null
     p.X = X; p.W8 = L->d_w8; p.W4 = L->d_w4; p.wshift = L->d_wshift;
-    p.ashift = L->dynamic == 1 ? L->d_ashift_dyn : L->d_ashift;
-    p.scan_masks = nullptr; p.scan_clear = nullptr; p.scan_g4 = 0;
-    if (L->dynamic == 2) {   // positions from the masks the producing layer left; the other set is cleared on the way
-        p.scan_masks = L->d_masks + (size_t)L->mask_cur * (L->G + 1);
-        p.scan_clear = L->d_masks + (size_t)(1 - L->mask_cur) * (L->G + 1);
-        p.scan_g4 = L->max_4bit_ch / L->group_size;
-    }
+    p.ashift = L->dynamic ? L->d_ashift_dyn : L->d_ashift;
     p.cs = L->d_cs; p.bias = L->d_bias;
     p.acc = out->acc; p.y = out->y; p.q = out->q;
     p.r_out = out->q ? 1.0f / out->out_scale : 1.0f;
@@ -119,13 +107,12 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     p.K4 = L->max_4bit_ch;
     p.x_pre = L->x_prelowered ? 1 : 0;
     p.next_ashift = nullptr; p.next_K4 = 0; p.next_G = 0; p.next_gs_log2 = 5;
-    p.next_scan = nullptr;
+    p.next_scan = nullptr; p.next_static = nullptr; p.next_dyn = nullptr; p.next_g4 = 0;
     if (out->lower_for && out->scan_for) return FLEXIQ_EINVAL;   // lowering needs positions the scan has yet to find
     if (out->lower_for) {
         const flexiq_layer *nx = out->lower_for;
         if (!out->q || nx->C != L->N || nx->device != L->device) return FLEXIQ_EINVAL;
-        if (nx->dynamic == 2) return FLEXIQ_EINVAL;   // its positions exist only as masks
-        p.next_ashift = nx->dynamic == 1 ? nx->d_ashift_dyn : nx->d_ashift;
+        p.next_ashift = nx->dynamic ? nx->d_ashift_dyn : nx->d_ashift;
         p.next_K4 = nx->max_4bit_ch;
         p.next_G = nx->G;
         p.next_gs_log2 = nx->group_size == 64 ? 6 : 5;
@@ -133,12 +120,10 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     if (out->scan_for) {
         flexiq_layer *nx = out->scan_for;
         if (!out->q || nx->C != L->N || nx->device != L->device || nx == L) return FLEXIQ_EINVAL;
-        if (nx->mask_dirty[nx->mask_set]) {   // the set was never consumed (two producer calls in a row): clear it first
-            k_zero_words<<<1, 256, 0, (hipStream_t)stream>>>(nx->d_masks + (size_t)nx->mask_set * (nx->G + 1), nx->G + 1);
-            FLEXIQ_HIP(hipGetLastError());
-            nx->mask_dirty[nx->mask_set] = false;
-        }
-        p.next_scan = nx->d_masks + (size_t)nx->mask_set * (nx->G + 1);
+        p.next_scan = nx->d_scan;
+        p.next_static = nx->d_ashift;
+        p.next_dyn = nx->d_ashift_dyn;
+        p.next_g4 = nx->max_4bit_ch / nx->group_size;
         p.next_G = nx->G;
         p.next_gs_log2 = nx->group_size == 64 ? 6 : 5;
     }
@@ -186,14 +171,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     g_last_resident = resident;
     hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3(ts.threads), ts.lds, (hipStream_t)stream, p);
     FLEXIQ_HIP(hipGetLastError());
-    if (out->scan_for) {   // the consumer's next calls take their positions from the masks this launch leaves
-        flexiq_layer *nx = out->scan_for;
-        nx->mask_dirty[nx->mask_set] = true;
-        nx->mask_cur = nx->mask_set;
-        nx->mask_set = 1 - nx->mask_set;
-        nx->dynamic = 2;
-    }
-    if (L->dynamic == 2) L->mask_dirty[1 - L->mask_cur] = false;   // this launch cleared it
+    if (out->scan_for) out->scan_for->dynamic = true;   // its next calls read the positions this launch leaves
     return FLEXIQ_OK;
 }
 

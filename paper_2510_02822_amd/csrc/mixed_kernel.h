@@ -68,13 +68,11 @@ struct GemmParams {
     const int32_t *next_ashift;
     int32_t next_K4, next_G, next_gs_log2;
     // optional: scan the int8 output for the consumer's run-time positions (OR of the magnitude bits per channel
-    // group of the consumer, merged into its mask words with fire-and-forget atomics)
-    uint32_t *next_scan;          // consumer's mask words [next_G] (zero before the call); null: no scan
-    // optional: this layer's own positions come from such masks (highest magnitude bit p of a 4-bit group ->
-    // max(0, p - 2); the table `ashift` for the other groups); block 0 clears the other mask set on the way
-    const uint32_t *scan_masks;
-    uint32_t *scan_clear;
-    int32_t scan_g4;
+    // group of the consumer, merged into its scan words; the block that finishes last turns them into positions)
+    uint32_t *next_scan;          // consumer's scan words [next_G + 1] (all zero between calls); null: no scan
+    const int32_t *next_static;   // consumer's calibrated positions (kept for its 8-bit groups)
+    int32_t *next_dyn;            // consumer's run-time position table
+    int32_t next_g4;              // consumer's 4-bit groups
     int32_t gs_shift;  // log2(group_size / 32): unit c32 belongs to group c32 >> gs_shift
     int32_t G;       // channel groups
     int32_t U;       // units in the reduction (even per tap), CU = C/32 per tap
@@ -357,15 +355,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // activation positions of all groups: loaded into a register here, written to LDS after the prologue's tile
     // loads have been issued (one memory latency for all)
     static_assert(BN <= NT && 160 <= NT, "one table element per thread");
-    int sa_v = tid <= p.G ? p.ashift[tid] : 0;
-    if (p.scan_masks) {
-        if (tid < p.scan_g4) {
-            const uint32_t mask = p.scan_masks[tid];
-            const int hb = mask ? 31 - __builtin_clz(mask) : -1;
-            sa_v = hb - 2 > 0 ? hb - 2 : 0;
-        }
-        if (blockIdx.x == 0 && tid <= p.G) p.scan_clear[tid] = 0;
-    }
+    const int sa_v = tid <= p.G ? p.ashift[tid] : 0;
     int parity = 0;   // which copy of the scale / bias table belongs to the tile being computed
     // Scales and biases of the BN columns from column c0 on, straight into table copy `par` (no register hop, so
     // nothing has to wait for them here; the end-of-step waits of the K loop cover them before the epilogue).
@@ -1007,13 +997,37 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         FQ_SB();
 #endif
     }
-    // ---- scan for the consumer: merge the block's masks into the consumer's mask words (device-scope atomics,
-    // fire-and-forget; the consumer's kernel reads them after this kernel has ended)
+    // ---- scan for the consumer: merge the block's masks into the consumer's scan words (device-scope atomics);
+    // the block that finishes last turns the merged masks into positions (highest magnitude bit p of a 4-bit
+    // group -> max(0, p - 2); calibrated value for the others) and clears the scan words for the next call.  It is
+    // enough that this block's atomics have been performed before its ticket is drawn (no release fence: that
+    // would also write back the output tile from L2).
     if (scan_out) {
         __syncthreads();
         if (tid < p.next_G) {
             const uint32_t m = mask_tab[tid];
             if (m) atomicOr(p.next_scan + tid, m);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0070);
+        __syncthreads();
+        int *flag = reinterpret_cast<int *>(lds);
+        if (tid == 0) *flag = atomicAdd(p.next_scan + p.next_G, 1u) == gridDim.x - 1 ? 1 : 0;
+        __syncthreads();
+        if (*flag) {
+            for (int g = tid; g < p.next_G; g += NT) {
+                if (g < p.next_g4) {
+                    const uint32_t mask = atomicOr(p.next_scan + g, 0u);   // device-scope read of what all blocks added
+                    const int hb = mask ? 31 - __builtin_clz(mask) : -1;
+                    p.next_dyn[g] = hb - 2 > 0 ? hb - 2 : 0;
+                } else {
+                    p.next_dyn[g] = p.next_static[g];
+                }
+                p.next_scan[g] = 0;
+            }
+            if (tid == 0) {
+                p.next_dyn[p.next_G] = p.next_static[p.next_G];
+                p.next_scan[p.next_G] = 0;
+            }
         }
     }
 #ifdef FLEXIQ_TIMING

@@ -322,7 +322,7 @@ struct DevBuf {  // frees on scope exit unless released
 extern "C" int flexiq_layer_free(flexiq_layer *L)
 {
     if (!L) return FLEXIQ_OK;
-    void *bufs[] = {L->d_w8, L->d_w4, L->d_wshift, L->d_ashift, L->d_ashift_dyn, L->d_scan, L->d_masks, L->d_cs, L->d_perm};   // d_w4x is the second half of d_w8, d_bias of d_cs
+    void *bufs[] = {L->d_w8, L->d_w4, L->d_wshift, L->d_ashift, L->d_ashift_dyn, L->d_scan, L->d_cs, L->d_perm};   // d_w4x is the second half of d_w8, d_bias of d_cs
     int rc = FLEXIQ_OK;
     for (void *b : bufs)
         if (b && hipFree(b) != hipSuccess) rc = FLEXIQ_EHIP;
@@ -385,8 +385,7 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
     L->max_4bit_ch = 0;
     L->x_scale = d->x_scale;
     L->has_bias = d->bias != nullptr;
-    L->d_w8 = nullptr; L->d_w4 = nullptr; L->d_w4x = nullptr; L->d_wshift = nullptr; L->d_ashift = nullptr; L->d_ashift_dyn = nullptr; L->d_scan = nullptr; L->d_masks = nullptr; L->dynamic = 0; L->x_prelowered = false;
-    L->mask_set = 0; L->mask_cur = 0; L->mask_dirty[0] = L->mask_dirty[1] = false;
+    L->d_w8 = nullptr; L->d_w4 = nullptr; L->d_w4x = nullptr; L->d_wshift = nullptr; L->d_ashift = nullptr; L->d_ashift_dyn = nullptr; L->d_scan = nullptr; L->dynamic = false; L->x_prelowered = false;
     L->d_cs = nullptr; L->d_bias = nullptr; L->d_perm = nullptr;
     FLEXIQ_HIP(hipGetDevice(&L->device));
     const int Npad = L->Npad;
@@ -448,8 +447,6 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
         FLEXIQ_HIP(hipMemcpy(L->d_ashift_dyn, a32.data(), a32.size() * sizeof(int32_t), hipMemcpyHostToDevice));
         FLEXIQ_HIP(hipMalloc((void **)&L->d_scan, (size_t)(G + 1) * sizeof(uint32_t)));
         FLEXIQ_HIP(hipMemset(L->d_scan, 0, (size_t)(G + 1) * sizeof(uint32_t)));
-        FLEXIQ_HIP(hipMalloc((void **)&L->d_masks, (size_t)2 * (G + 1) * sizeof(uint32_t)));
-        FLEXIQ_HIP(hipMemset(L->d_masks, 0, (size_t)2 * (G + 1) * sizeof(uint32_t)));
     }
     // one more (zero) row than groups: the pad unit of an odd unit count looks up group G
     FLEXIQ_HIP(hipMalloc((void **)&L->d_wshift, (size_t)(G + 1) * Npad));
@@ -590,7 +587,7 @@ extern "C" int flexiq_dynamic_positions(flexiq_layer *L, const int8_t *X, int64_
                                                                             tx_log2, L->group_size, L->G, g4, L->d_scan,
                                                                             L->d_ashift, L->d_ashift_dyn);
     FLEXIQ_HIP(hipGetLastError());
-    L->dynamic = 1;
+    L->dynamic = true;
     return FLEXIQ_OK;
 }
 
@@ -604,7 +601,7 @@ extern "C" int flexiq_input_prelowered(flexiq_layer *L, int on)
 extern "C" int flexiq_static_positions(flexiq_layer *L)
 {
     if (!L) return FLEXIQ_EINVAL;
-    L->dynamic = 0;
+    L->dynamic = false;
     return FLEXIQ_OK;
 }
 
@@ -613,20 +610,8 @@ extern "C" int flexiq_layer_positions(const flexiq_layer *L, uint8_t *a_shift)
     if (!L || !a_shift) return FLEXIQ_EINVAL;
     std::vector<int32_t> a32(L->G);
     FLEXIQ_HIP(hipDeviceSynchronize());
-    FLEXIQ_HIP(hipMemcpy(a32.data(), L->dynamic == 1 ? L->d_ashift_dyn : L->d_ashift, a32.size() * sizeof(int32_t),
+    FLEXIQ_HIP(hipMemcpy(a32.data(), L->dynamic ? L->d_ashift_dyn : L->d_ashift, a32.size() * sizeof(int32_t),
                          hipMemcpyDeviceToHost));
-    if (L->dynamic == 2) {   // masks left by the producer: the conversion the kernel's prologue does
-        std::vector<uint32_t> m(L->G);
-        FLEXIQ_HIP(hipMemcpy(m.data(), L->d_masks + (size_t)L->mask_cur * (L->G + 1), m.size() * sizeof(uint32_t),
-                             hipMemcpyDeviceToHost));
-        const int g4 = L->max_4bit_ch / L->group_size;
-        for (int g = 0; g < g4; ++g) {
-            int hb = -1;
-            for (int b = 0; b < 7; ++b)
-                if (m[g] >> b & 1u) hb = b;
-            a32[g] = hb - 2 > 0 ? hb - 2 : 0;
-        }
-    }
     for (int g = 0; g < L->G; ++g) a_shift[g] = (uint8_t)a32[g];
     return FLEXIQ_OK;
 }
