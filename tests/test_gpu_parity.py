@@ -347,6 +347,54 @@ def test_producer_scans_for_consumer(env):
     assert seen_dynamic
 
 
+def test_producer_scan_graph_replay(env):
+    # The chain producer (scan for the consumer) -> consumer captured once in a HIP graph and replayed on changing
+    # inputs, with eager work and synchronisations in between: every replay must see positions scanned from ITS
+    # data (the scan scratch is cleaned by the kernel itself, nothing is frozen at capture time).
+    torch, oracle, fq, dev = env
+    M, K1, N1, N2, gs = 200, 128, 128, 64, 32
+    c1 = workloads.make_linear("gscan1", 8, 221, M, K1, N1, gs, outlier_frac=0.02)
+    c2 = workloads.make_linear("gscan2", 8, 222, M, N1, N2, gs, outlier_frac=0.02)
+    xs1, am1 = __import__("helpers").calib(c1)
+    o1 = oracle.prepare_layer(c1.W, am1, xs1, gs, bias=c1.bias)
+    Xq0 = oracle.quantize(c1.X, xs1)[:, o1.perm]
+    acc0 = oracle.forward_gemm(o1, Xq0, 0.5)
+    s_mid = float(np.abs(oracle.dequant_f64(acc0, xs1, o1.w_scale, o1.bias)).max() / 127.0)
+    am2 = np.full(N1, 127.0 * s_mid, np.float32)
+    o2 = oracle.prepare_layer(c2.W, am2, s_mid, gs, bias=c2.bias)
+    h2 = fq.flexiq_quantize_pack(c2.W, am2, s_mid, gs, bias=c2.bias)
+    h1 = fq.flexiq_quantize_pack(c1.W, am1, xs1, gs, bias=c1.bias, out_perm=o2.perm)
+    fq.flexiq_set_ratio(h1, 0.5)
+    fq.flexiq_set_ratio(h2, 1.0)
+    x_in = torch.empty((M, K1), dtype=torch.int8, device=dev)
+    bufs1 = {"q": torch.empty((M, N1), dtype=torch.int8, device=dev)}
+    bufs2 = {"acc": torch.empty((M, N2), dtype=torch.int32, device=dev)}
+
+    def chain():
+        fq.flexiq_mixed_gemm(h1, x_in, q=True, out_scale=s_mid, bufs=bufs1, scan_for=h2)
+        fq.flexiq_mixed_gemm(h2, bufs1["q"], acc=True, bufs=bufs2)
+
+    x_in.copy_(_dev(torch, Xq0, dev))
+    chain()                                   # warm-up outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        chain()
+    for div in (1, 3, 9, 2):                  # smaller and smaller activations, then larger again
+        Xq = (Xq0.astype(np.int32) // div).astype(np.int8)
+        x_in.copy_(_dev(torch, Xq, dev))
+        g.replay()
+        torch.cuda.synchronize()
+        acc1 = oracle.forward_gemm(o1, Xq, 0.5)
+        X2 = np.ascontiguousarray(oracle.requant_i8(acc1, xs1, o1.w_scale, s_mid, o1.bias)[:, o2.perm])
+        assert (bufs1["q"].cpu().numpy() == X2).all(), div
+        dyn = oracle.dynamic_act_shifts(X2, gs, o2.G, o2.a_shift)
+        assert (fq.flexiq_layer_positions(h2) == dyn).all(), div
+        want = oracle.mixed_gemm(X2, o2.Wq.reshape(N2, N1), gs, o2.G, dyn, o2.w_shift)
+        assert (bufs2["acc"].cpu().numpy() == want).all(), div
+        _ = (x_in.float().sum().item())        # eager work between replays
+
+
 def test_gemm_saturating_inputs(env):
     # activations far beyond the calibrated range: the clamp of the lowering is active everywhere
     torch, oracle, fq, dev = env
