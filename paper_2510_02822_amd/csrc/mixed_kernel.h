@@ -355,7 +355,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // activation positions of all groups: loaded into a register here, written to LDS after the prologue's tile
     // loads have been issued (one memory latency for all)
     static_assert(BN <= NT && 160 <= NT, "one table element per thread");
-    const int sa_v = tid <= p.G ? p.ashift[tid] : 0;
+    const bool need_tab = p.K4 > 0 && !p.x_pre;   // some K-step lowers activations in this kernel
+    const int sa_v = need_tab && tid <= p.G ? p.ashift[tid] : 0;
     int parity = 0;   // which copy of the scale / bias table belongs to the tile being computed
     // Scales and biases of the BN columns from column c0 on, straight into table copy `par` (no register hop, so
     // nothing has to wait for them here; the end-of-step waits of the K loop cover them before the epilogue).
@@ -594,10 +595,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         }
         plain_prologue = !PACKED4 && pmode[0] == kMode88 && pmode[1] == kMode88 && mode_staged == kMode88;
         FQ_TS(tqb);
-        if (tid <= p.G) reinterpret_cast<int *>(sa_tab)[tid] = sa_v;
-        if (p.next_scan && tid < 160) mask_tab[tid] = 0;
-        __builtin_amdgcn_s_waitcnt(0xc07f);
-        __builtin_amdgcn_s_barrier();   // position table visible
+        if (p.next_scan && tid < 160) mask_tab[tid] = 0;   // (first used in an epilogue, many barriers from here)
+        if (need_tab) {
+            if (tid <= p.G) reinterpret_cast<int *>(sa_tab)[tid] = sa_v;
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_s_barrier();   // position table visible
+        }
         FQ_TS(tqc);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
