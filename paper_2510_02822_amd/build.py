@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflexiq.so")
-NUM_TILE_SHAPES = 12
+NUM_TILE_SHAPES = 13
 # (source, object, extra flags): the kernel of every tile shape is a translation unit of its own
 UNITS = [("pack.hip", "pack.o", []), ("gemm.hip", "gemm.o", [])] + \
         [("mixed_tile.hip", "mixed_tile_%d.o" % i, ["-DFQ_TILE=%d" % i]) for i in range(NUM_TILE_SHAPES)]

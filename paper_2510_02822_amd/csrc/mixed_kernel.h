@@ -179,7 +179,13 @@ struct Cfg {
     static_assert((4 * (BN / 64)) % NW == 0, "weight copies divide evenly over the waves");
     static constexpr int WI = 4 * (BN / 64) / NW;       // direct weight loads per wave per K-step (4 planes x BN rows / 64 rows per copy)
     static constexpr int WL4 = (BN + NT - 1) / NT;      // packed-code pieces per thread per 4-bit unit
-    static constexpr int XBYTES = XROWS * 64;           // activation tile, row-major
+    // The last round of activation pieces may reach past the tile's BM rows.  Where the stage ring only fits into
+    // LDS without that excess, the stage holds exactly BM rows and the waves whose piece would lie beyond them
+    // skip it (TIGHT); everywhere else the excess rows are staged as zeros, which keeps every wave's loads alike.
+    static constexpr int kLooseLds = 4 * (XROWS * 64 + 4 * (BN + 2) * 16) + 640 + 2 * (3 * BN * 4) + 640;
+    static constexpr int kTightLds = 4 * (BM * 64 + 4 * (BN + 2) * 16) + 640 + 2 * (3 * BN * 4) + 640;
+    static constexpr bool TIGHT = kLooseLds > 160 * 1024 && kTightLds <= 160 * 1024;
+    static constexpr int XBYTES = (TIGHT ? BM : XROWS) * 64;   // activation tile, row-major
     static constexpr int WPS = (BN + 2) * 16;           // bytes per weight k-plane (+2 pieces staggers the planes over the banks)
     static constexpr int STAGE = XBYTES + 4 * WPS;
     static constexpr int NSTAGE = 4;
@@ -190,8 +196,10 @@ struct Cfg {
     static constexpr int RING = NSTAGE * STAGE;
     // A block may walk several output tiles.  Not for the largest tiles: their accumulators fill the register
     // file, and the values that would have to stay live across an epilogue do not fit beside them.
-    static constexpr bool MULTI = TM * TN <= 10;
+    static constexpr bool MULTI = TM * TN <= 10 && !(NW == 8 && TM * TN > 8);
     static constexpr int LDS_BYTES = RING + TABLE;
+    static_assert(LDS_BYTES == (TIGHT ? kTightLds : kLooseLds), "the size formulas agree");
+    static_assert(LDS_BYTES <= 160 * 1024, "fits the CU's LDS");
 };
 
 // How the two 32-channel units of a K-step are staged.
@@ -465,9 +473,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // Item i of the K-step the iterator points at: load it, either straight into `stage` or into registers.
     // (The K offset of an activation piece goes into the per-lane offset, which the buffer range check covers:
     // what the pad unit of an odd unit count would read past the end of the window's last row comes back as zero.)
+    constexpr int kTailRows = BM - (XI - 1) * 16 * NW;          // rows of the last round that belong to the tile
+    constexpr int kFullWaves = (kTailRows + 15) / 16;           // waves 0 .. kFullWaves-1 own a piece of the last round
+    static_assert(kTailRows > 0 && kTailRows % 16 == 0, "whole pieces");
+    auto has_piece = [&](int i) { return !C_::TIGHT || i < XI - 1 || kFullWaves >= NW || wave < kFullWaves; };
     auto gload = [&](v4i(&sr)[NSR > 0 ? NSR : 1], int(&wsh)[2][WL4], int i, int mode, unsigned char *stage) {
         const int c64 = it_c64;
         if (i < XI) {
+            if (!has_piece(i)) return;
             const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)xbase, 0, xwin, kRsrcFlags);
             int off;
             if (CONV) {
@@ -521,6 +534,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     uint32_t wexp[8];   // expanded weights of the packed piece in progress
     auto lmicro = [&](v4i(&sr)[NSR > 0 ? NSR : 1], int(&wsh)[2][WL4], int i, int k, int mode) {
         if (i < XI) {
+            if (!has_piece(i)) return;
             if (mode == kMode44) {
                 sr[i][k] = (int)lower4((uint32_t)sr[i][k], lo2, hi2, amask);
             } else if (mode == kMode48) {
@@ -542,6 +556,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     };
     auto lstore = [&](v4i(&sr)[NSR > 0 ? NSR : 1], int i, int mode, unsigned char *stage) {
         if (i < XI) {
+            if (!has_piece(i)) return;
             if (mode == kMode44 || mode == kMode48) *reinterpret_cast<v4i *>(stage + x_lds + i * (NW * 1024)) = sr[i];
         } else if (PACKED4 && i >= XI + WI) {
             const int h = (i - XI - WI) / WL4, j = (i - XI - WI) % WL4;
@@ -634,8 +649,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // K-steps 0 and 1 have landed (step 0 reads the first fragments of step 1 ahead).  Step 2 may stay in flight
     // when all three are plain copies: every wave then has the same number of loads outstanding, and the wait at
     // the end of step 0 covers it.
-    if (plain_prologue)
+    if (plain_prologue && has_piece(XI - 1))
         __builtin_amdgcn_s_waitcnt(0x0070 | ((XI + WI) & 15) | (((XI + WI) >> 4) << 14));
+    else if (plain_prologue)   // this wave issues one load less per K-step
+        __builtin_amdgcn_s_waitcnt(0x0070 | ((XI - 1 + WI) & 15) | (((XI - 1 + WI) >> 4) << 14));
     else
         __builtin_amdgcn_s_waitcnt(0x0070);
     __builtin_amdgcn_s_waitcnt(0xc07f);
@@ -745,10 +762,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
 #ifdef FLEXIQ_TIMING
         const long long tw0 = __builtin_readcyclecounter();
 #endif
-        if (!PACKED4 && (mb == kMode88 || mb == kMode44 || mb == kMode48))
-            __builtin_amdgcn_s_waitcnt(0x0070 | ((XI + WI) & 15) | (((XI + WI) >> 4) << 14));
-        else
+        if (!PACKED4 && (mb == kMode88 || mb == kMode44 || mb == kMode48)) {
+            if (has_piece(XI - 1))
+                __builtin_amdgcn_s_waitcnt(0x0070 | ((XI + WI) & 15) | (((XI + WI) >> 4) << 14));
+            else   // this wave issues one load less per K-step
+                __builtin_amdgcn_s_waitcnt(0x0070 | ((XI - 1 + WI) & 15) | (((XI - 1 + WI) >> 4) << 14));
+        } else {
             __builtin_amdgcn_s_waitcnt(0x0070);
+        }
 #ifdef FLEXIQ_TIMING
         const long long tw1 = __builtin_readcyclecounter();
 #endif
@@ -1068,7 +1089,7 @@ inline TileShape make_shape(double step_alone, double share, double epilogue)
 }
 
 // Shape i of the table, defined in mixed_tile.hip built with -DFQ_TILE=i.
-constexpr int kNumTileShapes = 12;
+constexpr int kNumTileShapes = 13;
 TileShape tile_shape_0();
 TileShape tile_shape_1();
 TileShape tile_shape_2();
@@ -1081,5 +1102,6 @@ TileShape tile_shape_8();
 TileShape tile_shape_9();
 TileShape tile_shape_10();
 TileShape tile_shape_11();
+TileShape tile_shape_12();
 
 }  // namespace flexiq

@@ -3,7 +3,7 @@
 #include "mixed_kernel.h"
 
 #ifndef FQ_TILE
-#error "compile with -DFQ_TILE=<0..11>"
+#error "compile with -DFQ_TILE=<0..12>"
 #endif
 
 namespace flexiq {
@@ -34,6 +34,8 @@ TileShape tile_shape_9() { return make_shape<2, 4, 3, 2>(945.0, 0.00, 4000.0); }
 TileShape tile_shape_10() { return make_shape<1, 8, 5, 1>(835.0, 0.00, 2900.0); }   // 160 x 256, eight waves
 #elif FQ_TILE == 11
 TileShape tile_shape_11() { return make_shape<1, 8, 7, 1>(1125.0, 0.00, 4800.0); }  // 224 x 256, eight waves
+#elif FQ_TILE == 12
+TileShape tile_shape_12() { return make_shape<2, 4, 5, 2>(1500.0, 0.0, 6000.0); }   // 320 x 256, eight waves
 #else
 #error "FQ_TILE out of range"
 #endif
