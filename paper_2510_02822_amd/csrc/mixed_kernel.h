@@ -819,6 +819,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     const int frag_half_e = lane >> 5, frag_row_e = lane & 31;
     // (one call handles fragment column a; the variant is chosen per column, which keeps the live ranges of the
     // accumulators short where the variants branch apart)
+    v4i qout[TN][TM];   // int8 output pieces of a tile (row-contiguous form), stored after the last fragment column
     auto epilogue = [&](auto a_, auto wq_, auto wy_, auto wa_, auto nv_, auto qr_, auto lw_, auto sc_) {
         const bool wq = wq_, wy = wy_, wa = wa_, nv = nv_, qr = qr_, lw = lw_, sc = sc_;
         constexpr int a = decltype(a_)::value;
@@ -930,15 +931,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
             if (wq && qr) {
                 // The two halves of the wave hold alternating 4-byte pieces of a row.  Exchanging quads 0 <-> 2
                 // and 1 <-> 3 between the halves leaves lanes 0..31 with channels 0..15 of the fragment's 32 and
-                // lanes 32..63 with channels 16..31: one 16-byte store per lane.
+                // lanes 32..63 with channels 16..31: one 16-byte store per lane.  With several fragment columns per
+                // wave the pieces are kept until all columns are done, so that the 32-byte halves of a row's
+                // contiguous run leave together (stored column by column, a third of the lines left L2 half written).
 #pragma unroll
                 for (int b = 0; b < TM; ++b) {
                     const auto s02 = __builtin_amdgcn_permlane32_swap(qrow[b][0], qrow[b][2], false, false);
                     const auto s13 = __builtin_amdgcn_permlane32_swap(qrow[b][1], qrow[b][3], false, false);
-                    const int64_t m = m0 + (wm * TM + b) * 32 + frag_row_e;
-                    const int n = n0 + (wn * TN + a) * 32 + 16 * frag_half_e;
-                    if (m < p.M && n < p.N)
-                        *reinterpret_cast<v4i *>(p.q + m * p.N + n) = (v4i){(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+                    const v4i piece = (v4i){(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+                    if (TN > 1) {
+                        qout[a][b] = piece;
+                    } else {
+                        const int64_t m = m0 + (wm * TM + b) * 32 + frag_row_e;
+                        const int n = n0 + (wn * TN + a) * 32 + 16 * frag_half_e;
+                        if (m < p.M && n < p.N) *reinterpret_cast<v4i *>(p.q + m * p.N + n) = piece;
+                    }
                 }
             }
         }
@@ -996,6 +1003,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         if constexpr (TN > 2) epilogue_col(std::integral_constant<int, 2>{});
         if constexpr (TN > 3) epilogue_col(std::integral_constant<int, 3>{});
         static_assert(TN <= 4, "epilogue handles up to four fragment columns");
+        if (TN > 1 && q_rows) {
+#pragma unroll
+            for (int b = 0; b < TM; ++b)
+#pragma unroll
+                for (int a = 0; a < TN; ++a) {
+                    const int64_t m = m0 + (wm * TM + b) * 32 + frag_row_e;
+                    const int n = n0 + (wn * TN + a) * 32 + 16 * frag_half_e;
+                    if (m < p.M && n < p.N) *reinterpret_cast<v4i *>(p.q + m * p.N + n) = qout[a][b];
+                }
+        }
 #ifdef FLEXIQ_TIMING
         t_epi += __builtin_readcyclecounter() - te0;
         ++n_tiles;
