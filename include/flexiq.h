@@ -177,7 +177,7 @@ typedef struct {
  * The activations are bit-lowered on the fly inside the kernel, at the handle's current positions (calibrated, or
  * those of the last flexiq_dynamic_positions scan); the weights of 4-bit groups are read from the handle's cached
  * lowered copies.  Layer must be linear (R = S = 1).  Launches on `stream`; allocates nothing; returns before the
- * kernel has run.  Errors: FLEXIQ_EINVAL (null / inconsistent arguments, M >= 2^31 - 256, more than 159 channel
+ * kernel has run.  Errors: FLEXIQ_EINVAL (null / inconsistent arguments, M >= 2^31 - 512, more than 159 channel
  * groups, a padded weight matrix of 1 GiB or more, current device is not the handle's), FLEXIQ_EALIGN, FLEXIQ_EHIP. */
 int flexiq_mixed_gemm(const flexiq_layer *layer, const int8_t *X, int64_t M, const flexiq_out *out, void *stream);
 
@@ -185,7 +185,7 @@ int flexiq_mixed_gemm(const flexiq_layer *layer, const int8_t *X, int64_t M, con
  * X: dev int8 NHWC [B][H][W][C], stored channel order, zero padding `pad`, stride `stride`;
  * outputs are [B][Ho][Wo][N] with Ho = (H + 2*pad - R)/stride + 1 (likewise Wo).
  * The channel groups, a_shift and the 4-bit prefix are the same for every tap.
- * Further limit: H*W*C * (256 / (Ho*Wo) + 2) must be below 2^31 bytes (a block reads its images through a 2 GiB window). */
+ * Further limit: H*W*C * (320 / (Ho*Wo) + 2) must be below 2^31 bytes (a block reads its images through a 2 GiB window). */
 int flexiq_mixed_conv_implicit(const flexiq_layer *layer, const int8_t *X, int32_t B, int32_t H, int32_t W,
                                int32_t stride, int32_t pad, const flexiq_out *out, void *stream);
 

@@ -136,7 +136,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
         if (dev != L->device) return FLEXIQ_EINVAL;
     }
     if (L->G + 1 > 160) return FLEXIQ_EINVAL;  // position table kept in LDS
-    if (M > 0x7fffffff - 256) return FLEXIQ_EINVAL;  // row indices are 32-bit in the kernel
+    if (M > 0x7fffffff - 512) return FLEXIQ_EINVAL;  // row indices are 32-bit in the kernel
     if (L->C / kUnit >= 2 * 65535) return FLEXIQ_EINVAL;  // K-step indices are kept in 16-bit fields
     if ((int64_t)L->U * 32 * L->Npad * 2 > 0x7fffffff) return FLEXIQ_EINVAL;  // both int8 weight copies must fit one buffer descriptor
     p.H = H; p.Wd = Wd; p.Ho = Ho; p.Wo = Wo; p.S = L->S; p.stride = stride; p.pad = pad;
@@ -244,8 +244,8 @@ extern "C" int flexiq_mixed_conv_implicit(const flexiq_layer *L, const int8_t *X
     const int64_t M = (int64_t)B * Ho * Wo;
     if (M == 0) return FLEXIQ_OK;  // empty batch
     // A block addresses its input through a 2 GiB window that starts at the first image it touches; the images
-    // of the tallest tile (256 output rows) must fit in it.
-    if ((int64_t)H * W * L->C * (256 / ((int64_t)Ho * Wo) + 2) > 0x7fffffff) return FLEXIQ_EINVAL;
+    // of the tallest tile (320 output rows) must fit in it.
+    if ((int64_t)H * W * L->C * (320 / ((int64_t)Ho * Wo) + 2) > 0x7fffffff) return FLEXIQ_EINVAL;
     int rc = check_out(out);
     if (rc) return rc;
     if (!X) return FLEXIQ_EINVAL;
