@@ -67,7 +67,7 @@ static int resident_blocks(kernel_fn fn, int threads, int lds)
 
 // Pick the tile shape with the smallest modelled time on the busiest CU: the tiles that CU has to compute, how
 // many of them run side by side, and per tile the K-steps (slower when the CU is shared) plus the epilogue.
-static int choose_shape(int64_t M, int N, int steps, bool conv, bool packed)
+static int choose_shape(int64_t M, int N, int steps, bool conv, bool packed, double lowered_frac)
 {
     int cnt;
     const TileShape *tab = shapes(&cnt);
@@ -82,7 +82,7 @@ static int choose_shape(int64_t M, int N, int steps, bool conv, bool packed)
         const double tiles_cu = __builtin_ceil(tiles / ncu);
         const double conc = tiles_cu < occ ? tiles_cu : occ;
         const double seq = __builtin_ceil(tiles_cu / conc);
-        const double step = tab[i].step_alone * (1.0 + tab[i].share * (conc - 1.0));
+        const double step = (tab[i].step_alone + lowered_frac * tab[i].lower) * (1.0 + tab[i].share * (conc - 1.0));
         const double prologue = 7000.0;
         const bool walks = tab[i].multi;   // prologue paid once per block
         const double cost = walks ? prologue + seq * (steps * step + tab[i].epilogue)
@@ -144,7 +144,9 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     // (activations that arrive lowered always pair with the expanded weight copy)
     const bool packed = !L->x_prelowered && (g_force_packed >= 0 ? g_force_packed != 0 : M <= kPackedMaxRows);
     int cnt;
-    g_last_shape = choose_shape(M, L->N, steps, conv, packed);
+    // share of the K-steps whose activations the kernel lowers (none when they arrive lowered)
+    const double lowered_frac = L->x_prelowered ? 0.0 : (double)L->max_4bit_ch / (double)L->C;
+    g_last_shape = choose_shape(M, L->N, steps, conv, packed, lowered_frac);
     const TileShape &ts = shapes(&cnt)[g_last_shape];
     p.tiles_m = (int)((M + ts.BM - 1) / ts.BM);
     p.tiles_n = (L->N + ts.BN - 1) / ts.BN;

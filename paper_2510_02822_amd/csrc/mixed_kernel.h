@@ -1093,14 +1093,15 @@ struct TileShape {
     double step_alone;   // one K-step of a block that has its CU to itself
     double share;        // relative growth of that time per further block resident on the same CU
     double epilogue;     // epilogue of one output tile
+    double lower;        // growth of a K-step whose activations are bit-lowered in the kernel
     kernel_fn fn[2][2];  // [convolution][4-bit weights from the packed codes]
 };
 
 template <int WAVES_M, int WAVES_N, int TM, int TN>
-inline TileShape make_shape(double step_alone, double share, double epilogue)
+inline TileShape make_shape(double step_alone, double share, double epilogue, double lower)
 {
     using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
-    return TileShape{C_::BM, C_::BN, C_::NT, C_::LDS_BYTES, C_::MULTI, step_alone, share, epilogue,
+    return TileShape{C_::BM, C_::BN, C_::NT, C_::LDS_BYTES, C_::MULTI, step_alone, share, epilogue, lower,
                      {{k_mixed<WAVES_M, WAVES_N, TM, TN, false, false>, k_mixed<WAVES_M, WAVES_N, TM, TN, false, true>},
                       {k_mixed<WAVES_M, WAVES_N, TM, TN, true, false>, k_mixed<WAVES_M, WAVES_N, TM, TN, true, true>}}};
 }
