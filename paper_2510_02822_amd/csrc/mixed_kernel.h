@@ -1080,6 +1080,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
             d[4] = (int)t_wait0; d[5] = (int)t_wait_vm; d[6] = (int)t_wait_bar; d[7] = n_tiles;
             int *e = p.acc + (int64_t)gridDim.x * NW * 8 + ((int64_t)blockIdx.x * NW + wave) * 32;
             for (int i = 0; i < 32; ++i) e[i] = (int)t_at[wave][i >> 4][i & 15];
+            // prologue stamps (slots past the last K-step of the second row: free when a tile has at most 12 steps)
+            e[28] = (int)(tqa - tq0); e[29] = (int)(tqb - tq0); e[30] = (int)(tqc - tq0); e[31] = (int)(tqd - tq0);
         }
     }
 #endif
