@@ -587,48 +587,89 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // steps 0 and 1 go to LDS.
     int mode_staged = kModeNone;   // mode of K-step s+2, whose register-routed pieces sit in the staging registers
     bool plain_prologue;           // K-steps 0, 1 and 2 all exist and are plain copies into LDS
+    // K-steps 0, 1 and 2 all exist and all lower their activations: same code with the mode known at compile time,
+    // so that the waits for the staging registers are exact and the pieces of step 0 are lowered while the loads
+    // of steps 1 and 2 are still in flight (with a run-time mode those waits cover every load issued so far)
+    const bool lowering_prologue = !PACKED4 && it_mode == kMode44 && it_c64 + 2 < it_pe;
     {
         v4i sp[2][NSR > 0 ? NSR : 1];
         int wp[2][2][WL4];
         int pmode[2] = {kModeNone, kModeNone}, pc64[2] = {0, 0};
+        auto publish_tables = [&]() {
+            if (p.next_scan && tid < 160) mask_tab[tid] = 0;   // (first used in an epilogue, many barriers from here)
+            if (need_tab) {
+                if (tid <= p.G) reinterpret_cast<int *>(sa_tab)[tid] = sa_v;
+                __builtin_amdgcn_s_waitcnt(0xc07f);
+                __builtin_amdgcn_s_barrier();   // position table visible
+            }
+        };
+        if (lowering_prologue) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            if (it_mode != kModeNone) {   // the block has a K-step t (of its first tile, or of a following one when K is short)
-                pmode[t] = it_mode;
+            for (int t = 0; t < 2; ++t) {
                 pc64[t] = it_c64;
 #pragma unroll
-                for (int i = 0; i < NI; ++i) gload(sp[t], wp[t], i, pmode[t], lds + t * STAGE);
+                for (int i = 0; i < NI; ++i) gload(sp[t], wp[t], i, kMode44, lds + t * STAGE);
                 advance();
             }
-        }
-        if (it_mode != kModeNone) {
-            mode_staged = it_mode;
+            mode_staged = kMode44;
             st_c64 = it_c64;
 #pragma unroll
-            for (int i = 0; i < NI; ++i) gload(sr, wsh, i, mode_staged, lds + 2 * STAGE);
+            for (int i = 0; i < NI; ++i) gload(sr, wsh, i, kMode44, lds + 2 * STAGE);
             advance();
-        }
-        plain_prologue = !PACKED4 && pmode[0] == kMode88 && pmode[1] == kMode88 && mode_staged == kMode88;
-        FQ_TS(tqb);
-        if (p.next_scan && tid < 160) mask_tab[tid] = 0;   // (first used in an epilogue, many barriers from here)
-        if (need_tab) {
-            if (tid <= p.G) reinterpret_cast<int *>(sa_tab)[tid] = sa_v;
-            __builtin_amdgcn_s_waitcnt(0xc07f);
-            __builtin_amdgcn_s_barrier();   // position table visible
-        }
-        FQ_TS(tqc);
+            plain_prologue = false;
+            FQ_TS(tqb);
+            publish_tables();
+            FQ_TS(tqc);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            if (pmode[t] != kModeNone) {
-                if (pmode[t] != kMode88) {
-                    sa_fetch(pc64[t]);
-                    lower_setup();
-                }
+            for (int t = 0; t < 2; ++t) {
+                sa_fetch(pc64[t]);
+                lower_setup();
 #pragma unroll
                 for (int i = 0; i < NI; ++i) {
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) lmicro(sp[t], wp[t], i, k, pmode[t]);
-                    lstore(sp[t], i, pmode[t], lds + t * STAGE);
+                    for (int k = 0; k < 4; ++k) lmicro(sp[t], wp[t], i, k, kMode44);
+                    lstore(sp[t], i, kMode44, lds + t * STAGE);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                if (it_mode != kModeNone) {   // the block has a K-step t (of its first tile, or of a following one when K is short)
+                    pmode[t] = it_mode;
+                    pc64[t] = it_c64;
+#pragma unroll
+                    for (int i = 0; i < NI; ++i) gload(sp[t], wp[t], i, pmode[t], lds + t * STAGE);
+                    advance();
+                }
+            }
+            if (it_mode != kModeNone) {
+                mode_staged = it_mode;
+                st_c64 = it_c64;
+#pragma unroll
+                for (int i = 0; i < NI; ++i) gload(sr, wsh, i, mode_staged, lds + 2 * STAGE);
+                advance();
+            }
+            plain_prologue = !PACKED4 && pmode[0] == kMode88 && pmode[1] == kMode88 && mode_staged == kMode88;
+            FQ_TS(tqb);
+            publish_tables();
+            FQ_TS(tqc);
+            // (nothing to do when all three steps are plain copies; the branch also keeps the wait for the staging
+            // registers, which covers every load issued so far, out of that path)
+            if (!plain_prologue) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    if (pmode[t] != kModeNone) {
+                        if (pmode[t] != kMode88) {
+                            sa_fetch(pc64[t]);
+                            lower_setup();
+                        }
+#pragma unroll
+                        for (int i = 0; i < NI; ++i) {
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) lmicro(sp[t], wp[t], i, k, pmode[t]);
+                            lstore(sp[t], i, pmode[t], lds + t * STAGE);
+                        }
+                    }
                 }
             }
         }
@@ -649,9 +690,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // K-steps 0 and 1 have landed (step 0 reads the first fragments of step 1 ahead).  Step 2 may stay in flight
     // when all three are plain copies: every wave then has the same number of loads outstanding, and the wait at
     // the end of step 0 covers it.
-    if (plain_prologue && has_piece(XI - 1))
+    if ((plain_prologue || lowering_prologue) && has_piece(XI - 1))
         __builtin_amdgcn_s_waitcnt(0x0070 | ((XI + WI) & 15) | (((XI + WI) >> 4) << 14));
-    else if (plain_prologue)   // this wave issues one load less per K-step
+    else if (plain_prologue || lowering_prologue)   // this wave issues one load less per K-step
         __builtin_amdgcn_s_waitcnt(0x0070 | ((XI - 1 + WI) & 15) | (((XI - 1 + WI) >> 4) << 14));
     else
         __builtin_amdgcn_s_waitcnt(0x0070);
