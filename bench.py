@@ -36,8 +36,8 @@ RATIOS = (0.0, 0.25, 0.5, 0.75, 1.0)
 
 # Bytes per launch of the GEMM kernel on the default workload (fc1, int8 output) measured with
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the readings of a 256 MiB device copy (fetch x2.0,
-# write x1.0): median fetch 25.3 MB + write 19.8 MB.  See profiles/k_mixed_vitb_fc1_hbm_traffic.txt.
-MEASURED_TRAFFIC_BYTES = {("fc1", "q"): 45.3e6}
+# write x1.0): median fetch 25.8 MB + write 19.4 MB.  See profiles/k_mixed_vitb_fc1_hbm_traffic.txt.
+MEASURED_TRAFFIC_BYTES = {("fc1", "q"): 45.2e6}
 
 
 def log(*a):

@@ -146,7 +146,9 @@ def prepare_conv(torch, fq, dev, case):
 def conv_bytes(case, r):
     M = case.B * case.Ho * case.Wo
     K = case.R * case.S * case.C
-    return case.B * case.H * case.Wd * case.C + case.N * K * (1.0 - r / 2.0) + M * case.N
+    # a 1x1 filter with a stride reads only the pixels it lands on
+    pixels = case.Ho * case.Wo if case.R == 1 and case.S == 1 else case.H * case.Wd
+    return case.B * pixels * case.C + case.N * K * (1.0 - r / 2.0) + M * case.N
 
 
 def section_conv(torch, fq, workloads, dev):

@@ -241,7 +241,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     __builtin_assume(wave >= 0 && wave < NW);
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 #ifdef FLEXIQ_TIMING
-    long long tq0 = __builtin_readcyclecounter(), tqa = 0, tqb = 0, tqc = 0, tqd = 0;
+    long long tq0 = __builtin_readcyclecounter(), tqa = 0, tqb = 0, tqc = 0, tqd = 0, tqe = 0;
 #endif
 
     // ---- tile index -> tile.  A block computes the tiles blockIdx.x, blockIdx.x + gridDim.x, ... one after
@@ -585,6 +585,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // stages 0, 1, 2; the register-routed pieces of steps 0 and 1 into registers of their own, those of
     // step 2 into the staging registers of the main loop); then the tables and the register-routed pieces of
     // steps 0 and 1 go to LDS.
+    FQ_TS(tqe);
     int mode_staged = kModeNone;   // mode of K-step s+2, whose register-routed pieces sit in the staging registers
     bool plain_prologue;           // K-steps 0, 1 and 2 all exist and are plain copies into LDS
     // K-steps 0, 1 and 2 all exist and all lower their activations: same code with the mode known at compile time,
@@ -1122,7 +1123,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
             int *e = p.acc + (int64_t)gridDim.x * NW * 8 + ((int64_t)blockIdx.x * NW + wave) * 32;
             for (int i = 0; i < 32; ++i) e[i] = (int)t_at[wave][i >> 4][i & 15];
             // prologue stamps (slots past the last K-step of the second row: free when a tile has at most 12 steps)
-            e[28] = (int)(tqa - tq0); e[29] = (int)(tqb - tq0); e[30] = (int)(tqc - tq0); e[31] = (int)(tqd - tq0);
+            e[27] = (int)(tqe - tq0); e[28] = (int)(tqa - tq0); e[29] = (int)(tqb - tq0); e[30] = (int)(tqc - tq0); e[31] = (int)(tqd - tq0);
         }
     }
 #endif
