@@ -744,6 +744,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
 #pragma unroll
                 for (int a = 0; a < TN; ++a) {
                     const int slot = b * TN + a, g = kh * NMF + slot;
+                    // Two waves share a SIMD's matrix pipe in the eight-wave shapes, and the arbiter prefers the
+                    // older one: it would run ahead and then idle at the barrier (measured: 600 of a step's 1800
+                    // cycles) while the younger one finishes alone, too slow to keep the pipe full.  A wave's
+                    // priority therefore falls as it advances (one level per quarter of the step, up again for the
+                    // last MFMAs and the step boundary), so whichever is behind wins.  Measured: 3-5 % at r = 1 and
+                    // 1 % at r = 0 with twenty MFMAs per wave and step, nothing with ten to fourteen; several other
+                    // patterns (a level per eighth, wrapping) measured the same within 0.5 %.
+                    if (NW == 8 && NMF >= 10) {
+                        constexpr int kEighth = 2 * NMF / 8;
+                        const int level = g < 8 * kEighth ? 3 - g / (2 * kEighth) : (g < 9 * kEighth ? 0 : 2);
+                        if (g % kEighth == 0) {
+                            if (level == 3) __builtin_amdgcn_s_setprio(3);
+                            else if (level == 2) __builtin_amdgcn_s_setprio(2);
+                            else if (level == 1) __builtin_amdgcn_s_setprio(1);
+                            else __builtin_amdgcn_s_setprio(0);
+                        }
+                    }
                     if (kh == 0) acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fA[a], fA[TN + b], acc[a][b], 0, 0, 0);
                     else acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fB[a], fB[TN + b], acc[a][b], 0, 0, 0);
                     FQ_SB();
