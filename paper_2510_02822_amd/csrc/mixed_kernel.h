@@ -369,6 +369,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // Scales and biases of the BN columns from column c0 on, straight into table copy `par` (no register hop, so
     // nothing has to wait for them here; the end-of-step waits of the K loop cover them before the epilogue).
     // cs/bias are padded to Npad >= c0 + BN.
+    // Shapes whose blocks compute a single tile turn the table entries into the requantisation multiplier and addend
+    // (c * r_out, bias * r_out + 128) once per column when int8 is the only scaled output, instead of once per lane
+    // and quad in the epilogue: each thread rewrites the entries its own wave loaded, after the prologue's wait.
+    constexpr bool kScaleOnce = !C_::MULTI;
+    const bool pre_scaled = kScaleOnce && p.q != nullptr && p.y == nullptr;
     auto fetch_scales = [&](int c0, int par) {
         if (wave * 64 < BN) {
             float *dst = cs_tab + par * (3 * BN) + wave * 64;
@@ -701,6 +706,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int i = 0; i < NF; ++i) fread(fA, i, lds, 0);
+    // (the scale loads were issued before every tile load, so they have landed too; the table is first read in the
+    // epilogue, at least one barrier from here)
+    if (pre_scaled && wave * 64 < BN) {
+        float *own = cs_tab + wave * 64 + lane;
+        const float c = own[0], b = own[BN];
+        own[0] = c * p.r_out;
+        own[BN] = b * p.r_out + 128.0f;
+    }
 
 #ifdef FLEXIQ_TIMING
     long long tq1 = __builtin_readcyclecounter(), t_epi = 0, t_wait_vm = 0, t_wait_bar = 0, t_wait0 = 0;
@@ -881,6 +894,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     v4i qout[TN][TM];   // int8 output pieces of a tile (row-contiguous form), stored after the last fragment column
     auto epilogue = [&](auto a_, auto wq_, auto wy_, auto wa_, auto nv_, auto qr_, auto lw_, auto sc_) {
         const bool wq = wq_, wy = wy_, wa = wa_, nv = nv_, qr = qr_, lw = lw_, sc = sc_;
+        // the table holds multiplier and addend already: known at compile time in the int8-only variants
+        const bool pre = (std::is_same<decltype(wq_), std::true_type>::value && std::is_same<decltype(wy_), std::false_type>::value)
+                             ? kScaleOnce : pre_scaled;
         constexpr int a = decltype(a_)::value;
         const float *tab = cs_tab + parity * (3 * BN);
         {
@@ -914,8 +930,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                 if (wq) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        mul[i] = csv[i] * p.r_out;
-                        add[i] = biv[i] * p.r_out + 128.0f;
+                        mul[i] = pre ? csv[i] : csv[i] * p.r_out;
+                        add[i] = pre ? biv[i] : biv[i] * p.r_out + 128.0f;
                     }
                     // Output lowered for the consumer (its 4-bit channels only): L(v, s) << s = clamp(v, -(8<<s),
                     // (8<<s)-1) with the low s bits cleared; the four columns of a quad share a channel group.
