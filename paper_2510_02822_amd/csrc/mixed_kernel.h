@@ -691,7 +691,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
     };
-    zero_acc();
+    // (see the K loop: a tile that begins with lowering steps clears no accumulators)
+    constexpr bool kZeroStep = TM * TN <= 10;   // (the 16-fragment shape has no registers to spare for the extra variant)
+    bool zero_step = kZeroStep && mode_staged == kMode44 && it_mode == kMode44;
+    if (!zero_step) zero_acc();
 
     // K-steps 0 and 1 have landed (step 0 reads the first fragments of step 1 ahead).  Step 2 may stay in flight
     // when all three are plain copies: every wave then has the same number of loads outstanding, and the wait at
@@ -740,9 +743,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
             if (NMF + k * NMF / NF > kStageSlots - 1) ++n;
         return n < 15 ? n : 15;
     }();
-    auto step = [&](auto ma_, auto mb_, auto h1_) {
+    auto step = [&](auto ma_, auto mb_, auto h1_, auto z_) {
         const int ma = ma_, mb = mb_;
         const bool h1 = h1_;
+        const bool z = z_;   // first K-step of an output tile: the MFMAs of its first k-half start from zero
         const unsigned char *cur = lds + o_cur;
         const unsigned char *nx1 = lds + o_nx1;
         unsigned char *nx2 = lds + o_nx2;
@@ -766,15 +770,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                     // patterns (a level per eighth, wrapping) measured the same within 0.5 %.
                     if (NW == 8 && NMF >= 10) {
                         constexpr int kEighth = 2 * NMF / 8;
-                        const int level = g < 8 * kEighth ? 3 - g / (2 * kEighth) : (g < 9 * kEighth ? 0 : 2);
-                        if (g % kEighth == 0) {
+                        auto level_at = [](int x) { return x < 8 * kEighth ? 3 - x / (2 * kEighth) : (x < 9 * kEighth ? 0 : 2); };
+                        const int level = level_at(g);
+                        if (g == 0 || level != level_at(g - 1)) {
                             if (level == 3) __builtin_amdgcn_s_setprio(3);
                             else if (level == 2) __builtin_amdgcn_s_setprio(2);
                             else if (level == 1) __builtin_amdgcn_s_setprio(1);
                             else __builtin_amdgcn_s_setprio(0);
                         }
                     }
-                    if (kh == 0) acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fA[a], fA[TN + b], acc[a][b], 0, 0, 0);
+                    if (kh == 0) acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fA[a], fA[TN + b], z ? v16i{} : acc[a][b], 0, 0, 0);
                     else acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fB[a], fB[TN + b], acc[a][b], 0, 0, 0);
                     FQ_SB();
                     // fragment read k of the other register set at slot k*NMF/NF of this k-half
@@ -1044,21 +1049,25 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         // Nothing in flight (in particular none of the previous epilogue's stores) when the K loop starts: the
         // compiler can then count the register-routed loads of the 4-bit loops exactly.
         if ((n4 + mixed > 0 && !p.x_pre) || PACKED4) __builtin_amdgcn_s_waitcnt(0x0070);
+        // When the tile begins with steps that lower their activations, the first K-step starts its accumulators
+        // from a zero operand: clearing 16 registers per fragment with the vector ALU would compete with the
+        // prologue's lowering work (with plain copies the clearing hides behind the wait for the first loads).
+        if (zero_step) step(M44{}, M44{}, T_{}, T_{});
         while (s < steps) {
             if (mode_staged == kMode44 && it_mode == kMode44)
-                do step(M44{}, M44{}, T_{}); while (s < steps && it_mode == kMode44);
-            if (s < steps && mode_staged == kMode44 && it_mode == kMode88) step(M44{}, M88{}, T_{});
+                do step(M44{}, M44{}, T_{}, F_{}); while (s < steps && it_mode == kMode44);
+            if (s < steps && mode_staged == kMode44 && it_mode == kMode88) step(M44{}, M88{}, T_{}, F_{});
             if (s < steps && mode_staged == kMode88 && it_mode == kMode88)
-                do step(M88{}, M88{}, T_{}); while (s < steps && it_mode == kMode88);
-            if (s < steps && mode_staged == kMode88 && it_mode == kMode44) step(M88{}, M44{}, T_{});   // next tile begins
+                do step(M88{}, M88{}, T_{}, F_{}); while (s < steps && it_mode == kMode88);
+            if (s < steps && mode_staged == kMode88 && it_mode == kMode44) step(M88{}, M44{}, T_{}, F_{});   // next tile begins
             while (s < steps && mode_staged != kModeNone && it_mode != kModeNone && (mode_staged == kMode48 || it_mode == kMode48))
-                step(mode_staged, it_mode, true);                                                      // mixed steps
-            if (s < steps && mode_staged == kMode88 && it_mode == kModeNone) step(M88{}, MNone{}, T_{});
-            if (s < steps && mode_staged == kMode44 && it_mode == kModeNone) step(M44{}, MNone{}, T_{});
-            if (s < steps && mode_staged == kMode48 && it_mode == kModeNone) step(mode_staged, (int)kModeNone, true);
+                step(mode_staged, it_mode, true, F_{});                                                      // mixed steps
+            if (s < steps && mode_staged == kMode88 && it_mode == kModeNone) step(M88{}, MNone{}, T_{}, F_{});
+            if (s < steps && mode_staged == kMode44 && it_mode == kModeNone) step(M44{}, MNone{}, T_{}, F_{});
+            if (s < steps && mode_staged == kMode48 && it_mode == kModeNone) step(mode_staged, (int)kModeNone, true, F_{});
             // nothing left to stage; the block's very last step reads no fragments ahead
-            while (s < steps && mode_staged == kModeNone && (more_tiles || s + 1 < steps)) step(MNone{}, MNone{}, T_{});
-            if (s < steps && mode_staged == kModeNone && !more_tiles && s + 1 >= steps) step(MNone{}, MNone{}, F_{});
+            while (s < steps && mode_staged == kModeNone && (more_tiles || s + 1 < steps)) step(MNone{}, MNone{}, T_{}, F_{});
+            if (s < steps && mode_staged == kModeNone && !more_tiles && s + 1 >= steps) step(MNone{}, MNone{}, F_{}, F_{});
         }
 
 #ifdef FLEXIQ_TIMING
@@ -1104,7 +1113,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         }
         parity ^= 1;                           // the other table copy was last read two epilogues ago
         fetch_scales(n0, parity);
-        zero_acc();
+        zero_step = kZeroStep && mode_staged == kMode44 && it_mode == kMode44;
+        if (!zero_step) zero_acc();
         s = 0;
 #ifdef FLEXIQ_TIMING
         FQ_SB();
