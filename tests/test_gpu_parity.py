@@ -278,6 +278,15 @@ def test_two_layer_chain_static_reorder(env):
         assert all(oracle.bitlower(int(X2[i, j]), int(sh[0, j])) << int(sh[0, j]) == want_mid[i, j]
                    for i in (0, 7, 299) for j in range(0, k4, 5))
         assert (mid_l.cpu().numpy().astype(np.int32) == want_mid).all(), r2b
+        if r2b == 0.75:   # every tile shape of the producer lowers alike
+            n_tiles = fq.debug_force_tile(-1)
+            try:
+                for t in range(n_tiles):
+                    fq.debug_force_tile(t)
+                    got_t = fq.flexiq_mixed_gemm(h1, _dev(torch, Xq, dev), q=True, out_scale=s_mid, lower_for=h2)["q"]
+                    assert (got_t.cpu().numpy().astype(np.int32) == want_mid).all(), t
+            finally:
+                fq.debug_force_tile(-1)
         fq.flexiq_input_prelowered(h2, True)
         got = fq.flexiq_mixed_gemm(h2, mid_l, acc=True)["acc"].cpu().numpy()
         fq.flexiq_input_prelowered(h2, False)
