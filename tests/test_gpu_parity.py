@@ -500,6 +500,11 @@ def test_conv_all_tiles(env):
                     fq.debug_force_packed4(packed)
                     got = fq.flexiq_mixed_conv_implicit(hl, Xd, 1, 1, acc=True)["acc"].cpu().numpy()
                     assert (got == ref).all(), (t, r, packed)
+                # int8 as the only output (NHWC in, NHWC out)
+                so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
+                fq.debug_force_packed4(0)
+                q = fq.flexiq_mixed_conv_implicit(hl, Xd, 1, 1, q=True, out_scale=so)["q"].cpu().numpy()
+                assert (q == oracle.requant_i8(ref, x_scale, ol.w_scale, so, ol.bias)).all(), (t, r)
     finally:
         fq.debug_force_tile(-1)
         fq.debug_force_packed4(-1)
