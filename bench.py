@@ -12,7 +12,8 @@ order, positions, packing) run once before it, as in the paper.
 
 Prints ONE JSON line.  `value` = total int8 ops of the K timed steps / wall time (TOPS).
 The default step and warm-up counts keep the GPU busy for a few tenths of a second: the card needs tens of
-milliseconds of work to settle at its running clocks, and a shorter timed region reads about 4 % low.
+milliseconds of work to settle at its running clocks, and a short timed region after a cold start reads about 4 %
+low; for the same reason about 50 ms of untimed steps run before the requested warm-up steps.
 `roofline` covers the GEMM kernel (the only kernel in the timed region): algorithmic ops per launch
 = 2*M*N*K, average launch duration = HIP-event time of the timed region / launches in it.  `cpu_baseline` times the CPU oracle on a bounded row sample of the same workload.
 """
@@ -119,6 +120,12 @@ def main():
     else:
         run_chunk = one_step
 
+    # Untimed: about 50 ms of the same steps, so that the card has settled at its running clocks whatever warm-up and
+    # step counts were asked for (a cold start reads about 4 % low), then the requested warm-up steps.
+    t_settle = time.perf_counter() + 0.05
+    while time.perf_counter() < t_settle:
+        run_chunk()
+    torch.cuda.synchronize()
     for _ in range(-(-args.warmup // chunk)):    # at least the requested warm-up steps
         run_chunk()
     torch.cuda.synchronize()
