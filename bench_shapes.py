@@ -13,7 +13,7 @@ Sections (`--what`, comma-separated, default all):
             from the seeded schedule, and the same pass at fixed ratios (the difference is the cost of switching)
 
 All inputs are seeded and synthetic (module `workloads`).  Launches are captured into HIP graphs (ten launches of a
-shape, or one whole pass) and the median of seven replays, after ten untimed ones, is reported.
+shape, or one whole pass) and the median of seven replays, after about 40 ms of untimed ones, is reported.
 """
 from __future__ import annotations
 
@@ -40,8 +40,9 @@ def emit(section, **kw):
     print(json.dumps({"section": section, **kw}), flush=True)
 
 
-def median_replay_us(torch, graph, launches, repeats=7, warm=10):
-    for _ in range(warm):      # clocks and caches settle over the first few hundred microseconds of work
+def median_replay_us(torch, graph, launches, repeats=7, settle_s=0.04):
+    t_end = time.perf_counter() + settle_s      # the card needs tens of milliseconds of work to reach its running clocks
+    while time.perf_counter() < t_end:
         graph.replay()
     torch.cuda.synchronize()
     ts = []
