@@ -68,7 +68,11 @@ typedef struct {
  * channel scores and order, channel groups, extraction positions a_shift[g] (from the calibration
  * ranges) and w_shift[n][g] (from the quantised weights, over all filter taps), permuted int8 weight
  * tiles and the packed 4-bit bit-lowered copy.  Runs HIP kernels on the current device and
- * synchronises; allocates device memory owned by the handle.  *out is set only on success. */
+ * synchronises; allocates device memory owned by the handle (FLEXIQ_ENOMEM when the device has none left).  Also
+ * prepares the GEMM kernels for the current device once (dynamic-LDS limits, occupancy), so that the run-time entry
+ * points only launch.  *out is set only on success.
+ * Limits, refused with FLEXIQ_EINVAL before any device work: more than 159 channel groups (C / group_size); a padded
+ * weight matrix (R*S*C rounded up to 64 per tap, times N rounded up to 256) of 1 GiB or more. */
 int flexiq_quantize_pack(const flexiq_pack_desc *desc, flexiq_layer **out);
 
 /* Releases the handle and its device memory.  NULL is accepted. */
@@ -83,7 +87,8 @@ int flexiq_layer_free(flexiq_layer *layer);
 int flexiq_layer_info(const flexiq_layer *layer, const int32_t **perm, const uint8_t **a_shift,
                       const uint8_t **w_shift, const float **w_scale, int32_t *G, int32_t *max_4bit_ch);
 
-/* Copies the handle's device buffers back for inspection (tests: "no repacking between calls").
+/* Test aid for Section 7, "Low-bitwidth Ratio Adjustment" (one stored copy serves every ratio, nothing is
+ * repacked between calls): copies the handle's device buffers back for inspection.
  *   w8 : host int8  [N][R*S][C]    permuted 8-bit weights, decoded from the tiled device layout
  *   w4 : host uint8 [N][R*S][C/2]  4-bit codes of ALL groups, channel c in byte c/2 (low half for even c)
  *   w4x: host int8  [N][R*S][C]    the copy of those codes that the matrix kernel streams for compute-bound
@@ -126,10 +131,12 @@ int flexiq_dynamic_positions(flexiq_layer *layer, const int8_t *X, int64_t rows,
  * switch, O(1); on != 0 enables.  The caller keeps producer and consumer settings consistent. */
 int flexiq_input_prelowered(flexiq_layer *layer, int on);
 
-/* Back to the calibrated positions of flexiq_quantize_pack (host-side switch, O(1)). */
+/* Back to the calibrated positions of flexiq_quantize_pack, the static option of Section 4.1 (positions assigned
+ * per feature channel group from calibration ranges).  Host-side switch, O(1). */
 int flexiq_static_positions(flexiq_layer *layer);
 
-/* Copies the activation positions that the next GEMM / conv call would use to the host (tests).
+/* Test aid for Section 4.1 (static and dynamic extraction positions): copies the activation positions that the
+ * next GEMM / conv call would use to the host.
  *   a_shift : host uint8 [G].  Synchronises the device. */
 int flexiq_layer_positions(const flexiq_layer *layer, uint8_t *a_shift);
 
@@ -150,7 +157,8 @@ int flexiq_permute_channels(const flexiq_layer *layer, const int8_t *src, int8_t
  *               channels of the consumer under ITS current ratio are then written bit-lowered at ITS current
  *               positions, L(v, s) << s (Section 4.1), in the same pass: the consumer, switched with
  *               flexiq_input_prelowered(consumer, 1), no longer lowers them itself.  Both settings of the consumer
- *               are read when this call is made.  NULL: plain int8 codes
+ *               are read when this call is made.  FLEXIQ_EINVAL unless this layer's out_perm equals the consumer's
+ *               stored channel order (compared by hash).  NULL: plain int8 codes
  *   scan_for  : optional, not together with lower_for.  The layer that will consume q (same conditions).  The
  *               run-time scan of flexiq_dynamic_positions (Section 4.1; Section 9 "Finding extraction positions at
  *               runtime") is done on q in the same pass: every block ORs the magnitude bits of the codes it writes

@@ -1,0 +1,35 @@
+/*
+ * flexiq_test.h -- test and tuning aids of libflexiq.  Not part of the method and not needed by a user of
+ * the library: the parity tests use them to force every code path of the GEMM kernel (each tile shape, each
+ * weight route, blocks that walk several output tiles) on inputs small enough for the CPU oracle.
+ *
+ * All four act on process-wide state that the launch path reads without synchronisation: call them only
+ * while no flexiq call is in flight on any thread, and reset them (-1 / 0) afterwards.
+ */
+#ifndef FLEXIQ_TEST_H
+#define FLEXIQ_TEST_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Force tile shape `index` of the kernel's shape table for every following GEMM / convolution call;
+ * -1 = automatic choice (the default).  Returns the number of shapes in the table, or FLEXIQ_EINVAL. */
+int flexiq_debug_force_tile(int index);
+
+/* Where the kernel takes the weights of 4-bit channel groups from: 1 = the packed 4-bit codes (expanded in
+ * registers), 0 = the position-expanded int8 copy, -1 = automatic (the default). */
+int flexiq_debug_force_packed4(int mode);
+
+/* Blocks launched by a GEMM / convolution call whose tile shape lets a block walk several output tiles:
+ * 0 = automatic (one resident wave of blocks; the default), n > 0 = at most n blocks, n < 0 = one block per tile. */
+int flexiq_debug_max_blocks(int n);
+
+/* What the last GEMM / convolution launch used.  which = 0: tile shape index, 1: blocks launched,
+ * 2: blocks of that kernel resident per compute unit, 3: split-K slices (1 = the tiled kernel). */
+int flexiq_debug_last_launch(int which);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXIQ_TEST_H */

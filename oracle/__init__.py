@@ -82,7 +82,7 @@ def lib():
         L.fq_o_dequant_f64.restype = None
         L.fq_o_dequant_f64.argtypes = [i32p, C.c_int64, C.c_int64, C.c_float, f32p, f32p, f64p]
         L.fq_o_requant_i8.restype = None
-        L.fq_o_requant_i8.argtypes = [i32p, C.c_int64, C.c_int64, C.c_float, f32p, f32p, C.c_float, i8p]
+        L.fq_o_requant_i8.argtypes = [i32p, C.c_int64, C.c_int64, C.c_float, f32p, f32p, C.c_float, i8p, f64p]
         _lib = L
     return _lib
 
@@ -238,16 +238,19 @@ def dequant_f64(acc, x_scale: float, w_scale, bias=None) -> np.ndarray:
     return y
 
 
-def requant_i8(acc, x_scale: float, w_scale, out_scale: float, bias=None) -> np.ndarray:
+def requant_i8(acc, x_scale: float, w_scale, out_scale: float, bias=None, return_arg: bool = False):
+    """Eq. 1 applied to the dequantised output: clip(round_half_even(y / out_scale), -128, 127), in float64.
+    With return_arg also the float64 argument y / out_scale of every element."""
     acc = _c(acc, np.int32)
     N = acc.shape[-1]
     M = acc.size // N
     w_scale = _c(w_scale, np.float32)
     b = _c(bias, np.float32) if bias is not None else None
     q = np.empty(acc.shape, np.int8)
+    t = np.empty(acc.shape, np.float64) if return_arg else None
     lib().fq_o_requant_i8(_p(acc, C.c_int32), M, N, np.float32(x_scale), _p(w_scale, C.c_float),
-                          _p(b, C.c_float), np.float32(out_scale), _p(q, C.c_int8))
-    return q
+                          _p(b, C.c_float), np.float32(out_scale), _p(q, C.c_int8), _p(t, C.c_double))
+    return (q, t) if return_arg else q
 
 
 # ---- glue: one layer, offline preparation then forward ------------------------------------------

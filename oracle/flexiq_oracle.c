@@ -28,8 +28,8 @@
 /* ------------------------------------------------------------------------ */
 /* Uniform symmetric quantisation  (Section 2.1, Eq. 1)                      */
 /*   x_q = clip(round(x / S), Qn, Qp),  round = nearest, ties to even.       */
-/* The decision is taken in fp32 (the precision the HIP library uses), so    */
-/* that both sides agree bit for bit on the integer code.                    */
+/* The inputs are fp32 and the decision is taken in fp32: x / S is one        */
+/* correctly rounded single-precision division, then rounded to an integer.  */
 /* ------------------------------------------------------------------------ */
 
 /* S = max|x| / 127 (fp32); an all-zero tensor gets S = 1 so x/S is defined. */
@@ -351,32 +351,26 @@ void fq_o_dequant_f64(const int32_t *acc, int64_t M, int64_t N, float x_scale, c
                            (bias ? (double)bias[n] : 0.0);
 }
 
-/* Requantised 8-bit output for the next layer (Eq. 1 applied to y with the
- * output scale).  The paper fixes neither the precision nor the order of the
- * operations of this step; the integer code is decided in fp32, by the same
- * sequence of correctly rounded single-precision operations the HIP library
- * uses.  The code is formed in offset form (code + 128, an unsigned byte):
- *   c[n]   = S_x * S_w[n]            r = 1 / S_out
- *   mul[n] = c[n] * r                add[n] = bias[n] * r + 128   (two roundings)
- *   t      = fma(float(acc), mul[n], add[n])                      (one rounding)
- *   q      = clip(round_half_even(t), 0, 255) - 128
- * which is clip(round(y / S_out), -128, 127) up to single-precision rounding
- * of t.  Compile with -ffp-contract=off so that no other operation is fused. */
+/* Requantised 8-bit output for the next layer: Eq. 1 applied to the
+ * dequantised output y with the output scale S_out, the plain definition in
+ * double precision (the paper fixes neither precision nor operation order of
+ * this step, so the checker is the real-number formula itself):
+ *   t[m][n] = (acc[m][n] * S_x * S_w[n] + bias[n]) / S_out
+ *   q[m][n] = clip(round_half_even(t), -128, 127)
+ * `t_out` (optional) receives t, so that a comparison can tell how close an
+ * element lies to a rounding tie.                                            */
 void fq_o_requant_i8(const int32_t *acc, int64_t M, int64_t N, float x_scale, const float *w_scale,
-                     const float *bias, float out_scale, int8_t *q)
+                     const float *bias, float out_scale, int8_t *q, double *t_out)
 {
-    volatile float r = 1.0f / out_scale;
-    for (int64_t n = 0; n < N; ++n) {
-        volatile float c = x_scale * w_scale[n];
-        volatile float mul = c * r;
-        volatile float add0 = bias ? bias[n] * r : 0.0f;
-        volatile float add = add0 + 128.0f;
-        for (int64_t m = 0; m < M; ++m) {
-            float t = fmaf((float)acc[m * N + n], mul, add);
-            t = nearbyintf(t);
-            if (t < 0.0f) t = 0.0f;
-            if (t > 255.0f) t = 255.0f;
-            q[m * N + n] = (int8_t)((int)t - 128);
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double y = (double)acc[m * N + n] * (double)x_scale * (double)w_scale[n] +
+                       (bias ? (double)bias[n] : 0.0);
+            double t = y / (double)out_scale;
+            double c = nearbyint(t); /* default rounding mode: ties to even */
+            if (c < -128.0) c = -128.0;
+            if (c > 127.0) c = 127.0;
+            q[m * N + n] = (int8_t)c;
+            if (t_out) t_out[m * N + n] = t;
         }
-    }
 }

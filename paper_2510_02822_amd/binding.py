@@ -8,8 +8,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# FLEXIQ_LIB names another build of the same library (e.g. an instrumented one); there is no non-HIP path
-LIB_PATH = os.environ.get("FLEXIQ_LIB") or os.path.join(_HERE, "libflexiq.so")
+LIB_PATH = os.path.join(_HERE, "libflexiq.so")   # built in-tree; there is no non-HIP path
 _lib = None
 
 

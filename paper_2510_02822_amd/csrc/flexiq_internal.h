@@ -10,21 +10,44 @@
 namespace flexiq {
 
 // Channels are processed in "units" of 32 (the smallest group size of Section 7); a K-step of the
-// matrix pipeline is two units = 64 reduction elements = one v_mfma_i32_16x16x64_i8.
+// matrix pipeline is two units = 64 reduction elements = two v_mfma_i32_32x32x32_i8 per pair of fragments.
 constexpr int kUnit = 32;
 constexpr int kNPadTo = 256;  // weight tiles are padded in N to the largest block tile
 
 // Record a failed HIP call for flexiq_last_hip_error().
 void set_hip_error(hipError_t e, const char *what);
 
-#define FLEXIQ_HIP(call)                         \
-    do {                                         \
-        hipError_t e__ = (call);                 \
-        if (e__ != hipSuccess) {                 \
-            ::flexiq::set_hip_error(e__, #call); \
-            return FLEXIQ_EHIP;                  \
-        }                                        \
+// A failed HIP call ends the entry point: FLEXIQ_ENOMEM when the device is out of memory, FLEXIQ_EHIP otherwise.
+#define FLEXIQ_HIP(call)                                                       \
+    do {                                                                       \
+        hipError_t e__ = (call);                                               \
+        if (e__ != hipSuccess) {                                               \
+            ::flexiq::set_hip_error(e__, #call);                               \
+            return e__ == hipErrorOutOfMemory ? FLEXIQ_ENOMEM : FLEXIQ_EHIP;   \
+        }                                                                      \
     } while (0)
+
+// Once per device, when the first layer is packed on it: dynamic-LDS limits and occupancy of every kernel of the
+// GEMM shape table, so that a launch is only a launch.
+int prepare_kernels(int device);
+
+// Order hash of a channel permutation (FNV-1a over the 32-bit entries; `n` entries, identity when p == nullptr).
+inline uint64_t order_hash(const int32_t *p, int n)
+{
+    uint64_t h = 1469598103934665603ull;
+    for (int i = 0; i < n; ++i) {
+        uint32_t v = (uint32_t)(p ? p[i] : i);
+        for (int b = 0; b < 4; ++b) {
+            h ^= (v >> (8 * b)) & 0xFFu;
+            h *= 1099511628211ull;
+        }
+    }
+    return h;
+}
+
+// Limits of the GEMM kernel that depend on the layer alone (checked when it is packed, and again at launch).
+constexpr int kMaxGroups = 159;                       // the kernel keeps the position table of G + 1 groups in LDS
+constexpr int64_t kMaxWeightBytes = 0x7fffffff;       // both int8 weight copies sit behind one buffer descriptor
 
 }  // namespace flexiq
 
@@ -58,6 +81,8 @@ struct flexiq_layer {
     float x_scale;
     bool has_bias;
     std::vector<int32_t> perm;
+    uint64_t perm_hash;        // of perm: the order in which this layer reads its input channels
+    uint64_t out_order_hash;   // of out_perm (identity if none): the order in which it writes its output columns
     std::vector<uint8_t> a_shift, w_shift;
     std::vector<float> w_scale, bias;
     int device;

@@ -5,6 +5,7 @@
 #include <utility>
 #include <vector>
 
+#include "flexiq_test.h"
 #include "mixed_kernel.h"
 
 namespace flexiq {
@@ -23,8 +24,8 @@ static const TileShape *shapes(int *count)
     return tab;
 }
 
-// Process-wide tuning / test switches (not synchronised: set them while no call is in flight).
-static int g_num_cu = 0;
+// Test / tuning switches of include/flexiq_test.h: process-wide, not synchronised (set them while no call is in
+// flight).  The product never changes them.
 static int g_force_shape = -1;
 static int g_force_packed = -1;
 static int g_max_blocks = 0;
@@ -33,51 +34,58 @@ static int g_last_shape = -1, g_last_blocks = 0, g_last_resident = 0;
 // Calls with at most this many output rows stream the 4-bit units as packed codes (half the weight bytes, expanded
 // in registers); larger ones use the expanded copy.  Measured on MI355X the packed route never wins with this
 // kernel: a call with few rows has too few blocks to be limited by memory bandwidth, and pays for the expansion
-// in its (latency-bound) K loop.  It therefore stays off by default (-1) and is kept, parity-tested, for a
-// split-K small-batch kernel; flexiq_debug_force_packed4(1) selects it.
+// in its (latency-bound) K loop.  It therefore stays off by default (-1) and is kept, parity-tested, behind
+// flexiq_debug_force_packed4(1); few-row calls are served by the split-K kernel instead.
 constexpr int64_t kPackedMaxRows = -1;
 
-static int num_cu()
-{
-    if (g_num_cu <= 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            g_num_cu = prop.multiProcessorCount;
-        if (g_num_cu <= 0) g_num_cu = 256;
-    }
-    return g_num_cu;
-}
+// Per-device launch table, filled once per device by prepare_kernels() (called when a layer is packed, so never
+// inside a launch): compute units, and for every kernel of the shape table the blocks that fit on one CU.
+struct DeviceKernels {
+    bool ready = false;
+    int num_cu = 0;
+    int resident[kNumTileShapes][2][2] = {};
+};
+constexpr int kMaxDevices = 64;
+static DeviceKernels g_dev[kMaxDevices];
+static std::mutex g_dev_mu;
 
-// Blocks of kernel `fn` that fit on one CU (registers and LDS); raises the dynamic-LDS limit on first use.
-static int resident_blocks(kernel_fn fn, int threads, int lds)
+int prepare_kernels(int device)
 {
-    static std::mutex mu;
-    static std::vector<std::pair<const void *, int>> done;
-    std::lock_guard<std::mutex> lk(mu);
-    for (const auto &f : done)
-        if (f.first == (const void *)fn) return f.second;
-    int resident = 0;
-    if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return -1;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, (const void *)fn, threads, lds) != hipSuccess) return -1;
-    if (resident < 1) resident = 1;
-    done.emplace_back((const void *)fn, resident);
-    return resident;
+    if (device < 0 || device >= kMaxDevices) return FLEXIQ_EINVAL;
+    std::lock_guard<std::mutex> lk(g_dev_mu);
+    DeviceKernels &d = g_dev[device];
+    if (d.ready) return FLEXIQ_OK;
+    hipDeviceProp_t prop;
+    FLEXIQ_HIP(hipGetDeviceProperties(&prop, device));
+    d.num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    int cnt;
+    const TileShape *tab = shapes(&cnt);
+    for (int i = 0; i < cnt; ++i)
+        for (int c = 0; c < 2; ++c)
+            for (int k = 0; k < 2; ++k) {
+                const void *fn = (const void *)tab[i].fn[c][k];
+                int resident = 0;
+                // (raises the dynamic-LDS limit of the kernel; both calls are host-side bookkeeping)
+                FLEXIQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, tab[i].lds));
+                FLEXIQ_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, fn, tab[i].threads, tab[i].lds));
+                d.resident[i][c][k] = resident < 1 ? 1 : resident;
+            }
+    d.ready = true;
+    return FLEXIQ_OK;
 }
 
 // Pick the tile shape with the smallest modelled time on the busiest CU: the tiles that CU has to compute, how
 // many of them run side by side, and per tile the K-steps (slower when the CU is shared) plus the epilogue.
-static int choose_shape(int64_t M, int N, int steps, bool conv, bool packed, double lowered_frac)
+static int choose_shape(const DeviceKernels &dk, int64_t M, int N, int steps, bool conv, bool packed, double lowered_frac)
 {
     int cnt;
     const TileShape *tab = shapes(&cnt);
     if (g_force_shape >= 0 && g_force_shape < cnt) return g_force_shape;
-    const int ncu = num_cu();
+    const int ncu = dk.num_cu;
     double best = 1e300;
     int bi = 0;
     for (int i = 0; i < cnt; ++i) {
-        const int occ = resident_blocks(tab[i].fn[conv ? 1 : 0][packed ? 1 : 0], tab[i].threads, tab[i].lds);
-        if (occ < 1) continue;
+        const int occ = dk.resident[i][conv ? 1 : 0][packed ? 1 : 0];
         const double tiles = (double)((M + tab[i].BM - 1) / tab[i].BM) * (double)((N + tab[i].BN - 1) / tab[i].BN);
         const double tiles_cu = __builtin_ceil(tiles / ncu);
         const double conc = tiles_cu < occ ? tiles_cu : occ;
@@ -93,6 +101,12 @@ static int choose_shape(int64_t M, int N, int steps, bool conv, bool packed, dou
         }
     }
     return bi;
+}
+
+// The producer of a fused chain must write its columns in the order the consumer reads its channels.
+static bool orders_match(const flexiq_layer *producer, const flexiq_layer *consumer)
+{
+    return producer->out_order_hash == consumer->perm_hash;
 }
 
 static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, bool conv,
@@ -113,6 +127,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     if (out->lower_for) {
         const flexiq_layer *nx = out->lower_for;
         if (!out->q || nx->C != L->N || nx->device != L->device) return FLEXIQ_EINVAL;
+        if (nx->G > kMaxGroups || !orders_match(L, nx)) return FLEXIQ_EINVAL;   // consumer's table lives in LDS; column order
         p.next_ashift = nx->dynamic ? nx->d_ashift_dyn : nx->d_ashift;
         p.next_K4 = nx->max_4bit_ch;
         p.next_G = nx->G;
@@ -121,6 +136,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     if (out->scan_for) {
         flexiq_layer *nx = out->scan_for;
         if (!out->q || nx->C != L->N || nx->device != L->device || nx == L) return FLEXIQ_EINVAL;
+        if (nx->G > kMaxGroups || !orders_match(L, nx)) return FLEXIQ_EINVAL;   // the block's mask table holds 160 groups
         p.next_scan = nx->d_scan;
         p.next_static = nx->d_ashift;
         p.next_dyn = nx->d_ashift_dyn;
@@ -133,12 +149,14 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     {   // the handle's buffers live on the device it was packed on
         int dev = -1;
         FLEXIQ_HIP(hipGetDevice(&dev));
-        if (dev != L->device) return FLEXIQ_EINVAL;
+        if (dev != L->device || dev < 0 || dev >= kMaxDevices) return FLEXIQ_EINVAL;
     }
-    if (L->G + 1 > 160) return FLEXIQ_EINVAL;  // position table kept in LDS
+    const DeviceKernels &dk = g_dev[L->device];
+    if (!dk.ready) return FLEXIQ_EINVAL;   // (set up when the handle was packed)
+    if (L->G > kMaxGroups) return FLEXIQ_EINVAL;  // position table kept in LDS
     if (M > 0x7fffffff - 512) return FLEXIQ_EINVAL;  // row indices are 32-bit in the kernel
     if (L->C / kUnit >= 2 * 65535) return FLEXIQ_EINVAL;  // K-step indices are kept in 16-bit fields
-    if ((int64_t)L->U * 32 * L->Npad * 2 > 0x7fffffff) return FLEXIQ_EINVAL;  // both int8 weight copies must fit one buffer descriptor
+    if ((int64_t)L->U * 32 * L->Npad * 2 > kMaxWeightBytes) return FLEXIQ_EINVAL;  // both int8 weight copies must fit one buffer descriptor
     p.H = H; p.Wd = Wd; p.Ho = Ho; p.Wo = Wo; p.S = L->S; p.stride = stride; p.pad = pad;
     const int steps = L->T * ((p.CU + 1) / 2);
     // (activations that arrive lowered always pair with the expanded weight copy)
@@ -146,7 +164,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     int cnt;
     // share of the K-steps whose activations the kernel lowers (none when they arrive lowered)
     const double lowered_frac = L->x_prelowered ? 0.0 : (double)L->max_4bit_ch / (double)L->C;
-    g_last_shape = choose_shape(M, L->N, steps, conv, packed, lowered_frac);
+    g_last_shape = choose_shape(dk, M, L->N, steps, conv, packed, lowered_frac);
     const TileShape &ts = shapes(&cnt)[g_last_shape];
     p.tiles_m = (int)((M + ts.BM - 1) / ts.BM);
     p.tiles_n = (L->N + ts.BN - 1) / ts.BN;
@@ -160,16 +178,12 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     if (tiles > 0x7fffffff) return FLEXIQ_EINVAL;
     kernel_fn fn = ts.fn[conv ? 1 : 0][packed ? 1 : 0];
-    const int resident = resident_blocks(fn, ts.threads, ts.lds);   // blocks of this kernel that fit on one CU
-    if (resident < 1) {
-        set_hip_error(hipGetLastError(), "hipFuncSetAttribute / hipOccupancyMaxActiveBlocksPerMultiprocessor");
-        return FLEXIQ_EHIP;
-    }
+    const int resident = dk.resident[g_last_shape][conv ? 1 : 0][packed ? 1 : 0];   // blocks of this kernel that fit on one CU
     // Shapes whose blocks can walk several output tiles are launched as one resident wave of blocks (the kernel's
     // load pipeline then runs on across tile boundaries); the others with one block per tile.
     int64_t blocks = tiles;
     if (ts.multi && g_max_blocks >= 0)
-        blocks = std::min<int64_t>(tiles, g_max_blocks > 0 ? (int64_t)g_max_blocks : (int64_t)num_cu() * resident);
+        blocks = std::min<int64_t>(tiles, g_max_blocks > 0 ? (int64_t)g_max_blocks : (int64_t)dk.num_cu * resident);
     g_last_blocks = (int)blocks;
     g_last_resident = resident;
     hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3(ts.threads), ts.lds, (hipStream_t)stream, p);
@@ -192,7 +206,7 @@ static int check_out(const flexiq_out *out)
 
 using namespace flexiq;
 
-// Test / tuning hook: force tile shape `index` of the internal table (-1 = automatic choice).
+// Test / tuning hooks (include/flexiq_test.h).
 extern "C" int flexiq_debug_force_tile(int index)
 {
     int cnt;

@@ -206,11 +206,6 @@ struct Cfg {
 enum StepMode { kMode88 = 0, kMode44 = 1, kMode48 = 2, kModeNone = 3 };
 
 #define FQ_SB() __builtin_amdgcn_sched_barrier(0)
-#ifdef FLEXIQ_TIMING
-#define FQ_TS(v) FQ_SB(); v = __builtin_readcyclecounter(); FQ_SB()
-#else
-#define FQ_TS(v)
-#endif
 
 // Tiles with at most 128 accumulator registers per lane are compiled for two blocks per CU where LDS allows:
 // one block's prologue and epilogue then overlap the other's matrix work.
@@ -240,9 +235,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: lives in a scalar register
     __builtin_assume(wave >= 0 && wave < NW);
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-#ifdef FLEXIQ_TIMING
-    long long tq0 = __builtin_readcyclecounter(), tqa = 0, tqb = 0, tqc = 0, tqd = 0, tqe = 0;
-#endif
 
     // ---- tile index -> tile.  A block computes the tiles blockIdx.x, blockIdx.x + gridDim.x, ... one after
     // the other with the load pipeline running on across the tile boundary.  Consecutive block ids land on
@@ -358,8 +350,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         w4voff[j] = row * 16;
         w4lds[j] = XBYTES + row * 16;
     }
-
-    FQ_TS(tqa);
     // activation positions of all groups: loaded into a register here, written to LDS after the prologue's tile
     // loads have been issued (one memory latency for all)
     static_assert(BN <= NT && 160 <= NT, "one table element per thread");
@@ -590,7 +580,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // stages 0, 1, 2; the register-routed pieces of steps 0 and 1 into registers of their own, those of
     // step 2 into the staging registers of the main loop); then the tables and the register-routed pieces of
     // steps 0 and 1 go to LDS.
-    FQ_TS(tqe);
     int mode_staged = kModeNone;   // mode of K-step s+2, whose register-routed pieces sit in the staging registers
     bool plain_prologue;           // K-steps 0, 1 and 2 all exist and are plain copies into LDS
     // K-steps 0, 1 and 2 all exist and all lower their activations: same code with the mode known at compile time,
@@ -623,9 +612,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
             for (int i = 0; i < NI; ++i) gload(sr, wsh, i, kMode44, lds + 2 * STAGE);
             advance();
             plain_prologue = false;
-            FQ_TS(tqb);
             publish_tables();
-            FQ_TS(tqc);
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 sa_fetch(pc64[t]);
@@ -656,9 +643,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                 advance();
             }
             plain_prologue = !PACKED4 && pmode[0] == kMode88 && pmode[1] == kMode88 && mode_staged == kMode88;
-            FQ_TS(tqb);
             publish_tables();
-            FQ_TS(tqc);
             // (nothing to do when all three steps are plain copies; the branch also keeps the wait for the staging
             // registers, which covers every load issued so far, out of that path)
             if (!plain_prologue) {
@@ -681,7 +666,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         }
     }
     if (mode_staged == kMode44 || mode_staged == kMode48) sa_fetch(st_c64);
-    FQ_TS(tqd);
     v16i acc[TN][TM];
     auto zero_acc = [&]() {
 #pragma unroll
@@ -718,13 +702,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         own[BN] = b * p.r_out + 128.0f;
     }
 
-#ifdef FLEXIQ_TIMING
-    long long tq1 = __builtin_readcyclecounter(), t_epi = 0, t_wait_vm = 0, t_wait_bar = 0, t_wait0 = 0;
-    int n_tiles = 0;
-    long long t_tile0 = tq1, t_sw = 0;
-    __shared__ long long t_at[8][2][16];   // [wave][first tile / later tiles][step]
-    if (lane < 32) t_at[wave][lane >> 4][lane & 15] = 0;
-#endif
     // ---- main loop.  Step s computes K-step s from stage s % 4 while K-step s+3 is loaded (straight into stage
     // (s+3) % 4, or into the staging registers) and the register-routed pieces of K-step s+2 (loaded during step
     // s-1) are lowered / expanded and stored into stage (s+2) % 4.  `ma` is the mode of K-step s+2 (kModeNone:
@@ -836,9 +813,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         // The direct loads of the previous step (K-step s+2) must have landed before the barrier publishes them;
         // this step's own loads may stay in flight.  Their number is known at compile time where every wave
         // issues the same loads; otherwise wait for everything.
-#ifdef FLEXIQ_TIMING
-        const long long tw0 = __builtin_readcyclecounter();
-#endif
         if (!PACKED4 && (mb == kMode88 || mb == kMode44 || mb == kMode48)) {
             if (has_piece(XI - 1))
                 __builtin_amdgcn_s_waitcnt(0x0070 | ((XI + WI) & 15) | (((XI + WI) >> 4) << 14));
@@ -847,9 +821,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         } else {
             __builtin_amdgcn_s_waitcnt(0x0070);
         }
-#ifdef FLEXIQ_TIMING
-        const long long tw1 = __builtin_readcyclecounter();
-#endif
         // This wave's LDS stores and its reads of the stage that is refilled next are complete.  The fragment reads
         // issued after the last staging slot (they read the next step's stage, which nobody overwrites yet) may
         // stay in flight across the barrier: LDS operations complete in order, so allowing that many outstanding
@@ -859,15 +830,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         else
             __builtin_amdgcn_s_waitcnt(0xc07f);
         __builtin_amdgcn_s_barrier();
-#ifdef FLEXIQ_TIMING
-        t_wait_vm += tw1 - tw0;
-        if (s == 0) t_wait0 += tw1 - tw0;
-        {
-            const long long now = __builtin_readcyclecounter();
-            t_wait_bar += now - tw1;
-            if (lane == 0) t_at[wave][n_tiles > 0 ? 1 : 0][s < 15 ? s : 15] += now - t_tile0;
-        }
-#endif
         FQ_SB();
         {
             const int t = o_cur;
@@ -884,11 +846,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // quad g, the four consecutive output channels n = 32 a + 8 g + 4 (lane >> 5) + i.  The body is
     // instantiated with compile-time output flags for the common cases (int8 only; fp32 or int32 only) and
     // once with run-time flags for everything else (ragged N, several outputs at once).
-#ifdef FLEXIQ_TIMING
-    const bool want_q = p.q != nullptr, want_y = p.y != nullptr, want_acc = false;
-#else
     const bool want_q = p.q != nullptr, want_y = p.y != nullptr, want_acc = p.acc != nullptr;
-#endif
     const bool n_vec = (p.N & 3) == 0;
     const bool lower_out = p.next_ashift != nullptr;   // int8 output lowered for the consuming layer
     const bool scan_out = p.next_scan != nullptr;      // int8 output scanned for the consuming layer's positions
@@ -1070,9 +1028,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
             if (s < steps && mode_staged == kModeNone && !more_tiles && s + 1 >= steps) step(MNone{}, MNone{}, F_{}, F_{});
         }
 
-#ifdef FLEXIQ_TIMING
-        const long long te0 = __builtin_readcyclecounter();
-#endif
         auto epilogue_col = [&](auto a_) {
             if (q_rows && !want_y && !want_acc && !lower_out && !scan_out) epilogue(a_, T_{}, F_{}, F_{}, T_{}, T_{}, F_{}, F_{});
             else if (q_rows && !want_y && !want_acc && !scan_out) epilogue(a_, T_{}, F_{}, F_{}, T_{}, T_{}, T_{}, F_{});
@@ -1097,10 +1052,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                     if (m < p.M && n < p.N) *reinterpret_cast<v4i *>(p.q + m * p.N + n) = qout[a][b];
                 }
         }
-#ifdef FLEXIQ_TIMING
-        t_epi += __builtin_readcyclecounter() - te0;
-        ++n_tiles;
-#endif
         if (!more_tiles) break;
 
         // ---- next output tile of this block
@@ -1116,12 +1067,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         zero_step = kZeroStep && mode_staged == kMode44 && it_mode == kMode44;
         if (!zero_step) zero_acc();
         s = 0;
-#ifdef FLEXIQ_TIMING
-        FQ_SB();
-        t_tile0 = __builtin_readcyclecounter();
-        t_sw += t_tile0 - te0 - 0;
-        FQ_SB();
-#endif
     }
     // ---- scan for the consumer: merge the block's masks into the consumer's scan words (device-scope atomics);
     // the block that finishes last turns the merged masks into positions (highest magnitude bit p of a 4-bit
@@ -1156,20 +1101,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
             }
         }
     }
-#ifdef FLEXIQ_TIMING
-    {
-        long long tq3 = __builtin_readcyclecounter();
-        if (lane == 0 && p.acc) {
-            int *d = p.acc + ((int64_t)blockIdx.x * NW + wave) * 8;
-            d[0] = (int)(tq1 - tq0); d[1] = (int)(tq3 - tq1 - t_epi); d[2] = (int)t_epi; d[3] = steps * n_tiles;
-            d[4] = (int)t_wait0; d[5] = (int)t_wait_vm; d[6] = (int)t_wait_bar; d[7] = n_tiles;
-            int *e = p.acc + (int64_t)gridDim.x * NW * 8 + ((int64_t)blockIdx.x * NW + wave) * 32;
-            for (int i = 0; i < 32; ++i) e[i] = (int)t_at[wave][i >> 4][i & 15];
-            // prologue stamps (slots past the last K-step of the second row: free when a tile has at most 12 steps)
-            e[27] = (int)(tqe - tq0); e[28] = (int)(tqa - tq0); e[29] = (int)(tqb - tq0); e[30] = (int)(tqc - tq0); e[31] = (int)(tqd - tq0);
-        }
-    }
-#endif
 }
 
 typedef void (*kernel_fn)(const GemmParams);

@@ -338,6 +338,10 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
     if (d->C % d->group_size != 0) return FLEXIQ_EINVAL;
     if (!(d->x_scale > 0.0f) || !std::isfinite(d->x_scale)) return FLEXIQ_EINVAL;
     const int N = d->N, C = d->C, T = d->R * d->S, gs = d->group_size, G = C / gs;
+    {   // what the GEMM kernel could never launch is refused here, before any device work
+        const int64_t units = (int64_t)T * (((C / kUnit) + 1) & ~1), npad = cdiv(N, kNPadTo) * kNPadTo;
+        if (G > kMaxGroups || units * 32 * npad * 2 > kMaxWeightBytes) return FLEXIQ_EINVAL;
+    }
     if (d->perm) {  // must be a permutation of 0..C-1
         std::vector<char> seen(C, 0);
         for (int j = 0; j < C; ++j) {
@@ -388,6 +392,11 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
     L->d_w8 = nullptr; L->d_w4 = nullptr; L->d_w4x = nullptr; L->d_wshift = nullptr; L->d_ashift = nullptr; L->d_ashift_dyn = nullptr; L->d_scan = nullptr; L->dynamic = false; L->x_prelowered = false;
     L->d_cs = nullptr; L->d_bias = nullptr; L->d_perm = nullptr;
     FLEXIQ_HIP(hipGetDevice(&L->device));
+    {
+        const int rc = prepare_kernels(L->device);
+        if (rc != FLEXIQ_OK) return rc;
+    }
+    L->out_order_hash = order_hash(d->out_perm, N);
     const int Npad = L->Npad;
     const int64_t Kt = (int64_t)T * C, total = (int64_t)N * Kt;
 
@@ -426,6 +435,7 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
         std::iota(L->perm.begin(), L->perm.end(), 0);
         std::stable_sort(L->perm.begin(), L->perm.end(), [&](int a, int b) { return score[a] < score[b]; });
     }
+    L->perm_hash = order_hash(L->perm.data(), C);
     // Activation position of a group: the smallest that fits [-a, a], a = widest calibrated range in the group.
     L->a_shift.resize(G);
     for (int g = 0; g < G; ++g) {
@@ -566,26 +576,41 @@ extern "C" int flexiq_bitlower(const int8_t *src, uint8_t *dst, int64_t rows, in
     return FLEXIQ_OK;
 }
 
+namespace {
+// Launch shape of the scan kernel for `rows` rows of the handle's 4-bit channel range.
+struct ScanLaunch {
+    int g4, pieces, tx_log2;
+    unsigned gx, gy;
+};
+ScanLaunch scan_launch(const flexiq_layer *L, int64_t rows)
+{
+    ScanLaunch sl;
+    sl.g4 = L->max_4bit_ch / L->group_size;
+    sl.pieces = L->max_4bit_ch / 16;             // 16-channel pieces per row to scan
+    sl.tx_log2 = 0;
+    while ((1 << sl.tx_log2) < sl.pieces && sl.tx_log2 < 8) ++sl.tx_log2;
+    const int TX = 1 << sl.tx_log2, TY = kScanThreads >> sl.tx_log2;
+    sl.gx = 1;
+    sl.gy = 1;
+    if (sl.pieces > 0 && rows > 0) {
+        sl.gy = (unsigned)cdiv(sl.pieces, TX);
+        // about four rows per thread, and few blocks: every block ends with one atomic on a shared counter
+        sl.gx = (unsigned)std::min<int64_t>(cdiv(rows, (int64_t)TY * 4), std::max<int64_t>(1, 128 / sl.gy));
+        if (sl.gx < 1) sl.gx = 1;
+    }
+    return sl;
+}
+}  // namespace
+
 extern "C" int flexiq_dynamic_positions(flexiq_layer *L, const int8_t *X, int64_t rows, void *stream)
 {
     if (!L || rows < 0) return FLEXIQ_EINVAL;
     if (rows > 0 && !X) return FLEXIQ_EINVAL;
     if (rows > 0 && !aligned16(X)) return FLEXIQ_EALIGN;
-    const int g4 = L->max_4bit_ch / L->group_size;
-    const int pieces = L->max_4bit_ch / 16;             // 16-channel pieces per row to scan
-    int tx_log2 = 0;
-    while ((1 << tx_log2) < pieces && tx_log2 < 8) ++tx_log2;
-    const int TX = 1 << tx_log2, TY = kScanThreads >> tx_log2;
-    unsigned gx = 1, gy = 1;
-    if (pieces > 0 && rows > 0) {
-        gy = (unsigned)cdiv(pieces, TX);
-        // about four rows per thread, and few blocks: every block ends with one atomic on a shared counter
-        gx = (unsigned)std::min<int64_t>(cdiv(rows, (int64_t)TY * 4), std::max<int64_t>(1, 128 / gy));
-        if (gx < 1) gx = 1;
-    }
-    k_dyn_positions<<<dim3(gx, gy), kScanThreads, 0, (hipStream_t)stream>>>(X, pieces > 0 ? rows : 0, L->C, pieces,
-                                                                            tx_log2, L->group_size, L->G, g4, L->d_scan,
-                                                                            L->d_ashift, L->d_ashift_dyn);
+    const ScanLaunch sl = scan_launch(L, rows);
+    k_dyn_positions<<<dim3(sl.gx, sl.gy), kScanThreads, 0, (hipStream_t)stream>>>(X, sl.pieces > 0 ? rows : 0, L->C, sl.pieces,
+                                                                                    sl.tx_log2, L->group_size, L->G, sl.g4, L->d_scan,
+                                                                                    L->d_ashift, L->d_ashift_dyn);
     FLEXIQ_HIP(hipGetLastError());
     L->dynamic = true;
     return FLEXIQ_OK;

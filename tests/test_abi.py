@@ -18,15 +18,36 @@ def lib():
     return fq.load()
 
 
+def _declared(header):
+    hdr = open(os.path.join(ROOT, "include", header)).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    return set(re.findall(r"\b(flexiq_[a-z0-9_]+)\s*\(", hdr))
+
+
+def _dynamic_exports():
+    """flexiq_* functions in the library's real dynamic symbol table (nm -D), not a hand-written list."""
+    import subprocess
+    import paper_2510_02822_amd as fq
+    out = subprocess.check_output(["nm", "-D", "--defined-only", fq.binding.LIB_PATH], text=True)
+    names = set()
+    for line in out.splitlines():
+        parts = line.split()
+        if len(parts) >= 3 and parts[1] in ("T", "W") and parts[2].startswith("flexiq_"):
+            names.add(parts[2])
+    return names
+
+
 def test_exports_every_declared_symbol(lib):
     import paper_2510_02822_amd as fq
-    hdr = open(os.path.join(ROOT, "include", "flexiq.h")).read()
-    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(flexiq_[a-z0-9_]+)\s*\(", hdr))
+    api = _declared("flexiq.h")
+    test_aids = _declared("flexiq_test.h")
     assert {"flexiq_quantize_pack", "flexiq_bitlower", "flexiq_mixed_gemm", "flexiq_mixed_conv_implicit",
-            "flexiq_set_ratio"} <= declared
-    assert declared == set(fq.exported_symbols())
-    for name in declared:
+            "flexiq_set_ratio"} <= api
+    assert all(n.startswith("flexiq_debug_") for n in test_aids) and not (api & test_aids)
+    # the export table holds exactly what the two headers declare: nothing undeclared, nothing missing
+    assert _dynamic_exports() == api | test_aids
+    assert api == set(fq.exported_symbols())
+    for name in api | test_aids:
         assert getattr(lib, name) is not None
 
 
@@ -64,6 +85,25 @@ def test_host_argument_checks(lib):
     assert lib.flexiq_quantize_pack(C.byref(d), C.byref(h)) == EINVAL
     d = b._PackDesc(4, 64, 1, 1, 32, W.ctypes.data, am.ctypes.data, 0.0, None, None)
     assert lib.flexiq_quantize_pack(C.byref(d), C.byref(h)) == EINVAL
+
+
+def test_documented_layer_limits_are_refused_when_packing(lib):
+    # include/flexiq.h: more than 159 channel groups, or a padded weight matrix of 1 GiB or more, can never be
+    # launched; flexiq_quantize_pack refuses both before any device work (so this runs without a GPU; W is never read)
+    import numpy as np
+    import paper_2510_02822_amd.binding as b
+    EINVAL = -1
+    h = C.c_void_p()
+    W = np.zeros(16, np.float32)
+    for gs, cc in ((32, 160 * 32), (64, 160 * 64), (32, 200 * 32)):         # G = 160, 160, 200
+        am = np.ones(cc, np.float32)
+        d = b._PackDesc(8, cc, 1, 1, gs, W.ctypes.data, am.ctypes.data, 1.0, None, None, None)
+        assert lib.flexiq_quantize_pack(C.byref(d), C.byref(h)) == EINVAL
+    # weights: units of 32 channels (even per tap) x 32 bytes x N padded to 256 x two int8 copies >= 2^31 bytes
+    am = np.ones(8192, np.float32)
+    for n, cc, r in ((32768, 8192, 2), (16384, 8192, 3)):                   # exactly 2^31 bytes; 2.4e9 bytes
+        d = b._PackDesc(n, cc, r, r, 64, W.ctypes.data, am.ctypes.data, 1.0, None, None, None)
+        assert lib.flexiq_quantize_pack(C.byref(d), C.byref(h)) == EINVAL
 
 
 def test_missing_library_is_loud(monkeypatch):

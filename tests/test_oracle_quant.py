@@ -106,14 +106,31 @@ def test_dequant_and_requant(oracle):
     ref = acc.astype(np.float64) * np.float64(xs) * ws.astype(np.float64)[None, :] + bias.astype(np.float64)[None, :]
     assert np.allclose(y, ref, rtol=1e-15, atol=0)
     assert (oracle.dequant_f64(acc, xs, ws) == acc.astype(np.float64) * np.float64(xs) * ws.astype(np.float64)).all()
-    # requantised code: equals round(y / S_out) wherever y / S_out is not within float rounding of a tie
+    # requantised code = clip(round_half_even(y / S_out), -128, 127), checked against numpy in float64
     so = np.float32(np.abs(y).max() / 127 * 0.8)          # 0.8: some outputs clip
-    q = oracle.requant_i8(acc, xs, ws, so, bias)
-    t = y / np.float64(so)
-    frac = np.abs(t - np.floor(t) - 0.5)
-    clear = frac > 1e-4
-    assert clear.mean() > 0.99
-    want = np.clip(np.rint(t), -128, 127)
-    assert (q[clear] == want[clear]).all()
-    assert (np.abs(q.astype(np.float64) - np.clip(t, -128, 127)) <= 0.5 + 1e-4).all()
+    q, t = oracle.requant_i8(acc, xs, ws, so, bias, return_arg=True)
+    assert np.allclose(t, ref / np.float64(so), rtol=1e-15, atol=0)
+    assert (q == np.clip(np.rint(ref / np.float64(so)), -128, 127)).all()
     assert q.min() == -128 or q.max() == 127
+
+
+def test_requant_ties_and_clip_edges(oracle):
+    # Hand-placed arguments: S_x = 1, S_w = 0.5, S_out = 1 make t = acc / 2 + bias exact, so every expected code
+    # below is Eq. 1 worked by hand: ties go to the even code, the range is [-128, 127].
+    acc = np.array([[1, 3, 5, -1, -3, -5, 0, 2, 254, 255, 256, 257, 1000, -255, -256, -257, -258, -259, -1000, 7]],
+                   np.int32).T.copy()                    # one output channel, 20 rows
+    ws = np.array([0.5], np.float32)
+    q, t = oracle.requant_i8(acc, 1.0, ws, 1.0, None, return_arg=True)
+    want_t = [0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 0.0, 1.0, 127.0, 127.5, 128.0, 128.5, 500.0, -127.5, -128.0, -128.5,
+              -129.0, -129.5, -500.0, 3.5]
+    want_q = [0, 2, 2, 0, -2, -2, 0, 1, 127, 127, 127, 127, 127, -128, -128, -128, -128, -128, -128, 4]
+    assert t[:, 0].tolist() == want_t
+    assert q[:, 0].tolist() == want_q
+    # a bias moves the tie: t = acc / 2 + 0.25 is never a tie, t = acc / 2 + 0.5 turns even acc into ties
+    q2 = oracle.requant_i8(acc[:8], 1.0, ws, 1.0, np.array([0.25], np.float32))
+    assert q2[:, 0].tolist() == [1, 2, 3, 0, -1, -2, 0, 1]
+    q3 = oracle.requant_i8(np.array([[0], [2], [4], [-2], [-4]], np.int32), 1.0, ws, 1.0, np.array([0.5], np.float32))
+    assert q3[:, 0].tolist() == [0, 2, 2, 0, -2]
+    # the output scale divides: S_out = 0.25 -> t = 4 * (acc / 2) ; per-channel weight scales apply per column
+    q4 = oracle.requant_i8(np.array([[1, 1], [-3, -3]], np.int32), 1.0, np.array([0.5, 0.0625], np.float32), 0.25)
+    assert q4.tolist() == [[2, 0], [-6, -1]]    # columns: 4 * 0.5 = 2, 4 * 0.0625 = 0.25 -> 0; -6, -0.75 -> -1
