@@ -125,6 +125,15 @@ int flexiq_bitlower(const int8_t *src, uint8_t *dst, int64_t rows, int32_t C, in
  * One kernel, no allocation, no host synchronisation.  rows == 0: every scanned group gets position 0. */
 int flexiq_dynamic_positions(flexiq_layer *layer, const int8_t *X, int64_t rows, void *stream);
 
+/* flexiq_dynamic_positions() for callers that cannot allocate or must not depend on allocations made elsewhere
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same scan with the same
+ * result, but its scratch (one OR mask per channel group and a block counter) lives in a file-scope device array of
+ * the library, 160 32-bit words per GPU, instead of the handle's allocation.  Calls no hipMalloc / hipFree and no
+ * allocating routine.  Limit: G + 1 <= 160 channel groups, else FLEXIQ_EINVAL.  All calls on one GPU share that
+ * array: two calls of this function that overlap on one GPU (different streams, different handles) race; calls on
+ * one stream are ordered and each leaves the array zero for the next.  The handle's device must be current. */
+int flexiq_dynamic_positions_static(flexiq_layer *layer, const int8_t *X, int64_t rows, void *stream);
+
 /* Tells the handle that the activations handed to flexiq_mixed_gemm / flexiq_mixed_conv_implicit are bit-lowered
  * already for its current ratio and positions (written by the producing layer with flexiq_out.lower_for): the
  * kernel then copies them like 8-bit activations and only the weights of the 4-bit groups differ.  Host-side

@@ -29,7 +29,7 @@ class _Out(C.Structure):
 
 def exported_symbols():
     """Names include/flexiq.h declares."""
-    return ["flexiq_strerror", "flexiq_last_hip_error", "flexiq_quantize_pack", "flexiq_layer_free",
+    return ["flexiq_dynamic_positions_static", "flexiq_strerror", "flexiq_last_hip_error", "flexiq_quantize_pack", "flexiq_layer_free",
             "flexiq_layer_info", "flexiq_layer_dump", "flexiq_set_ratio", "flexiq_quantize_act",
             "flexiq_bitlower", "flexiq_dynamic_positions", "flexiq_static_positions", "flexiq_layer_positions",
             "flexiq_input_prelowered", "flexiq_permute_channels", "flexiq_mixed_gemm", "flexiq_mixed_conv_implicit"]
@@ -56,6 +56,7 @@ def load():
     L.flexiq_bitlower.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_int,
                                   C.c_int, C.c_void_p]
     L.flexiq_dynamic_positions.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+    L.flexiq_dynamic_positions_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     L.flexiq_static_positions.argtypes = [C.c_void_p]
     L.flexiq_input_prelowered.argtypes = [C.c_void_p, C.c_int]
     L.flexiq_layer_positions.argtypes = [C.c_void_p, C.c_void_p]
@@ -186,6 +187,14 @@ def flexiq_dynamic_positions(layer: Layer, X) -> None:
     assert X.dtype == torch.int8 and X.is_cuda and X.is_contiguous() and X.shape[-1] == layer.C
     rows = X.numel() // layer.C
     _check(load().flexiq_dynamic_positions(layer._h, X.data_ptr(), rows, _stream()))
+
+
+def flexiq_dynamic_positions_static(layer: Layer, X) -> None:
+    """flexiq_dynamic_positions with the scan scratch in the library's file-scope device array (allocates nothing)."""
+    import torch
+    assert X.dtype == torch.int8 and X.is_cuda and X.is_contiguous() and X.shape[-1] == layer.C
+    rows = X.numel() // layer.C
+    _check(load().flexiq_dynamic_positions_static(layer._h, X.data_ptr(), rows, _stream()))
 
 
 def flexiq_input_prelowered(layer: Layer, on: bool) -> None:

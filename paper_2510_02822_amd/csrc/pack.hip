@@ -616,6 +616,45 @@ extern "C" int flexiq_dynamic_positions(flexiq_layer *L, const int8_t *X, int64_
     return FLEXIQ_OK;
 }
 
+// ---- the same scan for callers that cannot allocate: the scan words live in a file-scope device array ----------
+// (each GPU the library runs on holds its own copy of the array, at its own address, until the process ends)
+constexpr int kStaticScanWords = 160;   // G + 1 <= 160 words: one OR mask per channel group, then the block counter
+static __device__ __align__(256) uint32_t scratch[kStaticScanWords];
+namespace {
+std::mutex g_scratch_mu;
+uint32_t *g_scratch_ptr[64];   // per device: the array's device address (the name `scratch` is only a host-side stand-in)
+}  // namespace
+
+extern "C" int flexiq_dynamic_positions_static(flexiq_layer *L, const int8_t *X, int64_t rows, void *stream)
+{
+    if (!L || rows < 0) return FLEXIQ_EINVAL;
+    if (rows > 0 && !X) return FLEXIQ_EINVAL;
+    if (rows > 0 && !aligned16(X)) return FLEXIQ_EALIGN;
+    if (L->G + 1 > kStaticScanWords) return FLEXIQ_EINVAL;   // more channel groups than the static scan words hold
+    int dev = -1;
+    FLEXIQ_HIP(hipGetDevice(&dev));
+    if (dev != L->device || dev < 0 || dev >= 64) return FLEXIQ_EINVAL;
+    uint32_t *words;
+    {
+        std::lock_guard<std::mutex> lk(g_scratch_mu);
+        if (!g_scratch_ptr[dev]) {   // first call on this device (which is current)
+            uint32_t *ptr = nullptr;
+            FLEXIQ_HIP(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+            g_scratch_ptr[dev] = ptr;
+        }
+        words = g_scratch_ptr[dev];
+    }
+    // The array is zero when the library is loaded and every scan leaves the words it touched at zero again (its
+    // last block clears masks and counter), so nothing is cleared here.
+    const ScanLaunch sl = scan_launch(L, rows);
+    k_dyn_positions<<<dim3(sl.gx, sl.gy), kScanThreads, 0, (hipStream_t)stream>>>(X, sl.pieces > 0 ? rows : 0, L->C, sl.pieces,
+                                                                                    sl.tx_log2, L->group_size, L->G, sl.g4, words,
+                                                                                    L->d_ashift, L->d_ashift_dyn);
+    FLEXIQ_HIP(hipGetLastError());
+    L->dynamic = true;
+    return FLEXIQ_OK;
+}
+
 extern "C" int flexiq_input_prelowered(flexiq_layer *L, int on)
 {
     if (!L) return FLEXIQ_EINVAL;
