@@ -176,7 +176,11 @@ int flexiq_permute_channels(const flexiq_layer *layer, const int8_t *src, int8_t
  *               as flexiq_dynamic_positions(consumer, q, M) would, without a second kernel.  Uses the consumer's scan
  *               scratch, which the kernel leaves clean (safe to replay from a captured graph): calls that scan for
  *               the same consumer must not overlap, nor overlap its flexiq_dynamic_positions.  A call with M == 0
- *               launches nothing and leaves the positions as they were.  NULL: no scan */
+ *               launches nothing and leaves the positions as they were.  NULL: no scan
+ *   x6        : optional, only with lower_for and only for flexiq_mixed_gemm_fp6 (FLEXIQ_EINVAL elsewhere): the
+ *               consumer's FP6 activation buffer (flexiq_fp6_bytes(consumer, M) bytes).  The columns that are FP6
+ *               channels of the consumer (flexiq_fp6_channels) are then written there as FP6 codes instead of into q;
+ *               q keeps the other columns (those of its remaining 4-bit channels lowered).  Needs N % 64 == 0 */
 typedef struct {
     int32_t *acc;
     float *y;
@@ -184,6 +188,7 @@ typedef struct {
     float out_scale;
     const flexiq_layer *lower_for;
     flexiq_layer *scan_for;
+    uint8_t *x6;
 } flexiq_out;
 
 /* Mixed-precision GEMM (Sections 2.3, 7):
@@ -205,6 +210,43 @@ int flexiq_mixed_gemm(const flexiq_layer *layer, const int8_t *X, int64_t M, con
  * Further limit: H*W*C * (320 / (Ho*Wo) + 2) must be below 2^31 bytes (a block reads its images through a 2 GiB window). */
 int flexiq_mixed_conv_implicit(const flexiq_layer *layer, const int8_t *X, int32_t B, int32_t H, int32_t W,
                                int32_t stride, int32_t pad, const flexiq_out *out, void *stream);
+
+/* ---- Variant of the 4-bit phase on the FP6 matrix path (Section 7: the low-bit groups on a faster matrix
+ * instruction; on gfx950 that instruction is the FP8/FP6/FP4 MFMA with block scales, since no 4-bit integer MFMA
+ * exists).  Same result, bit for bit, as flexiq_mixed_gemm: a 4-bit code L(v, s) in [-8, 7] is the exact FP6 (E2M3)
+ * value code / 8, and the block scale 2^(s+3) per 32 channels is the extraction shift.  Linear layers with
+ * C % 64 == 0 only.  The leading flexiq_fp6_channels() stored channels run as FP6: the 4-bit channels of the current
+ * ratio, cut to a multiple of 64 and to the prefix for which exact fp32 accumulation is certified from the packed
+ * weights and the positions in use (every partial sum below 2^24); remaining 4-bit channels run on the int8 path. */
+
+/* Leading stored channels that run as FP6 under the handle's current ratio and positions (a multiple of 64). */
+int flexiq_fp6_channels(const flexiq_layer *layer, int32_t *k6);
+
+/* Bytes of the FP6 activation buffer for M rows: ceil(M / 64) * (C / 64) * 3072 (negative flexiq_status on error).
+ * Layout [row / 64][K-step of 64 channels][plane 0..2][row % 64][16 bytes]: planes 0 and 1 hold the first 16 bytes of
+ * the 24-byte image of the K-step's two 32-channel units, plane 2 the last 8 bytes of both (unit h in half
+ * h ^ ((row >> 4) & 1)); element e (6 bits, little-endian bit order) of a unit is the code of its channel
+ * 8 * ((e % 16) / 4) + 4 * (e / 16) + e % 4, as sign << 5 | |code|. */
+int64_t flexiq_fp6_bytes(const flexiq_layer *layer, int64_t M);
+
+/* Stand-alone producer of that buffer (Section 4.1 bit-lowering of the activations, then the FP6 pattern):
+ *   X    : dev int8 [M][C], stored channel order
+ *   x6   : dev, flexiq_fp6_bytes(layer, M) bytes; K-steps below flexiq_fp6_channels() / 64 are written (rows of the last
+ *          block beyond M are not)
+ *   xlow : dev int8 [M][C] or NULL: copy of X whose 4-bit channels outside the FP6 prefix are lowered in place
+ *          (L(v, s) << s); required when flexiq_fp6_channels() is smaller than max_4bit_ch, else X itself can be
+ *          handed to flexiq_mixed_gemm_fp6
+ * Uses the handle's current ratio and positions.  Two kernels at most, no allocation. */
+int flexiq_lower_fp6(const flexiq_layer *layer, const int8_t *X, int64_t M, uint8_t *x6, int8_t *xlow, void *stream);
+
+/* The mixed GEMM with the FP6 prefix on v_mfma_scale_f32_32x32x64_f8f6f4 (twice the int8 matrix rate) and everything
+ * else on the int8 MFMA, same accumulators: acc, y, q as for flexiq_mixed_gemm (out->scan_for is not supported).
+ *   X  : dev int8 [M][C]; columns below flexiq_fp6_channels() are not read; 4-bit columns beyond it must arrive lowered
+ *        (flexiq_lower_fp6's xlow, or a producer's lower_for); may be NULL when every channel is FP6
+ *   x6 : dev FP6 activations (flexiq_lower_fp6, or a producer's flexiq_out.x6); may be NULL when no channel is FP6
+ * Launch only; no allocation.  Further limit: flexiq_fp6_bytes(layer, M) < 2^31. */
+int flexiq_mixed_gemm_fp6(const flexiq_layer *layer, const int8_t *X, const uint8_t *x6, int64_t M, const flexiq_out *out,
+                          void *stream);
 
 #ifdef __cplusplus
 }

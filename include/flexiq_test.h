@@ -3,7 +3,7 @@
  * the library: the parity tests use them to force every code path of the GEMM kernel (each tile shape, each
  * weight route, blocks that walk several output tiles) on inputs small enough for the CPU oracle.
  *
- * All four act on process-wide state that the launch path reads without synchronisation: call them only
+ * All of them act on process-wide state that the launch path reads without synchronisation: call them only
  * while no flexiq call is in flight on any thread, and reset them (-1 / 0) afterwards.
  */
 #ifndef FLEXIQ_TEST_H
@@ -28,6 +28,9 @@ int flexiq_debug_max_blocks(int n);
 /* What the last GEMM / convolution launch used.  which = 0: tile shape index, 1: blocks launched,
  * 2: blocks of that kernel resident per compute unit, 3: split-K slices (1 = the tiled kernel). */
 int flexiq_debug_last_launch(int which);
+
+/* Force tile shape `index` of the FP6-variant kernel's table (-1 = automatic).  Returns the table size. */
+int flexiq_debug_force_fp6_tile(int index);
 
 #ifdef __cplusplus
 }

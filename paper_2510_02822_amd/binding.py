@@ -24,12 +24,13 @@ class _PackDesc(C.Structure):
 
 class _Out(C.Structure):
     _fields_ = [("acc", C.c_void_p), ("y", C.c_void_p), ("q", C.c_void_p), ("out_scale", C.c_float),
-                ("lower_for", C.c_void_p), ("scan_for", C.c_void_p)]
+                ("lower_for", C.c_void_p), ("scan_for", C.c_void_p), ("x6", C.c_void_p)]
 
 
 def exported_symbols():
     """Names include/flexiq.h declares."""
-    return ["flexiq_dynamic_positions_static", "flexiq_strerror", "flexiq_last_hip_error", "flexiq_quantize_pack", "flexiq_layer_free",
+    return ["flexiq_dynamic_positions_static", "flexiq_fp6_channels", "flexiq_fp6_bytes", "flexiq_lower_fp6",
+            "flexiq_mixed_gemm_fp6", "flexiq_strerror", "flexiq_last_hip_error", "flexiq_quantize_pack", "flexiq_layer_free",
             "flexiq_layer_info", "flexiq_layer_dump", "flexiq_set_ratio", "flexiq_quantize_act",
             "flexiq_bitlower", "flexiq_dynamic_positions", "flexiq_static_positions", "flexiq_layer_positions",
             "flexiq_input_prelowered", "flexiq_permute_channels", "flexiq_mixed_gemm", "flexiq_mixed_conv_implicit"]
@@ -64,6 +65,12 @@ def load():
     L.flexiq_mixed_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(_Out), C.c_void_p]
     L.flexiq_mixed_conv_implicit.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                              C.c_int32, C.POINTER(_Out), C.c_void_p]
+    L.flexiq_fp6_channels.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+    L.flexiq_fp6_bytes.argtypes = [C.c_void_p, C.c_int64]
+    L.flexiq_fp6_bytes.restype = C.c_int64
+    L.flexiq_lower_fp6.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.flexiq_mixed_gemm_fp6.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(_Out), C.c_void_p]
+    L.flexiq_debug_force_fp6_tile.argtypes = [C.c_int]
     L.flexiq_debug_force_tile.argtypes = [C.c_int]
     L.flexiq_debug_force_packed4.argtypes = [C.c_int]
     L.flexiq_debug_max_blocks.argtypes = [C.c_int]
@@ -220,6 +227,61 @@ def flexiq_permute_channels(layer: Layer, src):
     return dst
 
 
+def flexiq_fp6_channels(layer: Layer) -> int:
+    """Leading stored channels that run on the FP6 matrix path under the current ratio and positions."""
+    k6 = C.c_int32()
+    _check(load().flexiq_fp6_channels(layer._h, C.byref(k6)))
+    return k6.value
+
+
+def flexiq_fp6_bytes(layer: Layer, M: int) -> int:
+    n = load().flexiq_fp6_bytes(layer._h, int(M))
+    if n < 0:
+        _check(int(n))
+    return int(n)
+
+
+def flexiq_lower_fp6(layer: Layer, X, x6=None, need_xlow: Optional[bool] = None):
+    """Stand-alone producer of the FP6 activations: returns (x6, xlow).  xlow is X itself unless some 4-bit channels
+    lie outside the FP6 prefix (then a copy with those channels lowered)."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.int8 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == layer.C
+    M = X.shape[0]
+    if x6 is None:
+        x6 = torch.empty(max(flexiq_fp6_bytes(layer, M), 16), dtype=torch.uint8, device=X.device)
+    k6 = flexiq_fp6_channels(layer)
+    k4 = layer.info()["max_4bit_ch"]
+    if need_xlow is None:
+        need_xlow = k6 < k4
+    xlow = torch.empty_like(X) if need_xlow else None
+    _check(load().flexiq_lower_fp6(layer._h, X.data_ptr(), M, x6.data_ptr(), xlow.data_ptr() if xlow is not None else None,
+                                   _stream()))
+    return x6, (xlow if xlow is not None else X)
+
+
+def flexiq_mixed_gemm_fp6(layer: Layer, X, x6, acc: bool = False, y: bool = False, q: bool = False,
+                          out_scale: float = 1.0, bufs: Optional[dict] = None, lower_for: Optional[Layer] = None,
+                          x6_out=None):
+    """The FP6-variant GEMM.  X: int8 cuda [M][C] (4-bit channels outside the FP6 prefix lowered), x6: FP6 activations.
+    x6_out: with lower_for, the consumer's FP6 activation buffer (flexiq_out.x6)."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.int8 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == layer.C
+    M = X.shape[0]
+    o, res = _outs((M, layer.N), X.device, acc, y, q, out_scale, bufs, lower_for, None)
+    if x6_out is not None:
+        o.x6 = x6_out.data_ptr()
+    _check(load().flexiq_mixed_gemm_fp6(layer._h, X.data_ptr(), x6.data_ptr() if x6 is not None else None, M, C.byref(o),
+                                        _stream()))
+    return res
+
+
+def debug_force_fp6_tile(index: int) -> int:
+    rc = load().flexiq_debug_force_fp6_tile(index)
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
 def _outs(shape, device, want_acc, want_y, want_q, out_scale, bufs, lower_for=None, scan_for=None):
     import torch
     acc = y = q = None
@@ -231,7 +293,7 @@ def _outs(shape, device, want_acc, want_y, want_q, out_scale, bufs, lower_for=No
         q = bufs.get("q") if bufs and "q" in bufs else torch.empty(shape, dtype=torch.int8, device=device)
     o = _Out(acc.data_ptr() if acc is not None else None, y.data_ptr() if y is not None else None,
              q.data_ptr() if q is not None else None, float(out_scale),
-             lower_for._h if lower_for is not None else None, scan_for._h if scan_for is not None else None)
+             lower_for._h if lower_for is not None else None, scan_for._h if scan_for is not None else None, None)
     return o, {"acc": acc, "y": y, "q": q}
 
 

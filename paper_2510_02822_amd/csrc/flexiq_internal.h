@@ -30,6 +30,7 @@ void set_hip_error(hipError_t e, const char *what);
 // Once per device, when the first layer is packed on it: dynamic-LDS limits and occupancy of every kernel of the
 // GEMM shape table, so that a launch is only a launch.
 int prepare_kernels(int device);
+int prepare_fp6_kernels(int device);
 
 // Order hash of a channel permutation (FNV-1a over the 32-bit entries; `n` entries, identity when p == nullptr).
 inline uint64_t order_hash(const int32_t *p, int n)
@@ -49,6 +50,12 @@ inline uint64_t order_hash(const int32_t *p, int n)
 constexpr int kMaxGroups = 159;                       // the kernel keeps the position table of G + 1 groups in LDS
 constexpr int64_t kMaxWeightBytes = 0x7fffffff;       // both int8 weight copies sit behind one buffer descriptor
 
+}  // namespace flexiq
+
+struct flexiq_layer;
+namespace flexiq {
+// Leading channels of the layer that run on the FP6 matrix path under its current ratio and positions (a multiple of 64).
+int fp6_channels(const flexiq_layer *L);
 }  // namespace flexiq
 
 // Device layouts (all offsets in bytes unless noted), T = R*S filter taps, CUp = C/32 rounded up to
@@ -99,4 +106,18 @@ struct flexiq_layer {
     float *d_cs;
     float *d_bias;
     int32_t *d_perm;
+    // FP6 copy of the 4-bit codes of all groups (linear layers with C a multiple of 64; null otherwise), for the variant
+    // whose 4-bit groups run on the FP6 matrix path:
+    //   w6   uint8 [C/64][3][Npad][16]  per K-step of 64 channels three 16-byte planes per output channel: planes 0 and
+    //                                   1 hold the first 16 bytes of the 24-byte FP6 image of units 0 and 1, plane 2 the
+    //                                   last 8 bytes of both (unit h in half h ^ ((n >> 4) & 1)); element e of a unit is
+    //                                   the code of its channel 8 * ((e % 16) / 4) + 4 * (e / 16) + e % 4, as the 6-bit
+    //                                   pattern sign << 5 | |code| (E2M3 value code / 8)
+    //   w6s  uint8 [ceil(C/256)][Npad][2][4]  E8M0 block scales 127 + 3 + w_shift of (output channel, unit 0 / 1 of a K-step)
+    //                                   for four consecutive K-steps: one 32-bit load per lane serves four steps
+    uint8_t *d_w6;
+    uint8_t *d_w6s;
+    // Leading channels whose FP6 accumulation is certified exact (every partial sum below 2^24 in magnitude, from the
+    // packed weights): with the calibrated activation positions, and with any positions (run-time scan).
+    int32_t fp6_limit_static, fp6_limit_dynamic;
 };

@@ -123,6 +123,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     p.x_pre = L->x_prelowered ? 1 : 0;
     p.next_ashift = nullptr; p.next_K4 = 0; p.next_G = 0; p.next_gs_log2 = 5;
     p.next_scan = nullptr; p.next_static = nullptr; p.next_dyn = nullptr; p.next_g4 = 0;
+    if (out->x6) return FLEXIQ_EINVAL;   // FP6 output is written by the FP6-variant kernel only
     if (out->lower_for && out->scan_for) return FLEXIQ_EINVAL;   // lowering needs positions the scan has yet to find
     if (out->lower_for) {
         const flexiq_layer *nx = out->lower_for;

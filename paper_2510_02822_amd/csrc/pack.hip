@@ -143,9 +143,104 @@ __global__ void k_pack_tiles(const int8_t *__restrict__ q, const int32_t *__rest
     px[((int64_t)u * 2 + 1) * Npad + n] = make_uint4(dx[4], dx[5], dx[6], dx[7]);
 }
 
+// FP6 image of the 4-bit codes (linear layers): one thread per (K-step t of 64 channels, padded output channel n)
+// writes the three 16-byte planes and the two block-scale bytes; also sabs[n][g32] = sum over the unit's channels of
+// |code << w_shift|, from which the host certifies exact fp32 accumulation.
+__device__ __forceinline__ uint32_t fp6_pattern(int code) { return (uint32_t)((code < 0 ? 32 : 0) | (code < 0 ? -code : code)); }
+__device__ __forceinline__ int fp6_channel_of_element(int e) { return 8 * ((e % 16) / 4) + 4 * (e / 16) + e % 4; }
+
+__global__ void k_pack_w6(const int8_t *__restrict__ q, const int32_t *__restrict__ perm, const uint8_t *__restrict__ ws_ng,
+                          int N, int C, int gs, int Npad, uint8_t *__restrict__ w6, uint8_t *__restrict__ w6s,
+                          int32_t *__restrict__ sabs)
+{
+    const int S = C / 64;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)S * Npad) return;
+    const int t = (int)(i / Npad), n = (int)(i % Npad);
+    uint32_t tail[4] = {0, 0, 0, 0};
+    for (int h = 0; h < 2; ++h) {
+        const int u = 2 * t + h;
+        uint32_t d[6] = {0, 0, 0, 0, 0, 0};
+        int s = 0, sum = 0;
+        if (n < N) {
+            s = ws_ng[(int64_t)n * (C / gs) + (u * 32) / gs];
+            for (int e = 0; e < 32; ++e) {
+                const int v = q[(int64_t)n * C + perm[u * 32 + fp6_channel_of_element(e)]];
+                const int code = min(7, max(-8, v >> s));
+                sum += (code < 0 ? -code : code) << s;
+                const uint32_t pat = fp6_pattern(code);
+                const int bit = 6 * e;
+                d[bit / 32] |= pat << (bit % 32);
+                if (bit % 32 > 26) d[bit / 32 + 1] |= pat >> (32 - bit % 32);
+            }
+            sabs[(int64_t)n * (C / 32) + u] = sum;
+        }
+        reinterpret_cast<uint4 *>(w6)[((int64_t)t * 3 + h) * Npad + n] = make_uint4(d[0], d[1], d[2], d[3]);
+        const int half = h ^ ((n >> 4) & 1);
+        tail[2 * half] = d[4];
+        tail[2 * half + 1] = d[5];
+        w6s[((((int64_t)(t >> 2) * Npad + n) * 2 + h) << 2) + (t & 3)] = (uint8_t)(127 + 3 + s);
+    }
+    reinterpret_cast<uint4 *>(w6)[((int64_t)t * 3 + 2) * Npad + n] = make_uint4(tail[0], tail[1], tail[2], tail[3]);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Run-time element-wise kernels
 // ---------------------------------------------------------------------------------------------
+
+// Activations for the FP6 variant (Section 4.1 bit-lowering, then the 6-bit pattern of code / 8): one thread per
+// (row, unit of 32 channels) of the leading k6 channels.  Layout of x6: [row / 64][K-step][plane][row % 64][16].
+__global__ void k_lower_fp6(const int8_t *__restrict__ X, int64_t rows, int C, int k6, int gs_shift,
+                            const int32_t *__restrict__ ashift, uint8_t *__restrict__ x6)
+{
+    const int units = k6 / 32, S = C / 64;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * units) return;
+    const int64_t m = i / units;
+    const int u = (int)(i % units), t = u >> 1, h = u & 1;
+    const int s = ashift[u >> gs_shift];
+    const uint4 lo = *reinterpret_cast<const uint4 *>(X + m * C + u * 32), hi = *reinterpret_cast<const uint4 *>(X + m * C + u * 32 + 16);
+    const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    uint32_t d[6] = {0, 0, 0, 0, 0, 0};
+    for (int e = 0; e < 32; ++e) {
+        const int c = fp6_channel_of_element(e);
+        const int v = (int)(int8_t)((w[c >> 2] >> (8 * (c & 3))) & 0xFF);
+        const uint32_t pat = fp6_pattern(min(7, max(-8, v >> s)));
+        const int bit = 6 * e;
+        d[bit / 32] |= pat << (bit % 32);
+        if (bit % 32 > 26) d[bit / 32 + 1] |= pat >> (32 - bit % 32);
+    }
+    const int rr = (int)(m & 63);
+    uint8_t *blk = x6 + ((m >> 6) * (int64_t)S + t) * 3072;
+    *reinterpret_cast<uint4 *>(blk + h * 1024 + rr * 16) = make_uint4(d[0], d[1], d[2], d[3]);
+    *reinterpret_cast<uint2 *>(blk + 2048 + rr * 16 + 8 * (h ^ ((rr >> 4) & 1))) = make_uint2(d[4], d[5]);
+}
+
+// Copy of X in which the channels [c_lo, c_hi) are bit-lowered at their position (L(v, s) << s) and all others are
+// unchanged: 16 channels per thread.
+__global__ void k_lower_int8_range(const int8_t *__restrict__ X, int8_t *__restrict__ Y, int64_t rows, int C, int c_lo,
+                                   int c_hi, int gs_shift, const int32_t *__restrict__ ashift)
+{
+    const int P = C / 16;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * P) return;
+    const int c0 = (int)(i % P) * 16;
+    uint4 v = *reinterpret_cast<const uint4 *>(X + i * 16);
+    if (c0 >= c_lo && c0 < c_hi) {
+        const int s = ashift[(c0 >> 5) >> gs_shift];
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        for (int k = 0; k < 4; ++k) {
+            uint32_t o = 0;
+            for (int b = 0; b < 4; ++b) {
+                const int x = (int)(int8_t)((w[k] >> (8 * b)) & 0xFF);
+                o |= (uint32_t)((min(7, max(-8, x >> s)) * (1 << s)) & 0xFF) << (8 * b);
+            }
+            w[k] = o;
+        }
+        v = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    *reinterpret_cast<uint4 *>(Y + i * 16) = v;
+}
 
 // Extraction positions found at run time (Section 4.1, dynamic option; Section 9 "Finding extraction positions
 // at runtime"): per channel group the magnitude bits of all values (ones' complement for negative ones) are
@@ -322,7 +417,7 @@ struct DevBuf {  // frees on scope exit unless released
 extern "C" int flexiq_layer_free(flexiq_layer *L)
 {
     if (!L) return FLEXIQ_OK;
-    void *bufs[] = {L->d_w8, L->d_w4, L->d_wshift, L->d_ashift, L->d_ashift_dyn, L->d_scan, L->d_cs, L->d_perm};   // d_w4x is the second half of d_w8, d_bias of d_cs
+    void *bufs[] = {L->d_w8, L->d_w4, L->d_wshift, L->d_ashift, L->d_ashift_dyn, L->d_scan, L->d_cs, L->d_perm, L->d_w6, L->d_w6s};   // d_w4x is the second half of d_w8, d_bias of d_cs
     int rc = FLEXIQ_OK;
     for (void *b : bufs)
         if (b && hipFree(b) != hipSuccess) rc = FLEXIQ_EHIP;
@@ -391,9 +486,11 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
     L->has_bias = d->bias != nullptr;
     L->d_w8 = nullptr; L->d_w4 = nullptr; L->d_w4x = nullptr; L->d_wshift = nullptr; L->d_ashift = nullptr; L->d_ashift_dyn = nullptr; L->d_scan = nullptr; L->dynamic = false; L->x_prelowered = false;
     L->d_cs = nullptr; L->d_bias = nullptr; L->d_perm = nullptr;
+    L->d_w6 = nullptr; L->d_w6s = nullptr; L->fp6_limit_static = 0; L->fp6_limit_dynamic = 0;
     FLEXIQ_HIP(hipGetDevice(&L->device));
     {
-        const int rc = prepare_kernels(L->device);
+        int rc = prepare_kernels(L->device);
+        if (rc == FLEXIQ_OK) rc = prepare_fp6_kernels(L->device);
         if (rc != FLEXIQ_OK) return rc;
     }
     L->out_order_hash = order_hash(d->out_perm, N);
@@ -475,6 +572,40 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
     FLEXIQ_HIP(hipGetLastError());
     L->w_shift.resize((size_t)N * G);
     FLEXIQ_HIP(hipMemcpy(L->w_shift.data(), dWsNG.p, (size_t)N * G, hipMemcpyDeviceToHost));
+
+    // FP6 image for the variant whose 4-bit groups run on the FP6 matrix path (linear layers, whole K-steps), and the
+    // certificate of exact fp32 accumulation: with a' = L(x, sa) << sa (|a'| <= 8 << sa) and w' = L(w, sw) << sw, every
+    // partial sum of the leading groups is bounded by sum_g (8 << sa_g) * sum_{k in g} |w'[n][k]|; the FP6 prefix ends
+    // where that bound would reach 2^24 for some output channel (fp32 holds integers exactly below it).
+    if (T == 1 && C % 64 == 0) {
+        const int S = C / 64, U32 = C / 32;
+        DevBuf dSabs;
+        FLEXIQ_HIP(hipMalloc((void **)&L->d_w6, (size_t)S * 3 * Npad * 16));
+        FLEXIQ_HIP(hipMalloc((void **)&L->d_w6s, (size_t)((S + 3) / 4) * Npad * 8));
+        FLEXIQ_HIP(hipMemset(L->d_w6s, 127, (size_t)((S + 3) / 4) * Npad * 8));
+        FLEXIQ_HIP(hipMalloc(&dSabs.p, (size_t)N * U32 * sizeof(int32_t)));
+        k_pack_w6<<<(unsigned)cdiv((int64_t)S * Npad, 256), 256>>>((const int8_t *)dQ.p, L->d_perm, (const uint8_t *)dWsNG.p, N, C, gs,
+                                                                  Npad, L->d_w6, L->d_w6s, (int32_t *)dSabs.p);
+        FLEXIQ_HIP(hipGetLastError());
+        std::vector<int32_t> sabs((size_t)N * U32);
+        FLEXIQ_HIP(hipMemcpy(sabs.data(), dSabs.p, sabs.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+        const int64_t kExact = (int64_t)1 << 24;
+        for (int pass = 0; pass < 2; ++pass) {   // calibrated positions; any positions
+            std::vector<int64_t> run(N, 0);
+            int limit = 0;
+            for (int u = 0; u < U32; ++u) {
+                const int amax = 8 << (pass == 0 ? (int)L->a_shift[(u * 32) / gs] : 4);
+                bool ok = true;
+                for (int n = 0; n < N; ++n) {
+                    run[n] += (int64_t)amax * sabs[(size_t)n * U32 + u];
+                    ok = ok && run[n] < kExact;
+                }
+                if (!ok) break;
+                limit = (u + 1) * 32;
+            }
+            (pass == 0 ? L->fp6_limit_static : L->fp6_limit_dynamic) = limit;
+        }
+    }
 
     std::vector<float> cs(Npad, 0.0f), bias(Npad, 0.0f);
     for (int n = 0; n < N; ++n) cs[n] = d->x_scale * L->w_scale[n];
@@ -652,6 +783,27 @@ extern "C" int flexiq_dynamic_positions_static(flexiq_layer *L, const int8_t *X,
                                                                                     L->d_ashift, L->d_ashift_dyn);
     FLEXIQ_HIP(hipGetLastError());
     L->dynamic = true;
+    return FLEXIQ_OK;
+}
+
+extern "C" int flexiq_lower_fp6(const flexiq_layer *L, const int8_t *X, int64_t M, uint8_t *x6, int8_t *xlow, void *stream)
+{
+    if (!L || M < 0 || !L->d_w6) return FLEXIQ_EINVAL;
+    if (M == 0) return FLEXIQ_OK;
+    const int k6 = fp6_channels(L), k4 = L->max_4bit_ch;
+    if (!X || (k6 > 0 && !x6) || (k6 < k4 && !xlow) || xlow == X) return FLEXIQ_EINVAL;
+    if (!aligned16(X) || !aligned16(x6) || !aligned16(xlow)) return FLEXIQ_EALIGN;
+    const int32_t *pos = L->dynamic ? L->d_ashift_dyn : L->d_ashift;
+    const int gs_shift = L->group_size == 64 ? 1 : 0;
+    if (k6 > 0) {
+        const int64_t threads = M * (k6 / 32);
+        k_lower_fp6<<<(unsigned)cdiv(threads, 256), 256, 0, (hipStream_t)stream>>>(X, M, L->C, k6, gs_shift, pos, x6);
+    }
+    if (xlow) {
+        const int64_t threads = M * (L->C / 16);
+        k_lower_int8_range<<<(unsigned)cdiv(threads, 256), 256, 0, (hipStream_t)stream>>>(X, xlow, M, L->C, k6, k4, gs_shift, pos);
+    }
+    FLEXIQ_HIP(hipGetLastError());
     return FLEXIQ_OK;
 }
 
