@@ -4,18 +4,23 @@
 Workload (BASELINE.json `metric`: "... vs low-bit ratio r (ViT-B fc1)", configs[1]): the ViT-B/16
 MLP fc1 linear at batch 32, M = 32*197 = 6304 tokens, K = 768, N = 3072, channel group size 32.
 One step = one pass of the run-time hot path over the ratio sweep r in {0, .25, .5, .75, 1}: per
-ratio the O(1) ratio switch, then the mixed 4/8-bit MFMA GEMM with on-the-fly bit-lowering of
-the activations, in-register expansion of the packed 4-bit weights and the fused per-channel
-dequant + int8 requant epilogue.  Inputs (int8 activations in stored channel order, packed layer)
-are resident in HBM before the timed region; the offline steps (weight quantisation, channel
-order, positions, packing) run once before it, as in the paper.
+ratio the O(1) ratio switch, then the mixed 4/8-bit int8-MFMA GEMM with on-the-fly bit-lowering of
+the activations, the weights of 4-bit groups streamed from their position-expanded int8 copy (one
+byte per weight: on this route r saves no bytes), and the fused per-channel dequant + int8 requant
+epilogue.  Inputs (int8 activations in stored channel order, packed layer) are resident in HBM
+before the timed region; the offline steps (weight quantisation, channel order, positions, packing)
+run once before it, as in the paper.
 
 Prints ONE JSON line.  `value` = total int8 ops of the K timed steps / wall time (TOPS).
 The default step and warm-up counts keep the GPU busy for a few tenths of a second: the card needs tens of
 milliseconds of work to settle at its running clocks, and a short timed region after a cold start reads about 4 %
 low; for the same reason about 50 ms of untimed steps run before the requested warm-up steps.
 `roofline` covers the GEMM kernel (the only kernel in the timed region): algorithmic ops per launch
-= 2*M*N*K, average launch duration = HIP-event time of the timed region / launches in it.  `cpu_baseline` times the CPU oracle on a bounded row sample of the same workload.
+= 2*M*N*K, average launch duration = HIP-event time of the timed region / launches in it.  `cpu_baseline` times the
+CPU oracle on a bounded row sample of the same workload.  `shapes` (after the timed region, not part of `value`)
+carries the other workloads of the benchmark spec: ViT-B fc2, ViT-L fc1 / fc2 (int8 kernel and the FP6 variant of the
+4-bit phase), fc1 -> fc2 chains, the 3x3 convolution, the ResNet-50 pass with the seeded ratio schedule, few-row
+calls, the residual reorder operator and a plain 2 GiB device copy as the HBM ceiling.
 """
 from __future__ import annotations
 
@@ -45,10 +50,230 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(M, N, K, r, out_bytes_per_elem=1):
-    """Bytes one call must move: int8 activations, weights (1 B per 8-bit channel, 1/2 B per 4-bit
-    channel when the packed codes are streamed), position table and scales, output."""
-    return M * K + N * K * (1.0 - r / 2.0) + N * (K // 32) + 8 * N + M * N * out_bytes_per_elem
+def algorithmic_bytes(M, N, K, r, out_bytes_per_elem=1, weight_route="w4x"):
+    """Bytes one call must move: int8 activations, weights, position table and scales, output.  Weights of 4-bit
+    groups: one byte each on the route that streams the position-expanded copy (`w4x`, the int8 kernel's default),
+    half a byte when the packed codes are streamed (`w4`), 3/4 byte as FP6 (`w6`; activations of those groups too)."""
+    wb = {"w4x": 1.0, "w4": 0.5, "w6": 0.75}[weight_route]
+    xb = 0.75 if weight_route == "w6" else 1.0
+    return M * K * (1.0 - r + r * xb) + N * K * (1.0 - r + r * wb) + N * (K // 32) + 8 * N + M * N * out_bytes_per_elem
+
+
+def _median_graph_us(torch, fn, launches, repeats=5, settle_s=0.02):
+    """Median microseconds per launch of `fn`, captured `launches` times into a HIP graph."""
+    fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(launches):
+            fn()
+    t_end = time.perf_counter() + settle_s
+    while time.perf_counter() < t_end:
+        g.replay()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(repeats):
+        a0 = torch.cuda.Event(enable_timing=True)
+        a1 = torch.cuda.Event(enable_timing=True)
+        a0.record()
+        g.replay()
+        a1.record()
+        torch.cuda.synchronize()
+        ts.append(a0.elapsed_time(a1) * 1e3 / launches)
+    del g
+    return float(np.median(ts))
+
+
+def _calib(case):
+    Xc = case.Xcal.reshape(-1, case.Xcal.shape[-1])
+    amax = np.abs(Xc).max(0)
+    return float(np.float32(amax.max()) / np.float32(127.0)), amax
+
+
+def measure_shapes(torch, fq, workloads, dev, resnet=True):
+    """The other workloads of the benchmark spec (not in `value`): one compact record per (workload, variant, r)."""
+    out = []
+
+    def rec(workload, variant, r, us, ops=None, byts=None, **kw):
+        e = {"workload": workload, "variant": variant, "r": r, "us": round(us, 2)}
+        if ops is not None:
+            e["tops"] = round(ops / us / 1e6, 1)
+            e["frac_mfma_peak"] = round(ops / us / 1e6 / INT8_MFMA_PEAK_TOPS, 4)
+        if byts is not None:
+            e["GBs"] = round(byts / us / 1e3, 1)
+            e["frac_hbm_peak"] = round(byts / us / 1e3 / HBM_PEAK_GBS, 4)
+        e["bound"] = kw.pop("bound", "mfma" if ops is not None else "hbm")
+        e.update(kw)
+        out.append(e)
+        log("shapes:", e)
+
+    # ---- HBM ceiling: a plain 2 GiB device copy
+    n = 2 << 30
+    src = torch.empty(n, dtype=torch.int8, device=dev)
+    dst = torch.empty_like(src)
+    src.fill_(1)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(5):
+        a0 = torch.cuda.Event(enable_timing=True)
+        a1 = torch.cuda.Event(enable_timing=True)
+        a0.record()
+        dst.copy_(src)
+        a1.record()
+        torch.cuda.synchronize()
+        ts.append(a0.elapsed_time(a1) * 1e3)
+    rec("device copy 2 GiB (read + write)", "copy", None, float(np.median(ts)), byts=2.0 * n)
+    del src, dst
+
+    # ---- linear layers at full size
+    packed = {}
+    for name, mk, which in (("vitb_fc1", workloads.config1, "fc1"), ("vitb_fc2", workloads.config1, "fc2"), ("vitl_fc1", workloads.config3, "fc1"),
+                            ("vitl_fc2", workloads.config3, "fc2")):
+        case = mk(which)
+        M, K, N = case.M, case.K, case.N
+        x_scale, amax = _calib(case)
+        layer = fq.flexiq_quantize_pack(case.W, amax, x_scale, case.group_size, bias=case.bias)
+        Xn = fq.flexiq_quantize_act(torch.from_numpy(case.X).to(dev), x_scale)
+        Xq = fq.flexiq_permute_channels(layer, Xn)
+        if name == "vitl_fc2":      # the residual reorder operator (Section 5 step 3) on the largest activation tensor
+            us = _median_graph_us(torch, lambda: fq.flexiq_permute_channels(layer, Xn), 10)
+            rec("channel reorder %d x %d int8" % (M, K), "permute_channels", None, us, byts=2.0 * M * K)
+        del Xn
+        fq.flexiq_set_ratio(layer, 0.0)
+        y0 = fq.flexiq_mixed_gemm(layer, Xq, y=True)["y"]
+        so = float(y0.abs().max().item() / 127.0)
+        del y0
+        bufs = {"q": torch.empty((M, N), dtype=torch.int8, device=dev)}
+        ops = 2.0 * M * N * K
+        wl = "%s M=%d K=%d N=%d gs=%d" % (name, M, K, N, case.group_size)
+        for r in (0.0, 0.5, 1.0):
+            fq.flexiq_set_ratio(layer, r)
+            us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm(layer, Xq, q=True, out_scale=so, bufs=bufs), 10)
+            rec(wl, "int8 kernel, activations lowered on the fly", r, us, ops=ops)
+            x6, xlow = fq.flexiq_lower_fp6(layer, Xq)
+            us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm_fp6(layer, xlow, x6, q=True, out_scale=so, bufs=bufs), 10)
+            rec(wl, "FP6 variant of the 4-bit phase, activations packed by the producer", r, us, ops=ops,
+                fp6_channels=fq.flexiq_fp6_channels(layer))
+            if r > 0:
+                us = _median_graph_us(torch, lambda: fq.flexiq_lower_fp6(layer, Xq, x6=x6, need_xlow=False), 10)
+                rec(wl, "stand-alone FP6 lowering kernel (when no producer packs)", r, us,
+                    byts=M * K * r * 1.75)
+            del x6, xlow
+        packed[name] = (case, layer, Xq, so, x_scale)
+        del bufs
+
+    # ---- ViT-L fc1 -> fc2 chain (fc1 writes fc2's input; in the model a GELU sits between them, outside this path)
+    c1, l1_plain, X1, so1, xs1 = packed["vitl_fc1"]
+    c2 = packed["vitl_fc2"][0]
+    M = c1.M
+    am2 = np.full(c2.K, 127.0 * so1, np.float32)
+    l2 = fq.flexiq_quantize_pack(c2.W, am2, so1, c2.group_size, bias=c2.bias)
+    l1 = fq.flexiq_quantize_pack(c1.W, _calib(c1)[1], xs1, c1.group_size, bias=c1.bias, out_perm=l2.info()["perm"])
+    mid = {"q": torch.empty((M, c1.N), dtype=torch.int8, device=dev)}
+    fin = {"q": torch.empty((M, c2.N), dtype=torch.int8, device=dev)}
+    x6_2 = torch.empty(fq.flexiq_fp6_bytes(l2, M), dtype=torch.uint8, device=dev)
+    ops2 = 2.0 * M * (c1.N * c1.K + c2.N * c2.K)
+    for r in (0.0, 0.5, 1.0):
+        fq.flexiq_set_ratio(l1, r)
+        fq.flexiq_set_ratio(l2, r)
+
+        def chain_plain():
+            fq.flexiq_mixed_gemm(l1, X1, q=True, out_scale=so1, bufs=mid)
+            fq.flexiq_mixed_gemm(l2, mid["q"], q=True, out_scale=so1, bufs=fin)
+
+        def chain_lowered():
+            fq.flexiq_mixed_gemm(l1, X1, q=True, out_scale=so1, bufs=mid, lower_for=l2)
+            fq.flexiq_mixed_gemm(l2, mid["q"], q=True, out_scale=so1, bufs=fin)
+
+        x6_1, xlow_1 = fq.flexiq_lower_fp6(l1, X1)
+
+        def chain_fp6():
+            fq.flexiq_mixed_gemm_fp6(l1, xlow_1, x6_1, q=True, out_scale=so1, bufs=mid, lower_for=l2, x6_out=x6_2)
+            fq.flexiq_mixed_gemm_fp6(l2, mid["q"], x6_2, q=True, out_scale=so1, bufs=fin)
+
+        wl = "vitl fc1 -> fc2 chain, M=%d" % M
+        rec(wl, "int8 kernels, consumer lowers on the fly", r, _median_graph_us(torch, chain_plain, 5), ops=ops2)
+        fq.flexiq_input_prelowered(l2, True)
+        rec(wl, "int8 kernels, producer lowers for the consumer", r, _median_graph_us(torch, chain_lowered, 5), ops=ops2)
+        fq.flexiq_input_prelowered(l2, False)
+        rec(wl, "FP6 variant, producer packs the consumer's FP6 activations", r, _median_graph_us(torch, chain_fp6, 5), ops=ops2)
+        del x6_1, xlow_1
+    del l1, l2, mid, fin, x6_2
+
+    # ---- few-row calls (weight streaming): ViT-L layers with M in {1, 16, 64}
+    for name in ("vitl_fc1", "vitl_fc2"):
+        case, layer, Xq, so, _ = packed[name]
+        for Ms in (1, 16, 64):
+            Xs = Xq[:Ms].contiguous()
+            bufs = {"q": torch.empty((Ms, case.N), dtype=torch.int8, device=dev)}
+            ws = fq.flexiq_small_m_workspace(layer, dev)
+            for r in (0.0, 0.5, 1.0):
+                fq.flexiq_set_ratio(layer, r)
+                for tag, kw in (("tiled kernel", {}), ("with a workspace (split-K kernel where it pays)", {"workspace": ws})):
+                    us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=so, bufs=bufs, **kw), 20)
+                    launch = fq.debug_last_launch()
+                    route = "w4" if launch["tile"] < 0 else "w4x"     # the split-K kernel streams the packed 4-bit codes
+                    rec("%s weights %d x %d, M=%d rows" % (name, case.N, case.K, Ms), "few-row call, " + tag, r, us,
+                        byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, route), launch=launch)
+            del ws
+    packed.clear()
+
+    # ---- configuration 2: 3x3 convolution 256 -> 256 at 14 x 14, batch 64
+    def conv_bytes(case, r):
+        Mo = case.B * case.Ho * case.Wo
+        pixels = case.Ho * case.Wo if case.R == 1 and case.S == 1 else case.H * case.Wd   # a strided 1x1 reads only its pixels
+        return case.B * pixels * case.C + case.N * case.R * case.S * case.C + Mo * case.N
+
+    def prepare_conv(case):
+        x_scale, amax = _calib(case)
+        layer = fq.flexiq_quantize_pack(case.W, amax, x_scale, case.group_size, bias=case.bias)
+        Xq = fq.flexiq_permute_channels(layer, fq.flexiq_quantize_act(torch.from_numpy(case.X).to(dev), x_scale))
+        fq.flexiq_set_ratio(layer, 0.0)
+        y0 = fq.flexiq_mixed_conv_implicit(layer, Xq, case.stride, case.pad, y=True)["y"]
+        so = float(y0.abs().max().item() / 127.0)
+        return layer, Xq, so
+
+    case = workloads.config2()
+    layer, Xq, so = prepare_conv(case)
+    q = {"q": torch.empty((case.B, case.Ho, case.Wo, case.N), dtype=torch.int8, device=dev)}
+    Mo, Kc = case.B * case.Ho * case.Wo, case.R * case.S * case.C
+    for r in (0.0, 0.5, 1.0):
+        fq.flexiq_set_ratio(layer, r)
+        us = _median_graph_us(torch, lambda: fq.flexiq_mixed_conv_implicit(layer, Xq, case.stride, case.pad, q=True, out_scale=so, bufs=q), 10)
+        rec("cfg2 conv 3x3 256->256 @14x14 batch 64 (M=%d K=%d N=%d)" % (Mo, Kc, case.N), "int8 kernel, implicit GEMM", r, us,
+            ops=2.0 * Mo * case.N * Kc)
+    del layer, Xq, q, case
+
+    # ---- configuration 4: ResNet-50 stages 1-4, batch 128; every layer packed once, buffers of its own (1.3 GB per
+    # pass: the cold regime), the ratio drawn per call from the seeded schedule, against passes at fixed ratios
+    if resnet:
+        layers = []
+        for i, sh in enumerate(workloads.resnet50_shapes()):
+            case = workloads.config4_layer(i, B=128)
+            layer, Xq, so = prepare_conv(case)
+            outs = [torch.empty((case.B, case.Ho, case.Wo, case.N), dtype=torch.int8, device=dev) for _ in range(sh.count)]
+            layers.append({"count": sh.count, "layer": layer, "X": Xq, "so": so, "outs": outs, "stride": case.stride, "pad": case.pad,
+                           "ops": 2.0 * case.B * case.Ho * case.Wo * case.N * case.R * case.S * case.C, "bytes": conv_bytes(case, 0)})
+            del case
+        calls = [(L, j) for L in layers for j in range(L["count"])]
+        sched = workloads.config4_ratio_schedule(len(calls))
+        ops = sum(L["ops"] for L, _ in calls)
+        byts = sum(L["bytes"] for L, _ in calls)
+
+        def one_pass(ratio_of_call):
+            for c, (L, j) in enumerate(calls):
+                fq.flexiq_set_ratio(L["layer"], float(ratio_of_call(c)))
+                fq.flexiq_mixed_conv_implicit(L["layer"], L["X"], L["stride"], L["pad"], q=True, out_scale=L["so"], bufs={"q": L["outs"][j]})
+
+        wl = "cfg4 ResNet-50 stages 1-4, batch 128: %d convolutions, %.0f GOP per pass, cold buffers" % (len(calls), ops / 1e9)
+        for tag, fn in (("fixed r", lambda c: 0.0), ("fixed r", lambda c: 0.5), ("fixed r", lambda c: 1.0),
+                        ("seeded per-call ratio schedule (mean r = %.2f)" % float(sched.mean()), lambda c: sched[c])):
+            us = _median_graph_us(torch, lambda: one_pass(fn), 1, repeats=5, settle_s=0.04)
+            rec(wl, "int8 kernel, " + tag, float(fn(0)) if tag == "fixed r" else None, us, ops=ops, GBs=round(byts / us / 1e3, 1),
+                frac_hbm_peak=round(byts / us / 1e3 / HBM_PEAK_GBS, 4), bound="mixed (mfma / hbm per layer)")
+        del layers, calls
+    return out
 
 
 def main():
@@ -60,6 +285,8 @@ def main():
     ap.add_argument("--out", default="q", choices=["q", "y", "acc"], help="epilogue output written in the timed region")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the workload the CPU oracle is timed on (0: skip)")
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of replaying a captured HIP graph")
+    ap.add_argument("--no-shapes", action="store_true", help="skip the side measurements of the other workloads (`shapes`)")
+    ap.add_argument("--no-resnet", action="store_true", help="skip the ResNet-50 pass inside `shapes`")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed region run one plain device copy of this many MiB (reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -234,12 +461,14 @@ def main():
 
     # the same scan done by the producing layer's own epilogue (flexiq_out.scan_for): this layer as the producer of
     # a small consumer with C = N input channels; the chain producer -> consumer with and without the scan (the
-    # consumer turns the masks into positions in its prologue and clears the other mask set).  Side measurement.
+    # producer's last block turns the merged masks into the consumer's positions).  Side measurement.
     fused_scan = None
     if args.out == "q":
         rng2 = np.random.default_rng(7)
         W2 = (rng2.standard_normal((32, N)) * 0.02).astype(np.float32)
-        cons = fq.flexiq_quantize_pack(W2, np.full(N, 127.0 * out_scale, np.float32), float(out_scale), 32)
+        # (the consumer reads its channels in the order this layer writes its columns: identity)
+        cons = fq.flexiq_quantize_pack(W2, np.full(N, 127.0 * out_scale, np.float32), float(out_scale), 32,
+                                       perm=np.arange(N, dtype=np.int32))
         fq.flexiq_set_ratio(cons, 1.0)
         fq.flexiq_set_ratio(layer, 0.5)
         cbufs = {"q": torch.empty((M, 32), dtype=torch.int8, device=dev)}
@@ -286,7 +515,7 @@ def main():
         us = per_r_us[r]
         per_r.append({"r": r, "us": round(us, 2), "tops": round(ops_call / us / 1e6, 1),
                       "frac_int8_mfma_peak": round(ops_call / us / 1e6 / INT8_MFMA_PEAK_TOPS, 4),
-                      "algorithmic_GBs": round(algorithmic_bytes(M, N, K, r, out_bytes) / us / 1e3, 1)})
+                      "algorithmic_GBs": round(algorithmic_bytes(M, N, K, r, out_bytes, "w4x") / us / 1e3, 1)})
     avg_us = dev_us / (args.steps * len(RATIOS))
     achieved = ops_call / avg_us / 1e6 if avg_us else value
     roofline = {"bound": "mfma", "kernel": "flexiq::k_mixed (int8 MFMA mixed GEMM)", "achieved": round(achieved, 1),
@@ -324,6 +553,14 @@ def main():
         parity = "int32 accumulators bit-exact with the oracle on %d rows x %d ratios" % (rows, len(RATIOS)) if ok \
             else "MISMATCH against the oracle"
 
+    shapes = None
+    if not args.no_shapes:
+        del layer, Xq, bufs
+        torch.cuda.empty_cache()
+        t_sh = time.time()
+        shapes = measure_shapes(torch, fq, workloads, dev, resnet=not args.no_resnet)
+        log("shapes: %.0f s" % (time.time() - t_sh))
+
     line = {
         "metric": METRIC, "value": round(value, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(wall / args.steps * 1e3, 4), "higher_is_better": True,
@@ -333,6 +570,7 @@ def main():
                                                           {"q": "int8 requant", "y": "fp32 dequant", "acc": "int32 dump"}[args.out]),
                    "M": M, "K": K, "N": N, "group_size": gs, "ratios": list(RATIOS), "steps_per_graph": chunk},
         "roofline": roofline, "cpu_baseline": cpu, "per_r": per_r, "prelowered_input": pre, "dynamic_positions": dyn, "fused_scan": fused_scan, "ratio_switch": ratio_switch, "parity": parity,
+        "shapes": shapes,
     }
     print(json.dumps(line), flush=True)
 

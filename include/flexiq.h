@@ -180,7 +180,16 @@ int flexiq_permute_channels(const flexiq_layer *layer, const int8_t *src, int8_t
  *   x6        : optional, only with lower_for and only for flexiq_mixed_gemm_fp6 (FLEXIQ_EINVAL elsewhere): the
  *               consumer's FP6 activation buffer (flexiq_fp6_bytes(consumer, M) bytes).  The columns that are FP6
  *               channels of the consumer (flexiq_fp6_channels) are then written there as FP6 codes instead of into q;
- *               q keeps the other columns (those of its remaining 4-bit channels lowered).  Needs N % 64 == 0 */
+ *               q keeps the other columns (those of its remaining 4-bit channels lowered).  Needs N % 64 == 0
+ *   workspace, workspace_bytes : optional.  Device memory (16-byte aligned, at least
+ *               flexiq_small_m_workspace_bytes(layer) bytes, ZERO when first handed in) that lets flexiq_mixed_gemm
+ *               serve calls of at most 64 rows with the split-K kernel: the reduction is cut into slices across
+ *               blocks so that every compute unit streams its share of the weights (4-bit groups from the packed
+ *               4-bit codes: half the bytes, Section 7), partial sums meet in the workspace and the block that arrives
+ *               last per 128 output columns adds them up and runs the epilogue.  The call leaves the first 128 KB (its
+ *               tickets) zero again, so one workspace serves any sequence of calls on one stream; calls that overlap
+ *               on one workspace race.  Ignored (the tiled kernel runs) for more than 64 rows, for convolutions, with
+ *               lower_for / scan_for, or when it is NULL or too small */
 typedef struct {
     int32_t *acc;
     float *y;
@@ -189,6 +198,8 @@ typedef struct {
     const flexiq_layer *lower_for;
     flexiq_layer *scan_for;
     uint8_t *x6;
+    void *workspace;
+    int64_t workspace_bytes;
 } flexiq_out;
 
 /* Mixed-precision GEMM (Sections 2.3, 7):
@@ -202,6 +213,9 @@ typedef struct {
  * kernel has run.  Errors: FLEXIQ_EINVAL (null / inconsistent arguments, M >= 2^31 - 512, more than 159 channel
  * groups, a padded weight matrix of 1 GiB or more, current device is not the handle's), FLEXIQ_EALIGN, FLEXIQ_EHIP. */
 int flexiq_mixed_gemm(const flexiq_layer *layer, const int8_t *X, int64_t M, const flexiq_out *out, void *stream);
+
+/* Bytes of flexiq_out.workspace that serve any few-row call on this layer (negative flexiq_status on error). */
+int64_t flexiq_small_m_workspace_bytes(const flexiq_layer *layer);
 
 /* The same sum as an implicit GEMM over (filter tap, channel) for a convolution layer:
  * X: dev int8 NHWC [B][H][W][C], stored channel order, zero padding `pad`, stride `stride`;

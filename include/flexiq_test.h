@@ -29,6 +29,9 @@ int flexiq_debug_max_blocks(int n);
  * 2: blocks of that kernel resident per compute unit, 3: split-K slices (1 = the tiled kernel). */
 int flexiq_debug_last_launch(int which);
 
+/* Slices of the split-K kernel for few-row calls: n > 0 forces n slices (capped by the reduction length), 0 = automatic. */
+int flexiq_debug_force_splits(int n);
+
 /* Force tile shape `index` of the FP6-variant kernel's table (-1 = automatic).  Returns the table size. */
 int flexiq_debug_force_fp6_tile(int index);
 

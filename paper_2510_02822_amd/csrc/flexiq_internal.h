@@ -56,6 +56,10 @@ struct flexiq_layer;
 namespace flexiq {
 // Leading channels of the layer that run on the FP6 matrix path under its current ratio and positions (a multiple of 64).
 int fp6_channels(const flexiq_layer *L);
+// Split-K kernel for linear calls of at most 64 rows (smallm.hip).
+int64_t small_m_workspace_bytes(const flexiq_layer *L);
+int launch_small_m(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int force_splits,
+                   int *splits_out);
 }  // namespace flexiq
 
 // Device layouts (all offsets in bytes unless noted), T = R*S filter taps, CUp = C/32 rounded up to
