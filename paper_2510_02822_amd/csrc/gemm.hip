@@ -19,7 +19,7 @@ static const TileShape *shapes(int *count)
     static const TileShape tab[kNumTileShapes] = {tile_shape_0(), tile_shape_1(), tile_shape_2(), tile_shape_3(),
                                                   tile_shape_4(), tile_shape_5(), tile_shape_6(), tile_shape_7(),
                                                   tile_shape_8(), tile_shape_9(), tile_shape_10(), tile_shape_11(),
-                                                  tile_shape_12()};
+                                                  tile_shape_12(), tile_shape_13()};
     *count = kNumTileShapes;
     return tab;
 }

@@ -1125,7 +1125,7 @@ inline TileShape make_shape(double step_alone, double share, double epilogue, do
 }
 
 // Shape i of the table, defined in mixed_tile.hip built with -DFQ_TILE=i.
-constexpr int kNumTileShapes = 13;
+constexpr int kNumTileShapes = 14;
 TileShape tile_shape_0();
 TileShape tile_shape_1();
 TileShape tile_shape_2();
@@ -1139,5 +1139,6 @@ TileShape tile_shape_9();
 TileShape tile_shape_10();
 TileShape tile_shape_11();
 TileShape tile_shape_12();
+TileShape tile_shape_13();
 
 }  // namespace flexiq

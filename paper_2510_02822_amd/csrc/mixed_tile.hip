@@ -3,7 +3,7 @@
 #include "mixed_kernel.h"
 
 #ifndef FQ_TILE
-#error "compile with -DFQ_TILE=<0..12>"
+#error "compile with -DFQ_TILE=<0..13>"
 #endif
 
 namespace flexiq {
@@ -37,6 +37,8 @@ TileShape tile_shape_10() { return make_shape<1, 8, 5, 1>(835.0, 0.00, 2900.0, 4
 TileShape tile_shape_11() { return make_shape<1, 8, 7, 1>(1125.0, 0.00, 4800.0, 260.0); }  // 224 x 256, eight waves
 #elif FQ_TILE == 12
 TileShape tile_shape_12() { return make_shape<2, 4, 5, 2>(1500.0, 0.0, 6000.0, 420.0); }   // 320 x 256, eight waves
+#elif FQ_TILE == 13
+TileShape tile_shape_13() { return make_shape<1, 8, 3, 1>(770.0, 0.0, 2500.0, 245.0); }    //  96 x 256, eight waves
 #else
 #error "FQ_TILE out of range"
 #endif
