@@ -276,6 +276,52 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
     return out
 
 
+PROFILE_TARGETS = ("vitl_fc2", "vitl_fc2_fp6", "vitl_fc2_rows16", "reorder", "resnet_1x1_64_256", "resnet_3x3_64_64")
+
+
+def profile_only(torch, fq, workloads, dev, what, launches):
+    """A short eager run of ONE side workload, for rocprofv3 (no headline, no oracle): `launches` launches per ratio in
+    the order r = 0, 0.5, 1 (the kernel trace lists dispatches in launch order), one copy of `--calib-copy-mib` after."""
+    res = {"profile_only": what, "launches_per_ratio": launches, "ratios": [0.0, 0.5, 1.0]}
+    if what.startswith("resnet_"):
+        idx = {"resnet_1x1_64_256": 2, "resnet_3x3_64_64": 1}[what]
+        case = workloads.config4_layer(idx, B=128)
+        x_scale, amax = _calib(case)
+        layer = fq.flexiq_quantize_pack(case.W, amax, x_scale, case.group_size, bias=case.bias)
+        Xq = fq.flexiq_permute_channels(layer, fq.flexiq_quantize_act(torch.from_numpy(case.X).to(dev), x_scale))
+        q = {"q": torch.empty((case.B, case.Ho, case.Wo, case.N), dtype=torch.int8, device=dev)}
+        res["workload"] = "%s batch 128: M=%d K=%d N=%d" % (case.name, case.B * case.Ho * case.Wo, case.R * case.S * case.C, case.N)
+        call = lambda: fq.flexiq_mixed_conv_implicit(layer, Xq, case.stride, case.pad, q=True, out_scale=0.05, bufs=q)
+    else:
+        case = workloads.config3("fc2")
+        x_scale, amax = _calib(case)
+        layer = fq.flexiq_quantize_pack(case.W, amax, x_scale, case.group_size, bias=case.bias)
+        Xn = fq.flexiq_quantize_act(torch.from_numpy(case.X).to(dev), x_scale)
+        Xq = fq.flexiq_permute_channels(layer, Xn)
+        rows = 16 if what == "vitl_fc2_rows16" else case.M
+        Xs = Xq[:rows].contiguous()
+        q = {"q": torch.empty((rows, case.N), dtype=torch.int8, device=dev)}
+        res["workload"] = "%s M=%d K=%d N=%d gs=%d" % (case.name, rows, case.K, case.N, case.group_size)
+        if what == "vitl_fc2":
+            call = lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=0.05, bufs=q)
+        elif what == "vitl_fc2_rows16":
+            ws = fq.flexiq_small_m_workspace(layer, dev)
+            call = lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=0.05, bufs=q, workspace=ws)
+        elif what == "reorder":
+            call = lambda: fq.flexiq_permute_channels(layer, Xn)
+        else:
+            call = None   # FP6 variant: the operands depend on the ratio
+    for r in res["ratios"]:
+        fq.flexiq_set_ratio(layer, r)
+        if what == "vitl_fc2_fp6":
+            x6, xlow = fq.flexiq_lower_fp6(layer, Xq)
+            call = lambda: fq.flexiq_mixed_gemm_fp6(layer, xlow, x6, q=True, out_scale=0.05, bufs=q)
+        for _ in range(launches):
+            call()
+        torch.cuda.synchronize()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -287,6 +333,8 @@ def main():
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of replaying a captured HIP graph")
     ap.add_argument("--no-shapes", action="store_true", help="skip the side measurements of the other workloads (`shapes`)")
     ap.add_argument("--no-resnet", action="store_true", help="skip the ResNet-50 pass inside `shapes`")
+    ap.add_argument("--profile-only", default=None, choices=PROFILE_TARGETS,
+                    help="run only this side workload, eagerly, --steps launches per ratio in {0, 0.5, 1} (for rocprofv3)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed region run one plain device copy of this many MiB (reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -304,6 +352,18 @@ def main():
     fq.load()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.profile_only:
+        res = profile_only(torch, fq, workloads, dev, args.profile_only, args.steps)
+        if args.calib_copy_mib > 0:
+            n = args.calib_copy_mib << 20
+            src = torch.ones(n, dtype=torch.int8, device=dev)
+            dst = torch.empty_like(src)
+            dst.copy_(src)
+            torch.cuda.synchronize()
+            res["calib_copy_bytes"] = n
+        print(json.dumps(res), flush=True)
+        return
 
     t0 = time.time()
     case = workloads.config1(args.layer)

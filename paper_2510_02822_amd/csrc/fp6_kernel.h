@@ -138,13 +138,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void k_fp6(const Params 
     __builtin_assume(wave >= 0 && wave < NW);
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
-    // ---- tile of this block.  Consecutive block ids land on different XCDs (each with its own L2): renumber so that
-    // the blocks of an XCD work on neighbouring tiles; inside a band of 8 tile rows the tile column varies slowest.
-    const int total = p.tiles_m * p.tiles_n;
+    // ---- tile of this block.  Consecutive block ids land on different XCDs (each with its own L2), and inside a band
+    // of 8 tile rows the tile column varies slowest: XCD x then computes tile row x of every band in all its columns,
+    // so an activation row is fetched into one L2 only (every L2 needs the whole weight matrix in any case).
     int tile_m, tile_n;
     {
-        uint32_t b = blockIdx.x;
-        if (total % 8 == 0) b = (b % 8) * (uint32_t)(total / 8) + b / 8;
+        const uint32_t b = blockIdx.x;
         const uint32_t band_sz = 8u * (uint32_t)p.tiles_n;
         const uint32_t band = b / band_sz, r = b - band * band_sz;
         const uint32_t rows_here = min(8u, (uint32_t)p.tiles_m - band * 8u);

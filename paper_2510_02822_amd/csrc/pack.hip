@@ -356,19 +356,61 @@ __global__ void k_bitlower(const int8_t *__restrict__ src, uint8_t *__restrict__
     *reinterpret_cast<uint32_t *>(dst + row * (C / 2) + c0 / 2) = out;
 }
 
-// Residual reorder operator (Section 5, step 3): dst[row][j] = src[row][perm[j]], four bytes per thread.
-__global__ void k_permute_channels(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
-                                   const int32_t *__restrict__ perm, int64_t rows, int C)
+// Residual reorder operator (Section 5, step 3): dst[row][j] = src[row][perm[j]].  Rows are a multiple of 32 bytes and
+// at most 159 groups long (checked when the layer is packed).  A block copies a run of whole rows into LDS with
+// coalesced 16-byte loads and gathers from there, so that every input byte leaves HBM once; a
+// thread owns the same 16-byte output piece(s) of every row and keeps their sixteen source indices in registers
+// (packed in pairs).  NP = pieces per thread: 1 for rows of up to 4096 bytes (several rows per pass then), else the
+// row's pieces are dealt out over the 256 threads.
+template <int NP>
+__global__ __launch_bounds__(256) void k_permute_rows(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
+                                                      const int32_t *__restrict__ perm, int64_t rows, int C)
 {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int C4 = C / 4;
-    if (i >= rows * C4) return;
-    int64_t row = i / C4;
-    int j0 = (int)(i % C4) * 4;
-    const int8_t *s = src + row * C;
-    uint32_t w = (uint32_t)(uint8_t)s[perm[j0]] | ((uint32_t)(uint8_t)s[perm[j0 + 1]] << 8) |
-                 ((uint32_t)(uint8_t)s[perm[j0 + 2]] << 16) | ((uint32_t)(uint8_t)s[perm[j0 + 3]] << 24);
-    *reinterpret_cast<uint32_t *>(dst + row * C + j0) = w;
+    extern __shared__ __align__(16) uint8_t stage[];
+    const int P = C >> 4;                              // 16-byte pieces per row
+    const int t = threadIdx.x;
+    const int RP = NP == 1 ? 256 / P : 1;              // rows per pass over the staged run
+    const int RB = 4 * RP;                             // rows per run
+    const int slot_row = NP == 1 ? t / P : 0;
+    const bool active = NP > 1 || slot_row < RP;
+    uint32_t pp[NP][8];
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const int piece = NP == 1 ? t % P : t + 256 * k;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            pp[k][i] = piece < P ? ((uint32_t)perm[16 * piece + 2 * i] | ((uint32_t)perm[16 * piece + 2 * i + 1] << 16)) : 0u;
+    }
+    const int64_t runs = (rows + RB - 1) / RB;
+    for (int64_t c = blockIdx.x; c < runs; c += gridDim.x) {
+        const int64_t r0 = c * RB;
+        const int64_t left = rows - r0;
+        const int span = (int)(left < RB ? left : RB) * C;   // bytes of this run (rows are contiguous)
+        const int8_t *run = src + r0 * C;
+        for (int o = t * 16; o < span; o += 256 * 16)
+            *reinterpret_cast<uint4 *>(stage + o) = *reinterpret_cast<const uint4 *>(run + o);
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int row_l = q * RP + slot_row;
+            if (!active || row_l >= left) continue;
+            const uint8_t *rowp = stage + row_l * C;
+#pragma unroll
+            for (int k = 0; k < NP; ++k) {
+                const int piece = NP == 1 ? t % P : t + 256 * k;
+                if (piece >= P) continue;
+                uint32_t w[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t a = pp[k][2 * i], b = pp[k][2 * i + 1];
+                    w[i] = (uint32_t)rowp[a & 0xFFFFu] | ((uint32_t)rowp[a >> 16] << 8) | ((uint32_t)rowp[b & 0xFFFFu] << 16) |
+                           ((uint32_t)rowp[b >> 16] << 24);
+                }
+                *reinterpret_cast<uint4 *>(dst + (r0 + row_l) * C + 16 * piece) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+        __syncthreads();
+    }
 }
 
 static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -839,8 +881,18 @@ extern "C" int flexiq_permute_channels(const flexiq_layer *L, const int8_t *src,
     if (rows == 0) return FLEXIQ_OK;
     if (!src || !dst || src == dst) return FLEXIQ_EINVAL;
     if (!aligned16(src) || !aligned16(dst)) return FLEXIQ_EALIGN;
-    int64_t threads = rows * (L->C / 4);
-    k_permute_channels<<<(unsigned)cdiv(threads, 256), 256, 0, (hipStream_t)stream>>>(src, dst, L->d_perm, rows, L->C);
+    const int C = L->C;
+    if (C % 16 != 0 || C > 16384) return FLEXIQ_EINVAL;   // (no packed layer has such rows)
+    const int P = C / 16;
+    const int np = P <= 256 ? 1 : P <= 512 ? 2 : 4;
+    const int rb = np == 1 ? 4 * (256 / P) : 4;          // rows per staged run: at most 16 KB (64 KB for the long rows)
+    const int64_t runs = cdiv(rows, rb);
+    const unsigned grid = (unsigned)std::min<int64_t>(runs, 2048);
+    const size_t lds = (size_t)rb * C;
+    hipStream_t st = (hipStream_t)stream;
+    if (np == 1) k_permute_rows<1><<<grid, 256, lds, st>>>(src, dst, L->d_perm, rows, C);
+    else if (np == 2) k_permute_rows<2><<<grid, 256, lds, st>>>(src, dst, L->d_perm, rows, C);
+    else k_permute_rows<4><<<grid, 256, lds, st>>>(src, dst, L->d_perm, rows, C);
     FLEXIQ_HIP(hipGetLastError());
     return FLEXIQ_OK;
 }

@@ -104,6 +104,24 @@ def test_permute_channels(env):
     assert (got.cpu().numpy() == Xq[:, ol.perm]).all()
 
 
+@pytest.mark.parametrize("C,gs,rows", [(32, 32, 1), (96, 32, 1000), (768, 32, 333), (4096, 64, 37), (4128, 32, 9),
+                                       (8192, 64, 6), (10176, 64, 5), (64, 32, 3000)])
+def test_permute_channels_row_lengths(env, C, gs, rows):
+    """Row lengths on every route of the reorder operator: several rows per staged run, one, long rows dealt out over
+    the block (up to the 159 groups of 64 channels a layer may have)."""
+    torch, oracle, fq, dev = env
+    rng = np.random.default_rng(7000 + C)
+    W = rng.normal(0, 0.02, size=(8, C)).astype(np.float32)
+    amax = np.abs(rng.normal(0, 1, size=C)).astype(np.float32) + 0.01
+    x_scale = float(np.float32(amax.max()) / np.float32(127.0))
+    ol = oracle.prepare_layer(W, amax, x_scale, gs)
+    hl = fq.flexiq_quantize_pack(W, amax, x_scale, gs)
+    assert (hl.info()["perm"] == ol.perm).all()
+    X = rng.integers(-128, 128, size=(rows, C)).astype(np.int8)
+    got = fq.flexiq_permute_channels(hl, _dev(torch, X, dev))
+    assert (got.cpu().numpy() == X[:, ol.perm]).all()
+
+
 _Q_WINDOW = [0, 0]   # int8 codes that needed the tie window / codes compared (printed by the last test)
 
 
