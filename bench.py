@@ -199,6 +199,21 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
         fq.flexiq_input_prelowered(l2, False)
         rec(wl, "FP6 variant, producer packs the consumer's FP6 activations", r, _median_graph_us(torch, chain_fp6, 5), ops=ops2)
         del x6_1, xlow_1
+        if r > 0:
+            # run-time extraction positions for the consumer (Section 4.1, dynamic option; the paper reports 2-5 % of
+            # the layer): the OR scan as a kernel of its own between the layers, and riding in the producer's epilogue
+            def chain_scan_kernel():
+                fq.flexiq_mixed_gemm(l1, X1, q=True, out_scale=so1, bufs=mid)
+                fq.flexiq_dynamic_positions(l2, mid["q"])
+                fq.flexiq_mixed_gemm(l2, mid["q"], q=True, out_scale=so1, bufs=fin)
+
+            def chain_scan_fused():
+                fq.flexiq_mixed_gemm(l1, X1, q=True, out_scale=so1, bufs=mid, scan_for=l2)
+                fq.flexiq_mixed_gemm(l2, mid["q"], q=True, out_scale=so1, bufs=fin)
+
+            rec(wl, "int8 kernels, consumer's positions found at run time by a scan kernel", r, _median_graph_us(torch, chain_scan_kernel, 5), ops=ops2)
+            rec(wl, "int8 kernels, consumer's positions found at run time in the producer's epilogue", r, _median_graph_us(torch, chain_scan_fused, 5), ops=ops2)
+            fq.flexiq_static_positions(l2)
     del l1, l2, mid, fin, x6_2
 
     # ---- few-row calls (weight streaming): ViT-L layers with M in {1, 16, 64}

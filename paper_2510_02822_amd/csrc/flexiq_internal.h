@@ -48,6 +48,16 @@ inline uint64_t order_hash(const int32_t *p, int n)
 
 // Limits of the GEMM kernel that depend on the layer alone (checked when it is packed, and again at launch).
 constexpr int kMaxGroups = 159;                       // the kernel keeps the position table of G + 1 groups in LDS
+// Scan words of a layer (run-time positions, d_scan; all zero between calls).  First the area a producing layer's GEMM
+// epilogue uses: a ticket (alone in its 64-byte line) and kFusedScanRows rows of G group masks (a block ORs into row
+// blockIdx.x % kFusedScanRows, so that the atomics of a launch spread over many addresses); then the area of the
+// stand-alone scan kernel: its ticket and one row of partial masks per block.
+constexpr int kScanHead = 16;
+constexpr int kFusedScanRows = 8;
+constexpr int kScanRowBlocks = 128;   // most blocks of the stand-alone scan along the rows (measured: 64 ... 128 is best)
+inline size_t fused_scan_words(int G) { return (size_t)kScanHead + (size_t)kFusedScanRows * G; }
+inline size_t scan_words_total(int G) { return ((fused_scan_words(G) + 15) & ~(size_t)15) + kScanHead + (size_t)kScanRowBlocks * G; }
+inline size_t standalone_scan_offset(int G) { return (fused_scan_words(G) + 15) & ~(size_t)15; }
 constexpr int64_t kMaxWeightBytes = 0x7fffffff;       // both int8 weight copies sit behind one buffer descriptor
 
 }  // namespace flexiq

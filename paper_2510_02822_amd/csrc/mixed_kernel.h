@@ -69,7 +69,8 @@ struct GemmParams {
     int32_t next_K4, next_G, next_gs_log2;
     // optional: scan the int8 output for the consumer's run-time positions (OR of the magnitude bits per channel
     // group of the consumer, merged into its scan words; the block that finishes last turns them into positions)
-    uint32_t *next_scan;          // consumer's scan words [next_G + 1] (all zero between calls); null: no scan
+    uint32_t *next_scan;          // consumer's scan words (ticket, then kFusedScanRows rows of next_G masks; all zero
+                                  // between calls); null: no scan
     const int32_t *next_static;   // consumer's calibrated positions (kept for its 8-bit groups)
     int32_t *next_dyn;            // consumer's run-time position table
     int32_t next_g4;              // consumer's 4-bit groups
@@ -864,7 +865,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         const float *tab = cs_tab + parity * (3 * BN);
         {
             uint32_t qrow[TM][4];   // int8 codes of the four quads of fragment (a, b)
-            uint32_t seen = 0;      // scan: OR of the magnitude bits (v >= 0 ? v : ~v) of this lane's valid codes, per byte
+            uint32_t seen = 0;      // scan: OR of v ^ (v << 1) over this lane's valid codes, per byte (bits 1..7 are used)
             // scale and bias of a quad's four columns are read from the LDS table one quad ahead
             const int nl0 = (wn * TN + a) * 32 + 4 * frag_half_e;
             float4 cs_nx = *reinterpret_cast<const float4 *>(tab + nl0);
@@ -922,10 +923,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                         qw ^= 0x80808080u;
                         if (lw) qw &= qmask;
                         qrow[b][g] = qw;
-                        if (sc) {
-                            const uint32_t flip = ((qw >> 7) & 0x01010101u) * 0xFFu;
-                            seen |= (m < p.M && n_ok) ? (qw ^ flip) : 0u;
-                        }
+                        // Bit j + 1 of v ^ (v << 1) says that bits j + 1 and j of v differ; the highest such j is the highest
+                        // set bit of the magnitude (v, or ~v when negative) whatever the sign, so no sign handling is
+                        // needed.  (The shift carries bit 7 of a byte into bit 0 of the next one, which is not used.)
+                        if (sc) seen |= (m < p.M && n_ok) ? (qw ^ (qw << 1)) : 0u;
                     }
                     if (!(wy || wa || (wq && !qr))) continue;   // nothing is stored quad by quad
                     if (m >= p.M || !n_ok) continue;
@@ -959,7 +960,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                 seen |= seen >> 8;
                 uint32_t w = 0;
 #pragma unroll
-                for (int bit = 0; bit < 7; ++bit)
+                for (int bit = 1; bit < 8; ++bit)
                     if (__builtin_amdgcn_ballot_w64(((seen >> bit) & 1u) != 0u) != 0) w |= 1u << bit;
                 const int ncol = n0 + (wn * TN + a) * 32;
                 // (into the block's LDS copy; the device-wide merge happens once, when the block has finished its
@@ -1074,31 +1075,41 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // enough that this block's atomics have been performed before its ticket is drawn (no release fence: that
     // would also write back the output tile from L2).
     if (scan_out) {
+        // The block's masks go into row blockIdx.x % kFusedScanRows of the consumer's scan words (device-scope atomics that
+        // spread over many addresses: on one row they queue up for microseconds); the block that draws the last ticket
+        // ORs the rows, writes the positions and leaves every word zero for the next call.
         __syncthreads();
+        uint32_t *rows = p.next_scan + kScanHead;
         if (tid < p.next_G) {
             const uint32_t m = mask_tab[tid];
-            if (m) atomicOr(p.next_scan + tid, m);
+            if (m) atomicOr(rows + (int)(blockIdx.x % kFusedScanRows) * p.next_G + tid, m);
         }
         __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
         int *flag = reinterpret_cast<int *>(lds);
-        if (tid == 0) *flag = atomicAdd(p.next_scan + p.next_G, 1u) == gridDim.x - 1 ? 1 : 0;
+        if (tid == 0) *flag = atomicAdd(p.next_scan, 1u) == gridDim.x - 1 ? 1 : 0;
+        if (tid < 160) mask_tab[tid] = 0;
         __syncthreads();
         if (*flag) {
-            for (int g = tid; g < p.next_G; g += NT) {
+            const int used = (int)min(gridDim.x, (unsigned)kFusedScanRows) * p.next_G;
+            for (int i = tid; i < used; i += NT) {
+                const uint32_t v = __hip_atomic_load(rows + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (v) {
+                    __hip_atomic_fetch_or(mask_tab + i % p.next_G, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    rows[i] = 0;
+                }
+            }
+            __syncthreads();
+            for (int g = tid; g <= p.next_G; g += NT) {
                 if (g < p.next_g4) {
-                    const uint32_t mask = atomicOr(p.next_scan + g, 0u);   // device-scope read of what all blocks added
-                    const int hb = mask ? 31 - __builtin_clz(mask) : -1;
-                    p.next_dyn[g] = hb - 2 > 0 ? hb - 2 : 0;
+                    const uint32_t mask = mask_tab[g] & 0xFEu;   // bit j + 1: some code has its highest magnitude bit at j
+                    const int hb = mask ? 31 - __builtin_clz(mask) : 0;
+                    p.next_dyn[g] = hb - 3 > 0 ? hb - 3 : 0;
                 } else {
                     p.next_dyn[g] = p.next_static[g];
                 }
-                p.next_scan[g] = 0;
             }
-            if (tid == 0) {
-                p.next_dyn[p.next_G] = p.next_static[p.next_G];
-                p.next_scan[p.next_G] = 0;
-            }
+            if (tid == 0) p.next_scan[0] = 0;
         }
     }
 }

@@ -243,15 +243,17 @@ __global__ void k_lower_int8_range(const int8_t *__restrict__ X, int8_t *__restr
 }
 
 // Extraction positions found at run time (Section 4.1, dynamic option; Section 9 "Finding extraction positions
-// at runtime"): per channel group the magnitude bits of all values (ones' complement for negative ones) are
-// OR-ed together; with p the highest set bit, three more bits below the sign can be kept: s = max(0, p - 2).
+// at runtime"): per channel group the highest magnitude bit p of all values (ones' complement for negative ones) is
+// found by OR-ing v ^ (v << 1) over the group; three more bits below the sign can be kept: s = max(0, p - 2).
 // Thread (tx, ty) of a block of 1024 ORs the 16 channels at column piece blockIdx.y*TX + tx over the rows
-// blockIdx.x*TY + ty, + gridDim.x*TY, ...; the block combines its rows in LDS and adds what is new to the group's
-// mask (an atomic only if a coherent read shows bits missing: the masks have seven bits and fill up after the
-// first few blocks, so the atomics on one address do not queue up).  The block that finishes last turns the
-// masks of the scanned groups (the first g4) into positions, copies the calibrated positions of the other
-// groups, and leaves the masks and the counter zero for the next call.  No block waits for another.
+// blockIdx.x*TY + ty, + gridDim.x*TY, ...; the block combines its rows in LDS.  PARTIAL: the block then leaves the
+// masks of its groups in a row of its own (no atomics on shared words: with a hundred blocks those queue up for tens
+// of microseconds) and the block that finishes last ORs the rows.  Otherwise (the variant that lives in G + 1 scan
+// words) it adds what is new to the group's mask (an atomic only if a coherent read shows bits missing).  Either way
+// the last block turns the masks of the scanned groups (the first g4) into positions, copies the calibrated
+// positions of the other groups, and leaves what must be zero for the next call zero.  No block waits for another.
 constexpr int kScanThreads = 1024;
+template <bool PARTIAL>
 __global__ __launch_bounds__(kScanThreads) void k_dyn_positions(const int8_t *__restrict__ X, int64_t rows, int C,
                                                                 int pieces, int tx_log2, int gs, int G, int g4,
                                                                 uint32_t *scan, const int32_t *__restrict__ ashift_static,
@@ -269,26 +271,72 @@ __global__ __launch_bounds__(kScanThreads) void k_dyn_positions(const int8_t *__
         uint32_t acc = 0;
         const int64_t step = (int64_t)gridDim.x * TY;
         const int8_t *src = X + (int64_t)piece * 16;
-        auto fold = [](const uint4 v) {   // per byte: v >= 0 ? v : ~v, then the four dwords together
-            const uint32_t f0 = ((v.x >> 7) & 0x01010101u) * 0xFFu, f1 = ((v.y >> 7) & 0x01010101u) * 0xFFu;
-            const uint32_t f2 = ((v.z >> 7) & 0x01010101u) * 0xFFu, f3 = ((v.w >> 7) & 0x01010101u) * 0xFFu;
-            return (v.x ^ f0) | (v.y ^ f1) | (v.z ^ f2) | (v.w ^ f3);
-        };
+        // per byte v ^ (v << 1): bit j + 1 is set when bits j + 1 and j of v differ, and the highest such j is the highest
+        // set bit of the magnitude (v, or ~v when negative), so the sign needs no handling (the shift carries bit 7 of a
+        // byte into bit 0 of the next, which is not used); then the four dwords together
+        auto fold = [](const uint4 v) { return (v.x ^ (v.x << 1)) | (v.y ^ (v.y << 1)) | (v.z ^ (v.z << 1)) | (v.w ^ (v.w << 1)); };
         int64_t r = (int64_t)blockIdx.x * TY + ty;
-        for (; r + 3 * step < rows; r += 4 * step) {   // four independent loads in flight
+        for (; r + 7 * step < rows; r += 8 * step) {   // eight independent loads in flight
+            uint4 v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = *reinterpret_cast<const uint4 *>(src + (r + k * step) * C);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc |= fold(v[k]);
+        }
+        for (; r + 1 * step < rows; r += 2 * step) {
             const uint4 v0 = *reinterpret_cast<const uint4 *>(src + r * C);
             const uint4 v1 = *reinterpret_cast<const uint4 *>(src + (r + step) * C);
-            const uint4 v2 = *reinterpret_cast<const uint4 *>(src + (r + 2 * step) * C);
-            const uint4 v3 = *reinterpret_cast<const uint4 *>(src + (r + 3 * step) * C);
-            acc |= fold(v0) | fold(v1) | fold(v2) | fold(v3);
+            acc |= fold(v0) | fold(v1);
         }
         for (; r < rows; r += step) acc |= fold(*reinterpret_cast<const uint4 *>(src + r * C));
         acc |= acc >> 16;
         acc |= acc >> 8;
-        m = acc & 0x7Fu;
+        m = acc & 0xFEu;
     }
     sh[tid] = m;
     __syncthreads();
+    if (PARTIAL) {
+        // Every block leaves the masks of its groups in a row of its own (device-coherent stores, no atomics on shared
+        // words: with a block per compute unit those queue up for tens of microseconds), draws a ticket once the
+        // stores have completed, and the block that draws the last one ORs the rows together.
+        __shared__ uint32_t gmask[kMaxGroups + 1];
+        const int ppg = gs >> 4;   // pieces per group
+        if (ty == 0) {
+            for (int y = 1; y < TY; ++y) m |= sh[y * TX + tx];
+        }
+        __syncthreads();
+        if (ty == 0) sh[tx] = m;
+        for (int g = tid; g <= kMaxGroups; g += kScanThreads) gmask[g] = 0;
+        __syncthreads();
+        uint32_t *part = scan + kScanHead;
+        if (ty == 0 && active && (tx & (ppg - 1)) == 0) {
+            uint32_t gm = 0;
+            for (int k = 0; k < ppg; ++k) gm |= sh[tx + k];
+            __hip_atomic_store(&part[(int64_t)blockIdx.x * g4 + (piece * 16) / gs], gm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0070);
+        __syncthreads();
+        if (tid == 0) last = atomicAdd(&scan[0], 1u) == gridDim.x * gridDim.y - 1;
+        __syncthreads();
+        if (!last) return;
+        const int total = (int)gridDim.x * g4;
+        for (int i = tid; i < total; i += kScanThreads) {
+            const uint32_t v = __hip_atomic_load(&part[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (v) atomicOr(&gmask[i % g4], v);
+        }
+        __syncthreads();
+        for (int g = tid; g <= G; g += kScanThreads) {
+            if (g < g4) {
+                const uint32_t mask = gmask[g];
+                const int p = mask ? 31 - __clz((int)mask) : 0;   // bit p of the mask: highest magnitude bit p - 1
+                ashift_dyn[g] = p - 3 > 0 ? p - 3 : 0;
+            } else {
+                ashift_dyn[g] = ashift_static[g];
+            }
+        }
+        if (tid == 0) scan[0] = 0;
+        return;
+    }
     if (ty == 0 && active) {
         for (int y = 1; y < TY; ++y) m |= sh[y * TX + tx];
         uint32_t *dst = &scan[(piece * 16) / gs];
@@ -306,8 +354,8 @@ __global__ __launch_bounds__(kScanThreads) void k_dyn_positions(const int8_t *__
     for (int g = tid; g <= G; g += kScanThreads) {
         if (g < g4) {
             const uint32_t mask = atomicOr(&scan[g], 0u);   // device-scope read of what all blocks added
-            const int p = mask ? 31 - __clz((int)mask) : -1;
-            ashift_dyn[g] = p - 2 > 0 ? p - 2 : 0;
+            const int p = mask ? 31 - __clz((int)mask) : 0;   // bit p of the mask: highest magnitude bit p - 1
+            ashift_dyn[g] = p - 3 > 0 ? p - 3 : 0;
             scan[g] = 0;
         } else {
             ashift_dyn[g] = ashift_static[g];
@@ -594,8 +642,9 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
         FLEXIQ_HIP(hipMemcpy(L->d_ashift, a32.data(), a32.size() * sizeof(int32_t), hipMemcpyHostToDevice));
         FLEXIQ_HIP(hipMalloc((void **)&L->d_ashift_dyn, a32.size() * sizeof(int32_t)));
         FLEXIQ_HIP(hipMemcpy(L->d_ashift_dyn, a32.data(), a32.size() * sizeof(int32_t), hipMemcpyHostToDevice));
-        FLEXIQ_HIP(hipMalloc((void **)&L->d_scan, (size_t)(G + 1) * sizeof(uint32_t)));
-        FLEXIQ_HIP(hipMemset(L->d_scan, 0, (size_t)(G + 1) * sizeof(uint32_t)));
+        const size_t scan_words = scan_words_total(G);
+        FLEXIQ_HIP(hipMalloc((void **)&L->d_scan, scan_words * sizeof(uint32_t)));
+        FLEXIQ_HIP(hipMemset(L->d_scan, 0, scan_words * sizeof(uint32_t)));
     }
     // one more (zero) row than groups: the pad unit of an odd unit count looks up group G
     FLEXIQ_HIP(hipMalloc((void **)&L->d_wshift, (size_t)(G + 1) * Npad));
@@ -755,7 +804,7 @@ struct ScanLaunch {
     int g4, pieces, tx_log2;
     unsigned gx, gy;
 };
-ScanLaunch scan_launch(const flexiq_layer *L, int64_t rows)
+ScanLaunch scan_launch(const flexiq_layer *L, int64_t rows, int max_blocks)
 {
     ScanLaunch sl;
     sl.g4 = L->max_4bit_ch / L->group_size;
@@ -767,8 +816,9 @@ ScanLaunch scan_launch(const flexiq_layer *L, int64_t rows)
     sl.gy = 1;
     if (sl.pieces > 0 && rows > 0) {
         sl.gy = (unsigned)cdiv(sl.pieces, TX);
-        // about four rows per thread, and few blocks: every block ends with one atomic on a shared counter
-        sl.gx = (unsigned)std::min<int64_t>(cdiv(rows, (int64_t)TY * 4), std::max<int64_t>(1, 128 / sl.gy));
+        // at least four rows per thread, and a bounded number of blocks: every block ends with one atomic on a shared
+        // counter (and, in the variant without partial rows, with atomics on the group masks)
+        sl.gx = (unsigned)std::min<int64_t>(cdiv(rows, (int64_t)TY * 4), std::max<int64_t>(1, max_blocks / sl.gy));
         if (sl.gx < 1) sl.gx = 1;
     }
     return sl;
@@ -780,10 +830,10 @@ extern "C" int flexiq_dynamic_positions(flexiq_layer *L, const int8_t *X, int64_
     if (!L || rows < 0) return FLEXIQ_EINVAL;
     if (rows > 0 && !X) return FLEXIQ_EINVAL;
     if (rows > 0 && !aligned16(X)) return FLEXIQ_EALIGN;
-    const ScanLaunch sl = scan_launch(L, rows);
-    k_dyn_positions<<<dim3(sl.gx, sl.gy), kScanThreads, 0, (hipStream_t)stream>>>(X, sl.pieces > 0 ? rows : 0, L->C, sl.pieces,
-                                                                                    sl.tx_log2, L->group_size, L->G, sl.g4, L->d_scan,
-                                                                                    L->d_ashift, L->d_ashift_dyn);
+    const ScanLaunch sl = scan_launch(L, rows, kScanRowBlocks);
+    k_dyn_positions<true><<<dim3(sl.gx, sl.gy), kScanThreads, 0, (hipStream_t)stream>>>(
+        X, sl.pieces > 0 ? rows : 0, L->C, sl.pieces, sl.tx_log2, L->group_size, L->G, sl.g4, L->d_scan + standalone_scan_offset(L->G), L->d_ashift,
+        L->d_ashift_dyn);
     FLEXIQ_HIP(hipGetLastError());
     L->dynamic = true;
     return FLEXIQ_OK;
@@ -819,10 +869,10 @@ extern "C" int flexiq_dynamic_positions_static(flexiq_layer *L, const int8_t *X,
     }
     // The array is zero when the library is loaded and every scan leaves the words it touched at zero again (its
     // last block clears masks and counter), so nothing is cleared here.
-    const ScanLaunch sl = scan_launch(L, rows);
-    k_dyn_positions<<<dim3(sl.gx, sl.gy), kScanThreads, 0, (hipStream_t)stream>>>(X, sl.pieces > 0 ? rows : 0, L->C, sl.pieces,
-                                                                                    sl.tx_log2, L->group_size, L->G, sl.g4, words,
-                                                                                    L->d_ashift, L->d_ashift_dyn);
+    const ScanLaunch sl = scan_launch(L, rows, 128);
+    k_dyn_positions<false><<<dim3(sl.gx, sl.gy), kScanThreads, 0, (hipStream_t)stream>>>(X, sl.pieces > 0 ? rows : 0, L->C, sl.pieces,
+                                                                                           sl.tx_log2, L->group_size, L->G, sl.g4, words,
+                                                                                           L->d_ashift, L->d_ashift_dyn);
     FLEXIQ_HIP(hipGetLastError());
     L->dynamic = true;
     return FLEXIQ_OK;
