@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflexiq.so")
-NUM_TILE_SHAPES = 14
+NUM_TILE_SHAPES = 15
 # (source, object, extra flags): the kernel of every tile shape is a translation unit of its own
 UNITS = [("pack.hip", "pack.o", []), ("gemm.hip", "gemm.o", []), ("fp6_gemm.hip", "fp6_gemm.o", []),
          ("smallm.hip", "smallm.o", [])] + \

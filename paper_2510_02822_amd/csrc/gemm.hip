@@ -19,7 +19,7 @@ static const TileShape *shapes(int *count)
     static const TileShape tab[kNumTileShapes] = {tile_shape_0(), tile_shape_1(), tile_shape_2(), tile_shape_3(),
                                                   tile_shape_4(), tile_shape_5(), tile_shape_6(), tile_shape_7(),
                                                   tile_shape_8(), tile_shape_9(), tile_shape_10(), tile_shape_11(),
-                                                  tile_shape_12(), tile_shape_13()};
+                                                  tile_shape_12(), tile_shape_13(), tile_shape_14()};
     *count = kNumTileShapes;
     return tab;
 }
@@ -83,6 +83,11 @@ static int choose_shape(const DeviceKernels &dk, int64_t M, int N, int steps, bo
     const TileShape *tab = shapes(&cnt);
     if (g_force_shape >= 0 && g_force_shape < cnt) return g_force_shape;
     const int ncu = dk.num_cu;
+    // Layers with at most 64 output channels and many rows (ResNet-50 stage 1 at batch 128): every wider shape computes
+    // padding columns, and the 128 x 64 shape at three blocks per CU measured 15-20 % faster than the model's pick
+    // on all three such layer kinds (1x1 and 3x3, K = 64 ... 576).
+    constexpr int kNarrowShape = 14;
+    if (N <= 64 && !packed && M >= (int64_t)3 * tab[kNarrowShape].BM * ncu) return kNarrowShape;
     double best = 1e300;
     int bi = 0;
     for (int i = 0; i < cnt; ++i) {

@@ -1136,7 +1136,7 @@ inline TileShape make_shape(double step_alone, double share, double epilogue, do
 }
 
 // Shape i of the table, defined in mixed_tile.hip built with -DFQ_TILE=i.
-constexpr int kNumTileShapes = 14;
+constexpr int kNumTileShapes = 15;
 TileShape tile_shape_0();
 TileShape tile_shape_1();
 TileShape tile_shape_2();
@@ -1151,5 +1151,6 @@ TileShape tile_shape_10();
 TileShape tile_shape_11();
 TileShape tile_shape_12();
 TileShape tile_shape_13();
+TileShape tile_shape_14();
 
 }  // namespace flexiq

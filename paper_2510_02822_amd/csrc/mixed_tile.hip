@@ -3,7 +3,7 @@
 #include "mixed_kernel.h"
 
 #ifndef FQ_TILE
-#error "compile with -DFQ_TILE=<0..13>"
+#error "compile with -DFQ_TILE=<0..14>"
 #endif
 
 namespace flexiq {
@@ -39,6 +39,8 @@ TileShape tile_shape_11() { return make_shape<1, 8, 7, 1>(1125.0, 0.00, 4800.0, 
 TileShape tile_shape_12() { return make_shape<2, 4, 5, 2>(1500.0, 0.0, 6000.0, 420.0); }   // 320 x 256, eight waves
 #elif FQ_TILE == 13
 TileShape tile_shape_13() { return make_shape<1, 8, 3, 1>(770.0, 0.0, 2500.0, 245.0); }    //  96 x 256, eight waves
+#elif FQ_TILE == 14
+TileShape tile_shape_14() { return make_shape<4, 1, 1, 2>(530.0, 0.45, 7000.0, 286.0); }   // 128 x  64 (layers with at most 64 output channels)
 #else
 #error "FQ_TILE out of range"
 #endif
