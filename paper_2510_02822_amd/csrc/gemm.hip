@@ -91,6 +91,9 @@ static int choose_shape(const DeviceKernels &dk, int64_t M, int N, int steps, bo
     double best = 1e300;
     int bi = 0;
     for (int i = 0; i < cnt; ++i) {
+        // (the 160 x 256 four-wave shape keeps part of its accumulators in scratch memory in the convolution form:
+        // measured five times slower than its neighbours there, so it only serves linear layers)
+        if (conv && i == 3) continue;
         const int occ = dk.resident[i][conv ? 1 : 0][packed ? 1 : 0];
         const double tiles = (double)((M + tab[i].BM - 1) / tab[i].BM) * (double)((N + tab[i].BN - 1) / tab[i].BN);
         const double tiles_cu = __builtin_ceil(tiles / ncu);
