@@ -210,7 +210,10 @@ def test_gemm_blocks_walk_several_tiles(env):
 
 
 @pytest.mark.parametrize("M,K,N,gs,scale", [(300, 256, 96, 32, 1.0), (1000, 192, 72, 32, 4.0), (77, 512, 64, 64, 0.25),
-                                            (2500, 96, 40, 32, 2.0), (1, 64, 16, 32, 1.0)])
+                                            (2500, 96, 40, 32, 2.0), (1, 64, 16, 32, 1.0),
+                                            # more than 4096 scanned channels (two column slabs of blocks), and many
+                                            # row blocks (one row of partial masks each)
+                                            (900, 8192, 16, 64, 1.0), (40000, 128, 16, 32, 0.5)])
 def test_dynamic_positions(env, M, K, N, gs, scale):
     # positions found by the run-time OR scan == the oracle's scan, and the GEMM that uses them == the oracle's
     # GEMM with those positions; `scale` moves the run-time range above / below the calibrated one
