@@ -156,6 +156,11 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
             rec(wl, "FP6 variant of the 4-bit phase, activations packed by the producer", r, us, ops=ops,
                 fp6_channels=fq.flexiq_fp6_channels(layer))
             if r > 0:
+                x4 = fq.flexiq_lower_packed4(layer, Xq)
+                us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm_packed4(layer, Xq, x4, q=True, out_scale=so, bufs=bufs), 10)
+                rec(wl, "int8 kernel, 4-bit activations arrive packed (two codes per byte)", r, us, ops=ops,
+                    packed_channels=fq.flexiq_packed4_channels(layer))
+                del x4
                 us = _median_graph_us(torch, lambda: fq.flexiq_lower_fp6(layer, Xq, x6=x6, need_xlow=False), 10)
                 rec(wl, "stand-alone FP6 lowering kernel (when no producer packs)", r, us,
                     byts=M * K * r * 1.75)
@@ -233,6 +238,32 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
                         byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, route), launch=launch)
             del ws
     packed.clear()
+
+    # ---- an HBM-bound layer as a linear call: the ResNet-50 stage-1 1x1 convolution 256 -> 64 at 56 x 56, batch 128
+    # (M = 401408 pixels, K = 256, N = 64): int8 activations against packed 4-bit activations, where the ratio saves
+    # activation bytes (algorithmic bytes: M*K*(1 - r/2) + N*K + M*N)
+    case = workloads.config4_layer(3, B=128)
+    Xl = case.X.reshape(-1, case.C)
+    Ml = Xl.shape[0]
+    x_scale, amax = _calib(case)
+    layer = fq.flexiq_quantize_pack(case.W.reshape(case.N, case.C), amax, x_scale, case.group_size, bias=case.bias)
+    Xq = fq.flexiq_permute_channels(layer, fq.flexiq_quantize_act(torch.from_numpy(np.ascontiguousarray(Xl)).to(dev), x_scale))
+    fq.flexiq_set_ratio(layer, 0.0)
+    so = float(fq.flexiq_mixed_gemm(layer, Xq, y=True)["y"].abs().max().item() / 127.0)
+    bufs = {"q": torch.empty((Ml, case.N), dtype=torch.int8, device=dev)}
+    wl = "resnet50 s1 1x1 256->64 as a linear layer, M=%d K=%d N=%d" % (Ml, case.C, case.N)
+    for r in (0.0, 0.5, 1.0):
+        fq.flexiq_set_ratio(layer, r)
+        us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm(layer, Xq, q=True, out_scale=so, bufs=bufs), 10)
+        rec(wl, "int8 activations, lowered on the fly", r, us, byts=Ml * case.C + case.N * case.C + Ml * case.N)
+        if r > 0:
+            x4 = fq.flexiq_lower_packed4(layer, Xq)
+            us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm_packed4(layer, Xq, x4, q=True, out_scale=so, bufs=bufs), 10)
+            k4p = fq.flexiq_packed4_channels(layer)
+            rec(wl, "4-bit activations arrive packed (two codes per byte)", r, us,
+                byts=Ml * (case.C - k4p // 2) + case.N * case.C + Ml * case.N)
+            del x4
+    del layer, Xq, bufs, case, Xl
 
     # ---- configuration 2: 3x3 convolution 256 -> 256 at 14 x 14, batch 64
     def conv_bytes(case, r):

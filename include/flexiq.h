@@ -181,6 +181,10 @@ int flexiq_permute_channels(const flexiq_layer *layer, const int8_t *src, int8_t
  *               consumer's FP6 activation buffer (flexiq_fp6_bytes(consumer, M) bytes).  The columns that are FP6
  *               channels of the consumer (flexiq_fp6_channels) are then written there as FP6 codes instead of into q;
  *               q keeps the other columns (those of its remaining 4-bit channels lowered).  Needs N % 64 == 0
+ *   x4        : optional, with lower_for on a linear consumer and q (flexiq_mixed_gemm / flexiq_mixed_conv_implicit): dev
+ *               pointer to the consumer's packed 4-bit activation buffer (flexiq_packed4_bytes(consumer, M) bytes).  The
+ *               columns that are packed channels of the consumer (flexiq_packed4_channels) are then written there as
+ *               4-bit codes instead of into q; q keeps the other columns.  Needs N % 32 == 0
  *   workspace, workspace_bytes : optional.  Device memory (16-byte aligned, at least
  *               flexiq_small_m_workspace_bytes(layer) bytes, ZERO when first handed in) that lets flexiq_mixed_gemm
  *               serve calls of at most 64 rows with the split-K kernel: the reduction is cut into slices across
@@ -198,6 +202,7 @@ typedef struct {
     const flexiq_layer *lower_for;
     flexiq_layer *scan_for;
     uint8_t *x6;
+    uint8_t *x4;
     void *workspace;
     int64_t workspace_bytes;
 } flexiq_out;
@@ -224,6 +229,33 @@ int64_t flexiq_small_m_workspace_bytes(const flexiq_layer *layer);
  * Further limit: H*W*C * (320 / (Ho*Wo) + 2) must be below 2^31 bytes (a block reads its images through a 2 GiB window). */
 int flexiq_mixed_conv_implicit(const flexiq_layer *layer, const int8_t *X, int32_t B, int32_t H, int32_t W,
                                int32_t stride, int32_t pad, const flexiq_out *out, void *stream);
+
+/* ---- 4-bit activations in packed form (Section 4.1: the bit-lowered activations, stored two codes per byte; Section 7
+ * "Resource Consumption" caches extracted 4-bit values for the weights, this does the same for a tensor that one layer
+ * writes and the next one reads).  Linear layers.  Where a layer is bound by memory traffic the ratio then saves
+ * activation bytes as well: the leading flexiq_packed4_channels() stored channels (the 4-bit channels of the current ratio,
+ * cut to whole K-steps of 64) are read from the packed buffer, everything else from X.  Same result, bit for bit, as
+ * flexiq_mixed_gemm. */
+
+/* Leading stored channels read in packed form under the handle's current ratio (a multiple of 64; 0 for convolutions and
+ * for handles whose input arrives lowered). */
+int flexiq_packed4_channels(const flexiq_layer *layer, int32_t *k4p);
+
+/* Bytes of the packed buffer for M rows: M * C / 2 (negative flexiq_status on error).  Row m starts at byte m * C / 2; the
+ * sixteen channels 16 p .. 16 p + 15 of a row are the eight bytes at 8 p: in dword e (little endian) byte b holds the code
+ * of channel 16 p + 8 e + b in its low half and the code of channel 16 p + 8 e + 4 + b in its high half (two's
+ * complement, L(v, s) & 15).  Only the first flexiq_packed4_channels() / 2 bytes of a row are read or written. */
+int64_t flexiq_packed4_bytes(const flexiq_layer *layer, int64_t M);
+
+/* Stand-alone producer of that buffer from X (dev int8 [M][C], stored channel order) with the handle's current ratio and
+ * positions.  One kernel, no allocation. */
+int flexiq_lower_packed4(const flexiq_layer *layer, const int8_t *X, int64_t M, uint8_t *x4, void *stream);
+
+/* flexiq_mixed_gemm with the leading flexiq_packed4_channels() channels taken from x4 (dev, flexiq_packed4_bytes(layer, M)
+ * bytes, 16-byte aligned, M * C / 2 < 2^31); those columns of X are not read.  Other 4-bit channels (a trailing group of 32)
+ * are lowered on the fly from X as usual.  Launch only; no allocation. */
+int flexiq_mixed_gemm_packed4(const flexiq_layer *layer, const int8_t *X, const uint8_t *x4, int64_t M, const flexiq_out *out,
+                              void *stream);
 
 /* ---- Variant of the 4-bit phase on the FP6 matrix path (Section 7: the low-bit groups on a faster matrix
  * instruction; on gfx950 that instruction is the FP8/FP6/FP4 MFMA with block scales, since no 4-bit integer MFMA

@@ -24,13 +24,14 @@ class _PackDesc(C.Structure):
 
 class _Out(C.Structure):
     _fields_ = [("acc", C.c_void_p), ("y", C.c_void_p), ("q", C.c_void_p), ("out_scale", C.c_float),
-                ("lower_for", C.c_void_p), ("scan_for", C.c_void_p), ("x6", C.c_void_p),
+                ("lower_for", C.c_void_p), ("scan_for", C.c_void_p), ("x6", C.c_void_p), ("x4", C.c_void_p),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64)]
 
 
 def exported_symbols():
     """Names include/flexiq.h declares."""
-    return ["flexiq_dynamic_positions_static", "flexiq_fp6_channels", "flexiq_fp6_bytes", "flexiq_lower_fp6",
+    return ["flexiq_packed4_channels", "flexiq_packed4_bytes", "flexiq_lower_packed4", "flexiq_mixed_gemm_packed4",
+            "flexiq_dynamic_positions_static", "flexiq_fp6_channels", "flexiq_fp6_bytes", "flexiq_lower_fp6",
             "flexiq_mixed_gemm_fp6", "flexiq_small_m_workspace_bytes", "flexiq_strerror", "flexiq_last_hip_error", "flexiq_quantize_pack", "flexiq_layer_free",
             "flexiq_layer_info", "flexiq_layer_dump", "flexiq_set_ratio", "flexiq_quantize_act",
             "flexiq_bitlower", "flexiq_dynamic_positions", "flexiq_static_positions", "flexiq_layer_positions",
@@ -71,6 +72,11 @@ def load():
     L.flexiq_fp6_bytes.restype = C.c_int64
     L.flexiq_lower_fp6.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
     L.flexiq_mixed_gemm_fp6.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(_Out), C.c_void_p]
+    L.flexiq_packed4_channels.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+    L.flexiq_packed4_bytes.argtypes = [C.c_void_p, C.c_int64]
+    L.flexiq_packed4_bytes.restype = C.c_int64
+    L.flexiq_lower_packed4.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+    L.flexiq_mixed_gemm_packed4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(_Out), C.c_void_p]
     L.flexiq_debug_force_fp6_tile.argtypes = [C.c_int]
     L.flexiq_debug_force_splits.argtypes = [C.c_int]
     L.flexiq_small_m_workspace_bytes.argtypes = [C.c_void_p]
@@ -245,6 +251,44 @@ def flexiq_fp6_bytes(layer: Layer, M: int) -> int:
     return int(n)
 
 
+def flexiq_packed4_channels(layer: Layer) -> int:
+    k = C.c_int32(0)
+    _check(load().flexiq_packed4_channels(layer._h, C.byref(k)))
+    return int(k.value)
+
+
+def flexiq_packed4_bytes(layer: Layer, M: int) -> int:
+    n = int(load().flexiq_packed4_bytes(layer._h, M))
+    if n < 0:
+        _check(n)
+    return n
+
+
+def flexiq_lower_packed4(layer: Layer, X, x4=None):
+    """Stand-alone producer of the packed 4-bit activations (uint8 cuda [M][C/2])."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.int8 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == layer.C
+    M = X.shape[0]
+    if x4 is None:
+        x4 = torch.empty((max(M, 1), layer.C // 2), dtype=torch.uint8, device=X.device)
+    _check(load().flexiq_lower_packed4(layer._h, X.data_ptr(), M, x4.data_ptr(), _stream()))
+    return x4
+
+
+def flexiq_mixed_gemm_packed4(layer: Layer, X, x4, acc: bool = False, y: bool = False, q: bool = False, out_scale: float = 1.0,
+                              bufs: Optional[dict] = None, lower_for: Optional[Layer] = None, x4_out=None):
+    """flexiq_mixed_gemm with the leading 4-bit channels read from packed codes.  x4_out: with lower_for, the consumer's
+    packed buffer (flexiq_out.x4)."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.int8 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == layer.C
+    M = X.shape[0]
+    o, res = _outs((M, layer.N), X.device, acc, y, q, out_scale, bufs, lower_for, None)
+    if x4_out is not None:
+        o.x4 = x4_out.data_ptr()
+    _check(load().flexiq_mixed_gemm_packed4(layer._h, X.data_ptr(), x4.data_ptr(), M, C.byref(o), _stream()))
+    return res
+
+
 def flexiq_lower_fp6(layer: Layer, X, x6=None, need_xlow: Optional[bool] = None):
     """Stand-alone producer of the FP6 activations: returns (x6, xlow).  xlow is X itself unless some 4-bit channels
     lie outside the FP6 prefix (then a copy with those channels lowered)."""
@@ -312,10 +356,11 @@ def flexiq_small_m_workspace(layer: Layer, device):
 
 def flexiq_mixed_gemm(layer: Layer, X, acc: bool = False, y: bool = False, q: bool = False,
                       out_scale: float = 1.0, bufs: Optional[dict] = None, lower_for: Optional[Layer] = None,
-                      scan_for: Optional[Layer] = None, workspace=None):
+                      scan_for: Optional[Layer] = None, workspace=None, x4_out=None):
     """X: int8 cuda [M][C] in stored channel order.  Returns a dict of the requested outputs.
     lower_for / scan_for: the layer that consumes q (flexiq_out.lower_for, flexiq_out.scan_for).
-    workspace: uint8 cuda tensor from flexiq_small_m_workspace (flexiq_out.workspace; few-row calls)."""
+    workspace: uint8 cuda tensor from flexiq_small_m_workspace (flexiq_out.workspace; few-row calls).
+    x4_out: with lower_for, the consumer's packed 4-bit activation buffer (flexiq_out.x4)."""
     import torch
     assert X.is_cuda and X.dtype == torch.int8 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == layer.C
     M = X.shape[0]
@@ -323,6 +368,8 @@ def flexiq_mixed_gemm(layer: Layer, X, acc: bool = False, y: bool = False, q: bo
     if workspace is not None:
         o.workspace = workspace.data_ptr()
         o.workspace_bytes = workspace.numel()
+    if x4_out is not None:
+        o.x4 = x4_out.data_ptr()
     _check(load().flexiq_mixed_gemm(layer._h, X.data_ptr(), M, C.byref(o), _stream()))
     return res
 

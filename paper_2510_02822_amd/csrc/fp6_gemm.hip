@@ -90,6 +90,7 @@ extern "C" int flexiq_mixed_gemm_fp6(const flexiq_layer *L, const int8_t *X, con
     if (!out || (!out->acc && !out->y && !out->q)) return FLEXIQ_EINVAL;
     if (out->q && !(out->out_scale > 0.0f)) return FLEXIQ_EINVAL;
     if (out->scan_for) return FLEXIQ_EINVAL;   // the run-time scan rides in the int8 kernel's epilogue only
+    if (out->x4) return FLEXIQ_EINVAL;         // packed 4-bit output is written by the int8 kernel only
     const int K6 = fp6_channels(L);
     if ((K6 > 0 && !X6) || (K6 < L->C && !X)) return FLEXIQ_EINVAL;
     const void *ps[] = {out->acc, out->y, out->q, X, X6, out->x6};

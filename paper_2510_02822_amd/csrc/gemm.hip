@@ -45,6 +45,7 @@ struct DeviceKernels {
     bool ready = false;
     int num_cu = 0;
     int resident[kNumTileShapes][2][2] = {};
+    int resident_xp[kNumTileShapes] = {};   // the variant that reads packed 4-bit activations
 };
 constexpr int kMaxDevices = 64;
 static DeviceKernels g_dev[kMaxDevices];
@@ -71,6 +72,13 @@ int prepare_kernels(int device)
                 FLEXIQ_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, fn, tab[i].threads, tab[i].lds));
                 d.resident[i][c][k] = resident < 1 ? 1 : resident;
             }
+    for (int i = 0; i < cnt; ++i) {
+        const void *fn = (const void *)tab[i].fn_xp;
+        int resident = 0;
+        FLEXIQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, tab[i].lds));
+        FLEXIQ_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, fn, tab[i].threads, tab[i].lds));
+        d.resident_xp[i] = resident < 1 ? 1 : resident;
+    }
     d.ready = true;
     return FLEXIQ_OK;
 }
@@ -122,9 +130,12 @@ static bool orders_match(const flexiq_layer *producer, const flexiq_layer *consu
 }
 
 static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, bool conv,
-                  int H, int Wd, int Ho, int Wo, int stride, int pad)
+                  int H, int Wd, int Ho, int Wo, int stride, int pad, const uint8_t *X4 = nullptr)
 {
     GemmParams p = {};   // every field starts as zero / null
+    // packed 4-bit activations only matter while some K-step is all 4-bit and the kernel stages activations itself
+    const bool xp = X4 != nullptr && !conv && !L->x_prelowered && L->max_4bit_ch >= 64;
+    p.X4 = xp ? X4 : nullptr;
     p.X = X; p.W8 = L->d_w8; p.W4 = L->d_w4; p.wshift = L->d_wshift;
     p.ashift = L->dynamic ? L->d_ashift_dyn : L->d_ashift;
     p.cs = L->d_cs; p.bias = L->d_bias;
@@ -145,6 +156,14 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
         p.next_K4 = nx->max_4bit_ch;
         p.next_G = nx->G;
         p.next_gs_log2 = nx->group_size == 64 ? 6 : 5;
+        if (out->x4) {   // the consumer's leading channels leave as packed 4-bit codes
+            if (nx->R != 1 || nx->S != 1 || (L->N & 31) || (reinterpret_cast<uintptr_t>(out->x4) & 15u)) return FLEXIQ_EINVAL;
+            if (M * (int64_t)(L->N / 2) > 0x7fffffff) return FLEXIQ_EINVAL;
+            p.next_x4 = out->x4;
+            p.next_K4P = nx->x_prelowered ? 0 : (nx->max_4bit_ch / 64) * 64;
+        }
+    } else if (out->x4) {
+        return FLEXIQ_EINVAL;   // packed output needs the consumer's positions
     }
     if (out->scan_for) {
         flexiq_layer *nx = out->scan_for;
@@ -177,7 +196,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     // kernel's 64 x 64 tiles would occupy less than a quarter of the compute units (every block then walks a long
     // reduction alone); with more columns the tiled kernel's two trips to memory beat the split-K kernel's chain of
     // stream, store, ticket, re-read.  The test hook forces it for any call of at most 64 rows.
-    const bool few_rows = !conv && M <= 64 && out->workspace && !out->lower_for && !out->scan_for && g_force_shape < 0 && g_force_packed < 0;
+    const bool few_rows = !conv && !xp && M <= 64 && out->workspace && !out->lower_for && !out->scan_for && g_force_shape < 0 && g_force_packed < 0;
     if (few_rows && (g_force_splits > 0 || (M <= 32 && ((L->N + 63) / 64) * 4 < dk.num_cu && L->C >= 2048))) {
         int splits = 1;
         const int rc = launch_small_m(L, X, M, out, stream, dk.num_cu, g_force_splits, &splits);
@@ -192,7 +211,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     }
     const int steps = L->T * ((p.CU + 1) / 2);
     // (activations that arrive lowered always pair with the expanded weight copy)
-    const bool packed = !L->x_prelowered && (g_force_packed >= 0 ? g_force_packed != 0 : M <= kPackedMaxRows);
+    const bool packed = !xp && !L->x_prelowered && (g_force_packed >= 0 ? g_force_packed != 0 : M <= kPackedMaxRows);
     int cnt;
     // share of the K-steps whose activations the kernel lowers (none when they arrive lowered)
     const double lowered_frac = L->x_prelowered ? 0.0 : (double)L->max_4bit_ch / (double)L->C;
@@ -209,8 +228,8 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     }
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     if (tiles > 0x7fffffff) return FLEXIQ_EINVAL;
-    kernel_fn fn = ts.fn[conv ? 1 : 0][packed ? 1 : 0];
-    const int resident = dk.resident[g_last_shape][conv ? 1 : 0][packed ? 1 : 0];   // blocks of this kernel that fit on one CU
+    kernel_fn fn = xp ? ts.fn_xp : ts.fn[conv ? 1 : 0][packed ? 1 : 0];
+    const int resident = xp ? dk.resident_xp[g_last_shape] : dk.resident[g_last_shape][conv ? 1 : 0][packed ? 1 : 0];   // blocks of this kernel that fit on one CU
     // Shapes whose blocks can walk several output tiles are launched as one resident wave of blocks (the kernel's
     // load pipeline then runs on across tile boundaries); the others with one block per tile.
     int64_t blocks = tiles;
@@ -294,6 +313,32 @@ extern "C" int flexiq_mixed_gemm(const flexiq_layer *L, const int8_t *X, int64_t
     if (!X) return FLEXIQ_EINVAL;
     if (reinterpret_cast<uintptr_t>(X) & 15u) return FLEXIQ_EALIGN;
     return launch(L, X, M, out, stream, false, 1, 1, 1, 1, 1, 0);
+}
+
+extern "C" int flexiq_packed4_channels(const flexiq_layer *L, int32_t *k4p)
+{
+    if (!L || !k4p) return FLEXIQ_EINVAL;
+    *k4p = L->R == 1 && L->S == 1 && !L->x_prelowered ? (L->max_4bit_ch / 64) * 64 : 0;
+    return FLEXIQ_OK;
+}
+
+extern "C" int64_t flexiq_packed4_bytes(const flexiq_layer *L, int64_t M)
+{
+    if (!L || M < 0 || L->R != 1 || L->S != 1) return FLEXIQ_EINVAL;
+    return M * (int64_t)(L->C / 2);
+}
+
+extern "C" int flexiq_mixed_gemm_packed4(const flexiq_layer *L, const int8_t *X, const uint8_t *X4, int64_t M, const flexiq_out *out,
+                                         void *stream)
+{
+    if (!L || M < 0 || L->R != 1 || L->S != 1) return FLEXIQ_EINVAL;
+    if (M == 0) return FLEXIQ_OK;
+    int rc = check_out(out);
+    if (rc) return rc;
+    if (!X || !X4) return FLEXIQ_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(X) & 15u) || (reinterpret_cast<uintptr_t>(X4) & 15u)) return FLEXIQ_EALIGN;
+    if (M * (int64_t)(L->C / 2) > 0x7fffffff) return FLEXIQ_EINVAL;   // a tile's window of X4 is addressed with 32 bits
+    return launch(L, X, M, out, stream, false, 1, 1, 1, 1, 1, 0, X4);
 }
 
 extern "C" int flexiq_mixed_conv_implicit(const flexiq_layer *L, const int8_t *X, int32_t B, int32_t H, int32_t W,

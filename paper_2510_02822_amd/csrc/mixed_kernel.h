@@ -48,6 +48,7 @@ typedef short v2s __attribute__((ext_vector_type(2)));
 
 struct GemmParams {
     const int8_t *X;
+    const uint8_t *X4;   // XP kernels: the 4-bit codes of the leading floor64(K4) channels, packed (see flexiq_packed4_bytes)
     const int8_t *W8;    // 8-bit weights, and right behind them (U * 32 * Npad bytes further) the 4-bit codes expanded
                          // to int8 at their position, in the same layout
     const uint8_t *W4;
@@ -67,6 +68,8 @@ struct GemmParams {
     // optional: lower the int8 output for the layer that consumes it (its positions, its 4-bit channel count)
     const int32_t *next_ashift;
     int32_t next_K4, next_G, next_gs_log2;
+    uint8_t *next_x4;     // optional with next_ashift: the consumer's packed 4-bit buffer (row stride N / 2) ...
+    int32_t next_K4P;     // ... which takes the codes of its leading next_K4P channels (a multiple of 64) instead of q
     // optional: scan the int8 output for the consumer's run-time positions (OR of the magnitude bits per channel
     // group of the consumer, merged into its scan words; the block that finishes last turns them into positions)
     uint32_t *next_scan;          // consumer's scan words (ticket, then kFusedScanRows rows of next_G masks; all zero
@@ -214,7 +217,11 @@ enum StepMode { kMode88 = 0, kMode44 = 1, kMode48 = 2, kModeNone = 3 };
 // PACKED4 selects where the weights of a 4-bit unit come from: the packed codes (half the bytes, expanded in
 // registers with vector-ALU work: for memory-bound shapes) or the copy that is already expanded (copied
 // exactly like an 8-bit unit: for compute-bound shapes).
-template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV, bool PACKED4>
+//
+// XP (linear form only): the activations of the all-4-bit K-steps arrive as packed 4-bit codes (half the bytes, written
+// by the producing layer or by the stand-alone packer) and are expanded to int8 at their position while the tile is
+// staged, in place of the bit-lowering: the HBM-bound regime, where r then saves activation bytes.
+template <int WAVES_M, int WAVES_N, int TM, int TN, bool CONV, bool PACKED4, bool XP = false>
 // (two blocks per CU only where two copies of the block's LDS fit: otherwise the register budget of a lone block)
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && TM * TN <= 8 && 2 * Cfg<WAVES_M, WAVES_N, TM, TN>::LDS_BYTES <= 160 * 1024 ? 2 : 1)) void k_mixed(const GemmParams p)
 {
@@ -295,11 +302,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // which holds k-plane xq = slot ^ ((row / 4) % 4); (row / 4) % 4 = (lane / 16) % 4 for every j.
     const int xrow = lane >> 2;
     const int xq = (lane & 3) ^ ((lane >> 4) & 3);   // k-plane of this thread's activation pieces; unit xq >> 1
+    int xvoff4[XI];                   // XP: byte offset of the piece's packed codes inside the window of X4
+    const uint8_t *x4base = nullptr;
+    int x4win = 0;
     int xvoff[XI];                    // linear: byte offset inside the window; conv: xq * 16
     int xh0[XI], xw0[XI], xpix[XI];   // conv: top-left input coordinate, pixel index of the image origin (-1: no row)
 #pragma unroll
     for (int j = 0; j < XI; ++j) {
         xvoff[j] = CONV ? xq * 16 : (16 * (wave + NW * j) + xrow) * p.C + xq * 16;  // linear: rows past the window read zeros
+        xvoff4[j] = (16 * (wave + NW * j) + xrow) * (p.C >> 1) + xq * 8;
         xh0[j] = xw0[j] = xpix[j] = 0;
     }
     auto load_tile_context = [&](int64_t lm0, int ln0) {
@@ -331,6 +342,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         } else {
             xbase = p.X + lm0 * p.C;
             xwin = rows_valid * p.C;
+            if (XP) {
+                x4base = p.X4 + lm0 * (p.C >> 1);
+                x4win = rows_valid * (p.C >> 1);
+            }
         }
     };
     load_tile_context(m0, n0);
@@ -486,10 +501,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
             } else {
                 off = xvoff[i] + c64 * 64;
             }
-            if (mode == kMode88)
+            if (mode == kMode88) {
                 lds_load16(rx, stage + (16 * (wave + NW * i)) * 64, off, 0);
-            else
+            } else if (XP && mode == kMode44) {   // eight bytes of packed codes: the piece's sixteen channels
+                const __amdgpu_buffer_rsrc_t rx4 = __builtin_amdgcn_make_buffer_rsrc((void *)x4base, 0, x4win, kRsrcFlags);
+                const auto v = __builtin_amdgcn_raw_buffer_load_b64(rx4, xvoff4[i] + c64 * 32, 0, 0);
+                sr[i].x = (int)v[0];
+                sr[i].y = (int)v[1];
+            } else {
                 sr[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
+            }
         } else if (i < XI + WI) {
             const int j = i - XI;
             const int idx = wave + NW * j;                      // (k-plane, 64-row block) of this copy
@@ -514,6 +535,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     // LDS table; sa_fetch() is called a step ahead of lower_setup() so that no step starts by waiting for LDS.
     v2s lo2, hi2;
     uint32_t amask;
+    short xp_t = 0;   // XP: right shift that puts a code sitting in the high half of a byte at its position
     int sa_next = 0;
     auto sa_fetch = [&](int c64) { sa_next = reinterpret_cast<const int *>(sa_tab)[(2 * c64 + (xq >> 1)) >> p.gs_shift]; };
     auto lower_setup = [&]() {
@@ -523,6 +545,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
         lo2 = (v2s){lo, lo};
         hi2 = (v2s){hi, hi};
         amask = 0x01010101u * ((0xFFu << sa) & 0xFFu);
+        xp_t = (short)(4 - sa);
     };
     // Register-routed pieces of the staged K-step -> LDS.  The VALU work of the 4-bit units (bit-lowering
     // of activations, expansion of packed weight codes) is cut into four pieces per item, lmicro(i, 0..3),
@@ -531,7 +554,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     auto lmicro = [&](v4i(&sr)[NSR > 0 ? NSR : 1], int(&wsh)[2][WL4], int i, int k, int mode) {
         if (i < XI) {
             if (!has_piece(i)) return;
-            if (mode == kMode44) {
+            if (XP && mode == kMode44) {
+                // dword e of the packed piece holds channels 8e .. 8e+3 in the low halves of its bytes and 8e+4 .. 8e+7
+                // in the high halves; expanded in place from the top so that no source is overwritten early
+                if (k == 0) sr[i][3] = (int)expand_hi((uint32_t)sr[i][1], xp_t, amask);
+                else if (k == 1) sr[i][2] = (int)expand_hi((uint32_t)sr[i][1] << 4, xp_t, amask);
+                else if (k == 2) sr[i][1] = (int)expand_hi((uint32_t)sr[i][0], xp_t, amask);
+                else sr[i][0] = (int)expand_hi((uint32_t)sr[i][0] << 4, xp_t, amask);
+            } else if (mode == kMode44) {
                 sr[i][k] = (int)lower4((uint32_t)sr[i][k], lo2, hi2, amask);
             } else if (mode == kMode48) {
                 const int l = (int)lower4((uint32_t)sr[i][k], lo2, hi2, amask);
@@ -855,6 +885,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     const int frag_half_e = lane >> 5, frag_row_e = lane & 31;
     // (one call handles fragment column a; the variant is chosen per column, which keeps the live ranges of the
     // accumulators short where the variants branch apart)
+    // Sixteen consecutive int8 codes of output row m from column n on.  When the consumer takes its leading channels as
+    // packed 4-bit codes, the pieces of those columns (already clamped and masked: L(v, s) << s) are packed instead: two
+    // codes per byte in the consumer's order (see flexiq_packed4_bytes) into its buffer, and q is left alone there.
+    auto store_row_piece = [&](int64_t m, int n, v4i piece, const float *tab) {
+        if (p.next_x4 != nullptr && n < p.next_K4P) {
+            const int sp = reinterpret_cast<const int *>(tab + 2 * BN)[n - n0];
+            const uint32_t d0 = ((uint32_t)piece.x >> sp) & 0x0F0F0F0Fu, d1 = ((uint32_t)piece.y >> sp) & 0x0F0F0F0Fu;
+            const uint32_t d2 = ((uint32_t)piece.z >> sp) & 0x0F0F0F0Fu, d3 = ((uint32_t)piece.w >> sp) & 0x0F0F0F0Fu;
+            typedef unsigned v2u __attribute__((ext_vector_type(2)));
+            *reinterpret_cast<v2u *>(p.next_x4 + m * (p.N >> 1) + (n >> 1)) = (v2u){d0 | (d1 << 4), d2 | (d3 << 4)};
+        } else {
+            *reinterpret_cast<v4i *>(p.q + m * p.N + n) = piece;
+        }
+    };
     v4i qout[TN][TM];   // int8 output pieces of a tile (row-contiguous form), stored after the last fragment column
     auto epilogue = [&](auto a_, auto wq_, auto wy_, auto wa_, auto nv_, auto qr_, auto lw_, auto sc_) {
         const bool wq = wq_, wy = wy_, wa = wa_, nv = nv_, qr = qr_, lw = lw_, sc = sc_;
@@ -983,7 +1027,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                     } else {
                         const int64_t m = m0 + (wm * TM + b) * 32 + frag_row_e;
                         const int n = n0 + (wn * TN + a) * 32 + 16 * frag_half_e;
-                        if (m < p.M && n < p.N) *reinterpret_cast<v4i *>(p.q + m * p.N + n) = piece;
+                        if (m < p.M && n < p.N) {
+                            if (lw) store_row_piece(m, n, piece, tab);
+                            else *reinterpret_cast<v4i *>(p.q + m * p.N + n) = piece;
+                        }
                     }
                 }
             }
@@ -1050,7 +1097,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                 for (int a = 0; a < TN; ++a) {
                     const int64_t m = m0 + (wm * TM + b) * 32 + frag_row_e;
                     const int n = n0 + (wn * TN + a) * 32 + 16 * frag_half_e;
-                    if (m < p.M && n < p.N) *reinterpret_cast<v4i *>(p.q + m * p.N + n) = qout[a][b];
+                    if (m < p.M && n < p.N) {
+                        if (lower_out) store_row_piece(m, n, qout[a][b], cs_tab + parity * (3 * BN));
+                        else *reinterpret_cast<v4i *>(p.q + m * p.N + n) = qout[a][b];
+                    }
                 }
         }
         if (!more_tiles) break;
@@ -1124,6 +1174,7 @@ struct TileShape {
     double epilogue;     // epilogue of one output tile
     double lower;        // growth of a K-step whose activations are bit-lowered in the kernel
     kernel_fn fn[2][2];  // [convolution][4-bit weights from the packed codes]
+    kernel_fn fn_xp;     // linear form, 4-bit activations from packed codes
 };
 
 template <int WAVES_M, int WAVES_N, int TM, int TN>
@@ -1132,7 +1183,8 @@ inline TileShape make_shape(double step_alone, double share, double epilogue, do
     using C_ = Cfg<WAVES_M, WAVES_N, TM, TN>;
     return TileShape{C_::BM, C_::BN, C_::NT, C_::LDS_BYTES, C_::MULTI, step_alone, share, epilogue, lower,
                      {{k_mixed<WAVES_M, WAVES_N, TM, TN, false, false>, k_mixed<WAVES_M, WAVES_N, TM, TN, false, true>},
-                      {k_mixed<WAVES_M, WAVES_N, TM, TN, true, false>, k_mixed<WAVES_M, WAVES_N, TM, TN, true, true>}}};
+                      {k_mixed<WAVES_M, WAVES_N, TM, TN, true, false>, k_mixed<WAVES_M, WAVES_N, TM, TN, true, true>}},
+                     k_mixed<WAVES_M, WAVES_N, TM, TN, false, false, true>};
 }
 
 // Shape i of the table, defined in mixed_tile.hip built with -DFQ_TILE=i.

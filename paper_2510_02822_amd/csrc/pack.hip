@@ -242,6 +242,32 @@ __global__ void k_lower_int8_range(const int8_t *__restrict__ X, int8_t *__restr
     *reinterpret_cast<uint4 *>(Y + i * 16) = v;
 }
 
+// Packed 4-bit activations (Section 4.1 bit-lowering, two codes per byte): one thread per (row, 16-channel piece) of the
+// leading k4p channels writes the piece's eight bytes: dword e holds the codes of channels 8e .. 8e+3 in the low halves of
+// its bytes and those of channels 8e+4 .. 8e+7 in the high halves (the order the GEMM kernel expands cheapest).
+__global__ void k_lower_packed4(const int8_t *__restrict__ X, uint8_t *__restrict__ X4, int64_t rows, int C, int k4p,
+                                int gs_shift, const int32_t *__restrict__ ashift)
+{
+    const int P = k4p / 16;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * P) return;
+    const int64_t row = i / P;
+    const int piece = (int)(i % P);
+    const uint4 v = *reinterpret_cast<const uint4 *>(X + row * C + piece * 16);
+    const int s = ashift[(piece >> 1) >> gs_shift];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t nib[4];   // the four codes of dword k in the low halves of its bytes
+    for (int k = 0; k < 4; ++k) {
+        uint32_t o = 0;
+        for (int b = 0; b < 4; ++b) {
+            const int x = (int)(int8_t)((w[k] >> (8 * b)) & 0xFF);
+            o |= (uint32_t)(min(7, max(-8, x >> s)) & 0xF) << (8 * b);
+        }
+        nib[k] = o;
+    }
+    *reinterpret_cast<uint2 *>(X4 + row * (C / 2) + piece * 8) = make_uint2(nib[0] | (nib[1] << 4), nib[2] | (nib[3] << 4));
+}
+
 // Extraction positions found at run time (Section 4.1, dynamic option; Section 9 "Finding extraction positions
 // at runtime"): per channel group the highest magnitude bit p of all values (ones' complement for negative ones) is
 // found by OR-ing v ^ (v << 1) over the group; three more bits below the sign can be kept: s = max(0, p - 2).
@@ -895,6 +921,22 @@ extern "C" int flexiq_lower_fp6(const flexiq_layer *L, const int8_t *X, int64_t 
         const int64_t threads = M * (L->C / 16);
         k_lower_int8_range<<<(unsigned)cdiv(threads, 256), 256, 0, (hipStream_t)stream>>>(X, xlow, M, L->C, k6, k4, gs_shift, pos);
     }
+    FLEXIQ_HIP(hipGetLastError());
+    return FLEXIQ_OK;
+}
+
+extern "C" int flexiq_lower_packed4(const flexiq_layer *L, const int8_t *X, int64_t M, uint8_t *x4, void *stream)
+{
+    if (!L || M < 0 || L->R != 1 || L->S != 1) return FLEXIQ_EINVAL;
+    if (M == 0) return FLEXIQ_OK;
+    if (!X || !x4) return FLEXIQ_EINVAL;
+    if (!aligned16(X) || !aligned16(x4)) return FLEXIQ_EALIGN;
+    const int k4p = (L->max_4bit_ch / 64) * 64;
+    if (k4p == 0) return FLEXIQ_OK;
+    const int64_t threads = M * (k4p / 16);
+    if (cdiv(threads, 256) > 0x7fffffff) return FLEXIQ_EINVAL;
+    k_lower_packed4<<<(unsigned)cdiv(threads, 256), 256, 0, (hipStream_t)stream>>>(X, x4, M, L->C, k4p, L->group_size == 64 ? 1 : 0,
+                                                                                     L->dynamic ? L->d_ashift_dyn : L->d_ashift);
     FLEXIQ_HIP(hipGetLastError());
     return FLEXIQ_OK;
 }

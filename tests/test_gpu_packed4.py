@@ -1,0 +1,175 @@
+"""GPU parity of the packed 4-bit activation path: the stand-alone packer, the GEMM that reads packed codes, and a producer
+that writes them for its consumer, against the CPU oracle (int32 accumulators, codes and bytes bit for bit)."""
+import numpy as np
+import pytest
+
+import workloads
+from helpers import both_layers, calib, check_q, requant_fp32_sequence
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import oracle
+    import paper_2510_02822_amd as fq
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    fq.load()
+    oracle.build()
+    return torch, oracle, fq, torch.device("cuda:0")
+
+
+def _dev(torch, a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def decode_packed4(x4, k4p):
+    """The documented layout, written out: the sixteen channels 16 p .. 16 p + 15 of a row are the eight bytes at 8 p; in
+    dword e byte b holds channel 16 p + 8 e + b in its low half and channel 16 p + 8 e + 4 + b in its high half."""
+    rows = x4.shape[0]
+    out = np.zeros((rows, k4p), np.int32)
+    for c in range(k4p):
+        p, e, hi, b = c // 16, (c % 16) // 8, (c % 8) // 4, c % 4
+        byte = x4[:, 8 * p + 4 * e + b].astype(np.int32)
+        nib = (byte >> 4) & 15 if hi else byte & 15
+        out[:, c] = np.where(nib >= 8, nib - 16, nib)
+    return out
+
+
+def _lowered_codes(oracle, Xq, gs, shifts, k):
+    sh = np.repeat(np.asarray(shifts, np.int32), gs)[None, :k]
+    L = np.clip(Xq[:, :k].astype(np.int32) >> sh, -8, 7)
+    # spot-check the vectorised form against the oracle's scalar definition
+    for i in (0, Xq.shape[0] - 1):
+        for j in range(0, k, 7):
+            assert L[i, j] == oracle.bitlower(int(Xq[i, j]), int(sh[0, j]))
+    return L
+
+
+@pytest.mark.parametrize("M,K,N,gs", [(64, 256, 256, 32), (301, 192, 72, 32), (77, 512, 64, 64), (1000, 160, 40, 32)])
+def test_packer_and_gemm(env, M, K, N, gs):
+    torch, oracle, fq, dev = env
+    case = workloads.make_linear("p4", 11, M + K + N, M, K, N, gs, outlier_frac=0.02)
+    ol, hl, x_scale = both_layers(case)
+    Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
+    Xd = _dev(torch, Xq, dev)
+    G = K // gs
+    for r in (1.0, 0.75, 0.5, 1.0 / G, 0.0):
+        k4 = fq.flexiq_set_ratio(hl, r)
+        k4p = fq.flexiq_packed4_channels(hl)
+        assert k4p == (k4 // 64) * 64
+        assert fq.flexiq_packed4_bytes(hl, M) == M * K // 2
+        x4 = torch.full((M, K // 2), 0xA5, dtype=torch.uint8, device=dev)
+        fq.flexiq_lower_packed4(hl, Xd, x4)
+        torch.cuda.synchronize()
+        x4h = x4.cpu().numpy()
+        if k4p:
+            assert (decode_packed4(x4h, k4p) == _lowered_codes(oracle, Xq, gs, ol.a_shift, k4p)).all(), r
+        assert (x4h[:, k4p // 2:] == 0xA5).all()          # nothing written beyond the packed channels
+        # the packed columns of X are not read: poison them
+        Xp = Xq.copy()
+        Xp[:, :k4p] = 77
+        ref = oracle.forward_gemm(ol, Xq, r)
+        so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
+        out = fq.flexiq_mixed_gemm_packed4(hl, _dev(torch, Xp, dev), x4, acc=True, y=True, q=True, out_scale=so)
+        torch.cuda.synchronize()
+        assert (out["acc"].cpu().numpy() == ref).all(), r
+        check_q(out["q"].cpu().numpy(), ref, ol, so)
+        assert (out["q"].cpu().numpy() == requant_fp32_sequence(ref, ol, so)).all()
+
+
+def test_every_tile_shape_and_block_count(env):
+    torch, oracle, fq, dev = env
+    case = workloads.make_linear("p4tiles", 11, 5, 700, 320, 136, 32, outlier_frac=0.02)
+    ol, hl, x_scale = both_layers(case)
+    Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
+    Xd = _dev(torch, Xq, dev)
+    n = fq.debug_force_tile(-1)
+    try:
+        for r in (1.0, 0.5):
+            k4 = fq.flexiq_set_ratio(hl, r)
+            x4 = fq.flexiq_lower_packed4(hl, Xd)
+            ref = oracle.forward_gemm(ol, Xq, r)
+            for t in range(n):
+                fq.debug_force_tile(t)
+                for nb in (0, 1, 3):
+                    fq.debug_max_blocks(nb)
+                    got = fq.flexiq_mixed_gemm_packed4(hl, Xd, x4, acc=True)["acc"].cpu().numpy()
+                    assert (got == ref).all(), (r, t, nb)
+    finally:
+        fq.debug_force_tile(-1)
+        fq.debug_max_blocks(0)
+
+
+def test_run_time_positions_and_saturating_inputs(env):
+    torch, oracle, fq, dev = env
+    M, K, N, gs = 500, 256, 48, 32
+    case = workloads.make_linear("p4dyn", 11, 9, M, K, N, gs, outlier_frac=0.02)
+    case.X *= 4.0   # well above the calibrated ranges: the static positions saturate, the run-time ones do not
+    ol, hl, x_scale = both_layers(case)
+    Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
+    Xd = _dev(torch, Xq, dev)
+    k4 = fq.flexiq_set_ratio(hl, 0.75)
+    G4 = k4 // gs
+    x4 = fq.flexiq_lower_packed4(hl, Xd)
+    got = fq.flexiq_mixed_gemm_packed4(hl, Xd, x4, acc=True)["acc"].cpu().numpy()
+    assert (got == oracle.forward_gemm(ol, Xq, 0.75)).all()
+    fq.flexiq_dynamic_positions(hl, Xd)
+    dyn = oracle.dynamic_act_shifts(Xq, gs, G4, ol.a_shift)
+    x4 = fq.flexiq_lower_packed4(hl, Xd)
+    assert (decode_packed4(x4.cpu().numpy(), (k4 // 64) * 64) == _lowered_codes(oracle, Xq, gs, dyn, (k4 // 64) * 64)).all()
+    got = fq.flexiq_mixed_gemm_packed4(hl, Xd, x4, acc=True)["acc"].cpu().numpy()
+    assert (got == oracle.mixed_gemm(Xq, ol.Wq.reshape(N, K), gs, G4, dyn, ol.w_shift)).all()
+    fq.flexiq_static_positions(hl)
+
+
+def test_producer_packs_for_consumer(env):
+    """fc1 writes fc2's leading channels as packed codes (flexiq_out.x4) and the rest of its int8 output lowered; fc2 reads
+    both.  Intermediate tensor and fc2's accumulators equal the oracle's chain, for every tile shape of the producer."""
+    torch, oracle, fq, dev = env
+    M, K1, N1, N2, gs = 300, 192, 256, 96, 32
+    c1 = workloads.make_linear("chain1", 8, 201, M, K1, N1, gs, outlier_frac=0.02)
+    c2 = workloads.make_linear("chain2", 8, 202, M, N1, N2, gs, outlier_frac=0.02)
+    xs1, am1 = calib(c1)
+    o1 = oracle.prepare_layer(c1.W, am1, xs1, gs, bias=c1.bias)
+    Xq = oracle.quantize(c1.X, xs1)[:, o1.perm]
+    acc1 = oracle.forward_gemm(o1, Xq, 0.5)
+    y1 = oracle.dequant_f64(acc1, xs1, o1.w_scale, o1.bias)
+    s_mid = float(np.abs(y1).max() / 127.0)
+    q1 = requant_fp32_sequence(acc1, o1, s_mid)
+    check_q(q1, acc1, o1, s_mid)
+    am2 = np.abs(q1).max(0).astype(np.float32) * np.float32(s_mid)
+    o2 = oracle.prepare_layer(c2.W, am2, s_mid, gs, bias=c2.bias)
+    X2 = np.ascontiguousarray(q1[:, o2.perm])
+    h2 = fq.flexiq_quantize_pack(c2.W, am2, s_mid, gs, bias=c2.bias)
+    h1 = fq.flexiq_quantize_pack(c1.W, am1, xs1, gs, bias=c1.bias, out_perm=o2.perm)
+    fq.flexiq_set_ratio(h1, 0.5)
+    Xd = _dev(torch, Xq, dev)
+    n_tiles = fq.debug_force_tile(-1)
+    try:
+        for r2 in (1.0, 0.75, 0.375, 0.0):
+            k4 = fq.flexiq_set_ratio(h2, r2)
+            k4p = fq.flexiq_packed4_channels(h2)
+            sh = np.repeat(o2.a_shift.astype(np.int32), gs)[None, :]
+            want_mid = X2.astype(np.int32).copy()
+            want_mid[:, :k4] = np.clip(want_mid[:, :k4] >> sh[:, :k4], -8, 7) << sh[:, :k4]
+            want_codes = _lowered_codes(oracle, X2, gs, o2.a_shift, k4p) if k4p else None
+            for t in (range(n_tiles) if r2 == 0.75 else (-1,)):
+                fq.debug_force_tile(t)
+                x4 = torch.full((M, N1 // 2), 0x5A, dtype=torch.uint8, device=dev)
+                qbuf = {"q": torch.full((M, N1), 99, dtype=torch.int8, device=dev)}
+                fq.flexiq_mixed_gemm(h1, Xd, q=True, out_scale=s_mid, bufs=qbuf, lower_for=h2, x4_out=x4)
+                torch.cuda.synchronize()
+                mid = qbuf["q"].cpu().numpy().astype(np.int32)
+                assert (mid[:, k4p:] == want_mid[:, k4p:]).all(), (r2, t)
+                assert (mid[:, :k4p] == 99).all(), (r2, t)          # q is left alone where the codes went to x4
+                if k4p:
+                    assert (decode_packed4(x4.cpu().numpy(), k4p) == want_codes).all(), (r2, t)
+            fq.debug_force_tile(-1)
+            got = fq.flexiq_mixed_gemm_packed4(h2, qbuf["q"], x4, acc=True)["acc"].cpu().numpy()
+            assert (got == oracle.forward_gemm(o2, X2, r2)).all(), r2
+    finally:
+        fq.debug_force_tile(-1)
+    with pytest.raises(fq.FlexiqError):   # packed output needs the consumer
+        fq.flexiq_mixed_gemm(h1, Xd, q=True, out_scale=s_mid, x4_out=x4)
