@@ -32,6 +32,11 @@ int flexiq_debug_last_launch(int which);
 /* Slices of the split-K kernel for few-row calls: n > 0 forces n slices (capped by the reduction length), 0 = automatic. */
 int flexiq_debug_force_splits(int n);
 
+/* The row-streaming kernel for layers with 64, 128 or 256 input channels (last launch: tile shape index -2):
+ * 1 = take it whenever the layer form qualifies (whatever the row count), 0 = never, -1 = automatic.  Returns whether the
+ * last GEMM / convolution call ran on it. */
+int flexiq_debug_force_stream(int mode);
+
 /* Force tile shape `index` of the FP6-variant kernel's table (-1 = automatic).  Returns the table size. */
 int flexiq_debug_force_fp6_tile(int index);
 

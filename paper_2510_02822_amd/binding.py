@@ -79,6 +79,7 @@ def load():
     L.flexiq_mixed_gemm_packed4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(_Out), C.c_void_p]
     L.flexiq_debug_force_fp6_tile.argtypes = [C.c_int]
     L.flexiq_debug_force_splits.argtypes = [C.c_int]
+    L.flexiq_debug_force_stream.argtypes = [C.c_int]
     L.flexiq_small_m_workspace_bytes.argtypes = [C.c_void_p]
     L.flexiq_small_m_workspace_bytes.restype = C.c_int64
     L.flexiq_debug_force_tile.argtypes = [C.c_int]
@@ -412,6 +413,14 @@ def debug_last_launch() -> dict:
     L = load()
     return {"tile": L.flexiq_debug_last_launch(0), "blocks": L.flexiq_debug_last_launch(1),
             "resident": L.flexiq_debug_last_launch(2), "splits": L.flexiq_debug_last_launch(3)}
+
+
+def debug_force_stream(mode: int) -> int:
+    """Row-streaming kernel: 1 = whenever the layer form qualifies, 0 = never, -1 = automatic; returns whether the last call used it."""
+    rc = load().flexiq_debug_force_stream(int(mode))
+    if rc < 0:
+        _check(rc)
+    return rc
 
 
 def debug_force_splits(n: int) -> None:

@@ -31,6 +31,7 @@ void set_hip_error(hipError_t e, const char *what);
 // GEMM shape table, so that a launch is only a launch.
 int prepare_kernels(int device);
 int prepare_fp6_kernels(int device);
+int prepare_stream_kernels(int device);
 
 // Order hash of a channel permutation (FNV-1a over the 32-bit entries; `n` entries, identity when p == nullptr).
 inline uint64_t order_hash(const int32_t *p, int n)
@@ -70,6 +71,8 @@ int fp6_channels(const flexiq_layer *L);
 int64_t small_m_workspace_bytes(const flexiq_layer *L);
 int launch_small_m(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int force_splits,
                    int *splits_out);
+// (stream.hip) the row-streaming kernel for layers with a short reduction; *taken = 0: the call does not qualify
+int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, bool rows_contiguous, int *taken);
 }  // namespace flexiq
 
 // Device layouts (all offsets in bytes unless noted), T = R*S filter taps, CUp = C/32 rounded up to

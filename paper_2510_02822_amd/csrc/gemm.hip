@@ -209,6 +209,20 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
             return FLEXIQ_OK;
         }
     }
+    // Layers with a short reduction and many contiguous rows: the row-streaming kernel (weights resident in LDS, whole
+    // row tiles copied several tiles ahead).
+    {
+        int taken = 0;
+        const bool ok = !xp && (!conv || (stride == 1 && pad == 0)) && g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0;
+        const int rc = launch_stream(L, X, M, out, stream, ok, &taken);
+        if (rc != FLEXIQ_OK) return rc;
+        if (taken) {
+            g_last_shape = -2;
+            g_last_blocks = 0;
+            g_last_resident = 0;
+            return FLEXIQ_OK;
+        }
+    }
     const int steps = L->T * ((p.CU + 1) / 2);
     // (activations that arrive lowered always pair with the expanded weight copy)
     const bool packed = !xp && !L->x_prelowered && (g_force_packed >= 0 ? g_force_packed != 0 : M <= kPackedMaxRows);
@@ -356,5 +370,7 @@ extern "C" int flexiq_mixed_conv_implicit(const flexiq_layer *L, const int8_t *X
     if (rc) return rc;
     if (!X) return FLEXIQ_EINVAL;
     if (reinterpret_cast<uintptr_t>(X) & 15u) return FLEXIQ_EALIGN;
+    // a 1x1 convolution with stride 1 and no padding is the linear form over the pixels: no per-tap address arithmetic
+    if (L->R == 1 && L->S == 1 && stride == 1 && pad == 0) return launch(L, X, M, out, stream, false, 1, 1, 1, 1, 1, 0);
     return launch(L, X, M, out, stream, true, H, W, Ho, Wo, stride, pad);
 }

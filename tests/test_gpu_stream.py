@@ -1,0 +1,160 @@
+"""GPU parity of the row-streaming kernel (layers with 64, 128 or 256 input channels) against the CPU oracle, through the
+same entry points as the tiled kernel: int32 accumulators and int8 codes bit for bit, fp32 within 1e-5."""
+import numpy as np
+import pytest
+
+import workloads
+from helpers import both_layers, check_q, check_y, requant_fp32_sequence
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import oracle
+    import paper_2510_02822_amd as fq
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    fq.load()
+    oracle.build()
+    return torch, oracle, fq, torch.device("cuda:0")
+
+
+def _dev(torch, a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+@pytest.mark.parametrize("M,K,N,gs", [(1000, 64, 64, 32), (777, 64, 256, 32), (129, 128, 16, 32), (2000, 128, 520, 64),
+                                      (513, 256, 72, 32), (300, 256, 128, 64), (1, 256, 40, 32), (4099, 64, 300, 32)])
+def test_linear_forced(env, M, K, N, gs):
+    torch, oracle, fq, dev = env
+    case = workloads.make_linear("st", 12, M + K + N, M, K, N, gs, outlier_frac=0.02)
+    case.X *= 2.0   # some rows saturate under the calibrated positions
+    ol, hl, x_scale = both_layers(case)
+    Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
+    Xd = _dev(torch, Xq, dev)
+    G = K // gs
+    fq.debug_force_stream(1)
+    try:
+        for r in (0.0, 1.0 / G, 0.5, 1.0):
+            fq.flexiq_set_ratio(hl, r)
+            ref = oracle.forward_gemm(ol, Xq, r)
+            so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
+            out = fq.flexiq_mixed_gemm(hl, Xd, acc=True, y=True, q=True, out_scale=so)
+            torch.cuda.synchronize()
+            assert fq.debug_force_stream(1) == 1          # the call ran on the streaming kernel
+            assert fq.debug_last_launch()["tile"] == -2
+            assert (out["acc"].cpu().numpy() == ref).all(), r
+            check_y(out["y"].cpu().numpy(), ref, ol)
+            got_q = out["q"].cpu().numpy()
+            check_q(got_q, ref, ol, so)
+            assert (got_q == requant_fp32_sequence(ref, ol, so)).all()
+            only_q = fq.flexiq_mixed_gemm(hl, Xd, q=True, out_scale=so)["q"]   # the variant with pre-multiplied scales
+            assert (only_q.cpu().numpy() == got_q).all(), r
+            # the tiled kernel gives the same bytes
+            fq.debug_force_stream(0)
+            tiled = fq.flexiq_mixed_gemm(hl, Xd, q=True, out_scale=so)["q"]
+            assert fq.debug_last_launch()["tile"] >= 0
+            fq.debug_force_stream(1)
+            assert (tiled.cpu().numpy() == got_q).all(), r
+    finally:
+        fq.debug_force_stream(-1)
+
+
+def test_run_time_positions_and_prelowered_input(env):
+    torch, oracle, fq, dev = env
+    M, K, N, gs = 3000, 256, 96, 32
+    case = workloads.make_linear("stdyn", 12, 3, M, K, N, gs, outlier_frac=0.02)
+    case.X *= 3.0
+    ol, hl, x_scale = both_layers(case)
+    Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
+    Xd = _dev(torch, Xq, dev)
+    fq.debug_force_stream(1)
+    try:
+        k4 = fq.flexiq_set_ratio(hl, 0.75)
+        G4 = k4 // gs
+        fq.flexiq_dynamic_positions(hl, Xd)
+        dyn = oracle.dynamic_act_shifts(Xq, gs, G4, ol.a_shift)
+        got = fq.flexiq_mixed_gemm(hl, Xd, acc=True)["acc"].cpu().numpy()
+        assert fq.debug_force_stream(1) == 1
+        assert (got == oracle.mixed_gemm(Xq, ol.Wq.reshape(N, K), gs, G4, dyn, ol.w_shift)).all()
+        fq.flexiq_static_positions(hl)
+        # activations that arrive lowered: the kernel must not lower again with other positions, only copy
+        sh = np.repeat(ol.a_shift.astype(np.int32), gs)[None, :]
+        Xl = Xq.astype(np.int32).copy()
+        Xl[:, :k4] = np.clip(Xl[:, :k4] >> sh[:, :k4], -8, 7) << sh[:, :k4]
+        fq.flexiq_input_prelowered(hl, True)
+        got = fq.flexiq_mixed_gemm(hl, _dev(torch, Xl.astype(np.int8), dev), acc=True)["acc"].cpu().numpy()
+        fq.flexiq_input_prelowered(hl, False)
+        assert (got == oracle.forward_gemm(ol, Xq, 0.75)).all()
+    finally:
+        fq.debug_force_stream(-1)
+        fq.flexiq_input_prelowered(hl, False)
+
+
+def test_conv_1x1_and_automatic_route(env):
+    torch, oracle, fq, dev = env
+    # a 1x1 convolution with stride 1 and no padding is a linear layer over the pixels
+    case = workloads.make_conv("st1x1", 12, 7, 3, 20, 20, 128, 48, 1, 1, 1, 0, 32)
+    ol, hl, x_scale = both_layers(case)
+    Xq = np.ascontiguousarray(oracle.quantize(case.X, x_scale)[..., ol.perm])
+    Xd = _dev(torch, Xq, dev)
+    fq.debug_force_stream(1)
+    try:
+        for r in (0.0, 0.5, 1.0):
+            fq.flexiq_set_ratio(hl, r)
+            ref = oracle.forward_conv(ol, Xq, 1, 0, r)
+            got = fq.flexiq_mixed_conv_implicit(hl, Xd, 1, 0, acc=True)["acc"].cpu().numpy()
+            assert fq.debug_force_stream(1) == 1
+            assert (got == ref).all(), r
+        # a strided 1x1 convolution does not qualify
+        fq.flexiq_mixed_conv_implicit(hl, Xd, 2, 0, acc=True)
+        assert fq.debug_force_stream(1) == 0
+    finally:
+        fq.debug_force_stream(-1)
+    # automatic: taken with many rows, not with few
+    M, K, N = 200000, 64, 64
+    rng = np.random.default_rng(5)
+    case = workloads.make_linear("stauto", 12, 9, 4096, K, N, 32, outlier_frac=0.02)
+    ol, hl, x_scale = both_layers(case)
+    Xbig = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    fq.flexiq_set_ratio(hl, 0.5)
+    got = fq.flexiq_mixed_gemm(hl, _dev(torch, Xbig, dev), acc=True)["acc"].cpu().numpy()
+    assert fq.debug_force_stream(-1) == 1
+    rows = np.r_[0:300, M - 300:M]
+    assert (got[rows] == oracle.forward_gemm(ol, Xbig[rows], 0.5)).all()
+    fq.flexiq_mixed_gemm(hl, _dev(torch, Xbig[:5000], dev), acc=True)
+    assert fq.debug_force_stream(-1) == 0
+
+
+@pytest.mark.parametrize("K,N", [(64, 256), (64, 64), (128, 128), (256, 64)])
+def test_blocks_walk_many_tiles(env, K, N):
+    """More row tiles than resident blocks: every block goes round its ring of tile slots several times (each wave-count
+    and ring-depth configuration of the kernel), int32 and int8 outputs together."""
+    torch, oracle, fq, dev = env
+    M = 150001
+    case = workloads.make_linear("stwalk", 12, K + N, 2048, K, N, 32, outlier_frac=0.02)
+    ol, hl, x_scale = both_layers(case)
+    rng = np.random.default_rng(K * 1000 + N)
+    Xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    Xd = _dev(torch, Xq, dev)
+    rows = np.r_[0:200, 70000:70300, M - 400:M]
+    fq.debug_force_stream(1)
+    try:
+        for r in (1.0, 0.5, 0.0):
+            fq.flexiq_set_ratio(hl, r)
+            ref = oracle.forward_gemm(ol, Xq[rows], r)
+            so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
+            out = fq.flexiq_mixed_gemm(hl, Xd, acc=True, q=True, out_scale=so)
+            torch.cuda.synchronize()
+            assert fq.debug_force_stream(1) == 1
+            assert (out["acc"].cpu().numpy()[rows] == ref).all(), r
+            assert (out["q"].cpu().numpy()[rows] == requant_fp32_sequence(ref, ol, so)).all(), r
+            # the whole int8 output against the tiled kernel's
+            fq.debug_force_stream(0)
+            tiled = fq.flexiq_mixed_gemm(hl, Xd, q=True, out_scale=so)["q"]
+            fq.debug_force_stream(1)
+            only_q = fq.flexiq_mixed_gemm(hl, Xd, q=True, out_scale=so)["q"]
+            assert bool((tiled == only_q).all()) and bool((only_q == out["q"]).all()), r
+    finally:
+        fq.debug_force_stream(-1)
