@@ -7,8 +7,8 @@
 // Here a block keeps the weights of its (up to 256) output columns in LDS for its whole life, position-expanded copies
 // for the 4-bit channel groups and 8-bit tiles for the others (Section 7: cached 4-bit parameters), and walks row tiles
 // of 128 rows: the whole tile (all channels) is copied from global memory straight into an LDS ring, several tiles ahead
-// of its use, whatever the ratio; the bit-lowering of the activations of 4-bit groups (Section 4.1) is applied to the
-// MFMA operand fragment in registers, between the LDS read and the matrix instruction.  Same int8 MFMA, same int32
+// of its use, whatever the ratio; the bit-lowering of the activations of 4-bit groups (Section 4.1) is one pass of the
+// whole block over the landed tile, in place in LDS, before any fragment is read.  Same int8 MFMA, same int32
 // accumulators and the same epilogue arithmetic as the tiled kernel: bit-identical outputs.
 //
 // Lane roles as in the tiled kernel: the MFMA "A" operand is the weight fragment (32 output channels x 32 channels of
@@ -64,30 +64,69 @@ __device__ __forceinline__ uint32_t lower4(uint32_t d, v2s lo2, v2s hi2, uint32_
 // of 8 consecutive rows (same logical piece) fall into 8 different 16-byte bank groups.
 __device__ __forceinline__ int swizzle(int row, int P) { return P == 4 ? (row >> 1) & 3 : row & (P - 1); }
 
-// NT: 32-column fragments of the block (its columns are 32 * NT); UNITS: 32-channel units (C = 32 * UNITS); CW: waves that
-// share a group of 32 rows and split the block's columns between them (1: four waves, 2: eight waves per block, two per SIMD)
-template <int NT, int UNITS, int CW>
-__global__ __launch_bounds__(256 * CW, (NT / CW == 8 || UNITS == 8) ? 2 : 4) void k_stream(const Params p)
+// Copies row tile t (all channels of its 128 rows) into a ring slot: copy j of a wave moves the 1 KB that holds LDS pieces
+// 64 (wave + NW j) .. + 63; voff[j] is the lane's source offset inside the tile (piece order permuted, see swizzle).
+template <int C, int COPIES, int NW>
+__device__ __forceinline__ void issue_tile(const Params &p, unsigned char *dst, const int *voff, int t, int wave)
 {
+    const int64_t m0 = (int64_t)t * kRows;
+    const int64_t left = p.M - m0;
+    const int win = (int)(left < kRows ? left : kRows) * C;    // rows beyond M read as zeros
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)(p.X + m0 * C), 0, win, kRsrcFlags);
+#pragma unroll
+    for (int j = 0; j < COPIES; ++j)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr_t)(dst + 1024 * (wave + NW * j)), 16, voff[j], 0, 0, 0);
+}
+
+// Blocks per compute unit and ring depth for a block of 32 * nt columns and 32 * units channels: the pair that keeps most
+// tiles in flight per compute unit (a slot is a whole tile; two to four slots per block; at most two blocks when a wave
+// would otherwise hold eight fragment columns of accumulators).  per_cu == 0: does not fit.
+struct Plan {
+    int per_cu, slots;
+};
+constexpr Plan plan(int nt, int units)
+{
+    const int bn = 32 * nt, wbytes = units * 2 * (bn + 2) * 16, slot = kRows * 32 * units;
+    Plan best = {0, 0};
+    int score = -1;
+    for (int b = nt == 8 ? 2 : 4; b >= 1; --b) {
+        int s = ((160 * 1024) / b - wbytes - 2 * bn * 4 - 128) / slot;
+        if (s > 4) s = 4;
+        if (s >= 2 && b * (s - 1) > score) {
+            score = b * (s - 1);
+            best = {b, s};
+        }
+    }
+    return best;
+}
+
+// NT: 32-column fragments of the block (its columns are 32 * NT); UNITS: 32-channel units (C = 32 * UNITS); CW: waves that
+// share a group of 32 rows and split the block's columns between them (1: four waves, 2: eight waves per block, two per SIMD);
+// QONLY: the call writes int8 rows and nothing else (the usual case between layers): a build without the other outputs'
+// address arithmetic, whose registers would otherwise spill, and a reload from scratch waits for every copy in flight
+template <int NT, int UNITS, int CW, bool QONLY>
+__global__ __launch_bounds__(256 * CW, plan(NT, UNITS).per_cu * CW) void k_stream(const Params p)   // (second figure: waves per SIMD)
+{
+    static_assert(CW == (plan(NT, UNITS).per_cu <= 2 ? 2 : 1), "eight waves where at most two blocks share a compute unit");
     extern __shared__ __align__(16) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 31, fh = lane >> 5;
     const int rg = wave & 3, ch = wave >> 2;      // row group of the wave, and which share of the columns it computes
     constexpr int NW = 4 * CW, NTW = NT / CW;     // waves per block, fragment columns per wave
     static_assert(NT % CW == 0, "the columns split evenly");
-    const int P = p.C >> 4;                        // 16-byte pieces per row
+    constexpr int C = 32 * UNITS, P = 2 * UNITS;   // channels and 16-byte pieces per row
     const int n_blk = blockIdx.y * kMaxCols;       // first output column of this block
     constexpr int BN = 32 * NT;
     constexpr int NS = BN + 2;                     // rows per weight k-plane in LDS (+2: the two planes of a fragment read hit different banks)
-    const int wbytes = p.units * 2 * NS * 16;
+    constexpr int wbytes = UNITS * 2 * NS * 16;
     float *const tab = reinterpret_cast<float *>(lds + wbytes);          // [BN] multipliers, [BN] addends
     unsigned char *const ring = lds + wbytes + 2 * BN * 4 + 128;   // (the ring starts on a 128-byte boundary of its own)
-    const int slot_bytes = kRows * p.C;
+    constexpr int slot_bytes = kRows * C;
 
     // ---- weights of the block's columns: unit u, k-plane pl, 64 rows per copy instruction
     {
         const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void *)p.W8, 0, 2 * p.w4x_delta, kRsrcFlags);
-        const int copies = p.units * 2 * (BN / 64 > 0 ? BN / 64 : 1);
+        constexpr int copies = UNITS * 2 * (BN / 64 > 0 ? BN / 64 : 1);
         for (int i = wave; i < copies; i += NW) {
             const int per_plane = BN / 64 > 0 ? BN / 64 : 1;
             const int plane = i / per_plane, blk = i % per_plane;      // plane = 2 u + pl
@@ -98,7 +137,7 @@ __global__ __launch_bounds__(256 * CW, (NT / CW == 8 || UNITS == 8) ? 2 : 4) voi
         }
     }
     // ---- scales and biases (pre-multiplied for the int8 output when it is the only scaled one), positions
-    const bool pre_scaled = p.q != nullptr && p.y == nullptr;
+    const bool pre_scaled = QONLY || (p.q != nullptr && p.y == nullptr);
     for (int c = tid; c < BN; c += 64 * NW) {
         const int n = n_blk + c;
         const float cs = n < p.Npad ? p.cs[n] : 0.0f, bi = n < p.Npad ? p.cs[p.Npad + n] : 0.0f;
@@ -113,41 +152,32 @@ __global__ __launch_bounds__(256 * CW, (NT / CW == 8 || UNITS == 8) ? 2 : 4) voi
 
     // ---- copies of a row tile into a ring slot: LDS piece index q = 64 (wave + 4 j) + lane holds row q / P, logical
     // piece (q % P) ^ swizzle(row)
-    const int copies_x = (kRows * P) / (64 * NW);   // per wave: 2 (C = 64), 4, 8 (C = 256) with four waves, half with eight
-    int voff[8];
+    constexpr int copies_x = (kRows * P) / (64 * NW);   // per wave: 2 (C = 64), 4, 8 (C = 256) with four waves, half with eight
+    int voff[copies_x];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < copies_x; ++j) {
         const int qi = 64 * (wave + NW * j) + lane;
         const int row = qi / P, pp = qi % P;
-        voff[j] = row * p.C + ((pp ^ swizzle(row, P)) << 4);
+        voff[j] = row * C + ((pp ^ swizzle(row, P)) << 4);
     }
-    auto issue_tile = [&](int t, int slot) {
-        const int64_t m0 = (int64_t)t * kRows;
-        const int64_t left = p.M - m0;
-        const int win = (int)(left < kRows ? left : kRows) * p.C;    // rows beyond M read as zeros
-        const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)(p.X + m0 * p.C), 0, win, kRsrcFlags);
-        unsigned char *dst = ring + slot * slot_bytes;
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-            if (j < copies_x) __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr_t)(dst + 1024 * (wave + NW * j)), 16, voff[j], 0, 0, 0);
-    };
 
     // ---- prologue: the first slots - 1 tiles of this block are put in flight
     const int D = p.slots - 1;   // tiles in flight ahead of the one being computed
     int t_load = blockIdx.x, slot_load = 0;
     for (int k = 0; k < D; ++k) {
-        if (t_load < p.tiles) issue_tile(t_load, slot_load);
+        if (t_load < p.tiles) issue_tile<C, copies_x, NW>(p, ring + slot_load * slot_bytes, voff, t_load, wave);
         t_load += gridDim.x;
         slot_load = slot_load + 1 == p.slots ? 0 : slot_load + 1;
     }
 
-    const int xrow = (32 * rg + fr) * p.C;
+    const int xrow = (32 * rg + fr) * C;
+    const bool q_rows = p.q != nullptr && (p.N & 15) == 0;   // int8 rows are stored in 16-byte pieces
     const int xswz = swizzle(32 * rg + fr, P);
     int slot = 0;
     for (int t = blockIdx.x; t < p.tiles; t += gridDim.x) {
         // the slot that receives tile t + D was read during the previous iteration: every wave is past it
         __builtin_amdgcn_s_barrier();
-        if (t_load < p.tiles) issue_tile(t_load, slot_load);
+        if (t_load < p.tiles) issue_tile<C, copies_x, NW>(p, ring + slot_load * slot_bytes, voff, t_load, wave);
         const bool issued = t_load < p.tiles;
         t_load += gridDim.x;
         slot_load = slot_load + 1 == p.slots ? 0 : slot_load + 1;
@@ -158,17 +188,12 @@ __global__ __launch_bounds__(256 * CW, (NT / CW == 8 || UNITS == 8) ? 2 : 4) voi
             for (int k = 1, tt = t + (int)gridDim.x; k <= D; ++k, tt += gridDim.x)
                 if (tt < p.tiles) ++newer;
             (void)issued;
-            const int pending = newer * copies_x;
-            // (the immediate must not exceed the copies issued after tile t: rounded down to a value that has a case)
-            if (pending >= 24) __builtin_amdgcn_s_waitcnt(0x4070 | 8);
-            else if (pending >= 16) __builtin_amdgcn_s_waitcnt(0x4070 | 0);
-            else if (pending >= 12) __builtin_amdgcn_s_waitcnt(0x0070 | 12);
-            else if (pending >= 8) __builtin_amdgcn_s_waitcnt(0x0070 | 8);
-            else if (pending >= 6) __builtin_amdgcn_s_waitcnt(0x0070 | 6);
-            else if (pending >= 4) __builtin_amdgcn_s_waitcnt(0x0070 | 4);
-            else if (pending >= 3) __builtin_amdgcn_s_waitcnt(0x0070 | 3);
-            else if (pending >= 2) __builtin_amdgcn_s_waitcnt(0x0070 | 2);
-            else if (pending >= 1) __builtin_amdgcn_s_waitcnt(0x0070 | 1);
+            // the immediate is the number of copies issued after tile t: vmcnt in bits 3:0 and 15:14, lgkmcnt 0
+            constexpr int w1 = copies_x, w2 = 2 * copies_x, w3 = 3 * copies_x;
+            static_assert(w3 <= 63, "the counter has six bits");
+            if (newer >= 3) __builtin_amdgcn_s_waitcnt(0x0070 | (w3 & 15) | ((w3 >> 4) << 14));
+            else if (newer == 2) __builtin_amdgcn_s_waitcnt(0x0070 | (w2 & 15) | ((w2 >> 4) << 14));
+            else if (newer == 1) __builtin_amdgcn_s_waitcnt(0x0070 | (w1 & 15) | ((w1 >> 4) << 14));
             else __builtin_amdgcn_s_waitcnt(0x0070);
         }
         __builtin_amdgcn_s_waitcnt(0xc07f);
@@ -188,7 +213,7 @@ __global__ __launch_bounds__(256 * CW, (NT / CW == 8 || UNITS == 8) ? 2 : 4) voi
             for (int k = 0; k < kPasses; ++k) {   // all reads first: their latencies overlap
                 const int idx = tid + k * 64 * NW;
                 const int row = idx & (kRows - 1), l = idx >> 7;
-                where[k] = reinterpret_cast<v4i *>(xt + row * p.C + ((l ^ swizzle(row, P)) << 4));
+                where[k] = reinterpret_cast<v4i *>(xt + row * C + ((l ^ swizzle(row, P)) << 4));
                 if (idx < kRows * 2 * n_low) {
                     piece[k] = *where[k];
                     // (the ring is only ever written by the copy instructions, which the compiler does not see as stores
@@ -216,31 +241,16 @@ __global__ __launch_bounds__(256 * CW, (NT / CW == 8 || UNITS == 8) ? 2 : 4) voi
             __builtin_amdgcn_s_barrier();
         }
         const unsigned char *xs = ring + slot * slot_bytes + xrow;
-        v16i acc[NTW];
-#pragma unroll
-        for (int a = 0; a < NTW; ++a)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][i] = 0;
-        // all activation fragments of the tile first (UNITS x 16 bytes per lane), then unit by unit: weight fragments and
-        // matrix instructions
+        // all activation fragments of the tile first (UNITS x 16 bytes per lane); then fragment column by fragment column:
+        // its weight fragments and matrix instructions, then its epilogue, whose vector-ALU work the scheduler (and the
+        // other wave of the SIMD) overlaps with the matrix instructions of the next column
         v4i bfrag[UNITS];
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) bfrag[u] = *reinterpret_cast<const v4i *>(xs + (((2 * u + fh) ^ xswz) << 4));
-#pragma unroll
-        for (int u = 0; u < UNITS; ++u) {
-            const v4i b = bfrag[u];
-            const unsigned char *ws = lds + ((2 * u + fh) * NS + ch * (32 * NTW) + fr) * 16;
-#pragma unroll
-            for (int a = 0; a < NTW; ++a) {
-                const v4i w = *reinterpret_cast<const v4i *>(ws + a * 512);
-                acc[a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w, b, acc[a], 0, 0, 0);
-            }
-        }
 
-        // ---- epilogue of the tile.  Lane: row m; accumulator register 4 g + i of fragment a: column 32 a + 8 g + 4 fh + i
+        // Lane: row m; accumulator register 4 g + i of fragment column a: output column 32 a + 8 g + 4 fh + i
         const int64_t m = (int64_t)t * kRows + 32 * rg + fr;
         const bool row_ok = m < p.M;
-        const bool q_rows = p.q != nullptr && (p.N & 15) == 0;
         // columns left from this lane's first one; made opaque per tile, or the compiler keeps one hoisted lane mask per
         // (fragment, quad, element) in scalar registers and spills them by the hundred
         int lim = p.N - n_blk - 4 * fh;
@@ -248,36 +258,63 @@ __global__ __launch_bounds__(256 * CW, (NT / CW == 8 || UNITS == 8) ? 2 : 4) voi
 #pragma unroll
         for (int a = 0; a < NTW; ++a) {
             const int ca = ch * NTW + a;   // fragment column within the block
+            v16i acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = 0;
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) {
+                const v4i w = *reinterpret_cast<const v4i *>(lds + ((2 * u + fh) * NS + 32 * ca + fr) * 16);
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w, bfrag[u], acc, 0, 0, 0);
+            }
             uint32_t qrow[4];
+            if constexpr (QONLY) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int c = 32 * ca + 8 * g + 4 * fh;
-                const int n = n_blk + c;
-                const float4 mul4 = *reinterpret_cast<const float4 *>(tab + c), add4 = *reinterpret_cast<const float4 *>(tab + BN + c);
-                const float mulv[4] = {mul4.x, mul4.y, mul4.z, mul4.w}, addv[4] = {add4.x, add4.y, add4.z, add4.w};
-                uint32_t qw = 0;
-                if (p.q) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float mu = pre_scaled ? mulv[i] : mulv[i] * p.r_out;
-                        const float ad = pre_scaled ? addv[i] : addv[i] * p.r_out + 128.0f;
-                        qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[a][4 * g + i], mu, ad), i, qw);
-                    }
-                    qw ^= 0x80808080u;
+                for (int g = 0; g < 4; ++g) {
+                    const int c = 32 * ca + 8 * g + 4 * fh;
+                    // (read as integer vectors: a float-typed read of LDS makes the compiler wait for every copy in flight;
+                    // made opaque: what the compiler cannot trace to a store it may take for undefined)
+                    v4i mi = *reinterpret_cast<const v4i *>(lds + wbytes + 4 * c), ai = *reinterpret_cast<const v4i *>(lds + wbytes + 4 * (BN + c));
+                    asm volatile("" : "+v"(mi), "+v"(ai));
+                    uint32_t qw = 0;
+                    qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 0], __int_as_float(mi.x), __int_as_float(ai.x)), 0, qw);
+                    qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 1], __int_as_float(mi.y), __int_as_float(ai.y)), 1, qw);
+                    qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 2], __int_as_float(mi.z), __int_as_float(ai.z)), 2, qw);
+                    qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 3], __int_as_float(mi.w), __int_as_float(ai.w)), 3, qw);
+                    qrow[g] = qw ^ 0x80808080u;
                 }
-                qrow[g] = qw;
-                if (row_ok && (p.acc || p.y || (p.q && !q_rows))) {
+            } else {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        if (c - 4 * fh + i >= lim) continue;
-                        const int64_t o = m * p.N + n + i;
-                        if (p.acc) p.acc[o] = acc[a][4 * g + i];
-                        if (p.y) p.y[o] = __builtin_fmaf((float)acc[a][4 * g + i], mulv[i], addv[i]);
-                        if (p.q && !q_rows) p.q[o] = (int8_t)((qw >> (8 * i)) & 0xFF);
+                for (int g = 0; g < 4; ++g) {
+                    const int c = 32 * ca + 8 * g + 4 * fh;
+                    const int n = n_blk + c;
+                    v4i mi = *reinterpret_cast<const v4i *>(lds + wbytes + 4 * c), ai = *reinterpret_cast<const v4i *>(lds + wbytes + 4 * (BN + c));
+                    asm volatile("" : "+v"(mi), "+v"(ai));
+                    const float mulv[4] = {__int_as_float(mi.x), __int_as_float(mi.y), __int_as_float(mi.z), __int_as_float(mi.w)};
+                    const float addv[4] = {__int_as_float(ai.x), __int_as_float(ai.y), __int_as_float(ai.z), __int_as_float(ai.w)};
+                    uint32_t qw = 0;
+                    if (p.q) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float mu = pre_scaled ? mulv[i] : mulv[i] * p.r_out;
+                            const float ad = pre_scaled ? addv[i] : addv[i] * p.r_out + 128.0f;
+                            qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + i], mu, ad), i, qw);
+                        }
+                        qw ^= 0x80808080u;
+                    }
+                    qrow[g] = qw;
+                    if (row_ok && (p.acc || p.y || (p.q && !q_rows))) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            if (c - 4 * fh + i >= lim) continue;
+                            const int64_t o = m * p.N + n + i;
+                            if (p.acc) p.acc[o] = acc[4 * g + i];
+                            if (p.y) p.y[o] = __builtin_fmaf((float)acc[4 * g + i], mulv[i], addv[i]);
+                            if (p.q && !q_rows) p.q[o] = (int8_t)((qw >> (8 * i)) & 0xFF);
+                        }
                     }
                 }
             }
-            if (q_rows) {
+            if (QONLY || q_rows) {
                 // the two halves of the wave hold alternating 4-byte pieces of a row: after exchanging quads 0 <-> 2
                 // and 1 <-> 3 lanes 0..31 own columns 0..15 of the fragment and lanes 32..63 columns 16..31
                 const auto s02 = __builtin_amdgcn_permlane32_swap(qrow[0], qrow[2], false, false);
@@ -298,7 +335,6 @@ struct DeviceState {
 static DeviceState g_dev[64];
 static int g_force = -1;   // test hook: 1 = take this kernel whenever the layer qualifies, 0 = never, -1 = automatic
 static int g_last = 0;
-static int g_cw = 0;     // experiment hook: waves per row group (0 = automatic)
 
 }  // namespace stream
 
@@ -310,12 +346,10 @@ int prepare_stream_kernels(int device)
     hipDeviceProp_t prop;
     FLEXIQ_HIP(hipGetDeviceProperties(&prop, device));
     g_dev[device].num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    const void *fns[] = {(const void *)k_stream<2, 2, 1>, (const void *)k_stream<2, 4, 1>, (const void *)k_stream<2, 8, 1>,
-                         (const void *)k_stream<4, 2, 1>, (const void *)k_stream<4, 4, 1>, (const void *)k_stream<4, 8, 1>,
-                         (const void *)k_stream<8, 2, 1>, (const void *)k_stream<8, 4, 1>, (const void *)k_stream<8, 8, 1>,
-                         (const void *)k_stream<2, 2, 2>, (const void *)k_stream<2, 4, 2>, (const void *)k_stream<2, 8, 2>,
-                         (const void *)k_stream<4, 2, 2>, (const void *)k_stream<4, 4, 2>, (const void *)k_stream<4, 8, 2>,
-                         (const void *)k_stream<8, 2, 2>, (const void *)k_stream<8, 4, 2>, (const void *)k_stream<8, 8, 2>};
+#define FQ_BOTH(NT_, U_, CW_) (const void *)k_stream<NT_, U_, CW_, false>, (const void *)k_stream<NT_, U_, CW_, true>
+    const void *fns[] = {FQ_BOTH(2, 2, 1), FQ_BOTH(4, 2, 1), FQ_BOTH(8, 2, 2), FQ_BOTH(2, 4, 2), FQ_BOTH(4, 4, 2), FQ_BOTH(8, 4, 2),
+                         FQ_BOTH(2, 8, 2), FQ_BOTH(4, 8, 2), FQ_BOTH(8, 8, 2)};
+#undef FQ_BOTH
     for (const void *fn : fns) FLEXIQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     g_dev[device].ready = true;
     return FLEXIQ_OK;
@@ -337,13 +371,19 @@ int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     const int64_t tiles = (M + kRows - 1) / kRows;
     if (tiles > 0x7fffffff) return FLEXIQ_OK;
     if (g_force < 0) {
-        // Taken where it measures faster than the tiled kernel (ResNet-50 stage 1 / 2 shapes at batch 128 and their
-        // neighbours): enough rows to give every compute unit several tiles; up to 256 output columns with 64 channels,
-        // up to 128 with more; and with 256 channels (one block per compute unit, which cannot hide the vector-ALU pass
-        // of the lowering behind its copies) many more rows and at most half of the channels lowered in the kernel.
+        // Taken where it measures faster than the tiled kernel (ResNet-50 stage 1 - 3 shapes at batch 128 and their
+        // neighbours).  Always: enough row tiles to give every compute unit a few.  64 channels: up to 256 output columns.
+        // 128 channels: up to 512.  256 channels (one block per compute unit, which cannot hide the vector-ALU pass of the
+        // lowering behind its copies): at most half of the channels lowered in the kernel unless there are 128 columns
+        // or more; beyond 256 columns only with at most half lowered.
         const int lowered = L->x_prelowered ? 0 : L->max_4bit_ch;
-        if (tiles < 2 * (int64_t)ds.num_cu || L->N > (L->C == 64 ? 256 : 128)) return FLEXIQ_OK;
-        if (L->C == 256 && (tiles < 8 * (int64_t)ds.num_cu || 2 * lowered > L->C)) return FLEXIQ_OK;
+        if (L->C == 64 && (L->N > 256 || tiles < 2 * (int64_t)ds.num_cu)) return FLEXIQ_OK;
+        if (L->C == 128 && (L->N > 512 || tiles < 2 * (int64_t)ds.num_cu)) return FLEXIQ_OK;
+        if (L->C == 256) {
+            if (L->N <= 256 && (tiles < 8 * (int64_t)ds.num_cu || L->N > 128)) return FLEXIQ_OK;
+            if (L->N > 256 && (L->N > 1024 || tiles * ((L->N + kMaxCols - 1) / kMaxCols) < 2 * (int64_t)ds.num_cu)) return FLEXIQ_OK;
+            if (2 * lowered > L->C && (L->N < 128 || L->N > 256)) return FLEXIQ_OK;
+        }
     }
     Params p = {};
     p.X = X; p.W8 = L->d_w8; p.ashift = L->dynamic ? L->d_ashift_dyn : L->d_ashift; p.cs = L->d_cs;
@@ -360,31 +400,31 @@ int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     const int nt = cols <= 64 ? 2 : (cols <= 128 ? 4 : 8);
     const int bn = 32 * nt;
     const int wbytes = p.units * 2 * (bn + 2) * 16, slot = kRows * L->C;
-    // blocks per compute unit and ring depth: the pair that keeps most tiles in flight per compute unit (a slot is a
-    // whole tile; two to four slots per block; at most two blocks when a wave holds eight fragment columns)
-    int per_cu = 1, slots = 2, best = -1;
-    for (int b = ((nt == 8 || p.units == 8) ? 2 : 4); b >= 1; --b) {
-        const int s = std::min(4, ((160 * 1024) / b - wbytes - 2 * bn * 4 - 128) / slot);
-        if (s >= 2 && b * (s - 1) > best) {
-            best = b * (s - 1);
-            per_cu = b;
-            slots = s;
-        }
-    }
-    if (best < 0) return FLEXIQ_OK;
+    const Plan pl = plan(nt, p.units);
+    if (pl.per_cu == 0) return FLEXIQ_OK;
+    const int per_cu = pl.per_cu, slots = pl.slots;
     p.slots = slots;
     const size_t lds = (size_t)wbytes + 2 * bn * 4 + 128 + (size_t)slots * slot;
-    const unsigned gx = (unsigned)std::min<int64_t>(tiles, (int64_t)ds.num_cu * per_cu);
+    // One resident wave of blocks in all: every block loads its weights once and walks tiles / gx row tiles.  With several
+    // column blocks (grid.y) the blocks of one row share gx = 0 mod 8, i.e. one XCD and its L2, which then fetches the
+    // activation rows from memory once.
     const unsigned gy = (unsigned)((L->N + kMaxCols - 1) / kMaxCols);
+    int64_t gx64 = std::max<int64_t>(1, std::min<int64_t>(tiles, (int64_t)ds.num_cu * per_cu / gy));
+    if (gy > 1 && gx64 >= 8) gx64 &= ~(int64_t)7;
+    const unsigned gx = (unsigned)gx64;
     // eight waves per block (two per SIMD, each pair sharing its rows and splitting the columns) where LDS leaves room
-    // for one or two blocks only: the second wave of a SIMD then fills the gaps of the first
-    const int cw = g_cw > 0 ? g_cw : (per_cu <= 2 ? 2 : 1);
+    // for one or two blocks only: the second wave of a SIMD then fills the gaps of the first.  That is every shape but
+    // 64 channels with at most 128 columns.
+    const int cw = per_cu <= 2 ? 2 : 1;
+    if (cw == 1 && !(p.units == 2 && nt <= 4)) return FLEXIQ_EINVAL;   // (no such build: cannot happen with the sizes above)
+    const bool q_only = out->q && !out->acc && !out->y && (L->N & 15) == 0;
     void (*fn)(const Params) = nullptr;
-    const int ui = p.units;
-#define FQ_PICK(NT_, CW_) (ui == 2 ? k_stream<NT_, 2, CW_> : (ui == 4 ? k_stream<NT_, 4, CW_> : k_stream<NT_, 8, CW_>))
-    if (cw == 1) fn = nt == 2 ? FQ_PICK(2, 1) : (nt == 4 ? FQ_PICK(4, 1) : FQ_PICK(8, 1));
-    else fn = nt == 2 ? FQ_PICK(2, 2) : (nt == 4 ? FQ_PICK(4, 2) : FQ_PICK(8, 2));
-#undef FQ_PICK
+#define FQ_Q(NT_, U_, CW_) (q_only ? k_stream<NT_, U_, CW_, true> : k_stream<NT_, U_, CW_, false>)
+    if (cw == 1) fn = nt == 2 ? FQ_Q(2, 2, 1) : FQ_Q(4, 2, 1);
+    else if (p.units == 2) fn = FQ_Q(8, 2, 2);
+    else if (p.units == 4) fn = nt == 2 ? FQ_Q(2, 4, 2) : (nt == 4 ? FQ_Q(4, 4, 2) : FQ_Q(8, 4, 2));
+    else fn = nt == 2 ? FQ_Q(2, 8, 2) : (nt == 4 ? FQ_Q(4, 8, 2) : FQ_Q(8, 8, 2));
+#undef FQ_Q
     hipLaunchKernelGGL(fn, dim3(gx, gy), dim3(256 * cw), lds, (hipStream_t)stream_, p);
     FLEXIQ_HIP(hipGetLastError());
     *taken = 1;
