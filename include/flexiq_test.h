@@ -37,6 +37,12 @@ int flexiq_debug_force_splits(int n);
  * last GEMM / convolution call ran on it. */
 int flexiq_debug_force_stream(int mode);
 
+/* The 3x3 convolution kernel for 64 or 128 input channels, stride 1, padding 1 (last launch: tile shape index -3):
+ * mode 1 = take it whenever the layer form qualifies (whatever the tile count), 0 = never, -1 = automatic;
+ * rows_per_tile > 0 forces the output rows of an image tile (0 = automatic).  Returns whether the last convolution call
+ * ran on it. */
+int flexiq_debug_force_conv3(int mode, int rows_per_tile);
+
 /* Force tile shape `index` of the FP6-variant kernel's table (-1 = automatic).  Returns the table size. */
 int flexiq_debug_force_fp6_tile(int index);
 

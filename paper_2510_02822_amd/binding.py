@@ -80,6 +80,7 @@ def load():
     L.flexiq_debug_force_fp6_tile.argtypes = [C.c_int]
     L.flexiq_debug_force_splits.argtypes = [C.c_int]
     L.flexiq_debug_force_stream.argtypes = [C.c_int]
+    L.flexiq_debug_force_conv3.argtypes = [C.c_int, C.c_int]
     L.flexiq_small_m_workspace_bytes.argtypes = [C.c_void_p]
     L.flexiq_small_m_workspace_bytes.restype = C.c_int64
     L.flexiq_debug_force_tile.argtypes = [C.c_int]
@@ -413,6 +414,15 @@ def debug_last_launch() -> dict:
     L = load()
     return {"tile": L.flexiq_debug_last_launch(0), "blocks": L.flexiq_debug_last_launch(1),
             "resident": L.flexiq_debug_last_launch(2), "splits": L.flexiq_debug_last_launch(3)}
+
+
+def debug_force_conv3(mode: int, rows_per_tile: int = 0) -> int:
+    """3x3 kernel with resident weights: 1 = whenever the layer form qualifies, 0 = never, -1 = automatic; rows_per_tile > 0
+    forces the output rows of an image tile; returns whether the last convolution call used it."""
+    rc = load().flexiq_debug_force_conv3(int(mode), int(rows_per_tile))
+    if rc < 0:
+        _check(rc)
+    return rc
 
 
 def debug_force_stream(mode: int) -> int:

@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libflexiq.so")
 NUM_TILE_SHAPES = 15
 # (source, object, extra flags): the kernel of every tile shape is a translation unit of its own
 UNITS = [("pack.hip", "pack.o", []), ("gemm.hip", "gemm.o", []), ("fp6_gemm.hip", "fp6_gemm.o", []),
-         ("smallm.hip", "smallm.o", []), ("stream.hip", "stream.o", [])] + \
+         ("smallm.hip", "smallm.o", []), ("stream.hip", "stream.o", []), ("conv3.hip", "conv3.o", [])] + \
         [("mixed_tile.hip", "mixed_tile_%d.o" % i, ["-DFQ_TILE=%d" % i]) for i in range(NUM_TILE_SHAPES)]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

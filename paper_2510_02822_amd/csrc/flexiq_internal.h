@@ -32,6 +32,7 @@ void set_hip_error(hipError_t e, const char *what);
 int prepare_kernels(int device);
 int prepare_fp6_kernels(int device);
 int prepare_stream_kernels(int device);
+int prepare_conv3_kernels(int device);
 
 // Order hash of a channel permutation (FNV-1a over the 32-bit entries; `n` entries, identity when p == nullptr).
 inline uint64_t order_hash(const int32_t *p, int n)
@@ -73,6 +74,9 @@ int launch_small_m(const flexiq_layer *L, const int8_t *X, int64_t M, const flex
                    int *splits_out);
 // (stream.hip) the row-streaming kernel for layers with a short reduction; *taken = 0: the call does not qualify
 int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, bool rows_contiguous, int *taken);
+// (conv3.hip) 3x3 convolutions, stride 1, padding 1, with 64 or 128 input channels: weights of all taps resident in LDS,
+// image tiles streamed past them; *taken = 0: the call does not qualify
+int launch_conv3(const flexiq_layer *L, const int8_t *X, int B, int H, int W, int stride, int pad, const flexiq_out *out, void *stream, int *taken);
 }  // namespace flexiq
 
 // Device layouts (all offsets in bytes unless noted), T = R*S filter taps, CUp = C/32 rounded up to

@@ -370,6 +370,20 @@ extern "C" int flexiq_mixed_conv_implicit(const flexiq_layer *L, const int8_t *X
     if (rc) return rc;
     if (!X) return FLEXIQ_EINVAL;
     if (reinterpret_cast<uintptr_t>(X) & 15u) return FLEXIQ_EALIGN;
+    {   // 3x3, stride 1, padding 1, 64 or 128 channels: the kernel that keeps all taps' weights resident (conv3.hip)
+        int taken = 0;
+        if (g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0) {
+            rc = launch_conv3(L, X, B, H, W, stride, pad, out, stream, &taken);
+            if (rc != FLEXIQ_OK) return rc;
+        }
+        if (taken) {
+            g_last_shape = -3;
+            g_last_blocks = 0;
+            g_last_resident = 0;
+            g_last_splits = 1;
+            return FLEXIQ_OK;
+        }
+    }
     // a 1x1 convolution with stride 1 and no padding is the linear form over the pixels: no per-tap address arithmetic
     if (L->R == 1 && L->S == 1 && stride == 1 && pad == 0) return launch(L, X, M, out, stream, false, 1, 1, 1, 1, 1, 0);
     return launch(L, X, M, out, stream, true, H, W, Ho, Wo, stride, pad);

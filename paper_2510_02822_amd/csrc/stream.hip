@@ -18,14 +18,12 @@
 
 #include "flexiq_internal.h"
 #include "flexiq_test.h"
+#include "stream_common.h"
 
 namespace flexiq {
 namespace stream {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef short v2s __attribute__((ext_vector_type(2)));
-typedef __attribute__((address_space(3))) void *lds_ptr_t;
+using namespace resident;
 
 struct Params {
     const int8_t *X;        // int8 [M][C], stored channel order
@@ -48,21 +46,6 @@ struct Params {
 
 constexpr int kRows = 128;        // rows per tile: four waves x 32
 constexpr int kMaxCols = 256;     // output columns per block (grid.y walks wider layers)
-constexpr int kRsrcFlags = 0x00020000;
-
-__device__ __forceinline__ uint32_t lower4(uint32_t d, v2s lo2, v2s hi2, uint32_t mask)
-{
-    v2s o = __builtin_bit_cast(v2s, d);   // odd bytes sit on top of the 16-bit halves
-    v2s e = o << (short)8;                // even bytes moved up
-    o = __builtin_elementwise_min(__builtin_elementwise_max(o, lo2), hi2);
-    e = __builtin_elementwise_min(__builtin_elementwise_max(e, lo2), hi2);
-    const uint32_t r = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, o), __builtin_bit_cast(uint32_t, e), 0x07030501u);
-    return r & mask;
-}
-
-// LDS image of a row tile: row-major, C bytes per row, the 16-byte pieces of a row permuted so that the fragment reads
-// of 8 consecutive rows (same logical piece) fall into 8 different 16-byte bank groups.
-__device__ __forceinline__ int swizzle(int row, int P) { return P == 4 ? (row >> 1) & 3 : row & (P - 1); }
 
 // Copies row tile t (all channels of its 128 rows) into a ring slot: copy j of a wave moves the 1 KB that holds LDS pieces
 // 64 (wave + NW j) .. + 63; voff[j] is the lane's source offset inside the tile (piece order permuted, see swizzle).
@@ -172,11 +155,12 @@ __global__ __launch_bounds__(256 * CW, plan(NT, UNITS).per_cu * CW) void k_strea
 
     const int xrow = (32 * rg + fr) * C;
     const bool q_rows = p.q != nullptr && (p.N & 15) == 0;   // int8 rows are stored in 16-byte pieces
+    const FragOut fo = {p.acc, p.y, p.q, p.r_out, p.N};
     const int xswz = swizzle(32 * rg + fr, P);
     int slot = 0;
     for (int t = blockIdx.x; t < p.tiles; t += gridDim.x) {
         // the slot that receives tile t + D was read during the previous iteration: every wave is past it
-        __builtin_amdgcn_s_barrier();
+        block_barrier();
         if (t_load < p.tiles) issue_tile<C, copies_x, NW>(p, ring + slot_load * slot_bytes, voff, t_load, wave);
         const bool issued = t_load < p.tiles;
         t_load += gridDim.x;
@@ -197,7 +181,7 @@ __global__ __launch_bounds__(256 * CW, plan(NT, UNITS).per_cu * CW) void k_strea
             else __builtin_amdgcn_s_waitcnt(0x0070);
         }
         __builtin_amdgcn_s_waitcnt(0xc07f);
-        __builtin_amdgcn_s_barrier();
+        block_barrier();
 
         // ---- bit-lowering (Section 4.1) of the tile's 4-bit channels, in place: every 16-byte piece of those channels
         // once, by all threads of the block (a wave takes 64 consecutive rows of one piece column, so the position is
@@ -227,18 +211,11 @@ __global__ __launch_bounds__(256 * CW, plan(NT, UNITS).per_cu * CW) void k_strea
                 if (idx >= kRows * 2 * n_low) continue;
                 const int l = idx >> 7;
                 const int sa = (int)((sap >> (4 * ((l >> 1) >> p.gs_shift))) & 15u);
-                const short lo = (short)((-(8 << sa)) << 8), hi = (short)((((8 << sa) - 1) << 8) | 0xFF);
-                const v2s lo2 = {lo, lo}, hi2 = {hi, hi};
-                const uint32_t mask = 0x01010101u * ((0xFFu << sa) & 0xFFu);
-                v4i b = piece[k];
-                b.x = (int)lower4((uint32_t)b.x, lo2, hi2, mask);
-                b.y = (int)lower4((uint32_t)b.y, lo2, hi2, mask);
-                b.z = (int)lower4((uint32_t)b.z, lo2, hi2, mask);
-                b.w = (int)lower4((uint32_t)b.w, lo2, hi2, mask);
+                const v4i b = lower16(piece[k], sa);
                 *where[k] = b;
             }
             __builtin_amdgcn_s_waitcnt(0xc07f);
-            __builtin_amdgcn_s_barrier();
+            block_barrier();
         }
         const unsigned char *xs = ring + slot * slot_bytes + xrow;
         // all activation fragments of the tile first (UNITS x 16 bytes per lane); then fragment column by fragment column:
@@ -266,62 +243,7 @@ __global__ __launch_bounds__(256 * CW, plan(NT, UNITS).per_cu * CW) void k_strea
                 const v4i w = *reinterpret_cast<const v4i *>(lds + ((2 * u + fh) * NS + 32 * ca + fr) * 16);
                 acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w, bfrag[u], acc, 0, 0, 0);
             }
-            uint32_t qrow[4];
-            if constexpr (QONLY) {
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int c = 32 * ca + 8 * g + 4 * fh;
-                    // (read as integer vectors: a float-typed read of LDS makes the compiler wait for every copy in flight;
-                    // made opaque: what the compiler cannot trace to a store it may take for undefined)
-                    v4i mi = *reinterpret_cast<const v4i *>(lds + wbytes + 4 * c), ai = *reinterpret_cast<const v4i *>(lds + wbytes + 4 * (BN + c));
-                    asm volatile("" : "+v"(mi), "+v"(ai));
-                    uint32_t qw = 0;
-                    qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 0], __int_as_float(mi.x), __int_as_float(ai.x)), 0, qw);
-                    qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 1], __int_as_float(mi.y), __int_as_float(ai.y)), 1, qw);
-                    qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 2], __int_as_float(mi.z), __int_as_float(ai.z)), 2, qw);
-                    qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 3], __int_as_float(mi.w), __int_as_float(ai.w)), 3, qw);
-                    qrow[g] = qw ^ 0x80808080u;
-                }
-            } else {
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int c = 32 * ca + 8 * g + 4 * fh;
-                    const int n = n_blk + c;
-                    v4i mi = *reinterpret_cast<const v4i *>(lds + wbytes + 4 * c), ai = *reinterpret_cast<const v4i *>(lds + wbytes + 4 * (BN + c));
-                    asm volatile("" : "+v"(mi), "+v"(ai));
-                    const float mulv[4] = {__int_as_float(mi.x), __int_as_float(mi.y), __int_as_float(mi.z), __int_as_float(mi.w)};
-                    const float addv[4] = {__int_as_float(ai.x), __int_as_float(ai.y), __int_as_float(ai.z), __int_as_float(ai.w)};
-                    uint32_t qw = 0;
-                    if (p.q) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float mu = pre_scaled ? mulv[i] : mulv[i] * p.r_out;
-                            const float ad = pre_scaled ? addv[i] : addv[i] * p.r_out + 128.0f;
-                            qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + i], mu, ad), i, qw);
-                        }
-                        qw ^= 0x80808080u;
-                    }
-                    qrow[g] = qw;
-                    if (row_ok && (p.acc || p.y || (p.q && !q_rows))) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            if (c - 4 * fh + i >= lim) continue;
-                            const int64_t o = m * p.N + n + i;
-                            if (p.acc) p.acc[o] = acc[4 * g + i];
-                            if (p.y) p.y[o] = __builtin_fmaf((float)acc[4 * g + i], mulv[i], addv[i]);
-                            if (p.q && !q_rows) p.q[o] = (int8_t)((qw >> (8 * i)) & 0xFF);
-                        }
-                    }
-                }
-            }
-            if (QONLY || q_rows) {
-                // the two halves of the wave hold alternating 4-byte pieces of a row: after exchanging quads 0 <-> 2
-                // and 1 <-> 3 lanes 0..31 own columns 0..15 of the fragment and lanes 32..63 columns 16..31
-                const auto s02 = __builtin_amdgcn_permlane32_swap(qrow[0], qrow[2], false, false);
-                const auto s13 = __builtin_amdgcn_permlane32_swap(qrow[1], qrow[3], false, false);
-                const int n = n_blk + 32 * ca + 16 * fh;
-                if (row_ok && 32 * ca + 12 * fh < lim) *reinterpret_cast<v4i *>(p.q + m * p.N + n) = (v4i){(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
-            }
+            store_fragment<QONLY, BN>(acc, fo, lds + wbytes, ca, n_blk, m, row_ok, lim, fh, pre_scaled, q_rows);
         }
         slot = slot + 1 == p.slots ? 0 : slot + 1;
     }

@@ -1,0 +1,131 @@
+// Pieces shared by the kernels that keep a block's weights resident in LDS and stream activations past them
+// (stream.hip: rows of a linear layer; conv3.hip: image rows of a 3x3 convolution): vector types, the bit-lowering of
+// four activation bytes (Section 4.1), the LDS piece permutation, and the epilogue of one 32 x 32 accumulator fragment.
+#pragma once
+#include "flexiq_internal.h"
+
+namespace flexiq {
+namespace resident {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef short v2s __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+constexpr int kRsrcFlags = 0x00020000;
+
+// Block barrier without the counter waits of __syncthreads() (the caller has waited for what it needs).  The barrier
+// builtin is no memory operation to the compiler: the clobbers keep LDS accesses on their side of it.
+__device__ __forceinline__ void block_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// clamp(v >> s, -8, 7) << s for the four int8 values of a dword: lo2 / hi2 hold the bounds in the upper byte of both
+// 16-bit halves, mask clears the s low bits of every byte
+__device__ __forceinline__ uint32_t lower4(uint32_t d, v2s lo2, v2s hi2, uint32_t mask)
+{
+    v2s o = __builtin_bit_cast(v2s, d);   // odd bytes sit on top of the 16-bit halves
+    v2s e = o << (short)8;                // even bytes moved up
+    o = __builtin_elementwise_min(__builtin_elementwise_max(o, lo2), hi2);
+    e = __builtin_elementwise_min(__builtin_elementwise_max(e, lo2), hi2);
+    const uint32_t r = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, o), __builtin_bit_cast(uint32_t, e), 0x07030501u);
+    return r & mask;
+}
+
+// all sixteen bytes of a piece, position sa
+__device__ __forceinline__ v4i lower16(v4i b, int sa)
+{
+    const short lo = (short)((-(8 << sa)) << 8), hi = (short)((((8 << sa) - 1) << 8) | 0xFF);
+    const v2s lo2 = {lo, lo}, hi2 = {hi, hi};
+    const uint32_t mask = 0x01010101u * ((0xFFu << sa) & 0xFFu);
+    b.x = (int)lower4((uint32_t)b.x, lo2, hi2, mask);
+    b.y = (int)lower4((uint32_t)b.y, lo2, hi2, mask);
+    b.z = (int)lower4((uint32_t)b.z, lo2, hi2, mask);
+    b.w = (int)lower4((uint32_t)b.w, lo2, hi2, mask);
+    return b;
+}
+
+// LDS image of activation rows (pixels): row-major, P = 4, 8 or 16 16-byte pieces per row, the pieces of a row permuted so
+// that the fragment reads of sixteen consecutive rows (same logical piece) fall into the sixteen different 16-byte groups
+// of the 64 banks: 16 / P consecutive rows already differ in their position modulo 256 bytes and share a permutation.
+__device__ __forceinline__ int swizzle(int row, int P) { return P == 4 ? (row >> 2) & 3 : (P == 8 ? (row >> 1) & 7 : row & 15); }
+
+struct FragOut {     // the outputs of a call (any may be null) and the requantisation factor 1 / S_out
+    int32_t *acc;
+    float *y;
+    int8_t *q;
+    float r_out;
+    int32_t N;
+};
+
+// Epilogue of one accumulator fragment (32 rows x 32 columns; lane: row m, register 4 g + i: column 32 ca + 8 g + 4 fh + i
+// of the block, n_blk + that of the layer).  tabb: the block's table in LDS, BN multipliers then BN addends (fp32;
+// pre-multiplied by 1 / S_out, with 128 added, when pre_scaled).  lim: columns left from the lane's first one
+// (N - n_blk - 4 fh).  QONLY: int8 rows and nothing else, N a multiple of 16.
+template <bool QONLY, int BN>
+__device__ __forceinline__ void store_fragment(const v16i &acc, const FragOut &o, const unsigned char *tabb, int ca, int n_blk, int64_t m,
+                                               bool row_ok, int lim, int fh, bool pre_scaled, bool q_rows)
+{
+    uint32_t qrow[4];
+    if constexpr (QONLY) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int c = 32 * ca + 8 * g + 4 * fh;
+            // (read as integer vectors: a float-typed read of LDS makes the compiler wait for every copy in flight;
+            // made opaque: what the compiler cannot trace to a store it may take for undefined)
+            v4i mi = *reinterpret_cast<const v4i *>(tabb + 4 * c), ai = *reinterpret_cast<const v4i *>(tabb + 4 * (BN + c));
+            asm volatile("" : "+v"(mi), "+v"(ai));
+            uint32_t qw = 0;
+            qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 0], __int_as_float(mi.x), __int_as_float(ai.x)), 0, qw);
+            qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 1], __int_as_float(mi.y), __int_as_float(ai.y)), 1, qw);
+            qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 2], __int_as_float(mi.z), __int_as_float(ai.z)), 2, qw);
+            qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 3], __int_as_float(mi.w), __int_as_float(ai.w)), 3, qw);
+            qrow[g] = qw ^ 0x80808080u;
+        }
+    } else {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int c = 32 * ca + 8 * g + 4 * fh;
+            const int n = n_blk + c;
+            v4i mi = *reinterpret_cast<const v4i *>(tabb + 4 * c), ai = *reinterpret_cast<const v4i *>(tabb + 4 * (BN + c));
+            asm volatile("" : "+v"(mi), "+v"(ai));
+            const float mulv[4] = {__int_as_float(mi.x), __int_as_float(mi.y), __int_as_float(mi.z), __int_as_float(mi.w)};
+            const float addv[4] = {__int_as_float(ai.x), __int_as_float(ai.y), __int_as_float(ai.z), __int_as_float(ai.w)};
+            uint32_t qw = 0;
+            if (o.q) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float mu = pre_scaled ? mulv[i] : mulv[i] * o.r_out;
+                    const float ad = pre_scaled ? addv[i] : addv[i] * o.r_out + 128.0f;
+                    qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + i], mu, ad), i, qw);
+                }
+                qw ^= 0x80808080u;
+            }
+            qrow[g] = qw;
+            if (row_ok && (o.acc || o.y || (o.q && !q_rows))) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (c - 4 * fh + i >= lim) continue;
+                    const int64_t at = m * o.N + n + i;
+                    if (o.acc) o.acc[at] = acc[4 * g + i];
+                    if (o.y) o.y[at] = __builtin_fmaf((float)acc[4 * g + i], mulv[i], addv[i]);
+                    if (o.q && !q_rows) o.q[at] = (int8_t)((qw >> (8 * i)) & 0xFF);
+                }
+            }
+        }
+    }
+    if (QONLY || q_rows) {
+        // the two halves of the wave hold alternating 4-byte pieces of a row: after exchanging quads 0 <-> 2
+        // and 1 <-> 3 lanes 0..31 own columns 0..15 of the fragment and lanes 32..63 columns 16..31
+        const auto s02 = __builtin_amdgcn_permlane32_swap(qrow[0], qrow[2], false, false);
+        const auto s13 = __builtin_amdgcn_permlane32_swap(qrow[1], qrow[3], false, false);
+        const int n = n_blk + 32 * ca + 16 * fh;
+        if (row_ok && 32 * ca + 12 * fh < lim) *reinterpret_cast<v4i *>(o.q + m * o.N + n) = (v4i){(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+    }
+}
+
+}  // namespace resident
+}  // namespace flexiq
