@@ -137,14 +137,16 @@ __global__ __launch_bounds__(64 * (kWaves + 1), 3) void k_conv3(const Params p) 
     const int n_low = p.x_pre ? 0 : p.units4;
     uint32_t sa_packed = 0;   // positions of up to 4 groups, four bits each
     for (int g = 0; g < (n_low > 0 ? ((n_low - 1) >> p.gs_shift) + 1 : 0); ++g) sa_packed |= (uint32_t)p.ashift[g] << (4 * g);
-    const int grid = gridDim.x;
+    // a block walks a run of consecutive tiles: the input rows two neighbouring tiles share are then fetched from memory
+    // once (by this block's XCD) instead of once per L2
+    const int t_first = (int)((int64_t)blockIdx.x * p.tiles / gridDim.x), t_end = (int)((int64_t)(blockIdx.x + 1) * p.tiles / gridDim.x);
     if (wave == kWaves) {
         // ================= the loading wave =================
         // LDS piece q = 64 j + lane of a tile buffer holds pixel q / P (row-major over TR + 2 rows of W + 2 pixels),
         // logical piece (q % P) ^ swizzle(pixel).  voff[j]: its source offset relative to the first pixel of the tile's
         // first output row; pixels of the zero columns get an offset beyond every window.
         int voff[kMaxCopies];
-        int t_load = blockIdx.x, b_load = 0;
+        int t_load = t_first, b_load = 0;
         const int ahead = p.nbuf - 1;
         {
             // (one division; from copy to copy the pixel advances by 64 / P)
@@ -162,19 +164,19 @@ __global__ __launch_bounds__(64 * (kWaves + 1), 3) void k_conv3(const Params p) 
         }
         // the first tiles are on their way while the other waves fetch the weights
         for (int k = 0; k < ahead; ++k) {
-            if (t_load < p.tiles) issue_tile<C>(p, bufs + b_load * tile_bytes, voff, t_load);
-            t_load += grid;
+            if (t_load < t_end) issue_tile<C>(p, bufs + b_load * tile_bytes, voff, t_load);
+            ++t_load;
             b_load = b_load + 1 == p.nbuf ? 0 : b_load + 1;
         }
         block_barrier();   // (the computing waves' weights and tables are in place)
-        for (int t = blockIdx.x; t < p.tiles; t += grid) {
+        for (int t = t_first; t < t_end; ++t) {
             // tile t has landed once at most the copies of the tiles issued after it are outstanding
             int newer = 0;
-            for (int k = 1; k < ahead; ++k) newer += t + k * grid < p.tiles ? 1 : 0;
+            for (int k = 1; k < ahead; ++k) newer += t + k < t_end ? 1 : 0;
             wait_outstanding(newer * p.copies);
             block_barrier();     // A: tile t may be read; the buffer of tile t - 1 is free
-            if (t_load < p.tiles) issue_tile<C>(p, bufs + b_load * tile_bytes, voff, t_load);
-            t_load += grid;
+            if (t_load < t_end) issue_tile<C>(p, bufs + b_load * tile_bytes, voff, t_load);
+            ++t_load;
             b_load = b_load + 1 == p.nbuf ? 0 : b_load + 1;
             if (n_low > 0) block_barrier();   // L: the computing waves have lowered tile t
         }
@@ -225,7 +227,7 @@ __global__ __launch_bounds__(64 * (kWaves + 1), 3) void k_conv3(const Params p) 
     const int CPP = (p.npix + 63) >> 6;   // 64-pixel chunks of a tile buffer
 
     int b_cur = 0;
-    for (int t = blockIdx.x; t < p.tiles; t += grid) {
+    for (int t = t_first; t < t_end; ++t) {
         block_barrier();   // A
         unsigned char *xt = bufs + b_cur * tile_bytes;
         if (n_low > 0) {
