@@ -149,21 +149,30 @@ __global__ __launch_bounds__(64 * (kWaves + 1), 3) void k_conv3(const Params p) 
         int t_load = t_first, b_load = 0;
         const int ahead = p.nbuf - 1;
         {
-            // (one division; from copy to copy the pixel advances by 64 / P)
+            // (one division; from copy to copy the pixel advances by 64 / P).  The copies
+            // of the block's first tile are issued as their offsets become known.
             const int pp = lane % P;
             int lp = lane / P;
             int ry = lp / Wp, px = lp - ry * Wp;
+            const bool first = t_first < t_end;
+            const int img = first ? t_first / p.tiles_per_img : 0, y0 = first ? (t_first - img * p.tiles_per_img) * p.TR : 0;
+            const int img_bytes = p.H * p.W * C;
+            const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)(p.X + (int64_t)img * img_bytes), 0, img_bytes, kRsrcFlags);
+            const int row0 = y0 * p.W * C;
 #pragma unroll
             for (int j = 0; j < kMaxCopies; ++j) {
                 const bool real = lp < p.npix && px >= 1 && px <= p.W;
                 voff[j] = real ? ((ry - 1) * p.W + (px - 1)) * C + ((pp ^ swizzle(lp, P)) << 4) : kFar;
+                if (first && j < p.copies) __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr_t)(bufs + 1024 * j), 16, voff[j] + row0, 0, 0, 0);
                 lp += 64 / P;
                 px += 64 / P;
                 while (px >= Wp) px -= Wp, ++ry;
             }
+            ++t_load;
+            b_load = 1 == p.nbuf ? 0 : 1;
         }
-        // the first tiles are on their way while the other waves fetch the weights
-        for (int k = 0; k < ahead; ++k) {
+        // the next tiles are on their way as well while the other waves fetch the weights
+        for (int k = 1; k < ahead; ++k) {
             if (t_load < t_end) issue_tile<C>(p, bufs + b_load * tile_bytes, voff, t_load);
             ++t_load;
             b_load = b_load + 1 == p.nbuf ? 0 : b_load + 1;
