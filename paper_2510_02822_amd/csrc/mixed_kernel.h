@@ -776,7 +776,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                     // last MFMAs and the step boundary), so whichever is behind wins.  Measured: 3-5 % at r = 1 and
                     // 1 % at r = 0 with twenty MFMAs per wave and step, nothing with ten to fourteen; several other
                     // patterns (a level per eighth, wrapping) measured the same within 0.5 %.
-                    if (NW == 8 && NMF >= 10) {
+                    if constexpr (NW == 8 && NMF >= 10) {
                         constexpr int kEighth = 2 * NMF / 8;
                         auto level_at = [](int x) { return x < 8 * kEighth ? 3 - x / (2 * kEighth) : (x < 9 * kEighth ? 0 : 2); };
                         const int level = level_at(g);
