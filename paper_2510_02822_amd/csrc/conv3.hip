@@ -159,14 +159,25 @@ __global__ __launch_bounds__(64 * (kWaves + 1), 3) void k_conv3(const Params p) 
             const int img_bytes = p.H * p.W * C;
             const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)(p.X + (int64_t)img * img_bytes), 0, img_bytes, kRsrcFlags);
             const int row0 = y0 * p.W * C;
+            const bool narrow = Wp < 64 / P;   // (an image row shorter than a copy's pixels: the general form, one division per copy)
 #pragma unroll
             for (int j = 0; j < kMaxCopies; ++j) {
-                const bool real = lp < p.npix && px >= 1 && px <= p.W;
-                voff[j] = real ? ((ry - 1) * p.W + (px - 1)) * C + ((pp ^ swizzle(lp, P)) << 4) : kFar;
-                if (first && j < p.copies) __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr_t)(bufs + 1024 * j), 16, voff[j] + row0, 0, 0, 0);
-                lp += 64 / P;
-                px += 64 / P;
-                while (px >= Wp) px -= Wp, ++ry;
+                voff[j] = kFar;
+                if (j < p.copies) {   // (the whole block waits for this loop: nothing is computed for copies that do not exist)
+                    const bool real = lp < p.npix && px >= 1 && px <= p.W;
+                    voff[j] = real ? ((ry - 1) * p.W + (px - 1)) * C + ((pp ^ swizzle(lp, P)) << 4) : kFar;
+                    if (first) __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr_t)(bufs + 1024 * j), 16, voff[j] + row0, 0, 0, 0);
+                    lp += 64 / P;
+                    if (narrow) {
+                        ry = lp / Wp;
+                        px = lp - ry * Wp;
+                    } else {
+                        px += 64 / P;
+                        const bool wrap = px >= Wp;
+                        px -= wrap ? Wp : 0;
+                        ry += wrap ? 1 : 0;
+                    }
+                }
             }
             ++t_load;
             b_load = 1 == p.nbuf ? 0 : 1;
