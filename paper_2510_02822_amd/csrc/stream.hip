@@ -106,6 +106,29 @@ __global__ __launch_bounds__(256 * CW, plan(NT, UNITS).per_cu * CW) void k_strea
     unsigned char *const ring = lds + wbytes + 2 * BN * 4 + 128;   // (the ring starts on a 128-byte boundary of its own)
     constexpr int slot_bytes = kRows * C;
 
+    // ---- scales and biases (pre-multiplied for the int8 output when it is the only scaled one), positions
+    const bool pre_scaled = QONLY || (p.q != nullptr && p.y == nullptr);
+    for (int c = tid; c < BN; c += 64 * NW) {
+        const int n = n_blk + c;
+        const float cs = n < p.Npad ? p.cs[n] : 0.0f, bi = n < p.Npad ? p.cs[p.Npad + n] : 0.0f;
+        tab[c] = pre_scaled ? cs * p.r_out : cs;
+        tab[BN + c] = pre_scaled ? bi * p.r_out + 128.0f : bi;
+    }
+    // positions of up to 8 groups (C <= 256), four bits each, in one scalar
+    const int n_low = p.x_pre ? 0 : p.units4;
+    uint32_t sa_packed = 0;
+    for (int g = 0; g < (n_low > 0 ? ((n_low - 1) >> p.gs_shift) + 1 : 0); ++g) sa_packed |= (uint32_t)p.ashift[g] << (4 * g);
+    // ---- copies of a row tile into a ring slot: LDS piece index q = 64 (wave + 4 j) + lane holds row q / P, logical
+    // piece (q % P) ^ swizzle(row)
+    constexpr int copies_x = (kRows * P) / (64 * NW);   // per wave: 2 (C = 64), 4, 8 (C = 256) with four waves, half with eight
+    int voff[copies_x];
+#pragma unroll
+    for (int j = 0; j < copies_x; ++j) {
+        const int qi = 64 * (wave + NW * j) + lane;
+        const int row = qi / P, pp = qi % P;
+        voff[j] = row * C + ((pp ^ swizzle(row, P)) << 4);
+    }
+
     // ---- weights of the block's columns: unit u, k-plane pl, 64 rows per copy instruction
     {
         const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void *)p.W8, 0, 2 * p.w4x_delta, kRsrcFlags);
@@ -119,39 +142,25 @@ __global__ __launch_bounds__(256 * CW, plan(NT, UNITS).per_cu * CW) void k_strea
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr_t)(lds + (plane * NS + blk * 64) * 16), 16, lane * 16, soff, 0, 0);
         }
     }
-    // ---- scales and biases (pre-multiplied for the int8 output when it is the only scaled one), positions
-    const bool pre_scaled = QONLY || (p.q != nullptr && p.y == nullptr);
-    for (int c = tid; c < BN; c += 64 * NW) {
-        const int n = n_blk + c;
-        const float cs = n < p.Npad ? p.cs[n] : 0.0f, bi = n < p.Npad ? p.cs[p.Npad + n] : 0.0f;
-        tab[c] = pre_scaled ? cs * p.r_out : cs;
-        tab[BN + c] = pre_scaled ? bi * p.r_out + 128.0f : bi;
-    }
-    // positions of up to 8 groups (C <= 256), four bits each, in one scalar
-    const int n_low = p.x_pre ? 0 : p.units4;
-    uint32_t sa_packed = 0;
-    for (int g = 0; g < (n_low > 0 ? ((n_low - 1) >> p.gs_shift) + 1 : 0); ++g) sa_packed |= (uint32_t)p.ashift[g] << (4 * g);
-    __syncthreads();   // the tables are visible (with the fences of a full barrier: their reads must not move above it)
-
-    // ---- copies of a row tile into a ring slot: LDS piece index q = 64 (wave + 4 j) + lane holds row q / P, logical
-    // piece (q % P) ^ swizzle(row)
-    constexpr int copies_x = (kRows * P) / (64 * NW);   // per wave: 2 (C = 64), 4, 8 (C = 256) with four waves, half with eight
-    int voff[copies_x];
-#pragma unroll
-    for (int j = 0; j < copies_x; ++j) {
-        const int qi = 64 * (wave + NW * j) + lane;
-        const int row = qi / P, pp = qi % P;
-        voff[j] = row * C + ((pp ^ swizzle(row, P)) << 4);
-    }
-
-    // ---- prologue: the first slots - 1 tiles of this block are put in flight
+    // ---- prologue: the first slots - 1 tiles of this block are put in flight, right behind the weights
     const int D = p.slots - 1;   // tiles in flight ahead of the one being computed
     int t_load = blockIdx.x, slot_load = 0;
+    int mine = 0;   // tiles whose copies this wave has issued
     for (int k = 0; k < D; ++k) {
-        if (t_load < p.tiles) issue_tile<C, copies_x, NW>(p, ring + slot_load * slot_bytes, voff, t_load, wave);
+        if (t_load < p.tiles) issue_tile<C, copies_x, NW>(p, ring + slot_load * slot_bytes, voff, t_load, wave), ++mine;
         t_load += gridDim.x;
         slot_load = slot_load + 1 == p.slots ? 0 : slot_load + 1;
     }
+
+    // the weights (issued before the tiles) and the tables are in place: at most the tile copies are outstanding
+    {
+        constexpr int w1 = copies_x, w2 = 2 * copies_x, w3 = 3 * copies_x;
+        if (mine >= 3) __builtin_amdgcn_s_waitcnt(0x0070 | (w3 & 15) | ((w3 >> 4) << 14));
+        else if (mine == 2) __builtin_amdgcn_s_waitcnt(0x0070 | (w2 & 15) | ((w2 >> 4) << 14));
+        else if (mine == 1) __builtin_amdgcn_s_waitcnt(0x0070 | (w1 & 15) | ((w1 >> 4) << 14));
+        else __builtin_amdgcn_s_waitcnt(0x0070);
+    }
+    block_barrier();
 
     const int xrow = (32 * rg + fr) * C;
     const bool q_rows = p.q != nullptr && (p.N & 15) == 0;   // int8 rows are stored in 16-byte pieces
