@@ -55,10 +55,10 @@ def test_conv3_forced(env, B, H, W, C, N, gs, rows):
             got_q = out["q"].cpu().numpy()
             check_q(got_q, ref, ol, so)
             assert (got_q == requant_fp32_sequence(ref, ol, so)).all()
-            if N % 16 == 0:
-                only_q = fq.flexiq_mixed_conv_implicit(hl, Xd, 1, 1, q=True, out_scale=so)["q"]   # the int8-only build
-                assert fq.debug_force_conv3(1, rows) == 1
-                assert (only_q.cpu().numpy() == got_q).all(), r
+            # int8 alone: the int8-only build when rows are whole 16-byte pieces, else the general one with pre-multiplied scales
+            only_q = fq.flexiq_mixed_conv_implicit(hl, Xd, 1, 1, q=True, out_scale=so)["q"]
+            assert fq.debug_force_conv3(1, rows) == 1
+            assert (only_q.cpu().numpy() == got_q).all(), r
             # the tiled kernel gives the same bytes
             fq.debug_force_conv3(0, 0)
             tiled = fq.flexiq_mixed_conv_implicit(hl, Xd, 1, 1, q=True, out_scale=so)["q"]
