@@ -255,7 +255,8 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
     for r in (0.0, 0.5, 1.0):
         fq.flexiq_set_ratio(layer, r)
         us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm(layer, Xq, q=True, out_scale=so, bufs=bufs), 10)
-        rec(wl, "int8 activations, lowered on the fly", r, us, byts=Ml * case.C + case.N * case.C + Ml * case.N)
+        kern = {-2: "row-streaming kernel", -3: "3x3 kernel"}.get(fq.debug_last_launch()["tile"], "tiled kernel")
+        rec(wl, "int8 activations, lowered on the fly", r, us, byts=Ml * case.C + case.N * case.C + Ml * case.N, kernel=kern)
         if r > 0:
             x4 = fq.flexiq_lower_packed4(layer, Xq)
             us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm_packed4(layer, Xq, x4, q=True, out_scale=so, bufs=bufs), 10)
@@ -316,8 +317,16 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
         for tag, fn in (("fixed r", lambda c: 0.0), ("fixed r", lambda c: 0.5), ("fixed r", lambda c: 1.0),
                         ("seeded per-call ratio schedule (mean r = %.2f)" % float(sched.mean()), lambda c: sched[c])):
             us = _median_graph_us(torch, lambda: one_pass(fn), 1, repeats=5, settle_s=0.04)
-            rec(wl, "int8 kernel, " + tag, float(fn(0)) if tag == "fixed r" else None, us, ops=ops, GBs=round(byts / us / 1e3, 1),
-                frac_hbm_peak=round(byts / us / 1e3 / HBM_PEAK_GBS, 4), bound="mixed (mfma / hbm per layer)")
+            # which kernel every call of the pass ran on (eager pass after the timing; the route depends on the ratio)
+            routes = {"tiled": 0, "row-streaming": 0, "3x3 resident weights": 0}
+            for c, (L, j) in enumerate(calls):
+                fq.flexiq_set_ratio(L["layer"], float(fn(c)))
+                fq.flexiq_mixed_conv_implicit(L["layer"], L["X"], L["stride"], L["pad"], q=True, out_scale=L["so"], bufs={"q": L["outs"][j]})
+                t = fq.debug_last_launch()["tile"]
+                routes["row-streaming" if t == -2 else ("3x3 resident weights" if t == -3 else "tiled")] += 1
+            torch.cuda.synchronize()
+            rec(wl, "int8 kernels, " + tag, float(fn(0)) if tag == "fixed r" else None, us, ops=ops, GBs=round(byts / us / 1e3, 1),
+                frac_hbm_peak=round(byts / us / 1e3 / HBM_PEAK_GBS, 4), bound="mixed (mfma / hbm per layer)", calls_per_kernel=routes)
         del layers, calls
     return out
 
