@@ -110,9 +110,10 @@ static int choose_shape(const DeviceKernels &dk, int64_t M, int N, int steps, bo
         const double step = (tab[i].step_alone + lowered_frac * tab[i].lower) * (1.0 + tab[i].share * (conc - 1.0));
         const double prologue = 7000.0;
         const bool walks = tab[i].multi;   // prologue paid once per block
-        // A block that walks several tiles whose K-steps change between lowering and plain copies waits once per tile
-        // for the copies in flight when it enters the next tile's lowering steps (measured: about 3 K cycles per tile).
-        const double phase_stall = walks && seq > 1 && lowered_frac > 0.0 && lowered_frac < 1.0 ? 3000.0 : 0.0;
+        // A block that walks several tiles whose K-steps change between lowering and plain copies waits for the copies in
+        // flight when it goes from plain steps to lowering steps (measured: about 3 K cycles); the tiles of a block take
+        // their phases in alternating order, so that happens once per two tiles.
+        const double phase_stall = walks && seq > 1 && lowered_frac > 0.0 && lowered_frac < 1.0 ? 1500.0 : 0.0;
         const double cost = walks ? prologue + seq * (steps * step + tab[i].epilogue + phase_stall)
                                   : seq * (prologue + steps * step + tab[i].epilogue);
         if (cost < best) {

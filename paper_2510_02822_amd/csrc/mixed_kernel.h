@@ -408,6 +408,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
     const uint64_t pb_tab = ((uint64_t)n4 << 16) | ((uint64_t)(n4 + mixed) << 32);                       // 16 bits per phase
     const uint64_t pe_tab = (uint64_t)n4 | ((uint64_t)(n4 + mixed) << 16) | ((uint64_t)SP << 32);
     const uint32_t pn_tab = (uint32_t)next1 | ((uint32_t)next2 << 4) | (3u << 8) | (3u << 12);             // 4 bits per phase
+    // A block that walks several tiles takes the phases of every other tile in reverse (8-bit steps first): a tile then
+    // begins with the kind of step the previous one ended with, and the change from plain steps to lowering steps, which
+    // costs a wait for every copy in flight (see the step ladder), happens once per two tiles instead of once per tile.
+    // Integer sums do not depend on the order.
+    const int last_phase = ne2 ? 2 : (ne1 ? 1 : (ne0 ? 0 : 3));
+    const int prev1 = ne0 ? 0 : 3, prev2 = ne1 ? 1 : (ne0 ? 0 : 3);
+    const uint32_t pp_tab = 3u | ((uint32_t)prev1 << 4) | ((uint32_t)prev2 << 8) | (3u << 12);            // phase before ph (3 = done)
+    bool it_rev = false;
     // how the activations of a phase's steps are staged: by the phase, unless they arrive lowered already (then
     // every step copies them like an 8-bit step, while the weights still follow the phase)
     const uint32_t pm_tab = p.x_pre ? ((uint32_t)kMode88 | (kMode88 << 4) | (kMode88 << 8) | (kModeNone << 12))
@@ -454,7 +462,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                     it_dx = wrap_x ? 0 : dx1;
                 }
             } else {             // the phase is finished
-                int ph = pn(it_phase);
+                int ph = it_rev ? (int)((pp_tab >> (4 * it_phase)) & 15u) : pn(it_phase);
                 // ... and with it the tile: move on to the block's next tile if there is one
                 if (C_::MULTI && ph == 3) {
                     const int nt = ltile + (int)gridDim.x;
@@ -463,7 +471,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (WAVES_M * WAVES_N == 4 && 
                         int tile_m, tile_n;
                         map_tile(nt, tile_m, tile_n);
                         load_tile_context((int64_t)tile_m * BM, tile_n * BN);
-                        ph = first_phase;
+                        it_rev = !it_rev;
+                        ph = it_rev ? last_phase : first_phase;
                     }
                 }
                 it_dy = 0;
