@@ -111,10 +111,13 @@ static int choose_shape(const DeviceKernels &dk, int64_t M, int N, int steps, bo
         const double prologue = 7000.0;
         const bool walks = tab[i].multi;   // prologue paid once per block
         // A block that walks several tiles whose K-steps change between lowering and plain copies waits for the copies in
-        // flight when it goes from plain steps to lowering steps (measured: about 3 K cycles); the tiles of a block take
-        // their phases in alternating order, so that happens once per two tiles.
-        const double phase_stall = walks && seq > 1 && lowered_frac > 0.0 && lowered_frac < 1.0 ? 1500.0 : 0.0;
-        const double cost = walks ? prologue + seq * (steps * step + tab[i].epilogue + phase_stall)
+        // flight when it goes from plain steps to lowering steps (the tiles of a block take their phases in alternating
+        // order, so that happens once per two tiles).  Priced per tile at what makes the choice match the fastest forced
+        // shape on ViT-L fc1 at r = 0.25 ... 0.75 on two boxes (shapes with many short tiles per block lose more than
+        // the wait alone: 160 x 256 reads 58.6 ... 64 us there, 320 x 256 58.5 on both).
+        const double phase_stall = walks && seq > 1 && lowered_frac > 0.0 && lowered_frac < 1.0 ? 3000.0 : 0.0;
+        const double tile_switch = 1200.0;   // next-tile mapping and window, scale fetch, clearing the accumulators
+        const double cost = walks ? prologue + seq * (steps * step + tab[i].epilogue + phase_stall) + (seq - 1.0) * tile_switch
                                   : seq * (prologue + steps * step + tab[i].epilogue);
         if (cost < best) {
             best = cost;
