@@ -264,7 +264,7 @@ __global__ __launch_bounds__(64 * (kWaves + 1), 3) void k_conv3(const Params p) 
                     v4i *where = reinterpret_cast<v4i *>(xt + pix * C + ((l ^ swizzle(pix, P)) << 4));
                     v4i piece = *where;
                     asm volatile("" : "+v"(piece));   // (the buffers are only written by copy instructions the compiler does not see as stores)
-                    *where = lower16(piece, sa);
+                    *where = lower16_checked(piece, sa);
                 }
             }
             __builtin_amdgcn_s_waitcnt(0xc07f);

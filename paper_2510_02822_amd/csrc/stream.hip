@@ -220,7 +220,7 @@ __global__ __launch_bounds__(256 * CW, plan(NT, UNITS).per_cu * CW) void k_strea
                 if (idx >= kRows * 2 * n_low) continue;
                 const int l = idx >> 7;
                 const int sa = (int)((sap >> (4 * ((l >> 1) >> p.gs_shift))) & 15u);
-                const v4i b = lower16(piece[k], sa);
+                const v4i b = lower16_checked(piece[k], sa);
                 *where[k] = b;
             }
             __builtin_amdgcn_s_waitcnt(0xc07f);
