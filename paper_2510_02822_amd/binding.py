@@ -426,7 +426,8 @@ def debug_force_conv3(mode: int, rows_per_tile: int = 0) -> int:
 
 
 def debug_force_stream(mode: int) -> int:
-    """Row-streaming kernel: 1 = whenever the layer form qualifies, 0 = never, -1 = automatic; returns whether the last call used it."""
+    """Row-streaming kernels: 1 / 2 = the one whose blocks walk tiles / whose waves walk row groups, whenever the layer form
+    qualifies; 0 = never; -1 = automatic.  Returns which of them the last call ran on (0: neither)."""
     rc = load().flexiq_debug_force_stream(int(mode))
     if rc < 0:
         _check(rc)

@@ -73,7 +73,8 @@ int64_t small_m_workspace_bytes(const flexiq_layer *L);
 int launch_small_m(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int force_splits,
                    int *splits_out);
 // (stream.hip) the row-streaming kernel for layers with a short reduction; *taken = 0: the call does not qualify
-int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, bool rows_contiguous, int *taken);
+int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, bool rows_contiguous, int *taken,
+                  const uint8_t *X4 = nullptr);
 // (conv3.hip) 3x3 convolutions, stride 1, padding 1, with 64 or 128 input channels: weights of all taps resident in LDS,
 // image tiles streamed past them; *taken = 0: the call does not qualify
 int launch_conv3(const flexiq_layer *L, const int8_t *X, int B, int H, int W, int stride, int pad, const flexiq_out *out, void *stream, int *taken);

@@ -217,8 +217,8 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     // row tiles copied several tiles ahead).
     {
         int taken = 0;
-        const bool ok = !xp && (!conv || (stride == 1 && pad == 0)) && g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0;
-        const int rc = launch_stream(L, X, M, out, stream, ok, &taken);
+        const bool ok = (!conv || (stride == 1 && pad == 0)) && g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0;
+        const int rc = launch_stream(L, X, M, out, stream, ok, &taken, xp ? X4 : nullptr);
         if (rc != FLEXIQ_OK) return rc;
         if (taken) {
             g_last_shape = -2;

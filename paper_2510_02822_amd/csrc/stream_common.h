@@ -64,6 +64,29 @@ __device__ __forceinline__ v4i lower16_checked(v4i b, int sa)
     return lower16(b, sa);
 }
 
+// Sixteen bytes of packed 4-bit activation codes (one 32-channel unit of a row; dword e: channels 8e .. 8e+3 in the low
+// halves of its bytes, 8e+4 .. 8e+7 in the high halves) -> the two 16-byte pieces of int8 values code << sa, i.e. the
+// bit-lowered activations put back at their position (Section 4.1).  Per dword and half: each 16-bit half is shifted right
+// arithmetically by 4 - sa with the wanted byte on top (that sign-extends the code), the two results are merged bytewise and
+// the low sa bits cleared.
+__device__ __forceinline__ uint32_t expand4(uint32_t codes_hi, short t, uint32_t mask)
+{
+    v2s o = __builtin_bit_cast(v2s, codes_hi);
+    v2s e = o << (short)8;
+    o = o >> t;
+    e = e >> t;
+    return __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, o), __builtin_bit_cast(uint32_t, e), 0x07030501u) & mask;
+}
+__device__ __forceinline__ void expand_unit(v4i pk, int sa, v4i &first16, v4i &second16)
+{
+    const short t = (short)(4 - sa);
+    const uint32_t mask = 0x01010101u * ((0xFFu << sa) & 0xFFu);
+    first16 = (v4i){(int)expand4((uint32_t)pk.x << 4, t, mask), (int)expand4((uint32_t)pk.x, t, mask),
+                    (int)expand4((uint32_t)pk.y << 4, t, mask), (int)expand4((uint32_t)pk.y, t, mask)};
+    second16 = (v4i){(int)expand4((uint32_t)pk.z << 4, t, mask), (int)expand4((uint32_t)pk.z, t, mask),
+                     (int)expand4((uint32_t)pk.w << 4, t, mask), (int)expand4((uint32_t)pk.w, t, mask)};
+}
+
 // LDS image of activation rows (pixels): row-major, P = 4, 8 or 16 16-byte pieces per row, the pieces of a row permuted so
 // that the fragment reads of sixteen consecutive rows (same logical piece) fall into the sixteen different 16-byte groups
 // of the 64 banks: 16 / P consecutive rows already differ in their position modulo 256 bytes and share a permutation.

@@ -102,6 +102,38 @@ def test_every_tile_shape_and_block_count(env):
         fq.debug_max_blocks(0)
 
 
+@pytest.mark.parametrize("M,K,N,gs", [(1000, 64, 64, 32), (777, 64, 256, 32), (2000, 128, 528, 64), (513, 256, 80, 32),
+                                      (300, 256, 128, 64), (4099, 128, 48, 32), (1, 256, 32, 32), (1500, 256, 272, 32)])
+def test_row_streaming_kernel_reads_packed_codes(env, M, K, N, gs, kernel=2):
+    """Layers with 64, 128 or 256 channels: the row-streaming kernel whose waves walk groups of 32 rows fetches the packed
+    codes (half the bytes) and expands them in registers after the fragment read.  int8 rows (its only output in that build) against the oracle's accumulators requantised, for ratios that
+    leave X pieces and packed pieces in one copy instruction, a trailing 4-bit group of 32 that is lowered from X, all
+    packed, none packed; saturating inputs; rows that do not fill the last tile; several column blocks."""
+    torch, oracle, fq, dev = env
+    case = workloads.make_linear("p4st", 11, 3 * M + K + N, M, K, N, gs, outlier_frac=0.02)
+    case.X *= 2.0   # some values saturate under the calibrated positions
+    ol, hl, x_scale = both_layers(case)
+    Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
+    Xd = _dev(torch, Xq, dev)
+    G = K // gs
+    fq.debug_force_stream(kernel)
+    try:
+        for r in sorted({1.0, (G - 1) / G, 0.5, 1.0 / G, 0.0}):
+            k4 = fq.flexiq_set_ratio(hl, r)
+            k4p = fq.flexiq_packed4_channels(hl)
+            x4 = fq.flexiq_lower_packed4(hl, Xd)
+            Xp = Xq.copy()
+            Xp[:, :k4p] = 77          # the packed columns of X are not read
+            ref = oracle.forward_gemm(ol, Xq, r)
+            so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.7) or 1.0
+            got = fq.flexiq_mixed_gemm_packed4(hl, _dev(torch, Xp, dev), x4, q=True, out_scale=so)["q"].cpu().numpy()
+            assert fq.debug_last_launch()["tile"] == -2 and fq.debug_force_stream(kernel) == kernel, (r, k4, k4p)   # ran on that kernel
+            check_q(got, ref, ol, so)
+            assert (got == requant_fp32_sequence(ref, ol, so)).all(), (r, k4, k4p)
+    finally:
+        fq.debug_force_stream(-1)
+
+
 def test_run_time_positions_and_saturating_inputs(env):
     torch, oracle, fq, dev = env
     M, K, N, gs = 500, 256, 48, 32

@@ -26,7 +26,8 @@ def _dev(torch, a, dev):
 
 @pytest.mark.parametrize("M,K,N,gs", [(1000, 64, 64, 32), (777, 64, 256, 32), (129, 128, 16, 32), (2000, 128, 520, 64),
                                       (513, 256, 72, 32), (300, 256, 128, 64), (1, 256, 40, 32), (4099, 64, 300, 32)])
-def test_linear_forced(env, M, K, N, gs):
+@pytest.mark.parametrize("kernel", [1, 2])   # 1: blocks walk tiles of 128 rows together; 2: every wave walks groups of 32 rows on its own
+def test_linear_forced(env, M, K, N, gs, kernel):
     torch, oracle, fq, dev = env
     case = workloads.make_linear("st", 12, M + K + N, M, K, N, gs, outlier_frac=0.02)
     case.X *= 2.0   # some rows saturate under the calibrated positions
@@ -34,7 +35,7 @@ def test_linear_forced(env, M, K, N, gs):
     Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
     Xd = _dev(torch, Xq, dev)
     G = K // gs
-    fq.debug_force_stream(1)
+    fq.debug_force_stream(kernel)
     try:
         for r in (0.0, 1.0 / G, 0.5, 1.0):
             fq.flexiq_set_ratio(hl, r)
@@ -42,7 +43,7 @@ def test_linear_forced(env, M, K, N, gs):
             so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
             out = fq.flexiq_mixed_gemm(hl, Xd, acc=True, y=True, q=True, out_scale=so)
             torch.cuda.synchronize()
-            assert fq.debug_force_stream(1) == 1          # the call ran on the streaming kernel
+            assert fq.debug_force_stream(kernel) == kernel          # the call ran on that kernel
             assert fq.debug_last_launch()["tile"] == -2
             assert (out["acc"].cpu().numpy() == ref).all(), r
             check_y(out["y"].cpu().numpy(), ref, ol)
@@ -55,7 +56,7 @@ def test_linear_forced(env, M, K, N, gs):
             fq.debug_force_stream(0)
             tiled = fq.flexiq_mixed_gemm(hl, Xd, q=True, out_scale=so)["q"]
             assert fq.debug_last_launch()["tile"] >= 0
-            fq.debug_force_stream(1)
+            fq.debug_force_stream(kernel)
             assert (tiled.cpu().numpy() == got_q).all(), r
     finally:
         fq.debug_force_stream(-1)
@@ -118,19 +119,21 @@ def test_conv_1x1_and_automatic_route(env):
     case = workloads.make_linear("stauto", 12, 9, 4096, K, N, 32, outlier_frac=0.02)
     ol, hl, x_scale = both_layers(case)
     Xbig = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
-    fq.flexiq_set_ratio(hl, 0.5)
-    got = fq.flexiq_mixed_gemm(hl, _dev(torch, Xbig, dev), acc=True)["acc"].cpu().numpy()
-    assert fq.debug_force_stream(-1) == 1
     rows = np.r_[0:300, M - 300:M]
-    assert (got[rows] == oracle.forward_gemm(ol, Xbig[rows], 0.5)).all()
+    for r, kernel in ((0.0, 1), (0.5, 2)):   # nothing to lower: blocks walk tiles; else (64 x 64): every wave on its own
+        fq.flexiq_set_ratio(hl, r)
+        got = fq.flexiq_mixed_gemm(hl, _dev(torch, Xbig, dev), acc=True)["acc"].cpu().numpy()
+        assert fq.debug_force_stream(-1) == kernel
+        assert (got[rows] == oracle.forward_gemm(ol, Xbig[rows], r)).all()
     fq.flexiq_mixed_gemm(hl, _dev(torch, Xbig[:5000], dev), acc=True)
     assert fq.debug_force_stream(-1) == 0
 
 
 @pytest.mark.parametrize("K,N", [(64, 256), (64, 64), (128, 128), (256, 64)])
-def test_blocks_walk_many_tiles(env, K, N):
-    """More row tiles than resident blocks: every block goes round its ring of tile slots several times (each wave-count
-    and ring-depth configuration of the kernel), int32 and int8 outputs together."""
+@pytest.mark.parametrize("kernel", [1, 2])
+def test_blocks_walk_many_tiles(env, K, N, kernel):
+    """More row tiles than resident blocks: every block (or wave, second kernel) goes round its ring of slots several times (each wave-count
+    and ring-depth configuration of the kernels), int32 and int8 outputs together."""
     torch, oracle, fq, dev = env
     M = 150001
     case = workloads.make_linear("stwalk", 12, K + N, 2048, K, N, 32, outlier_frac=0.02)
@@ -139,7 +142,7 @@ def test_blocks_walk_many_tiles(env, K, N):
     Xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
     Xd = _dev(torch, Xq, dev)
     rows = np.r_[0:200, 70000:70300, M - 400:M]
-    fq.debug_force_stream(1)
+    fq.debug_force_stream(kernel)
     try:
         for r in (1.0, 0.5, 0.0):
             fq.flexiq_set_ratio(hl, r)
@@ -147,13 +150,13 @@ def test_blocks_walk_many_tiles(env, K, N):
             so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
             out = fq.flexiq_mixed_gemm(hl, Xd, acc=True, q=True, out_scale=so)
             torch.cuda.synchronize()
-            assert fq.debug_force_stream(1) == 1
+            assert fq.debug_force_stream(kernel) == kernel
             assert (out["acc"].cpu().numpy()[rows] == ref).all(), r
             assert (out["q"].cpu().numpy()[rows] == requant_fp32_sequence(ref, ol, so)).all(), r
             # the whole int8 output against the tiled kernel's
             fq.debug_force_stream(0)
             tiled = fq.flexiq_mixed_gemm(hl, Xd, q=True, out_scale=so)["q"]
-            fq.debug_force_stream(1)
+            fq.debug_force_stream(kernel)
             only_q = fq.flexiq_mixed_gemm(hl, Xd, q=True, out_scale=so)["q"]
             assert bool((tiled == only_q).all()) and bool((only_q == out["q"]).all()), r
     finally:
