@@ -346,7 +346,8 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
     return out
 
 
-PROFILE_TARGETS = ("vitl_fc2", "vitl_fc2_fp6", "vitl_fc2_rows16", "reorder", "resnet_1x1_64_256", "resnet_3x3_64_64")
+PROFILE_TARGETS = ("vitl_fc2", "vitl_fc2_fp6", "vitl_fc2_rows16", "reorder", "resnet_1x1_64_256", "resnet_3x3_64_64",
+                   "resnet_1x1_256_64", "resnet_1x1_256_64_packed4")
 
 
 def profile_only(torch, fq, workloads, dev, what, launches):
@@ -354,7 +355,7 @@ def profile_only(torch, fq, workloads, dev, what, launches):
     the order r = 0, 0.5, 1 (the kernel trace lists dispatches in launch order), one copy of `--calib-copy-mib` after."""
     res = {"profile_only": what, "launches_per_ratio": launches, "ratios": [0.0, 0.5, 1.0]}
     if what.startswith("resnet_"):
-        idx = {"resnet_1x1_64_256": 2, "resnet_3x3_64_64": 1}[what]
+        idx = {"resnet_1x1_64_256": 2, "resnet_3x3_64_64": 1, "resnet_1x1_256_64": 3, "resnet_1x1_256_64_packed4": 3}[what]
         case = workloads.config4_layer(idx, B=128)
         x_scale, amax = _calib(case)
         layer = fq.flexiq_quantize_pack(case.W, amax, x_scale, case.group_size, bias=case.bias)
@@ -362,6 +363,9 @@ def profile_only(torch, fq, workloads, dev, what, launches):
         q = {"q": torch.empty((case.B, case.Ho, case.Wo, case.N), dtype=torch.int8, device=dev)}
         res["workload"] = "%s batch 128: M=%d K=%d N=%d" % (case.name, case.B * case.Ho * case.Wo, case.R * case.S * case.C, case.N)
         call = lambda: fq.flexiq_mixed_conv_implicit(layer, Xq, case.stride, case.pad, q=True, out_scale=0.05, bufs=q)
+        if what.endswith("_packed4"):   # the same pixels as rows of a linear layer (packed activations are defined for those)
+            Xq = Xq.reshape(-1, case.C)
+            q = {"q": q["q"].reshape(-1, case.N)}
     else:
         case = workloads.config3("fc2")
         x_scale, amax = _calib(case)
@@ -386,6 +390,9 @@ def profile_only(torch, fq, workloads, dev, what, launches):
         if what == "vitl_fc2_fp6":
             x6, xlow = fq.flexiq_lower_fp6(layer, Xq)
             call = lambda: fq.flexiq_mixed_gemm_fp6(layer, xlow, x6, q=True, out_scale=0.05, bufs=q)
+        if what.endswith("_packed4"):
+            x4 = fq.flexiq_lower_packed4(layer, Xq)
+            call = lambda: fq.flexiq_mixed_gemm_packed4(layer, Xq, x4, q=True, out_scale=0.05, bufs=q)
         for _ in range(launches):
             call()
         torch.cuda.synchronize()
