@@ -16,9 +16,9 @@
  * Parity pins (see tests/test_oracle_*.py): every function below is pinned to
  * something other than itself (the paper's worked examples of Section 4.1,
  * closed forms, exhaustive enumeration, numpy int64 matmul at r=0, brute force
- * with Python integers, permutation invariance).  The only unpinned item is
- * the round-half-up variant of fq_o_bitlower (mode 1): the paper prints no
- * value for it -- "parity unpinned" beyond self-consistency.
+ * with Python integers, permutation invariance).  The round-half-up variant
+ * of fq_o_bitlower (mode 1) has no printed value in the paper; it is pinned to
+ * floor(x + 1/2) in exact rational arithmetic, exhaustively.
  */
 #include <math.h>
 #include <stdint.h>
@@ -115,7 +115,7 @@ static int32_t floor_div_pow2(int32_t q, int32_t s)
  * (Section 4.1: "shifting and storing low four bits").  Values outside the
  * range the position was chosen for saturate to [-8, 7] (Appendix, saturated
  * channels).  mode 0: truncation (floor), the definition used everywhere;
- * mode 1: round-half-up variant (parity unpinned).                          */
+ * mode 1: round-half-up variant (nearest integer of q / 2^s, ties upwards).  */
 int32_t fq_o_bitlower(int32_t q, int32_t s, int32_t mode)
 {
     int32_t t;

@@ -122,13 +122,27 @@ def test_bitlower_pack_layout(oracle):
         assert val == max(-8, min(7, int(src[r, c]) >> int(sh_r[r, c // 32])))
 
 
-def test_round_variant_self_consistency(oracle):
-    # mode 1 (round half up) has no printed value in the paper: parity unpinned; only check that it
-    # is the floor of (q + half) and coincides with truncation at position 0
-    for q in range(-128, 128):
-        assert oracle.bitlower(q, 0, 1) == oracle.bitlower(q, 0, 0)
-        for s in range(1, 5):
-            assert oracle.bitlower(q, s, 1) == max(-8, min(7, (q + 2 ** (s - 1)) >> s))
+def test_round_half_up_variant_against_exact_rationals(oracle):
+    """mode 1 rounds q / 2^s to the nearest integer, ties upwards, then saturates.  The paper prints no value for it, so it
+    is pinned to the textbook definition floor(x + 1/2) evaluated in exact rational arithmetic (fractions.Fraction: no
+    shifts, no integer division), exhaustively, and to what follows from that definition: ties go up, it never differs
+    from truncation by more than one, and it is monotone in q."""
+    from fractions import Fraction
+    import math
+    for s in range(0, 5):
+        prev = -9
+        for q in range(-128, 128):
+            got = oracle.bitlower(q, s, 1)
+            x = Fraction(q, 2 ** s)
+            want = max(-8, min(7, math.floor(x + Fraction(1, 2))))
+            assert got == want, (q, s)
+            assert 0 <= got - oracle.bitlower(q, s, 0) <= 1      # truncation is the floor: rounding adds 0 or 1
+            assert got >= prev
+            prev = got
+        if s > 0:   # a tie: q = k * 2^s + 2^(s-1) rounds to k + 1 (inside the range)
+            for k in range(-8, 7):
+                assert oracle.bitlower(k * 2 ** s + 2 ** (s - 1), s, 1) == k + 1
+                assert oracle.bitlower(k * 2 ** s + 2 ** (s - 1) - 1, s, 1) == k
 
 
 def test_dynamic_act_shifts_match_range_definition(oracle):
