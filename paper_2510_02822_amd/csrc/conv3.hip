@@ -42,6 +42,9 @@ struct Params {
     int32_t npix;           // LDS pixels per tile: (TR + 2) * (W + 2)
     int32_t copies;         // 1 KB copy instructions per tile
     int32_t nbuf;           // tile buffers (2 to 4)
+    // LOWER builds: the layer that reads the int8 output (its positions, 4-bit prefix and log2 of its group size)
+    const int32_t *next_ashift;
+    int32_t next_K4, next_gs_log2;
 };
 
 constexpr int kCols = 64;           // output columns per block
@@ -117,7 +120,7 @@ __device__ __forceinline__ void wait_outstanding(int n)
 #undef FQ_W
 }
 
-template <int UNITS, bool QONLY>
+template <int UNITS, bool QONLY, bool LOWER = false>
 __global__ __launch_bounds__(64 * (kWaves + 1), 3) void k_conv3(const Params p)   // (nine waves: three on one SIMD)
 {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -129,8 +132,8 @@ __global__ __launch_bounds__(64 * (kWaves + 1), 3) void k_conv3(const Params p) 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int fr = lane & 31, fh = lane >> 5;
     const int n_blk = blockIdx.y * kCols;
-    float *const tab = reinterpret_cast<float *>(lds + wbytes);   // [64] multipliers, [64] addends
-    unsigned char *const bufs = lds + wbytes + 2 * kCols * 4;
+    float *const tab = reinterpret_cast<float *>(lds + wbytes);   // [64] multipliers, [64] addends, then the consumer's lowering table
+    unsigned char *const bufs = lds + wbytes + 3 * kCols * 4;
     const int tile_bytes = p.copies * 1024;
     const int Wp = p.W + 2;
 
@@ -220,6 +223,7 @@ __global__ __launch_bounds__(64 * (kWaves + 1), 3) void k_conv3(const Params p) 
         tab[tid] = pre_scaled ? cs * p.r_out : cs;
         tab[kCols + tid] = pre_scaled ? bi * p.r_out + 128.0f : bi;
     }
+    if constexpr (LOWER) fill_lower_table(lds + wbytes + 2 * kCols * 4, kCols / 4, n_blk, p.next_ashift, p.next_K4, p.next_gs_log2, tid, 64 * (kWaves + 1));
     __builtin_amdgcn_s_waitcnt(0x0070);   // weights and tables
     block_barrier();
 
@@ -285,18 +289,18 @@ __global__ __launch_bounds__(64 * (kWaves + 1), 3) void k_conv3(const Params p) 
             for (int r = 0; r < 2; ++r) {
                 const int tp = tp0 + 32 * kWaves * r;
                 const bool row_ok = tp < rows_ok * p.W;
-                store_fragment<QONLY, kCols>(acc[2 * r], fo, lds + wbytes, 0, n_blk, m0 + tp, row_ok, lim, fh, pre_scaled, q_rows);
+                store_fragment<QONLY, kCols, LOWER>(acc[2 * r], fo, lds + wbytes, 0, n_blk, m0 + tp, row_ok, lim, fh, pre_scaled, q_rows);
                 __builtin_amdgcn_sched_barrier(0);   // (one fragment at a time: interleaved, their temporaries spill)
-                store_fragment<QONLY, kCols>(acc[2 * r + 1], fo, lds + wbytes, 1, n_blk, m0 + tp, row_ok, lim, fh, pre_scaled, q_rows);
+                store_fragment<QONLY, kCols, LOWER>(acc[2 * r + 1], fo, lds + wbytes, 1, n_blk, m0 + tp, row_ok, lim, fh, pre_scaled, q_rows);
                 __builtin_amdgcn_sched_barrier(0);   // (one fragment at a time: interleaved, their temporaries spill)
             }
         } else {
             v16i acc[2];
             tile_mma<UNITS, 1>(xt, wbase, &base[0][0], acc);
             const bool row_ok = tp0 < rows_ok * p.W;
-            store_fragment<QONLY, kCols>(acc[0], fo, lds + wbytes, 0, n_blk, m0 + tp0, row_ok, lim, fh, pre_scaled, q_rows);
+            store_fragment<QONLY, kCols, LOWER>(acc[0], fo, lds + wbytes, 0, n_blk, m0 + tp0, row_ok, lim, fh, pre_scaled, q_rows);
             __builtin_amdgcn_sched_barrier(0);   // (one fragment at a time: interleaved, their temporaries spill)
-            store_fragment<QONLY, kCols>(acc[1], fo, lds + wbytes, 1, n_blk, m0 + tp0, row_ok, lim, fh, pre_scaled, q_rows);
+            store_fragment<QONLY, kCols, LOWER>(acc[1], fo, lds + wbytes, 1, n_blk, m0 + tp0, row_ok, lim, fh, pre_scaled, q_rows);
             __builtin_amdgcn_sched_barrier(0);   // (one fragment at a time: interleaved, their temporaries spill)
         }
         b_cur = b_cur + 1 == p.nbuf ? 0 : b_cur + 1;
@@ -323,29 +327,33 @@ int prepare_conv3_kernels(int device)
     FLEXIQ_HIP(hipGetDeviceProperties(&prop, device));
     g_dev[device].num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     const void *fns[] = {(const void *)k_conv3<2, false>, (const void *)k_conv3<2, true>, (const void *)k_conv3<4, false>,
-                         (const void *)k_conv3<4, true>};
+                         (const void *)k_conv3<4, true>, (const void *)k_conv3<2, true, true>, (const void *)k_conv3<4, true, true>};
     for (const void *fn : fns) FLEXIQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     g_dev[device].ready = true;
     return FLEXIQ_OK;
 }
 
 // Launches the 3x3 kernel when the call qualifies; *taken says whether it did (0: nothing was launched).  Qualifying: a 3x3
-// filter, stride 1, padding 1, 64 or 128 input channels, plain outputs (no consumer to lower or scan for), an image whose
+// filter, stride 1, padding 1, 64 or 128 input channels, plain outputs or int8 output lowered for a consumer (`lower`:
+// flexiq_out.lower_for, checked by the caller; no consumer to scan for), an image whose
 // tile of at least one output row fits a 40 KB buffer, and enough tiles to occupy the chip.
 int launch_conv3(const flexiq_layer *L, const int8_t *X, int B, int H, int W, int stride, int pad, const flexiq_out *out, void *stream_,
-                 int *taken)
+                 int *taken, const LowerArgs *lower)
 {
     using namespace conv3;
     *taken = 0;
     g_last = 0;
     if (g_force == 0) return FLEXIQ_OK;
     if (L->R != 3 || L->S != 3 || stride != 1 || pad != 1 || (L->C != 64 && L->C != 128)) return FLEXIQ_OK;
-    if (out->lower_for || out->scan_for || out->x4 || out->x6) return FLEXIQ_OK;
+    if (out->scan_for || out->x4 || out->x6) return FLEXIQ_OK;
+    const bool q_only = out->q && !out->acc && !out->y && (L->N & 15) == 0;
+    const bool lowering = out->lower_for != nullptr;
+    if (lowering && !(lower && lower->ashift && q_only)) return FLEXIQ_OK;   // (the lowering build writes int8 only)
     const DeviceState &ds = g_dev[L->device];
     if (!ds.ready) return FLEXIQ_OK;
     if ((int64_t)H * W * L->C >= (1 << 29) || W > 1024) return FLEXIQ_OK;
     const int units = L->C / kUnit;
-    const int wbytes = 9 * units * 2 * (kCols + 2) * 16 + 2 * kCols * 4;
+    const int wbytes = 9 * units * 2 * (kCols + 2) * 16 + 3 * kCols * 4;
     const int gy = (L->N + kCols - 1) / kCols;
     // output rows per tile: every choice whose buffer fits 40 KB, whose pixels fit sixteen fragments and of which two
     // buffers fit next to the weights; the one with the least estimated time of the busiest compute unit (matrix
@@ -392,8 +400,9 @@ int launch_conv3(const flexiq_layer *L, const int8_t *X, int B, int H, int W, in
     const size_t lds = (size_t)wbytes + (size_t)p.nbuf * p.copies * 1024;
     int64_t gx64 = std::max<int64_t>(1, std::min<int64_t>(tiles, ds.num_cu / gy));
     if (gy > 1 && gx64 >= 8) gx64 &= ~(int64_t)7;   // the column blocks of a tile share an XCD and its L2
-    const bool q_only = out->q && !out->acc && !out->y && (L->N & 15) == 0;
+    if (lowering) { p.next_ashift = lower->ashift; p.next_K4 = lower->K4; p.next_gs_log2 = lower->gs_log2; }
     void (*fn)(const Params) = units == 2 ? (q_only ? k_conv3<2, true> : k_conv3<2, false>) : (q_only ? k_conv3<4, true> : k_conv3<4, false>);
+    if (lowering) fn = units == 2 ? k_conv3<2, true, true> : k_conv3<4, true, true>;
     hipLaunchKernelGGL(fn, dim3((unsigned)gx64, (unsigned)gy), dim3(64 * (kWaves + 1)), lds, (hipStream_t)stream_, p);
     FLEXIQ_HIP(hipGetLastError());
     *taken = 1;

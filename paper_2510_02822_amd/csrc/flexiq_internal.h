@@ -72,12 +72,20 @@ int fp6_channels(const flexiq_layer *L);
 int64_t small_m_workspace_bytes(const flexiq_layer *L);
 int launch_small_m(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int force_splits,
                    int *splits_out);
-// (stream.hip) the row-streaming kernel for layers with a short reduction; *taken = 0: the call does not qualify
+// The consumer named by flexiq_out.lower_for, checked (gemm.hip): its positions, 4-bit prefix and log2 of its group size;
+// ashift == nullptr: the call names none.
+struct LowerArgs {
+    const int32_t *ashift = nullptr;
+    int32_t K4 = 0, gs_log2 = 5;
+};
+int lower_for_args(const flexiq_layer *L, const flexiq_out *out, LowerArgs *la);
+// (stream.hip) the row-streaming kernels for layers with a short reduction; *taken = 0: the call does not qualify
 int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, bool rows_contiguous, int *taken,
-                  const uint8_t *X4 = nullptr);
+                  const uint8_t *X4 = nullptr, const LowerArgs *lower = nullptr);
 // (conv3.hip) 3x3 convolutions, stride 1, padding 1, with 64 or 128 input channels: weights of all taps resident in LDS,
 // image tiles streamed past them; *taken = 0: the call does not qualify
-int launch_conv3(const flexiq_layer *L, const int8_t *X, int B, int H, int W, int stride, int pad, const flexiq_out *out, void *stream, int *taken);
+int launch_conv3(const flexiq_layer *L, const int8_t *X, int B, int H, int W, int stride, int pad, const flexiq_out *out, void *stream, int *taken,
+                 const LowerArgs *lower = nullptr);
 }  // namespace flexiq
 
 // Device layouts (all offsets in bytes unless noted), T = R*S filter taps, CUp = C/32 rounded up to

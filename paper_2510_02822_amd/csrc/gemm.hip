@@ -133,6 +133,21 @@ static bool orders_match(const flexiq_layer *producer, const flexiq_layer *consu
     return producer->out_order_hash == consumer->perm_hash;
 }
 
+// flexiq_out.lower_for as the kernels take it (the same checks whichever kernel serves the call).
+int lower_for_args(const flexiq_layer *L, const flexiq_out *out, LowerArgs *la)
+{
+    *la = LowerArgs();
+    const flexiq_layer *nx = out->lower_for;
+    if (!nx) return FLEXIQ_OK;
+    if (out->scan_for) return FLEXIQ_EINVAL;   // lowering needs positions the scan has yet to find
+    if (!out->q || nx->C != L->N || nx->device != L->device) return FLEXIQ_EINVAL;
+    if (nx->G > kMaxGroups || !orders_match(L, nx)) return FLEXIQ_EINVAL;
+    la->ashift = nx->dynamic ? nx->d_ashift_dyn : nx->d_ashift;
+    la->K4 = nx->max_4bit_ch;
+    la->gs_log2 = nx->group_size == 64 ? 6 : 5;
+    return FLEXIQ_OK;
+}
+
 static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, bool conv,
                   int H, int Wd, int Ho, int Wo, int stride, int pad, const uint8_t *X4 = nullptr)
 {
@@ -218,7 +233,9 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     {
         int taken = 0;
         const bool ok = (!conv || (stride == 1 && pad == 0)) && g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0;
-        const int rc = launch_stream(L, X, M, out, stream, ok, &taken, xp ? X4 : nullptr);
+        LowerArgs la;
+        la.ashift = p.next_ashift; la.K4 = p.next_K4; la.gs_log2 = p.next_gs_log2;   // (checked above)
+        const int rc = launch_stream(L, X, M, out, stream, ok, &taken, xp ? X4 : nullptr, out->lower_for ? &la : nullptr);
         if (rc != FLEXIQ_OK) return rc;
         if (taken) {
             g_last_shape = -2;
@@ -377,7 +394,15 @@ extern "C" int flexiq_mixed_conv_implicit(const flexiq_layer *L, const int8_t *X
     {   // 3x3, stride 1, padding 1, 64 or 128 channels: the kernel that keeps all taps' weights resident (conv3.hip)
         int taken = 0;
         if (g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0) {
-            rc = launch_conv3(L, X, B, H, W, stride, pad, out, stream, &taken);
+            LowerArgs la;
+            rc = lower_for_args(L, out, &la);
+            if (rc != FLEXIQ_OK) return rc;
+            {   // (as in launch(): the handle's buffers live on the device it was packed on)
+                int dev = -1;
+                FLEXIQ_HIP(hipGetDevice(&dev));
+                if (dev != L->device) return FLEXIQ_EINVAL;
+            }
+            rc = launch_conv3(L, X, B, H, W, stride, pad, out, stream, &taken, la.ashift ? &la : nullptr);
             if (rc != FLEXIQ_OK) return rc;
         }
         if (taken) {

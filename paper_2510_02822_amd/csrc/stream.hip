@@ -45,6 +45,9 @@ struct Params {
     int32_t tiles;          // row tiles of 128
     int32_t slots;          // stages of the activation ring
     int32_t groups;         // k_rows: groups of 32 rows
+    // LOWER builds: the layer that reads the int8 rows (its positions, 4-bit prefix and log2 of its group size)
+    const int32_t *next_ashift;
+    int32_t next_K4, next_gs_log2;
 };
 
 constexpr int kRows = 128;        // rows per tile: four waves x 32
@@ -90,7 +93,7 @@ constexpr Plan plan(int nt, int units)
     Plan best = {0, 0};
     int score = -1;
     for (int b = nt == 8 ? 2 : 4; b >= 1; --b) {
-        int s = ((160 * 1024) / b - wbytes - 2 * bn * 4 - 128) / slot;
+        int s = ((160 * 1024) / b - wbytes - 3 * bn * 4 - 128) / slot;
         if (s > 4) s = 4;
         if (s >= 2 && b * (s - 1) > score) {
             score = b * (s - 1);
@@ -104,7 +107,7 @@ constexpr Plan plan(int nt, int units)
 // share a group of 32 rows and split the block's columns between them (1: four waves, 2: eight waves per block, two per SIMD);
 // QONLY: the call writes int8 rows and nothing else (the usual case between layers): a build without the other outputs'
 // address arithmetic, whose registers would otherwise spill, and a reload from scratch waits for every copy in flight
-template <int NT, int UNITS, int CW, bool QONLY>
+template <int NT, int UNITS, int CW, bool QONLY, bool LOWER = false>
 __global__ __launch_bounds__(256 * CW, plan(NT, UNITS).per_cu * CW) void k_stream(const Params p)   // (second figure: waves per SIMD)
 {
     static_assert(CW == (plan(NT, UNITS).per_cu <= 2 ? 2 : 1), "eight waves where at most two blocks share a compute unit");
@@ -120,7 +123,7 @@ __global__ __launch_bounds__(256 * CW, plan(NT, UNITS).per_cu * CW) void k_strea
     constexpr int NS = BN + 2;                     // rows per weight k-plane in LDS (+2: the two planes of a fragment read hit different banks)
     constexpr int wbytes = UNITS * 2 * NS * 16;
     float *const tab = reinterpret_cast<float *>(lds + wbytes);          // [BN] multipliers, [BN] addends
-    unsigned char *const ring = lds + wbytes + 2 * BN * 4 + 128;   // (the ring starts on a 128-byte boundary of its own)
+    unsigned char *const ring = lds + wbytes + 3 * BN * 4 + 128;   // (two float tables and the consumer's lowering table; the ring starts on a 128-byte boundary of its own)
     constexpr int slot_bytes = kRows * C;
 
     // ---- scales and biases (pre-multiplied for the int8 output when it is the only scaled one), positions
@@ -131,6 +134,7 @@ __global__ __launch_bounds__(256 * CW, plan(NT, UNITS).per_cu * CW) void k_strea
         tab[c] = pre_scaled ? cs * p.r_out : cs;
         tab[BN + c] = pre_scaled ? bi * p.r_out + 128.0f : bi;
     }
+    if constexpr (LOWER) fill_lower_table(lds + wbytes + 2 * BN * 4, BN / 4, n_blk, p.next_ashift, p.next_K4, p.next_gs_log2, tid, 64 * NW);
     // positions of up to 8 groups (C <= 256), four bits each, in one scalar
     const int n_low = p.x_pre ? 0 : p.units4;
     uint32_t sa_packed = 0;
@@ -269,7 +273,7 @@ __global__ __launch_bounds__(256 * CW, plan(NT, UNITS).per_cu * CW) void k_strea
                 const v4i w = *reinterpret_cast<const v4i *>(lds + ((2 * u + fh) * NS + 32 * ca + fr) * 16);
                 acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w, bfrag[u], acc, 0, 0, 0);
             }
-            store_fragment<QONLY, BN>(acc, fo, lds + wbytes, ca, n_blk, m, row_ok, lim, fh, pre_scaled, q_rows);
+            store_fragment<QONLY, BN, LOWER>(acc, fo, lds + wbytes, ca, n_blk, m, row_ok, lim, fh, pre_scaled, q_rows);
         }
         slot = slot + 1 == p.slots ? 0 : slot + 1;
     }
@@ -295,7 +299,7 @@ constexpr RowPlan row_plan(int nt, int units)
     const int tries[4][2] = {{2, 8}, {1, 8}, {1, 6}, {1, 4}};
     for (int i = 0; i < 4; ++i) {
         const int b = tries[i][0], w = tries[i][1];
-        int sl = ((160 * 1024) / b - wbytes - 2 * bn * 4 - 128) / (w * sub);
+        int sl = ((160 * 1024) / b - wbytes - 3 * bn * 4 - 128) / (w * sub);
         if (sl > 4) sl = 4;
         if (sl >= 2) return {b, sl, w};
     }
@@ -369,7 +373,7 @@ __device__ __forceinline__ void issue_group(const Params &p, unsigned char *dst,
     }
 }
 
-template <int NT, int UNITS, bool QONLY, bool XP>
+template <int NT, int UNITS, bool QONLY, bool XP, bool LOWER = false>
 __global__ __launch_bounds__(64 * row_plan(NT, UNITS).waves, (row_plan(NT, UNITS).waves * row_plan(NT, UNITS).per_cu + 3) / 4) void k_rows(const Params p)
 {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -385,7 +389,7 @@ __global__ __launch_bounds__(64 * row_plan(NT, UNITS).waves, (row_plan(NT, UNITS
     constexpr int wbytes = UNITS * 2 * NS * 16;
     float *const tab = reinterpret_cast<float *>(lds + wbytes);
     constexpr int sub = kGroup * C;   // bytes of a group of rows
-    unsigned char *const ring = lds + wbytes + 2 * BN * 4 + 128 + wave * p.slots * sub;
+    unsigned char *const ring = lds + wbytes + 3 * BN * 4 + 128 + wave * p.slots * sub;
 
     const bool pre_scaled = QONLY || (p.q != nullptr && p.y == nullptr);
     for (int c = tid; c < BN; c += 64 * NW) {
@@ -394,6 +398,7 @@ __global__ __launch_bounds__(64 * row_plan(NT, UNITS).waves, (row_plan(NT, UNITS
         tab[c] = pre_scaled ? cs * p.r_out : cs;
         tab[BN + c] = pre_scaled ? bi * p.r_out + 128.0f : bi;
     }
+    if constexpr (LOWER) fill_lower_table(lds + wbytes + 2 * BN * 4, BN / 4, n_blk, p.next_ashift, p.next_K4, p.next_gs_log2, tid, 64 * NW);
     const int n_low = p.x_pre ? 0 : p.units4;
     uint32_t sa_packed = 0;
     for (int g = 0; g < (n_low > 0 ? ((n_low - 1) >> p.gs_shift) + 1 : 0); ++g) sa_packed |= (uint32_t)p.ashift[g] << (4 * g);
@@ -506,7 +511,7 @@ __global__ __launch_bounds__(64 * row_plan(NT, UNITS).waves, (row_plan(NT, UNITS
                 const v4i w = *reinterpret_cast<const v4i *>(lds + ((2 * u + fh) * NS + 32 * a + fr) * 16);
                 acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w, bfrag[u], acc, 0, 0, 0);
             }
-            store_fragment<QONLY, BN>(acc, fo, lds + wbytes, a, n_blk, m, row_ok, lim, fh, pre_scaled, q_rows);
+            store_fragment<QONLY, BN, LOWER>(acc, fo, lds + wbytes, a, n_blk, m, row_ok, lim, fh, pre_scaled, q_rows);
         }
         slot = slot + 1 == p.slots ? 0 : slot + 1;
     }
@@ -531,11 +536,12 @@ int prepare_stream_kernels(int device)
     hipDeviceProp_t prop;
     FLEXIQ_HIP(hipGetDeviceProperties(&prop, device));
     g_dev[device].num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-#define FQ_BOTH(NT_, U_, CW_) (const void *)k_stream<NT_, U_, CW_, false>, (const void *)k_stream<NT_, U_, CW_, true>
+#define FQ_BOTH(NT_, U_, CW_) (const void *)k_stream<NT_, U_, CW_, false>, (const void *)k_stream<NT_, U_, CW_, true>, (const void *)k_stream<NT_, U_, CW_, true, true>
     const void *fns[] = {FQ_BOTH(2, 2, 1), FQ_BOTH(4, 2, 1), FQ_BOTH(8, 2, 2), FQ_BOTH(2, 4, 2), FQ_BOTH(4, 4, 2), FQ_BOTH(8, 4, 2),
                          FQ_BOTH(2, 8, 2), FQ_BOTH(4, 8, 2), FQ_BOTH(8, 8, 2)};
 #undef FQ_BOTH
-#define FQ_R(NT_, U_) (const void *)k_rows<NT_, U_, false, false>, (const void *)k_rows<NT_, U_, true, false>, (const void *)k_rows<NT_, U_, true, true>
+#define FQ_R(NT_, U_) (const void *)k_rows<NT_, U_, false, false>, (const void *)k_rows<NT_, U_, true, false>, (const void *)k_rows<NT_, U_, true, true>, \
+                      (const void *)k_rows<NT_, U_, true, false, true>
     const void *fns_rows[] = {FQ_R(2, 2), FQ_R(4, 2), FQ_R(8, 2), FQ_R(2, 4), FQ_R(4, 4), FQ_R(8, 4), FQ_R(2, 8), FQ_R(4, 8), FQ_R(8, 8)};
 #undef FQ_R
     for (const void *fn : fns_rows) FLEXIQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
@@ -546,18 +552,19 @@ int prepare_stream_kernels(int device)
 
 // Launches the row-streaming kernel when the call qualifies; *taken says whether it did (0: nothing was launched).
 // Qualifying: rows are contiguous [M][C] (linear layers; 1x1 convolutions with stride 1 and no padding), C is 64, 128
-// or 256, plain outputs (no consumer to lower or scan for), and enough rows to give every compute unit several tiles.
+// or 256, plain outputs or int8 rows lowered for a consumer (`lower`: flexiq_out.lower_for, checked by the caller; no
+// consumer to scan for), and enough rows to give every compute unit several tiles.
 // X4 (optional): the packed 4-bit codes of the layer's leading (max_4bit_ch / 64) * 64 channels; taken only when int8 rows
 // are the call's only output (the caller has checked alignment and that M * C / 2 fits 31 bits).
 int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream_, bool rows_contiguous, int *taken,
-                  const uint8_t *X4)
+                  const uint8_t *X4, const LowerArgs *lower)
 {
     using namespace stream;
     *taken = 0;
     g_last = 0;
     if (g_force == 0 || !rows_contiguous) return FLEXIQ_OK;
     if (L->R != 1 || L->S != 1 || (L->C != 64 && L->C != 128 && L->C != 256)) return FLEXIQ_OK;
-    if (out->lower_for || out->scan_for || out->x4 || out->x6) return FLEXIQ_OK;
+    if (out->scan_for || out->x4 || out->x6) return FLEXIQ_OK;
     const DeviceState &ds = g_dev[L->device];
     if (!ds.ready) return FLEXIQ_OK;
     const int64_t tiles = (M + kRows - 1) / kRows;
@@ -565,6 +572,9 @@ int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     const bool q_only = out->q && !out->acc && !out->y && (L->N & 15) == 0;
     const int units_p = X4 && !L->x_prelowered ? (L->max_4bit_ch / 64) * 2 : 0;
     if (units_p > 0 && !q_only) return FLEXIQ_OK;   // (the packed-input builds write int8 rows only)
+    // a consumer to lower for: the builds that write int8 rows only, from int8 input
+    const bool lowering = out->lower_for != nullptr;
+    if (lowering && !(lower && lower->ashift && q_only && units_p == 0)) return FLEXIQ_OK;
     // k_rows (every wave on its own) instead of k_stream where it measures faster: whenever packed codes come in (k_stream
     // has no build for them), and where the kernel lowers activations of a layer with 256 channels and at most 64 columns
     // (any share) or 128 columns (half of the channels or more), or 64 channels and at most 64 columns: its bit-lowering
@@ -599,6 +609,7 @@ int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     p.x_pre = L->x_prelowered ? 1 : 0;
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.tiles = (int)tiles;
+    if (lowering) { p.next_ashift = lower->ashift; p.next_K4 = lower->K4; p.next_gs_log2 = lower->gs_log2; }
     const int cols = std::min(L->N, kMaxCols);
     const int nt = cols <= 64 ? 2 : (cols <= 128 ? 4 : 8);
     const int bn = 32 * nt;
@@ -612,11 +623,11 @@ int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
         if (groups > 0x7fffffff) return FLEXIQ_OK;
         p.groups = (int)groups;
         p.slots = rp.slots;
-        const size_t lds = (size_t)p.units * 2 * (bn + 2) * 16 + 2 * bn * 4 + 128 + (size_t)rp.waves * rp.slots * kGroup * L->C;
+        const size_t lds = (size_t)p.units * 2 * (bn + 2) * 16 + 3 * bn * 4 + 128 + (size_t)rp.waves * rp.slots * kGroup * L->C;
         int64_t gx64 = std::max<int64_t>(1, std::min<int64_t>((groups + rp.waves - 1) / rp.waves, (int64_t)ds.num_cu * rp.per_cu / gy));
         if (gy > 1 && gx64 >= 8) gx64 &= ~(int64_t)7;
         void (*fn)(const Params) = nullptr;
-#define FQ_R(NT_, U_) (units_p > 0 ? k_rows<NT_, U_, true, true> : (q_only ? k_rows<NT_, U_, true, false> : k_rows<NT_, U_, false, false>))
+#define FQ_R(NT_, U_) (lowering ? k_rows<NT_, U_, true, false, true> : (units_p > 0 ? k_rows<NT_, U_, true, true> : (q_only ? k_rows<NT_, U_, true, false> : k_rows<NT_, U_, false, false>)))
         if (p.units == 2) fn = nt == 2 ? FQ_R(2, 2) : (nt == 4 ? FQ_R(4, 2) : FQ_R(8, 2));
         else if (p.units == 4) fn = nt == 2 ? FQ_R(2, 4) : (nt == 4 ? FQ_R(4, 4) : FQ_R(8, 4));
         else fn = nt == 2 ? FQ_R(2, 8) : (nt == 4 ? FQ_R(4, 8) : FQ_R(8, 8));
@@ -632,7 +643,7 @@ int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     if (pl.per_cu == 0) return FLEXIQ_OK;
     const int per_cu = pl.per_cu, slots = pl.slots;
     p.slots = slots;
-    const size_t lds = (size_t)wbytes + 2 * bn * 4 + 128 + (size_t)slots * slot;
+    const size_t lds = (size_t)wbytes + 3 * bn * 4 + 128 + (size_t)slots * slot;
     // One resident wave of blocks in all: every block loads its weights once and walks tiles / gx row tiles.  With several
     // column blocks (grid.y) the blocks of one row share gx = 0 mod 8, i.e. one XCD and its L2, which then fetches the
     // activation rows from memory once.
@@ -645,7 +656,7 @@ int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     const int cw = per_cu <= 2 ? 2 : 1;
     if (cw == 1 && !(p.units == 2 && nt <= 4)) return FLEXIQ_EINVAL;   // (no such build: cannot happen with the sizes above)
     void (*fn)(const Params) = nullptr;
-#define FQ_Q(NT_, U_, CW_) (q_only ? k_stream<NT_, U_, CW_, true> : k_stream<NT_, U_, CW_, false>)
+#define FQ_Q(NT_, U_, CW_) (lowering ? k_stream<NT_, U_, CW_, true, true> : (q_only ? k_stream<NT_, U_, CW_, true> : k_stream<NT_, U_, CW_, false>))
     if (cw == 1) fn = nt == 2 ? FQ_Q(2, 2, 1) : FQ_Q(4, 2, 1);
     else if (p.units == 2) fn = FQ_Q(8, 2, 2);
     else if (p.units == 4) fn = nt == 2 ? FQ_Q(2, 4, 2) : (nt == 4 ? FQ_Q(4, 4, 2) : FQ_Q(8, 4, 2));

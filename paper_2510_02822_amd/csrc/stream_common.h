@@ -100,11 +100,30 @@ struct FragOut {     // the outputs of a call (any may be null) and the requanti
     int32_t N;
 };
 
+// What the consumer of the int8 rows does to its input, done here instead (Section 4.1 applied where the tensor is produced):
+// per quad of output columns (four consecutive channels of the consumer, which share a channel group) the clamp bounds of
+// the offset code, 128 - (8 << s) and 127 + (8 << s) as floats, and the mask that clears the s low bits of four bytes;
+// 0, 255 and all ones where the consumer reads the columns at 8 bits.  `quads` entries of 16 bytes from `ltab` on.
+__device__ __forceinline__ void fill_lower_table(unsigned char *ltab, int quads, int n_blk, const int32_t *next_ashift, int next_K4,
+                                                 int next_gs_log2, int tid, int nthreads)
+{
+    for (int qd = tid; qd < quads; qd += nthreads) {
+        const int n = n_blk + 4 * qd;
+        const bool low = n < next_K4;
+        const int s = low ? next_ashift[n >> next_gs_log2] : 0;
+        const int L = low ? (8 << s) : 128;
+        const uint32_t mask = 0x01010101u * ((0xFFu << s) & 0xFFu);
+        *reinterpret_cast<v4i *>(ltab + 16 * qd) = (v4i){__float_as_int(128.0f - (float)L), __float_as_int(127.0f + (float)L), (int)mask, 0};
+    }
+}
+
 // Epilogue of one accumulator fragment (32 rows x 32 columns; lane: row m, register 4 g + i: column 32 ca + 8 g + 4 fh + i
 // of the block, n_blk + that of the layer).  tabb: the block's table in LDS, BN multipliers then BN addends (fp32;
 // pre-multiplied by 1 / S_out, with 128 added, when pre_scaled).  lim: columns left from the lane's first one
-// (N - n_blk - 4 fh).  QONLY: int8 rows and nothing else, N a multiple of 16.
-template <bool QONLY, int BN>
+// (N - n_blk - 4 fh).  QONLY: int8 rows and nothing else, N a multiple of 16.  LOWER (with QONLY): the codes leave bit-lowered
+// for the consumer, by the table of fill_lower_table behind the two float tables: the offset code is clamped before it is
+// rounded (the bounds are integers, so that equals clamping the rounded code) and its low bits are cleared afterwards.
+template <bool QONLY, int BN, bool LOWER = false>
 __device__ __forceinline__ void store_fragment(const v16i &acc, const FragOut &o, const unsigned char *tabb, int ca, int n_blk, int64_t m,
                                                bool row_ok, int lim, int fh, bool pre_scaled, bool q_rows)
 {
@@ -118,6 +137,18 @@ __device__ __forceinline__ void store_fragment(const v16i &acc, const FragOut &o
             v4i mi = *reinterpret_cast<const v4i *>(tabb + 4 * c), ai = *reinterpret_cast<const v4i *>(tabb + 4 * (BN + c));
             asm volatile("" : "+v"(mi), "+v"(ai));
             uint32_t qw = 0;
+            if constexpr (LOWER) {
+                static_assert(QONLY, "the lowering epilogue writes int8 rows only");
+                v4i lt = *reinterpret_cast<const v4i *>(tabb + 4 * (2 * BN) + 4 * c);   // entry c / 4
+                asm volatile("" : "+v"(lt));
+                const float lo = __int_as_float(lt.x), hi = __int_as_float(lt.y);
+                qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f(__builtin_fmaf((float)acc[4 * g + 0], __int_as_float(mi.x), __int_as_float(ai.x)), lo, hi), 0, qw);
+                qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f(__builtin_fmaf((float)acc[4 * g + 1], __int_as_float(mi.y), __int_as_float(ai.y)), lo, hi), 1, qw);
+                qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f(__builtin_fmaf((float)acc[4 * g + 2], __int_as_float(mi.z), __int_as_float(ai.z)), lo, hi), 2, qw);
+                qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f(__builtin_fmaf((float)acc[4 * g + 3], __int_as_float(mi.w), __int_as_float(ai.w)), lo, hi), 3, qw);
+                qrow[g] = (qw ^ 0x80808080u) & (uint32_t)lt.z;
+                continue;
+            }
             qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 0], __int_as_float(mi.x), __int_as_float(ai.x)), 0, qw);
             qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 1], __int_as_float(mi.y), __int_as_float(ai.y)), 1, qw);
             qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)acc[4 * g + 2], __int_as_float(mi.z), __int_as_float(ai.z)), 2, qw);

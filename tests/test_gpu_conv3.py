@@ -126,3 +126,61 @@ def test_conv3_automatic_route(env):
     got = fq.flexiq_mixed_conv_implicit(hl, Xd, 2, 1, acc=True)["acc"].cpu().numpy()   # stride 2: the tiled kernel
     assert fq.debug_last_launch()["tile"] >= 0
     assert (got == oracle.forward_conv(ol, Xq, 2, 1, 0.5)).all()
+
+
+@pytest.mark.parametrize("B,H,W,C,N1,gs2,rows", [(2, 9, 12, 64, 64, 32, 0), (3, 7, 9, 128, 96, 32, 2), (1, 14, 14, 64, 128, 64, 3)])
+def test_conv3_lowers_for_consumer(env, B, H, W, C, N1, gs2, rows):
+    # the fused producer (Section 4.1 applied where the tensor is produced) on the 3x3 kernel: the NHWC int8 output in the
+    # consumer's stored channel order with the consumer's 4-bit channels clamped and masked at its positions; the consumer
+    # is a 1x1 convolution over the same pixels
+    torch, oracle, fq, dev = env
+    helpers = __import__("helpers")
+    c1 = workloads.make_conv("c3low1", 13, 400 + C + N1, B, H, W, C, N1, 3, 3, 1, 1, 32)
+    xs1, am1 = helpers.calib(c1)
+    o1 = oracle.prepare_layer(c1.W, am1, xs1, 32, bias=c1.bias)
+    X1 = np.ascontiguousarray(oracle.quantize(c1.X, xs1)[..., o1.perm])
+    acc1 = oracle.forward_conv(o1, X1, 1, 1, 0.5)
+    s_mid = float(np.abs(oracle.dequant_f64(acc1, xs1, o1.w_scale, o1.bias)).max() / 127.0 * 0.8)
+    q1 = requant_fp32_sequence(acc1, o1, s_mid)
+    check_q(q1, acc1, o1, s_mid)
+    c2 = workloads.make_conv("c3low2", 13, 401 + C + N1, B, H, W, N1, 48, 1, 1, 1, 0, gs2)
+    am2 = np.abs(q1).reshape(-1, N1).max(0).astype(np.float32) * np.float32(s_mid) * np.float32(0.5)   # too narrow: the clamp bites
+    o2 = oracle.prepare_layer(c2.W, am2, s_mid, gs2, bias=c2.bias)
+    h2 = fq.flexiq_quantize_pack(c2.W, am2, s_mid, gs2, bias=c2.bias)
+    h1 = fq.flexiq_quantize_pack(c1.W, am1, xs1, 32, bias=c1.bias, out_perm=o2.perm)
+    X2 = np.ascontiguousarray(q1[..., o2.perm])
+    fq.flexiq_set_ratio(h1, 0.5)
+    X1d = _dev(torch, X1, dev)
+    sh = np.repeat(o2.a_shift.astype(np.int32), gs2)
+    G2 = N1 // gs2
+    fq.debug_force_conv3(1, rows)
+    try:
+        for r2 in sorted({0.0, 1.0 / G2, 1.0}):
+            k4 = fq.flexiq_set_ratio(h2, r2)
+            want = X2.astype(np.int32).copy()
+            want[..., :k4] = np.clip(want[..., :k4] >> sh[:k4], -8, 7) << sh[:k4]
+            low = fq.flexiq_mixed_conv_implicit(h1, X1d, 1, 1, q=True, out_scale=s_mid, lower_for=h2)["q"]
+            torch.cuda.synchronize()
+            assert fq.debug_force_conv3(1, rows) == 1 and fq.debug_last_launch()["tile"] == -3   # ran on this kernel
+            assert (low.cpu().numpy().astype(np.int32) == want).all(), r2
+            fq.debug_force_conv3(0, 0)
+            tiled = fq.flexiq_mixed_conv_implicit(h1, X1d, 1, 1, q=True, out_scale=s_mid, lower_for=h2)["q"]
+            assert fq.debug_last_launch()["tile"] >= 0
+            assert (tiled.cpu().numpy() == low.cpu().numpy()).all(), r2
+            fq.flexiq_input_prelowered(h2, True)
+            got = fq.flexiq_mixed_conv_implicit(h2, low, 1, 0, acc=True)["acc"].cpu().numpy()
+            fq.flexiq_input_prelowered(h2, False)
+            fq.debug_force_conv3(1, rows)
+            assert (got == oracle.forward_conv(o2, X2, 1, 0, r2)).all(), r2
+    finally:
+        fq.debug_force_conv3(-1, 0)
+        fq.flexiq_input_prelowered(h2, False)
+    # a producer whose output order is not the consumer's stored order is refused on this route too
+    if not (o2.perm == np.arange(N1)).all():
+        h1_plain = fq.flexiq_quantize_pack(c1.W, am1, xs1, 32, bias=c1.bias)
+        fq.debug_force_conv3(1, rows)
+        try:
+            with pytest.raises(fq.FlexiqError):
+                fq.flexiq_mixed_conv_implicit(h1_plain, X1d, 1, 1, q=True, out_scale=s_mid, lower_for=h2)
+        finally:
+            fq.debug_force_conv3(-1, 0)

@@ -161,3 +161,59 @@ def test_blocks_walk_many_tiles(env, K, N, kernel):
             assert bool((tiled == only_q).all()) and bool((only_q == out["q"]).all()), r
     finally:
         fq.debug_force_stream(-1)
+
+
+@pytest.mark.parametrize("M,K1,N1,N2,gs2", [(1000, 64, 256, 40, 32), (777, 128, 576, 64, 64), (513, 256, 96, 24, 32), (300, 256, 128, 128, 64),
+                                           (2100, 64, 64, 256, 32)])
+@pytest.mark.parametrize("kernel", [1, 2])
+def test_producer_lowers_for_consumer(env, M, K1, N1, N2, gs2, kernel):
+    # the fused producer (Section 4.1 applied where the tensor is produced; Section 5 steps 1-2) on the row-streaming kernels:
+    # int8 rows in the consumer's stored channel order, its 4-bit channels clamped and masked at the consumer's positions;
+    # the consumer, told so, then copies them like 8-bit ones and gets the accumulators of lowering on the fly
+    torch, oracle, fq, dev = env
+    helpers = __import__("helpers")
+    c1 = workloads.make_linear("slow1", 12, 300 + M + N1, M, K1, N1, 32, outlier_frac=0.02)
+    c2 = workloads.make_linear("slow2", 12, 301 + M + N1, M, N1, N2, gs2, outlier_frac=0.02)
+    xs1, am1 = helpers.calib(c1)
+    o1 = oracle.prepare_layer(c1.W, am1, xs1, 32, bias=c1.bias)
+    Xq = np.ascontiguousarray(oracle.quantize(c1.X, xs1)[:, o1.perm])
+    acc1 = oracle.forward_gemm(o1, Xq, 0.5)
+    s_mid = float(np.abs(oracle.dequant_f64(acc1, xs1, o1.w_scale, o1.bias)).max() / 127.0 * 0.8)   # some codes clip
+    q1 = requant_fp32_sequence(acc1, o1, s_mid)
+    check_q(q1, acc1, o1, s_mid)
+    am2 = np.abs(q1).max(0).astype(np.float32) * np.float32(s_mid) * np.float32(0.5)   # calibrated too narrow: the clamp bites
+    o2 = oracle.prepare_layer(c2.W, am2, s_mid, gs2, bias=c2.bias)
+    h2 = fq.flexiq_quantize_pack(c2.W, am2, s_mid, gs2, bias=c2.bias)
+    h1 = fq.flexiq_quantize_pack(c1.W, am1, xs1, 32, bias=c1.bias, out_perm=o2.perm)
+    X2 = np.ascontiguousarray(q1[:, o2.perm])
+    fq.flexiq_set_ratio(h1, 0.5)
+    Xd = _dev(torch, Xq, dev)
+    sh = np.repeat(o2.a_shift.astype(np.int32), gs2)
+    G2 = N1 // gs2
+    fq.debug_force_stream(kernel)
+    try:
+        for r2 in sorted({0.0, 1.0 / G2, 0.5, 1.0}):
+            k4 = fq.flexiq_set_ratio(h2, r2)
+            want = X2.astype(np.int32).copy()
+            want[:, :k4] = np.clip(want[:, :k4] >> sh[:k4], -8, 7) << sh[:k4]
+            assert all(oracle.bitlower(int(X2[i, j]), int(sh[j])) << int(sh[j]) == want[i, j] for i in (0, M // 2, M - 1) for j in range(0, k4, 7))
+            low = fq.flexiq_mixed_gemm(h1, Xd, q=True, out_scale=s_mid, lower_for=h2)["q"]
+            torch.cuda.synchronize()
+            assert fq.debug_force_stream(kernel) == kernel and fq.debug_last_launch()["tile"] == -2   # ran on that kernel
+            assert (low.cpu().numpy().astype(np.int32) == want).all(), r2
+            fq.debug_force_stream(0)
+            tiled = fq.flexiq_mixed_gemm(h1, Xd, q=True, out_scale=s_mid, lower_for=h2)["q"]       # the tiled kernel lowers alike
+            assert fq.debug_last_launch()["tile"] >= 0
+            assert (tiled.cpu().numpy() == low.cpu().numpy()).all(), r2
+            fq.flexiq_input_prelowered(h2, True)
+            got = fq.flexiq_mixed_gemm(h2, low, acc=True)["acc"].cpu().numpy()
+            fq.flexiq_input_prelowered(h2, False)
+            fq.debug_force_stream(kernel)
+            assert (got == oracle.forward_gemm(o2, X2, r2)).all(), r2
+        # an output that is not int8 alone next to lower_for is served by the tiled kernel, with the same int8 rows
+        both = fq.flexiq_mixed_gemm(h1, Xd, acc=True, q=True, out_scale=s_mid, lower_for=h2)
+        assert fq.debug_last_launch()["tile"] >= 0
+        assert (both["q"].cpu().numpy() == low.cpu().numpy()).all() and (both["acc"].cpu().numpy() == acc1[:, o2.perm]).all()
+    finally:
+        fq.debug_force_stream(-1)
+        fq.flexiq_input_prelowered(h2, False)
