@@ -342,6 +342,55 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
             torch.cuda.synchronize()
             rec(wl, "int8 kernels, " + tag, float(fn(0)) if tag == "fixed r" else None, us, ops=ops, GBs=round(byts / us / 1e3, 1),
                 frac_hbm_peak=round(byts / us / 1e3 / HBM_PEAK_GBS, 4), bound="mixed (mfma / hbm per layer)", calls_per_kernel=routes)
+        # The same pass with the bottleneck chains fused (Section 5 steps 1-2, Section 4.1 at the producer): inside a
+        # bottleneck the reducing 1x1 feeds the 3x3 and the 3x3 feeds the expanding 1x1, so those producers are packed
+        # with the consumer's stored channel order as their output order and lower their int8 output for it
+        # (flexiq_out.lower_for); the consumers copy their activations like 8-bit ones.  The reducing 1x1 layers and
+        # the downsample layers read the output of the residual addition (not a layer of this library) and still lower
+        # on the fly.  Timing only: the consumers' input buffers hold the same synthetic activations as above.
+        names = [sh.name for sh in workloads.resnet50_shapes()]
+        consumer_of = {"s1_1x1_64_64": "s1_3x3_64_64", "s1_3x3_64_64": "s1_1x1_64_256", "s1_1x1_256_64": "s1_3x3_64_64",
+                       "s2_1x1_256_128": "s2_3x3_128_128_s2", "s2_3x3_128_128_s2": "s2_1x1_128_512", "s2_1x1_512_128": "s2_3x3_128_128",
+                       "s2_3x3_128_128": "s2_1x1_128_512", "s3_1x1_512_256": "s3_3x3_256_256_s2", "s3_3x3_256_256_s2": "s3_1x1_256_1024",
+                       "s3_1x1_1024_256": "s3_3x3_256_256", "s3_3x3_256_256": "s3_1x1_256_1024", "s4_1x1_1024_512": "s4_3x3_512_512_s2",
+                       "s4_3x3_512_512_s2": "s4_1x1_512_2048", "s4_1x1_2048_512": "s4_3x3_512_512", "s4_3x3_512_512": "s4_1x1_512_2048"}
+        fed = set(consumer_of.values())
+        for i, nm in enumerate(names):
+            L = layers[i]
+            L["consumer"] = layers[names.index(consumer_of[nm])]["layer"] if nm in consumer_of else None
+            L["chained"] = L["layer"]
+            if L["consumer"] is not None:
+                case = workloads.config4_layer(i, B=128)
+                x_scale, amax = _calib(case)
+                L["chained"] = fq.flexiq_quantize_pack(case.W, amax, x_scale, case.group_size, bias=case.bias,
+                                                       out_perm=L["consumer"].info()["perm"])
+                del case
+            L["fed"] = nm in fed
+
+        def chained_pass(r):
+            for L, j in calls:
+                fq.flexiq_mixed_conv_implicit(L["chained"], L["X"], L["stride"], L["pad"], q=True, out_scale=L["so"], bufs={"q": L["outs"][j]},
+                                              lower_for=L["consumer"])
+
+        for r in (0.5, 1.0):
+            for L in layers:
+                fq.flexiq_set_ratio(L["layer"], r)
+                fq.flexiq_set_ratio(L["chained"], r)
+                fq.flexiq_input_prelowered(L["chained"], L["fed"])
+            us = _median_graph_us(torch, lambda: chained_pass(r), 1, repeats=5, settle_s=0.04)
+            routes = {"tiled": 0, "row-streaming": 0, "3x3 resident weights": 0}
+            for L, j in calls:
+                fq.flexiq_mixed_conv_implicit(L["chained"], L["X"], L["stride"], L["pad"], q=True, out_scale=L["so"], bufs={"q": L["outs"][j]},
+                                              lower_for=L["consumer"])
+                t = fq.debug_last_launch()["tile"]
+                routes["row-streaming" if t == -2 else ("3x3 resident weights" if t == -3 else "tiled")] += 1
+            torch.cuda.synchronize()
+            rec(wl, "int8 kernels, fixed r, bottleneck chains fused: %d of %d calls lower for their consumer, %d read lowered input"
+                % (sum(1 for L, _ in calls if L["consumer"] is not None), len(calls), sum(1 for L, _ in calls if L["fed"])),
+                r, us, ops=ops, GBs=round(byts / us / 1e3, 1), frac_hbm_peak=round(byts / us / 1e3 / HBM_PEAK_GBS, 4),
+                bound="mixed (mfma / hbm per layer)", calls_per_kernel=routes)
+        for L in layers:
+            fq.flexiq_input_prelowered(L["chained"], False)
         del layers, calls
     return out
 
