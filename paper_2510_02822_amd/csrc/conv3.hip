@@ -347,8 +347,8 @@ int launch_conv3(const flexiq_layer *L, const int8_t *X, int B, int H, int W, in
     if (L->R != 3 || L->S != 3 || stride != 1 || pad != 1 || (L->C != 64 && L->C != 128)) return FLEXIQ_OK;
     if (out->scan_for || out->x4 || out->x6) return FLEXIQ_OK;
     const bool q_only = out->q && !out->acc && !out->y && (L->N & 15) == 0;
-    const bool lowering = out->lower_for != nullptr;
-    if (lowering && !(lower && lower->ashift && q_only)) return FLEXIQ_OK;   // (the lowering build writes int8 only)
+    const bool lowering = lower && lower->ashift;   // (null positions: the consumer has no 4-bit channels at its ratio)
+    if (lowering && !q_only) return FLEXIQ_OK;   // (the lowering build writes int8 only)
     const DeviceState &ds = g_dev[L->device];
     if (!ds.ready) return FLEXIQ_OK;
     if ((int64_t)H * W * L->C >= (1 << 29) || W > 1024) return FLEXIQ_OK;

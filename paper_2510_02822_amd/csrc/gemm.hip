@@ -142,6 +142,7 @@ int lower_for_args(const flexiq_layer *L, const flexiq_out *out, LowerArgs *la)
     if (out->scan_for) return FLEXIQ_EINVAL;   // lowering needs positions the scan has yet to find
     if (!out->q || nx->C != L->N || nx->device != L->device) return FLEXIQ_EINVAL;
     if (nx->G > kMaxGroups || !orders_match(L, nx)) return FLEXIQ_EINVAL;
+    if (nx->max_4bit_ch == 0) return FLEXIQ_OK;   // the consumer reads every channel at 8 bits: nothing to lower
     la->ashift = nx->dynamic ? nx->d_ashift_dyn : nx->d_ashift;
     la->K4 = nx->max_4bit_ch;
     la->gs_log2 = nx->group_size == 64 ? 6 : 5;
@@ -171,7 +172,8 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
         const flexiq_layer *nx = out->lower_for;
         if (!out->q || nx->C != L->N || nx->device != L->device) return FLEXIQ_EINVAL;
         if (nx->G > kMaxGroups || !orders_match(L, nx)) return FLEXIQ_EINVAL;   // consumer's table lives in LDS; column order
-        p.next_ashift = nx->dynamic ? nx->d_ashift_dyn : nx->d_ashift;
+        // (a consumer that reads every channel at 8 bits has nothing lowered: the plain epilogue serves the call)
+        if (nx->max_4bit_ch > 0 || out->x4) p.next_ashift = nx->dynamic ? nx->d_ashift_dyn : nx->d_ashift;
         p.next_K4 = nx->max_4bit_ch;
         p.next_G = nx->G;
         p.next_gs_log2 = nx->group_size == 64 ? 6 : 5;
@@ -235,7 +237,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
         const bool ok = (!conv || (stride == 1 && pad == 0)) && g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0;
         LowerArgs la;
         la.ashift = p.next_ashift; la.K4 = p.next_K4; la.gs_log2 = p.next_gs_log2;   // (checked above)
-        const int rc = launch_stream(L, X, M, out, stream, ok, &taken, xp ? X4 : nullptr, out->lower_for ? &la : nullptr);
+        const int rc = launch_stream(L, X, M, out, stream, ok, &taken, xp ? X4 : nullptr, &la);
         if (rc != FLEXIQ_OK) return rc;
         if (taken) {
             g_last_shape = -2;
@@ -402,7 +404,7 @@ extern "C" int flexiq_mixed_conv_implicit(const flexiq_layer *L, const int8_t *X
                 FLEXIQ_HIP(hipGetDevice(&dev));
                 if (dev != L->device) return FLEXIQ_EINVAL;
             }
-            rc = launch_conv3(L, X, B, H, W, stride, pad, out, stream, &taken, la.ashift ? &la : nullptr);
+            rc = launch_conv3(L, X, B, H, W, stride, pad, out, stream, &taken, &la);
             if (rc != FLEXIQ_OK) return rc;
         }
         if (taken) {

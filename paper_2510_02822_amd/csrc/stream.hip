@@ -573,8 +573,8 @@ int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     const int units_p = X4 && !L->x_prelowered ? (L->max_4bit_ch / 64) * 2 : 0;
     if (units_p > 0 && !q_only) return FLEXIQ_OK;   // (the packed-input builds write int8 rows only)
     // a consumer to lower for: the builds that write int8 rows only, from int8 input
-    const bool lowering = out->lower_for != nullptr;
-    if (lowering && !(lower && lower->ashift && q_only && units_p == 0)) return FLEXIQ_OK;
+    const bool lowering = lower && lower->ashift;   // (null positions: the consumer has no 4-bit channels at its ratio)
+    if (lowering && !(q_only && units_p == 0)) return FLEXIQ_OK;
     // k_rows (every wave on its own) instead of k_stream where it measures faster: whenever packed codes come in (k_stream
     // has no build for them), and where the kernel lowers activations of a layer with 256 channels and at most 64 columns
     // (any share) or 128 columns (half of the channels or more), or 64 channels and at most 64 columns: its bit-lowering
