@@ -32,6 +32,10 @@ int flexiq_debug_last_launch(int which);
 /* Slices of the split-K kernel for few-row calls: n > 0 forces n slices (capped by the reduction length), 0 = automatic. */
 int flexiq_debug_force_splits(int n);
 
+/* The few-row kernel without a workspace (linear calls with at most 64 rows; last launch: tile shape index -4):
+ * 1 = take it whenever the call qualifies, 0 = never, -1 = automatic.  Returns whether the last call it was offered ran on it. */
+int flexiq_debug_force_few_rows(int mode);
+
 /* The row-streaming kernels for layers with 64, 128 or 256 input channels (last launch: tile shape index -2):
  * 1 / 2 = take the one whose blocks walk tiles of 128 rows / the one whose waves walk groups of 32 rows on their own,
  * whenever the layer form qualifies (whatever the row count), 0 = never, -1 = automatic.  Returns which of them the

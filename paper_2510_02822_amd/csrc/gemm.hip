@@ -230,6 +230,18 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
             return FLEXIQ_OK;
         }
     }
+    // Few-row linear calls otherwise: a block per 16 output columns, the reduction split over its waves (no workspace).
+    if (!conv && !xp && M <= 64 && g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0) {
+        int taken = 0;
+        const int rc = launch_few_rows(L, X, M, out, stream, &taken);
+        if (rc != FLEXIQ_OK) return rc;
+        if (taken) {
+            g_last_shape = -4;
+            g_last_blocks = (L->N + 15) / 16;
+            g_last_resident = 0;
+            return FLEXIQ_OK;
+        }
+    }
     // Layers with a short reduction and many contiguous rows: the row-streaming kernel (weights resident in LDS, whole
     // row tiles copied several tiles ahead).
     {
