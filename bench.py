@@ -242,16 +242,16 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
         for Ms in (1, 16, 64):
             Xs = Xq[:Ms].contiguous()
             bufs = {"q": torch.empty((Ms, case.N), dtype=torch.int8, device=dev)}
-            ws = fq.flexiq_small_m_workspace(layer, dev)
             for r in (0.0, 0.5, 1.0):
                 fq.flexiq_set_ratio(layer, r)
-                for tag, kw in (("tiled kernel", {}), ("with a workspace (split-K kernel where it pays)", {"workspace": ws})):
-                    us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=so, bufs=bufs, **kw), 20)
+                for tag, force in (("tiled kernel", 0), ("few-row kernel (automatic route)", -1)):
+                    fq.debug_force_few_rows(force)
+                    us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=so, bufs=bufs), 20)
                     launch = fq.debug_last_launch()
-                    route = "w4" if launch["tile"] < 0 else "w4x"     # the split-K kernel streams the packed 4-bit codes
+                    route = "w4" if launch["tile"] == -4 else "w4x"     # the few-row kernel streams the packed 4-bit codes
                     rec("%s weights %d x %d, M=%d rows" % (name, case.N, case.K, Ms), "few-row call, " + tag, r, us,
                         byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, route), launch=launch)
-            del ws
+                fq.debug_force_few_rows(-1)
     packed.clear()
 
     # ---- an HBM-bound layer as a linear call: the ResNet-50 stage-1 1x1 convolution 256 -> 64 at 56 x 56, batch 128
@@ -428,8 +428,7 @@ def profile_only(torch, fq, workloads, dev, what, launches):
         if what == "vitl_fc2":
             call = lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=0.05, bufs=q)
         elif what == "vitl_fc2_rows16":
-            ws = fq.flexiq_small_m_workspace(layer, dev)
-            call = lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=0.05, bufs=q, workspace=ws)
+            call = lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=0.05, bufs=q)
         elif what == "reorder":
             call = lambda: fq.flexiq_permute_channels(layer, Xn)
         else:

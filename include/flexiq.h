@@ -184,16 +184,7 @@ int flexiq_permute_channels(const flexiq_layer *layer, const int8_t *src, int8_t
  *   x4        : optional, with lower_for on a linear consumer and q (flexiq_mixed_gemm / flexiq_mixed_conv_implicit): dev
  *               pointer to the consumer's packed 4-bit activation buffer (flexiq_packed4_bytes(consumer, M) bytes).  The
  *               columns that are packed channels of the consumer (flexiq_packed4_channels) are then written there as
- *               4-bit codes instead of into q; q keeps the other columns.  Needs N % 32 == 0
- *   workspace, workspace_bytes : optional.  Device memory (16-byte aligned, at least
- *               flexiq_small_m_workspace_bytes(layer) bytes, ZERO when first handed in) that lets flexiq_mixed_gemm
- *               serve calls of at most 64 rows with the split-K kernel: the reduction is cut into slices across
- *               blocks so that every compute unit streams its share of the weights (4-bit groups from the packed
- *               4-bit codes: half the bytes, Section 7), partial sums meet in the workspace and the block that arrives
- *               last per 128 output columns adds them up and runs the epilogue.  The call leaves the first 128 KB (its
- *               tickets) zero again, so one workspace serves any sequence of calls on one stream; calls that overlap
- *               on one workspace race.  Ignored (the tiled kernel runs) for more than 64 rows, for convolutions, with
- *               lower_for / scan_for, or when it is NULL or too small */
+ *               4-bit codes instead of into q; q keeps the other columns.  Needs N % 32 == 0 */
 typedef struct {
     int32_t *acc;
     float *y;
@@ -203,8 +194,6 @@ typedef struct {
     flexiq_layer *scan_for;
     uint8_t *x6;
     uint8_t *x4;
-    void *workspace;
-    int64_t workspace_bytes;
 } flexiq_out;
 
 /* Mixed-precision GEMM (Sections 2.3, 7):
@@ -218,9 +207,6 @@ typedef struct {
  * kernel has run.  Errors: FLEXIQ_EINVAL (null / inconsistent arguments, M >= 2^31 - 512, more than 159 channel
  * groups, a padded weight matrix of 1 GiB or more, current device is not the handle's), FLEXIQ_EALIGN, FLEXIQ_EHIP. */
 int flexiq_mixed_gemm(const flexiq_layer *layer, const int8_t *X, int64_t M, const flexiq_out *out, void *stream);
-
-/* Bytes of flexiq_out.workspace that serve any few-row call on this layer (negative flexiq_status on error). */
-int64_t flexiq_small_m_workspace_bytes(const flexiq_layer *layer);
 
 /* The same sum as an implicit GEMM over (filter tap, channel) for a convolution layer:
  * X: dev int8 NHWC [B][H][W][C], stored channel order, zero padding `pad`, stride `stride`;

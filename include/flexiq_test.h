@@ -26,13 +26,10 @@ int flexiq_debug_force_packed4(int mode);
 int flexiq_debug_max_blocks(int n);
 
 /* What the last GEMM / convolution launch used.  which = 0: tile shape index, 1: blocks launched,
- * 2: blocks of that kernel resident per compute unit, 3: split-K slices (1 = the tiled kernel). */
+ * 2: blocks of that kernel resident per compute unit. */
 int flexiq_debug_last_launch(int which);
 
-/* Slices of the split-K kernel for few-row calls: n > 0 forces n slices (capped by the reduction length), 0 = automatic. */
-int flexiq_debug_force_splits(int n);
-
-/* The few-row kernel without a workspace (linear calls with at most 64 rows; last launch: tile shape index -4):
+/* The few-row kernel (linear calls with at most 64 rows; last launch: tile shape index -4):
  * 1 = take it whenever the call qualifies, 0 = never, -1 = automatic.  Returns whether the last call it was offered ran on it. */
 int flexiq_debug_force_few_rows(int mode);
 

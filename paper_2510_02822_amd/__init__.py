@@ -8,7 +8,7 @@ from .binding import (FlexiqError, Layer, flexiq_bitlower, flexiq_dynamic_positi
                       flexiq_mixed_gemm, flexiq_permute_channels, flexiq_quantize_act, flexiq_quantize_pack,
                       flexiq_set_ratio, exported_symbols, load, debug_force_tile, debug_force_packed4,
                       debug_max_blocks, debug_last_launch, flexiq_fp6_channels, flexiq_fp6_bytes, flexiq_lower_fp6,
-                      flexiq_mixed_gemm_fp6, debug_force_fp6_tile, flexiq_small_m_workspace, debug_force_splits,
+                      flexiq_mixed_gemm_fp6, debug_force_fp6_tile,
                       flexiq_packed4_channels, flexiq_packed4_bytes, flexiq_lower_packed4, flexiq_mixed_gemm_packed4,
                       debug_force_stream, debug_force_conv3, debug_force_few_rows)
 
@@ -16,6 +16,6 @@ __all__ = ["FlexiqError", "Layer", "flexiq_bitlower", "flexiq_dynamic_positions"
            "flexiq_layer_positions", "flexiq_input_prelowered", "flexiq_layer_dump", "flexiq_mixed_conv_implicit",
            "flexiq_mixed_gemm", "flexiq_permute_channels", "flexiq_quantize_act", "flexiq_quantize_pack",
            "flexiq_set_ratio", "exported_symbols", "load", "debug_force_tile", "debug_force_packed4", "debug_max_blocks", "debug_last_launch", "flexiq_fp6_channels", "flexiq_fp6_bytes", "flexiq_lower_fp6",
-           "flexiq_mixed_gemm_fp6", "debug_force_fp6_tile", "flexiq_small_m_workspace", "debug_force_splits",
+           "flexiq_mixed_gemm_fp6", "debug_force_fp6_tile",
            "flexiq_packed4_channels", "flexiq_packed4_bytes", "flexiq_lower_packed4", "flexiq_mixed_gemm_packed4",
            "debug_force_stream", "debug_force_conv3", "debug_force_few_rows"]

@@ -24,15 +24,14 @@ class _PackDesc(C.Structure):
 
 class _Out(C.Structure):
     _fields_ = [("acc", C.c_void_p), ("y", C.c_void_p), ("q", C.c_void_p), ("out_scale", C.c_float),
-                ("lower_for", C.c_void_p), ("scan_for", C.c_void_p), ("x6", C.c_void_p), ("x4", C.c_void_p),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64)]
+                ("lower_for", C.c_void_p), ("scan_for", C.c_void_p), ("x6", C.c_void_p), ("x4", C.c_void_p)]
 
 
 def exported_symbols():
     """Names include/flexiq.h declares."""
     return ["flexiq_packed4_channels", "flexiq_packed4_bytes", "flexiq_lower_packed4", "flexiq_mixed_gemm_packed4",
             "flexiq_dynamic_positions_static", "flexiq_fp6_channels", "flexiq_fp6_bytes", "flexiq_lower_fp6",
-            "flexiq_mixed_gemm_fp6", "flexiq_small_m_workspace_bytes", "flexiq_strerror", "flexiq_last_hip_error", "flexiq_quantize_pack", "flexiq_layer_free",
+            "flexiq_mixed_gemm_fp6", "flexiq_strerror", "flexiq_last_hip_error", "flexiq_quantize_pack", "flexiq_layer_free",
             "flexiq_layer_info", "flexiq_layer_dump", "flexiq_set_ratio", "flexiq_quantize_act",
             "flexiq_bitlower", "flexiq_dynamic_positions", "flexiq_static_positions", "flexiq_layer_positions",
             "flexiq_input_prelowered", "flexiq_permute_channels", "flexiq_mixed_gemm", "flexiq_mixed_conv_implicit"]
@@ -78,12 +77,9 @@ def load():
     L.flexiq_lower_packed4.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     L.flexiq_mixed_gemm_packed4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(_Out), C.c_void_p]
     L.flexiq_debug_force_fp6_tile.argtypes = [C.c_int]
-    L.flexiq_debug_force_splits.argtypes = [C.c_int]
     L.flexiq_debug_force_stream.argtypes = [C.c_int]
     L.flexiq_debug_force_few_rows.argtypes = [C.c_int]
     L.flexiq_debug_force_conv3.argtypes = [C.c_int, C.c_int]
-    L.flexiq_small_m_workspace_bytes.argtypes = [C.c_void_p]
-    L.flexiq_small_m_workspace_bytes.restype = C.c_int64
     L.flexiq_debug_force_tile.argtypes = [C.c_int]
     L.flexiq_debug_force_packed4.argtypes = [C.c_int]
     L.flexiq_debug_max_blocks.argtypes = [C.c_int]
@@ -344,33 +340,20 @@ def _outs(shape, device, want_acc, want_y, want_q, out_scale, bufs, lower_for=No
         q = bufs.get("q") if bufs and "q" in bufs else torch.empty(shape, dtype=torch.int8, device=device)
     o = _Out(acc.data_ptr() if acc is not None else None, y.data_ptr() if y is not None else None,
              q.data_ptr() if q is not None else None, float(out_scale),
-             lower_for._h if lower_for is not None else None, scan_for._h if scan_for is not None else None, None, None, 0)
+             lower_for._h if lower_for is not None else None, scan_for._h if scan_for is not None else None, None, None)
     return o, {"acc": acc, "y": y, "q": q}
-
-
-def flexiq_small_m_workspace(layer: Layer, device):
-    """A zeroed workspace tensor for few-row calls on this layer (flexiq_out.workspace)."""
-    import torch
-    n = load().flexiq_small_m_workspace_bytes(layer._h)
-    if n < 0:
-        _check(int(n))
-    return torch.zeros(int(n), dtype=torch.uint8, device=device)
 
 
 def flexiq_mixed_gemm(layer: Layer, X, acc: bool = False, y: bool = False, q: bool = False,
                       out_scale: float = 1.0, bufs: Optional[dict] = None, lower_for: Optional[Layer] = None,
-                      scan_for: Optional[Layer] = None, workspace=None, x4_out=None):
+                      scan_for: Optional[Layer] = None, x4_out=None):
     """X: int8 cuda [M][C] in stored channel order.  Returns a dict of the requested outputs.
     lower_for / scan_for: the layer that consumes q (flexiq_out.lower_for, flexiq_out.scan_for).
-    workspace: uint8 cuda tensor from flexiq_small_m_workspace (flexiq_out.workspace; few-row calls).
     x4_out: with lower_for, the consumer's packed 4-bit activation buffer (flexiq_out.x4)."""
     import torch
     assert X.is_cuda and X.dtype == torch.int8 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == layer.C
     M = X.shape[0]
     o, res = _outs((M, layer.N), X.device, acc, y, q, out_scale, bufs, lower_for, scan_for)
-    if workspace is not None:
-        o.workspace = workspace.data_ptr()
-        o.workspace_bytes = workspace.numel()
     if x4_out is not None:
         o.x4 = x4_out.data_ptr()
     _check(load().flexiq_mixed_gemm(layer._h, X.data_ptr(), M, C.byref(o), _stream()))
@@ -414,7 +397,7 @@ def debug_last_launch() -> dict:
     """Tile shape index, block count and resident blocks per CU of the last GEMM / convolution launch."""
     L = load()
     return {"tile": L.flexiq_debug_last_launch(0), "blocks": L.flexiq_debug_last_launch(1),
-            "resident": L.flexiq_debug_last_launch(2), "splits": L.flexiq_debug_last_launch(3)}
+            "resident": L.flexiq_debug_last_launch(2)}
 
 
 def debug_force_conv3(mode: int, rows_per_tile: int = 0) -> int:
@@ -436,7 +419,7 @@ def debug_force_stream(mode: int) -> int:
 
 
 def debug_force_few_rows(mode: int) -> int:
-    """Few-row kernel without a workspace: 1 = whenever the call qualifies, 0 = never, -1 = automatic.  Returns whether the
+    """Few-row kernel: 1 = whenever the call qualifies, 0 = never, -1 = automatic.  Returns whether the
     last call it was offered ran on it."""
     rc = load().flexiq_debug_force_few_rows(int(mode))
     if rc < 0:
@@ -444,6 +427,3 @@ def debug_force_few_rows(mode: int) -> int:
     return rc
 
 
-def debug_force_splits(n: int) -> None:
-    """Slices of the split-K kernel for few-row calls (0: automatic)."""
-    _check(load().flexiq_debug_force_splits(int(n)))

@@ -68,13 +68,9 @@ struct flexiq_layer;
 namespace flexiq {
 // Leading channels of the layer that run on the FP6 matrix path under its current ratio and positions (a multiple of 64).
 int fp6_channels(const flexiq_layer *L);
-// Split-K kernel for linear calls of at most 64 rows (smallm.hip).
-int64_t small_m_workspace_bytes(const flexiq_layer *L);
-int launch_small_m(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int force_splits,
-                   int *splits_out);
-// (smallm.hip) linear calls with at most 64 rows, no workspace: a block per 16 output columns whose waves split the reduction
+// (smallm.hip) linear calls with at most 64 rows: a block per 16 output columns whose waves split the reduction
 // and meet in LDS; *taken = 0: the call does not qualify
-int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int *taken);
+int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken);
 // The consumer named by flexiq_out.lower_for, checked (gemm.hip): its positions, 4-bit prefix and log2 of its group size;
 // ashift == nullptr: the call names none.
 struct LowerArgs {

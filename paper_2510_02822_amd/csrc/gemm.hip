@@ -29,8 +29,7 @@ static const TileShape *shapes(int *count)
 static int g_force_shape = -1;
 static int g_force_packed = -1;
 static int g_max_blocks = 0;
-static int g_last_shape = -1, g_last_blocks = 0, g_last_resident = 0, g_last_splits = 1;
-static int g_force_splits = 0;
+static int g_last_shape = -1, g_last_blocks = 0, g_last_resident = 0;
 
 // Calls with at most this many output rows stream the 4-bit units as packed codes (half the weight bytes, expanded
 // in registers); larger ones use the expanded copy.  Measured on MI355X the packed route never wins with this
@@ -211,37 +210,6 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     if (L->C / kUnit >= 2 * 65535) return FLEXIQ_EINVAL;  // K-step indices are kept in 16-bit fields
     if ((int64_t)L->U * 32 * L->Npad * 2 > kMaxWeightBytes) return FLEXIQ_EINVAL;  // both int8 weight copies must fit one buffer descriptor
     p.H = H; p.Wd = Wd; p.Ho = Ho; p.Wo = Wo; p.S = L->S; p.stride = stride; p.pad = pad;
-    g_last_splits = 1;
-    // Few-row linear calls with a workspace: the split-K kernel (every compute unit streams its share of the weights).
-    // Taken where it measures faster than the tiled kernel: at most 32 rows and so few output columns that the tiled
-    // kernel's 64 x 64 tiles would occupy less than a quarter of the compute units (every block then walks a long
-    // reduction alone); with more columns the tiled kernel's two trips to memory beat the split-K kernel's chain of
-    // stream, store, ticket, re-read.  The test hook forces it for any call of at most 64 rows.
-    const bool few_rows = !conv && !xp && M <= 64 && out->workspace && !out->lower_for && !out->scan_for && g_force_shape < 0 && g_force_packed < 0;
-    if (few_rows && (g_force_splits > 0 || (M <= 32 && ((L->N + 63) / 64) * 4 < dk.num_cu && L->C >= 2048))) {
-        int splits = 1;
-        const int rc = launch_small_m(L, X, M, out, stream, dk.num_cu, g_force_splits, &splits);
-        if (rc != FLEXIQ_OK) return rc;
-        if (splits > 0) {
-            g_last_splits = splits;
-            g_last_shape = -1;
-            g_last_blocks = ((L->N + 127) / 128) * splits;
-            g_last_resident = 0;
-            return FLEXIQ_OK;
-        }
-    }
-    // Few-row linear calls otherwise: a block per 16 output columns, the reduction split over its waves (no workspace).
-    if (!conv && !xp && M <= 64 && g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0) {
-        int taken = 0;
-        const int rc = launch_few_rows(L, X, M, out, stream, &taken);
-        if (rc != FLEXIQ_OK) return rc;
-        if (taken) {
-            g_last_shape = -4;
-            g_last_blocks = (L->N + 15) / 16;
-            g_last_resident = 0;
-            return FLEXIQ_OK;
-        }
-    }
     // Layers with a short reduction and many contiguous rows: the row-streaming kernel (weights resident in LDS, whole
     // row tiles copied several tiles ahead).
     {
@@ -254,6 +222,20 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
         if (taken) {
             g_last_shape = -2;
             g_last_blocks = 0;
+            g_last_resident = 0;
+            return FLEXIQ_OK;
+        }
+    }
+    // Few-row linear calls: a block per 16 output columns, the reduction split over its waves (smallm.hip).  Measured against
+    // the tiled kernel, which launches 16-64 blocks of 64 x 64 here: faster for every call of at most 16 rows, and up to 64
+    // rows as long as there is at most one block per compute unit or so (every block reads all activation rows).
+    if (!conv && !xp && M <= 64 && g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0) {
+        int taken = 0;
+        const int rc = launch_few_rows(L, X, M, out, stream, dk.num_cu, &taken);
+        if (rc != FLEXIQ_OK) return rc;
+        if (taken) {
+            g_last_shape = -4;
+            g_last_blocks = (L->N + 15) / 16;
             g_last_resident = 0;
             return FLEXIQ_OK;
         }
@@ -296,7 +278,7 @@ static int check_out(const flexiq_out *out)
 {
     if (!out || (!out->acc && !out->y && !out->q)) return FLEXIQ_EINVAL;
     if (out->q && !(out->out_scale > 0.0f)) return FLEXIQ_EINVAL;
-    const void *ps[] = {out->acc, out->y, out->q, out->workspace};
+    const void *ps[] = {out->acc, out->y, out->q};
     for (const void *q : ps)
         if (q && (reinterpret_cast<uintptr_t>(q) & 15u)) return FLEXIQ_EALIGN;
     return FLEXIQ_OK;
@@ -320,7 +302,7 @@ extern "C" int flexiq_debug_force_tile(int index)
 // 2: blocks of that kernel resident per CU.
 extern "C" int flexiq_debug_last_launch(int which)
 {
-    return which == 0 ? g_last_shape : (which == 1 ? g_last_blocks : (which == 2 ? g_last_resident : g_last_splits));
+    return which == 0 ? g_last_shape : (which == 1 ? g_last_blocks : g_last_resident);
 }
 
 // Test / tuning hook for the number of blocks of a linear call: 0 = automatic (one resident wave of blocks,
@@ -338,19 +320,6 @@ extern "C" int flexiq_debug_force_packed4(int mode)
     if (mode < -1 || mode > 1) return FLEXIQ_EINVAL;
     g_force_packed = mode;
     return FLEXIQ_OK;
-}
-
-extern "C" int flexiq_debug_force_splits(int n)
-{
-    if (n < 0) return FLEXIQ_EINVAL;
-    g_force_splits = n;
-    return FLEXIQ_OK;
-}
-
-extern "C" int64_t flexiq_small_m_workspace_bytes(const flexiq_layer *L)
-{
-    if (!L || L->R != 1 || L->S != 1) return FLEXIQ_EINVAL;
-    return small_m_workspace_bytes(L);
 }
 
 extern "C" int flexiq_mixed_gemm(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream)
@@ -423,7 +392,6 @@ extern "C" int flexiq_mixed_conv_implicit(const flexiq_layer *L, const int8_t *X
             g_last_shape = -3;
             g_last_blocks = 0;
             g_last_resident = 0;
-            g_last_splits = 1;
             return FLEXIQ_OK;
         }
     }

@@ -1,4 +1,4 @@
-"""GPU parity of the split-K kernel for few-row calls (flexiq_out.workspace) against the CPU oracle, through the same
+"""GPU parity of the few-row kernel (linear calls with at most 64 rows) against the CPU oracle, through the same
 entry point as every other linear call: int32 accumulators bit-exact, fp32 within 1e-5, int8 codes by the float64
 definition with the tie window."""
 import numpy as np
@@ -21,78 +21,9 @@ def env():
     return torch, oracle, fq, torch.device("cuda:0")
 
 
-@pytest.mark.parametrize("K,N,gs", [(256, 256, 32), (1024, 520, 64), (192, 72, 32), (4096, 1024, 64), (64, 7, 32)])
-def test_small_m_split_k(env, K, N, gs):
-    torch, oracle, fq, dev = env
-    case = workloads.make_linear("smallm", 8, 500 + K + N, 64, K, N, gs, outlier_frac=0.02)
-    case.X *= 2.0                                    # some saturation in the lowering
-    ol, hl, x_scale = both_layers(case)
-    Xq_all = oracle.quantize(case.X, x_scale)[:, ol.perm]
-    ws = fq.flexiq_small_m_workspace(hl, dev)
-    G = K // gs
-    try:
-        for M in (1, 16, 33, 64):
-            Xq = np.ascontiguousarray(Xq_all[:M])
-            Xd = torch.from_numpy(Xq).to(dev)
-            for r in sorted({0.0, 1.0 / G, 0.5, 1.0}):
-                fq.flexiq_set_ratio(hl, r)
-                ref = oracle.forward_gemm(ol, Xq, r)
-                so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
-                for splits in (0, 1, 2, 3, 7, 13):   # automatic, none, a few (uneven slices included)
-                    fq.debug_force_splits(splits)
-                    out = fq.flexiq_mixed_gemm(hl, Xd, acc=True, y=True, q=True, out_scale=so, workspace=ws)
-                    torch.cuda.synchronize()
-                    launch = fq.debug_last_launch()
-                    if splits > 0:
-                        assert launch["tile"] == -1, launch         # the split-K kernel ran
-                    elif M <= 32 and K >= 2048 and N <= 4096:       # the automatic choice takes it where it pays
-                        assert launch["tile"] == -1 and launch["splits"] > 1, launch
-                    assert (out["acc"].cpu().numpy() == ref).all(), (M, r, splits, launch)
-                    check_y(out["y"].cpu().numpy(), ref, ol)
-                    got_q = out["q"].cpu().numpy()
-                    check_q(got_q, ref, ol, so)
-                    assert (got_q == requant_fp32_sequence(ref, ol, so)).all()
-                    assert int(ws[:131072].max().item()) == 0                 # tickets left at zero
-        # without a workspace, or for more rows, the tiled kernel serves the call
-        fq.debug_force_splits(0)
-        out = fq.flexiq_mixed_gemm(hl, Xd, acc=True)
-        assert fq.debug_last_launch()["tile"] >= 0 and (out["acc"].cpu().numpy() == ref).all()
-    finally:
-        fq.debug_force_splits(0)
-
-
-def test_small_m_prelowered_and_dynamic(env):
-    torch, oracle, fq, dev = env
-    case = workloads.make_linear("smallm_dyn", 8, 560, 48, 1024, 256, 32, outlier_frac=0.02)
-    case.X *= 0.4
-    ol, hl, x_scale = both_layers(case)
-    Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
-    Xd = torch.from_numpy(np.ascontiguousarray(Xq)).to(dev)
-    ws = fq.flexiq_small_m_workspace(hl, dev)
-    k4 = fq.flexiq_set_ratio(hl, 0.75)
-    G4 = k4 // 32
-    # run-time positions
-    fq.flexiq_dynamic_positions(hl, Xd)
-    dyn = oracle.dynamic_act_shifts(Xq, 32, G4, ol.a_shift)
-    fq.debug_force_splits(5)
-    got = fq.flexiq_mixed_gemm(hl, Xd, acc=True, workspace=ws)["acc"].cpu().numpy()
-    assert fq.debug_last_launch()["splits"] == 5
-    assert (got == oracle.mixed_gemm(Xq, ol.Wq.reshape(256, 1024), 32, G4, dyn, ol.w_shift)).all()
-    fq.flexiq_static_positions(hl)
-    # activations that arrive lowered
-    sh = np.repeat(ol.a_shift.astype(np.int32), 32)[None, :k4]
-    Xl = Xq.astype(np.int32).copy()
-    Xl[:, :k4] = np.clip(Xl[:, :k4] >> sh, -8, 7) << sh
-    fq.flexiq_input_prelowered(hl, True)
-    got = fq.flexiq_mixed_gemm(hl, torch.from_numpy(Xl.astype(np.int8)).to(dev), acc=True, workspace=ws)["acc"].cpu().numpy()
-    fq.flexiq_input_prelowered(hl, False)
-    fq.debug_force_splits(0)
-    assert (got == oracle.forward_gemm(ol, Xq, 0.75)).all()
-
-
 @pytest.mark.parametrize("K,N,gs", [(256, 256, 32), (1024, 520, 64), (192, 72, 32), (4096, 1024, 64), (64, 7, 32), (96, 30, 32), (2112, 48, 64)])
 def test_few_rows_kernel(env, K, N, gs):
-    # the few-row kernel that needs no workspace (a block per 16 output columns, its waves split the reduction and meet in LDS):
+    # the few-row kernel (a block per 16 output columns, its waves split the reduction and meet in LDS):
     # every fragment count (1 .. 64 rows), reductions with an odd unit count, a half 4-bit K-step, N below / not a multiple of 16
     torch, oracle, fq, dev = env
     case = workloads.make_linear("fewrows", 8, 700 + K + N, 64, K, N, gs, outlier_frac=0.02)

@@ -54,12 +54,15 @@ def test_linear_forced(env, M, K, N, gs, kernel):
             assert (only_q.cpu().numpy() == got_q).all(), r
             # the tiled kernel gives the same bytes
             fq.debug_force_stream(0)
+            fq.debug_force_few_rows(0)
             tiled = fq.flexiq_mixed_gemm(hl, Xd, q=True, out_scale=so)["q"]
             assert fq.debug_last_launch()["tile"] >= 0
+            fq.debug_force_few_rows(-1)
             fq.debug_force_stream(kernel)
             assert (tiled.cpu().numpy() == got_q).all(), r
     finally:
         fq.debug_force_stream(-1)
+        fq.debug_force_few_rows(-1)
 
 
 def test_run_time_positions_and_prelowered_input(env):
