@@ -29,8 +29,9 @@ int flexiq_debug_max_blocks(int n);
  * 2: blocks of that kernel resident per compute unit. */
 int flexiq_debug_last_launch(int which);
 
-/* The few-row kernel (linear calls with at most 64 rows; last launch: tile shape index -4):
- * 1 = take it whenever the call qualifies, 0 = never, -1 = automatic.  Returns whether the last call it was offered ran on it. */
+/* The few-row kernels (linear calls with at most 64 rows; last launch: tile shape index -4): 1 = the matrix-core kernel
+ * whenever the call qualifies, 2 = the dot-product kernel (at most 4 rows) whenever it qualifies, 0 = never, -1 = automatic.
+ * Returns which of them the last call they were offered ran on (0: neither). */
 int flexiq_debug_force_few_rows(int mode);
 
 /* The row-streaming kernels for layers with 64, 128 or 256 input channels (last launch: tile shape index -2):

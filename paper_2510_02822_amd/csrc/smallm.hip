@@ -80,11 +80,16 @@ struct RowsParams {
 
 constexpr int kRowCols = 16;   // output columns per block
 
-template <int MF>   // 16-row fragments of activations: M <= 16 MF
+// MF: 16-row fragments of activations (M <= 16 MF).  COOP (MF = 1, at most 8 rows, activations not lowered yet): the 4-bit
+// channels of the rows are lowered once per block into LDS instead of per lane in fragment layout.
+template <int MF, bool COOP>
 __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
 {
-    extern __shared__ __align__(16) unsigned char lds[];   // [waves][MF][64 lanes] accumulator quads
+    static_assert(!COOP || MF == 1, "the cooperative pass is for calls of a few rows");
+    extern __shared__ __align__(16) unsigned char lds[];   // [waves][MF][64 lanes] accumulator quads, then (COOP) the lowered rows
     v4i *const red = reinterpret_cast<v4i *>(lds);
+    const int xl_stride = 32 * p.units4 + 16;   // (+16: rows start in different banks)
+    unsigned char *const xl = lds + (blockDim.x >> 6) * MF * 1024;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = (int)(blockDim.x >> 6);
     const int c = lane & 15, qd = lane >> 4;   // row of the fragment (weight row / activation row), 16-channel quarter of the K-step
@@ -107,33 +112,63 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
     for (int f = 0; f < MF; ++f) acc[f] = (v4i){0, 0, 0, 0};
 
     constexpr int UN = MF <= 2 ? 4 : 2;   // K-steps in flight per wave
-    for (int ks0 = wave; ks0 < p.steps; ks0 += nw * UN) {
-        v4i w8[UN], x[UN][MF];
-        v2i w4[UN];
-        int sw[UN], sa[UN];
-        bool low[UN];
+    v4i w8[UN], x[UN][MF];
+    v2i w4[UN];
+    int sw[UN], sa[UN];
+    bool low[UN], valid[UN];
+    // weight fragments (and positions) of the K-steps ks0, ks0 + nw, ...: loads only
+    auto issue_w = [&](int ks0) {
 #pragma unroll
         for (int k = 0; k < UN; ++k) {
             const int ks = ks0 + k * nw;
             const int u = 2 * ks + (qd >> 1), h = qd & 1;   // this lane's unit and k-half
-            const bool valid = ks < p.steps && u < p.units;
-            low[k] = valid && u < p.units4;
+            valid[k] = ks < p.steps && u < p.units;
+            low[k] = valid[k] && u < p.units4;
             w8[k] = (v4i){0, 0, 0, 0};
             w4[k] = (v2i){0, 0};
             sw[k] = sa[k] = 0;
             if (low[k]) {
                 w4[k] = *reinterpret_cast<const v2i *>(p.W4 + ((int64_t)u * p.Npad + n) * 16 + 8 * h);
                 sw[k] = p.wshift[(int64_t)(u >> p.gs_shift) * p.Npad + n];
-                if (!p.x_pre) sa[k] = p.ashift[u >> p.gs_shift];
-            } else if (valid) {
+                if (!COOP && !p.x_pre) sa[k] = p.ashift[u >> p.gs_shift];
+            } else if (valid[k]) {
                 w8[k] = *reinterpret_cast<const v4i *>(p.W8 + (((int64_t)u * 2 + h) * p.Npad + n) * 16);
             }
+        }
+    };
+    // activation fragments of the same K-steps: from memory, or (COOP, 4-bit units) lowered already from LDS
+    auto issue_x = [&](int ks0) {
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            const int u = 2 * (ks0 + k * nw) + (qd >> 1), h = qd & 1;
 #pragma unroll
             for (int f = 0; f < MF; ++f) {
                 const int m = 16 * f + c;
-                x[k][f] = valid && m < p.M ? *reinterpret_cast<const v4i *>(p.X + (int64_t)m * p.C + u * 32 + 16 * h) : (v4i){0, 0, 0, 0};
+                if (COOP && low[k])
+                    x[k][f] = m < p.M ? *reinterpret_cast<const v4i *>(xl + m * xl_stride + u * 32 + 16 * h) : (v4i){0, 0, 0, 0};
+                else
+                    x[k][f] = valid[k] && m < p.M ? *reinterpret_cast<const v4i *>(p.X + (int64_t)m * p.C + u * 32 + 16 * h) : (v4i){0, 0, 0, 0};
             }
         }
+    };
+    int ks0 = wave;
+    issue_w(ks0);   // (a wave beyond the last K-step loads nothing and multiplies zeros once)
+    if constexpr (COOP) {
+        // few rows: in the fragment layout most lanes hold no row, and lowering there would cost every wave the full
+        // instruction count for a handful of values.  The block lowers the 4-bit channels of its rows once, every lane a
+        // 16-byte piece, into LDS, while the first weight fragments are on their way.
+        const int per_row = 2 * p.units4;   // pieces per row
+        for (int i = tid; i < p.M * per_row; i += (int)blockDim.x) {
+            const int m = i / per_row, j = i - m * per_row;
+            const v4i v = *reinterpret_cast<const v4i *>(p.X + (int64_t)m * p.C + 16 * j);
+            const int s_ = p.ashift[(j >> 1) >> p.gs_shift];
+            *reinterpret_cast<v4i *>(xl + m * xl_stride + 16 * j) =
+                (v4i){(int)lower4((uint32_t)v.x, s_), (int)lower4((uint32_t)v.y, s_), (int)lower4((uint32_t)v.z, s_), (int)lower4((uint32_t)v.w, s_)};
+        }
+        __syncthreads();
+    }
+    for (;;) {
+        issue_x(ks0);
 #pragma unroll
         for (int k = 0; k < UN; ++k) {
             v4i w = w8[k];
@@ -142,7 +177,7 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
                 // 8 e + 4 .. 8 e + 7 in the high halves; this lane holds dwords 2 h and 2 h + 1
                 w = (v4i){(int)expand4((uint32_t)w4[k].x << 4, sw[k]), (int)expand4((uint32_t)w4[k].x, sw[k]),
                           (int)expand4((uint32_t)w4[k].y << 4, sw[k]), (int)expand4((uint32_t)w4[k].y, sw[k])};
-                if (!p.x_pre) {
+                if (!COOP && !p.x_pre) {
 #pragma unroll
                     for (int f = 0; f < MF; ++f)
                         x[k][f] = (v4i){(int)lower4((uint32_t)x[k][f].x, sa[k]), (int)lower4((uint32_t)x[k][f].y, sa[k]),
@@ -152,6 +187,9 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
 #pragma unroll
             for (int f = 0; f < MF; ++f) acc[f] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w, x[k][f], acc[f], 0, 0, 0);
         }
+        ks0 += nw * UN;
+        if (ks0 >= p.steps) break;
+        issue_w(ks0);
     }
 
     // ---- the waves' sums meet in LDS
@@ -192,7 +230,144 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
     }
 }
 
-static int g_force_rows = -1;   // test hook: 1 = take k_few_rows whenever the call qualifies, 0 = never, -1 = automatic
+// ---- Calls of at most four rows: matrix-vector products on the vector ALU's integer dot instructions.
+//
+// With so few rows the matrix cores have nothing to reuse a weight fragment for, and their 16-column fragments tie the
+// block count to N / 16.  Here a lane multiplies a 16-channel piece of one weight row with the same piece of every
+// activation row: 8-bit units with `v_dot4_i32_i8` (four per piece and row), 4-bit units with `v_dot8_i32_i4` on the packed
+// codes as they are stored (two per piece and row; the sum of code products is put at its position afterwards,
+// sum << (activation position + weight position): Section 7's shifted accumulation, one `v_lshl_add_u32`).  This is the one
+// place on this chip where 4-bit groups cost fewer bytes AND fewer operations than 8-bit ones: nothing is expanded.
+// The activation codes of the 4-bit channels are produced once per block (clamp at the group's position, Section 4.1,
+// then two codes per byte in the order of the packed weights) and kept in LDS.  A block owns 8 output columns (a
+// wave load covers 8 columns x 8 pieces: 128-byte runs of the weight tiles) and the whole reduction; lanes of a
+// column meet by cross-lane adds, waves in LDS.
+constexpr int kVecCols = 8;
+
+template <int MR>   // activation rows (1 .. 4)
+__global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
+{
+    extern __shared__ __align__(16) unsigned char lds[];   // [waves][MR][8] wave sums, then [MR][units4][16] packed activation codes
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = (int)(blockDim.x >> 6);
+    int *const red = reinterpret_cast<int *>(lds);
+    unsigned char *const xl = lds + nw * MR * kVecCols * 4;
+    const int xl_stride = 16 * p.units4;
+    const int col = lane & 7, sub = lane >> 3;   // column of the block, piece of the wave load
+    const int n0 = blockIdx.x * kVecCols;
+    const int n = n0 + col;                      // < Npad: the weight tiles are padded
+    const int pieces = 2 * p.units;              // 16-channel pieces of the reduction
+    const int groups = (pieces + 7) >> 3;        // wave loads of 8 pieces
+
+    // the epilogue's scale and bias travel with the first operands (thread 8 m + col: row m, column n0 + col)
+    float cs_e = 0.f, bi_e = 0.f;
+    if (tid < MR * kVecCols) {
+        cs_e = p.cs[n0 + (tid & 7)];
+        bi_e = p.cs[p.Npad + n0 + (tid & 7)];
+    }
+    constexpr int UN = 4;   // wave loads in flight per wave
+    v4i w8[UN], x8[UN][MR];
+    v2i w4[UN];
+    int sh[UN], sa[UN];
+    bool low[UN], valid[UN];
+    auto issue = [&](int g0) {
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            const int j = 8 * (g0 + k * nw) + sub;   // this lane's piece: unit j / 2, half j % 2
+            const int u = j >> 1;
+            valid[k] = g0 + k * nw < groups && j < pieces;
+            low[k] = valid[k] && u < p.units4;
+            w8[k] = (v4i){0, 0, 0, 0};
+            w4[k] = (v2i){0, 0};
+            sh[k] = sa[k] = 0;
+            if (low[k]) {
+                w4[k] = *reinterpret_cast<const v2i *>(p.W4 + ((int64_t)u * p.Npad + n) * 16 + 8 * (j & 1));
+                sh[k] = p.wshift[(int64_t)(u >> p.gs_shift) * p.Npad + n];
+                sa[k] = p.ashift[u >> p.gs_shift];
+            } else if (valid[k]) {
+                w8[k] = *reinterpret_cast<const v4i *>(p.W8 + ((int64_t)j * p.Npad + n) * 16);
+#pragma unroll
+                for (int m = 0; m < MR; ++m)
+                    x8[k][m] = m < p.M ? *reinterpret_cast<const v4i *>(p.X + (int64_t)m * p.C + 16 * j) : (v4i){0, 0, 0, 0};
+            }
+        }
+    };
+    int g0 = wave;
+    issue(g0);   // (a wave beyond the last piece loads nothing)
+
+    // ---- activation codes of the 4-bit channels: every thread one 16-channel piece of one row at a time
+    {
+        const int per_row = 2 * p.units4;
+        for (int i = tid; i < p.M * per_row; i += (int)blockDim.x) {
+            const int m = i / per_row, j = i - m * per_row;
+            const v4i v = *reinterpret_cast<const v4i *>(p.X + (int64_t)m * p.C + 16 * j);
+            const int s_ = p.ashift[(j >> 1) >> p.gs_shift];
+            // lowered bytes are code << s with the low s bits clear, so a dword-wide shift right leaves the code's two's
+            // complement nibble at the bottom of every byte; dword e of a piece: channels 8 e .. 8 e + 3 in the low
+            // halves of its bytes, 8 e + 4 .. 8 e + 7 in the high halves (the order of the packed weight codes)
+            const uint32_t a = (lower4((uint32_t)v.x, s_) >> s_) & 0x0F0F0F0Fu, b = (lower4((uint32_t)v.y, s_) >> s_) & 0x0F0F0F0Fu;
+            const uint32_t c = (lower4((uint32_t)v.z, s_) >> s_) & 0x0F0F0F0Fu, d = (lower4((uint32_t)v.w, s_) >> s_) & 0x0F0F0F0Fu;
+            *reinterpret_cast<v2i *>(xl + m * xl_stride + 8 * j) = (v2i){(int)(a | (b << 4)), (int)(c | (d << 4))};
+        }
+        __syncthreads();
+    }
+
+    int acc[MR];
+#pragma unroll
+    for (int m = 0; m < MR; ++m) acc[m] = 0;
+    for (;;) {
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            const int j = 8 * (g0 + k * nw) + sub;
+            if (low[k]) {
+#pragma unroll
+                for (int m = 0; m < MR; ++m) {
+                    const v2i xc = m < p.M ? *reinterpret_cast<const v2i *>(xl + m * xl_stride + 8 * j) : (v2i){0, 0};
+                    int t = __builtin_amdgcn_sdot8(w4[k].x, xc.x, 0, false);
+                    t = __builtin_amdgcn_sdot8(w4[k].y, xc.y, t, false);
+                    acc[m] += (int)((uint32_t)t << (sh[k] + sa[k]));
+                }
+            } else if (valid[k]) {
+#pragma unroll
+                for (int m = 0; m < MR; ++m) {
+                    int t = __builtin_amdgcn_sdot4(w8[k].x, x8[k][m].x, acc[m], false);
+                    t = __builtin_amdgcn_sdot4(w8[k].y, x8[k][m].y, t, false);
+                    t = __builtin_amdgcn_sdot4(w8[k].z, x8[k][m].z, t, false);
+                    acc[m] = __builtin_amdgcn_sdot4(w8[k].w, x8[k][m].w, t, false);
+                }
+            }
+        }
+        g0 += nw * UN;
+        if (g0 >= groups) break;
+        issue(g0);
+    }
+
+    // ---- the eight lanes of a column, then the waves
+#pragma unroll
+    for (int m = 0; m < MR; ++m) {
+        acc[m] += __shfl_xor(acc[m], 8);
+        acc[m] += __shfl_xor(acc[m], 16);
+        acc[m] += __shfl_xor(acc[m], 32);
+        if (sub == 0) red[(wave * MR + m) * kVecCols + col] = acc[m];
+    }
+    __syncthreads();
+    if (tid >= MR * kVecCols) return;
+    const int m = tid >> 3, nn = n0 + (tid & 7);
+    if (m >= p.M || nn >= p.N) return;
+    int v = 0;
+    for (int w = 0; w < nw; ++w) v += red[(w * MR + m) * kVecCols + (tid & 7)];
+    const float c = cs_e, b = bi_e;
+    const int64_t o = (int64_t)m * p.N + nn;
+    if (p.acc) p.acc[o] = v;
+    if (p.y) p.y[o] = __builtin_fmaf((float)v, c, b);
+    if (p.q) {
+        // offset form, as in the tiled kernel: round to nearest-even, saturate to 0..255, flip the top bit
+        const float t = __builtin_fmaf((float)v, c * p.r_out, b * p.r_out + 128.0f);
+        p.q[o] = (int8_t)(__builtin_amdgcn_cvt_pk_u8_f32(t, 0, 0u) ^ 0x80u);
+    }
+}
+
+static int g_force_rows = -1;   // test hook: 1 / 2 = take k_few_rows / k_few_rows_dot whenever the call qualifies, 0 = never, -1 = automatic
 static int g_last_rows = 0;
 
 }  // namespace smallm
@@ -222,11 +397,31 @@ int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const fle
     p.x_pre = L->x_prelowered ? 1 : 0;
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.steps = (p.units + 1) / 2;
+    // one or two rows: the dot-product kernel (measured: ahead of the matrix-core kernel there, level at three rows, behind at four)
+    if (g_force_rows == 2 || (g_force_rows < 0 && M <= 2)) {
+        const int groups = (2 * p.units + 7) / 8;
+        const int nw = groups >= 32 ? 8 : 4;   // (eight waves for shorter reductions measured slower: 3.6 against 3.4 us on 4096 x 1024)
+        const size_t lds = (size_t)nw * M * kVecCols * 4 + (size_t)M * 16 * p.units4;
+        if (M <= 4 && lds <= 64 * 1024) {
+            void (*fn)(const RowsParams) = M == 1 ? k_few_rows_dot<1> : (M == 2 ? k_few_rows_dot<2> : (M == 3 ? k_few_rows_dot<3> : k_few_rows_dot<4>));
+            hipLaunchKernelGGL(fn, dim3((unsigned)((L->N + kVecCols - 1) / kVecCols)), dim3(64 * nw), lds, (hipStream_t)stream, p);
+            FLEXIQ_HIP(hipGetLastError());
+            *taken = 1;
+            g_last_rows = 2;
+            return FLEXIQ_OK;
+        }
+        if (g_force_rows == 2) return FLEXIQ_OK;
+    }
     const int mf = (int)((M + 15) / 16);
     const int nw = p.steps >= 12 ? 16 : (p.steps >= 6 ? 8 : 4);
     const unsigned blocks = (unsigned)((L->N + kRowCols - 1) / kRowCols);
-    const size_t lds = (size_t)nw * mf * 64 * 16;
-    void (*fn)(const RowsParams) = mf == 1 ? k_few_rows<1> : (mf == 2 ? k_few_rows<2> : (mf == 3 ? k_few_rows<3> : k_few_rows<4>));
+    size_t lds = (size_t)nw * mf * 64 * 16;
+    // few rows whose 4-bit channels the kernel lowers: once per block, through LDS
+    const size_t rows_bytes = (size_t)M * (32 * (size_t)p.units4 + 16);
+    const bool coop = M <= 8 && !p.x_pre && p.units4 > 0 && lds + rows_bytes <= 64 * 1024;
+    if (coop) lds += rows_bytes;
+    void (*fn)(const RowsParams) =
+        mf == 1 ? (coop ? k_few_rows<1, true> : k_few_rows<1, false>) : (mf == 2 ? k_few_rows<2, false> : (mf == 3 ? k_few_rows<3, false> : k_few_rows<4, false>));
     hipLaunchKernelGGL(fn, dim3(blocks), dim3(64 * nw), lds, (hipStream_t)stream, p);
     FLEXIQ_HIP(hipGetLastError());
     *taken = 1;
@@ -238,7 +433,7 @@ int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const fle
 
 extern "C" int flexiq_debug_force_few_rows(int mode)
 {
-    if (mode < -1 || mode > 1) return FLEXIQ_EINVAL;
+    if (mode < -1 || mode > 2) return FLEXIQ_EINVAL;
     flexiq::smallm::g_force_rows = mode;
     return flexiq::smallm::g_last_rows;
 }

@@ -22,18 +22,19 @@ def env():
 
 
 @pytest.mark.parametrize("K,N,gs", [(256, 256, 32), (1024, 520, 64), (192, 72, 32), (4096, 1024, 64), (64, 7, 32), (96, 30, 32), (2112, 48, 64)])
-def test_few_rows_kernel(env, K, N, gs):
-    # the few-row kernel (a block per 16 output columns, its waves split the reduction and meet in LDS):
-    # every fragment count (1 .. 64 rows), reductions with an odd unit count, a half 4-bit K-step, N below / not a multiple of 16
+@pytest.mark.parametrize("kernel", [1, 2])   # 1: matrix-core kernel (up to 64 rows); 2: dot-product kernel (up to 4 rows)
+def test_few_rows_kernel(env, K, N, gs, kernel):
+    # the few-row kernels (a block per 16 resp. 8 output columns, its waves split the reduction and meet in LDS): every
+    # fragment / row count, reductions with an odd unit count, a half 4-bit K-step, N below / not a multiple of 16
     torch, oracle, fq, dev = env
     case = workloads.make_linear("fewrows", 8, 700 + K + N, 64, K, N, gs, outlier_frac=0.02)
     case.X *= 2.0                                    # some saturation in the lowering
     ol, hl, x_scale = both_layers(case)
     Xq_all = oracle.quantize(case.X, x_scale)[:, ol.perm]
     G = K // gs
-    fq.debug_force_few_rows(1)
+    fq.debug_force_few_rows(kernel)
     try:
-        for M in (1, 7, 16, 17, 33, 48, 64):
+        for M in ((1, 7, 16, 17, 33, 48, 64) if kernel == 1 else (1, 2, 3, 4)):
             Xq = np.ascontiguousarray(Xq_all[:M])
             Xd = torch.from_numpy(Xq).to(dev)
             for r in sorted({0.0, 1.0 / G, 0.5, 1.0}):
@@ -42,7 +43,7 @@ def test_few_rows_kernel(env, K, N, gs):
                 so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
                 out = fq.flexiq_mixed_gemm(hl, Xd, acc=True, y=True, q=True, out_scale=so)
                 torch.cuda.synchronize()
-                assert fq.debug_force_few_rows(1) == 1 and fq.debug_last_launch()["tile"] == -4   # ran on this kernel
+                assert fq.debug_force_few_rows(kernel) == kernel and fq.debug_last_launch()["tile"] == -4   # ran on this kernel
                 assert (out["acc"].cpu().numpy() == ref).all(), (M, r)
                 check_y(out["y"].cpu().numpy(), ref, ol)
                 got_q = out["q"].cpu().numpy()
@@ -58,16 +59,17 @@ def test_few_rows_kernel(env, K, N, gs):
         fq.debug_force_few_rows(-1)
 
 
-def test_few_rows_prelowered_and_dynamic(env):
+@pytest.mark.parametrize("kernel,M", [(1, 48), (1, 5), (2, 3)])
+def test_few_rows_prelowered_and_dynamic(env, kernel, M):
     torch, oracle, fq, dev = env
-    case = workloads.make_linear("fewrows_dyn", 8, 760, 48, 1024, 256, 32, outlier_frac=0.02)
+    case = workloads.make_linear("fewrows_dyn", 8, 760, M, 1024, 256, 32, outlier_frac=0.02)
     case.X *= 0.4
     ol, hl, x_scale = both_layers(case)
     Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
     Xd = torch.from_numpy(np.ascontiguousarray(Xq)).to(dev)
     k4 = fq.flexiq_set_ratio(hl, 0.75)
     G4 = k4 // 32
-    fq.debug_force_few_rows(1)
+    fq.debug_force_few_rows(kernel)
     try:
         fq.flexiq_dynamic_positions(hl, Xd)      # run-time positions
         dyn = oracle.dynamic_act_shifts(Xq, 32, G4, ol.a_shift)
