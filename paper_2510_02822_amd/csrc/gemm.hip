@@ -235,7 +235,7 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
         if (rc != FLEXIQ_OK) return rc;
         if (taken) {
             g_last_shape = -4;
-            g_last_blocks = (L->N + 15) / 16;
+            g_last_blocks = taken == 2 ? (L->N + 7) / 8 : (L->N + 15) / 16;
             g_last_resident = 0;
             return FLEXIQ_OK;
         }

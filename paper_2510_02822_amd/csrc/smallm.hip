@@ -372,7 +372,8 @@ static int g_last_rows = 0;
 
 }  // namespace smallm
 
-// Launches k_few_rows for a linear call with at most 64 rows; *taken = 0: the call was left to the other kernels.
+// Launches k_few_rows (*taken = 1) or k_few_rows_dot (*taken = 2) for a linear call with at most 64 rows; *taken = 0: the call
+// was left to the other kernels.
 int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken)
 {
     using namespace smallm;
@@ -406,7 +407,7 @@ int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const fle
             void (*fn)(const RowsParams) = M == 1 ? k_few_rows_dot<1> : (M == 2 ? k_few_rows_dot<2> : (M == 3 ? k_few_rows_dot<3> : k_few_rows_dot<4>));
             hipLaunchKernelGGL(fn, dim3((unsigned)((L->N + kVecCols - 1) / kVecCols)), dim3(64 * nw), lds, (hipStream_t)stream, p);
             FLEXIQ_HIP(hipGetLastError());
-            *taken = 1;
+            *taken = 2;
             g_last_rows = 2;
             return FLEXIQ_OK;
         }
