@@ -420,7 +420,8 @@ def debug_force_stream(mode: int) -> int:
 
 def debug_force_few_rows(mode: int) -> int:
     """Few-row kernels: 1 / 2 = the matrix-core kernel / the dot-product kernel (at most 4 rows) whenever the call qualifies,
-    0 = never, -1 = automatic.  Returns which of them the last call they were offered ran on (0: neither)."""
+    14 = the dot-product kernel with 4 column groups per block, 0 = never, -1 = automatic.  Returns which of them the
+    last call they were offered ran on (0: neither)."""
     rc = load().flexiq_debug_force_few_rows(int(mode))
     if rc < 0:
         _check(rc)

@@ -244,31 +244,35 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
 // column meet by cross-lane adds, waves in LDS.
 constexpr int kVecCols = 8;
 
-template <int MR>   // activation rows (1 .. 4)
+// MR: activation rows (1 .. 4).  CG: groups of 8 columns per block (1 or 4; a lane then holds a piece of CG weight rows per
+// activation piece: more bytes in flight per wave, activation pieces and the block's set-up shared by more columns; for
+// layers with enough columns to still give every compute unit several blocks).
+template <int MR, int CG>
 __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
 {
-    extern __shared__ __align__(16) unsigned char lds[];   // [waves][MR][8] wave sums, then [MR][units4][16] packed activation codes
+    extern __shared__ __align__(16) unsigned char lds[];   // [waves][MR][8 CG] wave sums, then [MR][units4][16] packed activation codes
+    constexpr int BC = kVecCols * CG;   // columns per block
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = (int)(blockDim.x >> 6);
     int *const red = reinterpret_cast<int *>(lds);
-    unsigned char *const xl = lds + nw * MR * kVecCols * 4;
+    unsigned char *const xl = lds + nw * MR * BC * 4;
     const int xl_stride = 16 * p.units4;
-    const int col = lane & 7, sub = lane >> 3;   // column of the block, piece of the wave load
-    const int n0 = blockIdx.x * kVecCols;
-    const int n = n0 + col;                      // < Npad: the weight tiles are padded
+    const int col = lane & 7, sub = lane >> 3;   // column of a group, piece of the wave load
+    const int n0 = blockIdx.x * BC;
+    const int n = n0 + col;                      // + 8 c for column group c; < Npad (checked by the launcher)
     const int pieces = 2 * p.units;              // 16-channel pieces of the reduction
     const int groups = (pieces + 7) >> 3;        // wave loads of 8 pieces
 
-    // the epilogue's scale and bias travel with the first operands (thread 8 m + col: row m, column n0 + col)
+    // the epilogue's scale and bias travel with the first operands (thread BC m + j: row m, column n0 + j)
     float cs_e = 0.f, bi_e = 0.f;
-    if (tid < MR * kVecCols) {
-        cs_e = p.cs[n0 + (tid & 7)];
-        bi_e = p.cs[p.Npad + n0 + (tid & 7)];
+    if (tid < MR * BC) {
+        cs_e = p.cs[n0 + tid % BC];
+        bi_e = p.cs[p.Npad + n0 + tid % BC];
     }
-    constexpr int UN = 4;   // wave loads in flight per wave
-    v4i w8[UN], x8[UN][MR];
-    v2i w4[UN];
-    int sh[UN], sa[UN];
+    constexpr int UN = CG == 4 ? 2 : 4;   // wave loads in flight per wave and column group
+    v4i w8[UN][CG], x8[UN][MR];
+    v2i w4[UN][CG];
+    int sh[UN][CG], sa[UN];
     bool low[UN], valid[UN];
     auto issue = [&](int g0) {
 #pragma unroll
@@ -277,15 +281,23 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
             const int u = j >> 1;
             valid[k] = g0 + k * nw < groups && j < pieces;
             low[k] = valid[k] && u < p.units4;
-            w8[k] = (v4i){0, 0, 0, 0};
-            w4[k] = (v2i){0, 0};
-            sh[k] = sa[k] = 0;
+            sa[k] = 0;
+#pragma unroll
+            for (int c = 0; c < CG; ++c) {
+                w8[k][c] = (v4i){0, 0, 0, 0};
+                w4[k][c] = (v2i){0, 0};
+                sh[k][c] = 0;
+            }
             if (low[k]) {
-                w4[k] = *reinterpret_cast<const v2i *>(p.W4 + ((int64_t)u * p.Npad + n) * 16 + 8 * (j & 1));
-                sh[k] = p.wshift[(int64_t)(u >> p.gs_shift) * p.Npad + n];
+#pragma unroll
+                for (int c = 0; c < CG; ++c) {
+                    w4[k][c] = *reinterpret_cast<const v2i *>(p.W4 + ((int64_t)u * p.Npad + n + 8 * c) * 16 + 8 * (j & 1));
+                    sh[k][c] = p.wshift[(int64_t)(u >> p.gs_shift) * p.Npad + n + 8 * c];
+                }
                 sa[k] = p.ashift[u >> p.gs_shift];
             } else if (valid[k]) {
-                w8[k] = *reinterpret_cast<const v4i *>(p.W8 + ((int64_t)j * p.Npad + n) * 16);
+#pragma unroll
+                for (int c = 0; c < CG; ++c) w8[k][c] = *reinterpret_cast<const v4i *>(p.W8 + ((int64_t)j * p.Npad + n + 8 * c) * 16);
 #pragma unroll
                 for (int m = 0; m < MR; ++m)
                     x8[k][m] = m < p.M ? *reinterpret_cast<const v4i *>(p.X + (int64_t)m * p.C + 16 * j) : (v4i){0, 0, 0, 0};
@@ -312,9 +324,11 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
         __syncthreads();
     }
 
-    int acc[MR];
+    int acc[MR][CG];
 #pragma unroll
-    for (int m = 0; m < MR; ++m) acc[m] = 0;
+    for (int m = 0; m < MR; ++m)
+#pragma unroll
+        for (int c = 0; c < CG; ++c) acc[m][c] = 0;
     for (;;) {
 #pragma unroll
         for (int k = 0; k < UN; ++k) {
@@ -323,18 +337,23 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
 #pragma unroll
                 for (int m = 0; m < MR; ++m) {
                     const v2i xc = m < p.M ? *reinterpret_cast<const v2i *>(xl + m * xl_stride + 8 * j) : (v2i){0, 0};
-                    int t = __builtin_amdgcn_sdot8(w4[k].x, xc.x, 0, false);
-                    t = __builtin_amdgcn_sdot8(w4[k].y, xc.y, t, false);
-                    acc[m] += (int)((uint32_t)t << (sh[k] + sa[k]));
+#pragma unroll
+                    for (int c = 0; c < CG; ++c) {
+                        int t = __builtin_amdgcn_sdot8(w4[k][c].x, xc.x, 0, false);
+                        t = __builtin_amdgcn_sdot8(w4[k][c].y, xc.y, t, false);
+                        acc[m][c] += (int)((uint32_t)t << (sh[k][c] + sa[k]));
+                    }
                 }
             } else if (valid[k]) {
 #pragma unroll
-                for (int m = 0; m < MR; ++m) {
-                    int t = __builtin_amdgcn_sdot4(w8[k].x, x8[k][m].x, acc[m], false);
-                    t = __builtin_amdgcn_sdot4(w8[k].y, x8[k][m].y, t, false);
-                    t = __builtin_amdgcn_sdot4(w8[k].z, x8[k][m].z, t, false);
-                    acc[m] = __builtin_amdgcn_sdot4(w8[k].w, x8[k][m].w, t, false);
-                }
+                for (int m = 0; m < MR; ++m)
+#pragma unroll
+                    for (int c = 0; c < CG; ++c) {
+                        int t = __builtin_amdgcn_sdot4(w8[k][c].x, x8[k][m].x, acc[m][c], false);
+                        t = __builtin_amdgcn_sdot4(w8[k][c].y, x8[k][m].y, t, false);
+                        t = __builtin_amdgcn_sdot4(w8[k][c].z, x8[k][m].z, t, false);
+                        acc[m][c] = __builtin_amdgcn_sdot4(w8[k][c].w, x8[k][m].w, t, false);
+                    }
             }
         }
         g0 += nw * UN;
@@ -344,18 +363,21 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
 
     // ---- the eight lanes of a column, then the waves
 #pragma unroll
-    for (int m = 0; m < MR; ++m) {
-        acc[m] += __shfl_xor(acc[m], 8);
-        acc[m] += __shfl_xor(acc[m], 16);
-        acc[m] += __shfl_xor(acc[m], 32);
-        if (sub == 0) red[(wave * MR + m) * kVecCols + col] = acc[m];
-    }
+    for (int m = 0; m < MR; ++m)
+#pragma unroll
+        for (int c = 0; c < CG; ++c) {
+            int a = acc[m][c];
+            a += __shfl_xor(a, 8);
+            a += __shfl_xor(a, 16);
+            a += __shfl_xor(a, 32);
+            if (sub == 0) red[(wave * MR + m) * BC + 8 * c + col] = a;
+        }
     __syncthreads();
-    if (tid >= MR * kVecCols) return;
-    const int m = tid >> 3, nn = n0 + (tid & 7);
+    if (tid >= MR * BC) return;
+    const int m = tid / BC, jn = tid % BC, nn = n0 + jn;
     if (m >= p.M || nn >= p.N) return;
     int v = 0;
-    for (int w = 0; w < nw; ++w) v += red[(w * MR + m) * kVecCols + (tid & 7)];
+    for (int w = 0; w < nw; ++w) v += red[(w * MR + m) * BC + jn];
     const float c = cs_e, b = bi_e;
     const int64_t o = (int64_t)m * p.N + nn;
     if (p.acc) p.acc[o] = v;
@@ -367,6 +389,7 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
     }
 }
 
+static int g_force_cg = 0;      // test hook: column groups per block of k_few_rows_dot (0 = automatic)
 static int g_force_rows = -1;   // test hook: 1 / 2 = take k_few_rows / k_few_rows_dot whenever the call qualifies, 0 = never, -1 = automatic
 static int g_last_rows = 0;
 
@@ -402,10 +425,19 @@ int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const fle
     if (g_force_rows == 2 || (g_force_rows < 0 && M <= 2)) {
         const int groups = (2 * p.units + 7) / 8;
         const int nw = groups >= 32 ? 8 : 4;   // (eight waves for shorter reductions measured slower: 3.6 against 3.4 us on 4096 x 1024)
-        const size_t lds = (size_t)nw * M * kVecCols * 4 + (size_t)M * 16 * p.units4;
+        // column groups per block: four where the layer still gives every compute unit several blocks (measured on 16384 x 4096
+        // and 8192 x 8192 weights, one row, r = 0 / 1: 12.0 / 8.4 us and 12.0 / 9.3 us against 12.1 / 14.4 and 12.9 / 13.1 us with one
+        // group; ViT-L sizes are faster with one); the last block's columns must stay inside the padded weight tiles
+        const int ncg = (L->N + kVecCols - 1) / kVecCols;
+        int cg = M > 2 ? 1 : (g_force_cg > 0 ? g_force_cg : (ncg >= 4 * num_cu ? 4 : 1));
+        if (((ncg + cg - 1) / cg) * cg * kVecCols > L->Npad) cg = 1;
+        const size_t lds = (size_t)nw * M * kVecCols * cg * 4 + (size_t)M * 16 * p.units4;
         if (M <= 4 && lds <= 64 * 1024) {
-            void (*fn)(const RowsParams) = M == 1 ? k_few_rows_dot<1> : (M == 2 ? k_few_rows_dot<2> : (M == 3 ? k_few_rows_dot<3> : k_few_rows_dot<4>));
-            hipLaunchKernelGGL(fn, dim3((unsigned)((L->N + kVecCols - 1) / kVecCols)), dim3(64 * nw), lds, (hipStream_t)stream, p);
+            void (*fn)(const RowsParams) = nullptr;
+            if (M == 1) fn = cg == 4 ? k_few_rows_dot<1, 4> : k_few_rows_dot<1, 1>;
+            else if (M == 2) fn = cg == 4 ? k_few_rows_dot<2, 4> : k_few_rows_dot<2, 1>;
+            else fn = M == 3 ? k_few_rows_dot<3, 1> : k_few_rows_dot<4, 1>;
+            hipLaunchKernelGGL(fn, dim3((unsigned)((ncg + cg - 1) / cg)), dim3(64 * nw), lds, (hipStream_t)stream, p);
             FLEXIQ_HIP(hipGetLastError());
             *taken = 2;
             g_last_rows = 2;
@@ -434,6 +466,13 @@ int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const fle
 
 extern "C" int flexiq_debug_force_few_rows(int mode)
 {
+    // (mode 14: the dot-product kernel with 4 column groups per block where rows and padding allow)
+    if (mode == 14) {
+        flexiq::smallm::g_force_cg = 4;
+        mode = 2;
+    } else {
+        flexiq::smallm::g_force_cg = 0;
+    }
     if (mode < -1 || mode > 2) return FLEXIQ_EINVAL;
     flexiq::smallm::g_force_rows = mode;
     return flexiq::smallm::g_last_rows;
