@@ -414,7 +414,7 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
     return out
 
 
-PROFILE_TARGETS = ("vitl_fc2", "vitl_fc2_fp6", "vitl_fc2_rows16", "vitl_fc2_rows1", "reorder", "resnet_1x1_64_256", "resnet_3x3_64_64",
+PROFILE_TARGETS = ("vitl_fc2", "vitl_fc2_fp6", "vitl_fc2_rows16", "vitl_fc2_rows1", "stream_rows1", "reorder", "resnet_1x1_64_256", "resnet_3x3_64_64",
                    "resnet_1x1_256_64", "resnet_1x1_256_64_packed4")
 
 
@@ -435,18 +435,20 @@ def profile_only(torch, fq, workloads, dev, what, launches):
             Xq = Xq.reshape(-1, case.C)
             q = {"q": q["q"].reshape(-1, case.N)}
     else:
-        case = workloads.config3("fc2")
+        # (stream_rows1: the weight-streaming workload of `shapes`, one row against 16384 x 4096 weights)
+        case = workloads.make_linear("stream_16384x4096", 9, 16384 + 4096, 2, 4096, 16384, 64, outlier_frac=0.02) if what == "stream_rows1" \
+            else workloads.config3("fc2")
         x_scale, amax = _calib(case)
         layer = fq.flexiq_quantize_pack(case.W, amax, x_scale, case.group_size, bias=case.bias)
         Xn = fq.flexiq_quantize_act(torch.from_numpy(case.X).to(dev), x_scale)
         Xq = fq.flexiq_permute_channels(layer, Xn)
-        rows = {"vitl_fc2_rows16": 16, "vitl_fc2_rows1": 1}.get(what, case.M)
+        rows = {"vitl_fc2_rows16": 16, "vitl_fc2_rows1": 1, "stream_rows1": 1}.get(what, case.M)
         Xs = Xq[:rows].contiguous()
         q = {"q": torch.empty((rows, case.N), dtype=torch.int8, device=dev)}
         res["workload"] = "%s M=%d K=%d N=%d gs=%d" % (case.name, rows, case.K, case.N, case.group_size)
         if what == "vitl_fc2":
             call = lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=0.05, bufs=q)
-        elif what in ("vitl_fc2_rows16", "vitl_fc2_rows1"):   # few-row calls: the matrix-core resp. the dot-product kernel
+        elif what in ("vitl_fc2_rows16", "vitl_fc2_rows1", "stream_rows1"):   # few-row calls: the matrix-core resp. the dot-product kernel
             call = lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=0.05, bufs=q)
         elif what == "reorder":
             call = lambda: fq.flexiq_permute_channels(layer, Xn)
