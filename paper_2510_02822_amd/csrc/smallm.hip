@@ -250,13 +250,15 @@ constexpr int kVecCols = 8;
 template <int MR, int CG>
 __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
 {
-    extern __shared__ __align__(16) unsigned char lds[];   // [waves][MR][8 CG] wave sums, then [MR][units4][16] packed activation codes
+    // LDS: [waves][MR][8 CG] wave sums, then [MR][units4][16] packed activation codes, then [MR][C] the activation rows
+    extern __shared__ __align__(16) unsigned char lds[];
     constexpr int BC = kVecCols * CG;   // columns per block
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = (int)(blockDim.x >> 6);
     int *const red = reinterpret_cast<int *>(lds);
     unsigned char *const xl = lds + nw * MR * BC * 4;
     const int xl_stride = 16 * p.units4;
+    unsigned char *const xr = xl + MR * xl_stride;   // (8-bit channels only are read from here)
     const int col = lane & 7, sub = lane >> 3;   // column of a group, piece of the wave load
     const int n0 = blockIdx.x * BC;
     const int n = n0 + col;                      // + 8 c for column group c; < Npad (checked by the launcher)
@@ -270,7 +272,7 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
         bi_e = p.cs[p.Npad + n0 + tid % BC];
     }
     constexpr int UN = CG == 4 ? 2 : 4;   // wave loads in flight per wave and column group
-    v4i w8[UN][CG], x8[UN][MR];
+    v4i w8[UN][CG];
     v2i w4[UN][CG];
     int sh[UN][CG], sa[UN];
     bool low[UN], valid[UN];
@@ -298,18 +300,21 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
             } else if (valid[k]) {
 #pragma unroll
                 for (int c = 0; c < CG; ++c) w8[k][c] = *reinterpret_cast<const v4i *>(p.W8 + ((int64_t)j * p.Npad + n + 8 * c) * 16);
-#pragma unroll
-                for (int m = 0; m < MR; ++m)
-                    x8[k][m] = m < p.M ? *reinterpret_cast<const v4i *>(p.X + (int64_t)m * p.C + 16 * j) : (v4i){0, 0, 0, 0};
             }
         }
     };
     int g0 = wave;
     issue(g0);   // (a wave beyond the last piece loads nothing)
 
-    // ---- activation codes of the 4-bit channels: every thread one 16-channel piece of one row at a time
+    // ---- the activation rows go to LDS once per block (the eight columns of a wave load read the same pieces: a broadcast
+    // there, a trip through the vector memory path per lane otherwise); every thread one 16-channel piece of one row at a
+    // time: 8-bit channels as they are, 4-bit channels as codes
     {
-        const int per_row = 2 * p.units4;
+        const int per_row = 2 * p.units4, all_per_row = 2 * p.units;
+        for (int i = tid; i < p.M * (all_per_row - per_row); i += (int)blockDim.x) {
+            const int m = i / (all_per_row - per_row), j = per_row + i - m * (all_per_row - per_row);
+            *reinterpret_cast<v4i *>(xr + m * p.C + 16 * j) = *reinterpret_cast<const v4i *>(p.X + (int64_t)m * p.C + 16 * j);
+        }
         for (int i = tid; i < p.M * per_row; i += (int)blockDim.x) {
             const int m = i / per_row, j = i - m * per_row;
             const v4i v = *reinterpret_cast<const v4i *>(p.X + (int64_t)m * p.C + 16 * j);
@@ -346,14 +351,16 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
                 }
             } else if (valid[k]) {
 #pragma unroll
-                for (int m = 0; m < MR; ++m)
+                for (int m = 0; m < MR; ++m) {
+                    const v4i xv = m < p.M ? *reinterpret_cast<const v4i *>(xr + m * p.C + 16 * j) : (v4i){0, 0, 0, 0};
 #pragma unroll
                     for (int c = 0; c < CG; ++c) {
-                        int t = __builtin_amdgcn_sdot4(w8[k][c].x, x8[k][m].x, acc[m][c], false);
-                        t = __builtin_amdgcn_sdot4(w8[k][c].y, x8[k][m].y, t, false);
-                        t = __builtin_amdgcn_sdot4(w8[k][c].z, x8[k][m].z, t, false);
-                        acc[m][c] = __builtin_amdgcn_sdot4(w8[k][c].w, x8[k][m].w, t, false);
+                        int t = __builtin_amdgcn_sdot4(w8[k][c].x, xv.x, acc[m][c], false);
+                        t = __builtin_amdgcn_sdot4(w8[k][c].y, xv.y, t, false);
+                        t = __builtin_amdgcn_sdot4(w8[k][c].z, xv.z, t, false);
+                        acc[m][c] = __builtin_amdgcn_sdot4(w8[k][c].w, xv.w, t, false);
                     }
+                }
             }
         }
         g0 += nw * UN;
@@ -421,22 +428,28 @@ int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const fle
     p.x_pre = L->x_prelowered ? 1 : 0;
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.steps = (p.units + 1) / 2;
-    // one or two rows: the dot-product kernel (measured: ahead of the matrix-core kernel there, level at three rows, behind at four)
-    if (g_force_rows == 2 || (g_force_rows < 0 && M <= 2)) {
+    // One or two rows: the dot-product kernel.  Three or four rows: where the layer has columns enough for four column groups per
+    // block (measured on 16384 x 4096 weights, r = 0 / 1: 13.7 / 10.2 us at three and 14.7 / 11.7 us at four rows against 15.6 / 18.1 and
+    // 16.0 / 18.7 us on the matrix-core kernel; at ViT-L sizes the matrix-core kernel is ahead from three rows on).
+    const int ncg = (L->N + kVecCols - 1) / kVecCols;
+    const bool wide = ncg >= 4 * num_cu && (ncg + 3) / 4 * 4 * kVecCols <= L->Npad;
+    if (g_force_rows == 2 || (g_force_rows < 0 && (M <= 2 || (M <= 4 && wide)))) {
         const int groups = (2 * p.units + 7) / 8;
         const int nw = groups >= 32 ? 8 : 4;   // (eight waves for shorter reductions measured slower: 3.6 against 3.4 us on 4096 x 1024)
         // column groups per block: four where the layer still gives every compute unit several blocks (measured on 16384 x 4096
-        // and 8192 x 8192 weights, one row, r = 0 / 1: 12.0 / 8.4 us and 12.0 / 9.3 us against 12.1 / 14.4 and 12.9 / 13.1 us with one
+        // and 8192 x 8192 weights, one row, r = 0 / 1: 12.0 / 7.9 us and 12.0 / 9.3 us against 12.1 / 14.4 and 12.9 / 13.1 us with one
         // group; ViT-L sizes are faster with one); the last block's columns must stay inside the padded weight tiles
-        const int ncg = (L->N + kVecCols - 1) / kVecCols;
-        int cg = M > 2 ? 1 : (g_force_cg > 0 ? g_force_cg : (ncg >= 4 * num_cu ? 4 : 1));
+        int cg = g_force_cg > 0 ? g_force_cg : (wide ? 4 : 1);
         if (((ncg + cg - 1) / cg) * cg * kVecCols > L->Npad) cg = 1;
-        const size_t lds = (size_t)nw * M * kVecCols * cg * 4 + (size_t)M * 16 * p.units4;
+        const size_t lds = (size_t)nw * M * kVecCols * cg * 4 + (size_t)M * 16 * p.units4 + (size_t)M * L->C;
         if (M <= 4 && lds <= 64 * 1024) {
             void (*fn)(const RowsParams) = nullptr;
-            if (M == 1) fn = cg == 4 ? k_few_rows_dot<1, 4> : k_few_rows_dot<1, 1>;
-            else if (M == 2) fn = cg == 4 ? k_few_rows_dot<2, 4> : k_few_rows_dot<2, 1>;
-            else fn = M == 3 ? k_few_rows_dot<3, 1> : k_few_rows_dot<4, 1>;
+            switch ((int)M) {
+            case 1: fn = cg == 4 ? k_few_rows_dot<1, 4> : k_few_rows_dot<1, 1>; break;
+            case 2: fn = cg == 4 ? k_few_rows_dot<2, 4> : k_few_rows_dot<2, 1>; break;
+            case 3: fn = cg == 4 ? k_few_rows_dot<3, 4> : k_few_rows_dot<3, 1>; break;
+            default: fn = cg == 4 ? k_few_rows_dot<4, 4> : k_few_rows_dot<4, 1>; break;
+            }
             hipLaunchKernelGGL(fn, dim3((unsigned)((ncg + cg - 1) / cg)), dim3(64 * nw), lds, (hipStream_t)stream, p);
             FLEXIQ_HIP(hipGetLastError());
             *taken = 2;

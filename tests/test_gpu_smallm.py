@@ -35,7 +35,7 @@ def test_few_rows_kernel(env, K, N, gs, kernel):
     G = K // gs
     fq.debug_force_few_rows(kernel)
     try:
-        for M in ((1, 7, 16, 17, 33, 48, 64) if kernel == 1 else ((1, 2, 3, 4) if kernel == 2 else (1, 2))):
+        for M in ((1, 7, 16, 17, 33, 48, 64) if kernel == 1 else ((1, 2, 3, 4) if kernel == 2 else (1, 2, 4))):
             Xq = np.ascontiguousarray(Xq_all[:M])
             Xd = torch.from_numpy(Xq).to(dev)
             for r in sorted({0.0, 1.0 / G, 0.5, 1.0}):
