@@ -257,19 +257,19 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
     # ---- the weight-streaming regime proper: one activation row against a 16384 x 4096 weight matrix (67 MB as int8, group
     # size 64), where the call is HBM-bound at r = 0 and 4-bit groups move half the bytes (dot-product kernel: v_dot8_i32_i4
     # on the packed codes); seeded like the other linear layers
-    case = workloads.make_linear("stream_16384x4096", 9, 16384 + 4096, 4, 4096, 16384, 64, outlier_frac=0.02)
+    case = workloads.make_linear("stream_16384x4096", 9, 16384 + 4096, 16, 4096, 16384, 64, outlier_frac=0.02)
     x_scale, amax = _calib(case)
     layer = fq.flexiq_quantize_pack(case.W, amax, x_scale, 64, bias=case.bias)
     Xq = fq.flexiq_permute_channels(layer, fq.flexiq_quantize_act(torch.from_numpy(case.X).to(dev), x_scale))
     fq.flexiq_set_ratio(layer, 0.0)
     so = float(fq.flexiq_mixed_gemm(layer, Xq, y=True)["y"].abs().max().item() / 127.0)
-    for Ms in (1, 2, 4):
+    for Ms in (1, 2, 4, 16):
         Xs = Xq[:Ms].contiguous()
         bufs = {"q": torch.empty((Ms, case.N), dtype=torch.int8, device=dev)}
         for r in ((0.0, 0.25, 0.5, 0.75, 1.0) if Ms == 1 else (0.0, 0.5, 1.0)):
             fq.flexiq_set_ratio(layer, r)
             us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=so, bufs=bufs), 20)
-            rec("weight streaming: 16384 x 4096 weights, M=%d rows" % Ms, "few-row kernel (automatic route)", r, us,
+            rec("weight streaming: 16384 x 4096 weights, M=%d rows" % Ms, "few-row kernels (automatic route)", r, us,
                 byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, "w4"), launch=fq.debug_last_launch())
     del layer, Xq, case
 

@@ -429,11 +429,12 @@ int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const fle
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.steps = (p.units + 1) / 2;
     // One or two rows: the dot-product kernel.  Three or four rows: where the layer has columns enough for four column groups per
-    // block (measured on 16384 x 4096 weights, r = 0 / 1: 13.7 / 10.2 us at three and 14.7 / 11.7 us at four rows against 15.6 / 18.1 and
-    // 16.0 / 18.7 us on the matrix-core kernel; at ViT-L sizes the matrix-core kernel is ahead from three rows on).
+    // block and at least half of the channels run at 4 bits (measured on 16384 x 4096 weights at four rows, r = 0 / 0.5 / 1: 14.7 / 13.1 /
+    // 11.6 us against 13.1 / 12.9 / 14.4 us on the matrix-core kernel; from six rows on it is bound by its vector-ALU work, 22 us; at
+    // ViT-L sizes the matrix-core kernel is ahead from three rows on).
     const int ncg = (L->N + kVecCols - 1) / kVecCols;
     const bool wide = ncg >= 4 * num_cu && (ncg + 3) / 4 * 4 * kVecCols <= L->Npad;
-    if (g_force_rows == 2 || (g_force_rows < 0 && (M <= 2 || (M <= 4 && wide)))) {
+    if (g_force_rows == 2 || (g_force_rows < 0 && (M <= 2 || (M <= 4 && wide && 2 * L->max_4bit_ch >= L->C)))) {
         const int groups = (2 * p.units + 7) / 8;
         const int nw = groups >= 32 ? 8 : 4;   // (eight waves for shorter reductions measured slower: 3.6 against 3.4 us on 4096 x 1024)
         // column groups per block: four where the layer still gives every compute unit several blocks (measured on 16384 x 4096
