@@ -436,7 +436,7 @@ def profile_only(torch, fq, workloads, dev, what, launches):
             q = {"q": q["q"].reshape(-1, case.N)}
     else:
         # (stream_rows1: the weight-streaming workload of `shapes`, one row against 16384 x 4096 weights)
-        case = workloads.make_linear("stream_16384x4096", 9, 16384 + 4096, 2, 4096, 16384, 64, outlier_frac=0.02) if what == "stream_rows1" \
+        case = workloads.make_linear("stream_16384x4096", 9, 16384 + 4096, 16, 4096, 16384, 64, outlier_frac=0.02) if what == "stream_rows1" \
             else workloads.config3("fc2")
         x_scale, amax = _calib(case)
         layer = fq.flexiq_quantize_pack(case.W, amax, x_scale, case.group_size, bias=case.bias)
