@@ -3,14 +3,15 @@
 // low-bit ratio rises (Section 7: 4-bit groups move half the weight bytes).
 //
 // The tiled kernel launches one block per 64 x 64 output tile here: 16 to 64 blocks on 256 compute units, each
-// walking the whole reduction alone.  The kernel below gives a block 16 output columns and splits the reduction over
-// its waves.  Nothing but the partial sums goes through LDS: the packed weight layouts are already in MFMA fragment
-// order, so a wave's weight fragment of a K-step is a coalesced load per 16-channel quarter straight into the operand
-// registers:
-//   * 8-bit units: 16 bytes per lane from the 8-bit tiles;
-//   * 4-bit units: 8 bytes per lane of packed 4-bit codes (half the bytes) plus one position byte, expanded in
-//     registers to code << w_shift; the activations of those units are bit-lowered in registers (unless they arrive
-//     lowered), exactly as in the tiled kernel: same int8 MFMA, same int32 accumulators, bit-identical results.
+// walking the whole reduction alone.  The two kernels below give a block a few output columns and split the reduction
+// over its waves, which meet in LDS.  Weights never go through LDS: the packed weight layouts hold 16-channel pieces of
+// a weight row contiguously, which is both the MFMA fragment order and what a dot-product lane wants, so a lane loads
+//   * 8-bit units: 16 bytes from the 8-bit tiles;
+//   * 4-bit units: 8 bytes of packed 4-bit codes (half the bytes) plus one position byte.
+// k_few_rows (3 .. 64 rows) feeds the matrix cores: the codes are expanded in registers to code << w_shift and the
+// activations of those units are bit-lowered, exactly as in the tiled kernel (same int8 MFMA, same int32 sums).
+// k_few_rows_dot (1 .. 4 rows) multiplies on the vector ALU, 4-bit units as 4-bit codes (Section 7's shifted accumulation).
+// Both give the tiled kernel's results bit for bit.
 #include <algorithm>
 
 #include "flexiq_internal.h"
@@ -51,9 +52,9 @@ __device__ __forceinline__ uint32_t expand4(uint32_t p, int sw)
 // ---- A block owns 16 output columns and the whole reduction.
 //
 // Splitting the reduction across blocks makes the slices meet in memory (store, ticket, re-read: three dependent trips;
-// built and measured: ViT-L fc2 with 16 rows took 11 us that way, 4.7 us this way).  Here the slices of a column tile
-// are the waves of one block (up to sixteen), which meet in LDS: every wave takes the
-// K-steps (64 channels) wave, wave + waves, ... of the block's 16 columns, issues the loads of up to four of them at once
+// built and measured: ViT-L fc2 with 16 rows took 11 us that way, 4.7 us this way).  Here the slices of a column tile are
+// the waves of one block (up to sixteen), which meet in LDS: every wave takes the K-steps (64 channels) wave,
+// wave + waves, ... of the block's 16 columns, issues the loads of up to four of them at once
 // (weight fragments straight into MFMA operand registers: 16 bytes per lane from the 8-bit tiles, or 8 bytes
 // of packed codes and a position byte for 4-bit units), multiplies with `v_mfma_i32_16x16x64_i8` (lane: weight row
 // n0 + lane % 16 resp. activation row 16 f + lane % 16, channels 16 (lane / 16) ... of the K-step) and leaves its
