@@ -106,3 +106,27 @@ def test_resnet50_stack_ratio_schedule(env, lo, hi):
         case = workloads.config4_layer(i, B=128)
         _conv_fullsize(env, case, sched[3 * i:3 * i + 3], [0, 127])
         del case
+
+
+def test_weight_streaming_few_rows(env):
+    # bench.py's weight-streaming workload (16384 x 4096 weights, group size 64) in the launch configuration it times: 1, 2, 4
+    # and 16 rows through the automatic few-row route (dot-product kernel with four column groups per block for 1 and 2 rows
+    # and, from r = 0.5 on, 4 rows; the matrix-core kernel otherwise), whole outputs against the oracle
+    torch, oracle, fq, dev = env
+    case = workloads.make_linear("stream_16384x4096", 9, 16384 + 4096, 16, 4096, 16384, 64, outlier_frac=0.02)
+    x_scale, amax = calib(case)
+    ol = oracle.prepare_layer(case.W, amax, x_scale, 64, bias=case.bias)
+    hl = fq.flexiq_quantize_pack(case.W, amax, x_scale, 64, bias=case.bias)
+    assert (hl.info()["perm"] == ol.perm).all()
+    Xq = np.ascontiguousarray(oracle.quantize(case.X, x_scale)[:, ol.perm])
+    for r in (0.0, 0.25, 0.5, 1.0):
+        fq.flexiq_set_ratio(hl, r)
+        ref = oracle.forward_gemm(ol, Xq, r)
+        so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9)
+        for M in (1, 2, 4, 16):
+            out = fq.flexiq_mixed_gemm(hl, torch.from_numpy(Xq[:M]).to(dev), acc=True, q=True, out_scale=so)
+            torch.cuda.synchronize()
+            assert fq.debug_last_launch()["tile"] == -4
+            assert fq.debug_force_few_rows(-1) == (2 if M <= 2 or (M == 4 and r >= 0.5) else 1), (M, r)   # which kernel ran
+            assert (out["acc"].cpu().numpy() == ref[:M]).all(), (M, r)
+            check_q(out["q"].cpu().numpy(), ref[:M], ol, so)
