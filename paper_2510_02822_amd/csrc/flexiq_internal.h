@@ -70,7 +70,8 @@ namespace flexiq {
 int fp6_channels(const flexiq_layer *L);
 // (smallm.hip) linear calls with at most 64 rows: a block per 16 output columns whose waves split the reduction
 // and meet in LDS; *taken = 0: the call does not qualify
-int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken);
+int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,
+                    const uint8_t *X4 = nullptr);
 // The consumer named by flexiq_out.lower_for, checked (gemm.hip): its positions, 4-bit prefix and log2 of its group size;
 // ashift == nullptr: the call names none.
 struct LowerArgs {

@@ -229,9 +229,9 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     // Few-row linear calls: a block per 16 output columns, the reduction split over its waves (smallm.hip).  Measured against
     // the tiled kernel, which launches 16-64 blocks of 64 x 64 here: faster for every call of at most 16 rows, and up to 64
     // rows as long as there is at most one block per compute unit or so (every block reads all activation rows).
-    if (!conv && !xp && M <= 64 && g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0) {
+    if (!conv && M <= 64 && g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0) {
         int taken = 0;
-        const int rc = launch_few_rows(L, X, M, out, stream, dk.num_cu, &taken);
+        const int rc = launch_few_rows(L, X, M, out, stream, dk.num_cu, &taken, xp ? X4 : nullptr);
         if (rc != FLEXIQ_OK) return rc;
         if (taken) {
             g_last_shape = -4;

@@ -77,6 +77,8 @@ struct RowsParams {
     int32_t x_pre;          // activations of those units arrive lowered
     int32_t gs_shift;
     int32_t steps;          // K-steps of 64 channels (the last one may hold a single unit)
+    const uint8_t *X4;      // optional (k_few_rows_dot): packed activation codes [M][C / 2] of the leading pieces_p pieces of a row
+    int32_t pieces_p;       // 16-channel pieces whose codes come from X4 (a multiple of 4: whole K-steps)
 };
 
 constexpr int kRowCols = 16;   // output columns per block
@@ -318,6 +320,10 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
         }
         for (int i = tid; i < p.M * per_row; i += (int)blockDim.x) {
             const int m = i / per_row, j = i - m * per_row;
+            if (j < p.pieces_p) {   // the producer has made the codes (same layout: flexiq_lower_packed4, flexiq_out.x4)
+                *reinterpret_cast<v2i *>(xl + m * xl_stride + 8 * j) = *reinterpret_cast<const v2i *>(p.X4 + (int64_t)m * (p.C >> 1) + 8 * j);
+                continue;
+            }
             const v4i v = *reinterpret_cast<const v4i *>(p.X + (int64_t)m * p.C + 16 * j);
             const int s_ = p.ashift[(j >> 1) >> p.gs_shift];
             // lowered bytes are code << s with the low s bits clear, so a dword-wide shift right leaves the code's two's
@@ -405,7 +411,8 @@ static int g_last_rows = 0;
 
 // Launches k_few_rows (*taken = 1) or k_few_rows_dot (*taken = 2) for a linear call with at most 64 rows; *taken = 0: the call
 // was left to the other kernels.
-int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken)
+int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,
+                    const uint8_t *X4)
 {
     using namespace smallm;
     *taken = 0;
@@ -429,6 +436,10 @@ int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const fle
     p.x_pre = L->x_prelowered ? 1 : 0;
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.steps = (p.units + 1) / 2;
+    // packed activation codes of the leading whole K-steps of 4-bit channels (the caller has checked alignment): the dot-product
+    // kernel takes them as they are; the matrix-core kernel has no use for them and leaves such a call to the tiled kernel
+    p.X4 = X4 && !L->x_prelowered ? X4 : nullptr;
+    p.pieces_p = p.X4 ? (L->max_4bit_ch / 64) * 4 : 0;
     // One or two rows: the dot-product kernel.  Three or four rows: where the layer has columns enough for four column groups per
     // block and at least half of the channels run at 4 bits (measured on 16384 x 4096 weights at four rows, r = 0 / 0.5 / 1: 14.7 / 13.1 /
     // 11.6 us against 13.1 / 12.9 / 14.4 us on the matrix-core kernel; from six rows on it is bound by its vector-ALU work, 22 us; at
@@ -460,6 +471,7 @@ int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const fle
         }
         if (g_force_rows == 2) return FLEXIQ_OK;
     }
+    if (X4) return FLEXIQ_OK;
     const int mf = (int)((M + 15) / 16);
     const unsigned blocks = (unsigned)((L->N + kRowCols - 1) / kRowCols);
     // waves per block: as many as there are K-steps to split while the layer gives a compute unit a block or so (the call is one

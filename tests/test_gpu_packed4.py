@@ -205,3 +205,42 @@ def test_producer_packs_for_consumer(env):
         fq.debug_force_tile(-1)
     with pytest.raises(fq.FlexiqError):   # packed output needs the consumer
         fq.flexiq_mixed_gemm(h1, Xd, q=True, out_scale=s_mid, x4_out=x4)
+
+
+@pytest.mark.parametrize("K,N,gs", [(256, 256, 32), (1024, 72, 64), (192, 8200, 32)])
+def test_few_row_dot_kernel_reads_packed_codes(env, K, N, gs):
+    # calls of a few rows: the dot-product kernel takes the producer's packed codes as they are (no clamp, no packing in
+    # the kernel); rows 1 and 2 by the automatic route, 3 and 4 forced, with one and with four column groups per block
+    torch, oracle, fq, dev = env
+    case = workloads.make_linear("p4few", 11, 900 + K + N, 4, K, N, gs, outlier_frac=0.02)
+    case.X *= 2.0
+    ol, hl, x_scale = both_layers(case)
+    Xq = oracle.quantize(case.X, x_scale)[:, ol.perm]
+    G = K // gs
+    try:
+        for r in sorted({1.0, 0.5, 1.0 / G, 0.0}):
+            k4 = fq.flexiq_set_ratio(hl, r)
+            k4p = fq.flexiq_packed4_channels(hl)
+            ref = oracle.forward_gemm(ol, Xq, r)
+            so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
+            for M, mode in ((1, -1), (2, -1), (3, 2), (4, 2), (2, 14), (4, 14)):
+                Xd = _dev(torch, Xq[:M], dev)
+                x4 = fq.flexiq_lower_packed4(hl, Xd)
+                Xp = Xq[:M].copy()
+                Xp[:, :k4p] = 77                      # the packed columns of X are not read
+                fq.debug_force_few_rows(mode)
+                out = fq.flexiq_mixed_gemm_packed4(hl, _dev(torch, Xp, dev), x4, acc=True, q=True, out_scale=so)
+                torch.cuda.synchronize()
+                if k4p:   # (no packed channel at this ratio: an ordinary call)
+                    assert fq.debug_force_few_rows(mode) == 2 and fq.debug_last_launch()["tile"] == -4, (M, mode, r)
+                assert (out["acc"].cpu().numpy() == ref[:M]).all(), (M, mode, r)
+                check_q(out["q"].cpu().numpy(), ref[:M], ol, so)
+        # more rows than the dot-product kernel takes: the tiled kernel reads the packed codes
+        fq.debug_force_few_rows(-1)
+        fq.flexiq_set_ratio(hl, 1.0)
+        Xd = _dev(torch, np.ascontiguousarray(np.repeat(Xq, 3, axis=0)), dev)
+        out = fq.flexiq_mixed_gemm_packed4(hl, Xd, fq.flexiq_lower_packed4(hl, Xd), acc=True)
+        assert fq.debug_last_launch()["tile"] >= 0
+        assert (out["acc"].cpu().numpy() == np.repeat(oracle.forward_gemm(ol, Xq, 1.0), 3, axis=0)).all()
+    finally:
+        fq.debug_force_few_rows(-1)
