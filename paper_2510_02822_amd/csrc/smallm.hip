@@ -114,7 +114,7 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
 #pragma unroll
     for (int f = 0; f < MF; ++f) acc[f] = (v4i){0, 0, 0, 0};
 
-    constexpr int UN = MF <= 2 ? 4 : 2;   // K-steps in flight per wave
+    constexpr int UN = MF <= 2 ? 4 : 2;   // K-steps in flight per wave (four with three or four fragments spill)
     v4i w8[UN], x[UN][MF];
     v2i w4[UN];
     int sw[UN], sa[UN];
