@@ -7,10 +7,12 @@
 // over its waves, which meet in LDS.  Weights never go through LDS: the packed weight layouts hold 16-channel pieces of
 // a weight row contiguously, which is both the MFMA fragment order and what a dot-product lane wants, so a lane loads
 //   * 8-bit units: 16 bytes from the 8-bit tiles;
-//   * 4-bit units: 8 bytes of packed 4-bit codes (half the bytes) plus one position byte.
-// k_few_rows (3 .. 64 rows) feeds the matrix cores: the codes are expanded in registers to code << w_shift and the
-// activations of those units are bit-lowered, exactly as in the tiled kernel (same int8 MFMA, same int32 sums).
-// k_few_rows_dot (1 .. 4 rows) multiplies on the vector ALU, 4-bit units as 4-bit codes (Section 7's shifted accumulation).
+//   * 4-bit units: 16 bytes from the position-expanded copy, or 8 bytes of packed 4-bit codes (half the bytes) plus one
+//     position byte.
+// k_few_rows (3 .. 64 rows) feeds the matrix cores as the tiled kernel does: 4-bit units from the position-expanded int8 copy
+// (16 bytes per lane like 8-bit units), their activations bit-lowered (same int8 MFMA, same int32 sums).
+// k_few_rows_dot (1 .. 4 rows) multiplies on the vector ALU, 4-bit units as the packed 4-bit codes (Section 7's shifted
+// accumulation): the kernel for calls that are bound by weight bytes.
 // Both give the tiled kernel's results bit for bit.
 #include <algorithm>
 
@@ -37,34 +39,22 @@ __device__ __forceinline__ uint32_t lower4(uint32_t d, int s)
     return r & (0x01010101u * ((0xFFu << s) & 0xFFu));
 }
 
-// four 4-bit codes in the high halves of the bytes of p -> four int8 values code << sw
-__device__ __forceinline__ uint32_t expand4(uint32_t p, int sw)
-{
-    const short t = (short)(4 - sw);
-    v2s o = __builtin_bit_cast(v2s, p);
-    v2s e = o << (short)8;
-    o = o >> t;   // arithmetic: sign-extends the code, leaves junk only below bit sw and in the low byte
-    e = e >> t;
-    const uint32_t r = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, o), __builtin_bit_cast(uint32_t, e), 0x07030501u);
-    return r & (0x01010101u * ((0xFFu << sw) & 0xFFu));
-}
-
 // ---- A block owns 16 output columns and the whole reduction.
 //
 // Splitting the reduction across blocks makes the slices meet in memory (store, ticket, re-read: three dependent trips;
 // built and measured: ViT-L fc2 with 16 rows took 11 us that way, 4.7 us this way).  Here the slices of a column tile are
 // the waves of one block (up to sixteen), which meet in LDS: every wave takes the K-steps (64 channels) wave,
 // wave + waves, ... of the block's 16 columns, issues the loads of up to four of them at once
-// (weight fragments straight into MFMA operand registers: 16 bytes per lane from the 8-bit tiles, or 8 bytes
-// of packed codes and a position byte for 4-bit units), multiplies with `v_mfma_i32_16x16x64_i8` (lane: weight row
+// (weight fragments straight into MFMA operand registers: 16 bytes per lane), multiplies with `v_mfma_i32_16x16x64_i8` (lane: weight row
 // n0 + lane % 16 resp. activation row 16 f + lane % 16, channels 16 (lane / 16) ... of the K-step) and leaves its
 // accumulators in LDS; waves 0 .. MF-1 add them up and run the epilogue of one 16-row fragment each.  One trip to memory
 // for the operands and one for the outputs; nothing to zero, nothing to hand in.
 struct RowsParams {
     const int8_t *X;        // int8 [M][C], stored channel order
     const int8_t *W8;       // [U][2][Npad][16]
-    const uint8_t *W4;      // [U][Npad][16] packed 4-bit codes
-    const uint8_t *wshift;  // [G + 1][Npad]
+    int32_t w4x_delta;      // bytes from the 8-bit tiles to the position-expanded copy of every 4-bit group (same layout)
+    const uint8_t *W4;      // [U][Npad][16] packed 4-bit codes                  (k_few_rows_dot)
+    const uint8_t *wshift;  // [G + 1][Npad] weight positions                    (k_few_rows_dot)
     const int32_t *ashift;  // [G + 1]
     const float *cs;        // [2][Npad]: x_scale * w_scale, then bias
     int32_t *acc;
@@ -114,12 +104,15 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
 #pragma unroll
     for (int f = 0; f < MF; ++f) acc[f] = (v4i){0, 0, 0, 0};
 
-    constexpr int UN = MF <= 2 ? 4 : 2;   // K-steps in flight per wave (four with three or four fragments spill)
+    constexpr int UN = MF <= 3 ? 4 : 3;   // K-steps in flight per wave (four with four fragments spill)
     v4i w8[UN], x[UN][MF];
-    v2i w4[UN];
-    int sw[UN], sa[UN];
+    int sa[UN];
     bool low[UN], valid[UN];
-    // weight fragments (and positions) of the K-steps ks0, ks0 + nw, ...: loads only
+    // weight fragments (and activation positions) of the K-steps ks0, ks0 + nw, ...: loads only.  4-bit units come from the
+    // position-expanded copy (code << w_shift as int8, 16 bytes per lane like an 8-bit unit): measured against the packed codes
+    // expanded in registers (8 bytes and a position byte per lane, 22 vector-ALU operations per 16 codes) it is faster at every
+    // size (ViT-L fc2, 16 rows, r = 1: 5.2 against 6.1 us; 16384 x 4096 weights, 8 rows: 16.1 against 18.7 us): what the packed
+    // codes save in bytes the expansion costs in instructions.  One and two rows, where bytes decide, go to k_few_rows_dot.
     auto issue_w = [&](int ks0) {
 #pragma unroll
         for (int k = 0; k < UN; ++k) {
@@ -128,15 +121,9 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
             valid[k] = ks < p.steps && u < p.units;
             low[k] = valid[k] && u < p.units4;
             w8[k] = (v4i){0, 0, 0, 0};
-            w4[k] = (v2i){0, 0};
-            sw[k] = sa[k] = 0;
-            if (low[k]) {
-                w4[k] = *reinterpret_cast<const v2i *>(p.W4 + ((int64_t)u * p.Npad + n) * 16 + 8 * h);
-                sw[k] = p.wshift[(int64_t)(u >> p.gs_shift) * p.Npad + n];
-                if (!COOP && !p.x_pre) sa[k] = p.ashift[u >> p.gs_shift];
-            } else if (valid[k]) {
-                w8[k] = *reinterpret_cast<const v4i *>(p.W8 + (((int64_t)u * 2 + h) * p.Npad + n) * 16);
-            }
+            sa[k] = 0;
+            if (valid[k]) w8[k] = *reinterpret_cast<const v4i *>(p.W8 + (low[k] ? p.w4x_delta : 0) + (((int64_t)u * 2 + h) * p.Npad + n) * 16);
+            if (low[k] && !COOP && !p.x_pre) sa[k] = p.ashift[u >> p.gs_shift];
         }
     };
     // activation fragments of the same K-steps: from memory, or (COOP, 4-bit units) lowered already from LDS
@@ -174,21 +161,14 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
         issue_x(ks0);
 #pragma unroll
         for (int k = 0; k < UN; ++k) {
-            v4i w = w8[k];
-            if (low[k]) {
-                // dword e of the unit's 16 code bytes carries channels 8 e .. 8 e + 3 in the low halves of its bytes and
-                // 8 e + 4 .. 8 e + 7 in the high halves; this lane holds dwords 2 h and 2 h + 1
-                w = (v4i){(int)expand4((uint32_t)w4[k].x << 4, sw[k]), (int)expand4((uint32_t)w4[k].x, sw[k]),
-                          (int)expand4((uint32_t)w4[k].y << 4, sw[k]), (int)expand4((uint32_t)w4[k].y, sw[k])};
-                if (!COOP && !p.x_pre) {
+            if (low[k] && !COOP && !p.x_pre) {
 #pragma unroll
-                    for (int f = 0; f < MF; ++f)
-                        x[k][f] = (v4i){(int)lower4((uint32_t)x[k][f].x, sa[k]), (int)lower4((uint32_t)x[k][f].y, sa[k]),
-                                        (int)lower4((uint32_t)x[k][f].z, sa[k]), (int)lower4((uint32_t)x[k][f].w, sa[k])};
-                }
+                for (int f = 0; f < MF; ++f)
+                    x[k][f] = (v4i){(int)lower4((uint32_t)x[k][f].x, sa[k]), (int)lower4((uint32_t)x[k][f].y, sa[k]),
+                                    (int)lower4((uint32_t)x[k][f].z, sa[k]), (int)lower4((uint32_t)x[k][f].w, sa[k])};
             }
 #pragma unroll
-            for (int f = 0; f < MF; ++f) acc[f] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w, x[k][f], acc[f], 0, 0, 0);
+            for (int f = 0; f < MF; ++f) acc[f] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w8[k], x[k][f], acc[f], 0, 0, 0);
         }
         ks0 += nw * UN;
         if (ks0 >= p.steps) break;
@@ -436,6 +416,7 @@ int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const fle
     p.x_pre = L->x_prelowered ? 1 : 0;
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.steps = (p.units + 1) / 2;
+    p.w4x_delta = L->U * 32 * L->Npad;
     // packed activation codes of the leading whole K-steps of 4-bit channels (the caller has checked alignment): the dot-product
     // kernel takes them as they are; the matrix-core kernel has no use for them and leaves such a call to the tiled kernel
     p.X4 = X4 && !L->x_prelowered ? X4 : nullptr;
