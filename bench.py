@@ -248,7 +248,8 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
                     fq.debug_force_few_rows(force)
                     us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=so, bufs=bufs), 20)
                     launch = fq.debug_last_launch()
-                    route = "w4" if launch["tile"] == -4 else "w4x"     # the few-row kernel streams the packed 4-bit codes
+                    # (of the two few-row kernels only the dot-product one streams the packed 4-bit codes)
+                    route = "w4" if launch["tile"] == -4 and fq.debug_force_few_rows(force) == 2 else "w4x"
                     rec("%s weights %d x %d, M=%d rows" % (name, case.N, case.K, Ms), "few-row call, " + tag, r, us,
                         byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, route), launch=launch)
                 fq.debug_force_few_rows(-1)
@@ -279,11 +280,14 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
             for L in copies:
                 fq.flexiq_set_ratio(L, r)
             us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=so, bufs=bufs), 20)
+            kern = fq.debug_force_few_rows(-1)     # 2: the dot-product kernel (packed codes), 1: the matrix-core kernel (expanded copy)
+            route = "w4" if kern == 2 else "w4x"
+            kname = {1: "matrix-core kernel", 2: "dot-product kernel"}.get(kern, "?")
             rec("weight streaming: 16384 x 4096 weights, M=%d rows" % Ms, "few-row kernels (automatic route), warm: one weight set", r, us,
-                byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, "w4"), launch=fq.debug_last_launch())
+                byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, route), launch=fq.debug_last_launch(), kernel=kname)
             us = _median_graph_us(torch, lambda: cold_calls(Xs, bufs), 2) / len(copies)
             rec("weight streaming: 16384 x 4096 weights, M=%d rows" % Ms, "few-row kernels (automatic route), cold: ten weight sets in turn", r, us,
-                byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, "w4"), launch=fq.debug_last_launch())
+                byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, route), launch=fq.debug_last_launch(), kernel=kname)
     del layer, copies, Xq, case
 
     # ---- an HBM-bound layer as a linear call: the ResNet-50 stage-1 1x1 convolution 256 -> 64 at 56 x 56, batch 128
