@@ -203,8 +203,9 @@ typedef struct {
  * X: dev int8 [M][C] row-major, channels in stored order, 16-byte aligned; M >= 0 (M == 0 is a no-op).
  * The activations are bit-lowered on the fly inside the kernel, at the handle's current positions (calibrated, or
  * those of the last flexiq_dynamic_positions scan); the weights of 4-bit groups are read from the handle's cached
- * lowered copies.  Layer must be linear (R = S = 1).  Launches on `stream`; allocates nothing; returns before the
- * kernel has run.  Errors: FLEXIQ_EINVAL (null / inconsistent arguments, M >= 2^31 - 512, more than 159 channel
+ * lowered copies.  Layer must be linear (R = S = 1).  Which kernel serves the call (tiled, row-streaming for at most 256
+ * channels, the few-row kernels for at most 64 rows) follows from the shape; the int32 sums are the same bit for bit.
+ * Launches on `stream`; allocates nothing; returns before the kernel has run.  Errors: FLEXIQ_EINVAL (null / inconsistent arguments, M >= 2^31 - 512, more than 159 channel
  * groups, a padded weight matrix of 1 GiB or more, current device is not the handle's), FLEXIQ_EALIGN, FLEXIQ_EHIP. */
 int flexiq_mixed_gemm(const flexiq_layer *layer, const int8_t *X, int64_t M, const flexiq_out *out, void *stream);
 
