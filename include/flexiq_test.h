@@ -32,7 +32,8 @@ int flexiq_debug_last_launch(int which);
 /* The few-row kernels (linear calls with at most 64 rows; last launch: tile shape index -4): 1 = the matrix-core kernel
  * whenever the call qualifies, 2 = the dot-product kernel (at most 4 rows) whenever it qualifies (14: with 4 groups of 8 columns per
  * block where the layer's padding allows), 0 = never, -1 = automatic.
- * Returns which of them the last call they were offered ran on (0: neither). */
+ * Returns which of them the last call they were offered ran on (0: neither; 3: the matrix-core kernel's FP6 build, which
+ * flexiq_mixed_gemm_fp6 takes for at most 64 rows unless an FP6 tile shape is forced or mode is 0). */
 int flexiq_debug_force_few_rows(int mode);
 
 /* The row-streaming kernels for layers with 64, 128 or 256 input channels (last launch: tile shape index -2):

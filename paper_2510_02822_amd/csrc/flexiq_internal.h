@@ -72,6 +72,9 @@ int fp6_channels(const flexiq_layer *L);
 // and meet in LDS; *taken = 0: the call does not qualify
 int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,
                     const uint8_t *X4 = nullptr);
+// (smallm.hip) the same for flexiq_mixed_gemm_fp6: the leading K6 channels on the FP6 matrix path
+int launch_few_rows_fp6(const flexiq_layer *L, const int8_t *X, const uint8_t *X6, int64_t M, const flexiq_out *out, void *stream, int K6,
+                        int num_cu, int *taken);
 // The consumer named by flexiq_out.lower_for, checked (gemm.hip): its positions, 4-bit prefix and log2 of its group size;
 // ashift == nullptr: the call names none.
 struct LowerArgs {

@@ -103,6 +103,15 @@ extern "C" int flexiq_mixed_gemm_fp6(const flexiq_layer *L, const int8_t *X, con
     const int64_t x6_bytes = ((M + 63) / 64) * (int64_t)(L->C / 64) * 3072;
     if (x6_bytes > 0x7fffffff || (int64_t)L->U * 32 * L->Npad * 2 > kMaxWeightBytes) return FLEXIQ_EINVAL;
 
+    if (M <= 64 && g_force_shape < 0) {   // few rows: a block per 16 columns whose waves split the reduction (smallm.hip)
+        int taken = 0;
+        const int rc = launch_few_rows_fp6(L, X, X6, M, out, stream, K6, g_dev[dev].num_cu, &taken);
+        if (rc != FLEXIQ_OK) return rc;
+        if (taken) {
+            g_last_shape = -4;
+            return FLEXIQ_OK;
+        }
+    }
     Params p = {};
     p.X = X; p.X6 = X6; p.W8 = L->d_w8; p.W6 = L->d_w6; p.W6S = L->d_w6s;
     p.ashift = L->dynamic ? L->d_ashift_dyn : L->d_ashift;

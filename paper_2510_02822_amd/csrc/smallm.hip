@@ -24,6 +24,8 @@ namespace smallm {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef short v2s __attribute__((ext_vector_type(2)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 // clamp(v, -(8 << s), (8 << s) - 1) with the low s bits cleared, on the four int8 lanes of a dword: the bit-lowered
 // value L(v, s) put back at its position (Section 4.1)
@@ -67,6 +69,12 @@ struct RowsParams {
     int32_t x_pre;          // activations of those units arrive lowered
     int32_t gs_shift;
     int32_t steps;          // K-steps of 64 channels (the last one may hold a single unit)
+    // FP6 builds of k_few_rows (the variant of the 4-bit phase on the f8f6f4 matrix path, fp6_kernel.h): the leading s6 K-steps
+    // come as FP6 codes, 24 bytes per (row, 32-channel unit), in the layouts of that kernel
+    const uint8_t *X6;      // activations [ceil(M/64)][C/64][3][64][16]
+    const uint8_t *W6;      // weights [C/64][3][Npad][16]
+    const uint8_t *W6S;     // weight block scales [ceil(C/256)][Npad][2][4] (E8M0 bytes of four consecutive K-steps)
+    int32_t s6;             // K-steps on the FP6 path (K6 / 64)
     const uint8_t *X4;      // optional (k_few_rows_dot): packed activation codes [M][C / 2] of the leading pieces_p pieces of a row
     int32_t pieces_p;       // 16-channel pieces whose codes come from X4 (a multiple of 4: whole K-steps)
 };
@@ -74,11 +82,15 @@ struct RowsParams {
 constexpr int kRowCols = 16;   // output columns per block
 
 // MF: 16-row fragments of activations (M <= 16 MF).  COOP (MF = 1, at most 8 rows, activations not lowered yet): the 4-bit
-// channels of the rows are lowered once per block into LDS instead of per lane in fragment layout.
-template <int MF, bool COOP>
+// channels of the rows are lowered once per block into LDS instead of per lane in fragment layout.  FP6: the leading s6
+// K-steps run on the FP6 matrix path first (`v_mfma_scale_f32_16x16x128_f8f6f4`: two K-steps per instruction, a lane holds
+// the 32 codes of one unit and its block scale; exact integer sums in fp32, see fp6_kernel.h), every other K-step as usual
+// with activations that arrive lowered.
+template <int MF, bool COOP, bool FP6 = false>
 __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
 {
     static_assert(!COOP || MF == 1, "the cooperative pass is for calls of a few rows");
+    static_assert(!(COOP && FP6), "FP6 calls bring lowered activations");
     extern __shared__ __align__(16) unsigned char lds[];   // [waves][MF][64 lanes] accumulator quads, then (COOP) the lowered rows
     v4i *const red = reinterpret_cast<v4i *>(lds);
     const int xl_stride = 32 * p.units4 + 16;   // (+16: rows start in different banks)
@@ -142,6 +154,55 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
         }
     };
     int ks0 = wave;
+    if constexpr (FP6) {
+        // chunks of two FP6 K-steps (128 channels), dealt to the waves in turn; the int8 K-steps after them continue the deal
+        const int chunks = (p.s6 + 1) >> 1, S = p.C >> 6;
+        v4f accf[MF];
+#pragma unroll
+        for (int f = 0; f < MF; ++f) accf[f] = (v4f){0.f, 0.f, 0.f, 0.f};
+        constexpr int U6 = 2;   // chunks in flight
+        for (int c0 = wave; c0 < chunks; c0 += nw * U6) {
+            v4i wlo[U6], xlo[U6][MF];
+            v2i whi[U6], xhi[U6][MF];
+            int wsc[U6], asc[U6];
+#pragma unroll
+            for (int k = 0; k < U6; ++k) {
+                const int ks = 2 * (c0 + k * nw) + (qd >> 1), h = qd & 1;   // this lane's K-step and unit
+                const bool ok = ks < p.s6;
+                wlo[k] = (v4i){0, 0, 0, 0};
+                whi[k] = (v2i){0, 0};
+                wsc[k] = asc[k] = 127;
+                if (ok) {
+                    // the first 16 code bytes of unit h in plane h, the last 8 of both units in plane 2 (unit h in half h ^ ((row / 16) % 2))
+                    wlo[k] = *reinterpret_cast<const v4i *>(p.W6 + (((int64_t)ks * 3 + h) * p.Npad + n) * 16);
+                    whi[k] = *reinterpret_cast<const v2i *>(p.W6 + (((int64_t)ks * 3 + 2) * p.Npad + n) * 16 + 8 * (h ^ ((n >> 4) & 1)));
+                    wsc[k] = p.W6S[((int64_t)(ks >> 2) * p.Npad + n) * 8 + 4 * h + (ks & 3)];
+                    asc[k] = 130 + p.ashift[(2 * ks + h) >> p.gs_shift];   // 2^(position + 3): the codes are k / 8
+                }
+#pragma unroll
+                for (int f = 0; f < MF; ++f) {
+                    const int m = 16 * f + c, blk = m >> 6, r = m & 63;
+                    xlo[k][f] = (v4i){0, 0, 0, 0};
+                    xhi[k][f] = (v2i){0, 0};
+                    if (ok && m < p.M) {
+                        xlo[k][f] = *reinterpret_cast<const v4i *>(p.X6 + ((((int64_t)blk * S + ks) * 3 + h) * 64 + r) * 16);
+                        xhi[k][f] = *reinterpret_cast<const v2i *>(p.X6 + ((((int64_t)blk * S + ks) * 3 + 2) * 64 + r) * 16 + 8 * (h ^ ((r >> 4) & 1)));
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < U6; ++k)
+#pragma unroll
+                for (int f = 0; f < MF; ++f)
+                    accf[f] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                        (v8i){wlo[k].x, wlo[k].y, wlo[k].z, wlo[k].w, whi[k].x, whi[k].y, 0, 0},
+                        (v8i){xlo[k][f].x, xlo[k][f].y, xlo[k][f].z, xlo[k][f].w, xhi[k][f].x, xhi[k][f].y, 0, 0}, accf[f], 2, 2, 0, wsc[k], 0, asc[k]);
+        }
+#pragma unroll
+        for (int f = 0; f < MF; ++f)
+            acc[f] = (v4i){(int)accf[f].x, (int)accf[f].y, (int)accf[f].z, (int)accf[f].w};   // exact integers below 2^24
+        ks0 = p.s6 + (wave + nw - chunks % nw) % nw;
+    }
     issue_w(ks0);   // (a wave beyond the last K-step loads nothing and multiplies zeros once)
     if constexpr (COOP) {
         // few rows: in the fragment layout most lanes hold no row, and lowering there would cost every wave the full
@@ -470,6 +531,43 @@ int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const fle
     FLEXIQ_HIP(hipGetLastError());
     *taken = 1;
     g_last_rows = 1;
+    return FLEXIQ_OK;
+}
+
+// The FP6 variant of a linear call with at most 64 rows (flexiq_mixed_gemm_fp6): k_few_rows with the leading K6 channels on the
+// FP6 matrix path; *taken = 0: the call was left to the tiled FP6 kernel.
+int launch_few_rows_fp6(const flexiq_layer *L, const int8_t *X, const uint8_t *X6, int64_t M, const flexiq_out *out, void *stream, int K6,
+                        int num_cu, int *taken)
+{
+    using namespace smallm;
+    *taken = 0;
+    if (g_force_rows == 0 || M < 1 || M > 64) return FLEXIQ_OK;
+    if (out->lower_for || out->scan_for || out->x4 || out->x6) return FLEXIQ_OK;
+    if (g_force_rows < 0 && M > 16 && (L->N + kRowCols - 1) / kRowCols > num_cu) return FLEXIQ_OK;   // (as in launch_few_rows)
+    RowsParams p = {};
+    p.X = X; p.W8 = L->d_w8; p.X6 = X6; p.W6 = L->d_w6; p.W6S = L->d_w6s;
+    p.ashift = L->dynamic ? L->d_ashift_dyn : L->d_ashift;
+    p.cs = L->d_cs;
+    p.acc = out->acc; p.y = out->y; p.q = out->q;
+    p.r_out = out->q ? 1.0f / out->out_scale : 1.0f;
+    p.M = (int)M; p.N = L->N; p.Npad = L->Npad; p.C = L->C;
+    p.units = L->C / kUnit;
+    p.units4 = L->max_4bit_ch / kUnit;
+    p.x_pre = 1;   // the 4-bit channels beyond the FP6 ones arrive lowered
+    p.gs_shift = L->group_size == 64 ? 1 : 0;
+    p.steps = (p.units + 1) / 2;
+    p.w4x_delta = L->U * 32 * L->Npad;
+    p.s6 = K6 / 64;
+    const int mf = (int)((M + 15) / 16);
+    const unsigned blocks = (unsigned)((L->N + kRowCols - 1) / kRowCols);
+    const int items = (p.s6 + 1) / 2 + (p.steps - p.s6);   // FP6 chunks and int8 K-steps to deal out
+    const int nw = (int)blocks >= 2 * num_cu ? 4 : (items >= 12 ? 16 : (items >= 6 ? 8 : 4));
+    const size_t lds = (size_t)nw * mf * 64 * 16;
+    void (*fn)(const RowsParams) = mf == 1 ? k_few_rows<1, false, true> : (mf == 2 ? k_few_rows<2, false, true> : (mf == 3 ? k_few_rows<3, false, true> : k_few_rows<4, false, true>));
+    hipLaunchKernelGGL(fn, dim3(blocks), dim3(64 * nw), lds, (hipStream_t)stream, p);
+    FLEXIQ_HIP(hipGetLastError());
+    *taken = 1;
+    g_last_rows = 3;
     return FLEXIQ_OK;
 }
 

@@ -220,3 +220,39 @@ def test_fp6_two_layer_chain(env):
     odd = both_layers(workloads.make_linear("fp6odd", 8, 433, 8, 96, 16, 32))[1]
     with pytest.raises(fq.FlexiqError):
         fq.flexiq_fp6_bytes(odd, 8)
+
+
+@pytest.mark.parametrize("K,N,gs", [(256, 256, 32), (1024, 520, 64), (192, 72, 32), (4096, 1024, 64), (64, 7, 32), (2112, 48, 64)])
+def test_fp6_few_rows(env, K, N, gs):
+    # calls of at most 64 rows: the few-row kernel with the FP6 K-steps on v_mfma_scale_f32_16x16x128_f8f6f4 (chunks of two
+    # K-steps; an odd number of FP6 K-steps leaves half a chunk), every fragment count, ratios that leave 4-bit groups outside
+    # the FP6 prefix; the tiled FP6 kernel gives the same bytes
+    torch, oracle, fq, dev = env
+    case = workloads.make_linear("fp6few", 8, 800 + K + N, 64, K, N, gs, outlier_frac=0.02)
+    case.X *= 2.0
+    ol, hl, x_scale = both_layers(case)
+    Xq_all = oracle.quantize(case.X, x_scale)[:, ol.perm]
+    G = K // gs
+    try:
+        for M in (1, 7, 16, 17, 33, 48, 64):
+            Xq = np.ascontiguousarray(Xq_all[:M])
+            Xd = _dev(torch, Xq, dev)
+            for r in sorted({0.0, 1.0 / G, 0.5, 3.0 / G if G >= 3 else 1.0, 1.0}):
+                fq.flexiq_set_ratio(hl, r)
+                ref = oracle.forward_gemm(ol, Xq, r)
+                so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
+                x6, xlow = fq.flexiq_lower_fp6(hl, Xd)
+                fq.debug_force_fp6_tile(-1)
+                out = fq.flexiq_mixed_gemm_fp6(hl, xlow, x6, acc=True, y=True, q=True, out_scale=so)
+                torch.cuda.synchronize()
+                assert fq.debug_force_few_rows(-1) == 3, (M, r)           # the few-row kernel's FP6 build ran
+                assert (out["acc"].cpu().numpy() == ref).all(), (M, r)
+                check_y(out["y"].cpu().numpy(), ref, ol)
+                got_q = out["q"].cpu().numpy()
+                check_q(got_q, ref, ol, so)
+                assert (got_q == requant_fp32_sequence(ref, ol, so)).all()
+                fq.debug_force_fp6_tile(0)                                    # a forced tile shape: the tiled FP6 kernel
+                tiled = fq.flexiq_mixed_gemm_fp6(hl, xlow, x6, q=True, out_scale=so)["q"]
+                assert (tiled.cpu().numpy() == got_q).all(), (M, r)
+    finally:
+        fq.debug_force_fp6_tile(-1)
