@@ -253,6 +253,13 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
                     rec("%s weights %d x %d, M=%d rows" % (name, case.N, case.K, Ms), "few-row call, " + tag, r, us,
                         byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, route), launch=launch)
                 fq.debug_force_few_rows(-1)
+                if Ms >= 16:   # the FP6 variant of the 4-bit phase on the few-row kernel (activations packed by the producer)
+                    x6, xlow = fq.flexiq_lower_fp6(layer, Xs)
+                    us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm_fp6(layer, xlow, x6, q=True, out_scale=so, bufs=bufs), 20)
+                    k6 = fq.flexiq_fp6_channels(layer)
+                    rec("%s weights %d x %d, M=%d rows" % (name, case.N, case.K, Ms), "few-row call, FP6 variant of the 4-bit phase (few-row kernel)", r, us,
+                        byts=Ms * case.K + case.N * (case.K - k6 // 4) + Ms * case.N, fp6_channels=k6)
+                    del x6, xlow
     packed.clear()
 
     # ---- the weight-streaming regime proper: one activation row against a 16384 x 4096 weight matrix (67 MB as int8, group
@@ -288,6 +295,18 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
             us = _median_graph_us(torch, lambda: cold_calls(Xs, bufs), 2) / len(copies)
             rec("weight streaming: 16384 x 4096 weights, M=%d rows" % Ms, "few-row kernels (automatic route), cold: ten weight sets in turn", r, us,
                 byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, route), launch=fq.debug_last_launch(), kernel=kname)
+            if Ms == 16:   # the FP6 variant on the few-row kernel, cold as well (the positions of all copies are the same)
+                x6, xlow = fq.flexiq_lower_fp6(layer, Xs)
+
+                def cold_fp6():
+                    for L in copies:
+                        fq.flexiq_mixed_gemm_fp6(L, xlow, x6, q=True, out_scale=so, bufs=bufs)
+
+                us = _median_graph_us(torch, cold_fp6, 2) / len(copies)
+                k6 = fq.flexiq_fp6_channels(layer)
+                rec("weight streaming: 16384 x 4096 weights, M=%d rows" % Ms, "FP6 variant of the 4-bit phase (few-row kernel), cold: ten weight sets in turn",
+                    r, us, byts=Ms * case.K + case.N * (case.K - k6 // 4) + Ms * case.N, fp6_channels=k6)
+                del x6, xlow
     del layer, copies, Xq, case
 
     # ---- an HBM-bound layer as a linear call: the ResNet-50 stage-1 1x1 convolution 256 -> 64 at 56 x 56, batch 128
