@@ -103,6 +103,10 @@ extern "C" int flexiq_mixed_gemm_fp6(const flexiq_layer *L, const int8_t *X, con
     const int64_t x6_bytes = ((M + 63) / 64) * (int64_t)(L->C / 64) * 3072;
     if (x6_bytes > 0x7fffffff || (int64_t)L->U * 32 * L->Npad * 2 > kMaxWeightBytes) return FLEXIQ_EINVAL;
 
+    // No 4-bit channel at the current ratio: nothing runs as FP6 and nothing arrives lowered, so the call is an ordinary int8
+    // call, and the int8 kernels (more tile shapes, blocks that walk tiles) serve it faster than this kernel's int8 phase
+    // (ViT-L fc2 at r = 0: 41 against 50 us).  Not when the caller wants FP6 output for a consumer, which only this kernel writes.
+    if (L->max_4bit_ch == 0 && !out->x6 && g_force_shape < 0) return flexiq_mixed_gemm(L, X, M, out, stream);
     if (M <= 64 && g_force_shape < 0) {   // few rows: a block per 16 columns whose waves split the reduction (smallm.hip)
         int taken = 0;
         const int rc = launch_few_rows_fp6(L, X, X6, M, out, stream, K6, g_dev[dev].num_cu, &taken);
