@@ -450,7 +450,7 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
     return out
 
 
-PROFILE_TARGETS = ("vitl_fc2", "vitl_fc2_fp6", "vitl_fc2_rows16", "vitl_fc2_rows1", "stream_rows1", "reorder", "resnet_1x1_64_256", "resnet_3x3_64_64",
+PROFILE_TARGETS = ("vitl_fc2", "vitl_fc2_fp6", "vitl_fc2_fp6_rows64", "vitl_fc2_rows16", "vitl_fc2_rows1", "stream_rows1", "reorder", "resnet_1x1_64_256", "resnet_3x3_64_64",
                    "resnet_1x1_256_64", "resnet_1x1_256_64_packed4")
 
 
@@ -478,7 +478,7 @@ def profile_only(torch, fq, workloads, dev, what, launches):
         layer = fq.flexiq_quantize_pack(case.W, amax, x_scale, case.group_size, bias=case.bias)
         Xn = fq.flexiq_quantize_act(torch.from_numpy(case.X).to(dev), x_scale)
         Xq = fq.flexiq_permute_channels(layer, Xn)
-        rows = {"vitl_fc2_rows16": 16, "vitl_fc2_rows1": 1, "stream_rows1": 1}.get(what, case.M)
+        rows = {"vitl_fc2_rows16": 16, "vitl_fc2_rows1": 1, "stream_rows1": 1, "vitl_fc2_fp6_rows64": 64}.get(what, case.M)
         Xs = Xq[:rows].contiguous()
         q = {"q": torch.empty((rows, case.N), dtype=torch.int8, device=dev)}
         res["workload"] = "%s M=%d K=%d N=%d gs=%d" % (case.name, rows, case.K, case.N, case.group_size)
@@ -492,8 +492,8 @@ def profile_only(torch, fq, workloads, dev, what, launches):
             call = None   # FP6 variant: the operands depend on the ratio
     for r in res["ratios"]:
         fq.flexiq_set_ratio(layer, r)
-        if what == "vitl_fc2_fp6":
-            x6, xlow = fq.flexiq_lower_fp6(layer, Xq)
+        if what in ("vitl_fc2_fp6", "vitl_fc2_fp6_rows64"):
+            x6, xlow = fq.flexiq_lower_fp6(layer, Xs)
             call = lambda: fq.flexiq_mixed_gemm_fp6(layer, xlow, x6, q=True, out_scale=0.05, bufs=q)
         if what.endswith("_packed4"):
             x4 = fq.flexiq_lower_packed4(layer, Xq)

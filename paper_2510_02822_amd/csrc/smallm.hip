@@ -203,7 +203,7 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
             acc[f] = (v4i){(int)accf[f].x, (int)accf[f].y, (int)accf[f].z, (int)accf[f].w};   // exact integers below 2^24
         ks0 = p.s6 + (wave + nw - chunks % nw) % nw;
     }
-    issue_w(ks0);   // (a wave beyond the last K-step loads nothing and multiplies zeros once)
+    issue_w(ks0);   // (a wave beyond the last K-step loads nothing)
     if constexpr (COOP) {
         // few rows: in the fragment layout most lanes hold no row, and lowering there would cost every wave the full
         // instruction count for a handful of values.  The block lowers the 4-bit channels of its rows once, every lane a
@@ -218,7 +218,7 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
         }
         __syncthreads();
     }
-    for (;;) {
+    if (ks0 < p.steps) for (;;) {   // (a wave beyond the last K-step has nothing to multiply)
         issue_x(ks0);
 #pragma unroll
         for (int k = 0; k < UN; ++k) {
