@@ -68,10 +68,6 @@ struct flexiq_layer;
 namespace flexiq {
 // Leading channels of the layer that run on the FP6 matrix path under its current ratio and positions (a multiple of 64).
 int fp6_channels(const flexiq_layer *L);
-// (smallm.hip) linear calls with at most 64 rows: a block per 16 output columns whose waves split the reduction
-// and meet in LDS; *taken = 0: the call does not qualify
-int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,
-                    const uint8_t *X4 = nullptr);
 // (smallm.hip) the same for flexiq_mixed_gemm_fp6: the leading K6 channels on the FP6 matrix path
 int launch_few_rows_fp6(const flexiq_layer *L, const int8_t *X, const uint8_t *X6, int64_t M, const flexiq_out *out, void *stream, int K6,
                         int num_cu, int *taken);
@@ -82,6 +78,10 @@ struct LowerArgs {
     int32_t K4 = 0, gs_log2 = 5;
 };
 int lower_for_args(const flexiq_layer *L, const flexiq_out *out, LowerArgs *la);
+// (smallm.hip) linear calls with at most 64 rows: a block per 16 (or 8) output columns whose waves split the reduction
+// and meet in LDS; *taken = 0: the call does not qualify.  X4: a producer's packed activation codes; lower: flexiq_out.lower_for
+int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,
+                    const uint8_t *X4 = nullptr, const LowerArgs *lower = nullptr);
 // (stream.hip) the row-streaming kernels for layers with a short reduction; *taken = 0: the call does not qualify
 int launch_stream(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, bool rows_contiguous, int *taken,
                   const uint8_t *X4 = nullptr, const LowerArgs *lower = nullptr);

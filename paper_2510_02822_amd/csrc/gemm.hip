@@ -231,7 +231,9 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
     // rows as long as there is at most one block per compute unit or so (every block reads all activation rows).
     if (!conv && M <= 64 && g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0) {
         int taken = 0;
-        const int rc = launch_few_rows(L, X, M, out, stream, dk.num_cu, &taken, xp ? X4 : nullptr);
+        LowerArgs la;
+        la.ashift = p.next_ashift; la.K4 = p.next_K4; la.gs_log2 = p.next_gs_log2;   // (checked above)
+        const int rc = launch_few_rows(L, X, M, out, stream, dk.num_cu, &taken, xp ? X4 : nullptr, &la);
         if (rc != FLEXIQ_OK) return rc;
         if (taken) {
             g_last_shape = -4;

@@ -75,6 +75,10 @@ struct RowsParams {
     const uint8_t *W6;      // weights [C/64][3][Npad][16]
     const uint8_t *W6S;     // weight block scales [ceil(C/256)][Npad][2][4] (E8M0 bytes of four consecutive K-steps)
     int32_t s6;             // K-steps on the FP6 path (K6 / 64)
+    // optional: the layer that reads the int8 output (flexiq_out.lower_for): its positions, 4-bit prefix, log2 of its group size;
+    // the codes of its 4-bit channels then leave clamped and masked at its positions (Section 4.1 applied at the producer)
+    const int32_t *next_ashift;
+    int32_t next_K4, next_gs_log2;
     const uint8_t *X4;      // optional (k_few_rows_dot): packed activation codes [M][C / 2] of the leading pieces_p pieces of a row
     int32_t pieces_p;       // 16-channel pieces whose codes come from X4 (a multiple of 4: whole K-steps)
 };
@@ -252,13 +256,20 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
     const int64_t o = (int64_t)m * p.N + nn0;
     float yv[4];
     uint32_t qw = 0;
+    // the consumer's position for these four columns (one channel group of the consumer: nn0 is a multiple of four)
+    const bool lower = p.next_ashift != nullptr && nn0 < p.next_K4;
+    const int sn = lower ? p.next_ashift[nn0 >> p.next_gs_log2] : 4;
+    const float lo = 128.0f - (float)(8 << sn), hi = 127.0f + (float)(8 << sn);   // (position 4: the whole int8 range)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         yv[i] = __builtin_fmaf((float)s[i], cs4[i], bi4[i]);
-        // offset form, as in the tiled kernel: round to nearest-even, saturate to 0..255, flip the top bit
-        qw = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf((float)s[i], cs4[i] * p.r_out, bi4[i] * p.r_out + 128.0f), i, qw);
+        // offset form, as in the tiled kernel: round to nearest-even, saturate to 0..255, flip the top bit; for a consumer's
+        // 4-bit channel the offset code is clamped first (integer bounds: the same as clamping the rounded code)
+        qw = __builtin_amdgcn_cvt_pk_u8_f32(
+            __builtin_amdgcn_fmed3f(__builtin_fmaf((float)s[i], cs4[i] * p.r_out, bi4[i] * p.r_out + 128.0f), lo, hi), i, qw);
     }
     qw ^= 0x80808080u;
+    if (lower) qw &= 0x01010101u * ((0xFFu << sn) & 0xFFu);
     if ((p.N & 3) == 0) {   // four whole columns, aligned rows
         if (p.acc) *reinterpret_cast<v4i *>(p.acc + o) = s;
         if (p.y) *reinterpret_cast<float4 *>(p.y + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
@@ -439,8 +450,14 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
     if (p.y) p.y[o] = __builtin_fmaf((float)v, c, b);
     if (p.q) {
         // offset form, as in the tiled kernel: round to nearest-even, saturate to 0..255, flip the top bit
-        const float t = __builtin_fmaf((float)v, c * p.r_out, b * p.r_out + 128.0f);
-        p.q[o] = (int8_t)(__builtin_amdgcn_cvt_pk_u8_f32(t, 0, 0u) ^ 0x80u);
+        // (for a 4-bit channel of the consumer named by lower_for: clamped and masked at its position, as in k_few_rows)
+        const bool lower = p.next_ashift != nullptr && nn < p.next_K4;
+        const int sn = lower ? p.next_ashift[nn >> p.next_gs_log2] : 4;
+        const float t = __builtin_amdgcn_fmed3f(__builtin_fmaf((float)v, c * p.r_out, b * p.r_out + 128.0f), 128.0f - (float)(8 << sn),
+                                                127.0f + (float)(8 << sn));
+        uint32_t code = __builtin_amdgcn_cvt_pk_u8_f32(t, 0, 0u) ^ 0x80u;
+        if (lower) code &= (0xFFu << sn) & 0xFFu;
+        p.q[o] = (int8_t)code;
     }
 }
 
@@ -453,13 +470,14 @@ static int g_last_rows = 0;
 // Launches k_few_rows (*taken = 1) or k_few_rows_dot (*taken = 2) for a linear call with at most 64 rows; *taken = 0: the call
 // was left to the other kernels.
 int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,
-                    const uint8_t *X4)
+                    const uint8_t *X4, const LowerArgs *lower)
 {
     using namespace smallm;
     *taken = 0;
     g_last_rows = 0;
     if (g_force_rows == 0 || M < 1 || M > 64) return FLEXIQ_OK;
-    if (out->lower_for || out->scan_for || out->x4 || out->x6) return FLEXIQ_OK;
+    if (out->scan_for || out->x4 || out->x6) return FLEXIQ_OK;
+    if (out->lower_for && !lower) return FLEXIQ_OK;   // (the caller has checked the consumer; null positions: nothing to lower)
     if ((reinterpret_cast<uintptr_t>(X) & 15u) || (L->C & 15)) return FLEXIQ_OK;   // 16-byte activation pieces
     // Every block reads all activation rows: with more than 16 rows that traffic (blocks x M x C bytes through the compute
     // units' 64 B/clk path) decides, and beyond about one block per compute unit the tiled kernel's 64 x 64 tiles win
@@ -478,6 +496,7 @@ int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const fle
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.steps = (p.units + 1) / 2;
     p.w4x_delta = L->U * 32 * L->Npad;
+    if (lower && lower->ashift) { p.next_ashift = lower->ashift; p.next_K4 = lower->K4; p.next_gs_log2 = lower->gs_log2; }
     // packed activation codes of the leading whole K-steps of 4-bit channels (the caller has checked alignment): the dot-product
     // kernel takes them as they are; the matrix-core kernel has no use for them and leaves such a call to the tiled kernel
     p.X4 = X4 && !L->x_prelowered ? X4 : nullptr;
