@@ -206,6 +206,26 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
             fq.flexiq_mixed_gemm(l1, X1, q=True, out_scale=so1, bufs=mid, lower_for=l2)
             fq.flexiq_mixed_gemm(l2, mid["q"], q=True, out_scale=so1, bufs=fin)
 
+        # the same chain with 16 rows (few-row kernels): consumer lowers on the fly against producer lowers for the consumer
+        X16 = X1[:16].contiguous()
+        mid16 = {"q": mid["q"][:16]}
+        fin16 = {"q": fin["q"][:16]}
+
+        def few_plain():
+            fq.flexiq_mixed_gemm(l1, X16, q=True, out_scale=so1, bufs=mid16)
+            fq.flexiq_mixed_gemm(l2, mid16["q"], q=True, out_scale=so1, bufs=fin16)
+
+        def few_lowered():
+            fq.flexiq_mixed_gemm(l1, X16, q=True, out_scale=so1, bufs=mid16, lower_for=l2)
+            fq.flexiq_mixed_gemm(l2, mid16["q"], q=True, out_scale=so1, bufs=fin16)
+
+        wl16 = "vitl fc1 -> fc2 chain, M=16 rows (few-row kernels)"
+        by16 = c1.N * c1.K + c2.N * c2.K + 16 * (c1.K + 2 * c1.N + c2.N)
+        rec(wl16, "int8 kernels, consumer lowers on the fly", r, _median_graph_us(torch, few_plain, 10), byts=by16)
+        fq.flexiq_input_prelowered(l2, True)
+        rec(wl16, "int8 kernels, producer lowers for the consumer", r, _median_graph_us(torch, few_lowered, 10), byts=by16)
+        fq.flexiq_input_prelowered(l2, False)
+
         x6_1, xlow_1 = fq.flexiq_lower_fp6(l1, X1)
 
         def chain_fp6():
