@@ -36,6 +36,12 @@ int flexiq_debug_last_launch(int which);
  * flexiq_mixed_gemm_fp6 takes for at most 64 rows unless an FP6 tile shape is forced or mode is 0). */
 int flexiq_debug_force_few_rows(int mode);
 
+/* The kernel that gives a block one output tile and splits the reduction over its waves (linear calls of more than 64 rows with
+ * few tiles and a long reduction; last launch: tile shape index -5): 1 = take it whenever the call qualifies (whatever the
+ * tile count and reduction length), 2 / 3 / 4 = the same with tiles of 64 x 64 / 32 x 64 / 32 x 32 (rows x columns), 0 = never,
+ * -1 = automatic.  Returns the tile the last call it was offered ran on (1 / 2 / 3 in that order; 0: another kernel). */
+int flexiq_debug_force_tile_splitk(int mode);
+
 /* The row-streaming kernels for layers with 64, 128 or 256 input channels (last launch: tile shape index -2):
  * 1 / 2 = take the one whose blocks walk tiles of 128 rows / the one whose waves walk groups of 32 rows on their own,
  * whenever the layer form qualifies (whatever the row count), 0 = never, -1 = automatic.  Returns which of them the

@@ -79,6 +79,7 @@ def load():
     L.flexiq_debug_force_fp6_tile.argtypes = [C.c_int]
     L.flexiq_debug_force_stream.argtypes = [C.c_int]
     L.flexiq_debug_force_few_rows.argtypes = [C.c_int]
+    L.flexiq_debug_force_tile_splitk.argtypes = [C.c_int]
     L.flexiq_debug_force_conv3.argtypes = [C.c_int, C.c_int]
     L.flexiq_debug_force_tile.argtypes = [C.c_int]
     L.flexiq_debug_force_packed4.argtypes = [C.c_int]
@@ -413,6 +414,15 @@ def debug_force_stream(mode: int) -> int:
     """Row-streaming kernels: 1 / 2 = the one whose blocks walk tiles / whose waves walk row groups, whenever the layer form
     qualifies; 0 = never; -1 = automatic.  Returns which of them the last call ran on (0: neither)."""
     rc = load().flexiq_debug_force_stream(int(mode))
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def debug_force_tile_splitk(mode: int) -> int:
+    """The 64 x 64 tile kernel whose waves split the reduction: 1 = whenever the call qualifies, 0 = never, -1 = automatic.
+    Returns whether the last call it was offered ran on it."""
+    rc = load().flexiq_debug_force_tile_splitk(int(mode))
     if rc < 0:
         _check(rc)
     return rc

@@ -78,6 +78,10 @@ struct LowerArgs {
     int32_t K4 = 0, gs_log2 = 5;
 };
 int lower_for_args(const flexiq_layer *L, const flexiq_out *out, LowerArgs *la);
+// (smallm.hip) linear calls of more than 64 rows with few 64 x 64 tiles and a long reduction: a tile per block, the reduction
+// split over its waves; *taken = 0: the call does not qualify
+int launch_tile_splitk(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,
+                       const LowerArgs *lower = nullptr);
 // (smallm.hip) linear calls with at most 64 rows: a block per 16 (or 8) output columns whose waves split the reduction
 // and meet in LDS; *taken = 0: the call does not qualify.  X4: a producer's packed activation codes; lower: flexiq_out.lower_for
 int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,

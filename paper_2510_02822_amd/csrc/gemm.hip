@@ -226,6 +226,20 @@ static int launch(const flexiq_layer *L, const int8_t *X, int64_t M, const flexi
             return FLEXIQ_OK;
         }
     }
+    // More rows, few output tiles, a long reduction: a tile per block whose waves split the reduction (smallm.hip).
+    if (!conv && !xp && M > 16 && g_force_shape < 0 && g_force_packed < 0 && g_max_blocks == 0) {
+        int taken = 0;
+        LowerArgs la;
+        la.ashift = p.next_ashift; la.K4 = p.next_K4; la.gs_log2 = p.next_gs_log2;   // (checked above)
+        const int rc = launch_tile_splitk(L, X, M, out, stream, dk.num_cu, &taken, &la);
+        if (rc != FLEXIQ_OK) return rc;
+        if (taken) {
+            g_last_shape = -5;
+            g_last_blocks = (int)(((M + (taken == 1 ? 63 : 31)) / (taken == 1 ? 64 : 32)) * ((L->N + (taken == 3 ? 31 : 63)) / (taken == 3 ? 32 : 64)));
+            g_last_resident = 0;
+            return FLEXIQ_OK;
+        }
+    }
     // Few-row linear calls: a block per 16 output columns, the reduction split over its waves (smallm.hip).  Measured against
     // the tiled kernel, which launches 16-64 blocks of 64 x 64 here: faster for every call of at most 16 rows, and up to 64
     // rows as long as there is at most one block per compute unit or so (every block reads all activation rows).

@@ -461,6 +461,135 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
     }
 }
 
+// ---- Calls of 65 rows to about a thousand on layers with few output tiles: a 64 x 64 tile per block, the reduction split
+// over its waves.
+//
+// The tiled kernel gives such a call a handful of 64 x 64 blocks that each walk the whole reduction, one barrier per
+// K-step: bound by the latency of a step (ViT-L fc2 with 197 rows: 64 steps, 14.6 us at r = 0 and 22.1 us at r = 1 for
+// 0.3 us of matrix work).  Here the eight waves of a block take the K-steps wave, wave + 8, ... of the tile on their own:
+// operands straight from global memory into MFMA registers (every byte of the tile's weights and activations is loaded by
+// exactly one lane of the block), sixteen v_mfma_i32_16x16x64_i8 per K-step and wave, no barrier until the waves' sums
+// meet in LDS.  4-bit units come from the position-expanded weight copy and their activations are lowered in registers.
+// FR x FC: 16 x 16 fragments of the tile (rows x columns), NW: waves.  A smaller tile means more blocks, i.e. more compute
+// units pulling operands, at more operand bytes per multiply.
+template <int FR, int FC, int NW, int UN>
+__global__ __launch_bounds__(64 * NW) void k_tile_splitk(const RowsParams p)
+{
+    constexpr int kTileRows = 16 * FR, kTileCols = 16 * FC, kTileWaves = NW, NF = FR * FC;
+    constexpr int E = (NF + NW - 1) / NW;   // fragments a wave finishes: wave, wave + NW, ...
+    extern __shared__ __align__(16) unsigned char lds[];   // [waves][fragments][64 lanes] accumulator quads
+    v4i *const red = reinterpret_cast<v4i *>(lds);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 15, qd = lane >> 4;
+    const int n0 = blockIdx.x * kTileCols;      // columns n0 + 16 g + c < Npad: the weight tiles are padded
+    const int m0 = blockIdx.y * kTileRows;
+
+    // the epilogue's scales and biases travel with the first operands
+    // (fragment id = FC f + g: rows m0 + 16 f + c, columns n0 + 16 g + 4 qd + i)
+    float cs4[E][4], bi4[E][4];
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int nn = n0 + 16 * ((wave + NW * e) % FC) + 4 * qd + i;   // < Npad
+            cs4[e][i] = p.cs[nn];
+            bi4[e][i] = p.cs[p.Npad + nn];
+        }
+
+    v4i acc[FR][FC];
+#pragma unroll
+    for (int f = 0; f < FR; ++f)
+#pragma unroll
+        for (int g = 0; g < FC; ++g) acc[f][g] = (v4i){0, 0, 0, 0};
+
+    // UN K-steps in flight per wave
+    for (int ks0 = wave; ks0 < p.steps; ks0 += kTileWaves * UN) {
+        v4i w8[UN][FC], x[UN][FR];
+        int sa[UN];
+        bool low[UN];
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            const int ks = ks0 + k * kTileWaves;
+            const int u = 2 * ks + (qd >> 1), h = qd & 1;   // this lane's unit and k-half
+            const bool valid = ks < p.steps && u < p.units;
+            low[k] = valid && u < p.units4;
+            sa[k] = low[k] && !p.x_pre ? p.ashift[u >> p.gs_shift] : 0;
+#pragma unroll
+            for (int g = 0; g < FC; ++g)
+                w8[k][g] = valid ? *reinterpret_cast<const v4i *>(p.W8 + (low[k] ? p.w4x_delta : 0) + (((int64_t)u * 2 + h) * p.Npad + n0 + 16 * g + c) * 16)
+                                 : (v4i){0, 0, 0, 0};
+#pragma unroll
+            for (int f = 0; f < FR; ++f) {
+                const int m = m0 + 16 * f + c;
+                x[k][f] = valid && m < p.M ? *reinterpret_cast<const v4i *>(p.X + (int64_t)m * p.C + u * 32 + 16 * h) : (v4i){0, 0, 0, 0};
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            if (low[k] && !p.x_pre) {
+#pragma unroll
+                for (int f = 0; f < FR; ++f)
+                    x[k][f] = (v4i){(int)lower4((uint32_t)x[k][f].x, sa[k]), (int)lower4((uint32_t)x[k][f].y, sa[k]),
+                                    (int)lower4((uint32_t)x[k][f].z, sa[k]), (int)lower4((uint32_t)x[k][f].w, sa[k])};
+            }
+#pragma unroll
+            for (int f = 0; f < FR; ++f)
+#pragma unroll
+                for (int g = 0; g < FC; ++g) acc[f][g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w8[k][g], x[k][f], acc[f][g], 0, 0, 0);
+        }
+    }
+
+    // ---- the waves' sums meet in LDS; wave w adds up and finishes fragments w, w + NW, ...
+#pragma unroll
+    for (int f = 0; f < FR; ++f)
+#pragma unroll
+        for (int g = 0; g < FC; ++g) red[(wave * NF + FC * f + g) * 64 + lane] = acc[f][g];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int id = wave + NW * e, f = id / FC, g = id % FC;
+        if (id >= NF) break;
+        v4i s = {0, 0, 0, 0};
+#pragma unroll
+        for (int w = 0; w < kTileWaves; ++w) s += red[(w * NF + id) * 64 + lane];
+        const int m = m0 + 16 * f + c, nn0 = n0 + 16 * g + 4 * qd;
+        if (m >= p.M || nn0 >= p.N) continue;
+        const int64_t o = (int64_t)m * p.N + nn0;
+        float yv[4];
+        uint32_t qw = 0;
+        const bool lower = p.next_ashift != nullptr && nn0 < p.next_K4;   // (as in k_few_rows)
+        const int sn = lower ? p.next_ashift[nn0 >> p.next_gs_log2] : 4;
+        const float lo = 128.0f - (float)(8 << sn), hi = 127.0f + (float)(8 << sn);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            yv[i] = __builtin_fmaf((float)s[i], cs4[e][i], bi4[e][i]);
+            qw = __builtin_amdgcn_cvt_pk_u8_f32(
+                __builtin_amdgcn_fmed3f(__builtin_fmaf((float)s[i], cs4[e][i] * p.r_out, bi4[e][i] * p.r_out + 128.0f), lo, hi), i, qw);
+        }
+        qw ^= 0x80808080u;
+        if (lower) qw &= 0x01010101u * ((0xFFu << sn) & 0xFFu);
+        if ((p.N & 3) == 0) {
+            if (p.acc) *reinterpret_cast<v4i *>(p.acc + o) = s;
+            if (p.y) *reinterpret_cast<float4 *>(p.y + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
+            if (p.q) *reinterpret_cast<uint32_t *>(p.q + o) = qw;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (nn0 + i >= p.N) continue;
+                if (p.acc) p.acc[o + i] = s[i];
+                if (p.y) p.y[o + i] = yv[i];
+                if (p.q) p.q[o + i] = (int8_t)(qw >> (8 * i));
+            }
+        }
+    }
+}
+
+static int g_force_tile_splitk = -1;   // test hook: 1 = take k_tile_splitk whenever the call qualifies, 0 = never, -1 = automatic
+static int g_last_tile_splitk = 0;
+static bool g_tile_splitk_ready[64] = {};
+constexpr int kTileMinRows = 32;   // up to here the few-row kernels measure faster
+
 static int g_force_cg = 0;      // test hook: column groups per block of k_few_rows_dot (0 = automatic)
 static int g_force_rows = -1;   // test hook: 1 / 2 = take k_few_rows / k_few_rows_dot whenever the call qualifies, 0 = never, -1 = automatic
 static int g_last_rows = 0;
@@ -590,6 +719,60 @@ int launch_few_rows_fp6(const flexiq_layer *L, const int8_t *X, const uint8_t *X
     return FLEXIQ_OK;
 }
 
+// Launches k_tile_splitk for a linear call of more than 64 rows whose 64 x 64 tiles leave most compute units idle on a long
+// reduction; *taken = 0: the call was left to the tiled kernel.
+int launch_tile_splitk(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,
+                       const LowerArgs *lower)
+{
+    using namespace smallm;
+    *taken = 0;
+    g_last_tile_splitk = 0;
+    if (g_force_tile_splitk == 0 || M <= 16 || M > 0x7fffffff / 2) return FLEXIQ_OK;
+    // (calls of at most 64 rows: the few-row hook, in any forced state, keeps this kernel out of its comparisons)
+    if (M <= 64 && (g_force_rows >= 0 || (g_force_tile_splitk < 0 && M <= kTileMinRows))) return FLEXIQ_OK;
+    if (out->scan_for || out->x4 || out->x6 || (out->lower_for && !lower)) return FLEXIQ_OK;
+    if ((reinterpret_cast<uintptr_t>(X) & 15u) || (L->C & 15) || L->device < 0 || L->device >= 64) return FLEXIQ_OK;
+    const int steps = (L->C / kUnit + 1) / 2;
+    auto tiles_of = [&](int tr, int tc) { return ((M + tr - 1) / tr) * (int64_t)((L->N + tc - 1) / tc); };
+    // Where it measures faster than the tiled kernel: at most about one 64 x 64 tile per compute unit and a reduction of at
+    // least 12 K-steps for the waves to split.  The tile shrinks while the blocks would leave half the compute units idle.
+    if (g_force_tile_splitk < 0 && (tiles_of(64, 64) > (int64_t)num_cu || steps < 12)) return FLEXIQ_OK;
+    int shape = g_force_tile_splitk >= 2 ? g_force_tile_splitk - 2 : tiles_of(64, 64) * 2 > num_cu ? 0 : tiles_of(32, 64) * 2 > num_cu ? 1 : 2;
+    if (shape > 2) return FLEXIQ_EINVAL;
+    const int tr = shape == 0 ? 64 : 32, tc = shape == 2 ? 32 : 64;
+    if (tiles_of(tr, tc) > 0x7fffffff || (M + tr - 1) / tr > 65535) return FLEXIQ_OK;
+    const size_t lds = shape == 2 ? 64 * 1024 : 128 * 1024;   // waves x fragments x 1 KB
+    if (!g_tile_splitk_ready[L->device]) {
+        FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<4, 4, 8, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+        FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 4, 16, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+        FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 2, 16, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+        g_tile_splitk_ready[L->device] = true;
+    }
+    RowsParams p = {};
+    p.X = X; p.W8 = L->d_w8;
+    p.ashift = L->dynamic ? L->d_ashift_dyn : L->d_ashift;
+    p.cs = L->d_cs;
+    p.acc = out->acc; p.y = out->y; p.q = out->q;
+    p.r_out = out->q ? 1.0f / out->out_scale : 1.0f;
+    p.M = (int)M; p.N = L->N; p.Npad = L->Npad; p.C = L->C;
+    p.units = L->C / kUnit;
+    p.units4 = L->max_4bit_ch / kUnit;
+    p.x_pre = L->x_prelowered ? 1 : 0;
+    p.gs_shift = L->group_size == 64 ? 1 : 0;
+    p.steps = steps;
+    p.w4x_delta = L->U * 32 * L->Npad;
+    if (lower && lower->ashift) { p.next_ashift = lower->ashift; p.next_K4 = lower->K4; p.next_gs_log2 = lower->gs_log2; }
+    const dim3 grid((unsigned)((L->N + tc - 1) / tc), (unsigned)((M + tr - 1) / tr));
+    if (shape == 0) hipLaunchKernelGGL((k_tile_splitk<4, 4, 8, 2>), grid, dim3(512), lds, (hipStream_t)stream, p);
+    else if (shape == 1) hipLaunchKernelGGL((k_tile_splitk<2, 4, 16, 2>), grid, dim3(1024), lds, (hipStream_t)stream, p);
+    else hipLaunchKernelGGL((k_tile_splitk<2, 2, 16, 4>), grid, dim3(1024), lds, (hipStream_t)stream, p);
+    FLEXIQ_HIP(hipGetLastError());
+    *taken = 1 + shape;
+    g_last_tile_splitk = 1 + shape;
+    g_last_rows = 0;
+    return FLEXIQ_OK;
+}
+
 }  // namespace flexiq
 
 extern "C" int flexiq_debug_force_few_rows(int mode)
@@ -604,4 +787,11 @@ extern "C" int flexiq_debug_force_few_rows(int mode)
     if (mode < -1 || mode > 2) return FLEXIQ_EINVAL;
     flexiq::smallm::g_force_rows = mode;
     return flexiq::smallm::g_last_rows;
+}
+
+extern "C" int flexiq_debug_force_tile_splitk(int mode)
+{
+    if (mode < -1 || mode > 4) return FLEXIQ_EINVAL;
+    flexiq::smallm::g_force_tile_splitk = mode;
+    return flexiq::smallm::g_last_tile_splitk;
 }

@@ -135,3 +135,48 @@ def test_few_rows_lower_for_consumer(env, M, K1, N1, N2, gs2, kernel):
     finally:
         fq.debug_force_few_rows(-1)
         fq.flexiq_input_prelowered(h2, False)
+
+
+@pytest.mark.parametrize("M,K,N,gs", [(65, 1024, 72, 64), (197, 2112, 520, 64), (130, 96, 64, 32), (300, 1024, 1030, 32), (64 * 3, 256, 7, 32)])
+@pytest.mark.parametrize("shape", [2, 3, 4])
+def test_tile_splitk_kernel(env, M, K, N, gs, shape):
+    # more than 64 rows on a layer with few output tiles: a tile per block (64 x 64, 32 x 64, 32 x 32), the reduction split over
+    # its waves (ragged last row and column tiles, an odd unit count, a half 4-bit K-step, fewer K-steps than waves)
+    torch, oracle, fq, dev = env
+    case = workloads.make_linear("tilesplit", 8, 1000 + M + K + N, M, K, N, gs, outlier_frac=0.02)
+    case.X *= 2.0
+    ol, hl, x_scale = both_layers(case)
+    Xq = np.ascontiguousarray(oracle.quantize(case.X, x_scale)[:, ol.perm])
+    Xd = torch.from_numpy(Xq).to(dev)
+    G = K // gs
+    fq.debug_force_tile_splitk(shape)
+    try:
+        for r in sorted({0.0, 1.0 / G, 0.5, 1.0}):
+            fq.flexiq_set_ratio(hl, r)
+            ref = oracle.forward_gemm(ol, Xq, r)
+            so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
+            out = fq.flexiq_mixed_gemm(hl, Xd, acc=True, y=True, q=True, out_scale=so)
+            torch.cuda.synchronize()
+            assert fq.debug_force_tile_splitk(shape) == shape - 1 and fq.debug_last_launch()["tile"] == -5   # ran on this kernel, this tile
+            assert (out["acc"].cpu().numpy() == ref).all(), r
+            check_y(out["y"].cpu().numpy(), ref, ol)
+            got_q = out["q"].cpu().numpy()
+            check_q(got_q, ref, ol, so)
+            assert (got_q == requant_fp32_sequence(ref, ol, so)).all()
+            fq.debug_force_tile_splitk(0)
+            tiled = fq.flexiq_mixed_gemm(hl, Xd, q=True, out_scale=so)["q"]       # the tiled kernel gives the same bytes
+            assert fq.debug_last_launch()["tile"] >= 0 or fq.debug_last_launch()["tile"] == -2
+            fq.debug_force_tile_splitk(shape)
+            assert (tiled.cpu().numpy() == got_q).all(), r
+        # activations that arrive lowered
+        k4 = fq.flexiq_set_ratio(hl, 0.5)
+        sh = np.repeat(ol.a_shift.astype(np.int32), gs)[None, :k4]
+        Xl = Xq.astype(np.int32).copy()
+        Xl[:, :k4] = np.clip(Xl[:, :k4] >> sh, -8, 7) << sh
+        fq.flexiq_input_prelowered(hl, True)
+        got = fq.flexiq_mixed_gemm(hl, torch.from_numpy(Xl.astype(np.int8)).to(dev), acc=True)["acc"].cpu().numpy()
+        assert fq.debug_last_launch()["tile"] == -5
+        assert (got == oracle.forward_gemm(ol, Xq, 0.5)).all()
+    finally:
+        fq.flexiq_input_prelowered(hl, False)
+        fq.debug_force_tile_splitk(-1)
