@@ -256,24 +256,27 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
             fq.flexiq_static_positions(l2)
     del l1, l2, mid, fin, x6_2
 
-    # ---- few-row calls (weight streaming): ViT-L layers with M in {1, 16, 64}
+    # ---- calls of few rows (weight streaming) and of one image's tokens: ViT-L layers with M in {1, 16, 64, 197}
     for name in ("vitl_fc1", "vitl_fc2"):
         case, layer, Xq, so, _ = packed[name]
-        for Ms in (1, 16, 64):
+        for Ms in (1, 16, 64, 197):
             Xs = Xq[:Ms].contiguous()
             bufs = {"q": torch.empty((Ms, case.N), dtype=torch.int8, device=dev)}
             for r in (0.0, 0.5, 1.0):
                 fq.flexiq_set_ratio(layer, r)
-                for tag, force in (("tiled kernel", 0), ("few-row kernel (automatic route)", -1)):
+                for tag, force in (("tiled kernel", 0), ("automatic route", -1)):
                     fq.debug_force_few_rows(force)
+                    fq.debug_force_tile_splitk(force)
                     us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=so, bufs=bufs), 20)
                     launch = fq.debug_last_launch()
-                    # (of the two few-row kernels only the dot-product one streams the packed 4-bit codes)
+                    # (of the few-row kernels only the dot-product one streams the packed 4-bit codes)
                     route = "w4" if launch["tile"] == -4 and fq.debug_force_few_rows(force) == 2 else "w4x"
-                    rec("%s weights %d x %d, M=%d rows" % (name, case.N, case.K, Ms), "few-row call, " + tag, r, us,
+                    kern = {-4: ": few-row kernel", -5: ": tile per block, reduction split over its waves"}.get(launch["tile"], "")
+                    rec("%s weights %d x %d, M=%d rows" % (name, case.N, case.K, Ms), "%s call, %s%s" % ("few-row" if Ms <= 64 else "one-image", tag, kern), r, us,
                         byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, route), launch=launch)
                 fq.debug_force_few_rows(-1)
-                if Ms >= 16:   # the FP6 variant of the 4-bit phase on the few-row kernel (activations packed by the producer)
+                fq.debug_force_tile_splitk(-1)
+                if 16 <= Ms <= 64:   # the FP6 variant of the 4-bit phase on the few-row kernel (activations packed by the producer)
                     x6, xlow = fq.flexiq_lower_fp6(layer, Xs)
                     us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm_fp6(layer, xlow, x6, q=True, out_scale=so, bufs=bufs), 20)
                     k6 = fq.flexiq_fp6_channels(layer)
@@ -470,7 +473,7 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
     return out
 
 
-PROFILE_TARGETS = ("vitl_fc2", "vitl_fc2_fp6", "vitl_fc2_fp6_rows64", "vitl_fc2_rows16", "vitl_fc2_rows1", "stream_rows1", "reorder", "resnet_1x1_64_256", "resnet_3x3_64_64",
+PROFILE_TARGETS = ("vitl_fc2", "vitl_fc2_fp6", "vitl_fc2_fp6_rows64", "vitl_fc2_rows16", "vitl_fc2_rows197", "vitl_fc2_rows1", "stream_rows1", "reorder", "resnet_1x1_64_256", "resnet_3x3_64_64",
                    "resnet_1x1_256_64", "resnet_1x1_256_64_packed4")
 
 
@@ -498,13 +501,13 @@ def profile_only(torch, fq, workloads, dev, what, launches):
         layer = fq.flexiq_quantize_pack(case.W, amax, x_scale, case.group_size, bias=case.bias)
         Xn = fq.flexiq_quantize_act(torch.from_numpy(case.X).to(dev), x_scale)
         Xq = fq.flexiq_permute_channels(layer, Xn)
-        rows = {"vitl_fc2_rows16": 16, "vitl_fc2_rows1": 1, "stream_rows1": 1, "vitl_fc2_fp6_rows64": 64}.get(what, case.M)
+        rows = {"vitl_fc2_rows16": 16, "vitl_fc2_rows1": 1, "stream_rows1": 1, "vitl_fc2_fp6_rows64": 64, "vitl_fc2_rows197": 197}.get(what, case.M)
         Xs = Xq[:rows].contiguous()
         q = {"q": torch.empty((rows, case.N), dtype=torch.int8, device=dev)}
         res["workload"] = "%s M=%d K=%d N=%d gs=%d" % (case.name, rows, case.K, case.N, case.group_size)
         if what == "vitl_fc2":
             call = lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=0.05, bufs=q)
-        elif what in ("vitl_fc2_rows16", "vitl_fc2_rows1", "stream_rows1"):   # few-row calls: the matrix-core resp. the dot-product kernel
+        elif what in ("vitl_fc2_rows16", "vitl_fc2_rows1", "stream_rows1", "vitl_fc2_rows197"):   # few-row calls (the matrix-core resp. the dot-product kernel), one image's tokens
             call = lambda: fq.flexiq_mixed_gemm(layer, Xs, q=True, out_scale=0.05, bufs=q)
         elif what == "reorder":
             call = lambda: fq.flexiq_permute_channels(layer, Xn)
