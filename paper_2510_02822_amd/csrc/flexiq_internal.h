@@ -82,6 +82,8 @@ int lower_for_args(const flexiq_layer *L, const flexiq_out *out, LowerArgs *la);
 // split over its waves; *taken = 0: the call does not qualify
 int launch_tile_splitk(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,
                        const LowerArgs *lower = nullptr);
+int launch_tile_splitk_fp6(const flexiq_layer *L, const int8_t *X, const uint8_t *X6, int64_t M, const flexiq_out *out, void *stream, int K6,
+                           int num_cu, int *taken);
 // (smallm.hip) linear calls with at most 64 rows: a block per 16 (or 8) output columns whose waves split the reduction
 // and meet in LDS; *taken = 0: the call does not qualify.  X4: a producer's packed activation codes; lower: flexiq_out.lower_for
 int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,

@@ -107,6 +107,15 @@ extern "C" int flexiq_mixed_gemm_fp6(const flexiq_layer *L, const int8_t *X, con
     // call, and the int8 kernels (more tile shapes, blocks that walk tiles) serve it faster than this kernel's int8 phase
     // (ViT-L fc2 at r = 0: 41 against 50 us).  Not when the caller wants FP6 output for a consumer, which only this kernel writes.
     if (L->max_4bit_ch == 0 && !out->x6 && g_force_shape < 0) return flexiq_mixed_gemm(L, X, M, out, stream);
+    if (M > 16 && g_force_shape < 0) {   // few output tiles, a long reduction: a tile per block whose waves split the reduction (smallm.hip)
+        int taken = 0;
+        const int rc = launch_tile_splitk_fp6(L, X, X6, M, out, stream, K6, g_dev[dev].num_cu, &taken);
+        if (rc != FLEXIQ_OK) return rc;
+        if (taken) {
+            g_last_shape = -5;
+            return FLEXIQ_OK;
+        }
+    }
     if (M <= 64 && g_force_shape < 0) {   // few rows: a block per 16 columns whose waves split the reduction (smallm.hip)
         int taken = 0;
         const int rc = launch_few_rows_fp6(L, X, X6, M, out, stream, K6, g_dev[dev].num_cu, &taken);

@@ -472,7 +472,10 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
 // meet in LDS.  4-bit units come from the position-expanded weight copy and their activations are lowered in registers.
 // FR x FC: 16 x 16 fragments of the tile (rows x columns), NW: waves.  A smaller tile means more blocks, i.e. more compute
 // units pulling operands, at more operand bytes per multiply.
-template <int FR, int FC, int NW, int UN>
+// FP6: the leading s6 K-steps run first on `v_mfma_scale_f32_16x16x128_f8f6f4`, as in the FP6 build of k_few_rows (chunks of
+// two K-steps dealt to the waves in turn; a lane holds the 32 codes of one unit and its block scale), every other K-step as
+// usual with activations that arrive lowered.
+template <int FR, int FC, int NW, int UN, bool FP6 = false>
 __global__ __launch_bounds__(64 * NW) void k_tile_splitk(const RowsParams p)
 {
     constexpr int kTileRows = 16 * FR, kTileCols = 16 * FC, kTileWaves = NW, NF = FR * FC;
@@ -503,8 +506,67 @@ __global__ __launch_bounds__(64 * NW) void k_tile_splitk(const RowsParams p)
 #pragma unroll
         for (int g = 0; g < FC; ++g) acc[f][g] = (v4i){0, 0, 0, 0};
 
+    int first = wave;
+    if constexpr (FP6) {
+        const int chunks = (p.s6 + 1) >> 1, S = p.C >> 6;
+        v4f accf[FR][FC];
+#pragma unroll
+        for (int f = 0; f < FR; ++f)
+#pragma unroll
+            for (int g = 0; g < FC; ++g) accf[f][g] = (v4f){0.f, 0.f, 0.f, 0.f};
+        constexpr int U6 = UN >= 4 ? 2 : 1;   // chunks in flight
+        for (int c0 = wave; c0 < chunks; c0 += NW * U6) {
+            v4i wlo[U6][FC], xlo[U6][FR];
+            v2i whi[U6][FC], xhi[U6][FR];
+            int wsc[U6][FC], asc[U6];
+#pragma unroll
+            for (int k = 0; k < U6; ++k) {
+                const int ks = 2 * (c0 + k * NW) + (qd >> 1), h = qd & 1;   // this lane's K-step and unit
+                const bool ok = ks < p.s6;
+                asc[k] = ok ? 130 + p.ashift[(2 * ks + h) >> p.gs_shift] : 127;   // 2^(position + 3): the codes are k / 8
+#pragma unroll
+                for (int g = 0; g < FC; ++g) {
+                    const int n = n0 + 16 * g + c;
+                    wlo[k][g] = (v4i){0, 0, 0, 0};
+                    whi[k][g] = (v2i){0, 0};
+                    wsc[k][g] = 127;
+                    if (ok) {
+                        wlo[k][g] = *reinterpret_cast<const v4i *>(p.W6 + (((int64_t)ks * 3 + h) * p.Npad + n) * 16);
+                        whi[k][g] = *reinterpret_cast<const v2i *>(p.W6 + (((int64_t)ks * 3 + 2) * p.Npad + n) * 16 + 8 * (h ^ ((n >> 4) & 1)));
+                        wsc[k][g] = p.W6S[((int64_t)(ks >> 2) * p.Npad + n) * 8 + 4 * h + (ks & 3)];
+                    }
+                }
+#pragma unroll
+                for (int f = 0; f < FR; ++f) {
+                    const int m = m0 + 16 * f + c, blk = m >> 6, r = m & 63;
+                    xlo[k][f] = (v4i){0, 0, 0, 0};
+                    xhi[k][f] = (v2i){0, 0};
+                    if (ok && m < p.M) {
+                        xlo[k][f] = *reinterpret_cast<const v4i *>(p.X6 + ((((int64_t)blk * S + ks) * 3 + h) * 64 + r) * 16);
+                        xhi[k][f] = *reinterpret_cast<const v2i *>(p.X6 + ((((int64_t)blk * S + ks) * 3 + 2) * 64 + r) * 16 + 8 * (h ^ ((r >> 4) & 1)));
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < U6; ++k)
+#pragma unroll
+                for (int f = 0; f < FR; ++f)
+#pragma unroll
+                    for (int g = 0; g < FC; ++g)
+                        accf[f][g] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                            (v8i){wlo[k][g].x, wlo[k][g].y, wlo[k][g].z, wlo[k][g].w, whi[k][g].x, whi[k][g].y, 0, 0},
+                            (v8i){xlo[k][f].x, xlo[k][f].y, xlo[k][f].z, xlo[k][f].w, xhi[k][f].x, xhi[k][f].y, 0, 0}, accf[f][g], 2, 2, 0,
+                            wsc[k][g], 0, asc[k]);
+        }
+#pragma unroll
+        for (int f = 0; f < FR; ++f)
+#pragma unroll
+            for (int g = 0; g < FC; ++g)
+                acc[f][g] = (v4i){(int)accf[f][g].x, (int)accf[f][g].y, (int)accf[f][g].z, (int)accf[f][g].w};   // exact integers below 2^24
+        first = p.s6 + (wave + NW - chunks % NW) % NW;   // the int8 K-steps continue the deal
+    }
     // UN K-steps in flight per wave
-    for (int ks0 = wave; ks0 < p.steps; ks0 += kTileWaves * UN) {
+    for (int ks0 = first; ks0 < p.steps; ks0 += kTileWaves * UN) {
         v4i w8[UN][FC], x[UN][FR];
         int sa[UN];
         bool low[UN];
@@ -719,10 +781,8 @@ int launch_few_rows_fp6(const flexiq_layer *L, const int8_t *X, const uint8_t *X
     return FLEXIQ_OK;
 }
 
-// Launches k_tile_splitk for a linear call of more than 64 rows whose 64 x 64 tiles leave most compute units idle on a long
-// reduction; *taken = 0: the call was left to the tiled kernel.
-int launch_tile_splitk(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,
-                       const LowerArgs *lower)
+static int launch_tile_any(const flexiq_layer *L, const int8_t *X, const uint8_t *X6, int K6, int64_t M, const flexiq_out *out, void *stream,
+                           int num_cu, int *taken, const LowerArgs *lower)
 {
     using namespace smallm;
     *taken = 0;
@@ -746,6 +806,9 @@ int launch_tile_splitk(const flexiq_layer *L, const int8_t *X, int64_t M, const 
         FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<4, 4, 8, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
         FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 4, 16, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
         FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 2, 16, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+        FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<4, 4, 8, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+        FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 4, 8, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+        FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 2, 16, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
         g_tile_splitk_ready[L->device] = true;
     }
     RowsParams p = {};
@@ -757,13 +820,19 @@ int launch_tile_splitk(const flexiq_layer *L, const int8_t *X, int64_t M, const 
     p.M = (int)M; p.N = L->N; p.Npad = L->Npad; p.C = L->C;
     p.units = L->C / kUnit;
     p.units4 = L->max_4bit_ch / kUnit;
-    p.x_pre = L->x_prelowered ? 1 : 0;
+    p.x_pre = L->x_prelowered || X6 ? 1 : 0;   // (FP6 calls: the 4-bit channels beyond the FP6 ones arrive lowered)
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.steps = steps;
     p.w4x_delta = L->U * 32 * L->Npad;
     if (lower && lower->ashift) { p.next_ashift = lower->ashift; p.next_K4 = lower->K4; p.next_gs_log2 = lower->gs_log2; }
     const dim3 grid((unsigned)((L->N + tc - 1) / tc), (unsigned)((M + tr - 1) / tr));
-    if (shape == 0) hipLaunchKernelGGL((k_tile_splitk<4, 4, 8, 2>), grid, dim3(512), lds, (hipStream_t)stream, p);
+    if (X6) {
+        p.X6 = X6; p.W6 = L->d_w6; p.W6S = L->d_w6s;
+        p.s6 = K6 / 64;
+        if (shape == 0) hipLaunchKernelGGL((k_tile_splitk<4, 4, 8, 2, true>), grid, dim3(512), lds, (hipStream_t)stream, p);
+        else if (shape == 1) hipLaunchKernelGGL((k_tile_splitk<2, 4, 8, 4, true>), grid, dim3(512), lds / 2, (hipStream_t)stream, p);   // (eight waves: registers)
+        else hipLaunchKernelGGL((k_tile_splitk<2, 2, 16, 4, true>), grid, dim3(1024), lds, (hipStream_t)stream, p);
+    } else if (shape == 0) hipLaunchKernelGGL((k_tile_splitk<4, 4, 8, 2>), grid, dim3(512), lds, (hipStream_t)stream, p);
     else if (shape == 1) hipLaunchKernelGGL((k_tile_splitk<2, 4, 16, 2>), grid, dim3(1024), lds, (hipStream_t)stream, p);
     else hipLaunchKernelGGL((k_tile_splitk<2, 2, 16, 4>), grid, dim3(1024), lds, (hipStream_t)stream, p);
     FLEXIQ_HIP(hipGetLastError());
@@ -771,6 +840,23 @@ int launch_tile_splitk(const flexiq_layer *L, const int8_t *X, int64_t M, const 
     g_last_tile_splitk = 1 + shape;
     g_last_rows = 0;
     return FLEXIQ_OK;
+}
+
+// Launches k_tile_splitk for a linear call of more than 32 rows whose output tiles leave most compute units idle on a long
+// reduction; *taken = 0: the call was left to the other kernels, else 1 / 2 / 3: tiles of 64 x 64 / 32 x 64 / 32 x 32.
+int launch_tile_splitk(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,
+                       const LowerArgs *lower)
+{
+    return launch_tile_any(L, X, nullptr, 0, M, out, stream, num_cu, taken, lower);
+}
+
+// The same for the FP6 variant of the 4-bit phase: X holds the lowered activations, X6 the FP6 codes of the leading K6 channels.
+int launch_tile_splitk_fp6(const flexiq_layer *L, const int8_t *X, const uint8_t *X6, int64_t M, const flexiq_out *out, void *stream, int K6,
+                           int num_cu, int *taken)
+{
+    *taken = 0;
+    if (out->lower_for || !X6 || K6 < 0 || (K6 & 63)) return FLEXIQ_OK;
+    return launch_tile_any(L, X, X6, K6, M, out, stream, num_cu, taken, nullptr);
 }
 
 }  // namespace flexiq

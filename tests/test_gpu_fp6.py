@@ -233,6 +233,7 @@ def test_fp6_few_rows(env, K, N, gs):
     ol, hl, x_scale = both_layers(case)
     Xq_all = oracle.quantize(case.X, x_scale)[:, ol.perm]
     G = K // gs
+    fq.debug_force_few_rows(1)   # (beyond 32 rows the automatic route may prefer the kernel that gives a block a whole tile)
     try:
         for M in (1, 7, 16, 17, 33, 48, 64):
             Xq = np.ascontiguousarray(Xq_all[:M])
@@ -245,10 +246,8 @@ def test_fp6_few_rows(env, K, N, gs):
                 fq.debug_force_fp6_tile(-1)
                 out = fq.flexiq_mixed_gemm_fp6(hl, xlow, x6, acc=True, y=True, q=True, out_scale=so)
                 torch.cuda.synchronize()
-                # the few-row kernel's FP6 build ran (with no 4-bit channel at all the call is an ordinary int8 call, which
-                # beyond 32 rows may go to the kernel that gives a block a whole tile)
-                ran = fq.debug_force_few_rows(-1)
-                assert ran == (3 if r > 0 else (2 if M <= 2 else 1)) or (r == 0 and M > 32 and ran == 0 and fq.debug_last_launch()["tile"] == -5), (M, r)
+                # the few-row kernel's FP6 build ran (with no 4-bit channel at all the call is an ordinary int8 call)
+                assert fq.debug_force_few_rows(1) == (3 if r > 0 else 1), (M, r)
                 assert (out["acc"].cpu().numpy() == ref).all(), (M, r)
                 check_y(out["y"].cpu().numpy(), ref, ol)
                 got_q = out["q"].cpu().numpy()
@@ -259,3 +258,38 @@ def test_fp6_few_rows(env, K, N, gs):
                 assert (tiled.cpu().numpy() == got_q).all(), (M, r)
     finally:
         fq.debug_force_fp6_tile(-1)
+        fq.debug_force_few_rows(-1)
+
+
+@pytest.mark.parametrize("shape", [2, 3, 4])
+@pytest.mark.parametrize("K,N,gs", [(1024, 520, 64), (192, 72, 32), (4096, 100, 64), (2112, 48, 64)])
+def test_fp6_tile_splitk(env, K, N, gs, shape):
+    # tens to hundreds of rows on a layer with few output tiles: a tile per block (64 x 64, 32 x 64, 32 x 32), the reduction
+    # split over its waves, the FP6 K-steps first (an odd number of them leaves half a chunk; fewer chunks than waves), ratios
+    # that leave 4-bit groups outside the FP6 prefix; ragged last row and column tiles
+    torch, oracle, fq, dev = env
+    case = workloads.make_linear("fp6tile", 8, 900 + K + N, 197, K, N, gs, outlier_frac=0.02)
+    case.X *= 2.0
+    ol, hl, x_scale = both_layers(case)
+    Xq_all = oracle.quantize(case.X, x_scale)[:, ol.perm]
+    G = K // gs
+    fq.debug_force_tile_splitk(shape)
+    try:
+        for M in (33, 65, 197):
+            Xq = np.ascontiguousarray(Xq_all[:M])
+            Xd = _dev(torch, Xq, dev)
+            for r in sorted({1.0 / G, 0.5, 3.0 / G if G >= 3 else 1.0, 1.0}):
+                fq.flexiq_set_ratio(hl, r)
+                ref = oracle.forward_gemm(ol, Xq, r)
+                so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9) or 1.0
+                x6, xlow = fq.flexiq_lower_fp6(hl, Xd)
+                out = fq.flexiq_mixed_gemm_fp6(hl, xlow, x6, acc=True, y=True, q=True, out_scale=so)
+                torch.cuda.synchronize()
+                assert fq.debug_force_tile_splitk(shape) == shape - 1, (M, r)     # ran on this kernel, this tile
+                assert (out["acc"].cpu().numpy() == ref).all(), (M, r)
+                check_y(out["y"].cpu().numpy(), ref, ol)
+                got_q = out["q"].cpu().numpy()
+                check_q(got_q, ref, ol, so)
+                assert (got_q == requant_fp32_sequence(ref, ol, so)).all()
+    finally:
+        fq.debug_force_tile_splitk(-1)
