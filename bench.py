@@ -226,6 +226,34 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
         rec(wl16, "int8 kernels, producer lowers for the consumer", r, _median_graph_us(torch, few_lowered, 10), byts=by16)
         fq.flexiq_input_prelowered(l2, False)
 
+        # the same chain on one image's tokens (197 rows: a tile per block, the reduction split over its waves)
+        X197 = X1[:197].contiguous()
+        mid197 = {"q": torch.empty((197, c1.N), dtype=torch.int8, device=dev)}
+        fin197 = {"q": torch.empty((197, c2.N), dtype=torch.int8, device=dev)}
+        x6_197 = torch.empty(fq.flexiq_fp6_bytes(l2, 197), dtype=torch.uint8, device=dev)
+        x6_a, xlow_a = fq.flexiq_lower_fp6(l1, X197)
+
+        def img_plain():
+            fq.flexiq_mixed_gemm(l1, X197, q=True, out_scale=so1, bufs=mid197)
+            fq.flexiq_mixed_gemm(l2, mid197["q"], q=True, out_scale=so1, bufs=fin197)
+
+        def img_lowered():
+            fq.flexiq_mixed_gemm(l1, X197, q=True, out_scale=so1, bufs=mid197, lower_for=l2)
+            fq.flexiq_mixed_gemm(l2, mid197["q"], q=True, out_scale=so1, bufs=fin197)
+
+        def img_fp6():
+            fq.flexiq_mixed_gemm_fp6(l1, xlow_a, x6_a, q=True, out_scale=so1, bufs=mid197, lower_for=l2, x6_out=x6_197)
+            fq.flexiq_mixed_gemm_fp6(l2, mid197["q"], x6_197, q=True, out_scale=so1, bufs=fin197)
+
+        wl197 = "vitl fc1 -> fc2 chain, M=197 rows (one image)"
+        by197 = c1.N * c1.K + c2.N * c2.K + 197 * (c1.K + 2 * c1.N + c2.N)
+        rec(wl197, "int8 kernels, consumer lowers on the fly", r, _median_graph_us(torch, img_plain, 10), byts=by197)
+        fq.flexiq_input_prelowered(l2, True)
+        rec(wl197, "int8 kernels, producer lowers for the consumer", r, _median_graph_us(torch, img_lowered, 10), byts=by197)
+        fq.flexiq_input_prelowered(l2, False)
+        rec(wl197, "FP6 variant, producer packs the consumer's FP6 activations", r, _median_graph_us(torch, img_fp6, 10), byts=by197)
+        del x6_a, xlow_a, x6_197
+
         x6_1, xlow_1 = fq.flexiq_lower_fp6(l1, X1)
 
         def chain_fp6():
@@ -276,11 +304,12 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
                         byts=algorithmic_bytes(Ms, case.N, case.K, r, 1, route), launch=launch)
                 fq.debug_force_few_rows(-1)
                 fq.debug_force_tile_splitk(-1)
-                if 16 <= Ms <= 64:   # the FP6 variant of the 4-bit phase on the few-row kernel (activations packed by the producer)
+                if Ms >= 16:   # the FP6 variant of the 4-bit phase (activations packed by the producer)
                     x6, xlow = fq.flexiq_lower_fp6(layer, Xs)
                     us = _median_graph_us(torch, lambda: fq.flexiq_mixed_gemm_fp6(layer, xlow, x6, q=True, out_scale=so, bufs=bufs), 20)
                     k6 = fq.flexiq_fp6_channels(layer)
-                    rec("%s weights %d x %d, M=%d rows" % (name, case.N, case.K, Ms), "few-row call, FP6 variant of the 4-bit phase (few-row kernel)", r, us,
+                    kern = "tile per block, reduction split over its waves" if fq.debug_force_tile_splitk(-1) > 0 else ("few-row kernel" if Ms <= 64 else "tiled FP6 kernel")
+                    rec("%s weights %d x %d, M=%d rows" % (name, case.N, case.K, Ms), "%s call, FP6 variant of the 4-bit phase (%s)" % ("few-row" if Ms <= 64 else "one-image", kern), r, us,
                         byts=Ms * case.K + case.N * (case.K - k6 // 4) + Ms * case.N, fp6_channels=k6)
                     del x6, xlow
     packed.clear()
@@ -473,7 +502,7 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
     return out
 
 
-PROFILE_TARGETS = ("vitl_fc2", "vitl_fc2_fp6", "vitl_fc2_fp6_rows64", "vitl_fc2_rows16", "vitl_fc2_rows197", "vitl_fc2_rows1", "stream_rows1", "reorder", "resnet_1x1_64_256", "resnet_3x3_64_64",
+PROFILE_TARGETS = ("vitl_fc2", "vitl_fc2_fp6", "vitl_fc2_fp6_rows64", "vitl_fc2_fp6_rows197", "vitl_fc2_rows16", "vitl_fc2_rows197", "vitl_fc2_rows1", "stream_rows1", "reorder", "resnet_1x1_64_256", "resnet_3x3_64_64",
                    "resnet_1x1_256_64", "resnet_1x1_256_64_packed4")
 
 
@@ -501,7 +530,7 @@ def profile_only(torch, fq, workloads, dev, what, launches):
         layer = fq.flexiq_quantize_pack(case.W, amax, x_scale, case.group_size, bias=case.bias)
         Xn = fq.flexiq_quantize_act(torch.from_numpy(case.X).to(dev), x_scale)
         Xq = fq.flexiq_permute_channels(layer, Xn)
-        rows = {"vitl_fc2_rows16": 16, "vitl_fc2_rows1": 1, "stream_rows1": 1, "vitl_fc2_fp6_rows64": 64, "vitl_fc2_rows197": 197}.get(what, case.M)
+        rows = {"vitl_fc2_rows16": 16, "vitl_fc2_rows1": 1, "stream_rows1": 1, "vitl_fc2_fp6_rows64": 64, "vitl_fc2_rows197": 197, "vitl_fc2_fp6_rows197": 197}.get(what, case.M)
         Xs = Xq[:rows].contiguous()
         q = {"q": torch.empty((rows, case.N), dtype=torch.int8, device=dev)}
         res["workload"] = "%s M=%d K=%d N=%d gs=%d" % (case.name, rows, case.K, case.N, case.group_size)
@@ -515,7 +544,7 @@ def profile_only(torch, fq, workloads, dev, what, launches):
             call = None   # FP6 variant: the operands depend on the ratio
     for r in res["ratios"]:
         fq.flexiq_set_ratio(layer, r)
-        if what in ("vitl_fc2_fp6", "vitl_fc2_fp6_rows64"):
+        if what in ("vitl_fc2_fp6", "vitl_fc2_fp6_rows64", "vitl_fc2_fp6_rows197"):
             x6, xlow = fq.flexiq_lower_fp6(layer, Xs)
             call = lambda: fq.flexiq_mixed_gemm_fp6(layer, xlow, x6, q=True, out_scale=0.05, bufs=q)
         if what.endswith("_packed4"):

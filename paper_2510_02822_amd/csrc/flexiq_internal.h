@@ -76,6 +76,9 @@ int launch_few_rows_fp6(const flexiq_layer *L, const int8_t *X, const uint8_t *X
 struct LowerArgs {
     const int32_t *ashift = nullptr;
     int32_t K4 = 0, gs_log2 = 5;
+    // FP6 calls only (flexiq_out.x6, checked in fp6_gemm.hip): the consumer's FP6 activation buffer, its FP6 prefix and C / 64
+    uint8_t *x6 = nullptr;
+    int32_t K6 = 0, S = 0;
 };
 int lower_for_args(const flexiq_layer *L, const flexiq_out *out, LowerArgs *la);
 // (smallm.hip) linear calls of more than 64 rows with few 64 x 64 tiles and a long reduction: a tile per block, the reduction
@@ -83,7 +86,7 @@ int lower_for_args(const flexiq_layer *L, const flexiq_out *out, LowerArgs *la);
 int launch_tile_splitk(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,
                        const LowerArgs *lower = nullptr);
 int launch_tile_splitk_fp6(const flexiq_layer *L, const int8_t *X, const uint8_t *X6, int64_t M, const flexiq_out *out, void *stream, int K6,
-                           int num_cu, int *taken);
+                           int num_cu, int *taken, const LowerArgs *lower);
 // (smallm.hip) linear calls with at most 64 rows: a block per 16 (or 8) output columns whose waves split the reduction
 // and meet in LDS; *taken = 0: the call does not qualify.  X4: a producer's packed activation codes; lower: flexiq_out.lower_for
 int launch_few_rows(const flexiq_layer *L, const int8_t *X, int64_t M, const flexiq_out *out, void *stream, int num_cu, int *taken,

@@ -107,24 +107,6 @@ extern "C" int flexiq_mixed_gemm_fp6(const flexiq_layer *L, const int8_t *X, con
     // call, and the int8 kernels (more tile shapes, blocks that walk tiles) serve it faster than this kernel's int8 phase
     // (ViT-L fc2 at r = 0: 41 against 50 us).  Not when the caller wants FP6 output for a consumer, which only this kernel writes.
     if (L->max_4bit_ch == 0 && !out->x6 && g_force_shape < 0) return flexiq_mixed_gemm(L, X, M, out, stream);
-    if (M > 16 && g_force_shape < 0) {   // few output tiles, a long reduction: a tile per block whose waves split the reduction (smallm.hip)
-        int taken = 0;
-        const int rc = launch_tile_splitk_fp6(L, X, X6, M, out, stream, K6, g_dev[dev].num_cu, &taken);
-        if (rc != FLEXIQ_OK) return rc;
-        if (taken) {
-            g_last_shape = -5;
-            return FLEXIQ_OK;
-        }
-    }
-    if (M <= 64 && g_force_shape < 0) {   // few rows: a block per 16 columns whose waves split the reduction (smallm.hip)
-        int taken = 0;
-        const int rc = launch_few_rows_fp6(L, X, X6, M, out, stream, K6, g_dev[dev].num_cu, &taken);
-        if (rc != FLEXIQ_OK) return rc;
-        if (taken) {
-            g_last_shape = -4;
-            return FLEXIQ_OK;
-        }
-    }
     Params p = {};
     p.X = X; p.X6 = X6; p.W8 = L->d_w8; p.W6 = L->d_w6; p.W6S = L->d_w6s;
     p.ashift = L->dynamic ? L->d_ashift_dyn : L->d_ashift;
@@ -152,6 +134,28 @@ extern "C" int flexiq_mixed_gemm_fp6(const flexiq_layer *L, const int8_t *X, con
         }
     } else if (out->x6) {
         return FLEXIQ_EINVAL;   // FP6 output needs the consumer's positions
+    }
+
+    if (M > 16 && g_force_shape < 0) {   // few output tiles, a long reduction: a tile per block whose waves split the reduction (smallm.hip)
+        int taken = 0;
+        LowerArgs la;
+        la.ashift = p.next_ashift; la.K4 = p.next_K4; la.gs_log2 = p.next_gs_log2;   // (checked above; null: the call names no consumer)
+        la.x6 = p.nx6; la.K6 = p.next_K6; la.S = p.next_S;
+        const int rc = launch_tile_splitk_fp6(L, X, X6, M, out, stream, K6, g_dev[dev].num_cu, &taken, &la);
+        if (rc != FLEXIQ_OK) return rc;
+        if (taken) {
+            g_last_shape = -5;
+            return FLEXIQ_OK;
+        }
+    }
+    if (M <= 64 && g_force_shape < 0) {   // few rows: a block per 16 columns whose waves split the reduction (smallm.hip)
+        int taken = 0;
+        const int rc = launch_few_rows_fp6(L, X, X6, M, out, stream, K6, g_dev[dev].num_cu, &taken);
+        if (rc != FLEXIQ_OK) return rc;
+        if (taken) {
+            g_last_shape = -4;
+            return FLEXIQ_OK;
+        }
     }
 
     const DeviceState &ds = g_dev[dev];

@@ -79,6 +79,8 @@ struct RowsParams {
     // the codes of its 4-bit channels then leave clamped and masked at its positions (Section 4.1 applied at the producer)
     const int32_t *next_ashift;
     int32_t next_K4, next_gs_log2;
+    uint8_t *nx6;           // optional (k_tile_splitk, FP6 calls): the consumer's FP6 activation buffer; its leading next_K6 channels
+    int32_t next_K6, next_S;   //   leave as FP6 codes as well (next_S = its C / 64)
     const uint8_t *X4;      // optional (k_few_rows_dot): packed activation codes [M][C / 2] of the leading pieces_p pieces of a row
     int32_t pieces_p;       // 16-channel pieces whose codes come from X4 (a multiple of 4: whole K-steps)
 };
@@ -620,14 +622,36 @@ __global__ __launch_bounds__(64 * NW) void k_tile_splitk(const RowsParams p)
         const int64_t o = (int64_t)m * p.N + nn0;
         float yv[4];
         uint32_t qw = 0;
-        const bool lower = p.next_ashift != nullptr && nn0 < p.next_K4;   // (as in k_few_rows)
-        const int sn = lower ? p.next_ashift[nn0 >> p.next_gs_log2] : 4;
+        // the consumer's 4-bit channels (as in k_few_rows): those of its FP6 prefix leave clamped in q and as FP6 codes in its
+        // activation buffer, the others clamped and masked in q
+        const bool to6 = FP6 && p.nx6 != nullptr && nn0 < p.next_K6;
+        const bool lower = p.next_ashift != nullptr && !to6 && nn0 < p.next_K4;
+        const int sn = lower || to6 ? p.next_ashift[nn0 >> p.next_gs_log2] : 4;
         const float lo = 128.0f - (float)(8 << sn), hi = 127.0f + (float)(8 << sn);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             yv[i] = __builtin_fmaf((float)s[i], cs4[e][i], bi4[e][i]);
             qw = __builtin_amdgcn_cvt_pk_u8_f32(
                 __builtin_amdgcn_fmed3f(__builtin_fmaf((float)s[i], cs4[e][i] * p.r_out, bi4[e][i] * p.r_out + 128.0f), lo, hi), i, qw);
+        }
+        if (to6) {
+            // four codes (offset form u = code + 128, clamped above): floor(code / 2^sn) + 8 = (u >> sn) - ((128 >> sn) - 8), 0 .. 15 per
+            // byte; E2M3 pattern of L / 8: sign << 5 | |L|.  Element 16 a + 4 b + i of a unit is its channel 8 b + 4 a + i (the order of the
+            // packed FP6 weights), so the 24 bits are bytes 3 j .. 3 j + 2 of the unit's 24 with j = 4 a + b:
+            // the first 16 bytes of a unit lie in plane (unit % 2) of the consumer's K-step, the last 8 in plane 2
+            const uint32_t cb = ((qw >> sn) & (0x01010101u * (0xFFu >> sn))) - 0x01010101u * (uint32_t)((128 >> sn) - 8);
+            const uint32_t neg = (~cb >> 3) & 0x01010101u;
+            const uint32_t mag = ((cb & 0x07070707u) ^ (neg * 7u)) + neg;
+            const uint32_t c6 = mag | (neg << 5);
+            const uint32_t w24 = (c6 & 0x3Fu) | ((c6 >> 2) & 0xFC0u) | ((c6 >> 4) & 0x3F000u) | ((c6 >> 6) & 0xFC0000u);
+            const int u = nn0 >> 5, hh = u & 1, rr = m & 63, j = 4 * ((nn0 >> 2) & 1) + ((nn0 & 31) >> 3);
+            uint8_t *const blk = p.nx6 + ((int64_t)(m >> 6) * p.next_S + (u >> 1)) * 3072;
+#pragma unroll
+            for (int b = 0; b < 3; ++b) {
+                const int byte = 3 * j + b;
+                uint8_t *const d = byte < 16 ? blk + hh * 1024 + rr * 16 + byte : blk + 2048 + rr * 16 + 8 * (hh ^ ((rr >> 4) & 1)) + byte - 16;
+                *d = (uint8_t)(w24 >> (8 * b));
+            }
         }
         qw ^= 0x80808080u;
         if (lower) qw &= 0x01010101u * ((0xFFu << sn) & 0xFFu);
@@ -790,7 +814,8 @@ static int launch_tile_any(const flexiq_layer *L, const int8_t *X, const uint8_t
     if (g_force_tile_splitk == 0 || M <= 16 || M > 0x7fffffff / 2) return FLEXIQ_OK;
     // (calls of at most 64 rows: the few-row hook, in any forced state, keeps this kernel out of its comparisons)
     if (M <= 64 && (g_force_rows >= 0 || (g_force_tile_splitk < 0 && M <= kTileMinRows))) return FLEXIQ_OK;
-    if (out->scan_for || out->x4 || out->x6 || (out->lower_for && !lower)) return FLEXIQ_OK;
+    if (out->scan_for || out->x4 || (out->lower_for && !lower)) return FLEXIQ_OK;
+    if (out->x6 && !(X6 && lower && lower->x6 == out->x6 && (L->N & 63) == 0 && (lower->K6 & 63) == 0)) return FLEXIQ_OK;   // FP6 output: FP6 calls only
     if ((reinterpret_cast<uintptr_t>(X) & 15u) || (L->C & 15) || L->device < 0 || L->device >= 64) return FLEXIQ_OK;
     const int steps = (L->C / kUnit + 1) / 2;
     auto tiles_of = [&](int tr, int tc) { return ((M + tr - 1) / tr) * (int64_t)((L->N + tc - 1) / tc); };
@@ -824,7 +849,10 @@ static int launch_tile_any(const flexiq_layer *L, const int8_t *X, const uint8_t
     p.gs_shift = L->group_size == 64 ? 1 : 0;
     p.steps = steps;
     p.w4x_delta = L->U * 32 * L->Npad;
-    if (lower && lower->ashift) { p.next_ashift = lower->ashift; p.next_K4 = lower->K4; p.next_gs_log2 = lower->gs_log2; }
+    if (lower && lower->ashift) {
+        p.next_ashift = lower->ashift; p.next_K4 = lower->K4; p.next_gs_log2 = lower->gs_log2;
+        if (X6 && lower->x6) { p.nx6 = lower->x6; p.next_K6 = lower->K6; p.next_S = lower->S; }
+    }
     const dim3 grid((unsigned)((L->N + tc - 1) / tc), (unsigned)((M + tr - 1) / tr));
     if (X6) {
         p.X6 = X6; p.W6 = L->d_w6; p.W6S = L->d_w6s;
@@ -852,11 +880,11 @@ int launch_tile_splitk(const flexiq_layer *L, const int8_t *X, int64_t M, const 
 
 // The same for the FP6 variant of the 4-bit phase: X holds the lowered activations, X6 the FP6 codes of the leading K6 channels.
 int launch_tile_splitk_fp6(const flexiq_layer *L, const int8_t *X, const uint8_t *X6, int64_t M, const flexiq_out *out, void *stream, int K6,
-                           int num_cu, int *taken)
+                           int num_cu, int *taken, const LowerArgs *lower)
 {
     *taken = 0;
-    if (out->lower_for || !X6 || K6 < 0 || (K6 & 63)) return FLEXIQ_OK;
-    return launch_tile_any(L, X, X6, K6, M, out, stream, num_cu, taken, nullptr);
+    if (!X6 || K6 < 0 || (K6 & 63)) return FLEXIQ_OK;
+    return launch_tile_any(L, X, X6, K6, M, out, stream, num_cu, taken, lower);
 }
 
 }  // namespace flexiq

@@ -208,8 +208,22 @@ def test_fp6_two_layer_chain(env):
                 fq.debug_force_fp6_tile(-1)
                 got = fq.flexiq_mixed_gemm_fp6(h2, mid, x6_2, acc=True)["acc"].cpu().numpy()
                 assert (got == oracle.forward_gemm(o2, X2, r2)).all(), (r2, t)
+            # the same from the kernel that gives a block one tile and splits the reduction over its waves (three tile shapes)
+            for shape in (2, 3, 4):
+                fq.debug_force_tile_splitk(shape)
+                x6_2 = torch.zeros(fq.flexiq_fp6_bytes(h2, M), dtype=torch.uint8, device=dev)
+                mid = fq.flexiq_mixed_gemm_fp6(h1, xlow_1, x6_1, q=True, out_scale=s_mid, lower_for=h2, x6_out=x6_2)["q"]
+                torch.cuda.synchronize()
+                assert fq.debug_force_tile_splitk(-1) == shape - 1, (r2, shape)
+                got_mid = mid.cpu().numpy().astype(np.int32)
+                assert (got_mid[:, k6:] == want_mid[:, k6:]).all(), (r2, shape)
+                codes = _decode_x6(x6_2.cpu().numpy(), M, N1, k6)
+                assert (codes == np.clip(X2[:, :k6].astype(np.int32) >> sh[:, :k6], -8, 7)).all(), (r2, shape)
+                got = fq.flexiq_mixed_gemm_fp6(h2, mid, x6_2, acc=True)["acc"].cpu().numpy()
+                assert (got == oracle.forward_gemm(o2, X2, r2)).all(), (r2, shape)
     finally:
         fq.debug_force_fp6_tile(-1)
+        fq.debug_force_tile_splitk(-1)
     # refused: a consumer whose order the producer does not write; FP6 output without a consumer; C not a multiple of 64
     h1_plain = fq.flexiq_quantize_pack(c1.W, am1, xs1, gs, bias=c1.bias)
     fq.flexiq_set_ratio(h1_plain, r1)
