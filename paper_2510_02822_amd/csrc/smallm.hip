@@ -117,6 +117,8 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
             bi4[i] = p.cs[p.Npad + n0 + 4 * qd + i];
         }
     }
+    // ... and so does the consumer's position of these four columns (flexiq_out.lower_for; 4: no 4-bit channels of a consumer)
+    const int sn_pre = wave < MF && p.next_ashift != nullptr && n0 + 4 * qd < p.next_K4 ? p.next_ashift[(n0 + 4 * qd) >> p.next_gs_log2] : 4;
 
     v4i acc[MF];
 #pragma unroll
@@ -260,7 +262,7 @@ __global__ __launch_bounds__(1024) void k_few_rows(const RowsParams p)
     uint32_t qw = 0;
     // the consumer's position for these four columns (one channel group of the consumer: nn0 is a multiple of four)
     const bool lower = p.next_ashift != nullptr && nn0 < p.next_K4;
-    const int sn = lower ? p.next_ashift[nn0 >> p.next_gs_log2] : 4;
+    const int sn = sn_pre;
     const float lo = 128.0f - (float)(8 << sn), hi = 127.0f + (float)(8 << sn);   // (position 4: the whole int8 range)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -328,6 +330,8 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
         cs_e = p.cs[n0 + tid % BC];
         bi_e = p.cs[p.Npad + n0 + tid % BC];
     }
+    // ... and so does the consumer's position of that column (flexiq_out.lower_for; 4: no 4-bit channel of a consumer)
+    const int sn_e = tid < MR * BC && p.next_ashift != nullptr && n0 + tid % BC < p.next_K4 ? p.next_ashift[(n0 + tid % BC) >> p.next_gs_log2] : 4;
     constexpr int UN = CG == 4 ? 2 : 4;   // wave loads in flight per wave and column group
     v4i w8[UN][CG];
     v2i w4[UN][CG];
@@ -454,7 +458,7 @@ __global__ __launch_bounds__(512) void k_few_rows_dot(const RowsParams p)
         // offset form, as in the tiled kernel: round to nearest-even, saturate to 0..255, flip the top bit
         // (for a 4-bit channel of the consumer named by lower_for: clamped and masked at its position, as in k_few_rows)
         const bool lower = p.next_ashift != nullptr && nn < p.next_K4;
-        const int sn = lower ? p.next_ashift[nn >> p.next_gs_log2] : 4;
+        const int sn = sn_e;
         const float t = __builtin_amdgcn_fmed3f(__builtin_fmaf((float)v, c * p.r_out, b * p.r_out + 128.0f), 128.0f - (float)(8 << sn),
                                                 127.0f + (float)(8 << sn));
         uint32_t code = __builtin_amdgcn_cvt_pk_u8_f32(t, 0, 0u) ^ 0x80u;
@@ -501,6 +505,15 @@ __global__ __launch_bounds__(64 * NW) void k_tile_splitk(const RowsParams p)
             cs4[e][i] = p.cs[nn];
             bi4[e][i] = p.cs[p.Npad + nn];
         }
+    // ... and so does the consumer's position of the lane's four columns (flexiq_out.lower_for): those of its FP6 prefix leave
+    // clamped in q and as FP6 codes in its activation buffer, its other 4-bit channels clamped and masked in q
+    int sn_e[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int nn0 = n0 + 16 * ((wave + NW * e) % FC) + 4 * qd;
+        const bool to6 = FP6 && p.nx6 != nullptr && nn0 < p.next_K6;
+        sn_e[e] = p.next_ashift != nullptr && (to6 || nn0 < p.next_K4) ? p.next_ashift[nn0 >> p.next_gs_log2] : 4;
+    }
 
     v4i acc[FR][FC];
 #pragma unroll
@@ -622,11 +635,9 @@ __global__ __launch_bounds__(64 * NW) void k_tile_splitk(const RowsParams p)
         const int64_t o = (int64_t)m * p.N + nn0;
         float yv[4];
         uint32_t qw = 0;
-        // the consumer's 4-bit channels (as in k_few_rows): those of its FP6 prefix leave clamped in q and as FP6 codes in its
-        // activation buffer, the others clamped and masked in q
         const bool to6 = FP6 && p.nx6 != nullptr && nn0 < p.next_K6;
         const bool lower = p.next_ashift != nullptr && !to6 && nn0 < p.next_K4;
-        const int sn = lower || to6 ? p.next_ashift[nn0 >> p.next_gs_log2] : 4;
+        const int sn = sn_e[e];
         const float lo = 128.0f - (float)(8 << sn), hi = 127.0f + (float)(8 << sn);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -646,11 +657,14 @@ __global__ __launch_bounds__(64 * NW) void k_tile_splitk(const RowsParams p)
             const uint32_t w24 = (c6 & 0x3Fu) | ((c6 >> 2) & 0xFC0u) | ((c6 >> 4) & 0x3F000u) | ((c6 >> 6) & 0xFC0000u);
             const int u = nn0 >> 5, hh = u & 1, rr = m & 63, j = 4 * ((nn0 >> 2) & 1) + ((nn0 & 31) >> 3);
             uint8_t *const blk = p.nx6 + ((int64_t)(m >> 6) * p.next_S + (u >> 1)) * 3072;
-#pragma unroll
-            for (int b = 0; b < 3; ++b) {
-                const int byte = 3 * j + b;
-                uint8_t *const d = byte < 16 ? blk + hh * 1024 + rr * 16 + byte : blk + 2048 + rr * 16 + 8 * (hh ^ ((rr >> 4) & 1)) + byte - 16;
-                *d = (uint8_t)(w24 >> (8 * b));
+            // (one 2-byte and one 1-byte store: the even one of 3 j and 3 j + 1 starts the pair, which never straddles bytes 15 | 16)
+            auto at = [&](int byte) { return byte < 16 ? blk + hh * 1024 + rr * 16 + byte : blk + 2048 + rr * 16 + 8 * (hh ^ ((rr >> 4) & 1)) + byte - 16; };
+            if (j & 1) {
+                *at(3 * j) = (uint8_t)w24;
+                *reinterpret_cast<uint16_t *>(at(3 * j + 1)) = (uint16_t)(w24 >> 8);
+            } else {
+                *reinterpret_cast<uint16_t *>(at(3 * j)) = (uint16_t)w24;
+                *at(3 * j + 2) = (uint8_t)(w24 >> 16);
             }
         }
         qw ^= 0x80808080u;
