@@ -130,3 +130,34 @@ def test_weight_streaming_few_rows(env):
             assert fq.debug_force_few_rows(-1) == (2 if M <= 2 or (M == 4 and r >= 0.5) else 1), (M, r)   # which kernel ran
             assert (out["acc"].cpu().numpy() == ref[:M]).all(), (M, r)
             check_q(out["q"].cpu().numpy(), ref[:M], ol, so)
+
+
+@pytest.mark.parametrize("which", ["fc1", "fc2"])
+def test_one_image_vitl(env, which):
+    # bench.py's one-image calls (the 197 tokens of one image on the ViT-L linear layers) in the launch configuration it times: the
+    # automatic route (a tile per block, the reduction split over its waves), int8 and FP6 builds, whole outputs against the oracle
+    torch, oracle, fq, dev = env
+    case = workloads.config3(which)
+    x_scale, amax = calib(case)
+    ol = oracle.prepare_layer(case.W, amax, x_scale, case.group_size, bias=case.bias)
+    hl = fq.flexiq_quantize_pack(case.W, amax, x_scale, case.group_size, bias=case.bias)
+    assert (hl.info()["perm"] == ol.perm).all()
+    Xq = np.ascontiguousarray(oracle.quantize(case.X[:197], x_scale)[:, ol.perm])
+    Xd = torch.from_numpy(Xq).to(dev)
+    for r in (0.0, 0.5, 1.0):
+        fq.flexiq_set_ratio(hl, r)
+        ref = oracle.forward_gemm(ol, Xq, r)
+        so = float(np.abs(oracle.dequant_f64(ref, x_scale, ol.w_scale, ol.bias)).max() / 127 * 0.9)
+        out = fq.flexiq_mixed_gemm(hl, Xd, acc=True, q=True, out_scale=so)
+        torch.cuda.synchronize()
+        assert fq.debug_last_launch()["tile"] == -5, r
+        assert (out["acc"].cpu().numpy() == ref).all(), r
+        got_q = out["q"].cpu().numpy()
+        check_q(got_q, ref, ol, so)
+        assert (got_q == requant_fp32_sequence(ref, ol, so)).all()
+        x6, xlow = fq.flexiq_lower_fp6(hl, Xd)
+        out = fq.flexiq_mixed_gemm_fp6(hl, xlow, x6, acc=True, q=True, out_scale=so)
+        torch.cuda.synchronize()
+        assert fq.debug_force_tile_splitk(-1) > 0, r
+        assert (out["acc"].cpu().numpy() == ref).all(), r
+        assert (out["q"].cpu().numpy() == got_q).all(), r
