@@ -284,10 +284,10 @@ def measure_shapes(torch, fq, workloads, dev, resnet=True):
             fq.flexiq_static_positions(l2)
     del l1, l2, mid, fin, x6_2
 
-    # ---- calls of few rows (weight streaming) and of one image's tokens: ViT-L layers with M in {1, 16, 64, 197}
-    for name in ("vitl_fc1", "vitl_fc2"):
+    # ---- calls of few rows (weight streaming) and of one image's tokens: ViT-L layers with M in {1, 16, 64, 197}, ViT-B layers with M = 197
+    for name in ("vitl_fc1", "vitl_fc2", "vitb_fc1", "vitb_fc2"):
         case, layer, Xq, so, _ = packed[name]
-        for Ms in (1, 16, 64, 197):
+        for Ms in ((1, 16, 64, 197) if name.startswith("vitl") else (197,)):
             Xs = Xq[:Ms].contiguous()
             bufs = {"q": torch.empty((Ms, case.N), dtype=torch.int8, device=dev)}
             for r in (0.0, 0.5, 1.0):
