@@ -180,3 +180,48 @@ def test_tile_splitk_kernel(env, M, K, N, gs, shape):
     finally:
         fq.flexiq_input_prelowered(hl, False)
         fq.debug_force_tile_splitk(-1)
+
+
+@pytest.mark.parametrize("M,K1,N1,N2,gs2", [(100, 1024, 520, 128, 32), (197, 256, 136, 64, 32), (33, 2048, 256, 24, 64)])
+@pytest.mark.parametrize("shape", [2, 3, 4])
+def test_tile_splitk_lower_for_consumer(env, M, K1, N1, N2, gs2, shape):
+    # the fused producer on the tile-per-block kernel: int8 rows in the consumer's stored channel order with its 4-bit channels
+    # clamped and masked at its positions (ragged column tiles; a consumer group size of 64); the consumer, told so, reads them
+    torch, oracle, fq, dev = env
+    helpers = __import__("helpers")
+    N1 = (N1 // gs2) * gs2
+    c1 = workloads.make_linear("tilelow1", 8, 950 + M + N1, M, K1, N1, 32, outlier_frac=0.02)
+    c2 = workloads.make_linear("tilelow2", 8, 951 + M + N1, M, N1, N2, gs2, outlier_frac=0.02)
+    xs1, am1 = helpers.calib(c1)
+    o1 = oracle.prepare_layer(c1.W, am1, xs1, 32, bias=c1.bias)
+    Xq = np.ascontiguousarray(oracle.quantize(c1.X, xs1)[:, o1.perm])
+    acc1 = oracle.forward_gemm(o1, Xq, 0.5)
+    s_mid = float(np.abs(oracle.dequant_f64(acc1, xs1, o1.w_scale, o1.bias)).max() / 127.0 * 0.8) or 1.0   # some codes clip
+    q1 = requant_fp32_sequence(acc1, o1, s_mid)
+    check_q(q1, acc1, o1, s_mid)
+    am2 = np.abs(q1).max(0).astype(np.float32) * np.float32(s_mid) * np.float32(0.5) + np.float32(1e-6)   # too narrow: the clamp bites
+    o2 = oracle.prepare_layer(c2.W, am2, s_mid, gs2, bias=c2.bias)
+    h2 = fq.flexiq_quantize_pack(c2.W, am2, s_mid, gs2, bias=c2.bias)
+    h1 = fq.flexiq_quantize_pack(c1.W, am1, xs1, 32, bias=c1.bias, out_perm=o2.perm)
+    X2 = np.ascontiguousarray(q1[:, o2.perm])
+    fq.flexiq_set_ratio(h1, 0.5)
+    Xd = torch.from_numpy(Xq).to(dev)
+    sh = np.repeat(o2.a_shift.astype(np.int32), gs2)
+    G2 = N1 // gs2
+    try:
+        for r2 in sorted({0.0, 1.0 / G2, 0.5, 1.0}):
+            k4 = fq.flexiq_set_ratio(h2, r2)
+            want = X2.astype(np.int32).copy()
+            want[:, :k4] = np.clip(want[:, :k4] >> sh[:k4], -8, 7) << sh[:k4]
+            fq.debug_force_tile_splitk(shape)
+            low = fq.flexiq_mixed_gemm(h1, Xd, q=True, out_scale=s_mid, lower_for=h2)["q"]
+            torch.cuda.synchronize()
+            assert fq.debug_last_launch()["tile"] == -5 and fq.debug_force_tile_splitk(-1) == shape - 1, r2
+            assert (low.cpu().numpy().astype(np.int32) == want).all(), r2
+            fq.flexiq_input_prelowered(h2, True)
+            got = fq.flexiq_mixed_gemm(h2, low, acc=True)["acc"].cpu().numpy()
+            fq.flexiq_input_prelowered(h2, False)
+            assert (got == oracle.forward_gemm(o2, X2, r2)).all(), r2
+    finally:
+        fq.debug_force_tile_splitk(-1)
+        fq.flexiq_input_prelowered(h2, False)
