@@ -33,13 +33,16 @@ int flexiq_debug_last_launch(int which);
  * whenever the call qualifies, 2 = the dot-product kernel (at most 4 rows) whenever it qualifies (14: with 4 groups of 8 columns per
  * block where the layer's padding allows), 0 = never, -1 = automatic.
  * Returns which of them the last call they were offered ran on (0: neither; 3: the matrix-core kernel's FP6 build, which
- * flexiq_mixed_gemm_fp6 takes for at most 64 rows unless an FP6 tile shape is forced or mode is 0). */
+ * flexiq_mixed_gemm_fp6 takes for at most 64 rows unless an FP6 tile shape is forced or mode is 0).  While mode is not -1,
+ * calls of at most 64 rows are also kept off the kernel of flexiq_debug_force_tile_splitk (so that 0 means "the tiled kernel"). */
 int flexiq_debug_force_few_rows(int mode);
 
 /* The kernel that gives a block one output tile and splits the reduction over its waves (linear calls of more than 64 rows with
  * few tiles and a long reduction; last launch: tile shape index -5): 1 = take it whenever the call qualifies (whatever the
  * tile count and reduction length), 2 / 3 / 4 = the same with tiles of 64 x 64 / 32 x 64 / 32 x 32 (rows x columns), 0 = never,
- * -1 = automatic.  Returns the tile the last call it was offered ran on (1 / 2 / 3 in that order; 0: another kernel). */
+ * -1 = automatic (more than 32 rows, at most one 64 x 64 tile per compute unit, at least 12 K-steps of 64 channels).  Serves
+ * flexiq_mixed_gemm and flexiq_mixed_gemm_fp6 (FP6 build; forced FP6 tile shapes go first), from 17 rows when forced.
+ * Returns the tile the last call it was offered ran on (1 / 2 / 3 in that order; 0: another kernel). */
 int flexiq_debug_force_tile_splitk(int mode);
 
 /* The row-streaming kernels for layers with 64, 128 or 256 input channels (last launch: tile shape index -2):
