@@ -41,7 +41,8 @@ int flexiq_debug_force_few_rows(int mode);
  * few tiles and a long reduction; last launch: tile shape index -5): 1 = take it whenever the call qualifies (whatever the
  * tile count and reduction length), 2 / 3 / 4 = the same with tiles of 64 x 64 / 32 x 64 / 32 x 32 (rows x columns), 0 = never,
  * -1 = automatic (more than 32 rows, at most one 64 x 64 tile per compute unit, at least 12 K-steps of 64 channels).  Serves
- * flexiq_mixed_gemm and flexiq_mixed_gemm_fp6 (FP6 build; forced FP6 tile shapes go first), from 17 rows when forced.
+ * flexiq_mixed_gemm and flexiq_mixed_gemm_fp6 (FP6 build; forced FP6 tile shapes go first; FP6 calls with lower_for at any row
+ * count), from 17 rows when forced.
  * Returns the tile the last call it was offered ran on (1 / 2 / 3 in that order; 0: another kernel). */
 int flexiq_debug_force_tile_splitk(int mode);
 

@@ -136,7 +136,7 @@ extern "C" int flexiq_mixed_gemm_fp6(const flexiq_layer *L, const int8_t *X, con
         return FLEXIQ_EINVAL;   // FP6 output needs the consumer's positions
     }
 
-    if (M > 16 && g_force_shape < 0) {   // few output tiles, a long reduction: a tile per block whose waves split the reduction (smallm.hip)
+    if ((M > 16 || out->lower_for) && g_force_shape < 0) {   // few output tiles, a long reduction: a tile per block whose waves split the reduction (smallm.hip)
         int taken = 0;
         LowerArgs la;
         la.ashift = p.next_ashift; la.K4 = p.next_K4; la.gs_log2 = p.next_gs_log2;   // (checked above; null: the call names no consumer)

@@ -825,9 +825,11 @@ static int launch_tile_any(const flexiq_layer *L, const int8_t *X, const uint8_t
     using namespace smallm;
     *taken = 0;
     g_last_tile_splitk = 0;
-    if (g_force_tile_splitk == 0 || M <= 16 || M > 0x7fffffff / 2) return FLEXIQ_OK;
+    // FP6 calls that lower for a consumer have no few-row kernel to go to: this one takes them at any row count
+    const bool only_here = X6 && out->lower_for;
+    if (g_force_tile_splitk == 0 || M < 1 || (M <= 16 && !only_here) || M > 0x7fffffff / 2) return FLEXIQ_OK;
     // (calls of at most 64 rows: the few-row hook, in any forced state, keeps this kernel out of its comparisons)
-    if (M <= 64 && (g_force_rows >= 0 || (g_force_tile_splitk < 0 && M <= kTileMinRows))) return FLEXIQ_OK;
+    if (M <= 64 && (g_force_rows >= 0 || (g_force_tile_splitk < 0 && M <= kTileMinRows && !only_here))) return FLEXIQ_OK;
     if (out->scan_for || out->x4 || (out->lower_for && !lower)) return FLEXIQ_OK;
     if (out->x6 && !(X6 && lower && lower->x6 == out->x6 && (L->N & 63) == 0 && (lower->K6 & 63) == 0)) return FLEXIQ_OK;   // FP6 output: FP6 calls only
     if ((reinterpret_cast<uintptr_t>(X) & 15u) || (L->C & 15) || L->device < 0 || L->device >= 64) return FLEXIQ_OK;

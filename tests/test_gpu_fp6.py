@@ -307,3 +307,41 @@ def test_fp6_tile_splitk(env, K, N, gs, shape):
                 assert (got_q == requant_fp32_sequence(ref, ol, so)).all()
     finally:
         fq.debug_force_tile_splitk(-1)
+
+
+@pytest.mark.parametrize("M", [1, 5, 20, 48])
+def test_fp6_chain_few_rows(env, M):
+    # the two-layer FP6 chain on a few rows, automatic route: the producer (long reduction, few tiles) runs on the kernel that gives
+    # a block one tile and writes the consumer's FP6 codes and lowered int8 rows; the consumer reads both on a few-row kernel
+    torch, oracle, fq, dev = env
+    K1, N1, N2, gs = 1024, 256, 96, 32
+    c1 = workloads.make_linear("fp6few1", 8, 441 + M, M, K1, N1, gs, outlier_frac=0.02)
+    c2 = workloads.make_linear("fp6few2", 8, 442 + M, M, N1, N2, gs, outlier_frac=0.02)
+    xs1, am1 = calib(c1)
+    o1 = oracle.prepare_layer(c1.W, am1, xs1, gs, bias=c1.bias)
+    Xq = np.ascontiguousarray(oracle.quantize(c1.X, xs1)[:, o1.perm])
+    acc1 = oracle.forward_gemm(o1, Xq, 0.5)
+    s_mid = float(np.abs(oracle.dequant_f64(acc1, xs1, o1.w_scale, o1.bias)).max() / 127.0) or 1.0
+    q1 = requant_fp32_sequence(acc1, o1, s_mid)
+    am2 = np.abs(q1).max(0).astype(np.float32) * np.float32(s_mid) + np.float32(1e-6)
+    o2 = oracle.prepare_layer(c2.W, am2, s_mid, gs, bias=c2.bias)
+    X2 = np.ascontiguousarray(q1[:, o2.perm])
+    h2 = fq.flexiq_quantize_pack(c2.W, am2, s_mid, gs, bias=c2.bias)
+    h1 = fq.flexiq_quantize_pack(c1.W, am1, xs1, gs, bias=c1.bias, out_perm=o2.perm)
+    fq.flexiq_set_ratio(h1, 0.5)
+    x6_1, xlow_1 = fq.flexiq_lower_fp6(h1, _dev(torch, Xq, dev))
+    sh = np.repeat(o2.a_shift.astype(np.int32), gs)[None, :]
+    for r2 in (1.0, 0.625, 0.25):
+        k4 = fq.flexiq_set_ratio(h2, r2)
+        k6 = fq.flexiq_fp6_channels(h2)
+        x6_2 = torch.zeros(fq.flexiq_fp6_bytes(h2, M), dtype=torch.uint8, device=dev)
+        mid = fq.flexiq_mixed_gemm_fp6(h1, xlow_1, x6_1, q=True, out_scale=s_mid, lower_for=h2, x6_out=x6_2)["q"]
+        torch.cuda.synchronize()
+        assert fq.debug_force_tile_splitk(-1) > 0, (M, r2)
+        want_mid = X2.astype(np.int32).copy()
+        want_mid[:, :k4] = np.clip(want_mid[:, :k4] >> sh[:, :k4], -8, 7) << sh[:, :k4]
+        assert (mid.cpu().numpy().astype(np.int32)[:, k6:] == want_mid[:, k6:]).all(), (M, r2)
+        codes = _decode_x6(x6_2.cpu().numpy(), M, N1, k6)
+        assert (codes == np.clip(X2[:, :k6].astype(np.int32) >> sh[:, :k6], -8, 7)).all(), (M, r2)
+        got = fq.flexiq_mixed_gemm_fp6(h2, mid, x6_2, acc=True)["acc"].cpu().numpy()
+        assert (got == oracle.forward_gemm(o2, X2, r2)).all(), (M, r2)
