@@ -33,6 +33,7 @@ int prepare_kernels(int device);
 int prepare_fp6_kernels(int device);
 int prepare_stream_kernels(int device);
 int prepare_conv3_kernels(int device);
+int prepare_tile_splitk_kernels(int device);
 
 // Order hash of a channel permutation (FNV-1a over the 32-bit entries; `n` entries, identity when p == nullptr).
 inline uint64_t order_hash(const int32_t *p, int n)

@@ -609,6 +609,7 @@ extern "C" int flexiq_quantize_pack(const flexiq_pack_desc *d, flexiq_layer **ou
         if (rc == FLEXIQ_OK) rc = prepare_fp6_kernels(L->device);
         if (rc == FLEXIQ_OK) rc = prepare_stream_kernels(L->device);
         if (rc == FLEXIQ_OK) rc = prepare_conv3_kernels(L->device);
+        if (rc == FLEXIQ_OK) rc = prepare_tile_splitk_kernels(L->device);
         if (rc != FLEXIQ_OK) return rc;
     }
     L->out_order_hash = order_hash(d->out_perm, N);

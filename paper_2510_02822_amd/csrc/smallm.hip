@@ -819,6 +819,23 @@ int launch_few_rows_fp6(const flexiq_layer *L, const int8_t *X, const uint8_t *X
     return FLEXIQ_OK;
 }
 
+// Once per device, when the first layer is packed on it: the dynamic-LDS limit of every build of k_tile_splitk, so that a
+// launch is only a launch (and safe under stream capture).
+int prepare_tile_splitk_kernels(int device)
+{
+    using namespace smallm;
+    if (device < 0 || device >= 64) return FLEXIQ_EINVAL;
+    if (g_tile_splitk_ready[device]) return FLEXIQ_OK;
+    FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<4, 4, 8, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+    FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 4, 16, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+    FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 2, 16, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+    FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<4, 4, 8, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+    FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 4, 8, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+    FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 2, 16, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+    g_tile_splitk_ready[device] = true;
+    return FLEXIQ_OK;
+}
+
 static int launch_tile_any(const flexiq_layer *L, const int8_t *X, const uint8_t *X6, int K6, int64_t M, const flexiq_out *out, void *stream,
                            int num_cu, int *taken, const LowerArgs *lower)
 {
@@ -843,15 +860,7 @@ static int launch_tile_any(const flexiq_layer *L, const int8_t *X, const uint8_t
     const int tr = shape == 0 ? 64 : 32, tc = shape == 2 ? 32 : 64;
     if (tiles_of(tr, tc) > 0x7fffffff || (M + tr - 1) / tr > 65535) return FLEXIQ_OK;
     const size_t lds = shape == 2 ? 64 * 1024 : 128 * 1024;   // waves x fragments x 1 KB
-    if (!g_tile_splitk_ready[L->device]) {
-        FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<4, 4, 8, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
-        FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 4, 16, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
-        FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 2, 16, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
-        FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<4, 4, 8, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
-        FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 4, 8, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
-        FLEXIQ_HIP(hipFuncSetAttribute((const void *)k_tile_splitk<2, 2, 16, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
-        g_tile_splitk_ready[L->device] = true;
-    }
+    if (!g_tile_splitk_ready[L->device]) return FLEXIQ_OK;   // (set up when the first layer is packed on the device)
     RowsParams p = {};
     p.X = X; p.W8 = L->d_w8;
     p.ashift = L->dynamic ? L->d_ashift_dyn : L->d_ashift;
